@@ -1,0 +1,120 @@
+"""Epoch loops of Algorithms 1-3 of the paper, step by step -- TEST INFRASTRUCTURE ONLY.
+
+The M workers of the parameter-server network are taken as one synchronous round:
+all M read the same quantized model, the master averages the M decoded gradients and
+takes one proximal step (the paper applies gradients one at a time with bounded
+staleness; a round with zero staleness is this build's reading).  The iteration
+counter ``it = epoch_index * m + t`` addresses the random streams.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import numpy as np
+
+from . import (MASTER_ID, TAG_GRAD, TAG_MODEL, RefProblem, acc_mix, acc_snapshot, dequantize,
+               full_grad, master_update, objective, pack, quantize, sample_indices, sparsify, unpack,
+               vr_grad)
+
+
+@dataclass
+class Trace:
+    objectives: List[float] = field(default_factory=list)   # P(snapshot) at the start of each epoch, then final
+    bits_up: int = 0       # worker -> master
+    bits_down: int = 0     # master -> worker (per worker)
+    x: Optional[np.ndarray] = None
+    x_snap: Optional[np.ndarray] = None
+
+
+def model_message(x: np.ndarray, x_snap: np.ndarray, b_x: int, seed: int, it: int):
+    """Master step (i) of Alg. 1 (model parameter quantization).  Returns (q, packed words or None, delta_x, bits).
+
+    If x equals the snapshot bit for bit the master sends the flag bit of Section 4.1
+    and the workers use the snapshot they already hold.
+    """
+    d = x.size
+    if np.array_equal(x.view(np.uint32), x_snap.view(np.uint32)):
+        return x_snap.copy(), None, np.float32(0), 1
+    k, dx, _ = quantize(x, b_x, seed, it, MASTER_ID, TAG_MODEL)
+    words = pack(k, b_x)
+    q = dequantize(unpack(words, d, b_x), dx)
+    return q, words, dx, 32 + b_x * d
+
+
+def worker_message(rp: RefProblem, q, x_snap, model_is_snapshot: bool, B: int, b: int, seed: int,
+                   it: int, worker: int, sparse: bool):
+    """Worker steps of Alg. 1 ((i), (ii)) and of Alg. 2 ((i)-(iii)).
+
+    Returns (packed words, delta, bits, alpha, beta-or-None, idx).
+    """
+    d = rp.d
+    idx = sample_indices(rp.n, B, seed, it, worker)
+    if model_is_snapshot:
+        alpha = np.zeros(d, dtype=np.float32)        # grad f_a(xs) - grad f_a(xs)
+    else:
+        alpha = vr_grad(rp, idx, q, x_snap)
+    beta = None
+    v = alpha
+    nnz = d
+    if sparse:
+        beta, nnz = sparsify(alpha, seed, it, worker)
+        v = beta
+    k, dlt, _ = quantize(v, b, seed, it, worker, TAG_GRAD)
+    words = pack(k, b)
+    if sparse:
+        bits = 32 + int(np.count_nonzero(k)) * (math.ceil(math.log2(d)) + b)
+    else:
+        bits = 32 + b * d
+    return words, dlt, bits, alpha, beta, idx
+
+
+def run(prob, algo: str, M: int, B: int, b_x: int, b: int, m: int, S: int, lr: float, seed: int = 0,
+        x0: Optional[np.ndarray] = None, eval_objective: bool = True) -> Trace:
+    rp = RefProblem(prob)
+    d = rp.d
+    tr = Trace()
+    x_snap = np.zeros(d, dtype=np.float32) if x0 is None else np.array(x0, dtype=np.float32)
+    y = x_snap.copy()                     # Acc only: y_m^0 = snapshot^0
+    x = x_snap.copy()
+    sparse = algo == "sparse"
+    for e in range(S):
+        if algo == "acc":
+            s = e + 1
+            theta = np.float32(2.0 / (s + 2))
+            eta = np.float32(np.float32(lr) / theta)
+            x = acc_mix(y, x_snap, theta)                       # Alg. 3, epoch start
+            xsum = np.zeros(d, dtype=np.float32)
+        else:
+            theta, eta = np.float32(0), np.float32(lr)
+            x = x_snap.copy()                                   # Alg. 1, epoch start
+        if eval_objective:
+            tr.objectives.append(objective(rp, x_snap))
+        g_snap = full_grad(rp, x_snap)                          # global gradient   
+        for t in range(m):
+            it = e * m + t
+            q, _, _, bits = model_message(x, x_snap, b_x, seed, it)
+            flag = bits == 1
+            tr.bits_down += bits
+            codes = np.zeros((M, d), dtype=np.int8)
+            deltas = np.zeros(M, dtype=np.float32)
+            for w in range(M):
+                words, dlt, bits, _, _, _ = worker_message(rp, q, x_snap, flag, B, b, seed, it, w, sparse)
+                codes[w] = unpack(words, d, b)
+                deltas[w] = dlt
+                tr.bits_up += bits
+            if algo == "acc":
+                master_update(codes, deltas, np.float32(1.0 / M), g_snap, x, y, x_snap, xsum,
+                              eta=eta, theta=theta, l1=rp.l1)   # Alg. 3, master (ii)
+            else:
+                master_update(codes, deltas, np.float32(1.0 / M), g_snap, x,
+                              eta=eta, l1=rp.l1)                # Alg. 1, master (ii)
+        if algo == "acc":
+            x_snap = acc_snapshot(xsum, m)                      # Alg. 3, epoch end
+        else:
+            x_snap = x.copy()                                   # Alg. 1, epoch end
+    if eval_objective:
+        tr.objectives.append(objective(rp, x_snap))
+    tr.x, tr.x_snap = x, x_snap
+    return tr
