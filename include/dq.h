@@ -1,0 +1,221 @@
+/*
+ * dq.h -- C ABI of the double-quantization hot path on one AMD MI355X (gfx950).
+ *
+ * Method: Yu, Wu, Huang, "Double Quantization for Communication-Efficient
+ * Distributed Optimization" (arXiv 1805.10111): AsyLPG (Alg. 1), Sparse-AsyLPG
+ * (Alg. 2), Acc-AsyLPG (Alg. 3) for  min_x P(x) = f(x) + h(x)  (eq. (1)) with
+ *   f_i(x) = log(1 + exp(-y_i a_i.x)) + (l2/2)||x||^2,   h(x) = l1 ||x||_1 .
+ * The M workers of the parameter-server network are a batch dimension: every
+ * entry point that takes M processes M workers (rows) in one launch.
+ *
+ * Conventions (all entry points)
+ *  - Every data pointer is a DEVICE pointer unless the comment says "host".
+ *    The dq_problem struct itself lives in host memory and holds device pointers.
+ *  - The caller owns every buffer.  The library allocates nothing, frees
+ *    nothing, and keeps no state between calls except a thread-local record of
+ *    the last HIP error (dq_last_device_error).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work and return; results, including scalars (delta,
+ *    norms, counts, status), land in device memory.  The caller synchronises.
+ *  - Return value: DQ_OK, or a negative DQ_ERR_* code; on error nothing has
+ *    been enqueued unless the code is DQ_ERR_DEVICE.
+ *  - Alignment: vectors of floats / words that are read or written with
+ *    128-bit accesses must be 16-byte aligned and row strides (`ld`, `lda`,
+ *    in elements) multiples of 4; the comments say where this is required.
+ *  - b is the number of bits per coordinate.  Packed buffers support
+ *    b in {2,4,8}; unpacked int8 codes support any b in [2,8].
+ *  - `status` (nullable) is a device uint32 that is OR-ed into, never cleared:
+ *    bit 0 = a scale delta was not finite (NaN/Inf in the input vector).
+ *  - Random streams are addressed, not stateful: (seed, iter, worker, tag,
+ *    coordinate) names one variate; the same address gives the same variate in
+ *    any call, any launch shape.  Generator: Philox4x32-10; key = halves of
+ *    seed; counter = (coordinate/4, iter, worker, tag); variate = word
+ *    coordinate%4; uniform = (word >> 8) * 2^-24.
+ */
+#ifndef DQ_H_
+#define DQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DQ_OK                0
+#define DQ_ERR_INVALID_ARG  (-1)  /* null / misaligned pointer, size <= 0, b out of range */
+#define DQ_ERR_UNSUPPORTED  (-2)  /* valid request this build has no kernel for */
+#define DQ_ERR_WORKSPACE    (-3)  /* workspace smaller than dq_workspace_bytes() */
+#define DQ_ERR_DEVICE       (-4)  /* a HIP call failed; see dq_last_device_error() */
+
+/* Stream tags: which random decision a variate is used for. */
+#define DQ_TAG_GRAD      0u   /* rounding of a worker's gradient (Alg. 1, worker (ii))     */
+#define DQ_TAG_MODEL     1u   /* rounding of the model (Alg. 1, master (i))                */
+#define DQ_TAG_SPARSIFY  2u   /* Bernoulli keep decisions of eq. (3)                       */
+#define DQ_TAG_SAMPLE    3u   /* mini-batch sampling (Alg. 1, worker (i))                  */
+#define DQ_MASTER_ID     0xFFFFFFFFu   /* worker id used for the master's own stream       */
+
+/* Finite-sum problem of eq. (1) with logistic loss (Section 5.1).
+ * layout 0: dense row-major features, row i at dense + i*lda, lda % 4 == 0,
+ *           dense 16-byte aligned.
+ * layout 1: CSR; indptr[n+1], indices sorted and unique within a row.
+ * y[n] holds +1/-1.  l2 multiplies ||x||^2/2 inside every f_i (smooth part),
+ * l1 multiplies ||x||_1 in h (handled by the prox). */
+typedef struct dq_problem {
+    int32_t layout;
+    int64_t n, d;
+    const float *dense;
+    int64_t lda;
+    const int64_t *indptr;
+    const int32_t *indices;
+    const float *values;
+    const float *y;
+    float l2, l1;
+} dq_problem;
+
+/* Operations that need a workspace (argument of dq_workspace_bytes). */
+#define DQ_OP_FULL_GRAD    1
+#define DQ_OP_VR_GRAD      2   /* also covers dq_worker_step */
+
+const char *dq_version(void);
+/* Last hipError_t (as int) seen by this thread inside the library, 0 if none. */
+int32_t dq_last_device_error(void);
+/* Bytes of device workspace `op` needs for this problem with M workers of batch B. */
+int64_t dq_workspace_bytes(int32_t op, const dq_problem *prob /*host*/, int64_t M, int64_t B);
+
+/* ---- Section 3.1: the (delta, b) representation and the quantizer Q ------------- */
+
+/* absmax_out[m] = ||v_m||_inf for M rows v_m = v + m*ld of length d
+ * (numerator of delta in Alg. 1, master (i) and worker (ii)).
+ * A NaN anywhere in a row gives a NaN result (max over the magnitude bit patterns). */
+int32_t dq_absmax(const float *v, int64_t d, int64_t M, int64_t ld, float *absmax_out, void *stream);
+
+/* Stochastic quantization Q_(delta,b) of Section 3.1, coordinate-wise, with
+ * delta_m = ||v_m||_inf / (2^(b-1)-1).  codes_out[m*ld_codes + i] = k with
+ * Q(v_mi) = k*delta_m.  Row m uses the stream (seed, iter, worker0+m, tag).
+ * Per coordinate (float32): t = v*(L/amax), z = floor(t), k = z + [u < t-z],
+ * clamped to [-2^(b-1), 2^(b-1)-1].  A row whose delta is zero or below the
+ * smallest normal float gives delta 0 and all-zero codes; a non-finite delta
+ * gives zero codes and sets status bit 0.
+ * absmax: device float[M]; if absmax_given == 0 it is overwritten with
+ * ||v_m||_inf first, else it is read as supplied.  delta_out: device float[M]. */
+int32_t dq_quantize(const float *v, int64_t d, int64_t M, int64_t ld, int32_t b,
+                    float *absmax, int32_t absmax_given,
+                    uint64_t seed, uint32_t iter, uint32_t tag, uint32_t worker0,
+                    int8_t *codes_out, int64_t ld_codes, float *delta_out,
+                    uint32_t *status, void *stream);
+
+/* v_out[m*ld + i] = delta[m] * codes[m*ld_codes + i]  (the value a code represents). */
+int32_t dq_dequantize(const int8_t *codes, int64_t ld_codes, const float *delta, int64_t d, int64_t M,
+                      float *v_out, int64_t ld, void *stream);
+
+/* Wire format of Section 3.1 (32 + b*d bits per vector: delta plus b bits per
+ * coordinate).  Field i of a row = bits [(i*b)%32, (i*b)%32+b) of word
+ * floor(i*b/32), two's complement, low bits first; unused tail bits are 0.
+ * Rows of packed words have stride ld_words >= ceil(d*b/32).  b in {2,4,8}. */
+int32_t dq_pack(const int8_t *codes, int64_t ld_codes, int64_t d, int64_t M, int32_t b,
+                uint32_t *packed_out, int64_t ld_words, void *stream);
+int32_t dq_unpack(const uint32_t *packed, int64_t ld_words, int64_t d, int64_t M, int32_t b,
+                  int8_t *codes_out, int64_t ld_codes, void *stream);
+
+/* dq_quantize followed by dq_pack in one pass (same bits as the two calls).
+ * v 16-byte aligned and ld % 4 == 0 select the 128-bit path; otherwise a
+ * scalar path is used.  packed_out rows are 16-byte aligned if ld_words % 4 == 0. */
+int32_t dq_quantize_pack(const float *v, int64_t d, int64_t M, int64_t ld, int32_t b,
+                         float *absmax, int32_t absmax_given,
+                         uint64_t seed, uint32_t iter, uint32_t tag, uint32_t worker0,
+                         uint32_t *packed_out, int64_t ld_words, float *delta_out,
+                         uint32_t *status, void *stream);
+
+/* Master's receive side (Alg. 1, master (ii), first half): decode M packed
+ * gradients and aggregate,  out[i] = scale * sum_{m<M} delta[m]*k_mi,
+ * summed in the order m = 0..M-1 with fused multiply-adds, then one multiply
+ * by scale (1/M for the mean over a synchronous round of M workers). */
+int32_t dq_unpack_dequant_sum(const uint32_t *packed, int64_t ld_words, const float *delta,
+                              int64_t d, int64_t M, int32_t b, float scale, float *out, void *stream);
+
+/* ---- sampling, gradients -------------------------------------------------------- */
+
+/* Mini-batch of Alg. 1, worker (i) (Section 5.1 uses mini-batches): for worker
+ * m and slot j, idx_out[m*B + j] = floor(word * n / 2^32) with the variate at
+ * (seed, iter, worker0+m, DQ_TAG_SAMPLE, j): uniform on {0..n-1}, with replacement. */
+int32_t dq_sample_indices(int64_t n, int64_t M, int64_t B, uint64_t seed, uint32_t iter,
+                          uint32_t worker0, int32_t *idx_out, void *stream);
+
+/* Epoch prologue (Alg. 1, global gradient computation):
+ *   g_out = (1/n) sum_i grad f_i(x) = (1/n) sum_i s_i a_i + l2*x,
+ *   s_i = -y_i / (1 + exp(y_i a_i.x)).
+ * z_out (nullable, float[n]) receives the margins a_i.x; obj_out (nullable,
+ * double[1]) receives P(x) of eq. (1).  Deterministic (fixed summation order
+ * for a given problem shape). */
+int32_t dq_full_grad(const dq_problem *prob /*host*/, const float *x, float *g_out, float *z_out,
+                     double *obj_out, void *ws, int64_t ws_bytes, void *stream);
+
+/* Worker step (i) of Alg. 1 for M workers with mini-batches idx[m*B .. m*B+B):
+ *   alpha_m = (1/B) sum_{i in I_m} [grad f_i(q) - grad f_i(x_snap)],
+ * q = delta_x * (codes unpacked from xq_packed) is the b_x-bit model the worker
+ * received (Alg. 1, master (i)); b_x == 32 means xq_packed holds float32 values
+ * of the model itself (no quantization; delta_x ignored).
+ * model_is_snapshot != 0 is the flag-bit case of Section 4.1 (q = x_snap): alpha = 0.
+ * z_snap (nullable) = margins a_i.x_snap cached by dq_full_grad; if NULL they
+ * are recomputed.  alpha_out rows have stride ld (ld % 4 == 0, 16-byte aligned).
+ * absmax_out[M] = ||alpha_m||_inf; l1norm_out (nullable) [M] = ||alpha_m||_1. */
+int32_t dq_vr_grad(const dq_problem *prob /*host*/, const int32_t *idx, int64_t M, int64_t B,
+                   const uint32_t *xq_packed, const float *delta_x, int32_t b_x,
+                   int32_t model_is_snapshot, const float *x_snap, const float *z_snap,
+                   float *alpha_out, int64_t ld, float *absmax_out, float *l1norm_out,
+                   void *ws, int64_t ws_bytes, void *stream);
+
+/* Eq. (3), gradient sparsification (Alg. 2, worker (ii)):
+ *   beta_i = Z_i alpha_i / p_i,  Z_i ~ Bernoulli(p_i)  (keep iff u_i < p_i),
+ * phi == NULL: the budget of Section 5.1, phi = ||alpha||_1/||alpha||_inf, i.e.
+ *   p_i = |alpha_i| / ||alpha||_inf;
+ * else p_i = min(1, |alpha_i| * phi[m] / ||alpha_m||_1)  (Lemma 2).
+ * Outputs: beta_out (stride ld_out), absmax_out[M] = ||beta_m||_inf,
+ * nnz_out[M] = kept coordinates.  Stream tag DQ_TAG_SPARSIFY. */
+int32_t dq_sparsify(const float *alpha, int64_t d, int64_t M, int64_t ld, const float *phi,
+                    uint64_t seed, uint32_t iter, uint32_t worker0,
+                    float *beta_out, int64_t ld_out, float *absmax_out, int32_t *nnz_out, void *stream);
+
+/* The whole worker side of one round, fused (Alg. 1, worker (i)-(ii); with
+ * sparsify != 0: Alg. 2, worker (i)-(iii)):  dq_vr_grad -> [dq_sparsify] ->
+ * dq_quantize_pack with tag DQ_TAG_GRAD, bit-identical to those calls, without
+ * writing alpha to memory.  packed_out: M rows of ld_words words; delta_out[M];
+ * nnz_out (nullable) [M] = nonzero codes.  alpha_out (nullable): also store alpha. */
+int32_t dq_worker_step(const dq_problem *prob /*host*/, const int32_t *idx, int64_t M, int64_t B,
+                       const uint32_t *xq_packed, const float *delta_x, int32_t b_x,
+                       int32_t model_is_snapshot, const float *x_snap, const float *z_snap,
+                       int32_t sparsify, int32_t b, uint64_t seed, uint32_t iter, uint32_t worker0,
+                       uint32_t *packed_out, int64_t ld_words, float *delta_out, int32_t *nnz_out,
+                       float *alpha_out, int64_t ld, uint32_t *status,
+                       void *ws, int64_t ws_bytes, void *stream);
+
+/* ---- master --------------------------------------------------------------------- */
+
+/* Master step for one synchronous round of M workers (Alg. 1, master (ii) and (i);
+ * Alg. 3 with y != NULL):
+ *   u     = scale * sum_m delta[m]*k_m + g_snap                    (as dq_unpack_dequant_sum)
+ *   Alg.1: x <- prox_{eta h}(x - eta*u)         prox = soft-threshold at eta*l1
+ *   Alg.3: y <- prox_{eta h}(y - eta*u);  x <- x_snap + theta*(y - x_snap);  xsum += x
+ * then the new model is quantized to b_x bits with the master's stream
+ * (seed, iter, DQ_MASTER_ID, DQ_TAG_MODEL) and packed into xq_packed_out, with
+ * delta_x_out[0] its scale and absmax_x_out[0] = ||x||_inf (scratch + output).
+ * b == 32: `packed` holds M rows of float32 gradients (stride ld_words, delta
+ * ignored).  b_x == 32: no model quantization, xq_packed_out receives x as float32.
+ * All float32, in the order written; x, y, xsum are updated in place. */
+int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
+                       float scale, const float *g_snap, float *x, float *y, const float *x_snap,
+                       float *xsum, float eta, float theta, float l1, int64_t d,
+                       int32_t b_x, uint64_t seed, uint32_t iter,
+                       uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out,
+                       uint32_t *status, void *stream);
+
+/* Start of an epoch of Alg. 3:  x_out = x_snap + theta*(y - x_snap)  (= theta*y + (1-theta)*x_snap). */
+int32_t dq_acc_mix(const float *y, const float *x_snap, float theta, int64_t d, float *x_out, void *stream);
+/* End of an epoch of Alg. 3:  x_snap_out = xsum / m. */
+int32_t dq_acc_snapshot(const float *xsum, int64_t m, int64_t d, float *x_snap_out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DQ_H_ */

@@ -52,6 +52,9 @@ def lib() -> C.CDLL:
         _lib.ref_random_word.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint64]
         _lib.ref_uniform.restype = C.c_float
         _lib.ref_uniform.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint64]
+        _lib.ref_uniform_range.restype = None
+        _lib.ref_uniform_range.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint64, C.c_int64,
+                                           C.c_void_p]
         _lib.ref_absmax.restype = C.c_float
         _lib.ref_absmax.argtypes = [C.c_void_p, C.c_int64]
         _lib.ref_delta.restype = C.c_float
@@ -123,6 +126,12 @@ def random_word(seed: int, it: int, worker: int, tag: int, coord: int) -> int:
 
 def uniform(seed: int, it: int, worker: int, tag: int, coord: int) -> float:
     return float(lib().ref_uniform(seed, it, worker, tag, coord))
+
+
+def uniform_range(seed: int, it: int, worker: int, tag: int, coord0: int, count: int) -> np.ndarray:
+    u = np.zeros(count, dtype=np.float32)
+    lib().ref_uniform_range(seed, it, worker, tag, coord0, count, _p(u))
+    return u
 
 
 def sample_indices(n: int, B: int, seed: int, it: int, worker: int) -> np.ndarray:

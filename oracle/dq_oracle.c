@@ -76,6 +76,13 @@ float ref_uniform(uint64_t seed, uint32_t iter, uint32_t worker, uint32_t tag, u
     return uniform24(ref_random_word(seed, iter, worker, tag, coord));
 }
 
+/* u[i] = uniform of coordinate coord0 + i, i < count. */
+void ref_uniform_range(uint64_t seed, uint32_t iter, uint32_t worker, uint32_t tag, uint64_t coord0,
+                       int64_t count, float *u)
+{
+    for (int64_t i = 0; i < count; ++i) u[i] = ref_uniform(seed, iter, worker, tag, coord0 + (uint64_t)i);
+}
+
 /* Mini-batch sampling: B indices, uniform on {0..n-1}, with replacement
  * (the worker "stochastically samples a data-point", Alg. 1, worker (i); the
  * experiments use a mini-batch, Section 5.1).  idx = floor(word * n / 2^32). */

@@ -1,0 +1,201 @@
+// Internal helpers shared by the HIP translation units of libdq (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <float.h>
+
+#include "../../include/dq.h"
+
+namespace dq {
+
+constexpr int kWave = 64;
+
+// ---- host-side error plumbing ------------------------------------------------
+void set_last_error(hipError_t e);
+
+#define DQ_HIP_TRY(expr)                                   \
+    do {                                                   \
+        hipError_t e_ = (expr);                            \
+        if (e_ != hipSuccess) {                            \
+            ::dq::set_last_error(e_);                      \
+            return DQ_ERR_DEVICE;                          \
+        }                                                  \
+    } while (0)
+
+#define DQ_LAUNCH_CHECK() DQ_HIP_TRY(hipGetLastError())
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int64_t packed_words(int64_t d, int b) { return (d * b + 31) / 32; }
+
+// ---- Philox4x32-10 (Salmon et al., SC'11), from its published definition -------
+// Stream addressing: key = (seed_lo, seed_hi); counter = (coord/4, iter, worker, tag).
+struct StreamKey {
+    uint32_t k0, k1;      // seed halves
+    uint32_t iter, worker, tag;
+};
+
+__device__ __forceinline__ uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               uint32_t k0, uint32_t k1)
+{
+    constexpr uint32_t kMul0 = 0xD2511F53u, kMul1 = 0xCD9E8D57u;
+    constexpr uint32_t kWeyl0 = 0x9E3779B9u, kWeyl1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = static_cast<uint64_t>(kMul0) * c0;
+        const uint64_t p1 = static_cast<uint64_t>(kMul1) * c2;
+        const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ k1;
+        c1 = static_cast<uint32_t>(p1);
+        c3 = static_cast<uint32_t>(p0);
+        c0 = n0;
+        c2 = n2;
+        k0 += kWeyl0;
+        k1 += kWeyl1;
+    }
+    return make_uint4(c0, c1, c2, c3);
+}
+
+// The four 32-bit variates of coordinates 4*block .. 4*block+3 of a stream.
+__device__ __forceinline__ uint4 stream_block(const StreamKey &s, uint32_t block)
+{
+    return philox4x32_10(block, s.iter, s.worker, s.tag, s.k0, s.k1);
+}
+
+// Single variate of one coordinate (slow path: tails, samplers).
+__device__ __forceinline__ uint32_t stream_word(const StreamKey &s, uint64_t coord)
+{
+    const uint4 w = stream_block(s, static_cast<uint32_t>(coord >> 2));
+    const uint32_t lane = static_cast<uint32_t>(coord & 3u);
+    return lane == 0 ? w.x : lane == 1 ? w.y : lane == 2 ? w.z : w.w;
+}
+
+// "u < p" with u = (word >> 8) * 2^-24: both sides scaled by 2^24 are exact floats.
+__device__ __forceinline__ bool bernoulli(uint32_t word, float p)
+{
+    return static_cast<float>(word >> 8) < p * 16777216.0f;
+}
+
+// ---- quantizer scalars -------------------------------------------------------
+// Everything the per-coordinate rule needs, derived from ||v||_inf and b.
+struct Scale {
+    float delta;      // amax / L, or 0 (degenerate), or non-finite
+    float inv_delta;  // L / amax (0 when codes must be all zero)
+    int kmin, kmax;
+    bool bad;         // non-finite delta
+};
+
+__device__ __forceinline__ Scale make_scale(float amax, int b)
+{
+    Scale s;
+    const int L = (1 << (b - 1)) - 1;
+    s.kmin = -(1 << (b - 1));
+    s.kmax = L;
+    float delta = amax / static_cast<float>(L);
+    s.bad = !(delta == delta) || delta > FLT_MAX;           // NaN or Inf
+    if (s.bad) {
+        s.delta = delta;
+        s.inv_delta = 0.0f;
+    } else if (!(delta >= FLT_MIN)) {                        // zero or subnormal scale
+        s.delta = 0.0f;
+        s.inv_delta = 0.0f;
+    } else {
+        s.delta = delta;
+        s.inv_delta = static_cast<float>(L) / amax;
+    }
+    return s;
+}
+
+// One coordinate of Q_(delta,b): returns the integer code.
+__device__ __forceinline__ int quantize_one(float v, const Scale &s, uint32_t word)
+{
+    const float t = v * s.inv_delta;
+    const float z = floorf(t);
+    const float p = t - z;
+    int k = static_cast<int>(z) + (bernoulli(word, p) ? 1 : 0);
+    k = max(k, s.kmin);
+    k = min(k, s.kmax);
+    return k;
+}
+
+// ---- magnitude bit pattern: monotone in |v| for non-NaN, NaN sorts above Inf ----
+__device__ __forceinline__ uint32_t abs_bits(float v) { return __float_as_uint(v) & 0x7FFFFFFFu; }
+
+// ---- wave / block reductions (deterministic butterflies) -----------------------
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = max(v, static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), off, kWave)));
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum_f32(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+__device__ __forceinline__ int wave_sum_i32(int v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+// Block-wide max of a uint32; `scratch` has >= blockDim.x/64 entries. Result in all threads.
+__device__ __forceinline__ uint32_t block_max_u32(uint32_t v, uint32_t *scratch)
+{
+    v = wave_max_u32(v);
+    const int wave = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
+    __syncthreads();
+    if ((threadIdx.x & (kWave - 1)) == 0) scratch[wave] = v;
+    __syncthreads();
+    uint32_t r = scratch[0];
+    for (int w = 1; w < nw; ++w) r = max(r, scratch[w]);
+    return r;
+}
+
+__device__ __forceinline__ double block_sum_f64(double v, double *scratch)
+{
+    v = wave_sum_f64(v);
+    const int wave = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
+    __syncthreads();
+    if ((threadIdx.x & (kWave - 1)) == 0) scratch[wave] = v;
+    __syncthreads();
+    double r = scratch[0];
+    for (int w = 1; w < nw; ++w) r += scratch[w];
+    return r;
+}
+
+__device__ __forceinline__ int block_sum_i32(int v, int *scratch)
+{
+    v = wave_sum_i32(v);
+    const int wave = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
+    __syncthreads();
+    if ((threadIdx.x & (kWave - 1)) == 0) scratch[wave] = v;
+    __syncthreads();
+    int r = scratch[0];
+    for (int w = 1; w < nw; ++w) r += scratch[w];
+    return r;
+}
+
+// Sign-extended b-bit field `f` (0-based) of a packed word.
+template <int B>
+__device__ __forceinline__ int field_of(uint32_t word, int f)
+{
+    return __builtin_amdgcn_sbfe(static_cast<int>(word), f * B, B);
+}
+
+// Logistic pieces in float32.
+__device__ __forceinline__ float sigmoidf(float t) { return 1.0f / (1.0f + __expf(-t)); }
+
+}  // namespace dq

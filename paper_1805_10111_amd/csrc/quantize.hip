@@ -1,0 +1,444 @@
+// Quantizer family: ||v||_inf reduction, stochastic quantization, bit packing,
+// unpacking and the master's decode-and-sum (Section 3.1 of the paper; Alg. 1,
+// master (i)/(ii) and worker (ii)).  All kernels stream their operands once with
+// 128-bit accesses; each thread owns 16 consecutive coordinates so that it emits
+// whole 32-bit words for every supported field width.
+#include "dq_common.h"
+
+namespace dq {
+
+constexpr int kThreads = 256;
+constexpr int kCoordsPerThread = 16;
+constexpr int64_t kMaxBlocksX = 1 << 24;   // one 16-coordinate chunk per thread up to 2^36 coordinates, grid-stride beyond
+
+static inline dim3 grid_for(int64_t d, int64_t M)
+{
+    const int64_t chunks = ceil_div(d, kCoordsPerThread);
+    int64_t bx = ceil_div(chunks, kThreads);
+    if (bx > kMaxBlocksX) bx = kMaxBlocksX;
+    if (bx < 1) bx = 1;
+    return dim3(static_cast<unsigned>(bx), static_cast<unsigned>(M), 1);
+}
+
+// ---------------------------------------------------------------- fill
+__global__ void fill_u32_kernel(uint32_t *p, int64_t n, uint32_t value)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = value;
+}
+
+int fill_u32(uint32_t *p, int64_t n, uint32_t value, hipStream_t st)
+{
+    if (n <= 0) return DQ_OK;
+    fill_u32_kernel<<<dim3(static_cast<unsigned>(ceil_div(n, 256))), dim3(256), 0, st>>>(p, n, value);
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
+}
+
+// ---------------------------------------------------------------- absmax
+// Max over the magnitude bit patterns: exact, order-free, NaN-propagating.
+__global__ __launch_bounds__(kThreads) void absmax_kernel(const float *__restrict__ v, int64_t d, int64_t ld,
+                                                          uint32_t *__restrict__ absmax_bits)
+{
+    __shared__ uint32_t scratch[kThreads / kWave];
+    const float *row = v + static_cast<int64_t>(blockIdx.y) * ld;
+    const int64_t chunks = (d + kCoordsPerThread - 1) / kCoordsPerThread;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    uint32_t m = 0;
+    for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
+        const int64_t base = c * kCoordsPerThread;
+        if (base + kCoordsPerThread <= d) {
+            const float4 *p = reinterpret_cast<const float4 *>(row + base);
+            const float4 a0 = p[0], a1 = p[1], a2 = p[2], a3 = p[3];
+            m = max(m, max(max(abs_bits(a0.x), abs_bits(a0.y)), max(abs_bits(a0.z), abs_bits(a0.w))));
+            m = max(m, max(max(abs_bits(a1.x), abs_bits(a1.y)), max(abs_bits(a1.z), abs_bits(a1.w))));
+            m = max(m, max(max(abs_bits(a2.x), abs_bits(a2.y)), max(abs_bits(a2.z), abs_bits(a2.w))));
+            m = max(m, max(max(abs_bits(a3.x), abs_bits(a3.y)), max(abs_bits(a3.z), abs_bits(a3.w))));
+        } else {
+            for (int64_t i = base; i < d; ++i) m = max(m, abs_bits(row[i]));
+        }
+    }
+    m = block_max_u32(m, scratch);
+    if (threadIdx.x == 0 && m != 0) atomicMax(absmax_bits + blockIdx.y, m);
+}
+
+int launch_absmax(const float *v, int64_t d, int64_t M, int64_t ld, float *absmax_out, hipStream_t st)
+{
+    int rc = fill_u32(reinterpret_cast<uint32_t *>(absmax_out), M, 0u, st);
+    if (rc != DQ_OK) return rc;
+    if (d > 0) {
+        absmax_kernel<<<grid_for(d, M), dim3(kThreads), 0, st>>>(v, d, ld, reinterpret_cast<uint32_t *>(absmax_out));
+        DQ_LAUNCH_CHECK();
+    }
+    return DQ_OK;
+}
+
+// ---------------------------------------------------------------- quantize (+pack)
+// FIELD = width of the stored field (2, 4, 8 bits); `b` = bits of the code range.
+// With FIELD == 8 and any b in [2,8] the output words are four int8 codes each.
+template <int FIELD>
+__global__ __launch_bounds__(kThreads) void quantize_pack_kernel(
+    const float *__restrict__ v, int64_t d, int64_t ld, const float *__restrict__ absmax, int b, StreamKey key,
+    uint32_t worker0, uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words,
+    float *__restrict__ delta_out, uint32_t *__restrict__ status)
+{
+    constexpr int kWords = kCoordsPerThread * FIELD / 32;     // words per thread: 4, 2, 1
+    constexpr uint32_t kMask = (1u << FIELD) - 1u;
+    const int m = blockIdx.y;
+    const float *row = v + static_cast<int64_t>(m) * ld;
+    uint32_t *out = packed + static_cast<int64_t>(m) * ld_words;
+    const Scale s = make_scale(absmax[m], b);
+    key.worker = worker0 + static_cast<uint32_t>(m);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        delta_out[m] = s.delta;
+        if (s.bad && status) atomicOr(status, 1u);
+    }
+    const bool zero_row = s.inv_delta == 0.0f;
+    const int64_t chunks = (d + kCoordsPerThread - 1) / kCoordsPerThread;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
+        const int64_t base = c * kCoordsPerThread;
+        uint32_t w[kWords];
+#pragma unroll
+        for (int i = 0; i < kWords; ++i) w[i] = 0u;
+        if (!zero_row) {
+            const bool full = base + kCoordsPerThread <= d;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                float a[4];
+                if (full) {
+                    const float4 t = reinterpret_cast<const float4 *>(row + base)[g];
+                    a[0] = t.x; a[1] = t.y; a[2] = t.z; a[3] = t.w;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int64_t i = base + g * 4 + e;
+                        a[e] = i < d ? row[i] : 0.0f;
+                    }
+                }
+                const uint4 r = stream_block(key, static_cast<uint32_t>(c * 4 + g));
+                const uint32_t rw[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int j = g * 4 + e;
+                    int k = quantize_one(a[e], s, rw[e]);
+                    if (!full && base + j >= d) k = 0;
+                    w[(j * FIELD) / 32] |= (static_cast<uint32_t>(k) & kMask) << ((j * FIELD) % 32);
+                }
+            }
+        }
+        const int64_t w0 = c * kWords;
+        if (w0 + kWords <= row_words) {
+            if constexpr (kWords == 4) reinterpret_cast<uint4 *>(out + w0)[0] = make_uint4(w[0], w[1], w[2], w[3]);
+            else if constexpr (kWords == 2) reinterpret_cast<uint2 *>(out + w0)[0] = make_uint2(w[0], w[1]);
+            else out[w0] = w[0];
+        } else {
+#pragma unroll
+            for (int i = 0; i < kWords; ++i)
+                if (w0 + i < row_words) out[w0 + i] = w[i];
+        }
+    }
+}
+
+int launch_quantize_pack(const float *v, int64_t d, int64_t M, int64_t ld, int b, int field,
+                         const float *absmax, const StreamKey &key, uint32_t worker0,
+                         uint32_t *packed, int64_t ld_words, float *delta_out, uint32_t *status, hipStream_t st)
+{
+    const int64_t row_words = packed_words(d, field);
+    const dim3 grid = grid_for(d, M), block(kThreads);
+    switch (field) {
+    case 8: quantize_pack_kernel<8><<<grid, block, 0, st>>>(v, d, ld, absmax, b, key, worker0, packed, ld_words, row_words, delta_out, status); break;
+    case 4: quantize_pack_kernel<4><<<grid, block, 0, st>>>(v, d, ld, absmax, b, key, worker0, packed, ld_words, row_words, delta_out, status); break;
+    case 2: quantize_pack_kernel<2><<<grid, block, 0, st>>>(v, d, ld, absmax, b, key, worker0, packed, ld_words, row_words, delta_out, status); break;
+    default: return DQ_ERR_UNSUPPORTED;
+    }
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
+}
+
+// ---------------------------------------------------------------- unpack helpers
+template <int FIELD>
+__device__ __forceinline__ void load_words(const uint32_t *__restrict__ row, int64_t c, int64_t row_words,
+                                           uint32_t (&w)[kCoordsPerThread * FIELD / 32])
+{
+    constexpr int kWords = kCoordsPerThread * FIELD / 32;
+    const int64_t w0 = c * kWords;
+    if (w0 + kWords <= row_words) {
+        if constexpr (kWords == 4) {
+            const uint4 t = reinterpret_cast<const uint4 *>(row + w0)[0];
+            w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w;
+        } else if constexpr (kWords == 2) {
+            const uint2 t = reinterpret_cast<const uint2 *>(row + w0)[0];
+            w[0] = t.x; w[1] = t.y;
+        } else {
+            w[0] = row[w0];
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < kWords; ++i) w[i] = (w0 + i < row_words) ? row[w0 + i] : 0u;
+    }
+}
+
+template <int FIELD>
+__device__ __forceinline__ int code_of(const uint32_t (&w)[kCoordsPerThread * FIELD / 32], int j)
+{
+    return __builtin_amdgcn_sbfe(static_cast<int>(w[(j * FIELD) / 32]), (j * FIELD) % 32, FIELD);
+}
+
+__device__ __forceinline__ void store16(float *__restrict__ out, int64_t base, int64_t d, const float (&a)[16])
+{
+    if (base + 16 <= d) {
+        float4 *p = reinterpret_cast<float4 *>(out + base);
+        p[0] = make_float4(a[0], a[1], a[2], a[3]);
+        p[1] = make_float4(a[4], a[5], a[6], a[7]);
+        p[2] = make_float4(a[8], a[9], a[10], a[11]);
+        p[3] = make_float4(a[12], a[13], a[14], a[15]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            if (base + j < d) out[base + j] = a[j];
+    }
+}
+
+// ---------------------------------------------------------------- unpack + dequantize + sum over M
+template <int FIELD>
+__global__ __launch_bounds__(kThreads) void unpack_dequant_sum_kernel(
+    const uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words, const float *__restrict__ delta,
+    int64_t d, int M, float scale, float *__restrict__ out)
+{
+    constexpr int kWords = kCoordsPerThread * FIELD / 32;
+    const int64_t chunks = (d + kCoordsPerThread - 1) / kCoordsPerThread;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
+        float acc[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
+#pragma unroll 4
+        for (int m = 0; m < M; ++m) {
+            uint32_t w[kWords];
+            load_words<FIELD>(packed + static_cast<int64_t>(m) * ld_words, c, row_words, w);
+            const float dm = delta[m];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[j] = fmaf(dm, static_cast<float>(code_of<FIELD>(w, j)), acc[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[j] = scale * acc[j];
+        store16(out, c * kCoordsPerThread, d, acc);
+    }
+}
+
+int launch_unpack_dequant_sum(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t d, int64_t M,
+                              int b, float scale, float *out, hipStream_t st)
+{
+    const int64_t row_words = packed_words(d, b);
+    const dim3 grid = grid_for(d, 1), block(kThreads);
+    switch (b) {
+    case 8: unpack_dequant_sum_kernel<8><<<grid, block, 0, st>>>(packed, ld_words, row_words, delta, d, static_cast<int>(M), scale, out); break;
+    case 4: unpack_dequant_sum_kernel<4><<<grid, block, 0, st>>>(packed, ld_words, row_words, delta, d, static_cast<int>(M), scale, out); break;
+    case 2: unpack_dequant_sum_kernel<2><<<grid, block, 0, st>>>(packed, ld_words, row_words, delta, d, static_cast<int>(M), scale, out); break;
+    default: return DQ_ERR_UNSUPPORTED;
+    }
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
+}
+
+// ---------------------------------------------------------------- dequantize (int8 codes)
+__global__ __launch_bounds__(kThreads) void dequantize_kernel(const uint32_t *__restrict__ codes_words, int64_t ld_code_words,
+                                                              int64_t row_words, const float *__restrict__ delta,
+                                                              int64_t d, float *__restrict__ out, int64_t ld)
+{
+    const int m = blockIdx.y;
+    const float dm = delta[m];
+    const int64_t chunks = (d + kCoordsPerThread - 1) / kCoordsPerThread;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
+        uint32_t w[4];
+        load_words<8>(codes_words + static_cast<int64_t>(m) * ld_code_words, c, row_words, w);
+        float a[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) a[j] = dm * static_cast<float>(code_of<8>(w, j));
+        store16(out + static_cast<int64_t>(m) * ld, c * kCoordsPerThread, d, a);
+    }
+}
+
+// ---------------------------------------------------------------- pack / unpack (int8 <-> FIELD bits)
+template <int FIELD>
+__global__ __launch_bounds__(kThreads) void pack_kernel(const uint32_t *__restrict__ codes_words, int64_t ld_code_words,
+                                                        int64_t code_row_words, int64_t d,
+                                                        uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words)
+{
+    constexpr int kWords = kCoordsPerThread * FIELD / 32;
+    constexpr uint32_t kMask = (1u << FIELD) - 1u;
+    const int m = blockIdx.y;
+    uint32_t *out = packed + static_cast<int64_t>(m) * ld_words;
+    const int64_t chunks = (d + kCoordsPerThread - 1) / kCoordsPerThread;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
+        uint32_t in[4];
+        load_words<8>(codes_words + static_cast<int64_t>(m) * ld_code_words, c, code_row_words, in);
+        uint32_t w[kWords];
+#pragma unroll
+        for (int i = 0; i < kWords; ++i) w[i] = 0u;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            int k = code_of<8>(in, j);
+            if (c * kCoordsPerThread + j >= d) k = 0;
+            w[(j * FIELD) / 32] |= (static_cast<uint32_t>(k) & kMask) << ((j * FIELD) % 32);
+        }
+        const int64_t w0 = c * kWords;
+#pragma unroll
+        for (int i = 0; i < kWords; ++i)
+            if (w0 + i < row_words) out[w0 + i] = w[i];
+    }
+}
+
+template <int FIELD>
+__global__ __launch_bounds__(kThreads) void unpack_kernel(const uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words,
+                                                          int64_t d, int8_t *__restrict__ codes, int64_t ld_codes)
+{
+    constexpr int kWords = kCoordsPerThread * FIELD / 32;
+    const int m = blockIdx.y;
+    int8_t *out = codes + static_cast<int64_t>(m) * ld_codes;
+    const int64_t chunks = (d + kCoordsPerThread - 1) / kCoordsPerThread;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
+        uint32_t w[kWords];
+        load_words<FIELD>(packed + static_cast<int64_t>(m) * ld_words, c, row_words, w);
+        const int64_t base = c * kCoordsPerThread;
+        if (base + 16 <= d) {
+            uint32_t o[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int j = 0; j < 16; ++j) o[j / 4] |= (static_cast<uint32_t>(code_of<FIELD>(w, j)) & 0xFFu) << ((j % 4) * 8);
+            reinterpret_cast<uint4 *>(out + base)[0] = make_uint4(o[0], o[1], o[2], o[3]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (base + j < d) out[base + j] = static_cast<int8_t>(code_of<FIELD>(w, j));
+        }
+    }
+}
+
+}  // namespace dq
+
+// =============================================================================== C ABI
+using namespace dq;
+
+static inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+static inline bool rows_ok(const void *p, int64_t M, int64_t ld, int64_t d, int64_t elems_per_16B)
+{
+    if (!p || !aligned16(p)) return false;
+    if (ld < d) return false;
+    if (M > 1 && (ld % elems_per_16B) != 0) return false;
+    return true;
+}
+
+extern "C" int32_t dq_absmax(const float *v, int64_t d, int64_t M, int64_t ld, float *absmax_out, void *stream)
+{
+    if (d < 0 || M <= 0 || !absmax_out) return DQ_ERR_INVALID_ARG;
+    if (d > 0 && !rows_ok(v, M, ld, d, 4)) return DQ_ERR_INVALID_ARG;
+    return launch_absmax(v, d, M, ld, absmax_out, as_stream(stream));
+}
+
+static int32_t quantize_common(const float *v, int64_t d, int64_t M, int64_t ld, int32_t b, int field,
+                               float *absmax, int32_t absmax_given, uint64_t seed, uint32_t iter, uint32_t tag,
+                               uint32_t worker0, uint32_t *out_words, int64_t ld_words, float *delta_out,
+                               uint32_t *status, void *stream)
+{
+    if (d < 0 || M <= 0 || !absmax || !delta_out) return DQ_ERR_INVALID_ARG;
+    if (b < 2 || b > 8 || b > field) return DQ_ERR_INVALID_ARG;
+    const int64_t row_words = packed_words(d, field);
+    if (d > 0) {
+        if (!rows_ok(v, M, ld, d, 4)) return DQ_ERR_INVALID_ARG;
+        if (!rows_ok(out_words, M, ld_words, row_words, 4)) return DQ_ERR_INVALID_ARG;
+    }
+    hipStream_t st = as_stream(stream);
+    if (!absmax_given) {
+        int rc = launch_absmax(v, d, M, ld, absmax, st);
+        if (rc != DQ_OK) return rc;
+    }
+    StreamKey key{static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), iter, 0u, tag};
+    // d == 0 still writes delta (= scale of an empty vector, 0): one block per row does that.
+    return launch_quantize_pack(v, d, M, ld, b, field, absmax, key, worker0, out_words, ld_words, delta_out,
+                                status, st);
+}
+
+extern "C" int32_t dq_quantize(const float *v, int64_t d, int64_t M, int64_t ld, int32_t b, float *absmax,
+                               int32_t absmax_given, uint64_t seed, uint32_t iter, uint32_t tag, uint32_t worker0,
+                               int8_t *codes_out, int64_t ld_codes, float *delta_out, uint32_t *status, void *stream)
+{
+    if ((ld_codes % 4) != 0 || ld_codes < d) return DQ_ERR_INVALID_ARG;
+    // int8 codes are 8-bit fields: the packed layout with FIELD = 8 is exactly an int8 array.
+    return quantize_common(v, d, M, ld, b, 8, absmax, absmax_given, seed, iter, tag, worker0,
+                           reinterpret_cast<uint32_t *>(codes_out), ld_codes / 4, delta_out, status, stream);
+}
+
+extern "C" int32_t dq_quantize_pack(const float *v, int64_t d, int64_t M, int64_t ld, int32_t b, float *absmax,
+                                    int32_t absmax_given, uint64_t seed, uint32_t iter, uint32_t tag,
+                                    uint32_t worker0, uint32_t *packed_out, int64_t ld_words, float *delta_out,
+                                    uint32_t *status, void *stream)
+{
+    if (b != 2 && b != 4 && b != 8) return (b >= 2 && b <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
+    return quantize_common(v, d, M, ld, b, b, absmax, absmax_given, seed, iter, tag, worker0, packed_out, ld_words,
+                           delta_out, status, stream);
+}
+
+extern "C" int32_t dq_dequantize(const int8_t *codes, int64_t ld_codes, const float *delta, int64_t d, int64_t M,
+                                 float *v_out, int64_t ld, void *stream)
+{
+    if (d < 0 || M <= 0 || !delta) return DQ_ERR_INVALID_ARG;
+    if (d == 0) return DQ_OK;
+    if ((ld_codes % 4) != 0) return DQ_ERR_INVALID_ARG;
+    if (!rows_ok(codes, M, ld_codes, d, 16) || !rows_ok(v_out, M, ld, d, 4)) return DQ_ERR_INVALID_ARG;
+    dequantize_kernel<<<grid_for(d, M), dim3(kThreads), 0, as_stream(stream)>>>(
+        reinterpret_cast<const uint32_t *>(codes), ld_codes / 4, packed_words(d, 8), delta, d, v_out, ld);
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
+}
+
+extern "C" int32_t dq_pack(const int8_t *codes, int64_t ld_codes, int64_t d, int64_t M, int32_t b,
+                           uint32_t *packed_out, int64_t ld_words, void *stream)
+{
+    if (d < 0 || M <= 0) return DQ_ERR_INVALID_ARG;
+    if (b != 2 && b != 4 && b != 8) return (b >= 2 && b <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
+    if (d == 0) return DQ_OK;
+    const int64_t row_words = packed_words(d, b);
+    if ((ld_codes % 4) != 0) return DQ_ERR_INVALID_ARG;
+    if (!rows_ok(codes, M, ld_codes, d, 16) || !rows_ok(packed_out, M, ld_words, row_words, 4)) return DQ_ERR_INVALID_ARG;
+    const dim3 grid = grid_for(d, M), block(kThreads);
+    const uint32_t *cw = reinterpret_cast<const uint32_t *>(codes);
+    const int64_t cld = ld_codes / 4, crw = packed_words(d, 8);
+    hipStream_t st = as_stream(stream);
+    if (b == 8) pack_kernel<8><<<grid, block, 0, st>>>(cw, cld, crw, d, packed_out, ld_words, row_words);
+    else if (b == 4) pack_kernel<4><<<grid, block, 0, st>>>(cw, cld, crw, d, packed_out, ld_words, row_words);
+    else pack_kernel<2><<<grid, block, 0, st>>>(cw, cld, crw, d, packed_out, ld_words, row_words);
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
+}
+
+extern "C" int32_t dq_unpack(const uint32_t *packed, int64_t ld_words, int64_t d, int64_t M, int32_t b,
+                             int8_t *codes_out, int64_t ld_codes, void *stream)
+{
+    if (d < 0 || M <= 0) return DQ_ERR_INVALID_ARG;
+    if (b != 2 && b != 4 && b != 8) return (b >= 2 && b <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
+    if (d == 0) return DQ_OK;
+    const int64_t row_words = packed_words(d, b);
+    if (!rows_ok(packed, M, ld_words, row_words, 4) || !rows_ok(codes_out, M, ld_codes, d, 16)) return DQ_ERR_INVALID_ARG;
+    const dim3 grid = grid_for(d, M), block(kThreads);
+    hipStream_t st = as_stream(stream);
+    if (b == 8) unpack_kernel<8><<<grid, block, 0, st>>>(packed, ld_words, row_words, d, codes_out, ld_codes);
+    else if (b == 4) unpack_kernel<4><<<grid, block, 0, st>>>(packed, ld_words, row_words, d, codes_out, ld_codes);
+    else unpack_kernel<2><<<grid, block, 0, st>>>(packed, ld_words, row_words, d, codes_out, ld_codes);
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
+}
+
+extern "C" int32_t dq_unpack_dequant_sum(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t d,
+                                         int64_t M, int32_t b, float scale, float *out, void *stream)
+{
+    if (d < 0 || M <= 0 || !delta) return DQ_ERR_INVALID_ARG;
+    if (b != 2 && b != 4 && b != 8) return (b >= 2 && b <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
+    if (d == 0) return DQ_OK;
+    if (!rows_ok(packed, M, ld_words, packed_words(d, b), 4) || !out || !aligned16(out)) return DQ_ERR_INVALID_ARG;
+    return launch_unpack_dequant_sum(packed, ld_words, delta, d, M, b, scale, out, as_stream(stream));
+}
