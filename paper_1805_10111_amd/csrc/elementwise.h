@@ -1,0 +1,128 @@
+// Per-thread building blocks shared by the quantizer, master and worker kernels:
+// 16-coordinate loads/stores, packed-word access, the decode-and-sum of the
+// master, the soft-threshold prox and the per-coordinate sparsifier rule.
+#pragma once
+
+#include "dq_common.h"
+
+namespace dq {
+
+// Words of a thread's 16 coordinates: FIELD in {2,4,8} -> 1, 2, 4 words; FIELD == 32 -> 16 floats.
+template <int FIELD>
+struct Words16 {
+    static constexpr int n = 16 * FIELD / 32;
+};
+
+template <int FIELD>
+__device__ __forceinline__ void load_words(const uint32_t *__restrict__ row, int64_t c, int64_t row_words,
+                                           uint32_t (&w)[Words16<FIELD>::n])
+{
+    constexpr int kWords = Words16<FIELD>::n;
+    const int64_t w0 = c * kWords;
+    if (w0 + kWords <= row_words) {
+        if constexpr (kWords >= 4) {
+#pragma unroll
+            for (int q = 0; q < kWords / 4; ++q) {
+                const uint4 t = reinterpret_cast<const uint4 *>(row + w0)[q];
+                w[4 * q] = t.x; w[4 * q + 1] = t.y; w[4 * q + 2] = t.z; w[4 * q + 3] = t.w;
+            }
+        } else if constexpr (kWords == 2) {
+            const uint2 t = reinterpret_cast<const uint2 *>(row + w0)[0];
+            w[0] = t.x; w[1] = t.y;
+        } else {
+            w[0] = row[w0];
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < kWords; ++i) w[i] = (w0 + i < row_words) ? row[w0 + i] : 0u;
+    }
+}
+
+// Code j (0..15) of the thread's words as a float: sign-extended field, or the float itself.
+template <int FIELD>
+__device__ __forceinline__ int code_of(const uint32_t (&w)[Words16<FIELD>::n], int j)
+{
+    static_assert(FIELD == 2 || FIELD == 4 || FIELD == 8, "packed field width");
+    return __builtin_amdgcn_sbfe(static_cast<int>(w[(j * FIELD) / 32]), (j * FIELD) % 32, FIELD);
+}
+
+template <int FIELD>
+__device__ __forceinline__ float value_of(const uint32_t (&w)[Words16<FIELD>::n], int j)
+{
+    if constexpr (FIELD == 32) return __uint_as_float(w[j]);
+    else return static_cast<float>(code_of<FIELD>(w, j));
+}
+
+__device__ __forceinline__ void load16(const float *__restrict__ src, int64_t base, int64_t d, float (&a)[16])
+{
+    if (base + 16 <= d) {
+        const float4 *p = reinterpret_cast<const float4 *>(src + base);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 t = p[q];
+            a[4 * q] = t.x; a[4 * q + 1] = t.y; a[4 * q + 2] = t.z; a[4 * q + 3] = t.w;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) a[j] = (base + j < d) ? src[base + j] : 0.0f;
+    }
+}
+
+__device__ __forceinline__ void store16(float *__restrict__ out, int64_t base, int64_t d, const float (&a)[16])
+{
+    if (base + 16 <= d) {
+        float4 *p = reinterpret_cast<float4 *>(out + base);
+        p[0] = make_float4(a[0], a[1], a[2], a[3]);
+        p[1] = make_float4(a[4], a[5], a[6], a[7]);
+        p[2] = make_float4(a[8], a[9], a[10], a[11]);
+        p[3] = make_float4(a[12], a[13], a[14], a[15]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            if (base + j < d) out[base + j] = a[j];
+    }
+}
+
+// Alg. 1, master (ii), receive side: acc[j] = sum_{m<M} delta[m] * k_m[16c + j], m ascending, one fma each.
+// For FIELD == 32 the rows hold float32 values and delta is taken as 1.
+template <int FIELD>
+__device__ __forceinline__ void decode_sum16(const uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words,
+                                             const float *__restrict__ delta, int M, int64_t c, int64_t d, float (&acc)[16])
+{
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
+#pragma unroll 4
+    for (int m = 0; m < M; ++m) {
+        uint32_t w[Words16<FIELD>::n];
+        load_words<FIELD>(packed + static_cast<int64_t>(m) * ld_words, c, row_words, w);
+        const float dm = FIELD == 32 ? 1.0f : delta[m];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[j] = fmaf(dm, value_of<FIELD>(w, j), acc[j]);
+    }
+}
+
+// prox of eta*l1*|.| : soft-threshold at kappa = eta*l1.
+__device__ __forceinline__ float soft_threshold(float z, float kappa)
+{
+    const float m = fabsf(z) - kappa;
+    return m > 0.0f ? copysignf(m, z) : 0.0f;
+}
+
+// Eq. (3): keep coordinate with probability p, rescale by 1/p.
+struct SparsifyRule {
+    float amax;        // ||alpha||_inf
+    float c;           // phi / ||alpha||_1 (caller's budget)
+    bool use_budget;   // false: the budget ||alpha||_1/||alpha||_inf, p = |alpha|/amax
+};
+
+__device__ __forceinline__ float sparsify_one(float alpha, const SparsifyRule &r, uint32_t word)
+{
+    const float a = fabsf(alpha);
+    if (a == 0.0f) return 0.0f;
+    float p;
+    if (r.use_budget) p = fminf(a * r.c, 1.0f);
+    else p = a / r.amax;
+    return bernoulli(word, p) ? alpha / p : 0.0f;
+}
+
+}  // namespace dq

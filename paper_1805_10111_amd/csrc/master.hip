@@ -1,0 +1,247 @@
+// Master side of a round (Alg. 1, master (ii) then (i); Alg. 3 momentum update),
+// the epoch-boundary vector operations of Alg. 3, mini-batch index sampling and the
+// stand-alone gradient sparsifier of eq. (3).
+#include "dq_common.h"
+#include "elementwise.h"
+
+namespace dq {
+
+int fill_u32(uint32_t *p, int64_t n, uint32_t value, hipStream_t st);
+int launch_quantize_pack(const float *v, int64_t d, int64_t M, int64_t ld, int b, int field, const float *absmax,
+                         const StreamKey &key, uint32_t worker0, uint32_t *packed, int64_t ld_words, float *delta_out,
+                         uint32_t *status, hipStream_t st);
+
+constexpr int kThreads = 256;
+
+// ------------------------------------------------------------------ master update
+// FIELD in {2,4,8}: packed codes; FIELD == 32: rows of float32 gradients (delta ignored).
+template <int FIELD, bool ACC>
+__global__ __launch_bounds__(kThreads) void master_update_kernel(
+    const uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words, const float *__restrict__ delta, int M,
+    float scale, const float *__restrict__ g_snap, float *__restrict__ x, float *__restrict__ y,
+    const float *__restrict__ x_snap, float *__restrict__ xsum, float eta, float theta, float kappa, int64_t d,
+    uint32_t *__restrict__ absmax_bits)
+{
+    __shared__ uint32_t scratch[kThreads / kWave];
+    const int64_t chunks = (d + 15) / 16;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    uint32_t amax = 0;
+    for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
+        float acc[16];
+        decode_sum16<FIELD>(packed, ld_words, row_words, delta, M, c, d, acc);
+        const int64_t base = c * 16;
+        float gs[16], xv[16], yv[16], xs[16], sm[16];
+        load16(g_snap, base, d, gs);
+        if (ACC) {
+            load16(y, base, d, yv);
+            load16(x_snap, base, d, xs);
+            if (xsum) load16(xsum, base, d, sm);
+        } else {
+            load16(x, base, d, xv);
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float u = scale * acc[j] + gs[j];                 // u = Q-mean + grad f(snapshot)
+            if (ACC) {
+                yv[j] = soft_threshold(yv[j] - eta * u, kappa);     // y <- prox(y - eta u)
+                xv[j] = xs[j] + theta * (yv[j] - xs[j]);            // x <- snapshot + theta (y - snapshot)
+                if (xsum) sm[j] = sm[j] + xv[j];
+            } else {
+                xv[j] = soft_threshold(xv[j] - eta * u, kappa);     // x <- prox(x - eta u)
+            }
+            if (base + j < d) amax = max(amax, abs_bits(xv[j]));
+        }
+        store16(x, base, d, xv);
+        if (ACC) {
+            store16(y, base, d, yv);
+            if (xsum) store16(xsum, base, d, sm);
+        }
+    }
+    amax = block_max_u32(amax, scratch);
+    if (threadIdx.x == 0 && amax != 0) atomicMax(absmax_bits, amax);
+}
+
+template <int FIELD>
+static int launch_master_update(bool acc, dim3 grid, hipStream_t st, const uint32_t *packed, int64_t ld_words,
+                                int64_t row_words, const float *delta, int M, float scale, const float *g_snap, float *x,
+                                float *y, const float *x_snap, float *xsum, float eta, float theta, float kappa,
+                                int64_t d, uint32_t *absmax_bits)
+{
+    if (acc)
+        master_update_kernel<FIELD, true><<<grid, dim3(kThreads), 0, st>>>(packed, ld_words, row_words, delta, M, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, absmax_bits);
+    else
+        master_update_kernel<FIELD, false><<<grid, dim3(kThreads), 0, st>>>(packed, ld_words, row_words, delta, M, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, absmax_bits);
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
+}
+
+__global__ __launch_bounds__(kThreads) void copy_f32_kernel(const float *__restrict__ a, float *__restrict__ b, int64_t n)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (i < n) b[i] = a[i];
+}
+
+// ------------------------------------------------------------------ Alg. 3 epoch boundary
+__global__ __launch_bounds__(kThreads) void acc_mix_kernel(const float *__restrict__ y, const float *__restrict__ xs, float theta,
+                                                           int64_t d, float *__restrict__ x)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (i < d) x[i] = xs[i] + theta * (y[i] - xs[i]);
+}
+
+__global__ __launch_bounds__(kThreads) void acc_snapshot_kernel(const float *__restrict__ xsum, float m, int64_t d,
+                                                                float *__restrict__ xs)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (i < d) xs[i] = xsum[i] / m;
+}
+
+// ------------------------------------------------------------------ sampling
+__global__ __launch_bounds__(kThreads) void sample_indices_kernel(uint32_t n, int64_t B, StreamKey key, uint32_t worker0,
+                                                                  int32_t *__restrict__ idx)
+{
+    const int64_t j = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (j >= B) return;
+    key.worker = worker0 + blockIdx.y;
+    const uint32_t w = stream_word(key, static_cast<uint64_t>(j));
+    idx[static_cast<int64_t>(blockIdx.y) * B + j] = static_cast<int32_t>(__umulhi(w, n));
+}
+
+// ------------------------------------------------------------------ sparsifier, one block per row
+constexpr int kSparsifyThreads = 1024;
+
+__global__ __launch_bounds__(kSparsifyThreads) void sparsify_kernel(
+    const float *__restrict__ alpha, int64_t d, int64_t ld, const float *__restrict__ phi, StreamKey key, uint32_t worker0,
+    float *__restrict__ beta, int64_t ld_out, float *__restrict__ absmax_out, int32_t *__restrict__ nnz_out)
+{
+    __shared__ uint32_t su[kSparsifyThreads / kWave];
+    __shared__ double sd[kSparsifyThreads / kWave];
+    __shared__ int si[kSparsifyThreads / kWave];
+    const int m = blockIdx.x;
+    const float *row = alpha + static_cast<int64_t>(m) * ld;
+    float *out = beta + static_cast<int64_t>(m) * ld_out;
+    key.worker = worker0 + static_cast<uint32_t>(m);
+    key.tag = DQ_TAG_SPARSIFY;
+    // pass 1: ||alpha||_inf and, for a caller-supplied budget, ||alpha||_1 (double, fixed order)
+    uint32_t mb = 0;
+    double s1 = 0.0;
+    for (int64_t i = threadIdx.x; i < d; i += kSparsifyThreads) {
+        const float a = row[i];
+        mb = max(mb, abs_bits(a));
+        s1 += static_cast<double>(fabsf(a));
+    }
+    mb = block_max_u32(mb, su);
+    SparsifyRule rule;
+    rule.amax = __uint_as_float(mb);
+    rule.use_budget = phi != nullptr;
+    rule.c = 0.0f;
+    if (rule.use_budget) {
+        const double total = block_sum_f64(s1, sd);
+        rule.c = phi[m] / static_cast<float>(total);
+    }
+    // pass 2: Bernoulli keep, rescale
+    uint32_t bmax = 0;
+    int kept = 0;
+    for (int64_t i = threadIdx.x; i < d; i += kSparsifyThreads) {
+        const float b = sparsify_one(row[i], rule, stream_word(key, static_cast<uint64_t>(i)));
+        out[i] = b;
+        bmax = max(bmax, abs_bits(b));
+        kept += b != 0.0f ? 1 : 0;
+    }
+    bmax = block_max_u32(bmax, su);
+    kept = block_sum_i32(kept, si);
+    if (threadIdx.x == 0) {
+        absmax_out[m] = __uint_as_float(bmax);
+        nnz_out[m] = kept;
+    }
+}
+
+}  // namespace dq
+
+using namespace dq;
+static inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+extern "C" int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
+                                  float scale, const float *g_snap, float *x, float *y, const float *x_snap, float *xsum,
+                                  float eta, float theta, float l1, int64_t d, int32_t b_x, uint64_t seed, uint32_t iter,
+                                  uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out, uint32_t *status,
+                                  void *stream)
+{
+    if (d <= 0 || M <= 0 || !packed || !g_snap || !x || !xq_packed_out || !delta_x_out || !absmax_x_out)
+        return DQ_ERR_INVALID_ARG;
+    if (b != 32 && !delta) return DQ_ERR_INVALID_ARG;
+    if (y && !x_snap) return DQ_ERR_INVALID_ARG;
+    if (b != 2 && b != 4 && b != 8 && b != 32) return (b >= 2 && b <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
+    if (b_x != 2 && b_x != 4 && b_x != 8 && b_x != 32) return (b_x >= 2 && b_x <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
+    const int64_t row_words = packed_words(d, b);
+    if (ld_words < row_words || (M > 1 && ld_words % 4 != 0)) return DQ_ERR_INVALID_ARG;
+    const void *ptrs[] = {packed, g_snap, x, y, x_snap, xsum, xq_packed_out};
+    for (const void *p : ptrs)
+        if (p && !aligned16(p)) return DQ_ERR_INVALID_ARG;
+    hipStream_t st = as_stream(stream);
+    uint32_t *absmax_bits = reinterpret_cast<uint32_t *>(absmax_x_out);
+    int rc = fill_u32(absmax_bits, 1, 0u, st);
+    if (rc != DQ_OK) return rc;
+    const float kappa = eta * l1;
+    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(d, 16), kThreads)));
+    const bool acc = y != nullptr;
+    const int Mi = static_cast<int>(M);
+    switch (b) {
+    case 8: rc = launch_master_update<8>(acc, grid, st, packed, ld_words, row_words, delta, Mi, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, absmax_bits); break;
+    case 4: rc = launch_master_update<4>(acc, grid, st, packed, ld_words, row_words, delta, Mi, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, absmax_bits); break;
+    case 2: rc = launch_master_update<2>(acc, grid, st, packed, ld_words, row_words, delta, Mi, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, absmax_bits); break;
+    default: rc = launch_master_update<32>(acc, grid, st, packed, ld_words, row_words, delta, Mi, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, absmax_bits); break;
+    }
+    if (rc != DQ_OK) return rc;
+    if (b_x == 32) {
+        // full-precision model: "packed" output is x itself, delta is 1
+        copy_f32_kernel<<<dim3(static_cast<unsigned>(ceil_div(d, kThreads))), dim3(kThreads), 0, st>>>(
+            x, reinterpret_cast<float *>(xq_packed_out), d);
+        DQ_LAUNCH_CHECK();
+        return fill_u32(reinterpret_cast<uint32_t *>(delta_x_out), 1, 0x3F800000u, st);
+    }
+    StreamKey key{static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), iter, 0u, DQ_TAG_MODEL};
+    return launch_quantize_pack(x, d, 1, d, b_x, b_x, absmax_x_out, key, DQ_MASTER_ID, xq_packed_out,
+                                packed_words(d, b_x), delta_x_out, status, st);
+}
+
+extern "C" int32_t dq_acc_mix(const float *y, const float *x_snap, float theta, int64_t d, float *x_out, void *stream)
+{
+    if (d <= 0 || !y || !x_snap || !x_out) return DQ_ERR_INVALID_ARG;
+    acc_mix_kernel<<<dim3(static_cast<unsigned>(ceil_div(d, kThreads))), dim3(kThreads), 0, as_stream(stream)>>>(y, x_snap, theta, d, x_out);
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
+}
+
+extern "C" int32_t dq_acc_snapshot(const float *xsum, int64_t m, int64_t d, float *x_snap_out, void *stream)
+{
+    if (d <= 0 || m <= 0 || !xsum || !x_snap_out) return DQ_ERR_INVALID_ARG;
+    acc_snapshot_kernel<<<dim3(static_cast<unsigned>(ceil_div(d, kThreads))), dim3(kThreads), 0, as_stream(stream)>>>(
+        xsum, static_cast<float>(m), d, x_snap_out);
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
+}
+
+extern "C" int32_t dq_sample_indices(int64_t n, int64_t M, int64_t B, uint64_t seed, uint32_t iter, uint32_t worker0,
+                                     int32_t *idx_out, void *stream)
+{
+    if (n <= 0 || n > 0x7FFFFFFFll || M <= 0 || B <= 0 || !idx_out) return DQ_ERR_INVALID_ARG;
+    StreamKey key{static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), iter, 0u, DQ_TAG_SAMPLE};
+    const dim3 grid(static_cast<unsigned>(ceil_div(B, kThreads)), static_cast<unsigned>(M));
+    sample_indices_kernel<<<grid, dim3(kThreads), 0, as_stream(stream)>>>(static_cast<uint32_t>(n), B, key, worker0, idx_out);
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
+}
+
+extern "C" int32_t dq_sparsify(const float *alpha, int64_t d, int64_t M, int64_t ld, const float *phi, uint64_t seed,
+                               uint32_t iter, uint32_t worker0, float *beta_out, int64_t ld_out, float *absmax_out,
+                               int32_t *nnz_out, void *stream)
+{
+    if (d <= 0 || M <= 0 || !alpha || !beta_out || !absmax_out || !nnz_out || ld < d || ld_out < d)
+        return DQ_ERR_INVALID_ARG;
+    StreamKey key{static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), iter, 0u, DQ_TAG_SPARSIFY};
+    sparsify_kernel<<<dim3(static_cast<unsigned>(M)), dim3(kSparsifyThreads), 0, as_stream(stream)>>>(
+        alpha, d, ld, phi, key, worker0, beta_out, ld_out, absmax_out, nnz_out);
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
+}

@@ -4,6 +4,7 @@
 // 128-bit accesses; each thread owns 16 consecutive coordinates so that it emits
 // whole 32-bit words for every supported field width.
 #include "dq_common.h"
+#include "elementwise.h"
 
 namespace dq {
 
@@ -156,71 +157,17 @@ int launch_quantize_pack(const float *v, int64_t d, int64_t M, int64_t ld, int b
     return DQ_OK;
 }
 
-// ---------------------------------------------------------------- unpack helpers
-template <int FIELD>
-__device__ __forceinline__ void load_words(const uint32_t *__restrict__ row, int64_t c, int64_t row_words,
-                                           uint32_t (&w)[kCoordsPerThread * FIELD / 32])
-{
-    constexpr int kWords = kCoordsPerThread * FIELD / 32;
-    const int64_t w0 = c * kWords;
-    if (w0 + kWords <= row_words) {
-        if constexpr (kWords == 4) {
-            const uint4 t = reinterpret_cast<const uint4 *>(row + w0)[0];
-            w[0] = t.x; w[1] = t.y; w[2] = t.z; w[3] = t.w;
-        } else if constexpr (kWords == 2) {
-            const uint2 t = reinterpret_cast<const uint2 *>(row + w0)[0];
-            w[0] = t.x; w[1] = t.y;
-        } else {
-            w[0] = row[w0];
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < kWords; ++i) w[i] = (w0 + i < row_words) ? row[w0 + i] : 0u;
-    }
-}
-
-template <int FIELD>
-__device__ __forceinline__ int code_of(const uint32_t (&w)[kCoordsPerThread * FIELD / 32], int j)
-{
-    return __builtin_amdgcn_sbfe(static_cast<int>(w[(j * FIELD) / 32]), (j * FIELD) % 32, FIELD);
-}
-
-__device__ __forceinline__ void store16(float *__restrict__ out, int64_t base, int64_t d, const float (&a)[16])
-{
-    if (base + 16 <= d) {
-        float4 *p = reinterpret_cast<float4 *>(out + base);
-        p[0] = make_float4(a[0], a[1], a[2], a[3]);
-        p[1] = make_float4(a[4], a[5], a[6], a[7]);
-        p[2] = make_float4(a[8], a[9], a[10], a[11]);
-        p[3] = make_float4(a[12], a[13], a[14], a[15]);
-    } else {
-#pragma unroll
-        for (int j = 0; j < 16; ++j)
-            if (base + j < d) out[base + j] = a[j];
-    }
-}
-
 // ---------------------------------------------------------------- unpack + dequantize + sum over M
 template <int FIELD>
 __global__ __launch_bounds__(kThreads) void unpack_dequant_sum_kernel(
     const uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words, const float *__restrict__ delta,
     int64_t d, int M, float scale, float *__restrict__ out)
 {
-    constexpr int kWords = kCoordsPerThread * FIELD / 32;
     const int64_t chunks = (d + kCoordsPerThread - 1) / kCoordsPerThread;
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
     for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
         float acc[16];
-#pragma unroll
-        for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
-#pragma unroll 4
-        for (int m = 0; m < M; ++m) {
-            uint32_t w[kWords];
-            load_words<FIELD>(packed + static_cast<int64_t>(m) * ld_words, c, row_words, w);
-            const float dm = delta[m];
-#pragma unroll
-            for (int j = 0; j < 16; ++j) acc[j] = fmaf(dm, static_cast<float>(code_of<FIELD>(w, j)), acc[j]);
-        }
+        decode_sum16<FIELD>(packed, ld_words, row_words, delta, M, c, d, acc);
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[j] = scale * acc[j];
         store16(out, c * kCoordsPerThread, d, acc);
