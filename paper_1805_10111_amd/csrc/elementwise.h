@@ -125,4 +125,61 @@ __device__ __forceinline__ float sparsify_one(float alpha, const SparsifyRule &r
     return bernoulli(word, p) ? alpha / p : 0.0f;
 }
 
+// Eq. (3) on a thread's 16 coordinates (chunk c): in place alpha -> beta.
+__device__ __forceinline__ void sparsify16(float (&a)[16], const SparsifyRule &r, const StreamKey &key, int64_t c)
+{
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const uint4 w = stream_block(key, static_cast<uint32_t>(c * 4 + g));
+        a[4 * g + 0] = sparsify_one(a[4 * g + 0], r, w.x);
+        a[4 * g + 1] = sparsify_one(a[4 * g + 1], r, w.y);
+        a[4 * g + 2] = sparsify_one(a[4 * g + 2], r, w.z);
+        a[4 * g + 3] = sparsify_one(a[4 * g + 3], r, w.w);
+    }
+}
+
+// Q_(delta,b) on a thread's 16 coordinates (chunk c) packed into FIELD-bit fields.
+// Coordinates past the end of the vector must be passed as 0 (they encode as 0).
+// Returns the number of nonzero codes.
+template <int FIELD>
+__device__ __forceinline__ int quantize16(const float (&v)[16], const Scale &s, const StreamKey &key, int64_t c,
+                                          uint32_t (&w)[Words16<FIELD>::n])
+{
+    constexpr uint32_t kMask = (1u << FIELD) - 1u;
+    int nz = 0;
+#pragma unroll
+    for (int i = 0; i < Words16<FIELD>::n; ++i) w[i] = 0u;
+    if (s.inv_delta == 0.0f) return 0;               // degenerate scale: all codes are zero
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const uint4 r = stream_block(key, static_cast<uint32_t>(c * 4 + g));
+        const uint32_t rw[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int j = g * 4 + e;
+            const int k = quantize_one(v[j], s, rw[e]);
+            nz += k != 0 ? 1 : 0;
+            w[(j * FIELD) / 32] |= (static_cast<uint32_t>(k) & kMask) << ((j * FIELD) % 32);
+        }
+    }
+    return nz;
+}
+
+template <int FIELD>
+__device__ __forceinline__ void store_words(uint32_t *__restrict__ out, int64_t c, int64_t row_words,
+                                            const uint32_t (&w)[Words16<FIELD>::n])
+{
+    constexpr int kWords = Words16<FIELD>::n;
+    const int64_t w0 = c * kWords;
+    if (w0 + kWords <= row_words) {
+        if constexpr (kWords == 4) reinterpret_cast<uint4 *>(out + w0)[0] = make_uint4(w[0], w[1], w[2], w[3]);
+        else if constexpr (kWords == 2) reinterpret_cast<uint2 *>(out + w0)[0] = make_uint2(w[0], w[1]);
+        else out[w0] = w[0];
+    } else {
+#pragma unroll
+        for (int i = 0; i < kWords; ++i)
+            if (w0 + i < row_words) out[w0 + i] = w[i];
+    }
+}
+
 }  // namespace dq

@@ -1,0 +1,43 @@
+// Host-side argument bundle of a worker step and the per-layout launchers.
+#pragma once
+
+#include "dq_common.h"
+
+namespace dq {
+
+struct WorkerArgs {
+    const int32_t *idx;
+    int64_t M, B;
+    const uint32_t *xq;
+    const float *delta_x;
+    int b_x;
+    int model_is_snapshot;
+    const float *x_snap, *z_snap;
+    // dq_vr_grad outputs (alpha_out also optional in dq_worker_step)
+    float *alpha_out;
+    int64_t ld;
+    float *absmax_out, *l1norm_out;
+    // dq_worker_step outputs; packed == nullptr selects the dq_vr_grad behaviour
+    int sparsify, b;
+    uint64_t seed;
+    uint32_t iter, worker0;
+    uint32_t *packed;
+    int64_t ld_words;
+    float *delta_out;
+    int32_t *nnz_out;
+    uint32_t *status;
+    void *ws;
+    int64_t ws_bytes;
+};
+
+int64_t dense_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64_t B);
+int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float *z_out, double *obj_out, void *ws,
+                    int64_t ws_bytes, hipStream_t st);
+int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st);
+
+int64_t csr_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64_t B);
+int csr_full_grad(const dq_problem *prob, const float *x, float *g_out, float *z_out, double *obj_out, void *ws,
+                  int64_t ws_bytes, hipStream_t st);
+int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st);
+
+}  // namespace dq

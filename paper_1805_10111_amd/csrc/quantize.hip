@@ -83,8 +83,6 @@ __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(
     uint32_t worker0, uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words,
     float *__restrict__ delta_out, uint32_t *__restrict__ status)
 {
-    constexpr int kWords = kCoordsPerThread * FIELD / 32;     // words per thread: 4, 2, 1
-    constexpr uint32_t kMask = (1u << FIELD) - 1u;
     const int m = blockIdx.y;
     const float *row = v + static_cast<int64_t>(m) * ld;
     uint32_t *out = packed + static_cast<int64_t>(m) * ld_words;
@@ -94,50 +92,14 @@ __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(
         delta_out[m] = s.delta;
         if (s.bad && status) atomicOr(status, 1u);
     }
-    const bool zero_row = s.inv_delta == 0.0f;
     const int64_t chunks = (d + kCoordsPerThread - 1) / kCoordsPerThread;
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
     for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
-        const int64_t base = c * kCoordsPerThread;
-        uint32_t w[kWords];
-#pragma unroll
-        for (int i = 0; i < kWords; ++i) w[i] = 0u;
-        if (!zero_row) {
-            const bool full = base + kCoordsPerThread <= d;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                float a[4];
-                if (full) {
-                    const float4 t = reinterpret_cast<const float4 *>(row + base)[g];
-                    a[0] = t.x; a[1] = t.y; a[2] = t.z; a[3] = t.w;
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const int64_t i = base + g * 4 + e;
-                        a[e] = i < d ? row[i] : 0.0f;
-                    }
-                }
-                const uint4 r = stream_block(key, static_cast<uint32_t>(c * 4 + g));
-                const uint32_t rw[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int j = g * 4 + e;
-                    int k = quantize_one(a[e], s, rw[e]);
-                    if (!full && base + j >= d) k = 0;
-                    w[(j * FIELD) / 32] |= (static_cast<uint32_t>(k) & kMask) << ((j * FIELD) % 32);
-                }
-            }
-        }
-        const int64_t w0 = c * kWords;
-        if (w0 + kWords <= row_words) {
-            if constexpr (kWords == 4) reinterpret_cast<uint4 *>(out + w0)[0] = make_uint4(w[0], w[1], w[2], w[3]);
-            else if constexpr (kWords == 2) reinterpret_cast<uint2 *>(out + w0)[0] = make_uint2(w[0], w[1]);
-            else out[w0] = w[0];
-        } else {
-#pragma unroll
-            for (int i = 0; i < kWords; ++i)
-                if (w0 + i < row_words) out[w0 + i] = w[i];
-        }
+        float a[16];
+        load16(row, c * kCoordsPerThread, d, a);             // coordinates past d read as 0 -> code 0
+        uint32_t w[Words16<FIELD>::n];
+        quantize16<FIELD>(a, s, key, c, w);
+        store_words<FIELD>(out, c, row_words, w);
     }
 }
 
