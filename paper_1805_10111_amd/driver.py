@@ -1,0 +1,140 @@
+"""Epoch loops of AsyLPG / Sparse-AsyLPG / Acc-AsyLPG (Alg. 1-3 of the paper) on one GPU.
+
+Host-side sequencing only: every numerical step is a call into libdq (see include/dq.h).
+The M workers of the parameter-server network are one synchronous round: all M read the
+same b_x-bit model, the master averages the M decoded b-bit gradients and takes one
+proximal (or momentum) step.  ``it = epoch * m + t`` addresses the random streams.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import torch
+
+from . import api as dq
+
+
+@dataclass
+class RunLog:
+    objectives: List[float] = field(default_factory=list)   # P(snapshot) at each epoch start, then final
+    bits_up: int = 0
+    bits_down: int = 0
+    rounds: int = 0
+
+
+class DoubleQuantTrainer:
+    """Device-resident state of one run plus the per-epoch call sequence."""
+
+    def __init__(self, prob: dq.DeviceProblem, algo: str, M: int, B: int, b_x: int, b: int, m: int, lr: float,
+                 seed: int = 0, x0: Optional[torch.Tensor] = None, cache_margins: bool = True):
+        assert algo in ("asylpg", "sparse", "acc")
+        self.prob, self.algo, self.M, self.B, self.b_x, self.b, self.m = prob, algo, M, B, b_x, b, m
+        self.lr, self.seed = float(lr), int(seed)
+        d, n, dev = prob.d, prob.n, prob.y.device
+        f32 = dict(dtype=torch.float32, device=dev)
+        i32 = dict(dtype=torch.int32, device=dev)
+        self.x_snap = torch.zeros(d, **f32) if x0 is None else x0.to(**f32).clone()
+        self.x = self.x_snap.clone()
+        self.y = self.x_snap.clone()                   # Alg. 3: y_m^0 = snapshot^0
+        self.xsum = torch.zeros(d, **f32)
+        self.g_snap = torch.zeros(d, **f32)
+        self.z_snap = torch.zeros(n, **f32) if cache_margins else None
+        self.obj = torch.zeros(1, dtype=torch.float64, device=dev)
+        self.idx = torch.zeros((M, B), **i32)
+        self.xq_words = d if b_x == 32 else dq.packed_words(d, b_x)
+        self.xq = torch.zeros(self.xq_words + 4, **i32)
+        self.delta_x = torch.zeros(1, **f32)
+        self.absmax_x = torch.zeros(1, **f32)
+        self.row_words = d if b == 32 else dq.packed_words(d, b)
+        self.ld_words = (self.row_words + 3) // 4 * 4
+        self.packed = torch.zeros((M, self.ld_words), **i32)
+        self.delta = torch.zeros(M, **f32)
+        self.nnz = torch.zeros((m, M), **i32)
+        self.status = torch.zeros(1, **i32)
+        nbytes = max(dq.dq_workspace_bytes(dq.OP_FULL_GRAD, prob, M, B),
+                     dq.dq_workspace_bytes(dq.OP_VR_GRAD, prob, M, B), 16)
+        self.ws = torch.empty((nbytes + 3) // 4, **f32)
+        self.epoch_index = 0
+        self.log = RunLog()
+
+    # -- one epoch ---------------------------------------------------------------------------
+    def epoch_prologue(self) -> None:
+        """Epoch start of Alg. 1 / Alg. 3 and the full gradient at the snapshot."""
+        e = self.epoch_index
+        if self.algo == "acc":
+            s = e + 1
+            self.theta = 2.0 / (s + 2)                                  # Section 5.1: theta_s = 2/(s+2)
+            self.eta = float(torch.tensor(self.lr, dtype=torch.float32) /
+                             torch.tensor(self.theta, dtype=torch.float32))   # eta_s = lr/theta_s in float32
+            dq.dq_acc_mix(self.y, self.x_snap, self.theta, self.x)
+            self.xsum.zero_()
+        else:
+            self.theta, self.eta = 0.0, self.lr
+            self.x.copy_(self.x_snap)
+        dq.dq_full_grad(self.prob, self.x_snap, self.g_snap, self.z_snap, self.obj, self.ws)
+
+    def round(self, t: int) -> None:
+        e, m, M = self.epoch_index, self.m, self.M
+        it = e * m + t
+        acc = self.algo == "acc"
+        # x equals the snapshot bit for bit exactly at the first round of an epoch of Alg. 1/2,
+        # and of the first epoch of Alg. 3: the master then sends the flag bit of Section 4.1.
+        flag = t == 0 and (not acc or e == 0)
+        if t == 0 and not flag:
+            # Alg. 3, later epochs: x_0 differs from the snapshot, so the master quantizes it (master (i))
+            if self.b_x == 32:
+                self.xq[: self.prob.d].copy_(self.x.view(torch.int32))
+            else:
+                dq.dq_quantize_pack(self.x, self.b_x, self.absmax_x, False, self.seed, it, dq.TAG_MODEL,
+                                    dq.MASTER_ID, self.xq, self.delta_x, self.status)
+        dq.dq_sample_indices(self.prob.n, M, self.B, self.seed, it, 0, self.idx)
+        dq.dq_worker_step(self.prob, self.idx, M, self.B, self.xq, self.delta_x, self.b_x, flag, self.x_snap,
+                          self.z_snap, self.algo == "sparse", self.b, self.seed, it, 0, self.packed, self.delta,
+                          self.nnz[t], None, self.status, self.ws)
+        dq.dq_master_step(self.packed, self.delta, M, self.b, 1.0 / M, self.g_snap, self.x,
+                          self.y if acc else None, self.x_snap, self.xsum if acc else None,
+                          self.eta, self.theta, self.prob.l1, self.b_x, self.seed, it + 1,
+                          self.xq, self.delta_x, self.absmax_x, self.status)
+        self._flags.append(flag)
+
+    def epoch_epilogue(self) -> None:
+        if self.algo == "acc":
+            dq.dq_acc_snapshot(self.xsum, self.m, self.x_snap)
+        else:
+            self.x_snap.copy_(self.x)
+        self.epoch_index += 1
+
+    def run_epoch(self) -> None:
+        self._flags = []
+        self.epoch_prologue()
+        for t in range(self.m):
+            self.round(t)
+        self.epoch_epilogue()
+        self._account()
+
+    def _account(self) -> None:
+        d, M, m = self.prob.d, self.M, self.m
+        self.log.objectives.append(float(self.obj.item()))
+        self.log.rounds += m
+        for flag in self._flags:
+            self.log.bits_down += 1 if flag else 32 + self.b_x * d
+        if self.algo == "sparse":
+            nz = int(self.nnz.sum().item())
+            self.log.bits_up += 32 * m * M + nz * (math.ceil(math.log2(d)) + self.b)
+        else:
+            self.log.bits_up += m * M * (32 + self.b * d)
+
+    def run(self, S: int) -> RunLog:
+        for _ in range(S):
+            self.run_epoch()
+        self.log.objectives.append(self.objective(self.x_snap))
+        if int(self.status.item()) != 0:
+            raise FloatingPointError("a quantization scale was not finite (NaN/Inf in a gradient or the model)")
+        return self.log
+
+    def objective(self, x: torch.Tensor) -> float:
+        g = torch.empty_like(self.g_snap)
+        dq.dq_full_grad(self.prob, x, g, None, self.obj, self.ws)
+        return float(self.obj.item())

@@ -1,0 +1,142 @@
+"""GPU parity of whole rounds and epochs (Alg. 1-3) against the oracle's loops.
+
+Two protocols.  Lock-step: before every round the GPU state is overwritten with the
+oracle's, the GPU runs the round, and its outputs are compared with the oracle's round
+(codes up to decisions flipped by sub-tolerance differences of alpha; the new model to
+1e-5).  Free run: both sides run whole epochs independently from the same seed and the
+objectives at the snapshots are compared.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import algorithms as alg
+import synth
+from gpu_util import dev, host, words
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def dq():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_1805_10111_amd as dq
+    return dq
+
+
+def _trainer(dq, p, cfg, m, seed):
+    from paper_1805_10111_amd.driver import DoubleQuantTrainer
+    P = dq.DeviceProblem.from_host(p)
+    return DoubleQuantTrainer(P, cfg.algo, cfg.M, cfg.B, cfg.b_x, cfg.b, m, cfg.lr, seed=seed)
+
+
+def _small(cfg_name):
+    cfg = synth.CONFIGS[cfg_name]
+    if cfg_name == "C1":
+        return cfg, synth.make_problem(cfg), 40
+    if cfg_name == "C4":
+        return cfg, synth.make_problem(cfg, n=3000), 6
+    return cfg, synth.make_problem(cfg, n=4000), 12
+
+
+@pytest.mark.parametrize("name", ["C1", "C4"])
+def test_lock_step_rounds(dq, name):
+    cfg, p, m = _small(name)
+    seed = 3
+    tr = _trainer(dq, p, cfg, m, seed)
+    rp = oracle.RefProblem(p)
+    d, M, B, b, bx = p.d, cfg.M, cfg.B, cfg.b, cfg.b_x
+    acc = cfg.algo == "acc"
+    x_snap = np.zeros(d, dtype=np.float32)
+    y = x_snap.copy()
+    flips = total = 0
+    for e in range(2):
+        # ---- oracle epoch start
+        if acc:
+            theta = np.float32(2.0 / (e + 3))
+            eta = np.float32(np.float32(cfg.lr) / theta)
+            x = oracle.acc_mix(y, x_snap, theta)
+            xsum = np.zeros(d, dtype=np.float32)
+        else:
+            theta, eta = np.float32(0), np.float32(cfg.lr)
+            x = x_snap.copy()
+        g_snap = oracle.full_grad(rp, x_snap)
+        # ---- GPU epoch start from the oracle's state
+        tr.epoch_index = e
+        tr.x_snap.copy_(dev(x_snap)); tr.y.copy_(dev(y))
+        tr._flags = []
+        tr.epoch_prologue()
+        assert np.abs(host(tr.g_snap) - g_snap).max() <= TOL * np.abs(g_snap).max()
+        assert np.array_equal(host(tr.x), x)
+        for t in range(m):
+            it = e * m + t
+            q, xq_words, dx, bits = alg.model_message(x, x_snap, bx, seed, it)
+            flag = bits == 1
+            # overwrite the GPU state with the oracle's
+            tr.x.copy_(dev(x)); tr.g_snap.copy_(dev(g_snap))
+            if acc:
+                tr.y.copy_(dev(y)); tr.xsum.copy_(dev(xsum))
+            if not flag:
+                tr.xq[: xq_words.size].copy_(dev(xq_words.view(np.int32)))
+                tr.delta_x.copy_(dev(np.array([dx], dtype=np.float32)))
+            tr.round(t)
+            assert tr._flags[-1] == flag
+            # ---- oracle round
+            codes = np.zeros((M, d), dtype=np.int8)
+            deltas = np.zeros(M, dtype=np.float32)
+            for w in range(M):
+                wd, dl, _, _, _, _ = alg.worker_message(rp, q, x_snap, flag, B, b, seed, it, w, cfg.algo == "sparse")
+                codes[w] = oracle.unpack(wd, d, b)
+                deltas[w] = dl
+            if acc:
+                oracle.master_update(codes, deltas, np.float32(1.0 / M), g_snap, x, y, x_snap, xsum, eta=eta,
+                                     theta=theta, l1=rp.l1)
+            else:
+                oracle.master_update(codes, deltas, np.float32(1.0 / M), g_snap, x, eta=eta, l1=rp.l1)
+            # ---- compare the round
+            got_codes = np.stack([oracle.unpack(words(tr.packed)[w], d, b) for w in range(M)])
+            diff = np.abs(got_codes.astype(np.int32) - codes)
+            assert diff.max() <= 1
+            flips += int(diff.sum()); total += diff.size
+            assert np.all(np.abs(host(tr.delta) - deltas) <= 2e-5 * deltas + 1e-30)
+            scale = max(np.abs(x).max(), 1e-30)
+            # a flipped code moves a coordinate by eta*delta/M; everything else agrees to rounding
+            bound = TOL * scale + float(eta) * float(deltas.max()) / M * (diff.max(axis=0) > 0)
+            assert np.all(np.abs(host(tr.x) - x) <= bound + 1e-7 * scale)
+        if acc:
+            x_snap = oracle.acc_snapshot(xsum, m)
+        else:
+            x_snap = x.copy()
+        tr.x.copy_(dev(x))
+        if acc:
+            tr.xsum.copy_(dev(xsum)); tr.y.copy_(dev(y))
+        tr.epoch_epilogue()
+        assert np.array_equal(host(tr.x_snap), x_snap)
+    assert flips <= max(2, 1e-3 * total), (flips, total)
+
+
+@pytest.mark.parametrize("name", ["C1", "C4"])
+def test_free_run_objectives(dq, name):
+    cfg, p, m = _small(name)
+    S = 2
+    tr = _trainer(dq, p, cfg, m, seed=0)
+    log = tr.run(S)
+    ref = alg.run(p, cfg.algo, cfg.M, cfg.B, cfg.b_x, cfg.b, m, S, cfg.lr, seed=0)
+    assert len(log.objectives) == len(ref.objectives) == S + 1
+    for a, b in zip(log.objectives, ref.objectives):
+        assert abs(a - b) <= TOL * abs(b), (log.objectives, ref.objectives)
+    assert log.objectives[-1] < log.objectives[0]
+    assert log.bits_up == ref.bits_up and log.bits_down == ref.bits_down
+    rel = np.abs(host(tr.x_snap) - ref.x_snap).max() / np.abs(ref.x_snap).max()
+    assert rel < 1e-3, rel       # free-running trajectories differ by a few flipped roundings
+
+
+def test_runs_are_reproducible(dq):
+    cfg, p, m = _small("C1")
+    a = _trainer(dq, p, cfg, 10, seed=5); a.run(2)
+    b = _trainer(dq, p, cfg, 10, seed=5); b.run(2)
+    c = _trainer(dq, p, cfg, 10, seed=6); c.run(2)
+    assert torch.equal(a.x_snap, b.x_snap) and torch.equal(a.packed, b.packed)
+    assert not torch.equal(a.x_snap, c.x_snap)
