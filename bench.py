@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the double-quantization hot path on one MI355X.
+
+A step is one synchronous round of the whole path for all M workers: model message ->
+variance-reduced mini-batch gradients -> stochastic quantization -> packing -> master
+decode/aggregate -> prox or momentum update -> model re-quantization, with the epoch
+prologue (full gradient) executed inside the timed region at its real cadence (every m
+rounds).  Inputs are resident in HBM before the clock starts.
+
+Prints ONE JSON line: worker-steps/s (= M * rounds / time) on the accelerated dense
+workload (config C4), the roofline figures of the dominant kernel measured with HIP
+events on the launch stream, the quantizer microbenchmark (config C5) as extra fields,
+and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--config", default="C4", choices=["C1", "C2", "C3", "C4"])
+    ap.add_argument("--n", type=int, default=None, help="override the number of samples (testing only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-quantizer", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    return ap.parse_args()
+
+
+def run_rounds(tr, rounds, events=None):
+    """Advance the trainer by `rounds` rounds, running epoch prologues/epilogues at their cadence."""
+    import torch
+    done = 0
+    while done < rounds:
+        if tr._t == 0:
+            tr._flags = []
+            tr.epoch_prologue()
+        take = min(rounds - done, tr.m - tr._t)
+        for _ in range(take):
+            if events is not None:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                flag = tr.round(tr._t, worker_events=(e0, e1))
+                events.append((e0, e1, flag))
+            else:
+                tr.round(tr._t)
+            tr._t += 1
+        done += take
+        if tr._t == tr.m:
+            tr.epoch_epilogue()
+            tr._t = 0
+
+
+def quantizer_leg(dq, torch):
+    """Config C5: delta reduce, quantize+pack at b in {8,4,2}, decode-and-sum over M=16, on 2^28 coordinates."""
+    import synth
+    N, M = 1 << 28, 16
+    v = torch.from_numpy(synth.mixture_vector(N, seed=0)).cuda()
+    out = {}
+    absmax = torch.zeros(1, device="cuda")
+    delta = torch.zeros(M, device="cuda")
+
+    def timed(fn, reps=5):
+        fn(); torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
+    t = timed(lambda: dq.dq_absmax(v, absmax))
+    out["absmax"] = {"GB/s": round(N * 4 / t * 1e-9, 1), "us": round(t * 1e6, 1)}
+    for b in (8, 4, 2):
+        nw = dq.packed_words(N, b)
+        packed = torch.zeros((M, nw), dtype=torch.int32, device="cuda")
+        t = timed(lambda: dq.dq_quantize_pack(v, b, absmax, True, 0, 0, dq.TAG_GRAD, 3, packed[3], delta[3:4]))
+        out[f"quantize_pack_b{b}"] = {"GB/s": round(N * (4 + b / 8) / t * 1e-9, 1), "us": round(t * 1e6, 1)}
+        for w in range(M):
+            dq.dq_quantize_pack(v, b, absmax, True, 0, 0, dq.TAG_GRAD, w, packed[w], delta[w:w + 1])
+        res = torch.zeros(N, device="cuda")
+        t = timed(lambda: dq.dq_unpack_dequant_sum(packed, delta, N, b, 1.0 / M, res))
+        out[f"unpack_dequant_sum_b{b}_M16"] = {"GB/s": round(N * (M * b / 8 + 4) / t * 1e-9, 1), "us": round(t * 1e6, 1)}
+        del packed, res
+    for k in out:
+        out[k]["frac_of_hbm_peak"] = round(out[k]["GB/s"] / HBM_PEAK_GBS, 3)
+    return out
+
+
+def cpu_baseline(cfg, prob, seconds):
+    """The oracle, as it stands, on a bounded sample of the same workload: whole rounds for `seconds`."""
+    import numpy as np
+    import oracle
+    from oracle import algorithms as alg
+    rp = oracle.RefProblem(prob)
+    d, M, B = prob.d, cfg.M, cfg.B
+    rng = np.random.default_rng(0)
+    x_snap = (0.01 * rng.standard_normal(d)).astype(np.float32)
+    x = (x_snap + 0.001 * rng.standard_normal(d)).astype(np.float32)
+    g_snap = np.zeros(d, dtype=np.float32)
+    y = x.copy()
+    xsum = np.zeros(d, dtype=np.float32)
+    t0 = time.perf_counter()
+    rounds = 0
+    while True:
+        it = rounds + 1
+        q, _, _, _ = alg.model_message(x, x_snap, cfg.b_x, 0, it)
+        codes = np.zeros((M, d), dtype=np.int8)
+        deltas = np.zeros(M, dtype=np.float32)
+        for w in range(M):
+            wd, dl, *_ = alg.worker_message(rp, q, x_snap, False, B, cfg.b, 0, it, w, cfg.algo == "sparse")
+            codes[w] = oracle.unpack(wd, d, cfg.b)
+            deltas[w] = dl
+        if cfg.algo == "acc":
+            oracle.master_update(codes, deltas, np.float32(1 / M), g_snap, x, y, x_snap, xsum, eta=0.1, theta=0.5, l1=rp.l1)
+        else:
+            oracle.master_update(codes, deltas, np.float32(1 / M), g_snap, x, eta=0.1, l1=rp.l1)
+        rounds += 1
+        el = time.perf_counter() - t0
+        if el >= seconds:
+            break
+    return {"value": round(M * rounds / el, 2), "unit": "worker-steps/s", "cores": 1, "kind": "oracle",
+            "sample": f"{rounds} rounds of {cfg.name} (M={M}, B={B}, d={d}; full gradient excluded), "
+                      f"{el:.1f} s, single thread, gcc -O2"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU (the M workers are a batch dimension on it); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import synth
+    import paper_1805_10111_amd as dq
+    from paper_1805_10111_amd.driver import DoubleQuantTrainer
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    cfg = synth.CONFIGS[args.config]
+    t_gen = time.perf_counter()
+    prob = synth.make_problem(cfg, n=args.n)
+    t_gen = time.perf_counter() - t_gen
+    P = dq.DeviceProblem.from_host(prob)
+    tr = DoubleQuantTrainer(P, cfg.algo, cfg.M, cfg.B, cfg.b_x, cfg.b, cfg.m, cfg.lr, seed=cfg.seed)
+    tr._t = 0
+
+    run_rounds(tr, args.warmup)
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    run_rounds(tr, args.steps, events)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    if int(tr.status.item()) != 0:
+        raise FloatingPointError("non-finite quantization scale during the benchmark")
+
+    # dominant kernel: the worker step (all M workers in one call); skip the flag-bit rounds (no rows read)
+    durs = [e0.elapsed_time(e1) * 1e-3 for e0, e1, flag in events if not flag]
+    k_avg = float(np.mean(durs))
+    if prob.dense is not None:
+        rows_bytes = cfg.M * cfg.B * prob.d * 4
+    else:
+        rows_bytes = int(cfg.M * cfg.B * (prob.indptr[-1] / prob.n) * 8)
+    per_worker = tr.xq_words * 4 + prob.d * 4 + tr.row_words * 4 + cfg.B * 8
+    alg_bytes = rows_bytes + cfg.M * per_worker
+    achieved = alg_bytes / k_avg * 1e-9
+
+    result = {
+        "metric": "quantized VR-gradient worker-steps/s + quantize/pack GB/s (% of HBM peak)",
+        "value": round(cfg.M * args.steps / dt, 1),
+        "unit": "worker-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(dt / args.steps * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.algo} logistic, n={prob.n}, d={prob.d}, M={cfg.M}, B={cfg.B}, "
+                               f"b_x={cfg.b_x}, b={cfg.b}, m={cfg.m} rounds/epoch, "
+                               f"{'CSR' if prob.is_csr else 'dense fp32'}; full gradient every m rounds inside the timed region",
+                   "seed": cfg.seed, "datagen_s": round(t_gen, 1)},
+        "roofline": {"bound": "hbm", "kernel": "worker step (VR gradient + quantize + pack, all M workers)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "bytes_per_launch": alg_bytes, "avg_launch_us": round(k_avg * 1e6, 2)},
+    }
+    if not args.no_quantizer:
+        result["quantizer_C5"] = quantizer_leg(dq, torch)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, prob, args.cpu_seconds)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -80,8 +80,13 @@ typedef struct dq_problem {
 const char *dq_version(void);
 /* Last hipError_t (as int) seen by this thread inside the library, 0 if none. */
 int32_t dq_last_device_error(void);
-/* Bytes of device workspace `op` needs for this problem with M workers of batch B. */
+/* Bytes of device workspace `op` needs for this problem with M workers of batch B
+ * (a multiple of 16; negative = DQ_ERR_*).  Workspaces are 16-byte aligned. */
 int64_t dq_workspace_bytes(int32_t op, const dq_problem *prob /*host*/, int64_t M, int64_t B);
+/* Zero-fills a workspace (optional: no operation needs initialised workspace memory;
+ * provided so that a caller can keep its buffers defined).  Two calls that share a
+ * workspace must not run concurrently.  ws_bytes must be a multiple of 16. */
+int32_t dq_workspace_init(void *ws, int64_t ws_bytes, void *stream);
 
 /* ---- Section 3.1: the (delta, b) representation and the quantizer Q ------------- */
 
@@ -181,7 +186,11 @@ int32_t dq_sparsify(const float *alpha, int64_t d, int64_t M, int64_t ld, const 
  * sparsify != 0: Alg. 2, worker (i)-(iii)):  dq_vr_grad -> [dq_sparsify] ->
  * dq_quantize_pack with tag DQ_TAG_GRAD, bit-identical to those calls, without
  * writing alpha to memory.  packed_out: M rows of ld_words words; delta_out[M];
- * nnz_out (nullable) [M] = nonzero codes.  alpha_out (nullable): also store alpha. */
+ * nnz_out (nullable) [M] = nonzero codes.  alpha_out (nullable): also store alpha.
+ * idx == NULL: the mini-batches are sampled inside the kernel, exactly as
+ * dq_sample_indices(n, M, B, seed, iter, worker0, .) would produce them.
+ * b == 32: no gradient quantization, packed_out rows receive alpha (or beta) as
+ * float32 (ld_words >= d) and delta_out = 1. */
 int32_t dq_worker_step(const dq_problem *prob /*host*/, const int32_t *idx, int64_t M, int64_t B,
                        const uint32_t *xq_packed, const float *delta_x, int32_t b_x,
                        int32_t model_is_snapshot, const float *x_snap, const float *z_snap,

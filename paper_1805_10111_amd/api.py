@@ -52,6 +52,7 @@ _SIGS = {
     "dq_version": (C.c_char_p, []),
     "dq_last_device_error": (_i32, []),
     "dq_workspace_bytes": (_i64, [_i32, _vp, _i64, _i64]),
+    "dq_workspace_init": (_i32, [_vp, _i64, _vp]),
     "dq_absmax": (_i32, [_vp, _i64, _i64, _i64, _vp, _vp]),
     "dq_quantize": (_i32, [_vp, _i64, _i64, _i64, _i32, _vp, _i32, _u64, _u32, _u32, _u32, _vp, _i64, _vp, _vp, _vp]),
     "dq_dequantize": (_i32, [_vp, _i64, _vp, _i64, _i64, _vp, _i64, _vp]),
@@ -170,6 +171,20 @@ def dq_last_device_error() -> int:
 
 def dq_workspace_bytes(op: int, prob: DeviceProblem, M: int, B: int) -> int:
     return int(_lib.dq_workspace_bytes(op, prob.ptr, M, B))
+
+
+def dq_workspace_init(ws: torch.Tensor) -> None:
+    _check("dq_workspace_init", _lib.dq_workspace_init(_ptr(ws, None, "ws"), ws.numel() * ws.element_size(), _stream()))
+
+
+def new_workspace(op: int, prob: DeviceProblem, M: int = 1, B: int = 1) -> torch.Tensor:
+    """Allocates and zero-initialises a workspace for `op` (torch owns the memory)."""
+    nbytes = dq_workspace_bytes(op, prob, M, B)
+    if nbytes < 0:
+        raise DqError("dq_workspace_bytes", nbytes)
+    ws = torch.empty((max(nbytes, 16) + 15) // 16 * 4, dtype=torch.float32, device=prob.y.device)
+    dq_workspace_init(ws)
+    return ws
 
 
 # ------------------------------------------------------------------ quantizer
@@ -295,7 +310,7 @@ __all__ = [
     "DqError", "DeviceProblem", "EXPORTS", "LIB_PATH", "packed_words",
     "OK", "ERR_INVALID_ARG", "ERR_UNSUPPORTED", "ERR_WORKSPACE", "ERR_DEVICE",
     "TAG_GRAD", "TAG_MODEL", "TAG_SPARSIFY", "TAG_SAMPLE", "MASTER_ID", "OP_FULL_GRAD", "OP_VR_GRAD",
-    "dq_version", "dq_last_device_error", "dq_workspace_bytes", "dq_absmax", "dq_quantize", "dq_dequantize",
+    "dq_version", "dq_last_device_error", "dq_workspace_bytes", "dq_workspace_init", "new_workspace", "dq_absmax", "dq_quantize", "dq_dequantize",
     "dq_pack", "dq_unpack", "dq_quantize_pack", "dq_unpack_dequant_sum", "dq_sample_indices", "dq_full_grad",
     "dq_vr_grad", "dq_sparsify", "dq_worker_step", "dq_master_step", "dq_acc_mix", "dq_acc_snapshot",
 ]

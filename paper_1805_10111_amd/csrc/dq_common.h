@@ -188,11 +188,12 @@ __device__ __forceinline__ int block_sum_i32(int v, int *scratch)
     return r;
 }
 
-// Sign-extended b-bit field `f` (0-based) of a packed word.
-template <int B>
-__device__ __forceinline__ int field_of(uint32_t word, int f)
+// Sign-extended bit field [offset, offset+width) of a word.  (The builtin returns its
+// result as an unsigned value; the conversion to int here keeps later int->float
+// conversions signed.)
+__device__ __forceinline__ int sext_field(uint32_t word, unsigned offset, unsigned width)
 {
-    return __builtin_amdgcn_sbfe(static_cast<int>(word), f * B, B);
+    return static_cast<int>(__builtin_amdgcn_sbfe(word, offset, width));
 }
 
 // Logistic pieces in float32.

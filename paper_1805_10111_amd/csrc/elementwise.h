@@ -43,7 +43,7 @@ template <int FIELD>
 __device__ __forceinline__ int code_of(const uint32_t (&w)[Words16<FIELD>::n], int j)
 {
     static_assert(FIELD == 2 || FIELD == 4 || FIELD == 8, "packed field width");
-    return __builtin_amdgcn_sbfe(static_cast<int>(w[(j * FIELD) / 32]), (j * FIELD) % 32, FIELD);
+    return sext_field(w[(j * FIELD) / 32], (j * FIELD) % 32, FIELD);
 }
 
 template <int FIELD>

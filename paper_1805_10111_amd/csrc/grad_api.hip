@@ -26,7 +26,25 @@ extern "C" int64_t dq_workspace_bytes(int32_t op, const dq_problem *prob, int64_
     if (check_problem(prob) != DQ_OK) return DQ_ERR_INVALID_ARG;
     if (op != DQ_OP_FULL_GRAD && op != DQ_OP_VR_GRAD) return DQ_ERR_INVALID_ARG;
     if (op == DQ_OP_VR_GRAD && (M <= 0 || B <= 0)) return DQ_ERR_INVALID_ARG;
-    return prob->layout == 0 ? dense_workspace_bytes(op, prob, M, B) : csr_workspace_bytes(op, prob, M, B);
+    const int64_t bytes = prob->layout == 0 ? dense_workspace_bytes(op, prob, M, B) : csr_workspace_bytes(op, prob, M, B);
+    return bytes < 0 ? bytes : (bytes + 15) / 16 * 16;
+}
+
+__global__ void ws_zero_kernel(uint4 *p, int64_t n16)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n16) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+extern "C" int32_t dq_workspace_init(void *ws, int64_t ws_bytes, void *stream)
+{
+    if (!ws || ws_bytes < 0 || !aligned16(ws) || (ws_bytes % 16) != 0) return DQ_ERR_INVALID_ARG;
+    const int64_t n16 = ws_bytes / 16;
+    if (n16 == 0) return DQ_OK;
+    ws_zero_kernel<<<dim3(static_cast<unsigned>(ceil_div(n16, 256))), dim3(256), 0, as_stream(stream)>>>(
+        static_cast<uint4 *>(ws), n16);
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
 }
 
 extern "C" int32_t dq_full_grad(const dq_problem *prob, const float *x, float *g_out, float *z_out, double *obj_out,
@@ -43,7 +61,8 @@ static int32_t worker_common(const dq_problem *prob, const WorkerArgs &a, void *
 {
     int32_t rc = check_problem(prob);
     if (rc != DQ_OK) return rc;
-    if (a.M <= 0 || a.B <= 0 || a.B > 0x7FFFFFFFll || !a.idx || !a.x_snap || !aligned16(a.x_snap)) return DQ_ERR_INVALID_ARG;
+    if (a.M <= 0 || a.B <= 0 || a.B > 0x7FFFFFFFll || !a.x_snap || !aligned16(a.x_snap)) return DQ_ERR_INVALID_ARG;
+    if (!a.idx && !a.packed) return DQ_ERR_INVALID_ARG;          // only dq_worker_step can sample in the kernel
     if (!a.model_is_snapshot) {
         if (!a.xq || !aligned16(a.xq)) return DQ_ERR_INVALID_ARG;
         if (a.b_x < 2 || (a.b_x > 8 && a.b_x != 32)) return DQ_ERR_INVALID_ARG;

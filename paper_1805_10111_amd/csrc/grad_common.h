@@ -45,8 +45,7 @@ __device__ __forceinline__ float model_value(const ModelMsg &q, int64_t j)
 {
     if (q.b_x == 32) return __uint_as_float(q.words[j]);
     const int64_t bit = j * q.b_x;
-    const int k = __builtin_amdgcn_sbfe(static_cast<int>(q.words[bit >> 5]), static_cast<unsigned>(bit & 31),
-                                        static_cast<unsigned>(q.b_x));
+    const int k = sext_field(q.words[bit >> 5], static_cast<unsigned>(bit & 31), static_cast<unsigned>(q.b_x));
     return q.delta_x * static_cast<float>(k);
 }
 

@@ -1,14 +1,22 @@
 // Dense-feature gradient kernels: the epoch prologue (full gradient, Alg. 1) and the
-// worker's variance-reduced mini-batch gradient (Alg. 1, worker (i)), optionally fused
-// with the rest of the worker step (Alg. 1 worker (ii) / Alg. 2 worker (ii)-(iii)).
+// worker's variance-reduced mini-batch gradient (Alg. 1, worker (i)) fused with the rest
+// of the worker step (Alg. 1 worker (ii) / Alg. 2 worker (ii)-(iii)).
 //
-// Work shape: GEMV-like (every matrix element is used for two dot products and one
-// rank-1 update, ~1.5 flop per byte), so the bound is HBM and the kernels are built
-// around reading each feature row exactly once: one wavefront owns a row, holds it in
-// registers (NCH float4 per lane, covering d <= 256*NCH), reduces the margin with a
-// butterfly, and accumulates coef * row into a per-wave register accumulator.  Partial
-// sums leave the block through LDS in a fixed order and are combined by a second
-// small kernel, so results are run-to-run deterministic.
+// Work shape: GEMV-like -- every matrix element feeds one or two dot products and one
+// rank-1 update, about 1.5 flop per byte -- so the bound is HBM and the kernels are
+// built around reading each feature row exactly once.  A block of 256 threads owns a
+// group of rows of one worker; thread t holds float4 columns t, t+256, ... of R rows at
+// a time in registers (R*NC float4), so R full rows (R*16 KB at d = 4096) are in flight
+// per block.  The R margins are reduced through LDS with one barrier per batch, the
+// coefficients are formed redundantly by every thread, and coef*row is accumulated into
+// NC float4 registers per thread.  When one block owns a worker's whole mini-batch it
+// goes straight on to the tail of the worker step; otherwise each block writes its
+// partial sum and a second small kernel adds the partial sums in a fixed order and runs
+// the tail (the kernel boundary is what makes the partial sums visible across the
+// chip's L2 slices; a per-block device-scope fence was measured to cost far more).
+// Either way the summation order is fixed, so results are run-to-run deterministic.
+#include <cstdlib>
+
 #include "dq_common.h"
 #include "elementwise.h"
 #include "grad_common.h"
@@ -16,16 +24,17 @@
 
 namespace dq {
 
-constexpr int kRowThreads = 256;                 // 4 wavefronts per block
+constexpr int kRowThreads = 256;
 constexpr int kRowWaves = kRowThreads / kWave;
+constexpr int kMaxRowsPerBlock = 256;            // mini-batch rows a block may own (LDS metadata)
 
-// Loads the lane's share of a row: float4 number lane + 64*c for c < NCH; zero past d.
-template <int NCH>
-__device__ __forceinline__ void load_row(const float *__restrict__ row, int64_t d, int lane, float4 (&a)[NCH])
+// Thread's share of a row: float4 columns tid + 256*c, c < NC; zero past d.
+template <int NC>
+__device__ __forceinline__ void load_cols(const float *__restrict__ row, int64_t d, float4 (&a)[NC])
 {
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        const int64_t col = 4ll * (lane + kWave * c);
+    for (int c = 0; c < NC; ++c) {
+        const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
         if (col + 3 < d) {
             a[c] = *reinterpret_cast<const float4 *>(row + col);
         } else {
@@ -37,12 +46,19 @@ __device__ __forceinline__ void load_row(const float *__restrict__ row, int64_t 
     }
 }
 
-template <int NCH>
-__device__ __forceinline__ float dot_row(const float4 (&a)[NCH], const float4 (&v)[NCH])
+template <int NC>
+__device__ __forceinline__ void zero_cols(float4 (&a)[NC])
+{
+#pragma unroll
+    for (int c = 0; c < NC; ++c) a[c] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+}
+
+template <int NC>
+__device__ __forceinline__ float dot_cols(const float4 (&a)[NC], const float4 (&v)[NC])
 {
     float s = 0.0f;
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
+    for (int c = 0; c < NC; ++c) {
         s = fmaf(a[c].x, v[c].x, s);
         s = fmaf(a[c].y, v[c].y, s);
         s = fmaf(a[c].z, v[c].z, s);
@@ -51,11 +67,11 @@ __device__ __forceinline__ float dot_row(const float4 (&a)[NCH], const float4 (&
     return s;
 }
 
-template <int NCH>
-__device__ __forceinline__ void axpy_row(float coef, const float4 (&a)[NCH], float4 (&acc)[NCH])
+template <int NC>
+__device__ __forceinline__ void axpy_cols(float coef, const float4 (&a)[NC], float4 (&acc)[NC])
 {
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
+    for (int c = 0; c < NC; ++c) {
         acc[c].x = fmaf(coef, a[c].x, acc[c].x);
         acc[c].y = fmaf(coef, a[c].y, acc[c].y);
         acc[c].z = fmaf(coef, a[c].z, acc[c].z);
@@ -63,116 +79,115 @@ __device__ __forceinline__ void axpy_row(float coef, const float4 (&a)[NCH], flo
     }
 }
 
-// Sum of the block's per-wave accumulators in wave order, through LDS, then to `dst`.
-template <int NCH>
-__device__ __forceinline__ void block_reduce_store(const float4 (&acc)[NCH], float4 *sh, int lane, int wave,
-                                                   float *__restrict__ dst, int64_t d)
+template <int NC>
+__device__ __forceinline__ void store_cols(float *__restrict__ dst, int64_t ldp, const float4 (&a)[NC])
 {
-    for (int w = 0; w < kRowWaves; ++w) {
-        if (wave == w) {
 #pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                const int k = lane + kWave * c;
-                if (w == 0) {
-                    sh[k] = acc[c];
-                } else {
-                    float4 t = sh[k];
-                    t.x += acc[c].x; t.y += acc[c].y; t.z += acc[c].z; t.w += acc[c].w;
-                    sh[k] = t;
-                }
-            }
-        }
-        __syncthreads();
+    for (int c = 0; c < NC; ++c) {
+        const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
+        if (col < ldp) *reinterpret_cast<float4 *>(dst + col) = a[c];       // ldp is a multiple of 4
     }
-    const int64_t d4 = (d + 3) / 4;                       // dst rows are padded to a multiple of 4
-    for (int64_t k = threadIdx.x; k < d4; k += kRowThreads) reinterpret_cast<float4 *>(dst)[k] = sh[k];
 }
 
-// ------------------------------------------------------------------ worker: partial sums
-// grid (P, M).  Wave (blockIdx.x*4 + wave) of worker m takes mini-batch slots r, r+4P, ...
-// partial[(m*P + blockIdx.x) * ldp + j] = sum over the block's rows of coef_i * a_ij.
-template <int NCH, bool HAVE_Z>
-__global__ __launch_bounds__(kRowThreads) void vr_dense_partial_kernel(
-    const float *__restrict__ X, int64_t lda, int64_t n, int64_t d, const float *__restrict__ yv,
-    const int32_t *__restrict__ idx, int B, const uint32_t *__restrict__ xq, const float *__restrict__ delta_x, int b_x,
-    const float *__restrict__ x_snap, const float *__restrict__ z_snap, float *__restrict__ partial, int64_t ldp)
+// Block-wide sums of R per-thread values: wave butterflies, then the 4 wave sums are
+// added in wave order by every thread.  `sh` holds 2 buffers of [kRowWaves][R] floats and
+// is used alternately, so one barrier per call is enough.
+template <int R>
+__device__ __forceinline__ void block_sum_R(float (&v)[R], float *sh, int &buf)
 {
-    __shared__ float4 sh[kWave * NCH];
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int m = blockIdx.y, P = gridDim.x;
-    const ModelMsg msg{xq, b_x == 32 ? 1.0f : delta_x[0], b_x};
-    float4 dx[NCH], xs[HAVE_Z ? 1 : NCH], acc[NCH];
+    float *mine = sh + buf * (kRowWaves * R);
 #pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        const int64_t col = 4ll * (lane + kWave * c);
+    for (int r = 0; r < R; ++r) {
+        const float s = wave_sum_f32(v[r]);
+        if (lane == 0) mine[wave * R + r] = s;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        float s = mine[r];
+#pragma unroll
+        for (int w = 1; w < kRowWaves; ++w) s += mine[w * R + r];
+        v[r] = s;
+    }
+    buf ^= 1;
+}
+
+// ------------------------------------------------------------------ worker step
+struct VrDenseArgs {
+    const float *X; int64_t lda, n, d;
+    const float *y;
+    const int32_t *idx;              // nullable: sampled in the kernel
+    int B, P;
+    const uint32_t *xq; const float *delta_x; int b_x;
+    const float *x_snap, *z_snap;
+    float l2;
+    float *partial; int64_t ldp;
+    // outputs (written by the block that runs the tail)
+    float *alpha_out; int64_t ld;
+    float *absmax_out, *l1norm_out;
+    int sparsify, b;
+    StreamKey key; uint32_t worker0;
+    uint32_t *packed; int64_t ld_words, row_words;
+    float *delta_out; int32_t *nnz_out; uint32_t *status;
+};
+
+// dx = q - snapshot for the thread's columns (q: the dequantized model message); xs = the
+// snapshot itself when HAVE_Z is false (margins at the snapshot must then be recomputed).
+template <int NC, bool HAVE_Z>
+__device__ __forceinline__ void model_minus_snapshot(const VrDenseArgs &a, const ModelMsg &msg, float4 (&dx)[NC],
+                                                     float4 (&xs)[HAVE_Z ? 1 : NC])
+{
+    const int64_t d = a.d;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
         float q[4], s[4];
+        if (col + 3 < d) {
+            const float4 t = *reinterpret_cast<const float4 *>(a.x_snap + col);
+            s[0] = t.x; s[1] = t.y; s[2] = t.z; s[3] = t.w;
+            if (a.b_x == 8) {
+                const uint32_t w = a.xq[col >> 2];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const bool in = col + e < d;
-            s[e] = in ? x_snap[col + e] : 0.0f;
-            q[e] = in ? model_value(msg, col + e) : 0.0f;
+                for (int e = 0; e < 4; ++e) q[e] = msg.delta_x * static_cast<float>(sext_field(w, 8 * e, 8));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) q[e] = model_value(msg, col + e);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool in = col + e < d;
+                s[e] = in ? a.x_snap[col + e] : 0.0f;
+                q[e] = in ? model_value(msg, col + e) : 0.0f;
+            }
         }
         dx[c] = make_float4(q[0] - s[0], q[1] - s[1], q[2] - s[2], q[3] - s[3]);
         if constexpr (!HAVE_Z) xs[c] = make_float4(s[0], s[1], s[2], s[3]);
-        acc[c] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     }
-    const int32_t *my_idx = idx + static_cast<int64_t>(m) * B;
-    const float fB = static_cast<float>(B);
-    for (int r = blockIdx.x * kRowWaves + wave; r < B; r += P * kRowWaves) {
-        const int64_t i = my_idx[r];
-        if (static_cast<uint64_t>(i) >= static_cast<uint64_t>(n)) continue;      // out-of-range index: ignored
-        float4 a[NCH];
-        load_row<NCH>(X + i * lda, d, lane, a);
-        const float dz = wave_sum_f32(dot_row<NCH>(a, dx));
-        float zs;
-        if constexpr (HAVE_Z) zs = z_snap[i];
-        else zs = wave_sum_f32(dot_row<NCH>(a, xs));
-        const float coef = vr_slope_diff(yv[i], zs, dz) / fB;
-        axpy_row<NCH>(coef, a, acc);
-    }
-    block_reduce_store<NCH>(acc, sh, lane, wave, partial + (static_cast<int64_t>(m) * P + blockIdx.x) * ldp, d);
 }
 
-// ------------------------------------------------------------------ worker: combine + tail
-// grid (M), dynamic LDS: d floats.  alpha = sum_p partial_p + l2*(q - snapshot), then either
-// store alpha and its norms (packed == nullptr) or run the worker tail.
-template <int FIELD>
-__global__ __launch_bounds__(kRowThreads) void vr_dense_finish_kernel(
-    const float *__restrict__ partial, int P, int64_t ldp, int64_t d, const uint32_t *__restrict__ xq,
-    const float *__restrict__ delta_x, int b_x, const float *__restrict__ x_snap, float l2,
-    float *__restrict__ alpha_out, int64_t ld, float *__restrict__ absmax_out, float *__restrict__ l1norm_out,
-    int sparsify, int b, StreamKey key, uint32_t worker0, uint32_t *__restrict__ packed, int64_t ld_words,
-    int64_t row_words, float *__restrict__ delta_out, int32_t *__restrict__ nnz_out, uint32_t *__restrict__ status)
+// alpha = acc + l2*(q - snapshot) for worker m, then its norms (dq_vr_grad) or the tail of the
+// worker step (dq_worker_step).  acc holds the full sum over the worker's mini-batch.
+template <int NC>
+__device__ __forceinline__ void worker_finish(const VrDenseArgs &a, int m, const float4 (&acc)[NC], const float4 (&dx)[NC],
+                                              float *sh_alpha, uint32_t *su, int *si, double *sd)
 {
-    extern __shared__ float sh_alpha[];
-    __shared__ uint32_t su[kRowWaves];
-    __shared__ int si[kRowWaves];
-    __shared__ double sd[kRowWaves];
-    const int m = blockIdx.x;
-    const ModelMsg msg{xq, b_x == 32 ? 1.0f : delta_x[0], b_x};
-    const int64_t chunks = (d + 15) / 16;
-    for (int64_t c = threadIdx.x; c < chunks; c += kRowThreads) {
-        const int64_t base = c * 16;
-        float a[16], t[16];
+    const int64_t d = a.d;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) a[j] = 0.0f;
-        for (int p = 0; p < P; ++p) {
-            load16(partial + (static_cast<int64_t>(m) * P + p) * ldp, base, ldp, t);
+    for (int c = 0; c < NC; ++c) {
+        const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
+        const float v[4] = {acc[c].x + a.l2 * dx[c].x, acc[c].y + a.l2 * dx[c].y, acc[c].z + a.l2 * dx[c].z,
+                            acc[c].w + a.l2 * dx[c].w};
 #pragma unroll
-            for (int j = 0; j < 16; ++j) a[j] += t[j];
-        }
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            if (base + j < d) {
-                const float dxj = model_value(msg, base + j) - x_snap[base + j];
-                a[j] = a[j] + l2 * dxj;
-                sh_alpha[base + j] = a[j];
+        for (int e = 0; e < 4; ++e)
+            if (col + e < d) {
+                sh_alpha[col + e] = v[e];
+                if (a.alpha_out) a.alpha_out[static_cast<int64_t>(m) * a.ld + col + e] = v[e];
             }
-        }
-        if (alpha_out) store16(alpha_out + static_cast<int64_t>(m) * ld, base, d, a);
     }
     __syncthreads();
-    if (!packed) {
+    if (!a.packed) {
         uint32_t vmax = 0;
         double s1 = 0.0;
         for (int64_t i = threadIdx.x; i < d; i += kRowThreads) {
@@ -180,17 +195,128 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_finish_kernel(
             s1 += static_cast<double>(fabsf(sh_alpha[i]));
         }
         vmax = block_max_u32(vmax, su);
-        if (threadIdx.x == 0) absmax_out[m] = __uint_as_float(vmax);
-        if (l1norm_out) {
+        if (threadIdx.x == 0) a.absmax_out[m] = __uint_as_float(vmax);
+        if (a.l1norm_out) {
             s1 = block_sum_f64(s1, sd);
-            if (threadIdx.x == 0) l1norm_out[m] = static_cast<float>(s1);
+            if (threadIdx.x == 0) a.l1norm_out[m] = static_cast<float>(s1);
         }
         return;
     }
-    key.worker = worker0 + static_cast<uint32_t>(m);
-    const WorkerOut out{packed + static_cast<int64_t>(m) * ld_words, row_words, delta_out + m,
-                        nnz_out ? nnz_out + m : nullptr, status};
-    worker_tail_from_lds<FIELD>(sh_alpha, d, sparsify != 0, b, key, out, su, si);
+    StreamKey key = a.key;
+    key.worker = a.worker0 + static_cast<uint32_t>(m);
+    const WorkerOut out{a.packed + static_cast<int64_t>(m) * a.ld_words, a.row_words, a.delta_out + m,
+                        a.nnz_out ? a.nnz_out + m : nullptr, a.status};
+    switch (a.b) {
+    case 2: worker_tail_from_lds<2>(sh_alpha, d, a.sparsify != 0, a.b, key, out, su, si); break;
+    case 4: worker_tail_from_lds<4>(sh_alpha, d, a.sparsify != 0, a.b, key, out, su, si); break;
+    case 32: worker_tail_from_lds<32>(sh_alpha, d, a.sparsify != 0, a.b, key, out, su, si); break;
+    default: worker_tail_from_lds<8>(sh_alpha, d, a.sparsify != 0, a.b, key, out, su, si); break;
+    }
+}
+
+template <int NC, int R, bool HAVE_Z>
+__global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs a)
+{
+    __shared__ float sh_red[2 * kRowWaves * R * 2];
+    __shared__ int sh_row[kMaxRowsPerBlock];
+    __shared__ float sh_y[kMaxRowsPerBlock], sh_z[kMaxRowsPerBlock];
+    __shared__ float sh_alpha[4 * kRowThreads * NC];
+    __shared__ uint32_t su[kRowWaves];
+    __shared__ int si[kRowWaves];
+    __shared__ double sd[kRowWaves];
+
+    const int m = blockIdx.y;
+    const int64_t d = a.d;
+    const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
+
+    // ---- rows of this block and their scalars
+    const int per = (a.B + a.P - 1) / a.P;
+    const int r0 = blockIdx.x * per;
+    const int nrows = max(0, min(a.B, r0 + per) - r0);
+    if (static_cast<int>(threadIdx.x) < nrows) {
+        const int r = r0 + threadIdx.x;
+        int64_t i;
+        if (a.idx) {
+            i = a.idx[static_cast<int64_t>(m) * a.B + r];
+        } else {
+            StreamKey sk = a.key;
+            sk.worker = a.worker0 + static_cast<uint32_t>(m);
+            sk.tag = DQ_TAG_SAMPLE;
+            i = __umulhi(stream_word(sk, static_cast<uint64_t>(r)), static_cast<uint32_t>(a.n));
+        }
+        const bool ok = static_cast<uint64_t>(i) < static_cast<uint64_t>(a.n);   // out-of-range index: ignored
+        sh_row[threadIdx.x] = ok ? static_cast<int>(i) : -1;
+        sh_y[threadIdx.x] = ok ? a.y[i] : 1.0f;
+        sh_z[threadIdx.x] = (ok && HAVE_Z) ? a.z_snap[i] : 0.0f;
+    }
+
+    // ---- q - snapshot (and the snapshot itself when margins are not cached) for the thread's columns
+    float4 dx[NC], xs[HAVE_Z ? 1 : NC], acc[NC];
+    model_minus_snapshot<NC, HAVE_Z>(a, msg, dx, xs);
+    zero_cols<NC>(acc);
+    __syncthreads();
+
+    // ---- stream the rows, R at a time
+    const float fB = static_cast<float>(a.B);
+    int buf = 0;
+    for (int rb = 0; rb < nrows; rb += R) {
+        float4 row[R][NC];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int i = rb + r < nrows ? sh_row[rb + r] : -1;
+            if (i >= 0) load_cols<NC>(a.X + static_cast<int64_t>(i) * a.lda, d, row[r]);
+            else zero_cols<NC>(row[r]);
+        }
+        float dots[HAVE_Z ? R : 2 * R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            dots[r] = dot_cols<NC>(row[r], dx);
+            if constexpr (!HAVE_Z) dots[R + r] = dot_cols<NC>(row[r], xs);
+        }
+        block_sum_R<HAVE_Z ? R : 2 * R>(dots, sh_red, buf);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const bool live = rb + r < nrows && sh_row[min(rb + r, kMaxRowsPerBlock - 1)] >= 0;
+            if (live) {
+                const float zs = HAVE_Z ? sh_z[rb + r] : dots[HAVE_Z ? r : R + r];
+                const float coef = vr_slope_diff(sh_y[rb + r], zs, dots[r]) / fB;
+                axpy_cols<NC>(coef, row[r], acc);
+            }
+        }
+    }
+
+    if (a.P > 1) {          // several blocks per worker: leave the partial sum for vr_dense_finish_kernel
+        store_cols<NC>(a.partial + (static_cast<int64_t>(m) * a.P + blockIdx.x) * a.ldp, a.ldp, acc);
+        return;
+    }
+    worker_finish<NC>(a, m, acc, dx, sh_alpha, su, si, sd);
+}
+
+// Second stage when a worker's mini-batch was split over P > 1 blocks.  grid (M).
+template <int NC>
+__global__ __launch_bounds__(kRowThreads) void vr_dense_finish_kernel(const VrDenseArgs a)
+{
+    __shared__ float sh_alpha[4 * kRowThreads * NC];
+    __shared__ uint32_t su[kRowWaves];
+    __shared__ int si[kRowWaves];
+    __shared__ double sd[kRowWaves];
+    const int m = blockIdx.x;
+    const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
+    float4 dx[NC], xs[1], acc[NC];
+    model_minus_snapshot<NC, true>(a, msg, dx, xs);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
+        float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (col < a.ldp) {
+            for (int p = 0; p < a.P; ++p) {
+                const float4 t = *reinterpret_cast<const float4 *>(a.partial + (static_cast<int64_t>(m) * a.P + p) * a.ldp + col);
+                s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+            }
+        }
+        acc[c] = s;
+    }
+    worker_finish<NC>(a, m, acc, dx, sh_alpha, su, si, sd);
 }
 
 // Flag-bit round (Section 4.1: the model equals the snapshot): alpha = 0 for every worker.
@@ -211,64 +337,95 @@ __global__ __launch_bounds__(kRowThreads) void worker_zero_kernel(
     }
 }
 
+int launch_worker_zero(const WorkerArgs &a, int64_t d, int64_t row_words, hipStream_t st)
+{
+    const int64_t span = row_words > d ? row_words : d;
+    worker_zero_kernel<<<dim3(static_cast<unsigned>(ceil_div(span, kRowThreads)), static_cast<unsigned>(a.M)), dim3(kRowThreads), 0, st>>>(
+        d, a.alpha_out, a.ld, a.absmax_out, a.l1norm_out, a.packed, a.ld_words, row_words, a.delta_out,
+        a.b == 32 ? 1.0f : 0.0f, a.nnz_out);
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
+}
+
 // ------------------------------------------------------------------ epoch prologue: partial sums
-// grid (P).  Wave g = blockIdx.x*4 + wave takes rows g, g + 4P, ...
-template <int NCH>
+// grid (P).  Block p owns rows [p*per, (p+1)*per).
+template <int NC, int R>
 __global__ __launch_bounds__(kRowThreads) void full_dense_partial_kernel(
     const float *__restrict__ X, int64_t lda, int64_t n, int64_t d, const float *__restrict__ yv,
     const float *__restrict__ x, float *__restrict__ z_out, float *__restrict__ partial, int64_t ldp,
     double *__restrict__ loss_partial)
 {
-    __shared__ float4 sh[kWave * NCH];
-    __shared__ double sh_loss[kRowWaves];
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int P = gridDim.x;
-    float4 xv[NCH], acc[NCH];
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) acc[c] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    load_row<NCH>(x, d, lane, xv);
+    __shared__ float sh_red[2 * kRowWaves * R];
+    const int64_t per = (n + gridDim.x - 1) / gridDim.x;
+    const int64_t i0 = blockIdx.x * per, i1 = min(n, i0 + per);
+    float4 xv[NC], acc[NC];
+    zero_cols<NC>(acc);
+    load_cols<NC>(x, d, xv);
     const float fn = static_cast<float>(n);
     double loss = 0.0;
-    for (int64_t i = blockIdx.x * kRowWaves + wave; i < n; i += static_cast<int64_t>(P) * kRowWaves) {
-        float4 a[NCH];
-        load_row<NCH>(X + i * lda, d, lane, a);
-        const float z = wave_sum_f32(dot_row<NCH>(a, xv));
-        const float y = yv[i];
-        if (z_out && lane == 0) z_out[i] = z;
-        loss += static_cast<double>(logistic_loss(y * z));
-        axpy_row<NCH>(logistic_slope(y, z) / fn, a, acc);
+    int buf = 0;
+    for (int64_t ib = i0; ib < i1; ib += R) {
+        float4 row[R][NC];
+        float z[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (ib + r < i1) load_cols<NC>(X + (ib + r) * lda, d, row[r]);
+            else zero_cols<NC>(row[r]);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) z[r] = dot_cols<NC>(row[r], xv);
+        block_sum_R<R>(z, sh_red, buf);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (ib + r < i1) {
+                const float y = yv[ib + r];
+                if (z_out && threadIdx.x == 0) z_out[ib + r] = z[r];
+                loss += static_cast<double>(logistic_loss(y * z[r]));
+                axpy_cols<NC>(logistic_slope(y, z[r]) / fn, row[r], acc);
+            }
+        }
     }
-    if (lane == 0) sh_loss[wave] = loss;
-    block_reduce_store<NCH>(acc, sh, lane, wave, partial + static_cast<int64_t>(blockIdx.x) * ldp, d);
-    if (threadIdx.x == 0) {
-        double t = sh_loss[0];
-        for (int w = 1; w < kRowWaves; ++w) t += sh_loss[w];
-        loss_partial[blockIdx.x] = t;
-    }
+    store_cols<NC>(partial + static_cast<int64_t>(blockIdx.x) * ldp, ldp, acc);
+    if (threadIdx.x == 0) loss_partial[blockIdx.x] = loss;
 }
 
-// g = sum_p partial_p + l2*x; block 0 also writes P(x) = loss/n + (l2/2)||x||^2 + l1||x||_1.
-__global__ __launch_bounds__(kWave) void full_finish_kernel(
+// g = sum_p partial_p + l2*x.  Block (64 x 16): thread (tx, ty) adds partials ty, ty+16, ... of
+// float4 column blockIdx.x*64 + tx; the 16 sub-sums are then added in ty order.
+// Block 0 also writes P(x) = loss/n + (l2/2)||x||^2 + l1||x||_1.
+constexpr int kFinishY = 16;
+__global__ __launch_bounds__(kWave *kFinishY) void full_finish_kernel(
     const float *__restrict__ partial, int P, int64_t ldp, int64_t n, int64_t d, const float *__restrict__ x, float l2,
     float l1, const double *__restrict__ loss_partial, float *__restrict__ g_out, double *__restrict__ obj_out)
 {
-    const int64_t k = static_cast<int64_t>(blockIdx.x) * kWave + threadIdx.x;      // float4 index
+    __shared__ float4 sh[kFinishY][kWave];
+    __shared__ double sdl[kFinishY * 3];
+    const int tx = threadIdx.x, ty = threadIdx.y;
+    const int64_t k = static_cast<int64_t>(blockIdx.x) * kWave + tx;      // float4 index
     const int64_t col = 4 * k;
-    if (col < d) {
-        float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        for (int p = 0; p < P; ++p) {
+    float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (col < ldp) {
+        for (int p = ty; p < P; p += kFinishY) {
             const float4 t = reinterpret_cast<const float4 *>(partial + static_cast<int64_t>(p) * ldp)[k];
             s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
         }
-        const float v[4] = {s.x, s.y, s.z, s.w};
+    }
+    sh[ty][tx] = s;
+    __syncthreads();
+    if (ty == 0 && col < d) {
+        float4 t = sh[0][tx];
+        for (int j = 1; j < kFinishY; ++j) {
+            t.x += sh[j][tx].x; t.y += sh[j][tx].y; t.z += sh[j][tx].z; t.w += sh[j][tx].w;
+        }
+        const float v[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e)
             if (col + e < d) g_out[col + e] = v[e] + l2 * x[col + e];
     }
     if (blockIdx.x == 0 && obj_out) {
+        const int tid = ty * kWave + tx, nt = kWave * kFinishY;
         double loss = 0.0, sq = 0.0, ab = 0.0;
-        for (int p = threadIdx.x; p < P; p += kWave) loss += loss_partial[p];
-        for (int64_t j = threadIdx.x; j < d; j += kWave) {
+        for (int p = tid; p < P; p += nt) loss += loss_partial[p];
+        for (int64_t j = tid; j < d; j += nt) {
             const double xj = static_cast<double>(x[j]);
             sq += xj * xj;
             ab += fabs(xj);
@@ -276,27 +433,38 @@ __global__ __launch_bounds__(kWave) void full_finish_kernel(
         loss = wave_sum_f64(loss);
         sq = wave_sum_f64(sq);
         ab = wave_sum_f64(ab);
-        if (threadIdx.x == 0)
-            obj_out[0] = loss / static_cast<double>(n) + 0.5 * static_cast<double>(l2) * sq + static_cast<double>(l1) * ab;
+        if (tx == 0) { sdl[ty * 3] = loss; sdl[ty * 3 + 1] = sq; sdl[ty * 3 + 2] = ab; }
+        __syncthreads();
+        if (tid == 0) {
+            double L = 0.0, S = 0.0, A = 0.0;
+            for (int j = 0; j < kFinishY; ++j) { L += sdl[j * 3]; S += sdl[j * 3 + 1]; A += sdl[j * 3 + 2]; }
+            obj_out[0] = L / static_cast<double>(n) + 0.5 * static_cast<double>(l2) * S + static_cast<double>(l1) * A;
+        }
     }
 }
 
 // ------------------------------------------------------------------ host side
-static int dense_nch(int64_t d) { return d <= 1024 ? 4 : d <= 2048 ? 8 : d <= 4096 ? 16 : 0; }
+static int dense_nc(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 4096 ? 4 : 0; }
 
 int64_t dense_vr_splits(int64_t M, int64_t B)
 {
-    // blocks per worker: aim at ~768 blocks in flight, at least one mini-batch row per wavefront
-    int64_t P = ceil_div(768, M);
-    const int64_t by_rows = ceil_div(B, kRowWaves);
+    // blocks per worker: about 1024 blocks in the grid, at least 4 rows per block when the batch allows
+    static const int64_t target = [] {
+        const char *e = getenv("DQ_VR_BLOCKS");
+        return e ? atoll(e) : 512ll;
+    }();
+    int64_t P = ceil_div(target, M);
+    const int64_t by_rows = ceil_div(B, 4);
     if (P > by_rows) P = by_rows;
+    const int64_t need = ceil_div(B, kMaxRowsPerBlock);        // a block owns at most kMaxRowsPerBlock rows
+    if (P < need) P = need;
     if (P < 1) P = 1;
     return P;
 }
 
 int64_t dense_full_splits(int64_t n)
 {
-    int64_t P = ceil_div(n, kRowWaves * 8);
+    int64_t P = ceil_div(n, 16);
     if (P > 1024) P = 1024;
     if (P < 1) P = 1;
     return P;
@@ -304,6 +472,7 @@ int64_t dense_full_splits(int64_t n)
 
 static int64_t pad4(int64_t d) { return (d + 3) / 4 * 4; }
 
+// Workspace of a worker step: partial sums, M*P*ldp floats (unused when P == 1).
 int64_t dense_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64_t B)
 {
     const int64_t ldp = pad4(prob->d);
@@ -318,79 +487,70 @@ int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float 
                     int64_t ws_bytes, hipStream_t st)
 {
     const int64_t d = prob->d, n = prob->n;
-    const int nch = dense_nch(d);
-    if (nch == 0) return DQ_ERR_UNSUPPORTED;
+    const int nc = dense_nc(d);
+    if (nc == 0) return DQ_ERR_UNSUPPORTED;
     if (ws_bytes < dense_workspace_bytes(DQ_OP_FULL_GRAD, prob, 0, 0) || !ws) return DQ_ERR_WORKSPACE;
     const int64_t ldp = pad4(d);
     const int P = static_cast<int>(dense_full_splits(n));
     float *partial = static_cast<float *>(ws);
     double *loss_partial = reinterpret_cast<double *>(partial + static_cast<int64_t>(P) * ldp);
     const dim3 grid(P), block(kRowThreads);
-    switch (nch) {
-    case 4: full_dense_partial_kernel<4><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
-    case 8: full_dense_partial_kernel<8><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
-    default: full_dense_partial_kernel<16><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
+    switch (nc) {
+    case 1: full_dense_partial_kernel<1, 8><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
+    case 2: full_dense_partial_kernel<2, 4><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
+    default: full_dense_partial_kernel<4, 4><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
     }
     DQ_LAUNCH_CHECK();
-    full_finish_kernel<<<dim3(static_cast<unsigned>(ceil_div(ceil_div(d, 4), kWave))), dim3(kWave), 0, st>>>(
+    full_finish_kernel<<<dim3(static_cast<unsigned>(ceil_div(ceil_div(d, 4), kWave))), dim3(kWave, kFinishY), 0, st>>>(
         partial, P, ldp, n, d, x, prob->l2, prob->l1, loss_partial, g_out, obj_out);
     DQ_LAUNCH_CHECK();
     return DQ_OK;
 }
 
-template <int NCH>
-static void launch_vr_partial(bool have_z, dim3 grid, hipStream_t st, const dq_problem *prob, const int32_t *idx, int B,
-                              const uint32_t *xq, const float *delta_x, int b_x, const float *x_snap, const float *z_snap,
-                              float *partial, int64_t ldp)
+template <int NC, int R>
+static void launch_vr(bool have_z, dim3 grid, hipStream_t st, const VrDenseArgs &k)
 {
-    if (have_z)
-        vr_dense_partial_kernel<NCH, true><<<grid, dim3(kRowThreads), 0, st>>>(prob->dense, prob->lda, prob->n, prob->d, prob->y, idx, B, xq, delta_x, b_x, x_snap, z_snap, partial, ldp);
-    else
-        vr_dense_partial_kernel<NCH, false><<<grid, dim3(kRowThreads), 0, st>>>(prob->dense, prob->lda, prob->n, prob->d, prob->y, idx, B, xq, delta_x, b_x, x_snap, z_snap, partial, ldp);
+    if (have_z) vr_dense_kernel<NC, R, true><<<grid, dim3(kRowThreads), 0, st>>>(k);
+    else vr_dense_kernel<NC, R, false><<<grid, dim3(kRowThreads), 0, st>>>(k);
 }
 
 int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
 {
     const int64_t d = prob->d;
-    const int nch = dense_nch(d);
-    if (nch == 0) return DQ_ERR_UNSUPPORTED;
+    const int nc = dense_nc(d);
+    if (nc == 0) return DQ_ERR_UNSUPPORTED;
     const int64_t row_words = a.packed ? (a.b == 32 ? d : packed_words(d, a.b)) : 0;
-    if (a.model_is_snapshot) {
-        const int64_t span = row_words > d ? row_words : d;
-        worker_zero_kernel<<<dim3(static_cast<unsigned>(ceil_div(span, kRowThreads)), static_cast<unsigned>(a.M)), dim3(kRowThreads), 0, st>>>(
-            d, a.alpha_out, a.ld, a.absmax_out, a.l1norm_out, a.packed, a.ld_words, row_words, a.delta_out,
-            a.b == 32 ? 1.0f : 0.0f, a.nnz_out);
-        DQ_LAUNCH_CHECK();
-        return DQ_OK;
-    }
+    if (a.model_is_snapshot) return launch_worker_zero(a, d, row_words, st);
     if (a.ws_bytes < dense_workspace_bytes(DQ_OP_VR_GRAD, prob, a.M, a.B) || !a.ws) return DQ_ERR_WORKSPACE;
-    const int64_t ldp = pad4(d);
-    const int P = static_cast<int>(dense_vr_splits(a.M, a.B));
-    float *partial = static_cast<float *>(a.ws);
-    const dim3 grid(P, static_cast<unsigned>(a.M));
+    VrDenseArgs k{};
+    k.X = prob->dense; k.lda = prob->lda; k.n = prob->n; k.d = d; k.y = prob->y;
+    k.idx = a.idx; k.B = static_cast<int>(a.B); k.P = static_cast<int>(dense_vr_splits(a.M, a.B));
+    k.xq = a.xq; k.delta_x = a.delta_x; k.b_x = a.b_x; k.x_snap = a.x_snap; k.z_snap = a.z_snap; k.l2 = prob->l2;
+    k.partial = static_cast<float *>(a.ws);
+    k.ldp = pad4(d);
+    k.alpha_out = a.alpha_out; k.ld = a.ld; k.absmax_out = a.absmax_out; k.l1norm_out = a.l1norm_out;
+    k.sparsify = a.sparsify; k.b = a.b;
+    k.key = StreamKey{static_cast<uint32_t>(a.seed), static_cast<uint32_t>(a.seed >> 32), a.iter, 0u, DQ_TAG_GRAD};
+    k.worker0 = a.worker0;
+    k.packed = a.packed; k.ld_words = a.ld_words; k.row_words = row_words;
+    k.delta_out = a.delta_out; k.nnz_out = a.nnz_out; k.status = a.status;
+    const dim3 grid(k.P, static_cast<unsigned>(a.M));
     const bool have_z = a.z_snap != nullptr;
-    const int B = static_cast<int>(a.B);
-    switch (nch) {
-    case 4: launch_vr_partial<4>(have_z, grid, st, prob, a.idx, B, a.xq, a.delta_x, a.b_x, a.x_snap, a.z_snap, partial, ldp); break;
-    case 8: launch_vr_partial<8>(have_z, grid, st, prob, a.idx, B, a.xq, a.delta_x, a.b_x, a.x_snap, a.z_snap, partial, ldp); break;
-    default: launch_vr_partial<16>(have_z, grid, st, prob, a.idx, B, a.xq, a.delta_x, a.b_x, a.x_snap, a.z_snap, partial, ldp); break;
+    switch (nc) {
+    case 1: launch_vr<1, 8>(have_z, grid, st, k); break;
+    case 2: launch_vr<2, 4>(have_z, grid, st, k); break;
+    default: launch_vr<4, 4>(have_z, grid, st, k); break;
     }
     DQ_LAUNCH_CHECK();
-    const size_t lds = static_cast<size_t>(d) * sizeof(float);
-    const dim3 fgrid(static_cast<unsigned>(a.M)), fblock(kRowThreads);
-    const StreamKey key{static_cast<uint32_t>(a.seed), static_cast<uint32_t>(a.seed >> 32), a.iter, 0u, DQ_TAG_GRAD};
-#define DQ_FINISH(F)                                                                                                   \
-    vr_dense_finish_kernel<F><<<fgrid, fblock, lds, st>>>(partial, P, ldp, d, a.xq, a.delta_x, a.b_x, a.x_snap, prob->l2, \
-        a.alpha_out, a.ld, a.absmax_out, a.l1norm_out, a.sparsify, a.b, key, a.worker0, a.packed, a.ld_words, row_words,  \
-        a.delta_out, a.nnz_out, a.status)
-    switch (a.packed ? a.b : 8) {
-    case 2: DQ_FINISH(2); break;
-    case 4: DQ_FINISH(4); break;
-    case 32: DQ_FINISH(32); break;
-    default: DQ_FINISH(8); break;
+    if (k.P > 1) {
+        const dim3 fgrid(static_cast<unsigned>(a.M)), fblock(kRowThreads);
+        switch (nc) {
+        case 1: vr_dense_finish_kernel<1><<<fgrid, fblock, 0, st>>>(k); break;
+        case 2: vr_dense_finish_kernel<2><<<fgrid, fblock, 0, st>>>(k); break;
+        default: vr_dense_finish_kernel<4><<<fgrid, fblock, 0, st>>>(k); break;
+        }
+        DQ_LAUNCH_CHECK();
     }
-#undef DQ_FINISH
-    DQ_LAUNCH_CHECK();
     return DQ_OK;
 }
 

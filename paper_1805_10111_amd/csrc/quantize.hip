@@ -68,7 +68,11 @@ int launch_absmax(const float *v, int64_t d, int64_t M, int64_t ld, float *absma
     int rc = fill_u32(reinterpret_cast<uint32_t *>(absmax_out), M, 0u, st);
     if (rc != DQ_OK) return rc;
     if (d > 0) {
-        absmax_kernel<<<grid_for(d, M), dim3(kThreads), 0, st>>>(v, d, ld, reinterpret_cast<uint32_t *>(absmax_out));
+        // every block ends in one atomic on the row's slot: keep the grid small (grid-stride loop)
+        dim3 grid = grid_for(d, M);
+        const unsigned cap = static_cast<unsigned>(ceil_div(4096, M));
+        if (grid.x > cap) grid.x = cap;
+        absmax_kernel<<<grid, dim3(kThreads), 0, st>>>(v, d, ld, reinterpret_cast<uint32_t *>(absmax_out));
         DQ_LAUNCH_CHECK();
     }
     return DQ_OK;

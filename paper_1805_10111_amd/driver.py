@@ -53,9 +53,8 @@ class DoubleQuantTrainer:
         self.delta = torch.zeros(M, **f32)
         self.nnz = torch.zeros((m, M), **i32)
         self.status = torch.zeros(1, **i32)
-        nbytes = max(dq.dq_workspace_bytes(dq.OP_FULL_GRAD, prob, M, B),
-                     dq.dq_workspace_bytes(dq.OP_VR_GRAD, prob, M, B), 16)
-        self.ws = torch.empty((nbytes + 3) // 4, **f32)
+        self.ws_full = dq.new_workspace(dq.OP_FULL_GRAD, prob)
+        self.ws = dq.new_workspace(dq.OP_VR_GRAD, prob, M, B)
         self.epoch_index = 0
         self.log = RunLog()
 
@@ -73,9 +72,11 @@ class DoubleQuantTrainer:
         else:
             self.theta, self.eta = 0.0, self.lr
             self.x.copy_(self.x_snap)
-        dq.dq_full_grad(self.prob, self.x_snap, self.g_snap, self.z_snap, self.obj, self.ws)
+        dq.dq_full_grad(self.prob, self.x_snap, self.g_snap, self.z_snap, self.obj, self.ws_full)
 
-    def round(self, t: int) -> None:
+    def round(self, t: int, worker_events=None) -> bool:
+        """One synchronous round; returns True if it was a flag-bit round.  `worker_events`: optional pair of
+        torch.cuda.Event recorded on the current stream right before / after the worker-step launch."""
         e, m, M = self.epoch_index, self.m, self.M
         it = e * m + t
         acc = self.algo == "acc"
@@ -90,14 +91,19 @@ class DoubleQuantTrainer:
                 dq.dq_quantize_pack(self.x, self.b_x, self.absmax_x, False, self.seed, it, dq.TAG_MODEL,
                                     dq.MASTER_ID, self.xq, self.delta_x, self.status)
         dq.dq_sample_indices(self.prob.n, M, self.B, self.seed, it, 0, self.idx)
+        if worker_events is not None:
+            worker_events[0].record()
         dq.dq_worker_step(self.prob, self.idx, M, self.B, self.xq, self.delta_x, self.b_x, flag, self.x_snap,
                           self.z_snap, self.algo == "sparse", self.b, self.seed, it, 0, self.packed, self.delta,
                           self.nnz[t], None, self.status, self.ws)
+        if worker_events is not None:
+            worker_events[1].record()
         dq.dq_master_step(self.packed, self.delta, M, self.b, 1.0 / M, self.g_snap, self.x,
                           self.y if acc else None, self.x_snap, self.xsum if acc else None,
                           self.eta, self.theta, self.prob.l1, self.b_x, self.seed, it + 1,
                           self.xq, self.delta_x, self.absmax_x, self.status)
         self._flags.append(flag)
+        return flag
 
     def epoch_epilogue(self) -> None:
         if self.algo == "acc":
@@ -136,5 +142,5 @@ class DoubleQuantTrainer:
 
     def objective(self, x: torch.Tensor) -> float:
         g = torch.empty_like(self.g_snap)
-        dq.dq_full_grad(self.prob, x, g, None, self.obj, self.ws)
+        dq.dq_full_grad(self.prob, x, g, None, self.obj, self.ws_full)
         return float(self.obj.item())

@@ -25,8 +25,7 @@ def dq():
 
 
 def _ws(dq, op, P, M=1, B=1):
-    nbytes = dq.dq_workspace_bytes(op, P, M, B)
-    return torch.empty(max(nbytes, 16) // 4 + 4, dtype=torch.float32, device="cuda")
+    return dq.new_workspace(op, P, M, B)
 
 
 def _close(got, want, tol=TOL):
