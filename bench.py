@@ -40,22 +40,27 @@ def parse():
 
 
 def run_rounds(tr, rounds, events=None):
-    """Advance the trainer by `rounds` rounds, running epoch prologues/epilogues at their cadence."""
+    """Advance the trainer by `rounds` rounds, running epoch prologues/epilogues at their cadence.
+
+    `events`: optional list that receives (start, end, is_flag_round) per round, the two torch events
+    being recorded on the launch stream right before / after the round's worker-step kernels.
+    """
     import torch
     done = 0
     while done < rounds:
         if tr._t == 0:
-            tr._flags = []
             tr.epoch_prologue()
         take = min(rounds - done, tr.m - tr._t)
-        for _ in range(take):
-            if events is not None:
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                flag = tr.round(tr._t, worker_events=(e0, e1))
-                events.append((e0, e1, flag))
-            else:
-                tr.round(tr._t)
-            tr._t += 1
+        handles = None
+        if events is not None:
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(2 * take)]
+            for e in evs:
+                e.record()                      # instantiates the HIP event; it is re-recorded by the library
+            handles = [e.cuda_event for e in evs]
+            for k in range(take):
+                events.append((evs[2 * k], evs[2 * k + 1], tr.is_flag_round(tr._t + k)))
+        tr.rounds(tr._t, take, handles)
+        tr._t += take
         done += take
         if tr._t == tr.m:
             tr.epoch_epilogue()

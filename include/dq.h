@@ -224,6 +224,52 @@ int32_t dq_acc_mix(const float *y, const float *x_snap, float theta, int64_t d, 
 /* End of an epoch of Alg. 3:  x_snap_out = xsum / m. */
 int32_t dq_acc_snapshot(const float *xsum, int64_t m, int64_t d, float *x_snap_out, void *stream);
 
+/* ---- inner loop ------------------------------------------------------------------ */
+
+#define DQ_ALGO_ASYLPG  0   /* Alg. 1 */
+#define DQ_ALGO_SPARSE  1   /* Alg. 2: sparsify before quantizing */
+#define DQ_ALGO_ACC     2   /* Alg. 3: momentum */
+
+/* Settings of a run (host struct). */
+typedef struct dq_run_config {
+    int32_t algo;        /* DQ_ALGO_* */
+    int64_t M, B;        /* workers per round, mini-batch per worker */
+    int32_t b_x, b;      /* bits of the model message and of the gradient message (32 = not quantized) */
+    int64_t m;           /* rounds per epoch */
+    uint64_t seed;
+} dq_run_config;
+
+/* Device buffers of a run (host struct holding device pointers; all caller-owned).
+ * x, x_snap, g_snap: float[d].  y, xsum: float[d], Alg. 3 only.  z_snap: float[n] margins at the
+ * snapshot from dq_full_grad, nullable.  xq: model message (ceil(d*b_x/32) words, or d floats),
+ * delta_x, absmax_x: float[1].  packed: M rows of ld_words words; delta: float[M];
+ * nnz: int32[m*M] nonzero codes per round and worker, nullable.  ws: DQ_OP_VR_GRAD workspace. */
+typedef struct dq_run_state {
+    float *x, *x_snap, *y, *xsum, *g_snap;
+    const float *z_snap;
+    uint32_t *xq;
+    float *delta_x, *absmax_x;
+    uint32_t *packed;
+    int64_t ld_words;
+    float *delta;
+    int32_t *nnz;
+    uint32_t *status;
+    void *ws;
+    int64_t ws_bytes;
+} dq_run_state;
+
+/* Enqueues rounds t0 .. t0+rounds-1 of epoch `epoch` (0-based) of Alg. 1, 2 or 3: per round the
+ * worker side (dq_worker_step with in-kernel sampling; the flag-bit case of Section 4.1 at the
+ * first round of an epoch whose start equals the snapshot) and the master side (dq_master_step,
+ * mean over the M workers, model re-quantized for the next round).  Random streams use
+ * iter = epoch*m + t.  eta, theta: step size and momentum weight of this epoch (theta unused by
+ * Alg. 1/2).  The epoch prologue (dq_full_grad, dq_acc_mix / copy) and epilogue stay with the
+ * caller.  worker_events (host array, nullable): 2*rounds hipEvent_t handles, recorded on
+ * `stream` right before and after each round's worker-step launches. */
+int32_t dq_run_rounds(const dq_problem *prob /*host*/, const dq_run_config *cfg /*host*/, const dq_run_state *st /*host*/,
+                      int64_t epoch, int64_t t0, int64_t rounds, float eta, float theta,
+                      void **worker_events /*host*/, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

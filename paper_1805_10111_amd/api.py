@@ -46,6 +46,20 @@ class _Problem(C.Structure):
     ]
 
 
+class RunConfig(C.Structure):
+    _fields_ = [("algo", C.c_int32), ("M", C.c_int64), ("B", C.c_int64), ("b_x", C.c_int32), ("b", C.c_int32),
+                ("m", C.c_int64), ("seed", C.c_uint64)]
+
+
+class RunState(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("x_snap", C.c_void_p), ("y", C.c_void_p), ("xsum", C.c_void_p),
+                ("g_snap", C.c_void_p), ("z_snap", C.c_void_p), ("xq", C.c_void_p), ("delta_x", C.c_void_p),
+                ("absmax_x", C.c_void_p), ("packed", C.c_void_p), ("ld_words", C.c_int64), ("delta", C.c_void_p),
+                ("nnz", C.c_void_p), ("status", C.c_void_p), ("ws", C.c_void_p), ("ws_bytes", C.c_int64)]
+
+
+ALGO = {"asylpg": 0, "sparse": 1, "acc": 2}
+
 _vp, _i64, _i32, _u64, _u32, _f32 = C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_uint32, C.c_float
 
 _SIGS = {
@@ -70,6 +84,7 @@ _SIGS = {
                               _i32, _u64, _u32, _vp, _vp, _vp, _vp, _vp]),
     "dq_acc_mix": (_i32, [_vp, _vp, _f32, _i64, _vp, _vp]),
     "dq_acc_snapshot": (_i32, [_vp, _i64, _i64, _vp, _vp]),
+    "dq_run_rounds": (_i32, [_vp, _vp, _vp, _i64, _i64, _i64, _f32, _f32, _vp, _vp]),
 }
 
 EXPORTS = tuple(_SIGS)
@@ -306,6 +321,17 @@ def dq_acc_snapshot(xsum, m, x_snap_out) -> None:
                                                    _ptr(x_snap_out, torch.float32, "x_snap_out"), _stream()))
 
 
+def dq_run_rounds(prob: DeviceProblem, cfg: RunConfig, state: RunState, epoch: int, t0: int, rounds: int,
+                  eta: float, theta: float, worker_events=None) -> None:
+    """worker_events: optional list of 2*rounds raw hipEvent_t handles (ints)."""
+    ev = None
+    if worker_events is not None:
+        assert len(worker_events) == 2 * rounds
+        ev = (C.c_void_p * len(worker_events))(*worker_events)
+    _check("dq_run_rounds", _lib.dq_run_rounds(prob.ptr, C.byref(cfg), C.byref(state), epoch, t0, rounds, eta, theta,
+                                               ev, _stream()))
+
+
 __all__ = [
     "DqError", "DeviceProblem", "EXPORTS", "LIB_PATH", "packed_words",
     "OK", "ERR_INVALID_ARG", "ERR_UNSUPPORTED", "ERR_WORKSPACE", "ERR_DEVICE",
@@ -313,4 +339,5 @@ __all__ = [
     "dq_version", "dq_last_device_error", "dq_workspace_bytes", "dq_workspace_init", "new_workspace", "dq_absmax", "dq_quantize", "dq_dequantize",
     "dq_pack", "dq_unpack", "dq_quantize_pack", "dq_unpack_dequant_sum", "dq_sample_indices", "dq_full_grad",
     "dq_vr_grad", "dq_sparsify", "dq_worker_step", "dq_master_step", "dq_acc_mix", "dq_acc_snapshot",
+    "dq_run_rounds", "RunConfig", "RunState", "ALGO",
 ]

@@ -28,6 +28,7 @@ void set_last_error(hipError_t e);
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline int64_t packed_words(int64_t d, int b) { return (d * b + 31) / 32; }
+__device__ __forceinline__ int64_t packed_words_dev(int64_t d, int b) { return (d * b + 31) / 32; }
 
 // ---- Philox4x32-10 (Salmon et al., SC'11), from its published definition -------
 // Stream addressing: key = (seed_lo, seed_hi); counter = (coord/4, iter, worker, tag).

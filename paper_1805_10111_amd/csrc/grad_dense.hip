@@ -167,30 +167,15 @@ __device__ __forceinline__ void model_minus_snapshot(const VrDenseArgs &a, const
     }
 }
 
-// alpha = acc + l2*(q - snapshot) for worker m, then its norms (dq_vr_grad) or the tail of the
-// worker step (dq_worker_step).  acc holds the full sum over the worker's mini-batch.
-template <int NC>
-__device__ __forceinline__ void worker_finish(const VrDenseArgs &a, int m, const float4 (&acc)[NC], const float4 (&dx)[NC],
-                                              float *sh_alpha, uint32_t *su, int *si, double *sd)
+// With alpha of worker m in LDS: its norms (dq_vr_grad) or the tail of the worker step
+// (dq_worker_step).  Scratch arrays hold one entry per wavefront of the block.
+__device__ __forceinline__ void worker_outputs(const VrDenseArgs &a, int m, float *sh_alpha, uint32_t *su, int *si, double *sd)
 {
     const int64_t d = a.d;
-#pragma unroll
-    for (int c = 0; c < NC; ++c) {
-        const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
-        const float v[4] = {acc[c].x + a.l2 * dx[c].x, acc[c].y + a.l2 * dx[c].y, acc[c].z + a.l2 * dx[c].z,
-                            acc[c].w + a.l2 * dx[c].w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (col + e < d) {
-                sh_alpha[col + e] = v[e];
-                if (a.alpha_out) a.alpha_out[static_cast<int64_t>(m) * a.ld + col + e] = v[e];
-            }
-    }
-    __syncthreads();
     if (!a.packed) {
         uint32_t vmax = 0;
         double s1 = 0.0;
-        for (int64_t i = threadIdx.x; i < d; i += kRowThreads) {
+        for (int64_t i = threadIdx.x; i < d; i += blockDim.x) {
             vmax = max(vmax, abs_bits(sh_alpha[i]));
             s1 += static_cast<double>(fabsf(sh_alpha[i]));
         }
@@ -212,6 +197,28 @@ __device__ __forceinline__ void worker_finish(const VrDenseArgs &a, int m, const
     case 32: worker_tail_from_lds<32>(sh_alpha, d, a.sparsify != 0, a.b, key, out, su, si); break;
     default: worker_tail_from_lds<8>(sh_alpha, d, a.sparsify != 0, a.b, key, out, su, si); break;
     }
+}
+
+// One block owned the whole mini-batch of worker m: alpha = acc + l2*(q - snapshot), then the outputs.
+template <int NC>
+__device__ __forceinline__ void worker_finish(const VrDenseArgs &a, int m, const float4 (&acc)[NC], const float4 (&dx)[NC],
+                                              float *sh_alpha, uint32_t *su, int *si, double *sd)
+{
+    const int64_t d = a.d;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
+        const float v[4] = {acc[c].x + a.l2 * dx[c].x, acc[c].y + a.l2 * dx[c].y, acc[c].z + a.l2 * dx[c].z,
+                            acc[c].w + a.l2 * dx[c].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (col + e < d) {
+                sh_alpha[col + e] = v[e];
+                if (a.alpha_out) a.alpha_out[static_cast<int64_t>(m) * a.ld + col + e] = v[e];
+            }
+    }
+    __syncthreads();
+    worker_outputs(a, m, sh_alpha, su, si, sd);
 }
 
 template <int NC, int R, bool HAVE_Z>
@@ -259,14 +266,15 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
     // ---- stream the rows, R at a time
     const float fB = static_cast<float>(a.B);
     int buf = 0;
-    for (int rb = 0; rb < nrows; rb += R) {
-        float4 row[R][NC];
+    auto load_batch = [&](int rb, float4 (&row)[R][NC]) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int i = rb + r < nrows ? sh_row[rb + r] : -1;
             if (i >= 0) load_cols<NC>(a.X + static_cast<int64_t>(i) * a.lda, d, row[r]);
             else zero_cols<NC>(row[r]);
         }
+    };
+    auto compute_batch = [&](int rb, const float4 (&row)[R][NC]) {
         float dots[HAVE_Z ? R : 2 * R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -283,6 +291,13 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
                 axpy_cols<NC>(coef, row[r], acc);
             }
         }
+    };
+    // (no software prefetch here: a block owns only a few batches, and the extra registers
+    //  of a second row buffer cost a resident block per compute unit -- measured slower)
+    for (int rb = 0; rb < nrows; rb += R) {
+        float4 row[R][NC];
+        load_batch(rb, row);
+        compute_batch(rb, row);
     }
 
     if (a.P > 1) {          // several blocks per worker: leave the partial sum for vr_dense_finish_kernel
@@ -292,31 +307,48 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
     worker_finish<NC>(a, m, acc, dx, sh_alpha, su, si, sd);
 }
 
-// Second stage when a worker's mini-batch was split over P > 1 blocks.  grid (M).
-template <int NC>
-__global__ __launch_bounds__(kRowThreads) void vr_dense_finish_kernel(const VrDenseArgs a)
+// Second stage when a worker's mini-batch was split over P > 1 blocks.  grid (M), 1024
+// threads: thread t adds the P partial sums of float4 columns t, t+1024, ... in the order
+// p = 0..P-1 (loads issued eight at a time), adds l2*(q - snapshot), leaves alpha in LDS
+// and the block runs the tail of the worker step.
+constexpr int kFinishThreads = 1024;
+__global__ __launch_bounds__(kFinishThreads) void vr_dense_finish_kernel(const VrDenseArgs a)
 {
-    __shared__ float sh_alpha[4 * kRowThreads * NC];
-    __shared__ uint32_t su[kRowWaves];
-    __shared__ int si[kRowWaves];
-    __shared__ double sd[kRowWaves];
+    extern __shared__ float sh_alpha_dyn[];
+    __shared__ uint32_t su[kFinishThreads / kWave];
+    __shared__ int si[kFinishThreads / kWave];
+    __shared__ double sd[kFinishThreads / kWave];
     const int m = blockIdx.x;
+    const int64_t d = a.d;
     const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
-    float4 dx[NC], xs[1], acc[NC];
-    model_minus_snapshot<NC, true>(a, msg, dx, xs);
-#pragma unroll
-    for (int c = 0; c < NC; ++c) {
-        const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
+    const float *base = a.partial + static_cast<int64_t>(m) * a.P * a.ldp;
+    for (int64_t col = 4ll * threadIdx.x; col < a.ldp; col += 4ll * kFinishThreads) {
         float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        if (col < a.ldp) {
-            for (int p = 0; p < a.P; ++p) {
-                const float4 t = *reinterpret_cast<const float4 *>(a.partial + (static_cast<int64_t>(m) * a.P + p) * a.ldp + col);
-                s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        int p = 0;
+        for (; p + 8 <= a.P; p += 8) {
+            float4 t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = *reinterpret_cast<const float4 *>(base + (p + u) * a.ldp + col);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { s.x += t[u].x; s.y += t[u].y; s.z += t[u].z; s.w += t[u].w; }
+        }
+        for (; p < a.P; ++p) {
+            const float4 t = *reinterpret_cast<const float4 *>(base + p * a.ldp + col);
+            s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+        }
+        const float acc[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (col + e < d) {
+                const float dxe = model_value(msg, col + e) - a.x_snap[col + e];
+                const float v = acc[e] + a.l2 * dxe;
+                sh_alpha_dyn[col + e] = v;
+                if (a.alpha_out) a.alpha_out[static_cast<int64_t>(m) * a.ld + col + e] = v;
             }
         }
-        acc[c] = s;
     }
-    worker_finish<NC>(a, m, acc, dx, sh_alpha, su, si, sd);
+    __syncthreads();
+    worker_outputs(a, m, sh_alpha_dyn, su, si, sd);
 }
 
 // Flag-bit round (Section 4.1: the model equals the snapshot): alpha = 0 for every worker.
@@ -364,14 +396,15 @@ __global__ __launch_bounds__(kRowThreads) void full_dense_partial_kernel(
     const float fn = static_cast<float>(n);
     double loss = 0.0;
     int buf = 0;
-    for (int64_t ib = i0; ib < i1; ib += R) {
-        float4 row[R][NC];
-        float z[R];
+    auto load_batch = [&](int64_t ib, float4 (&row)[R][NC]) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             if (ib + r < i1) load_cols<NC>(X + (ib + r) * lda, d, row[r]);
             else zero_cols<NC>(row[r]);
         }
+    };
+    auto compute_batch = [&](int64_t ib, const float4 (&row)[R][NC]) {
+        float z[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) z[r] = dot_cols<NC>(row[r], xv);
         block_sum_R<R>(z, sh_red, buf);
@@ -382,6 +415,19 @@ __global__ __launch_bounds__(kRowThreads) void full_dense_partial_kernel(
                 if (z_out && threadIdx.x == 0) z_out[ib + r] = z[r];
                 loss += static_cast<double>(logistic_loss(y * z[r]));
                 axpy_cols<NC>(logistic_slope(y, z[r]) / fn, row[r], acc);
+            }
+        }
+    };
+    if (i0 < i1) {
+        float4 rowA[R][NC], rowB[R][NC];
+        load_batch(i0, rowA);
+        for (int64_t ib = i0; ib < i1; ib += 2 * R) {
+            const bool more1 = ib + R < i1, more2 = ib + 2 * R < i1;
+            if (more1) load_batch(ib + R, rowB);
+            compute_batch(ib, rowA);
+            if (more1) {
+                if (more2) load_batch(ib + 2 * R, rowA);
+                compute_batch(ib + R, rowB);
             }
         }
     }
@@ -543,12 +589,7 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     }
     DQ_LAUNCH_CHECK();
     if (k.P > 1) {
-        const dim3 fgrid(static_cast<unsigned>(a.M)), fblock(kRowThreads);
-        switch (nc) {
-        case 1: vr_dense_finish_kernel<1><<<fgrid, fblock, 0, st>>>(k); break;
-        case 2: vr_dense_finish_kernel<2><<<fgrid, fblock, 0, st>>>(k); break;
-        default: vr_dense_finish_kernel<4><<<fgrid, fblock, 0, st>>>(k); break;
-        }
+        vr_dense_finish_kernel<<<dim3(static_cast<unsigned>(a.M)), dim3(kFinishThreads), static_cast<size_t>(d) * sizeof(float), st>>>(k);
         DQ_LAUNCH_CHECK();
     }
     return DQ_OK;

@@ -75,6 +75,126 @@ static int launch_master_update(bool acc, dim3 grid, hipStream_t st, const uint3
     return DQ_OK;
 }
 
+// ------------------------------------------------------------------ fused master step, one block
+// For d <= 16384*CH the whole master step is one block of 1024 threads: each thread owns CH
+// chunks of 16 coordinates, keeps the updated model in registers across the block-wide
+// ||x||_inf reduction and quantizes + packs it right away (Alg. 1, master (ii) then (i)).
+constexpr int kFusedThreads = 1024;
+
+template <int FIELD, bool ACC, int CH>
+__global__ __launch_bounds__(kFusedThreads) void master_fused_kernel(
+    const uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words, const float *__restrict__ delta, int M,
+    float scale, const float *__restrict__ g_snap, float *__restrict__ x, float *__restrict__ y,
+    const float *__restrict__ x_snap, float *__restrict__ xsum, float eta, float theta, float kappa, int64_t d,
+    int b_x, StreamKey key, uint32_t *__restrict__ xq_out, float *__restrict__ delta_x_out,
+    float *__restrict__ absmax_x_out, uint32_t *__restrict__ status)
+{
+    __shared__ uint32_t scratch[kFusedThreads / kWave];
+    const int64_t chunks = (d + 15) / 16;
+    float xv[CH][16];
+    uint32_t amax = 0;
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) {
+        const int64_t c = threadIdx.x + static_cast<int64_t>(kFusedThreads) * ch;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) xv[ch][j] = 0.0f;
+        if (c >= chunks) continue;
+        float acc[16];
+        decode_sum16<FIELD>(packed, ld_words, row_words, delta, M, c, d, acc);
+        const int64_t base = c * 16;
+        float gs[16], yv[16], xs[16], sm[16];
+        load16(g_snap, base, d, gs);
+        if (ACC) {
+            load16(y, base, d, yv);
+            load16(x_snap, base, d, xs);
+            if (xsum) load16(xsum, base, d, sm);
+        } else {
+            load16(x, base, d, xv[ch]);
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float u = scale * acc[j] + gs[j];
+            if (ACC) {
+                yv[j] = soft_threshold(yv[j] - eta * u, kappa);
+                xv[ch][j] = xs[j] + theta * (yv[j] - xs[j]);
+                if (xsum) sm[j] = sm[j] + xv[ch][j];
+            } else {
+                xv[ch][j] = soft_threshold(xv[ch][j] - eta * u, kappa);
+            }
+            if (base + j >= d) xv[ch][j] = 0.0f;
+            amax = max(amax, abs_bits(xv[ch][j]));
+        }
+        store16(x, base, d, xv[ch]);
+        if (ACC) {
+            store16(y, base, d, yv);
+            if (xsum) store16(xsum, base, d, sm);
+        }
+    }
+    amax = block_max_u32(amax, scratch);
+    if (threadIdx.x == 0) absmax_x_out[0] = __uint_as_float(amax);
+    if (b_x == 32) {
+        if (threadIdx.x == 0) delta_x_out[0] = 1.0f;
+#pragma unroll
+        for (int ch = 0; ch < CH; ++ch) {
+            const int64_t c = threadIdx.x + static_cast<int64_t>(kFusedThreads) * ch;
+            if (c < chunks) store16(reinterpret_cast<float *>(xq_out), c * 16, d, xv[ch]);
+        }
+        return;
+    }
+    const Scale s = make_scale(__uint_as_float(amax), b_x);
+    if (threadIdx.x == 0) {
+        delta_x_out[0] = s.delta;
+        if (s.bad && status) atomicOr(status, 1u);
+    }
+    key.worker = DQ_MASTER_ID;
+    const int64_t xq_words = packed_words_dev(d, b_x);
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) {
+        const int64_t c = threadIdx.x + static_cast<int64_t>(kFusedThreads) * ch;
+        if (c >= chunks) continue;
+        if (b_x == 8) {
+            uint32_t w[Words16<8>::n];
+            quantize16<8>(xv[ch], s, key, c, w);
+            store_words<8>(xq_out, c, xq_words, w);
+        } else if (b_x == 4) {
+            uint32_t w[Words16<4>::n];
+            quantize16<4>(xv[ch], s, key, c, w);
+            store_words<4>(xq_out, c, xq_words, w);
+        } else {
+            uint32_t w[Words16<2>::n];
+            quantize16<2>(xv[ch], s, key, c, w);
+            store_words<2>(xq_out, c, xq_words, w);
+        }
+    }
+}
+
+template <int FIELD, bool ACC>
+static void launch_master_fused2(int ch, hipStream_t st, const uint32_t *packed, int64_t ld_words, int64_t row_words,
+                                 const float *delta, int M, float scale, const float *g_snap, float *x, float *y,
+                                 const float *x_snap, float *xsum, float eta, float theta, float kappa, int64_t d, int b_x,
+                                 const StreamKey &key, uint32_t *xq_out, float *delta_x_out, float *absmax_x_out,
+                                 uint32_t *status)
+{
+    const dim3 grid(1), block(kFusedThreads);
+    if (ch == 1)
+        master_fused_kernel<FIELD, ACC, 1><<<grid, block, 0, st>>>(packed, ld_words, row_words, delta, M, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
+    else
+        master_fused_kernel<FIELD, ACC, 2><<<grid, block, 0, st>>>(packed, ld_words, row_words, delta, M, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
+}
+
+template <int FIELD>
+static int launch_master_fused(bool acc, int ch, hipStream_t st, const uint32_t *packed, int64_t ld_words,
+                               int64_t row_words, const float *delta, int M, float scale, const float *g_snap, float *x,
+                               float *y, const float *x_snap, float *xsum, float eta, float theta, float kappa, int64_t d,
+                               int b_x, const StreamKey &key, uint32_t *xq_out, float *delta_x_out, float *absmax_x_out,
+                               uint32_t *status)
+{
+    if (acc) launch_master_fused2<FIELD, true>(ch, st, packed, ld_words, row_words, delta, M, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
+    else launch_master_fused2<FIELD, false>(ch, st, packed, ld_words, row_words, delta, M, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
+}
+
 __global__ __launch_bounds__(kThreads) void copy_f32_kernel(const float *__restrict__ a, float *__restrict__ b, int64_t n)
 {
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
@@ -173,12 +293,26 @@ extern "C" int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, cons
     if (y && !x_snap) return DQ_ERR_INVALID_ARG;
     if (b != 2 && b != 4 && b != 8 && b != 32) return (b >= 2 && b <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
     if (b_x != 2 && b_x != 4 && b_x != 8 && b_x != 32) return (b_x >= 2 && b_x <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
-    const int64_t row_words = packed_words(d, b);
+    const int64_t row_words = b == 32 ? d : packed_words(d, b);
     if (ld_words < row_words || (M > 1 && ld_words % 4 != 0)) return DQ_ERR_INVALID_ARG;
     const void *ptrs[] = {packed, g_snap, x, y, x_snap, xsum, xq_packed_out};
     for (const void *p : ptrs)
         if (p && !aligned16(p)) return DQ_ERR_INVALID_ARG;
     hipStream_t st = as_stream(stream);
+    const float kappa_f = eta * l1;
+    if (d <= 16384 * 2) {
+        // small model: the whole step in one block, one launch
+        const int ch = d <= 16384 ? 1 : 2;
+        const StreamKey mkey{static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), iter, 0u, DQ_TAG_MODEL};
+        const bool accf = y != nullptr;
+        const int Mf = static_cast<int>(M);
+        switch (b) {
+        case 8: return launch_master_fused<8>(accf, ch, st, packed, ld_words, row_words, delta, Mf, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa_f, d, b_x, mkey, xq_packed_out, delta_x_out, absmax_x_out, status);
+        case 4: return launch_master_fused<4>(accf, ch, st, packed, ld_words, row_words, delta, Mf, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa_f, d, b_x, mkey, xq_packed_out, delta_x_out, absmax_x_out, status);
+        case 2: return launch_master_fused<2>(accf, ch, st, packed, ld_words, row_words, delta, Mf, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa_f, d, b_x, mkey, xq_packed_out, delta_x_out, absmax_x_out, status);
+        default: return launch_master_fused<32>(accf, ch, st, packed, ld_words, row_words, delta, Mf, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa_f, d, b_x, mkey, xq_packed_out, delta_x_out, absmax_x_out, status);
+        }
+    }
     uint32_t *absmax_bits = reinterpret_cast<uint32_t *>(absmax_x_out);
     int rc = fill_u32(absmax_bits, 1, 0u, st);
     if (rc != DQ_OK) return rc;

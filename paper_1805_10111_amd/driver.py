@@ -42,7 +42,6 @@ class DoubleQuantTrainer:
         self.g_snap = torch.zeros(d, **f32)
         self.z_snap = torch.zeros(n, **f32) if cache_margins else None
         self.obj = torch.zeros(1, dtype=torch.float64, device=dev)
-        self.idx = torch.zeros((M, B), **i32)
         self.xq_words = d if b_x == 32 else dq.packed_words(d, b_x)
         self.xq = torch.zeros(self.xq_words + 4, **i32)
         self.delta_x = torch.zeros(1, **f32)
@@ -56,7 +55,15 @@ class DoubleQuantTrainer:
         self.ws_full = dq.new_workspace(dq.OP_FULL_GRAD, prob)
         self.ws = dq.new_workspace(dq.OP_VR_GRAD, prob, M, B)
         self.epoch_index = 0
+        self.theta, self.eta = 0.0, self.lr
         self.log = RunLog()
+        p = lambda t: None if t is None else t.data_ptr()
+        self.cfg = dq.RunConfig(algo=dq.ALGO[algo], M=M, B=B, b_x=b_x, b=b, m=m, seed=self.seed)
+        self.state = dq.RunState(
+            x=p(self.x), x_snap=p(self.x_snap), y=p(self.y), xsum=p(self.xsum), g_snap=p(self.g_snap),
+            z_snap=p(self.z_snap), xq=p(self.xq), delta_x=p(self.delta_x), absmax_x=p(self.absmax_x),
+            packed=p(self.packed), ld_words=self.ld_words, delta=p(self.delta), nnz=p(self.nnz),
+            status=p(self.status), ws=p(self.ws), ws_bytes=self.ws.numel() * 4)
 
     # -- one epoch ---------------------------------------------------------------------------
     def epoch_prologue(self) -> None:
@@ -74,36 +81,20 @@ class DoubleQuantTrainer:
             self.x.copy_(self.x_snap)
         dq.dq_full_grad(self.prob, self.x_snap, self.g_snap, self.z_snap, self.obj, self.ws_full)
 
-    def round(self, t: int, worker_events=None) -> bool:
-        """One synchronous round; returns True if it was a flag-bit round.  `worker_events`: optional pair of
-        torch.cuda.Event recorded on the current stream right before / after the worker-step launch."""
-        e, m, M = self.epoch_index, self.m, self.M
-        it = e * m + t
-        acc = self.algo == "acc"
-        # x equals the snapshot bit for bit exactly at the first round of an epoch of Alg. 1/2,
-        # and of the first epoch of Alg. 3: the master then sends the flag bit of Section 4.1.
-        flag = t == 0 and (not acc or e == 0)
-        if t == 0 and not flag:
-            # Alg. 3, later epochs: x_0 differs from the snapshot, so the master quantizes it (master (i))
-            if self.b_x == 32:
-                self.xq[: self.prob.d].copy_(self.x.view(torch.int32))
-            else:
-                dq.dq_quantize_pack(self.x, self.b_x, self.absmax_x, False, self.seed, it, dq.TAG_MODEL,
-                                    dq.MASTER_ID, self.xq, self.delta_x, self.status)
-        dq.dq_sample_indices(self.prob.n, M, self.B, self.seed, it, 0, self.idx)
-        if worker_events is not None:
-            worker_events[0].record()
-        dq.dq_worker_step(self.prob, self.idx, M, self.B, self.xq, self.delta_x, self.b_x, flag, self.x_snap,
-                          self.z_snap, self.algo == "sparse", self.b, self.seed, it, 0, self.packed, self.delta,
-                          self.nnz[t], None, self.status, self.ws)
-        if worker_events is not None:
-            worker_events[1].record()
-        dq.dq_master_step(self.packed, self.delta, M, self.b, 1.0 / M, self.g_snap, self.x,
-                          self.y if acc else None, self.x_snap, self.xsum if acc else None,
-                          self.eta, self.theta, self.prob.l1, self.b_x, self.seed, it + 1,
-                          self.xq, self.delta_x, self.absmax_x, self.status)
-        self._flags.append(flag)
-        return flag
+    def is_flag_round(self, t: int) -> bool:
+        """x equals the snapshot bit for bit exactly at the first round of an epoch of Alg. 1/2 and of the
+        first epoch of Alg. 3: the master then sends the flag bit of Section 4.1 instead of the model."""
+        return t == 0 and (self.algo != "acc" or self.epoch_index == 0)
+
+    def rounds(self, t0: int, count: int, worker_events=None) -> None:
+        """Enqueue rounds t0 .. t0+count-1 of the current epoch (one library call).  `worker_events`: optional
+        list of 2*count raw hipEvent_t handles recorded around each round's worker-step launches."""
+        dq.dq_run_rounds(self.prob, self.cfg, self.state, self.epoch_index, t0, count, self.eta, self.theta,
+                         worker_events)
+
+    def round(self, t: int) -> bool:
+        self.rounds(t, 1)
+        return self.is_flag_round(t)
 
     def epoch_epilogue(self) -> None:
         if self.algo == "acc":
@@ -113,18 +104,17 @@ class DoubleQuantTrainer:
         self.epoch_index += 1
 
     def run_epoch(self) -> None:
-        self._flags = []
         self.epoch_prologue()
-        for t in range(self.m):
-            self.round(t)
+        self.rounds(0, self.m)
+        flags = [self.is_flag_round(t) for t in range(self.m)]
         self.epoch_epilogue()
-        self._account()
+        self._account(flags)
 
-    def _account(self) -> None:
+    def _account(self, flags) -> None:
         d, M, m = self.prob.d, self.M, self.m
         self.log.objectives.append(float(self.obj.item()))
         self.log.rounds += m
-        for flag in self._flags:
+        for flag in flags:
             self.log.bits_down += 1 if flag else 32 + self.b_x * d
         if self.algo == "sparse":
             nz = int(self.nnz.sum().item())

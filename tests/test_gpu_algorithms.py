@@ -66,7 +66,6 @@ def test_lock_step_rounds(dq, name):
         # ---- GPU epoch start from the oracle's state
         tr.epoch_index = e
         tr.x_snap.copy_(dev(x_snap)); tr.y.copy_(dev(y))
-        tr._flags = []
         tr.epoch_prologue()
         assert np.abs(host(tr.g_snap) - g_snap).max() <= TOL * np.abs(g_snap).max()
         assert np.array_equal(host(tr.x), x)
@@ -81,8 +80,7 @@ def test_lock_step_rounds(dq, name):
             if not flag:
                 tr.xq[: xq_words.size].copy_(dev(xq_words.view(np.int32)))
                 tr.delta_x.copy_(dev(np.array([dx], dtype=np.float32)))
-            tr.round(t)
-            assert tr._flags[-1] == flag
+            assert tr.round(t) == flag
             # ---- oracle round
             codes = np.zeros((M, d), dtype=np.int8)
             deltas = np.zeros(M, dtype=np.float32)

@@ -196,6 +196,29 @@ def test_worker_step(dq, n, d, M, B, b, sparsify):
     assert flips <= max(3, 2e-3 * M * d), flips          # decisions flipped by sub-tolerance differences
 
 
+def test_worker_step_samples_its_own_minibatch(dq):
+    """idx = None: the kernel draws the mini-batch itself, identically to dq_sample_indices."""
+    n, d, M, B = 2000, 1000, 4, 16
+    p = synth.dense_logistic(n, d, seed=8)
+    P = dq.DeviceProblem.from_host(p)
+    rng = np.random.default_rng(2)
+    x_snap = (0.3 * rng.standard_normal(d)).astype(np.float32)
+    xq, dx, _ = _model(rng, d, 8, x_snap)
+    seed, it, w0 = 5, 17, 3
+    idx = torch.zeros((M, B), dtype=torch.int32, device="cuda")
+    dq.dq_sample_indices(n, M, B, seed, it, w0, idx)
+    ws = _ws(dq, dq.OP_VR_GRAD, P, M, B)
+    outs = []
+    for use_idx in (idx, None):
+        packed = torch.zeros((M, 252), dtype=torch.int32, device="cuda")
+        delta = torch.zeros(M, device="cuda")
+        dq.dq_worker_step(P, use_idx, M, B, dev(xq.view(np.int32)), dev(np.array([dx], dtype=np.float32)), 8, False,
+                          dev(x_snap), None, False, 8, seed, it, w0, packed, delta, None, None, None, ws)
+        outs.append((packed, delta))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    assert outs[0][0].any()
+
+
 def test_worker_step_full_precision_message(dq):
     """b = 32: the worker sends alpha itself (AsyFPG / QSVRG-style comparison modes)."""
     n, d, M, B = 300, 1000, 2, 8
