@@ -24,6 +24,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+EVENT_STRIDE = 8          # rounds between HIP-event brackets around the worker step
 
 
 def parse():
@@ -51,15 +52,22 @@ def run_rounds(tr, rounds, events=None):
         if tr._t == 0:
             tr.epoch_prologue()
         take = min(rounds - done, tr.m - tr._t)
-        handles = None
-        if events is not None:
-            evs = [torch.cuda.Event(enable_timing=True) for _ in range(2 * take)]
-            for e in evs:
-                e.record()                      # instantiates the HIP event; it is re-recorded by the library
-            handles = [e.cuda_event for e in evs]
-            for k in range(take):
-                events.append((evs[2 * k], evs[2 * k + 1], tr.is_flag_round(tr._t + k)))
-        tr.rounds(tr._t, take, handles)
+        if events is None:
+            tr.rounds(tr._t, take)
+        else:
+            # an event pair costs ~5 us of stream time each, so only every EVENT_STRIDE-th round is bracketed
+            k = 0
+            while k < take:
+                if (done + k) % EVENT_STRIDE == EVENT_STRIDE - 1:
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(); e1.record()            # instantiates the HIP events; the library re-records them
+                    tr.rounds(tr._t + k, 1, [e0.cuda_event, e1.cuda_event])
+                    events.append((e0, e1, tr.is_flag_round(tr._t + k)))
+                    k += 1
+                else:
+                    run = min(take - k, EVENT_STRIDE - 1 - (done + k) % EVENT_STRIDE)
+                    tr.rounds(tr._t + k, run)
+                    k += run
         tr._t += take
         done += take
         if tr._t == tr.m:

@@ -123,29 +123,53 @@ __device__ __forceinline__ int quantize_one(float v, const Scale &s, uint32_t wo
 // ---- magnitude bit pattern: monotone in |v| for non-NaN, NaN sorts above Inf ----
 __device__ __forceinline__ uint32_t abs_bits(float v) { return __float_as_uint(v) & 0x7FFFFFFFu; }
 
-// ---- wave / block reductions (deterministic butterflies) -----------------------
+// ---- wave / block reductions (fixed order, hence deterministic) ---------------------
+// Cross-lane moves on the VALU data path (DPP) instead of LDS permutes: two quad
+// permutes, two row shifts and two row broadcasts leave the wave's total in lane 63,
+// from where it is read back as a wave-uniform value.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_move_or_zero(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xf, true);
+}
+
+#define DQ_WAVE_REDUCE(v, OP, TO_INT, FROM_INT)                                               \
+    do {                                                                                      \
+        v = OP(v, FROM_INT(dpp_move_or_zero<0xb1, 0xf>(TO_INT(v))));  /* quad_perm [1,0,3,2] */ \
+        v = OP(v, FROM_INT(dpp_move_or_zero<0x4e, 0xf>(TO_INT(v))));  /* quad_perm [2,3,0,1] */ \
+        v = OP(v, FROM_INT(dpp_move_or_zero<0x114, 0xf>(TO_INT(v)))); /* row_shr:4           */ \
+        v = OP(v, FROM_INT(dpp_move_or_zero<0x118, 0xf>(TO_INT(v)))); /* row_shr:8           */ \
+        v = OP(v, FROM_INT(dpp_move_or_zero<0x142, 0xa>(TO_INT(v)))); /* row_bcast:15        */ \
+        v = OP(v, FROM_INT(dpp_move_or_zero<0x143, 0xc>(TO_INT(v)))); /* row_bcast:31        */ \
+        v = FROM_INT(__builtin_amdgcn_readlane(TO_INT(v), 63));                                \
+    } while (0)
+
+__device__ __forceinline__ float dq_addf(float a, float b) { return a + b; }
+__device__ __forceinline__ int dq_addi(int a, int b) { return a + b; }
+__device__ __forceinline__ uint32_t dq_maxu(uint32_t a, uint32_t b) { return max(a, b); }
+__device__ __forceinline__ int dq_u2i(uint32_t a) { return static_cast<int>(a); }
+__device__ __forceinline__ uint32_t dq_i2u(int a) { return static_cast<uint32_t>(a); }
+__device__ __forceinline__ int dq_id(int a) { return a; }
+
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = max(v, static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), off, kWave)));
+    DQ_WAVE_REDUCE(v, dq_maxu, dq_u2i, dq_i2u);     // lanes without a source contribute 0, the identity of max
     return v;
 }
 
 __device__ __forceinline__ float wave_sum_f32(float v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-    return v;
-}
-
-__device__ __forceinline__ double wave_sum_f64(double v)
-{
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    DQ_WAVE_REDUCE(v, dq_addf, __float_as_int, __int_as_float);
     return v;
 }
 
 __device__ __forceinline__ int wave_sum_i32(int v)
+{
+    DQ_WAVE_REDUCE(v, dq_addi, dq_id, dq_id);
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum_f64(double v)
 {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);

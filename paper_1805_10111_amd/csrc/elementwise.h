@@ -91,8 +91,23 @@ __device__ __forceinline__ void decode_sum16(const uint32_t *__restrict__ packed
 {
 #pragma unroll
     for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
-#pragma unroll 4
-    for (int m = 0; m < M; ++m) {
+    // the words of 8 workers are requested together, then folded in in worker order
+    constexpr int kGroup = FIELD == 32 ? 2 : 8;
+    int m = 0;
+    for (; m + kGroup <= M; m += kGroup) {
+        uint32_t w[kGroup][Words16<FIELD>::n];
+        float dm[kGroup];
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u) {
+            load_words<FIELD>(packed + static_cast<int64_t>(m + u) * ld_words, c, row_words, w[u]);
+            dm[u] = FIELD == 32 ? 1.0f : delta[m + u];
+        }
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[j] = fmaf(dm[u], value_of<FIELD>(w[u], j), acc[j]);
+    }
+    for (; m < M; ++m) {
         uint32_t w[Words16<FIELD>::n];
         load_words<FIELD>(packed + static_cast<int64_t>(m) * ld_words, c, row_words, w);
         const float dm = FIELD == 32 ? 1.0f : delta[m];

@@ -236,7 +236,7 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
     const int64_t d = a.d;
     const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
 
-    // ---- rows of this block and their scalars
+    // ---- rows of this block
     const int per = (a.B + a.P - 1) / a.P;
     const int r0 = blockIdx.x * per;
     const int nrows = max(0, min(a.B, r0 + per) - r0);
@@ -253,17 +253,10 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
         }
         const bool ok = static_cast<uint64_t>(i) < static_cast<uint64_t>(a.n);   // out-of-range index: ignored
         sh_row[threadIdx.x] = ok ? static_cast<int>(i) : -1;
-        sh_y[threadIdx.x] = ok ? a.y[i] : 1.0f;
-        sh_z[threadIdx.x] = (ok && HAVE_Z) ? a.z_snap[i] : 0.0f;
     }
-
-    // ---- q - snapshot (and the snapshot itself when margins are not cached) for the thread's columns
-    float4 dx[NC], xs[HAVE_Z ? 1 : NC], acc[NC];
-    model_minus_snapshot<NC, HAVE_Z>(a, msg, dx, xs);
-    zero_cols<NC>(acc);
     __syncthreads();
 
-    // ---- stream the rows, R at a time
+    float4 dx[NC], xs[HAVE_Z ? 1 : NC], acc[NC];
     const float fB = static_cast<float>(a.B);
     int buf = 0;
     auto load_batch = [&](int rb, float4 (&row)[R][NC]) {
@@ -282,21 +275,44 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
             if constexpr (!HAVE_Z) dots[R + r] = dot_cols<NC>(row[r], xs);
         }
         block_sum_R<HAVE_Z ? R : 2 * R>(dots, sh_red, buf);
+        // lane r of every wave evaluates the coefficient of row rb + r once (exp, expm1 and the
+        // division are the expensive part of a batch); the R results are then read back wave-uniformly
+        const int lane = threadIdx.x & (kWave - 1);
+        float dz = dots[0], zs = HAVE_Z ? 0.0f : dots[HAVE_Z ? 0 : R];
+#pragma unroll
+        for (int r = 1; r < R; ++r) {
+            dz = lane == r ? dots[r] : dz;
+            if constexpr (!HAVE_Z) zs = lane == r ? dots[R + r] : zs;
+        }
+        float coef_l = 0.0f;
+        if (lane < R && rb + lane < nrows && sh_row[rb + lane] >= 0) {
+            if constexpr (HAVE_Z) zs = sh_z[rb + lane];
+            coef_l = vr_slope_diff(sh_y[rb + lane], zs, dz) / fB;
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const bool live = rb + r < nrows && sh_row[min(rb + r, kMaxRowsPerBlock - 1)] >= 0;
-            if (live) {
-                const float zs = HAVE_Z ? sh_z[rb + r] : dots[HAVE_Z ? r : R + r];
-                const float coef = vr_slope_diff(sh_y[rb + r], zs, dots[r]) / fB;
-                axpy_cols<NC>(coef, row[r], acc);
-            }
+            const float coef = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(coef_l), r));
+            axpy_cols<NC>(coef, row[r], acc);          // dead rows: coef = 0 and the row registers are 0
         }
     };
-    // (no software prefetch here: a block owns only a few batches, and the extra registers
-    //  of a second row buffer cost a resident block per compute unit -- measured slower)
+
+    // ---- the first batch of rows is requested before anything else is fetched; the labels and cached
+    //      margins of the rows and q - snapshot (the thread's columns) arrive while those loads are in flight
+    float4 row[R][NC];
+    load_batch(0, row);
+    if (static_cast<int>(threadIdx.x) < nrows) {
+        const int i = sh_row[threadIdx.x];
+        sh_y[threadIdx.x] = i >= 0 ? a.y[i] : 1.0f;
+        sh_z[threadIdx.x] = (i >= 0 && HAVE_Z) ? a.z_snap[i] : 0.0f;
+    }
+    model_minus_snapshot<NC, HAVE_Z>(a, msg, dx, xs);
+    zero_cols<NC>(acc);
+    __syncthreads();
+
+    // ---- stream the rows, R at a time.  (No software prefetch beyond the first batch: a block owns
+    //      only a few batches, and a second row buffer costs a resident block per compute unit.)
     for (int rb = 0; rb < nrows; rb += R) {
-        float4 row[R][NC];
-        load_batch(rb, row);
+        if (rb > 0) load_batch(rb, row);
         compute_batch(rb, row);
     }
 
@@ -323,14 +339,43 @@ __global__ __launch_bounds__(kFinishThreads) void vr_dense_finish_kernel(const V
     const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
     const float *base = a.partial + static_cast<int64_t>(m) * a.P * a.ldp;
     for (int64_t col = 4ll * threadIdx.x; col < a.ldp; col += 4ll * kFinishThreads) {
+        // everything this column group needs is requested up front: the model words, the snapshot
+        // and the partial sums (sixteen at a time)
+        float q[4], xs[4];
+        if (col + 3 < d) {
+            const float4 t = *reinterpret_cast<const float4 *>(a.x_snap + col);
+            xs[0] = t.x; xs[1] = t.y; xs[2] = t.z; xs[3] = t.w;
+            if (a.b_x == 8) {
+                const uint32_t w = a.xq[col >> 2];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) q[e] = msg.delta_x * static_cast<float>(sext_field(w, 8 * e, 8));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) q[e] = model_value(msg, col + e);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool in = col + e < d;
+                xs[e] = in ? a.x_snap[col + e] : 0.0f;
+                q[e] = in ? model_value(msg, col + e) : 0.0f;
+            }
+        }
         float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         int p = 0;
-        for (; p + 8 <= a.P; p += 8) {
-            float4 t[8];
+        for (; p + 16 <= a.P; p += 16) {
+            float4 t[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) t[u] = *reinterpret_cast<const float4 *>(base + (p + u) * a.ldp + col);
+            for (int u = 0; u < 16; ++u) t[u] = *reinterpret_cast<const float4 *>(base + (p + u) * a.ldp + col);
 #pragma unroll
-            for (int u = 0; u < 8; ++u) { s.x += t[u].x; s.y += t[u].y; s.z += t[u].z; s.w += t[u].w; }
+            for (int u = 0; u < 16; ++u) { s.x += t[u].x; s.y += t[u].y; s.z += t[u].z; s.w += t[u].w; }
+        }
+        for (; p + 4 <= a.P; p += 4) {
+            float4 t[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) t[u] = *reinterpret_cast<const float4 *>(base + (p + u) * a.ldp + col);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { s.x += t[u].x; s.y += t[u].y; s.z += t[u].z; s.w += t[u].w; }
         }
         for (; p < a.P; ++p) {
             const float4 t = *reinterpret_cast<const float4 *>(base + p * a.ldp + col);
@@ -340,8 +385,7 @@ __global__ __launch_bounds__(kFinishThreads) void vr_dense_finish_kernel(const V
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             if (col + e < d) {
-                const float dxe = model_value(msg, col + e) - a.x_snap[col + e];
-                const float v = acc[e] + a.l2 * dxe;
+                const float v = acc[e] + a.l2 * (q[e] - xs[e]);
                 sh_alpha_dyn[col + e] = v;
                 if (a.alpha_out) a.alpha_out[static_cast<int64_t>(m) * a.ld + col + e] = v;
             }
@@ -408,14 +452,24 @@ __global__ __launch_bounds__(kRowThreads) void full_dense_partial_kernel(
 #pragma unroll
         for (int r = 0; r < R; ++r) z[r] = dot_cols<NC>(row[r], xv);
         block_sum_R<R>(z, sh_red, buf);
+        // lane r evaluates row ib + r (slope, loss) once; wave 0 also records margin and loss
+        const int lane = threadIdx.x & (kWave - 1);
+        float zl = z[0];
+#pragma unroll
+        for (int r = 1; r < R; ++r) zl = lane == r ? z[r] : zl;
+        float coef_l = 0.0f;
+        if (lane < R && ib + lane < i1) {
+            const float y = yv[ib + lane];
+            coef_l = logistic_slope(y, zl) / fn;
+            if (threadIdx.x < R) {
+                loss += static_cast<double>(logistic_loss(y * zl));
+                if (z_out) z_out[ib + lane] = zl;
+            }
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            if (ib + r < i1) {
-                const float y = yv[ib + r];
-                if (z_out && threadIdx.x == 0) z_out[ib + r] = z[r];
-                loss += static_cast<double>(logistic_loss(y * z[r]));
-                axpy_cols<NC>(logistic_slope(y, z[r]) / fn, row[r], acc);
-            }
+            const float coef = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(coef_l), r));
+            axpy_cols<NC>(coef, row[r], acc);
         }
     };
     if (i0 < i1) {
@@ -432,7 +486,10 @@ __global__ __launch_bounds__(kRowThreads) void full_dense_partial_kernel(
         }
     }
     store_cols<NC>(partial + static_cast<int64_t>(blockIdx.x) * ldp, ldp, acc);
-    if (threadIdx.x == 0) loss_partial[blockIdx.x] = loss;
+    if (threadIdx.x < kWave) {                       // lanes 0..R-1 of wave 0 hold the block's loss terms
+        loss = wave_sum_f64(loss);
+        if (threadIdx.x == 0) loss_partial[blockIdx.x] = loss;
+    }
 }
 
 // g = sum_p partial_p + l2*x.  Block (64 x 16): thread (tx, ty) adds partials ty, ty+16, ... of
@@ -585,7 +642,13 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     switch (nc) {
     case 1: launch_vr<1, 8>(have_z, grid, st, k); break;
     case 2: launch_vr<2, 4>(have_z, grid, st, k); break;
-    default: launch_vr<4, 4>(have_z, grid, st, k); break;
+    default: {
+        static const int rows = [] { const char *e = getenv("DQ_VR_ROWS"); return e ? atoi(e) : 4; }();
+        if (rows == 8) launch_vr<4, 8>(have_z, grid, st, k);
+        else if (rows == 2) launch_vr<4, 2>(have_z, grid, st, k);
+        else launch_vr<4, 4>(have_z, grid, st, k);
+        break;
+    }
     }
     DQ_LAUNCH_CHECK();
     if (k.P > 1) {
