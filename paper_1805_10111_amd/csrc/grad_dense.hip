@@ -546,6 +546,15 @@ __global__ __launch_bounds__(kWave *kFinishY) void full_finish_kernel(
     }
 }
 
+int launch_full_finish(const float *partial, int P, int64_t ldp, int64_t n, int64_t d, const float *x, float l2, float l1,
+                       const double *loss_partial, float *g_out, double *obj_out, hipStream_t st)
+{
+    full_finish_kernel<<<dim3(static_cast<unsigned>(ceil_div(ceil_div(d, 4), kWave))), dim3(kWave, kFinishY), 0, st>>>(
+        partial, P, ldp, n, d, x, l2, l1, loss_partial, g_out, obj_out);
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
+}
+
 // ------------------------------------------------------------------ host side
 static int dense_nc(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 4096 ? 4 : 0; }
 
@@ -604,10 +613,7 @@ int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float 
     default: full_dense_partial_kernel<4, 4><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
     }
     DQ_LAUNCH_CHECK();
-    full_finish_kernel<<<dim3(static_cast<unsigned>(ceil_div(ceil_div(d, 4), kWave))), dim3(kWave, kFinishY), 0, st>>>(
-        partial, P, ldp, n, d, x, prob->l2, prob->l1, loss_partial, g_out, obj_out);
-    DQ_LAUNCH_CHECK();
-    return DQ_OK;
+    return launch_full_finish(partial, P, ldp, n, d, x, prob->l2, prob->l1, loss_partial, g_out, obj_out, st);
 }
 
 template <int NC, int R>

@@ -41,7 +41,7 @@ def _small(cfg_name):
     return cfg, synth.make_problem(cfg, n=4000), 12
 
 
-@pytest.mark.parametrize("name", ["C1", "C4"])
+@pytest.mark.parametrize("name", ["C1", "C4", "C2", "C3"])
 def test_lock_step_rounds(dq, name):
     cfg, p, m = _small(name)
     seed = 3
@@ -115,7 +115,7 @@ def test_lock_step_rounds(dq, name):
     assert flips <= max(2, 1e-3 * total), (flips, total)
 
 
-@pytest.mark.parametrize("name", ["C1", "C4"])
+@pytest.mark.parametrize("name", ["C1", "C4", "C2", "C3"])
 def test_free_run_objectives(dq, name):
     cfg, p, m = _small(name)
     S = 2

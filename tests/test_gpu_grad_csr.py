@@ -1,0 +1,195 @@
+"""GPU parity: CSR full gradient, variance-reduced gradient and fused worker step versus the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synth
+from gpu_util import dev, host, words
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def dq():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_1805_10111_amd as dq
+    return dq
+
+
+def _close(got, want, tol=TOL):
+    scale = np.abs(want).max()
+    err = np.abs(got.astype(np.float64) - want).max()
+    assert err <= tol * scale + 1e-30, (err, scale)
+
+
+def _long_rows_problem(n=40, d=20958, seed=0):
+    """CSR with a few very long rows: exercises staging groups and the unstaged path."""
+    rng = np.random.default_rng(seed)
+    lens = rng.integers(1, 80, size=n)
+    lens[3] = 10000
+    lens[7] = lens[8] = lens[9] = 3000
+    lens[20] = 1
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(lens, out=indptr[1:])
+    indices = np.concatenate([np.sort(rng.choice(d, size=l, replace=False)) for l in lens]).astype(np.int32)
+    values = (rng.standard_normal(indptr[-1]) / np.sqrt(np.repeat(lens, lens))).astype(np.float32)
+    y = np.where(rng.random(n) < 0.5, 1.0, -1.0).astype(np.float32)
+    return synth.Problem(n=n, d=d, y=y, l2=1e-3, l1=1e-4, indptr=indptr, indices=indices, values=values)
+
+
+def _problems():
+    return {
+        "text": synth.sparse_text_logistic(3000, 20958, seed=1),
+        "tiny": synth.sparse_text_logistic(60, 50, mean_nnz=6.0, seed=2, l2=1e-2),
+        "long": _long_rows_problem(),
+        "mid": synth.sparse_text_logistic(500, 4099, mean_nnz=30.0, seed=3),
+    }
+
+
+@pytest.fixture(scope="module")
+def problems():
+    return _problems()
+
+
+def _model(rng, d, b_x, x_snap, spread=0.05):
+    x = (x_snap + spread * rng.standard_normal(d)).astype(np.float32)
+    if b_x == 32:
+        return x.view(np.uint32).copy(), np.float32(1.0), x
+    k, dx, _ = oracle.quantize(x, b_x, 3, 1, oracle.MASTER_ID, oracle.TAG_MODEL)
+    return oracle.pack(k, b_x), dx, oracle.dequantize(k, dx)
+
+
+@pytest.mark.parametrize("name", ["text", "tiny", "long", "mid"])
+def test_full_grad(dq, problems, name):
+    p = problems[name]
+    P = dq.DeviceProblem.from_host(p)
+    rp = oracle.RefProblem(p)
+    x = (0.5 * np.random.default_rng(1).standard_normal(p.d)).astype(np.float32)
+    g = torch.zeros(p.d, device="cuda")
+    z = torch.zeros(p.n, device="cuda")
+    obj = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ws = dq.new_workspace(dq.OP_FULL_GRAD, P)
+    dq.dq_full_grad(P, dev(x), g, z, obj, ws)
+    g_ref, z_ref = oracle.full_grad(rp, x, want_margins=True)
+    _close(host(g), g_ref.astype(np.float64))
+    _close(host(z), z_ref.astype(np.float64))
+    assert abs(host(obj)[0] - oracle.objective(rp, x)) <= TOL * oracle.objective(rp, x)
+    g2 = torch.zeros(p.d, device="cuda")
+    dq.dq_full_grad(P, dev(x), g2, None, None, ws)
+    assert torch.equal(g, g2)                      # deterministic
+
+
+@pytest.mark.parametrize("have_z", [True, False])
+@pytest.mark.parametrize("b_x", [8, 2, 32])
+@pytest.mark.parametrize("name,M,B", [("text", 8, 32), ("tiny", 3, 5), ("long", 2, 40), ("mid", 4, 300)])
+def test_vr_grad(dq, problems, name, M, B, b_x, have_z):
+    p = problems[name]
+    P = dq.DeviceProblem.from_host(p)
+    rp = oracle.RefProblem(p)
+    d, n = p.d, p.n
+    rng = np.random.default_rng(5)
+    x_snap = (0.3 * rng.standard_normal(d)).astype(np.float32)
+    xq, dx, q = _model(rng, d, b_x, x_snap)
+    idx = np.stack([oracle.sample_indices(n, B, 11, 2, w) for w in range(M)])
+    if name == "long":
+        idx[:, :6] = [3, 7, 8, 9, 3, 20]            # make sure the long rows are in the batch
+    z_snap = None
+    if have_z:
+        _, z_ref = oracle.full_grad(rp, x_snap, want_margins=True)
+        z_snap = dev(z_ref)
+    ld = (d + 3) // 4 * 4
+    alpha = torch.full((M, ld), 5.0, device="cuda")[:, :d]
+    amax = torch.zeros(M, device="cuda")
+    l1n = torch.zeros(M, device="cuda")
+    dq.dq_vr_grad(P, dev(idx), M, B, dev(xq.view(np.int32)), dev(np.array([dx], dtype=np.float32)), b_x, False,
+                  dev(x_snap), z_snap, alpha, amax, l1n, None)
+    for w in range(M):
+        want = oracle.vr_grad(rp, idx[w], q, x_snap).astype(np.float64)
+        got = host(alpha)[w]
+        _close(got, want)
+        assert host(amax)[w] == np.abs(got).max()
+        assert abs(host(l1n)[w] - np.abs(got.astype(np.float64)).sum()) <= 1e-6 * np.abs(got).sum()
+    # deterministic
+    alpha2 = torch.zeros((M, ld), device="cuda")[:, :d]
+    dq.dq_vr_grad(P, dev(idx), M, B, dev(xq.view(np.int32)), dev(np.array([dx], dtype=np.float32)), b_x, False,
+                  dev(x_snap), z_snap, alpha2, amax, None, None)
+    assert torch.equal(alpha, alpha2)
+
+
+@pytest.mark.parametrize("sparsify", [False, True])
+@pytest.mark.parametrize("b", [8, 4])
+@pytest.mark.parametrize("name,M,B", [("text", 16, 64), ("tiny", 2, 7), ("long", 2, 12)])
+def test_worker_step(dq, problems, name, M, B, b, sparsify):
+    p = problems[name]
+    P = dq.DeviceProblem.from_host(p)
+    rp = oracle.RefProblem(p)
+    d, n = p.d, p.n
+    rng = np.random.default_rng(6)
+    x_snap = (0.3 * rng.standard_normal(d)).astype(np.float32)
+    xq, dx, q = _model(rng, d, 8, x_snap)
+    seed, it, w0 = 77, 9, 100
+    idx = np.stack([oracle.sample_indices(n, B, seed, it, w0 + w) for w in range(M)])
+    xs_d, xq_d, dx_d = dev(x_snap), dev(xq.view(np.int32)), dev(np.array([dx], dtype=np.float32))
+    nw = dq.packed_words(d, b)
+    ldw = (nw + 3) // 4 * 4
+    ld = (d + 3) // 4 * 4
+    # fused, sampling inside the kernel
+    packed = torch.full((M, ldw), -1, dtype=torch.int32, device="cuda")
+    delta = torch.zeros(M, device="cuda")
+    nnz = torch.zeros(M, dtype=torch.int32, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    alpha_f = torch.zeros((M, ld), device="cuda")[:, :d]
+    dq.dq_worker_step(P, None, M, B, xq_d, dx_d, 8, False, xs_d, None, sparsify, b, seed, it, w0, packed, delta, nnz,
+                      alpha_f, status, None)
+    # unfused chain of the same library with explicit indices: bit for bit
+    alpha = torch.zeros((M, ld), device="cuda")[:, :d]
+    amax = torch.zeros(M, device="cuda")
+    dq.dq_vr_grad(P, dev(idx), M, B, xq_d, dx_d, 8, False, xs_d, None, alpha, amax, None, None)
+    assert torch.equal(alpha, alpha_f)
+    v = alpha
+    if sparsify:
+        beta = torch.zeros((M, ld), device="cuda")[:, :d]
+        kept = torch.zeros(M, dtype=torch.int32, device="cuda")
+        dq.dq_sparsify(alpha, None, seed, it, w0, beta, amax, kept)
+        v = beta
+    packed2 = torch.full((M, ldw), -1, dtype=torch.int32, device="cuda")
+    delta2 = torch.zeros(M, device="cuda")
+    dq.dq_quantize_pack(v, b, amax, True, seed, it, dq.TAG_GRAD, w0, packed2, delta2)
+    assert torch.equal(packed[:, :nw], packed2[:, :nw]) and torch.equal(delta, delta2)
+    assert np.all(words(packed)[:, nw:] == 0xFFFFFFFF) and host(status)[0] == 0
+    flips = 0
+    for w in range(M):
+        a_ref = oracle.vr_grad(rp, idx[w], q, x_snap)
+        _close(host(alpha_f)[w], a_ref.astype(np.float64))
+        v_ref = oracle.sparsify(a_ref, seed, it, w0 + w)[0] if sparsify else a_ref
+        k_ref, d_ref, _ = oracle.quantize(v_ref, b, seed, it, w0 + w)
+        k = oracle.unpack(words(packed)[w, :nw], d, b)
+        assert host(nnz)[w] == np.count_nonzero(k)
+        assert abs(host(delta)[w] - d_ref) <= 2e-5 * d_ref
+        diff = np.abs(k.astype(np.int32) - k_ref.astype(np.int32))
+        flips += int(np.count_nonzero(diff))
+        if not sparsify:
+            assert diff.max() <= 1
+    assert flips <= max(3, 2e-3 * M * d), flips
+
+
+def test_flag_bit_round_and_limits(dq, problems):
+    p = problems["tiny"]
+    P = dq.DeviceProblem.from_host(p)
+    M, B, d = 2, 4, p.d
+    packed = torch.full((M, 16), -1, dtype=torch.int32, device="cuda")
+    delta = torch.full((M,), 3.0, device="cuda")
+    dq.dq_worker_step(P, None, M, B, None, None, 8, True, torch.zeros(d, device="cuda"), None, True, 4, 1, 1, 0,
+                      packed, delta, None, None, None, None)
+    assert not words(packed)[:, : dq.packed_words(d, 4)].any() and not host(delta).any()
+    # a model too wide for the on-chip gradient buffer is refused, not mangled
+    big = synth.Problem(n=2, d=60000, y=np.ones(2, dtype=np.float32), l2=0.0, l1=0.0,
+                        indptr=np.array([0, 1, 2], dtype=np.int64), indices=np.array([0, 5], dtype=np.int32),
+                        values=np.ones(2, dtype=np.float32))
+    Pb = dq.DeviceProblem.from_host(big)
+    x = torch.zeros(60000, device="cuda")
+    with pytest.raises(dq.DqError) as e:
+        dq.dq_full_grad(Pb, x, x.clone(), None, None, torch.zeros(1 << 22, device="cuda"))
+    assert e.value.code == dq.ERR_UNSUPPORTED
