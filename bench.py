@@ -36,6 +36,7 @@ def parse():
     ap.add_argument("--n", type=int, default=None, help="override the number of samples (testing only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-quantizer", action="store_true")
+    ap.add_argument("--no-other-configs", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     return ap.parse_args()
 
@@ -108,6 +109,30 @@ def quantizer_leg(dq, torch):
         del packed, res
     for k in out:
         out[k]["frac_of_hbm_peak"] = round(out[k]["GB/s"] / HBM_PEAK_GBS, 3)
+    return out
+
+
+def other_configs_leg(dq, torch, synth, Trainer, skip):
+    """Rounds of the small, launch-bound configs (C1-C3): microseconds per round and worker-steps/s."""
+    out = {}
+    for name in ("C1", "C2", "C3"):
+        if name == skip:
+            continue
+        cfg = synth.CONFIGS[name]
+        prob = synth.make_problem(cfg)
+        tr = Trainer(dq.DeviceProblem.from_host(prob), cfg.algo, cfg.M, cfg.B, cfg.b_x, cfg.b, cfg.m, cfg.lr, seed=cfg.seed)
+        tr._t = 0
+        run_rounds(tr, cfg.m)                      # one epoch of warm-up
+        torch.cuda.synchronize()
+        rounds = 2 * cfg.m
+        t0 = time.perf_counter()
+        run_rounds(tr, rounds)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        out[name] = {"us_per_round": round(dt / rounds * 1e6, 2), "worker_steps_per_s": round(cfg.M * rounds / dt, 1),
+                     "rounds": rounds, "M": cfg.M, "B": cfg.B, "d": prob.d,
+                     "note": "launch/latency-bound: under 3 MB of traffic per round"}
+        del tr
     return out
 
 
@@ -207,6 +232,10 @@ def main():
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                      "bytes_per_launch": alg_bytes, "avg_launch_us": round(k_avg * 1e6, 2)},
     }
+    del tr, P
+    torch.cuda.empty_cache()
+    if not args.no_other_configs:
+        result["other_configs"] = other_configs_leg(dq, torch, synth, DoubleQuantTrainer, args.config)
     if not args.no_quantizer:
         result["quantizer_C5"] = quantizer_leg(dq, torch)
     if not args.no_cpu_baseline:

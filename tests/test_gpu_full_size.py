@@ -1,0 +1,109 @@
+"""GPU parity at the full sizes of the configs, in the launch shapes the benchmark uses.
+
+The oracle checks what it can reach in seconds: the whole full gradient, the gradients of a
+few sampled workers, and one whole master step fed with the oracle's own messages.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import algorithms as alg
+import synth
+from gpu_util import dev, host, words
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def dq():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_1805_10111_amd as dq
+    return dq
+
+
+def _close(got, want, tol=TOL):
+    scale = np.abs(want).max()
+    err = np.abs(got.astype(np.float64) - want).max()
+    assert err <= tol * scale + 1e-30, (err, scale)
+
+
+@pytest.mark.parametrize("name", ["C4", "C2", "C3"])
+def test_one_round_at_full_size(dq, name):
+    cfg = synth.CONFIGS[name]
+    p = synth.make_problem(cfg)
+    P = dq.DeviceProblem.from_host(p)
+    rp = oracle.RefProblem(p)
+    d, n, M, B, b, bx = p.d, p.n, cfg.M, cfg.B, cfg.b, cfg.b_x
+    sparse = cfg.algo == "sparse"
+    rng = np.random.default_rng(1)
+    x_snap = (0.05 * rng.standard_normal(d)).astype(np.float32)
+    x = (x_snap + 0.01 * rng.standard_normal(d)).astype(np.float32)
+    seed, it = 5, 40
+    # ---- epoch prologue: whole vectors
+    g = torch.zeros(d, device="cuda")
+    z = torch.zeros(n, device="cuda")
+    obj = torch.zeros(1, dtype=torch.float64, device="cuda")
+    dq.dq_full_grad(P, dev(x_snap), g, z, obj, dq.new_workspace(dq.OP_FULL_GRAD, P))
+    g_ref, z_ref = oracle.full_grad(rp, x_snap, want_margins=True)
+    _close(host(g), g_ref.astype(np.float64))
+    _close(host(z), z_ref.astype(np.float64))
+    assert abs(host(obj)[0] - oracle.objective(rp, x_snap)) <= TOL * oracle.objective(rp, x_snap)
+    # ---- master (i): the model message, bit-exact
+    kx, dx, _ = oracle.quantize(x, bx, seed, it, oracle.MASTER_ID, oracle.TAG_MODEL)
+    xq_ref = oracle.pack(kx, bx)
+    q = oracle.dequantize(kx, dx)
+    xq = torch.zeros(dq.packed_words(d, bx), dtype=torch.int32, device="cuda")
+    dxo, amx = torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda")
+    dq.dq_quantize_pack(dev(x), bx, amx, False, seed, it, dq.TAG_MODEL, dq.MASTER_ID, xq, dxo)
+    assert np.array_equal(words(xq), xq_ref) and host(dxo)[0] == dx
+    # ---- worker side of the round, all M workers in one call, cached margins, in-kernel sampling
+    nw = dq.packed_words(d, b)
+    ldw = (nw + 3) // 4 * 4
+    packed = torch.zeros((M, ldw), dtype=torch.int32, device="cuda")
+    delta = torch.zeros(M, device="cuda")
+    nnz = torch.zeros(M, dtype=torch.int32, device="cuda")
+    alpha = torch.zeros((M, (d + 3) // 4 * 4), device="cuda")[:, :d]
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = dq.new_workspace(dq.OP_VR_GRAD, P, M, B)
+    dq.dq_worker_step(P, None, M, B, xq, dxo, bx, False, dev(x_snap), z, sparse, b, seed, it, 0, packed, delta, nnz,
+                      alpha, status, ws)
+    assert host(status)[0] == 0
+    flips = 0
+    for w in (0, M // 2, M - 1):
+        wd, dl, _, a_ref, _, _ = alg.worker_message(rp, q, x_snap, False, B, b, seed, it, w, sparse)
+        _close(host(alpha)[w], a_ref.astype(np.float64))
+        k = oracle.unpack(words(packed)[w, :nw], d, b)
+        k_ref = oracle.unpack(wd, d, b)
+        assert abs(host(delta)[w] - dl) <= 2e-5 * dl
+        assert host(nnz)[w] == np.count_nonzero(k)
+        flips += int(np.count_nonzero(k != k_ref))
+    assert flips <= max(3, 2e-3 * 3 * d), flips
+    # ---- master (ii)+(i) at full M, fed with the oracle's messages: bit-exact
+    codes = np.zeros((M, d), dtype=np.int8)
+    deltas = np.zeros(M, dtype=np.float32)
+    pw = np.zeros((M, ldw), dtype=np.uint32)
+    for w in range(M):
+        wd, dl, *_ = alg.worker_message(rp, q, x_snap, False, B, b, seed, it, w, sparse)
+        pw[w, :nw] = wd
+        codes[w] = oracle.unpack(wd, d, b)
+        deltas[w] = dl
+    y0 = (x + 0.01 * rng.standard_normal(d)).astype(np.float32)
+    s0 = rng.standard_normal(d).astype(np.float32)
+    acc = cfg.algo == "acc"
+    eta, theta = np.float32(0.3), np.float32(0.5)
+    x_ref, y_ref, s_ref = x.copy(), y0.copy(), s0.copy()
+    if acc:
+        oracle.master_update(codes, deltas, np.float32(1 / M), g_ref, x_ref, y_ref, x_snap, s_ref, eta=eta, theta=theta, l1=rp.l1)
+    else:
+        oracle.master_update(codes, deltas, np.float32(1 / M), g_ref, x_ref, eta=eta, l1=rp.l1)
+    kx2, dx2, _ = oracle.quantize(x_ref, bx, seed, it + 1, oracle.MASTER_ID, oracle.TAG_MODEL)
+    xd, yd, sd = dev(x), dev(y0), dev(s0)
+    dq.dq_master_step(dev(pw.view(np.int32)), dev(deltas), M, b, float(np.float32(1 / M)), dev(g_ref), xd,
+                      yd if acc else None, dev(x_snap), sd if acc else None, float(eta), float(theta), float(rp.l1),
+                      bx, seed, it + 1, xq, dxo, amx)
+    assert np.array_equal(host(xd).view(np.uint32), x_ref.view(np.uint32))
+    if acc:
+        assert np.array_equal(host(yd), y_ref) and np.array_equal(host(sd), s_ref)
+    assert np.array_equal(words(xq), oracle.pack(kx2, bx)) and host(dxo)[0] == dx2
