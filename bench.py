@@ -24,7 +24,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-EVENT_STRIDE = 8          # rounds between HIP-event brackets around the worker step
+EVENT_STRIDE = 8          # rounds between HIP-event brackets around the dominant kernel
+KERNEL_NAME = {False: "vr_dense_kernel (variance-reduced gradient, all M workers)",
+               True: "csr_worker_kernel (whole worker step, all M workers)"}
 
 
 def parse():
@@ -37,6 +39,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-quantizer", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (known traffic) for calibrating profiler byte counters")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     return ap.parse_args()
 
@@ -44,8 +48,9 @@ def parse():
 def run_rounds(tr, rounds, events=None):
     """Advance the trainer by `rounds` rounds, running epoch prologues/epilogues at their cadence.
 
-    `events`: optional list that receives (start, end, is_flag_round) per round, the two torch events
-    being recorded on the launch stream right before / after the round's worker-step kernels.
+    `events`: optional list that receives (start, end, is_flag_round) for the bracketed rounds, the two
+    torch events being recorded by the library on the launch stream right before / after the kernel that
+    streams the feature rows (the dominant kernel of a round).
     """
     import torch
     done = 0
@@ -74,6 +79,21 @@ def run_rounds(tr, rounds, events=None):
         if tr._t == tr.m:
             tr.epoch_epilogue()
             tr._t = 0
+
+
+def recorded_traffic(workload: str):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter passes
+    (profiles/traffic_<workload>.json), or None if the kernel sources changed since they were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload.lower()}.json")
+    if not os.path.exists(path):
+        return None
+    rec = json.load(open(path))
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_1805_10111_amd", "csrc")
+    for fn in sorted(os.listdir(csrc)):
+        h.update(open(os.path.join(csrc, fn), "rb").read())
+    return rec["traffic_bytes_per_launch"] if rec.get("csrc_sha256") == h.hexdigest() else None
 
 
 def quantizer_leg(dq, torch):
@@ -204,7 +224,8 @@ def main():
     if int(tr.status.item()) != 0:
         raise FloatingPointError("non-finite quantization scale during the benchmark")
 
-    # dominant kernel: the worker step (all M workers in one call); skip the flag-bit rounds (no rows read)
+    # dominant kernel: the row-streaming kernel of the worker step (all M workers in one launch);
+    # flag-bit rounds read no rows and are skipped
     durs = [e0.elapsed_time(e1) * 1e-3 for e0, e1, flag in events if not flag]
     k_avg = float(np.mean(durs))
     if prob.dense is not None:
@@ -227,13 +248,20 @@ def main():
                                f"b_x={cfg.b_x}, b={cfg.b}, m={cfg.m} rounds/epoch, "
                                f"{'CSR' if prob.is_csr else 'dense fp32'}; full gradient every m rounds inside the timed region",
                    "seed": cfg.seed, "datagen_s": round(t_gen, 1)},
-        "roofline": {"bound": "hbm", "kernel": "worker step (VR gradient + quantize + pack, all M workers)",
+        "roofline": {"bound": "hbm", "kernel": KERNEL_NAME[prob.is_csr],
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": recorded_traffic(cfg.name),
                      "bytes_per_launch": alg_bytes, "avg_launch_us": round(k_avg * 1e6, 2)},
     }
     del tr, P
     torch.cuda.empty_cache()
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)                     # reads 2^30 bytes, writes 2^30 bytes per launch
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_other_configs:
         result["other_configs"] = other_configs_leg(dq, torch, synth, DoubleQuantTrainer, args.config)
     if not args.no_quantizer:

@@ -57,7 +57,7 @@ extern "C" int32_t dq_full_grad(const dq_problem *prob, const float *x, float *g
                              : csr_full_grad(prob, x, g_out, z_out, obj_out, ws, ws_bytes, as_stream(stream));
 }
 
-static int32_t worker_common(const dq_problem *prob, const WorkerArgs &a, void *stream)
+int32_t dq::worker_step_impl(const dq_problem *prob, const WorkerArgs &a, void *stream)
 {
     int32_t rc = check_problem(prob);
     if (rc != DQ_OK) return rc;
@@ -85,7 +85,7 @@ extern "C" int32_t dq_vr_grad(const dq_problem *prob, const int32_t *idx, int64_
     a.model_is_snapshot = model_is_snapshot; a.x_snap = x_snap; a.z_snap = z_snap;
     a.alpha_out = alpha_out; a.ld = ld; a.absmax_out = absmax_out; a.l1norm_out = l1norm_out;
     a.b = 8; a.ws = ws; a.ws_bytes = ws_bytes;
-    return worker_common(prob, a, stream);
+    return worker_step_impl(prob, a, stream);
 }
 
 extern "C" int32_t dq_worker_step(const dq_problem *prob, const int32_t *idx, int64_t M, int64_t B,
@@ -107,5 +107,5 @@ extern "C" int32_t dq_worker_step(const dq_problem *prob, const int32_t *idx, in
     a.sparsify = sparsify; a.b = b; a.seed = seed; a.iter = iter; a.worker0 = worker0;
     a.packed = packed_out; a.ld_words = ld_words; a.delta_out = delta_out; a.nnz_out = nnz_out; a.status = status;
     a.ws = ws; a.ws_bytes = ws_bytes;
-    return worker_common(prob, a, stream);
+    return worker_step_impl(prob, a, stream);
 }

@@ -368,6 +368,7 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     if (rc != DQ_OK) return rc;
     csr_worker_kernel<<<dim3(static_cast<unsigned>(a.M)), dim3(kCsrThreads), lds, st>>>(k);
     DQ_LAUNCH_CHECK();
+    if (a.ev_after_stream) DQ_HIP_TRY(hipEventRecord(a.ev_after_stream, st));
     return DQ_OK;
 }
 

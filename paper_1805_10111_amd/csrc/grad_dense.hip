@@ -657,6 +657,7 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     }
     }
     DQ_LAUNCH_CHECK();
+    if (a.ev_after_stream) DQ_HIP_TRY(hipEventRecord(a.ev_after_stream, st));
     if (k.P > 1) {
         vr_dense_finish_kernel<<<dim3(static_cast<unsigned>(a.M)), dim3(kFinishThreads), static_cast<size_t>(d) * sizeof(float), st>>>(k);
         DQ_LAUNCH_CHECK();

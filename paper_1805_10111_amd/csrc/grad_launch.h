@@ -28,7 +28,11 @@ struct WorkerArgs {
     uint32_t *status;
     void *ws;
     int64_t ws_bytes;
+    hipEvent_t ev_after_stream;   // nullable: recorded right after the kernel that streams the feature rows
 };
+
+// Validation + dispatch shared by dq_vr_grad, dq_worker_step and dq_run_rounds.
+int32_t worker_step_impl(const dq_problem *prob, const WorkerArgs &a, void *stream);
 
 int64_t dense_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64_t B);
 int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float *z_out, double *obj_out, void *ws,
