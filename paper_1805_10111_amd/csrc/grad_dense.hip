@@ -560,11 +560,14 @@ static int dense_nc(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 409
 
 int64_t dense_vr_splits(int64_t M, int64_t B)
 {
-    // blocks per worker: about 1024 blocks in the grid, at least 4 rows per block when the batch allows
+    // blocks per worker.  A mini-batch of at most 32 rows stays in one block, which then runs the
+    // whole worker step in a single launch; larger ones are split so that about 512 blocks
+    // (two per compute unit) stream rows, each owning at least 4 of them.
     static const int64_t target = [] {
         const char *e = getenv("DQ_VR_BLOCKS");
         return e ? atoll(e) : 512ll;
     }();
+    if (B <= 32) return 1;
     int64_t P = ceil_div(target, M);
     const int64_t by_rows = ceil_div(B, 4);
     if (P > by_rows) P = by_rows;
