@@ -92,6 +92,10 @@ def lib() -> C.CDLL:
         _lib.ref_master_update.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_float, C.c_void_p,
                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_float, C.c_float, C.c_float]
+        _lib.ref_master_update_full.restype = None
+        _lib.ref_master_update_full.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_float, C.c_void_p,
+                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                C.c_float, C.c_float, C.c_float]
         _lib.ref_acc_mix.restype = None
         _lib.ref_acc_mix.argtypes = [C.c_void_p, C.c_void_p, C.c_float, C.c_int64, C.c_void_p]
         _lib.ref_acc_snapshot.restype = None
@@ -275,6 +279,16 @@ def master_update(codes, delta, scale, g_snap, x, y=None, x_snap=None, xsum=None
         assert a is None or (a.dtype == np.float32 and a.flags.c_contiguous and a.size == d)
     lib().ref_master_update(_p(codes), _p(delta), M, d, np.float32(scale), _p(g_snap), _p(x), _p(y),
                             _p(x_snap), _p(xsum), np.float32(eta), np.float32(theta), np.float32(l1))
+
+
+def master_update_full(grads, scale, g_snap, x, y=None, x_snap=None, xsum=None, eta=0.0, theta=0.0, l1=0.0) -> None:
+    """Master update from unquantized gradients: grads float32 [M, d]."""
+    grads = np.ascontiguousarray(grads, dtype=np.float32)
+    M, d = grads.shape
+    for a in (g_snap, x, y, x_snap, xsum):
+        assert a is None or (a.dtype == np.float32 and a.flags.c_contiguous and a.size == d)
+    lib().ref_master_update_full(_p(grads), M, d, np.float32(scale), _p(g_snap), _p(x), _p(y), _p(x_snap),
+                                 _p(xsum), np.float32(eta), np.float32(theta), np.float32(l1))
 
 
 def acc_mix(y, x_snap, theta) -> np.ndarray:

@@ -5,6 +5,10 @@ all M read the same quantized model, the master averages the M decoded gradients
 takes one proximal step (the paper applies gradients one at a time with bounded
 staleness; a round with zero staleness is this build's reading).  The iteration
 counter ``it = epoch_index * m + t`` addresses the random streams.
+
+``b_x = 32`` / ``b = 32`` switch the corresponding quantization off (the message is the
+float32 vector, 32*d bits): with both off this is AsyFPG / Acc-AsyFPG, with only the model
+unquantized it is the gradient-quantized QSVRG arrangement of Section 5.1.
 """
 from __future__ import annotations
 
@@ -15,8 +19,8 @@ from typing import List, Optional
 import numpy as np
 
 from . import (MASTER_ID, TAG_GRAD, TAG_MODEL, RefProblem, acc_mix, acc_snapshot, dequantize,
-               full_grad, master_update, objective, pack, quantize, sample_indices, sparsify, unpack,
-               vr_grad)
+               full_grad, master_update, master_update_full, objective, pack, quantize, sample_indices,
+               sparsify, unpack, vr_grad)
 
 
 @dataclass
@@ -37,6 +41,8 @@ def model_message(x: np.ndarray, x_snap: np.ndarray, b_x: int, seed: int, it: in
     d = x.size
     if np.array_equal(x.view(np.uint32), x_snap.view(np.uint32)):
         return x_snap.copy(), None, np.float32(0), 1
+    if b_x == 32:
+        return x.copy(), x.view(np.uint32).copy(), np.float32(1), 32 * d
     k, dx, _ = quantize(x, b_x, seed, it, MASTER_ID, TAG_MODEL)
     words = pack(k, b_x)
     q = dequantize(unpack(words, d, b_x), dx)
@@ -61,6 +67,10 @@ def worker_message(rp: RefProblem, q, x_snap, model_is_snapshot: bool, B: int, b
     if sparse:
         beta, nnz = sparsify(alpha, seed, it, worker)
         v = beta
+    if b == 32:                                      # unquantized message: the vector itself
+        nz = int(np.count_nonzero(v))
+        bits = 32 * d if not sparse else nz * (math.ceil(math.log2(d)) + 32)
+        return v.view(np.uint32).copy(), np.float32(1), bits, alpha, beta, idx
     k, dlt, _ = quantize(v, b, seed, it, worker, TAG_GRAD)
     words = pack(k, b)
     if sparse:
@@ -98,18 +108,22 @@ def run(prob, algo: str, M: int, B: int, b_x: int, b: int, m: int, S: int, lr: f
             flag = bits == 1
             tr.bits_down += bits
             codes = np.zeros((M, d), dtype=np.int8)
+            grads = np.zeros((M, d), dtype=np.float32)
             deltas = np.zeros(M, dtype=np.float32)
             for w in range(M):
                 words, dlt, bits, _, _, _ = worker_message(rp, q, x_snap, flag, B, b, seed, it, w, sparse)
-                codes[w] = unpack(words, d, b)
+                if b == 32:
+                    grads[w] = words.view(np.float32)
+                else:
+                    codes[w] = unpack(words, d, b)
                 deltas[w] = dlt
                 tr.bits_up += bits
-            if algo == "acc":
-                master_update(codes, deltas, np.float32(1.0 / M), g_snap, x, y, x_snap, xsum,
-                              eta=eta, theta=theta, l1=rp.l1)   # Alg. 3, master (ii)
+            yy, ss = (y, xsum) if algo == "acc" else (None, None)     # Alg. 3 / Alg. 1, master (ii)
+            if b == 32:
+                master_update_full(grads, np.float32(1.0 / M), g_snap, x, yy, x_snap, ss, eta=eta, theta=theta, l1=rp.l1)
             else:
-                master_update(codes, deltas, np.float32(1.0 / M), g_snap, x,
-                              eta=eta, l1=rp.l1)                # Alg. 1, master (ii)
+                master_update(codes, deltas, np.float32(1.0 / M), g_snap, x, yy, x_snap, ss, eta=eta, theta=theta,
+                              l1=rp.l1)
         if algo == "acc":
             x_snap = acc_snapshot(xsum, m)                      # Alg. 3, epoch end
         else:

@@ -354,6 +354,24 @@ static float soft_threshold(float z, float kappa)
     return m > 0.0f ? copysignf(m, z) : 0.0f;
 }
 
+static void master_apply(int64_t j, float acc, float scale, const float *g_snap, float *x, float *y,
+                         const float *x_snap, float *xsum, float eta, float theta, float kappa)
+{
+    float gbar = scale * acc;
+    float u = gbar + g_snap[j];
+    if (!y) {
+        float step = eta * u;
+        x[j] = soft_threshold(x[j] - step, kappa);
+    } else {
+        float step = eta * u;
+        y[j] = soft_threshold(y[j] - step, kappa);
+        float dy = y[j] - x_snap[j];
+        float mv = theta * dy;
+        x[j] = x_snap[j] + mv;
+        if (xsum) xsum[j] = xsum[j] + x[j];
+    }
+}
+
 void ref_master_update(const int8_t *codes, const float *delta, int64_t M, int64_t d, float scale,
                        const float *g_snap, float *x, float *y, const float *x_snap, float *xsum,
                        float eta, float theta, float l1)
@@ -362,19 +380,21 @@ void ref_master_update(const int8_t *codes, const float *delta, int64_t M, int64
     for (int64_t j = 0; j < d; ++j) {
         float acc = 0.0f;
         for (int64_t w = 0; w < M; ++w) acc = fmaf(delta[w], (float)codes[w * d + j], acc);
-        float gbar = scale * acc;
-        float u = gbar + g_snap[j];
-        if (!y) {
-            float step = eta * u;
-            x[j] = soft_threshold(x[j] - step, kappa);
-        } else {
-            float step = eta * u;
-            y[j] = soft_threshold(y[j] - step, kappa);
-            float dy = y[j] - x_snap[j];
-            float mv = theta * dy;
-            x[j] = x_snap[j] + mv;
-            if (xsum) xsum[j] = xsum[j] + x[j];
-        }
+        master_apply(j, acc, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa);
+    }
+}
+
+/* The same update when the workers send their gradients unquantized (the full-precision
+ * comparison algorithms of Section 5.1): grads holds M rows of d floats, summed in worker order. */
+void ref_master_update_full(const float *grads, int64_t M, int64_t d, float scale,
+                            const float *g_snap, float *x, float *y, const float *x_snap, float *xsum,
+                            float eta, float theta, float l1)
+{
+    const float kappa = eta * l1;
+    for (int64_t j = 0; j < d; ++j) {
+        float acc = 0.0f;
+        for (int64_t w = 0; w < M; ++w) acc = acc + grads[w * d + j];
+        master_apply(j, acc, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa);
     }
 }
 

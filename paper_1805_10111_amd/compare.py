@@ -1,0 +1,78 @@
+"""Bits-to-loss comparison of the six algorithms of Section 5.1 on a synthetic problem.
+
+AsyLPG, Sparse-AsyLPG, Acc-AsyLPG (double quantization), QSVRG (gradient quantization only) and the
+full-precision AsyFPG / Acc-AsyFPG all run through the same kernels (b = 32 / b_x = 32 switch a
+quantizer off).  Reports, per algorithm, the objective per epoch and the number of transmitted bits
+(worker -> master plus M copies of master -> worker) when the objective at a snapshot first falls below
+the threshold, and the saving relative to AsyFPG -- the quantity of Fig. 4 and Table 1 of the paper,
+here on synthetic data.
+
+    python -m paper_1805_10111_amd.compare --config C1 --epochs 6 --threshold 0.6
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+ALGORITHMS = {                      # name: (loop, b_x, b or None = config's)
+    "AsyFPG": ("asylpg", 32, 32),
+    "Acc-AsyFPG": ("acc", 32, 32),
+    "QSVRG": ("asylpg", 32, None),
+    "AsyLPG": ("asylpg", 8, None),
+    "Sparse-AsyLPG": ("sparse", 8, None),
+    "Acc-AsyLPG": ("acc", 8, None),
+}
+
+
+def run_comparison(cfg, prob, epochs: int, threshold: float, b: int, m: int | None = None, seed: int = 0):
+    import paper_1805_10111_amd as dq
+    from paper_1805_10111_amd.driver import DoubleQuantTrainer
+
+    P = dq.DeviceProblem.from_host(prob)
+    m = cfg.m if m is None else m
+    out = {}
+    for name, (algo, b_x, bb) in ALGORITHMS.items():
+        tr = DoubleQuantTrainer(P, algo, cfg.M, cfg.B, b_x, b if bb is None else bb, m, cfg.lr, seed=seed)
+        bits_at, objs, hit = [], [], None
+        for e in range(epochs):
+            tr.run_epoch()
+            objs.append(tr.log.objectives[-1])                 # objective at the start of epoch e
+            bits_at.append(tr.log.bits_up + cfg.M * tr.log.bits_down)
+        objs.append(tr.objective(tr.x_snap))
+        # objective e+1 is reached after the bits of epochs 0..e
+        for e in range(epochs):
+            if objs[e + 1] < threshold:
+                hit = bits_at[e]
+                break
+        out[name] = {"objectives": [round(o, 6) for o in objs], "bits_total": bits_at[-1], "bits_to_threshold": hit}
+    base = out["AsyFPG"]["bits_to_threshold"]
+    for name, r in out.items():
+        r["saving_vs_AsyFPG"] = None if not (base and r["bits_to_threshold"]) else round(base / r["bits_to_threshold"], 2)
+    return out
+
+
+def main():
+    import synth
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", default="C1", choices=["C1", "C2", "C4"])
+    ap.add_argument("--n", type=int, default=None)
+    ap.add_argument("--epochs", type=int, default=6)
+    ap.add_argument("--rounds", type=int, default=None, help="rounds per epoch (default: the config's)")
+    ap.add_argument("--threshold", type=float, default=0.6)
+    ap.add_argument("--bits", type=int, default=8, help="b of the quantized algorithms")
+    args = ap.parse_args()
+    cfg = synth.CONFIGS[args.config]
+    prob = synth.make_problem(cfg, n=args.n)
+    res = run_comparison(cfg, prob, args.epochs, args.threshold, args.bits, args.rounds)
+    print(json.dumps({"config": cfg.name, "n": prob.n, "d": prob.d, "M": cfg.M, "B": cfg.B, "threshold": args.threshold,
+                      "b": args.bits, "results": res}, indent=1))
+
+
+if __name__ == "__main__":
+    main()

@@ -111,16 +111,20 @@ class DoubleQuantTrainer:
         self._account(flags)
 
     def _account(self, flags) -> None:
+        """Objective at the epoch start and transmitted bits of the epoch (Section 3.1: 32 + b*d bits per
+        quantized vector, 32*d unquantized; Section 4.2: position + value per nonzero of a sparsified one)."""
         d, M, m = self.prob.d, self.M, self.m
         self.log.objectives.append(float(self.obj.item()))
         self.log.rounds += m
+        model_bits = 32 * d if self.b_x == 32 else 32 + self.b_x * d
         for flag in flags:
-            self.log.bits_down += 1 if flag else 32 + self.b_x * d
+            self.log.bits_down += 1 if flag else model_bits
         if self.algo == "sparse":
             nz = int(self.nnz.sum().item())
-            self.log.bits_up += 32 * m * M + nz * (math.ceil(math.log2(d)) + self.b)
+            header = 0 if self.b == 32 else 32
+            self.log.bits_up += header * m * M + nz * (math.ceil(math.log2(d)) + self.b)
         else:
-            self.log.bits_up += m * M * (32 + self.b * d)
+            self.log.bits_up += m * M * (32 * d if self.b == 32 else 32 + self.b * d)
 
     def run(self, S: int) -> RunLog:
         for _ in range(S):

@@ -138,3 +138,38 @@ def test_runs_are_reproducible(dq):
     c = _trainer(dq, p, cfg, 10, seed=6); c.run(2)
     assert torch.equal(a.x_snap, b.x_snap) and torch.equal(a.packed, b.packed)
     assert not torch.equal(a.x_snap, c.x_snap)
+
+
+@pytest.mark.parametrize("algo,b_x,b", [("asylpg", 32, 32), ("acc", 32, 32), ("asylpg", 32, 8), ("asylpg", 8, 32),
+                                        ("sparse", 32, 4)])
+def test_unquantized_modes_free_run(dq, algo, b_x, b):
+    """b = 32 / b_x = 32: AsyFPG, Acc-AsyFPG and QSVRG-style runs through the same kernels."""
+    from paper_1805_10111_amd.driver import DoubleQuantTrainer
+    cfg = synth.CONFIGS["C1"]
+    p = synth.make_problem(cfg, n=600, d=200)
+    m, S = 12, 2
+    tr = DoubleQuantTrainer(dq.DeviceProblem.from_host(p), algo, cfg.M, cfg.B, b_x, b, m, cfg.lr, seed=4)
+    log = tr.run(S)
+    ref = alg.run(p, algo, cfg.M, cfg.B, b_x, b, m, S, cfg.lr, seed=4)
+    for a, r in zip(log.objectives, ref.objectives):
+        assert abs(a - r) <= TOL * abs(r)
+    assert log.bits_down == ref.bits_down
+    if algo != "sparse":
+        assert log.bits_up == ref.bits_up
+    else:
+        assert abs(log.bits_up - ref.bits_up) <= 0.01 * ref.bits_up      # a flipped keep decision moves a few codes
+    rel = np.abs(host(tr.x_snap) - ref.x_snap).max() / np.abs(ref.x_snap).max()
+    assert rel < (2e-5 if (b, b_x) == (32, 32) else 2e-3), rel
+
+
+def test_comparison_of_the_six_algorithms(dq):
+    from paper_1805_10111_amd.compare import run_comparison
+    cfg = synth.CONFIGS["C1"]
+    p = synth.make_problem(cfg, n=1000, d=400)
+    res = run_comparison(cfg, p, epochs=3, threshold=0.69, b=8, m=40)
+    assert set(res) == {"AsyFPG", "Acc-AsyFPG", "QSVRG", "AsyLPG", "Sparse-AsyLPG", "Acc-AsyLPG"}
+    fp, lp, qs, sp = res["AsyFPG"], res["AsyLPG"], res["QSVRG"], res["Sparse-AsyLPG"]
+    assert lp["bits_total"] < qs["bits_total"] < fp["bits_total"]
+    assert sp["bits_total"] < lp["bits_total"]
+    assert abs(lp["objectives"][-1] - fp["objectives"][-1]) < 0.01 * fp["objectives"][-1]
+    assert 3.5 < fp["bits_total"] / lp["bits_total"] < 4.1        # (32 d) / (32 + 8 d) per message
