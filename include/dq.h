@@ -219,6 +219,13 @@ int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, const float *de
                        uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out,
                        uint32_t *status, void *stream);
 
+/* The two sides of the precision-loss condition on the model quantization (eq. (2); eq. (4) for
+ * Alg. 3):  out[0] = E_Q ||Q_(delta_x,b)(x) - x||^2 over the rounding decisions, which is
+ * delta_x^2 * sum_i p_i (1 - p_i) (proof of Lemma 5; nothing is sampled), and
+ * out[1] = ||x - x_snap||^2.  The condition holds for a given mu iff out[0] <= mu * out[1]
+ * (theta_s * mu for Alg. 3).  out: device double[2].  b in [2,8].  Diagnostic, one block. */
+int32_t dq_mu_terms(const float *x, const float *x_snap, int64_t d, int32_t b, double *out, void *stream);
+
 /* Start of an epoch of Alg. 3:  x_out = x_snap + theta*(y - x_snap)  (= theta*y + (1-theta)*x_snap). */
 int32_t dq_acc_mix(const float *y, const float *x_snap, float theta, int64_t d, float *x_out, void *stream);
 /* End of an epoch of Alg. 3:  x_snap_out = xsum / m. */

@@ -102,6 +102,10 @@ def lib() -> C.CDLL:
         _lib.ref_acc_snapshot.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p]
         _lib.ref_mu_terms.restype = None
         _lib.ref_mu_terms.argtypes = [C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+        _lib.ref_expected_sq_error.restype = C.c_double
+        _lib.ref_expected_sq_error.argtypes = [C.c_void_p, C.c_int64, C.c_int]
+        _lib.ref_sq_distance.restype = C.c_double
+        _lib.ref_sq_distance.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
         _lib.ref_philox4x32_10.restype = None
         _lib.ref_philox4x32_10.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     return _lib
@@ -311,3 +315,23 @@ def mu_terms(codes, delta, x, x_snap):
     out = np.zeros(2, dtype=np.float64)
     lib().ref_mu_terms(_p(codes), np.float32(delta), _p(x), _p(x_snap), x.size, _p(out))
     return out
+
+
+def expected_sq_error(x, b: int) -> float:
+    """E_Q ||Q(x) - x||^2 for the b-bit quantizer with the max-norm scale (left side of condition (2))."""
+    x = _f32(x)
+    return float(lib().ref_expected_sq_error(_p(x), x.size, b))
+
+
+def sq_distance(x, x_snap) -> float:
+    x, x_snap = _f32(x), _f32(x_snap)
+    return float(lib().ref_sq_distance(_p(x), _p(x_snap), x.size))
+
+
+def smallest_bx(x, x_snap, mu: float, candidates=(2, 4, 8)) -> int:
+    """Smallest b_x among `candidates` that satisfies condition (2) for this mu; 32 if none does."""
+    r = sq_distance(x, x_snap)
+    for b in sorted(candidates):
+        if expected_sq_error(x, b) <= mu * r:
+            return b
+    return 32

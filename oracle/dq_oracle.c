@@ -415,6 +415,37 @@ void ref_acc_snapshot(const float *xsum, int64_t m, int64_t d, float *x_snap_out
     for (int64_t j = 0; j < d; ++j) x_snap_out[j] = xsum[j] / (float)m;
 }
 
+/* Left side of condition (2) / (4): E_Q ||Q_(delta,b)(x) - x||^2 over the rounding decisions.
+ * Coordinate i moves to z+delta with probability p_i and to z with 1-p_i, so its expected
+ * squared error is delta^2 p_i (1 - p_i) (proof of Lemma 5); p_i as the quantizer computes it. */
+double ref_expected_sq_error(const float *x, int64_t d, int b)
+{
+    const int L = level_max(b);
+    float amax = ref_absmax(x, d);
+    float delta = ref_delta(amax, b);
+    if (!(delta > 0.0f) || isinf(delta)) {          /* all codes are zero: the error is ||x||^2 */
+        double s = 0.0;
+        for (int64_t i = 0; i < d; ++i) s += (double)x[i] * (double)x[i];
+        return s;
+    }
+    const float inv_delta = (float)L / amax;
+    double s = 0.0;
+    for (int64_t i = 0; i < d; ++i) {
+        float t = x[i] * inv_delta;
+        float p = t - floorf(t);
+        s += (double)p * (1.0 - (double)p);
+    }
+    return (double)delta * (double)delta * s;
+}
+
+/* Right side of condition (2) without mu: ||x - xs||^2. */
+double ref_sq_distance(const float *x, const float *xs, int64_t d)
+{
+    double r = 0.0;
+    for (int64_t j = 0; j < d; ++j) r += ((double)x[j] - (double)xs[j]) * ((double)x[j] - (double)xs[j]);
+    return r;
+}
+
 /* Squared distances of condition (2): ||Q(x)-x||^2 and ||x-xs||^2 (double). */
 void ref_mu_terms(const int8_t *codes, float delta, const float *x, const float *x_snap, int64_t d,
                   double out[2])

@@ -84,6 +84,7 @@ _SIGS = {
                               _i32, _u64, _u32, _vp, _vp, _vp, _vp, _vp]),
     "dq_acc_mix": (_i32, [_vp, _vp, _f32, _i64, _vp, _vp]),
     "dq_acc_snapshot": (_i32, [_vp, _i64, _i64, _vp, _vp]),
+    "dq_mu_terms": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp]),
     "dq_run_rounds": (_i32, [_vp, _vp, _vp, _i64, _i64, _i64, _f32, _f32, _vp, _vp]),
 }
 
@@ -321,6 +322,11 @@ def dq_acc_snapshot(xsum, m, x_snap_out) -> None:
                                                    _ptr(x_snap_out, torch.float32, "x_snap_out"), _stream()))
 
 
+def dq_mu_terms(x, x_snap, b, out) -> None:
+    _check("dq_mu_terms", _lib.dq_mu_terms(_ptr(x, torch.float32, "x"), _ptr(x_snap, torch.float32, "x_snap"), x.numel(), b,
+                                           _ptr(out, torch.float64, "out"), _stream()))
+
+
 def dq_run_rounds(prob: DeviceProblem, cfg: RunConfig, state: RunState, epoch: int, t0: int, rounds: int,
                   eta: float, theta: float, worker_events=None) -> None:
     """worker_events: optional list of 2*rounds raw hipEvent_t handles (ints)."""
@@ -339,5 +345,5 @@ __all__ = [
     "dq_version", "dq_last_device_error", "dq_workspace_bytes", "dq_workspace_init", "new_workspace", "dq_absmax", "dq_quantize", "dq_dequantize",
     "dq_pack", "dq_unpack", "dq_quantize_pack", "dq_unpack_dequant_sum", "dq_sample_indices", "dq_full_grad",
     "dq_vr_grad", "dq_sparsify", "dq_worker_step", "dq_master_step", "dq_acc_mix", "dq_acc_snapshot",
-    "dq_run_rounds", "RunConfig", "RunState", "ALGO",
+    "dq_run_rounds", "dq_mu_terms", "RunConfig", "RunState", "ALGO",
 ]

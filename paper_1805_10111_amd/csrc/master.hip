@@ -276,10 +276,52 @@ __global__ __launch_bounds__(kSparsifyThreads) void sparsify_kernel(
     }
 }
 
+// ------------------------------------------------------------------ condition (2) / (4) of the paper
+// out[0] = E_Q ||Q_(delta,b)(x) - x||^2 = delta^2 sum_i p_i (1 - p_i)   (p_i as the quantizer forms it)
+// out[1] = ||x - x_snap||^2.   One block; double accumulation in a fixed order.
+__global__ __launch_bounds__(kSparsifyThreads) void mu_terms_kernel(const float *__restrict__ x, const float *__restrict__ xs,
+                                                                    int64_t d, int b, double *__restrict__ out)
+{
+    __shared__ uint32_t su[kSparsifyThreads / kWave];
+    __shared__ double sd[kSparsifyThreads / kWave];
+    uint32_t mb = 0;
+    for (int64_t i = threadIdx.x; i < d; i += kSparsifyThreads) mb = max(mb, abs_bits(x[i]));
+    mb = block_max_u32(mb, su);
+    const Scale s = make_scale(__uint_as_float(mb), b);
+    double e = 0.0, r = 0.0;
+    for (int64_t i = threadIdx.x; i < d; i += kSparsifyThreads) {
+        const float xi = x[i];
+        if (s.inv_delta == 0.0f) {
+            e += static_cast<double>(xi) * static_cast<double>(xi);          // every code is zero
+        } else {
+            const float t = xi * s.inv_delta;
+            const float p = t - floorf(t);
+            e += static_cast<double>(p) * (1.0 - static_cast<double>(p));
+        }
+        const double dxs = static_cast<double>(xi) - static_cast<double>(xs[i]);
+        r += dxs * dxs;
+    }
+    e = block_sum_f64(e, sd);
+    r = block_sum_f64(r, sd);
+    if (threadIdx.x == 0) {
+        out[0] = s.inv_delta == 0.0f ? e : static_cast<double>(s.delta) * static_cast<double>(s.delta) * e;
+        out[1] = r;
+    }
+}
+
 }  // namespace dq
 
 using namespace dq;
 static inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+extern "C" int32_t dq_mu_terms(const float *x, const float *x_snap, int64_t d, int32_t b, double *out, void *stream)
+{
+    if (d <= 0 || !x || !x_snap || !out) return DQ_ERR_INVALID_ARG;
+    if (b < 2 || b > 8) return DQ_ERR_INVALID_ARG;
+    mu_terms_kernel<<<dim3(1), dim3(kSparsifyThreads), 0, as_stream(stream)>>>(x, x_snap, d, b, out);
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
+}
 
 extern "C" int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
                                   float scale, const float *g_snap, float *x, float *y, const float *x_snap, float *xsum,

@@ -57,6 +57,7 @@ class DoubleQuantTrainer:
         self.epoch_index = 0
         self.theta, self.eta = 0.0, self.lr
         self.log = RunLog()
+        self.mu_trace = []
         p = lambda t: None if t is None else t.data_ptr()
         self.cfg = dq.RunConfig(algo=dq.ALGO[algo], M=M, B=B, b_x=b_x, b=b, m=m, seed=self.seed)
         self.state = dq.RunState(
@@ -103,9 +104,20 @@ class DoubleQuantTrainer:
             self.x_snap.copy_(self.x)
         self.epoch_index += 1
 
-    def run_epoch(self) -> None:
+    def run_epoch(self, record_mu: bool = False) -> None:
+        """One epoch.  record_mu: after every round also evaluate both sides of condition (2) for the model
+        the master is about to send (appended to ``self.mu_trace`` as [epoch, t, E||Q(x)-x||^2, ||x-x_snap||^2];
+        their ratio is the smallest mu for which the condition holds, cf. Fig. 2 of the paper)."""
         self.epoch_prologue()
-        self.rounds(0, self.m)
+        if not record_mu or self.b_x == 32:
+            self.rounds(0, self.m)
+        else:
+            buf = torch.zeros((self.m, 2), dtype=torch.float64, device=self.x.device)
+            for t in range(self.m):
+                self.rounds(t, 1)
+                dq.dq_mu_terms(self.x, self.x_snap, self.b_x, buf[t])
+            for t, (e, r) in enumerate(buf.cpu().tolist()):
+                self.mu_trace.append([self.epoch_index, t, e, r])
         flags = [self.is_flag_round(t) for t in range(self.m)]
         self.epoch_epilogue()
         self._account(flags)
@@ -138,3 +150,16 @@ class DoubleQuantTrainer:
         g = torch.empty_like(self.g_snap)
         dq.dq_full_grad(self.prob, x, g, None, self.obj, self.ws_full)
         return float(self.obj.item())
+
+
+def smallest_bx(x: torch.Tensor, x_snap: torch.Tensor, mu: float, candidates=(2, 4, 8)) -> int:
+    """Smallest b_x among `candidates` for which condition (2) holds with this mu (32 if none does):
+    the selection procedure behind the mu / b_x table of Section 5.2."""
+    out = torch.zeros((len(candidates), 2), dtype=torch.float64, device=x.device)
+    cands = sorted(candidates)
+    for i, b in enumerate(cands):
+        dq.dq_mu_terms(x, x_snap, b, out[i])
+    for b, (e, r) in zip(cands, out.cpu().tolist()):
+        if e <= mu * r:
+            return b
+    return 32

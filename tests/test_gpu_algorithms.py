@@ -173,3 +173,19 @@ def test_comparison_of_the_six_algorithms(dq):
     assert sp["bits_total"] < lp["bits_total"]
     assert abs(lp["objectives"][-1] - fp["objectives"][-1]) < 0.01 * fp["objectives"][-1]
     assert 3.5 < fp["bits_total"] / lp["bits_total"] < 4.1        # (32 d) / (32 + 8 d) per message
+
+
+def test_mu_trace_follows_the_papers_observation(dq):
+    """Fig. 2 of the paper: the mu needed for condition (2) is largest right after the snapshot
+    (x is still close to it) and falls as x moves away within the epoch."""
+    from paper_1805_10111_amd.driver import DoubleQuantTrainer
+    cfg = synth.CONFIGS["C1"]
+    p = synth.make_problem(cfg, n=600, d=200)
+    tr = DoubleQuantTrainer(dq.DeviceProblem.from_host(p), "asylpg", cfg.M, cfg.B, 8, 8, 30, cfg.lr, seed=1)
+    tr.run_epoch(record_mu=True)
+    tr.run_epoch(record_mu=True)
+    assert len(tr.mu_trace) == 60
+    # (in the very first epoch the snapshot is 0 and both sides scale with ||x||^2: the ratio is flat)
+    mus = [r[2] / r[3] for r in tr.mu_trace if r[0] == 1 and r[3] > 0]
+    assert all(np.isfinite(mus))
+    assert mus[0] == max(mus) and mus[0] > 10 * mus[-1]

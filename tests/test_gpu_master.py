@@ -145,3 +145,34 @@ def test_master_invalid_arguments(dq):
     with pytest.raises(dq.DqError) as e:
         dq.dq_master_step(p, one, 1, 8, 1.0, z, z.clone(), z.clone(), None, None, 0.1, 0.0, 0.0, 8, 0, 0, p.clone(), one, one.clone())
     assert e.value.code == dq.ERR_INVALID_ARG          # momentum update without a snapshot
+
+
+@pytest.mark.parametrize("b", [2, 4, 8])
+@pytest.mark.parametrize("d", [1, 1000, 20958, 100003])
+def test_mu_terms(dq, b, d):
+    rng = np.random.default_rng(d + b)
+    x = rng.standard_normal(d).astype(np.float32)
+    xs = (x + 0.05 * rng.standard_normal(d)).astype(np.float32)
+    out = torch.zeros(2, dtype=torch.float64, device="cuda")
+    dq.dq_mu_terms(dev(x), dev(xs), b, out)
+    e, r = host(out)
+    assert abs(e - oracle.expected_sq_error(x, b)) <= 1e-10 * oracle.expected_sq_error(x, b) + 1e-300
+    assert abs(r - oracle.sq_distance(x, xs)) <= 1e-10 * oracle.sq_distance(x, xs)
+
+
+def test_mu_terms_degenerate_and_bx_choice(dq):
+    from paper_1805_10111_amd.driver import smallest_bx
+    out = torch.zeros(2, dtype=torch.float64, device="cuda")
+    z = np.zeros(50, dtype=np.float32)
+    dq.dq_mu_terms(dev(z), dev(z), 8, out)
+    assert host(out).tolist() == [0.0, 0.0]
+    tiny = np.full(7, 1e-44, dtype=np.float32)
+    dq.dq_mu_terms(dev(tiny), dev(z[:7]), 8, out)
+    assert np.isclose(host(out)[0], oracle.expected_sq_error(tiny, 8), rtol=1e-12)
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(3000).astype(np.float32)
+    xs = (x + 0.02 * rng.standard_normal(3000)).astype(np.float32)
+    for mu in (1e-6, 1e-3, 0.05, 1.0, 100.0):
+        assert smallest_bx(dev(x), dev(xs), mu) == oracle.smallest_bx(x, xs, mu)
+    with pytest.raises(dq.DqError):
+        dq.dq_mu_terms(dev(x), dev(xs), 9, out)
