@@ -244,12 +244,17 @@ typedef struct dq_run_config {
     int32_t b_x, b;      /* bits of the model message and of the gradient message (32 = not quantized) */
     int64_t m;           /* rounds per epoch */
     uint64_t seed;
+    int32_t tau;         /* emulated bounded delay (Assumption 3): 0 = every worker reads the current model;
+                            tau > 0: the workers form tau+1 contiguous groups, worker w belongs to group
+                            g = floor(w*(tau+1)/M) and reads the model message of round max(0, t-g) */
 } dq_run_config;
 
 /* Device buffers of a run (host struct holding device pointers; all caller-owned).
  * x, x_snap, g_snap: float[d].  y, xsum: float[d], Alg. 3 only.  z_snap: float[n] margins at the
- * snapshot from dq_full_grad, nullable.  xq: model message (ceil(d*b_x/32) words, or d floats),
- * delta_x, absmax_x: float[1].  packed: M rows of ld_words words; delta: float[M];
+ * snapshot from dq_full_grad, nullable.  xq: ring of tau+1 model messages, slot s at
+ * xq + s*xq_stride_words (each ceil(d*b_x/32) words, or d floats; 16-byte aligned slots);
+ * delta_x: float[tau+1], one scale per slot; absmax_x: float[1].  The message of round t lives in
+ * slot t mod (tau+1).  packed: M rows of ld_words words; delta: float[M];
  * nnz: int32[m*M] nonzero codes per round and worker, nullable.  ws: DQ_OP_VR_GRAD workspace. */
 typedef struct dq_run_state {
     float *x, *x_snap, *y, *xsum, *g_snap;
@@ -263,6 +268,7 @@ typedef struct dq_run_state {
     uint32_t *status;
     void *ws;
     int64_t ws_bytes;
+    int64_t xq_stride_words;
 } dq_run_state;
 
 /* Enqueues rounds t0 .. t0+rounds-1 of epoch `epoch` (0-based) of Alg. 1, 2 or 3: per round the
@@ -273,7 +279,8 @@ typedef struct dq_run_state {
  * Alg. 1/2).  The epoch prologue (dq_full_grad, dq_acc_mix / copy) and epilogue stay with the
  * caller.  worker_events (host array, nullable): 2*rounds hipEvent_t handles; for round k the
  * pair [2k], [2k+1] is recorded on `stream` right before and right after the kernel of the
- * worker step that streams the feature rows (its first kernel; for CSR its only one). */
+ * worker step that streams the feature rows (its first kernel; for CSR its only one; with
+ * tau > 0 the one of the first worker group). */
 int32_t dq_run_rounds(const dq_problem *prob /*host*/, const dq_run_config *cfg /*host*/, const dq_run_state *st /*host*/,
                       int64_t epoch, int64_t t0, int64_t rounds, float eta, float theta,
                       void **worker_events /*host*/, void *stream);

@@ -6,6 +6,10 @@ takes one proximal step (the paper applies gradients one at a time with bounded
 staleness; a round with zero staleness is this build's reading).  The iteration
 counter ``it = epoch_index * m + t`` addresses the random streams.
 
+Bounded delay (Assumption 3, Section 3.2) can be emulated: with ``tau > 0`` the M workers are split
+into tau+1 contiguous groups and group g computes its gradient on the model message of round
+t - g (of round 0 while t < g), i.e. on a model that is g rounds stale.
+
 ``b_x = 32`` / ``b = 32`` switch the corresponding quantization off (the message is the
 float32 vector, 32*d bits): with both off this is AsyFPG / Acc-AsyFPG, with only the model
 unquantized it is the gradient-quantized QSVRG arrangement of Section 5.1.
@@ -80,8 +84,13 @@ def worker_message(rp: RefProblem, q, x_snap, model_is_snapshot: bool, B: int, b
     return words, dlt, bits, alpha, beta, idx
 
 
+def worker_delay(w: int, M: int, tau: int) -> int:
+    """Staleness (in rounds) of worker w: tau+1 contiguous groups of workers, group g is g rounds behind."""
+    return (w * (tau + 1)) // M
+
+
 def run(prob, algo: str, M: int, B: int, b_x: int, b: int, m: int, S: int, lr: float, seed: int = 0,
-        x0: Optional[np.ndarray] = None, eval_objective: bool = True) -> Trace:
+        x0: Optional[np.ndarray] = None, eval_objective: bool = True, tau: int = 0) -> Trace:
     rp = RefProblem(prob)
     d = rp.d
     tr = Trace()
@@ -102,16 +111,18 @@ def run(prob, algo: str, M: int, B: int, b_x: int, b: int, m: int, S: int, lr: f
         if eval_objective:
             tr.objectives.append(objective(rp, x_snap))
         g_snap = full_grad(rp, x_snap)                          # global gradient   
+        history = []                                            # (q, flag) of the model messages of this epoch
         for t in range(m):
             it = e * m + t
             q, _, _, bits = model_message(x, x_snap, b_x, seed, it)
-            flag = bits == 1
+            history.append((q, bits == 1))
             tr.bits_down += bits
             codes = np.zeros((M, d), dtype=np.int8)
             grads = np.zeros((M, d), dtype=np.float32)
             deltas = np.zeros(M, dtype=np.float32)
             for w in range(M):
-                words, dlt, bits, _, _, _ = worker_message(rp, q, x_snap, flag, B, b, seed, it, w, sparse)
+                q_w, flag_w = history[max(0, t - worker_delay(w, M, tau))]       # x_{D(t)}: a delayed model
+                words, dlt, bits, _, _, _ = worker_message(rp, q_w, x_snap, flag_w, B, b, seed, it, w, sparse)
                 if b == 32:
                     grads[w] = words.view(np.float32)
                 else:

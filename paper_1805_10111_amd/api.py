@@ -48,14 +48,15 @@ class _Problem(C.Structure):
 
 class RunConfig(C.Structure):
     _fields_ = [("algo", C.c_int32), ("M", C.c_int64), ("B", C.c_int64), ("b_x", C.c_int32), ("b", C.c_int32),
-                ("m", C.c_int64), ("seed", C.c_uint64)]
+                ("m", C.c_int64), ("seed", C.c_uint64), ("tau", C.c_int32)]
 
 
 class RunState(C.Structure):
     _fields_ = [("x", C.c_void_p), ("x_snap", C.c_void_p), ("y", C.c_void_p), ("xsum", C.c_void_p),
                 ("g_snap", C.c_void_p), ("z_snap", C.c_void_p), ("xq", C.c_void_p), ("delta_x", C.c_void_p),
                 ("absmax_x", C.c_void_p), ("packed", C.c_void_p), ("ld_words", C.c_int64), ("delta", C.c_void_p),
-                ("nnz", C.c_void_p), ("status", C.c_void_p), ("ws", C.c_void_p), ("ws_bytes", C.c_int64)]
+                ("nnz", C.c_void_p), ("status", C.c_void_p), ("ws", C.c_void_p), ("ws_bytes", C.c_int64),
+                ("xq_stride_words", C.c_int64)]
 
 
 ALGO = {"asylpg": 0, "sparse": 1, "acc": 2}

@@ -22,41 +22,57 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
     }
     const bool acc = cfg->algo == DQ_ALGO_ACC;
     if (acc && (!st->y || !st->xsum)) return DQ_ERR_INVALID_ARG;
+    if (cfg->tau < 0 || cfg->tau >= cfg->M) return DQ_ERR_INVALID_ARG;
+    const int64_t slots = cfg->tau + 1;
+    const int64_t xq_words = cfg->b_x == 32 ? prob->d : dq::packed_words(prob->d, cfg->b_x);
+    if (slots > 1 && (st->xq_stride_words < xq_words || st->xq_stride_words % 4 != 0)) return DQ_ERR_INVALID_ARG;
     const float scale = 1.0f / static_cast<float>(cfg->M);
+    // the model equals the snapshot bit for bit at the first round of an epoch of Alg. 1/2 and of the
+    // first epoch of Alg. 3: flag-bit case of Section 4.1
+    const bool start_is_snapshot = !acc || epoch == 0;
     for (int64_t t = t0; t < t0 + rounds; ++t) {
         const uint32_t it = static_cast<uint32_t>(epoch * cfg->m + t);
-        // the model equals the snapshot bit for bit at the first round of an epoch of Alg. 1/2 and
-        // of the first epoch of Alg. 3: flag-bit case of Section 4.1
-        const int flag = t == 0 && (!acc || epoch == 0);
+        uint32_t *xq_now = st->xq + (t % slots) * st->xq_stride_words;
+        float *dx_now = st->delta_x + (t % slots);
         int32_t rc;
-        if (t == 0 && !flag) {
+        if (t == 0 && !start_is_snapshot) {
             // Alg. 3, later epochs: x_0 = snapshot + theta (y - snapshot) is quantized by the master
             if (cfg->b_x == 32) {
-                DQ_HIP_TRY(hipMemcpyAsync(st->xq, st->x, static_cast<size_t>(prob->d) * sizeof(float),
+                DQ_HIP_TRY(hipMemcpyAsync(xq_now, st->x, static_cast<size_t>(prob->d) * sizeof(float),
                                           hipMemcpyDeviceToDevice, as_stream(stream)));
             } else {
                 rc = dq_quantize_pack(st->x, prob->d, 1, prob->d, cfg->b_x, st->absmax_x, 0, cfg->seed, it, DQ_TAG_MODEL,
-                                      DQ_MASTER_ID, st->xq, dq::packed_words(prob->d, cfg->b_x), st->delta_x, st->status,
-                                      stream);
+                                      DQ_MASTER_ID, xq_now, xq_words, dx_now, st->status, stream);
                 if (rc != DQ_OK) return rc;
             }
         }
-        dq::WorkerArgs w{};
-        w.M = cfg->M; w.B = cfg->B; w.xq = st->xq; w.delta_x = st->delta_x; w.b_x = cfg->b_x;
-        w.model_is_snapshot = flag; w.x_snap = st->x_snap; w.z_snap = st->z_snap;
-        w.sparsify = cfg->algo == DQ_ALGO_SPARSE; w.b = cfg->b; w.seed = cfg->seed; w.iter = it; w.worker0 = 0u;
-        w.packed = st->packed; w.ld_words = st->ld_words; w.delta_out = st->delta;
-        w.nnz_out = st->nnz ? st->nnz + t * cfg->M : nullptr; w.status = st->status;
-        w.ws = st->ws; w.ws_bytes = st->ws_bytes;
-        if (worker_events) {
-            DQ_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(worker_events[2 * (t - t0)]), as_stream(stream)));
-            w.ev_after_stream = static_cast<hipEvent_t>(worker_events[2 * (t - t0) + 1]);
+        // worker side: group g of the workers is g rounds behind (g = 0 only when tau = 0)
+        for (int64_t g = 0; g < slots; ++g) {
+            const int64_t w_lo = dq::ceil_div(g * cfg->M, slots), w_hi = dq::ceil_div((g + 1) * cfg->M, slots);
+            if (w_hi <= w_lo) continue;
+            const int64_t tm = t - g > 0 ? t - g : 0;                  // round whose model message the group holds
+            dq::WorkerArgs w{};
+            w.M = w_hi - w_lo; w.B = cfg->B;
+            w.xq = st->xq + (tm % slots) * st->xq_stride_words; w.delta_x = st->delta_x + (tm % slots); w.b_x = cfg->b_x;
+            w.model_is_snapshot = tm == 0 && start_is_snapshot;
+            w.x_snap = st->x_snap; w.z_snap = st->z_snap;
+            w.sparsify = cfg->algo == DQ_ALGO_SPARSE; w.b = cfg->b; w.seed = cfg->seed; w.iter = it;
+            w.worker0 = static_cast<uint32_t>(w_lo);
+            w.packed = st->packed + w_lo * st->ld_words; w.ld_words = st->ld_words; w.delta_out = st->delta + w_lo;
+            w.nnz_out = st->nnz ? st->nnz + t * cfg->M + w_lo : nullptr; w.status = st->status;
+            w.ws = st->ws; w.ws_bytes = st->ws_bytes;
+            if (worker_events && g == 0) {
+                DQ_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(worker_events[2 * (t - t0)]), as_stream(stream)));
+                w.ev_after_stream = static_cast<hipEvent_t>(worker_events[2 * (t - t0) + 1]);
+            }
+            rc = dq::worker_step_impl(prob, w, stream);
+            if (rc != DQ_OK) return rc;
         }
-        rc = dq::worker_step_impl(prob, w, stream);
-        if (rc != DQ_OK) return rc;
+        // master side; the new model is the message of round t+1
         rc = dq_master_step(st->packed, st->ld_words, st->delta, cfg->M, cfg->b, scale, st->g_snap, st->x,
                             acc ? st->y : nullptr, st->x_snap, acc ? st->xsum : nullptr, eta, theta, prob->l1, prob->d,
-                            cfg->b_x, cfg->seed, it + 1u, st->xq, st->delta_x, st->absmax_x, st->status, stream);
+                            cfg->b_x, cfg->seed, it + 1u, st->xq + ((t + 1) % slots) * st->xq_stride_words,
+                            st->delta_x + ((t + 1) % slots), st->absmax_x, st->status, stream);
         if (rc != DQ_OK) return rc;
     }
     return DQ_OK;

@@ -28,10 +28,10 @@ class DoubleQuantTrainer:
     """Device-resident state of one run plus the per-epoch call sequence."""
 
     def __init__(self, prob: dq.DeviceProblem, algo: str, M: int, B: int, b_x: int, b: int, m: int, lr: float,
-                 seed: int = 0, x0: Optional[torch.Tensor] = None, cache_margins: bool = True):
+                 seed: int = 0, x0: Optional[torch.Tensor] = None, cache_margins: bool = True, tau: int = 0):
         assert algo in ("asylpg", "sparse", "acc")
         self.prob, self.algo, self.M, self.B, self.b_x, self.b, self.m = prob, algo, M, B, b_x, b, m
-        self.lr, self.seed = float(lr), int(seed)
+        self.lr, self.seed, self.tau = float(lr), int(seed), int(tau)
         d, n, dev = prob.d, prob.n, prob.y.device
         f32 = dict(dtype=torch.float32, device=dev)
         i32 = dict(dtype=torch.int32, device=dev)
@@ -43,8 +43,9 @@ class DoubleQuantTrainer:
         self.z_snap = torch.zeros(n, **f32) if cache_margins else None
         self.obj = torch.zeros(1, dtype=torch.float64, device=dev)
         self.xq_words = d if b_x == 32 else dq.packed_words(d, b_x)
-        self.xq = torch.zeros(self.xq_words + 4, **i32)
-        self.delta_x = torch.zeros(1, **f32)
+        self.xq_stride = (self.xq_words + 3) // 4 * 4
+        self.xq = torch.zeros((self.tau + 1) * self.xq_stride, **i32)     # ring of the last tau+1 model messages
+        self.delta_x = torch.zeros(self.tau + 1, **f32)
         self.absmax_x = torch.zeros(1, **f32)
         self.row_words = d if b == 32 else dq.packed_words(d, b)
         self.ld_words = (self.row_words + 3) // 4 * 4
@@ -59,12 +60,12 @@ class DoubleQuantTrainer:
         self.log = RunLog()
         self.mu_trace = []
         p = lambda t: None if t is None else t.data_ptr()
-        self.cfg = dq.RunConfig(algo=dq.ALGO[algo], M=M, B=B, b_x=b_x, b=b, m=m, seed=self.seed)
+        self.cfg = dq.RunConfig(algo=dq.ALGO[algo], M=M, B=B, b_x=b_x, b=b, m=m, seed=self.seed, tau=self.tau)
         self.state = dq.RunState(
             x=p(self.x), x_snap=p(self.x_snap), y=p(self.y), xsum=p(self.xsum), g_snap=p(self.g_snap),
             z_snap=p(self.z_snap), xq=p(self.xq), delta_x=p(self.delta_x), absmax_x=p(self.absmax_x),
             packed=p(self.packed), ld_words=self.ld_words, delta=p(self.delta), nnz=p(self.nnz),
-            status=p(self.status), ws=p(self.ws), ws_bytes=self.ws.numel() * 4)
+            status=p(self.status), ws=p(self.ws), ws_bytes=self.ws.numel() * 4, xq_stride_words=self.xq_stride)
 
     # -- one epoch ---------------------------------------------------------------------------
     def epoch_prologue(self) -> None:

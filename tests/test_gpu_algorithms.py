@@ -189,3 +189,34 @@ def test_mu_trace_follows_the_papers_observation(dq):
     mus = [r[2] / r[3] for r in tr.mu_trace if r[0] == 1 and r[3] > 0]
     assert all(np.isfinite(mus))
     assert mus[0] == max(mus) and mus[0] > 10 * mus[-1]
+
+
+@pytest.mark.parametrize("name,algo,tau,b_x,b", [("C1", "asylpg", 1, 8, 8), ("C1", "asylpg", 3, 8, 8), ("C1", "acc", 2, 8, 8),
+                                                 ("C1", "asylpg", 3, 32, 32), ("C2", "asylpg", 3, 8, 8), ("C3", "sparse", 5, 8, 4)])
+def test_bounded_delay_free_run(dq, name, algo, tau, b_x, b):
+    """Emulated staleness (Assumption 3): worker group g reads the model of g rounds ago."""
+    from paper_1805_10111_amd.driver import DoubleQuantTrainer
+    cfg = synth.CONFIGS[name]
+    p = synth.make_problem(cfg, n=1500) if cfg.csr else synth.make_problem(cfg, n=600, d=200)
+    m, S = 10, 2
+    tr = DoubleQuantTrainer(dq.DeviceProblem.from_host(p), algo, cfg.M, cfg.B, b_x, b, m, cfg.lr, seed=2, tau=tau)
+    log = tr.run(S)
+    ref = alg.run(p, algo, cfg.M, cfg.B, b_x, b, m, S, cfg.lr, seed=2, tau=tau)
+    sync = alg.run(p, algo, cfg.M, cfg.B, b_x, b, m, S, cfg.lr, seed=2)
+    for a, r in zip(log.objectives, ref.objectives):
+        assert abs(a - r) <= TOL * abs(r)
+    rel = np.abs(host(tr.x_snap) - ref.x_snap).max() / np.abs(ref.x_snap).max()
+    assert rel < 2e-3, rel
+    # the delay is visible: the delayed trajectory differs from the synchronous one by more than that
+    assert np.abs(ref.x_snap - sync.x_snap).max() / np.abs(ref.x_snap).max() > 5 * max(rel, 1e-6)
+    assert log.bits_down == ref.bits_down
+
+
+def test_delay_argument_checks(dq):
+    from paper_1805_10111_amd.driver import DoubleQuantTrainer
+    cfg = synth.CONFIGS["C1"]
+    p = synth.make_problem(cfg, n=100, d=64)
+    tr = DoubleQuantTrainer(dq.DeviceProblem.from_host(p), "asylpg", cfg.M, cfg.B, 8, 8, 4, cfg.lr, tau=cfg.M)
+    with pytest.raises(dq.DqError) as e:          # at most one delay group per worker
+        tr.run_epoch()
+    assert e.value.code == dq.ERR_INVALID_ARG
