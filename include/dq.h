@@ -123,6 +123,20 @@ int32_t dq_pack(const int8_t *codes, int64_t ld_codes, int64_t d, int64_t M, int
 int32_t dq_unpack(const uint32_t *packed, int64_t ld_words, int64_t d, int64_t M, int32_t b,
                   int8_t *codes_out, int64_t ld_codes, void *stream);
 
+/* Sparse message of Section 4.2 (after sparsification most codes are zero): the scale plus,
+ * per NONZERO coordinate in ascending order, an entry of ceil(log2 d) position bits (low) and
+ * the b-bit two's-complement code (high), entries back to back, low bits first across 32-bit
+ * words: 32 + nnz*(ceil(log2 d) + b) bits in all.  dq_sparse_stream_words(d, b) is the row
+ * capacity (every coordinate nonzero).  dq_sparse_encode turns M rows of dense packed codes
+ * into M streams (stride ld_stream >= capacity, words past the used ones zero) and writes
+ * nnz_out[M]; dq_sparse_decode is the inverse (packed_out rows fully rewritten).  b in {2,4,8};
+ * streams of more than 36864 words (144 KB) are DQ_ERR_UNSUPPORTED. */
+int64_t dq_sparse_stream_words(int64_t d, int32_t b);
+int32_t dq_sparse_encode(const uint32_t *packed, int64_t ld_words, int64_t d, int64_t M, int32_t b,
+                         uint32_t *stream_out, int64_t ld_stream, int32_t *nnz_out, void *stream);
+int32_t dq_sparse_decode(const uint32_t *stream_in, int64_t ld_stream, const int32_t *nnz, int64_t d, int64_t M,
+                         int32_t b, uint32_t *packed_out, int64_t ld_words, void *stream);
+
 /* dq_quantize followed by dq_pack in one pass (same bits as the two calls).
  * v 16-byte aligned and ld % 4 == 0 select the 128-bit path; otherwise a
  * scalar path is used.  packed_out rows are 16-byte aligned if ld_words % 4 == 0. */

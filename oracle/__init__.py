@@ -106,6 +106,12 @@ def lib() -> C.CDLL:
         _lib.ref_expected_sq_error.argtypes = [C.c_void_p, C.c_int64, C.c_int]
         _lib.ref_sq_distance.restype = C.c_double
         _lib.ref_sq_distance.argtypes = [C.c_void_p, C.c_void_p, C.c_int64]
+        _lib.ref_position_bits.restype = C.c_int
+        _lib.ref_position_bits.argtypes = [C.c_int64]
+        _lib.ref_sparse_encode.restype = C.c_int64
+        _lib.ref_sparse_encode.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_int64]
+        _lib.ref_sparse_decode.restype = None
+        _lib.ref_sparse_decode.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_void_p]
         _lib.ref_philox4x32_10.restype = None
         _lib.ref_philox4x32_10.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     return _lib
@@ -335,3 +341,28 @@ def smallest_bx(x, x_snap, mu: float, candidates=(2, 4, 8)) -> int:
         if expected_sq_error(x, b) <= mu * r:
             return b
     return 32
+
+
+def position_bits(d: int) -> int:
+    return int(lib().ref_position_bits(d))
+
+
+def sparse_stream_words(d: int, b: int) -> int:
+    """Words that hold the sparse message when every coordinate is nonzero."""
+    return (d * (position_bits(d) + b) + 31) // 32
+
+
+def sparse_encode(codes, b: int):
+    """Returns (stream words uint32[capacity], nnz): position+value per nonzero code (Section 4.2)."""
+    codes = np.ascontiguousarray(codes, dtype=np.int8)
+    cap = sparse_stream_words(codes.size, b)
+    words = np.zeros(cap, dtype=np.uint32)
+    nnz = lib().ref_sparse_encode(_p(codes), codes.size, b, _p(words), cap)
+    return words, int(nnz)
+
+
+def sparse_decode(words, nnz: int, d: int, b: int) -> np.ndarray:
+    words = np.ascontiguousarray(words, dtype=np.uint32)
+    codes = np.zeros(d, dtype=np.int8)
+    lib().ref_sparse_decode(_p(words), nnz, d, b, _p(codes))
+    return codes

@@ -203,6 +203,50 @@ void ref_unpack(const uint32_t *words, int64_t d, int b, int8_t *codes)
     }
 }
 
+/* Section 4.2: a sparsified message lists only the nonzero coordinates, each as its
+ * position (ceil(log2 d) bits) followed by its b-bit value.  Entry e occupies bits
+ * [e*E, (e+1)*E) of the stream, E = posbits + b, low bits first across 32-bit words;
+ * position in the low posbits bits of the entry, two's-complement code above it. */
+int ref_position_bits(int64_t d)
+{
+    int bits = 0;
+    while (((int64_t)1 << bits) < d) ++bits;        /* ceil(log2 d); the paper's logarithm is base 2 */
+    return bits;
+}
+
+int64_t ref_sparse_encode(const int8_t *codes, int64_t d, int b, uint32_t *words, int64_t capacity_words)
+{
+    const int pb = ref_position_bits(d), E = pb + b;
+    int64_t nnz = 0;
+    for (int64_t w = 0; w < capacity_words; ++w) words[w] = 0;
+    for (int64_t i = 0; i < d; ++i) {
+        if (codes[i] == 0) continue;
+        uint64_t entry = (uint64_t)i | ((uint64_t)((uint32_t)(int32_t)codes[i] & ((1u << b) - 1u)) << pb);
+        int64_t bit = nnz * E;
+        for (int k = 0; k < E; ++k, ++bit)
+            if ((entry >> k) & 1u) words[bit / 32] |= 1u << (bit % 32);
+        ++nnz;
+    }
+    return nnz;
+}
+
+void ref_sparse_decode(const uint32_t *words, int64_t nnz, int64_t d, int b, int8_t *codes)
+{
+    const int pb = ref_position_bits(d), E = pb + b;
+    for (int64_t i = 0; i < d; ++i) codes[i] = 0;
+    for (int64_t e = 0; e < nnz; ++e) {
+        uint64_t entry = 0;
+        int64_t bit = e * E;
+        for (int k = 0; k < E; ++k, ++bit)
+            entry |= (uint64_t)((words[bit / 32] >> (bit % 32)) & 1u) << k;
+        int64_t pos = (int64_t)(entry & (((uint64_t)1 << pb) - 1));
+        uint32_t f = (uint32_t)(entry >> pb) & ((1u << b) - 1u);
+        int k = (int)f;
+        if (f >> (b - 1)) k -= (1 << b);
+        codes[pos] = (int8_t)k;
+    }
+}
+
 /* ------------------------------------------------------------------------- */
 /* Problem (1): P(x) = f(x) + h(x), f = (1/n) sum f_i,                        */
 /*   f_i(x) = log(1 + exp(-y_i a_i.x)) + (l2/2)||x||^2   (smooth part)        */

@@ -85,6 +85,9 @@ _SIGS = {
                               _i32, _u64, _u32, _vp, _vp, _vp, _vp, _vp]),
     "dq_acc_mix": (_i32, [_vp, _vp, _f32, _i64, _vp, _vp]),
     "dq_acc_snapshot": (_i32, [_vp, _i64, _i64, _vp, _vp]),
+    "dq_sparse_stream_words": (_i64, [_i64, _i32]),
+    "dq_sparse_encode": (_i32, [_vp, _i64, _i64, _i64, _i32, _vp, _i64, _vp, _vp]),
+    "dq_sparse_decode": (_i32, [_vp, _i64, _vp, _i64, _i64, _i32, _vp, _i64, _vp]),
     "dq_mu_terms": (_i32, [_vp, _vp, _i64, _i32, _vp, _vp]),
     "dq_run_rounds": (_i32, [_vp, _vp, _vp, _i64, _i64, _i64, _f32, _f32, _vp, _vp]),
 }
@@ -323,6 +326,25 @@ def dq_acc_snapshot(xsum, m, x_snap_out) -> None:
                                                    _ptr(x_snap_out, torch.float32, "x_snap_out"), _stream()))
 
 
+def dq_sparse_stream_words(d: int, b: int) -> int:
+    return int(_lib.dq_sparse_stream_words(d, b))
+
+
+def dq_sparse_encode(packed, d, b, stream_out, nnz_out) -> None:
+    M = _rows(packed)
+    _check("dq_sparse_encode", _lib.dq_sparse_encode(_ptr(packed, torch.int32, "packed"), _row_stride(packed), d, M, b,
+                                                     _ptr(stream_out, torch.int32, "stream_out"), _row_stride(stream_out),
+                                                     _ptr(nnz_out, torch.int32, "nnz_out"), _stream()))
+
+
+def dq_sparse_decode(stream_in, nnz, d, b, packed_out) -> None:
+    M = _rows(stream_in)
+    _check("dq_sparse_decode", _lib.dq_sparse_decode(_ptr(stream_in, torch.int32, "stream_in"), _row_stride(stream_in),
+                                                     _ptr(nnz, torch.int32, "nnz"), d, M, b,
+                                                     _ptr(packed_out, torch.int32, "packed_out"), _row_stride(packed_out),
+                                                     _stream()))
+
+
 def dq_mu_terms(x, x_snap, b, out) -> None:
     _check("dq_mu_terms", _lib.dq_mu_terms(_ptr(x, torch.float32, "x"), _ptr(x_snap, torch.float32, "x_snap"), x.numel(), b,
                                            _ptr(out, torch.float64, "out"), _stream()))
@@ -346,5 +368,5 @@ __all__ = [
     "dq_version", "dq_last_device_error", "dq_workspace_bytes", "dq_workspace_init", "new_workspace", "dq_absmax", "dq_quantize", "dq_dequantize",
     "dq_pack", "dq_unpack", "dq_quantize_pack", "dq_unpack_dequant_sum", "dq_sample_indices", "dq_full_grad",
     "dq_vr_grad", "dq_sparsify", "dq_worker_step", "dq_master_step", "dq_acc_mix", "dq_acc_snapshot",
-    "dq_run_rounds", "dq_mu_terms", "RunConfig", "RunState", "ALGO",
+    "dq_run_rounds", "dq_mu_terms", "dq_sparse_stream_words", "dq_sparse_encode", "dq_sparse_decode", "RunConfig", "RunState", "ALGO",
 ]
