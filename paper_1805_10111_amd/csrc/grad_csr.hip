@@ -24,9 +24,10 @@ namespace dq {
 
 constexpr int kCsrThreads = 1024;
 constexpr int kCsrWaves = kCsrThreads / kWave;
+constexpr int kFlight = 4;                       // rows a wavefront reduces at the same time
 constexpr int kCsrMaxRows = 256;                 // rows a block handles per pass (LDS metadata)
 constexpr int64_t kLdsBudget = 152 * 1024;       // of the 160 KB per compute unit
-constexpr int64_t kCsrFixedLds = 12 * 1024;      // static arrays below, rounded up
+constexpr int64_t kCsrFixedLds = 10 * 1024;      // static arrays below, rounded up
 
 struct CsrView {
     const int64_t *indptr;
@@ -41,59 +42,187 @@ struct RowMeta {
     int row[kCsrMaxRows];        // sample index, -1 = ignored
     int64_t start[kCsrMaxRows];  // first entry
     int len[kCsrMaxRows];
-    int off[kCsrMaxRows];        // offset in the staging buffer (rows of the current group)
+    int pre[kCsrMaxRows + 1];    // exclusive prefix sum of len
     float coef[kCsrMaxRows];
+    float z[kCsrMaxRows];        // cached margin at the snapshot (worker step only)
 };
 
-// Steps 2 and 3 for rows [0, nrows) described by `meta`, accumulating into alpha (LDS).
-// stage_col / stage_val hold `cap` entries.  Rows longer than `cap` are read from memory.
-__device__ __forceinline__ void csr_scatter_rows(const CsrView &A, RowMeta &meta, int nrows, float *alpha,
-                                                 int *stage_col, float *stage_val, int cap, int *sh_ctl)
+// Fills meta.pre with the exclusive prefix sums of meta.len[0..nrows) (pre[nrows] = total).
+// The first wavefront scans the lengths, kCsrMaxRows/64 consecutive rows per lane; all threads of
+// the block must call it (barriers before and after).
+__device__ __forceinline__ void csr_prefix_lengths(RowMeta &meta, int nrows)
+{
+    constexpr int kPer = kCsrMaxRows / kWave;
+    __syncthreads();
+    if (threadIdx.x < kWave) {
+        const int lane = threadIdx.x;
+        int v[kPer], sum = 0;
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int r = lane * kPer + u;
+            v[u] = r < nrows ? meta.len[r] : 0;
+            sum += v[u];
+        }
+        int incl = sum;                                  // inclusive scan of the lane sums
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int up = __shfl_up(incl, off, kWave);
+            if (lane >= off) incl += up;
+        }
+        int run = incl - sum;
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            meta.pre[lane * kPer + u] = run;
+            run += v[u];
+        }
+        if (lane == kWave - 1) meta.pre[kCsrMaxRows] = run;
+    }
+    __syncthreads();
+}
+
+// Steps 1-3 for rows [0, nrows) described by `meta`, accumulating into alpha (LDS).
+// The rows are taken in groups that fit the staging buffer (`stage`, `cap` (column, value) entries):
+//   stage  : the group's (column, value) pairs are copied to LDS, one wavefront per row;
+//   margins: one wavefront per row (two rows in flight) reduces sum_k value_k * vec(column_k), where
+//            vec(c) returns {first, second} operands gathered from memory; lane 0 hands the two sums to
+//            coef_of(row, first_sum, second_sum), which returns the row's coefficient;
+//   scatter: each wavefront owns a contiguous range of columns and walks the staged rows in order,
+//            adding coefficient*value for the entries that fall in its range.
+// A row longer than `cap` is handled alone, straight from memory.
+template <bool SECOND, typename VecFn, typename CoefFn>
+__device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta, int nrows, float *alpha,
+                                                 int2 *stage, int cap, int *sh_ctl, VecFn vec,
+                                                 CoefFn coef_of)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int64_t span = (A.d + kCsrWaves - 1) / kCsrWaves;
     const int64_t lo = wave * span, hi = min(A.d, lo + span);
     int g0 = 0;
     while (g0 < nrows) {
-        // group of consecutive rows that fits the staging buffer (thread 0 decides, all follow)
+        // group of consecutive rows that fits the staging buffer: rows g0..g1-1 with
+        // pre[g1] - pre[g0] <= cap; a first row longer than cap is taken alone, unstaged
         if (threadIdx.x == 0) {
-            int g = g0, off = 0, direct = 0;
-            if (meta.len[g0] > cap) {
-                g = g0 + 1;
-                direct = 1;
-            } else {
-                while (g < nrows && meta.len[g] <= cap && off + meta.len[g] <= cap) {
-                    meta.off[g] = off;
-                    off += meta.len[g];
-                    ++g;
-                }
-            }
-            sh_ctl[0] = g;
-            sh_ctl[1] = direct;
+            sh_ctl[0] = nrows;
+            sh_ctl[1] = meta.len[g0] > cap;
         }
+        __syncthreads();
+        const int base = meta.pre[g0];
+        if (static_cast<int>(threadIdx.x) >= g0 && static_cast<int>(threadIdx.x) < nrows &&
+            meta.pre[threadIdx.x + 1] - base > cap)
+            atomicMin(&sh_ctl[0], max(static_cast<int>(threadIdx.x), g0 + 1));
         __syncthreads();
         const int g1 = sh_ctl[0];
         const bool direct = sh_ctl[1] != 0;
         if (!direct) {
-            for (int r = g0 + wave; r < g1; r += kCsrWaves) {          // stage: one wave per row
-                const float cf = meta.coef[r];
-                const int64_t s = meta.start[r];
-                for (int k = lane; k < meta.len[r]; k += kWave) {
-                    stage_col[meta.off[r] + k] = A.indices[s + k];
-                    stage_val[meta.off[r] + k] = cf * A.values[s + k];
+            // ---- stage: flat copy of the group's entries; the row of an entry by bisection on pre[]
+            const int total = meta.pre[g1] - base;
+            for (int p0 = threadIdx.x; p0 < total; p0 += 4 * kCsrThreads) {     // four entries per thread in flight
+                int64_t src[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int p = p0 + u * kCsrThreads;
+                    int lo_r = g0, hi_r = g1;                       // pre[lo_r] - base <= p < pre[hi_r] - base
+                    while (hi_r - lo_r > 1) {
+                        const int mid = (lo_r + hi_r) >> 1;
+                        if (meta.pre[mid] - base <= p) lo_r = mid; else hi_r = mid;
+                    }
+                    src[u] = p < total ? meta.start[lo_r] + (p - (meta.pre[lo_r] - base)) : -1;
                 }
+                int2 e[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (src[u] >= 0) e[u] = make_int2(A.indices[src[u]], __float_as_int(A.values[src[u]]));
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    if (src[u] >= 0) stage[p0 + u * kCsrThreads] = e[u];
             }
             __syncthreads();
-            for (int r = g0; r < g1; ++r) {                              // scatter: rows in order
-                const int base = meta.off[r];
-                for (int k = lane; k < meta.len[r]; k += kWave) {
-                    const int c = stage_col[base + k];
-                    if (c >= lo && c < hi) alpha[c] += stage_val[base + k];
+            // ---- margins and coefficients: four rows per wavefront in flight; lane u evaluates row u's scalar
+            for (int r = g0 + wave; r < g1; r += kFlight * kCsrWaves) {
+                int len[kFlight], off[kFlight], maxlen = 0;
+                float sa[kFlight], sb[kFlight];
+#pragma unroll
+                for (int u = 0; u < kFlight; ++u) {
+                    const int ru = r + u * kCsrWaves;
+                    len[u] = ru < g1 ? meta.len[ru] : 0;
+                    off[u] = ru < g1 ? meta.pre[ru] - base : 0;
+                    maxlen = max(maxlen, len[u]);
+                    sa[u] = sb[u] = 0.0f;
+                }
+                for (int k = lane; k < maxlen; k += kWave) {
+                    int2 e[kFlight];
+                    float2 f[kFlight];
+#pragma unroll
+                    for (int u = 0; u < kFlight; ++u) e[u] = k < len[u] ? stage[off[u] + k] : make_int2(0, 0);
+#pragma unroll
+                    for (int u = 0; u < kFlight; ++u) f[u] = vec(e[u].x);
+#pragma unroll
+                    for (int u = 0; u < kFlight; ++u) {
+                        sa[u] = fmaf(__int_as_float(e[u].y), f[u].x, sa[u]);
+                        if (SECOND) sb[u] = fmaf(__int_as_float(e[u].y), f[u].y, sb[u]);
+                    }
+                }
+                float mine_a = 0.0f, mine_b = 0.0f;
+#pragma unroll
+                for (int u = 0; u < kFlight; ++u) {
+                    const float ta = wave_sum_f32(sa[u]);
+                    const float tb = SECOND ? wave_sum_f32(sb[u]) : 0.0f;
+                    if (lane == u) {
+                        mine_a = ta;
+                        mine_b = tb;
+                    }
+                }
+                const int rl = r + lane * kCsrWaves;
+                if (lane < kFlight && rl < g1) meta.coef[rl] = coef_of(rl, mine_a, mine_b);
+            }
+            __syncthreads();
+            // ---- scatter: rows in order.  Lane j of every wavefront keeps the length, staging offset and
+            //      coefficient of row w0+j in registers; each step broadcasts one row's triple from there, so
+            //      the only LDS traffic of a step is the (prefetched) entry read and the add of owned columns.
+            for (int w0 = g0; w0 < g1; w0 += kWave) {
+                const int cnt = min(kWave, g1 - w0);
+                int my_len = 0, my_off = 0, my_cf = 0;
+                if (lane < cnt) {
+                    my_len = meta.len[w0 + lane];
+                    my_off = meta.pre[w0 + lane] - base;
+                    my_cf = __float_as_int(meta.coef[w0 + lane]);
+                }
+                int len_n = __builtin_amdgcn_readlane(my_len, 0), off_n = __builtin_amdgcn_readlane(my_off, 0);
+                int2 en = make_int2(-1, 0);
+                if (lane < len_n) en = stage[off_n + lane];
+                for (int j = 0; j < cnt; ++j) {
+                    const int len_c = len_n, off_c = off_n;
+                    const int2 ec = en;
+                    const float cf = __int_as_float(__builtin_amdgcn_readlane(my_cf, j));
+                    en = make_int2(-1, 0);
+                    if (j + 1 < cnt) {
+                        len_n = __builtin_amdgcn_readlane(my_len, j + 1);
+                        off_n = __builtin_amdgcn_readlane(my_off, j + 1);
+                        if (lane < len_n) en = stage[off_n + lane];
+                    }
+                    if (ec.x >= lo && ec.x < hi) alpha[ec.x] += cf * __int_as_float(ec.y);
+                    for (int k = lane + kWave; k < len_c; k += kWave) {
+                        const int2 ek = stage[off_c + k];
+                        if (ek.x >= lo && ek.x < hi) alpha[ek.x] += cf * __int_as_float(ek.y);
+                    }
                 }
             }
         } else {
-            const float cf = meta.coef[g0];
+            // ---- one very long row, straight from memory (every wavefront computes the same sums)
             const int64_t s = meta.start[g0];
+            float a1 = 0.0f, b1 = 0.0f;
+            for (int k = lane; k < meta.len[g0]; k += kWave) {
+                const float2 f = vec(A.indices[s + k]);
+                const float v = A.values[s + k];
+                a1 = fmaf(v, f.x, a1);
+                if (SECOND) b1 = fmaf(v, f.y, b1);
+            }
+            a1 = wave_sum_f32(a1);
+            if (SECOND) b1 = wave_sum_f32(b1);
+            __syncthreads();
+            if (threadIdx.x == 0) meta.coef[g0] = coef_of(g0, a1, b1);
+            __syncthreads();
+            const float cf = meta.coef[g0];
             for (int k = lane; k < meta.len[g0]; k += kWave) {
                 const int c = A.indices[s + k];
                 if (c >= lo && c < hi) alpha[c] += cf * A.values[s + k];
@@ -123,7 +252,7 @@ struct CsrWorkerArgs {
 
 __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorkerArgs a)
 {
-    extern __shared__ float lds[];
+    extern __shared__ __align__(16) float lds[];
     __shared__ RowMeta meta;
     __shared__ float sh_y[kCsrMaxRows];
     __shared__ uint32_t su[kCsrWaves];
@@ -132,17 +261,36 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     __shared__ int sh_ctl[2];
     const int64_t d = a.A.d;
     float *alpha = lds;
-    int *stage_col = reinterpret_cast<int *>(lds + ((d + 3) / 4) * 4);
-    float *stage_val = reinterpret_cast<float *>(stage_col + a.cap);
+    int2 *stage = reinterpret_cast<int2 *>(lds + ((d + 3) / 4) * 4);
 
     const int m = blockIdx.x;
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
 
-    // alpha starts as the dense part  l2*(q - snapshot)
-    for (int64_t j = threadIdx.x; j < d; j += kCsrThreads) alpha[j] = a.l2 * (model_value(msg, j) - a.x_snap[j]);
+    // alpha starts as the dense part  l2*(q - snapshot); four coordinates per thread and step
+    for (int64_t j = 4ll * threadIdx.x; j < d; j += 4ll * kCsrThreads) {
+        if (j + 3 < d && a.b_x == 8) {
+            const float4 xs = *reinterpret_cast<const float4 *>(a.x_snap + j);
+            const uint32_t w = a.xq[j >> 2];
+            alpha[j + 0] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 0, 8)) - xs.x);
+            alpha[j + 1] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 8, 8)) - xs.y);
+            alpha[j + 2] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 16, 8)) - xs.z);
+            alpha[j + 3] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 24, 8)) - xs.w);
+        } else {
+            for (int64_t e = j; e < min(d, j + 4); ++e) alpha[e] = a.l2 * (model_value(msg, e) - a.x_snap[e]);
+        }
+    }
 
     const float fB = static_cast<float>(a.B);
+    const bool have_z = a.z_snap != nullptr;
+    auto vec = [&](int c) {
+        const float xc = a.x_snap[c];
+        return make_float2(model_value(msg, c) - xc, xc);
+    };
+    auto coef_of = [&](int r, float dz, float zs) {
+        if (meta.row[r] < 0) return 0.0f;
+        if (have_z) zs = meta.z[r];
+        return vr_slope_diff(sh_y[r], zs, dz) / fB;
+    };
     for (int r0 = 0; r0 < a.B; r0 += kCsrMaxRows) {                     // passes of at most kCsrMaxRows rows
         const int nrows = min(kCsrMaxRows, a.B - r0);
         if (static_cast<int>(threadIdx.x) < nrows) {
@@ -162,33 +310,11 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
             meta.start[threadIdx.x] = s;
             meta.len[threadIdx.x] = ok ? static_cast<int>(a.A.indptr[i + 1] - s) : 0;
             sh_y[threadIdx.x] = ok ? a.A.y[i] : 1.0f;
+            meta.z[threadIdx.x] = (ok && have_z) ? a.z_snap[i] : 0.0f;
         }
-        __syncthreads();
-        // 1. margins and coefficients: one wave per row
-        for (int r = wave; r < nrows; r += kCsrWaves) {
-            const int64_t s = meta.start[r];
-            float dz = 0.0f, zs = 0.0f;
-            for (int k = lane; k < meta.len[r]; k += kWave) {
-                const int c = a.A.indices[s + k];
-                const float v = a.A.values[s + k];
-                const float xc = a.x_snap[c];
-                dz = fmaf(v, model_value(msg, c) - xc, dz);
-                if (!a.z_snap) zs = fmaf(v, xc, zs);
-            }
-            dz = wave_sum_f32(dz);
-            if (!a.z_snap) zs = wave_sum_f32(zs);
-            if (lane == 0) {
-                float cf = 0.0f;
-                if (meta.row[r] >= 0) {
-                    if (a.z_snap) zs = a.z_snap[meta.row[r]];
-                    cf = vr_slope_diff(sh_y[r], zs, dz) / fB;
-                }
-                meta.coef[r] = cf;
-            }
-        }
-        __syncthreads();
-        // 2.-3. staged, ordered scatter into alpha
-        csr_scatter_rows(a.A, meta, nrows, alpha, stage_col, stage_val, a.cap, sh_ctl);
+        csr_prefix_lengths(meta, nrows);
+        if (have_z) csr_process_rows<false>(a.A, meta, nrows, alpha, stage, a.cap, sh_ctl, vec, coef_of);
+        else csr_process_rows<true>(a.A, meta, nrows, alpha, stage, a.cap, sh_ctl, vec, coef_of);
     }
 
     // 4. outputs
@@ -227,20 +353,19 @@ __global__ __launch_bounds__(kCsrThreads) void csr_full_partial_kernel(
     const CsrView A, const float *__restrict__ x, float *__restrict__ z_out, float *__restrict__ partial, int64_t ldp,
     double *__restrict__ loss_partial, int cap)
 {
-    extern __shared__ float lds[];
+    extern __shared__ __align__(16) float lds[];
     __shared__ RowMeta meta;
     __shared__ double sh_loss[kCsrWaves];
     __shared__ int sh_ctl[2];
     const int64_t d = A.d;
     float *acc = lds;
-    int *stage_col = reinterpret_cast<int *>(lds + ((d + 3) / 4) * 4);
-    float *stage_val = reinterpret_cast<float *>(stage_col + cap);
+    int2 *stage = reinterpret_cast<int2 *>(lds + ((d + 3) / 4) * 4);
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     for (int64_t j = threadIdx.x; j < ldp; j += kCsrThreads) acc[j] = 0.0f;
     const int64_t per = (A.n + gridDim.x - 1) / gridDim.x;
     const int64_t i0 = blockIdx.x * per, i1 = min(A.n, i0 + per);
     const float fn = static_cast<float>(A.n);
-    double loss = 0.0;                                   // lane 0 of each wave
+    double loss = 0.0;                                   // the lanes that evaluate row scalars add to theirs
     for (int64_t ib = i0; ib < i1; ib += kCsrMaxRows) {
         const int nrows = static_cast<int>(min<int64_t>(kCsrMaxRows, i1 - ib));
         if (static_cast<int>(threadIdx.x) < nrows) {
@@ -250,24 +375,20 @@ __global__ __launch_bounds__(kCsrThreads) void csr_full_partial_kernel(
             meta.start[threadIdx.x] = s;
             meta.len[threadIdx.x] = static_cast<int>(A.indptr[i + 1] - s);
         }
-        __syncthreads();
-        for (int r = wave; r < nrows; r += kCsrWaves) {
-            const int64_t s = meta.start[r];
-            float z = 0.0f;
-            for (int k = lane; k < meta.len[r]; k += kWave) z = fmaf(A.values[s + k], x[A.indices[s + k]], z);
-            z = wave_sum_f32(z);
-            if (lane == 0) {
-                const int64_t i = ib + r;
-                const float y = A.y[i];
-                if (z_out) z_out[i] = z;
-                loss += static_cast<double>(logistic_loss(y * z));
-                meta.coef[r] = logistic_slope(y, z) / fn;
-            }
-        }
-        __syncthreads();
-        csr_scatter_rows(A, meta, nrows, acc, stage_col, stage_val, cap, sh_ctl);
+        csr_prefix_lengths(meta, nrows);
+        const int64_t ib_now = ib;
+        auto vec = [&](int c) { return make_float2(x[c], 0.0f); };
+        auto coef_of = [&](int r, float z, float) {
+            const int64_t i = ib_now + r;
+            const float y = A.y[i];
+            if (z_out) z_out[i] = z;
+            loss += static_cast<double>(logistic_loss(y * z));
+            return logistic_slope(y, z) / fn;
+        };
+        csr_process_rows<false>(A, meta, nrows, acc, stage, cap, sh_ctl, vec, coef_of);
     }
     for (int64_t j = threadIdx.x; j < ldp; j += kCsrThreads) partial[static_cast<int64_t>(blockIdx.x) * ldp + j] = acc[j];
+    loss = wave_sum_f64(loss);
     if (lane == 0) sh_loss[wave] = loss;
     __syncthreads();
     if (threadIdx.x == 0) {

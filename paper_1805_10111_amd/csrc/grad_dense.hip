@@ -227,7 +227,7 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
     __shared__ float sh_red[2 * kRowWaves * R * 2];
     __shared__ int sh_row[kMaxRowsPerBlock];
     __shared__ float sh_y[kMaxRowsPerBlock], sh_z[kMaxRowsPerBlock];
-    __shared__ float sh_alpha[4 * kRowThreads * NC];
+    __shared__ __align__(16) float sh_alpha[4 * kRowThreads * NC];
     __shared__ uint32_t su[kRowWaves];
     __shared__ int si[kRowWaves];
     __shared__ double sd[kRowWaves];
@@ -330,7 +330,7 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
 constexpr int kFinishThreads = 1024;
 __global__ __launch_bounds__(kFinishThreads) void vr_dense_finish_kernel(const VrDenseArgs a)
 {
-    extern __shared__ float sh_alpha_dyn[];
+    extern __shared__ __align__(16) float sh_alpha_dyn[];
     __shared__ uint32_t su[kFinishThreads / kWave];
     __shared__ int si[kFinishThreads / kWave];
     __shared__ double sd[kFinishThreads / kWave];
