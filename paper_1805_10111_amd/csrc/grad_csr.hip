@@ -24,6 +24,9 @@ namespace dq {
 
 constexpr int kCsrThreads = 1024;
 constexpr int kCsrWaves = kCsrThreads / kWave;
+constexpr int kScatterWaves = 4;                 // wavefronts that add rows into the LDS vector (one per SIMD)
+constexpr int kColBits = 20;                     // staged entries carry column | row << kColBits
+constexpr int kColMask = (1 << kColBits) - 1;
 constexpr int kFlight = 4;                       // rows a wavefront reduces at the same time
 constexpr int kCsrMaxRows = 256;                 // rows a block handles per pass (LDS metadata)
 constexpr int64_t kLdsBudget = 152 * 1024;       // of the 160 KB per compute unit
@@ -95,8 +98,8 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
                                                  CoefFn coef_of)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int64_t span = (A.d + kCsrWaves - 1) / kCsrWaves;
-    const int64_t lo = wave * span, hi = min(A.d, lo + span);
+    const int span = static_cast<int>((A.d + kScatterWaves - 1) / kScatterWaves);
+    const int lo = wave * span, hi = wave < kScatterWaves ? min(static_cast<int>(A.d), lo + span) : lo;
     int g0 = 0;
     while (g0 < nrows) {
         // group of consecutive rows that fits the staging buffer: rows g0..g1-1 with
@@ -118,6 +121,7 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
             const int total = meta.pre[g1] - base;
             for (int p0 = threadIdx.x; p0 < total; p0 += 4 * kCsrThreads) {     // four entries per thread in flight
                 int64_t src[4];
+                int tag[4];                                         // row number, shifted above the column bits
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const int p = p0 + u * kCsrThreads;
@@ -127,11 +131,12 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
                         if (meta.pre[mid] - base <= p) lo_r = mid; else hi_r = mid;
                     }
                     src[u] = p < total ? meta.start[lo_r] + (p - (meta.pre[lo_r] - base)) : -1;
+                    tag[u] = lo_r << kColBits;
                 }
                 int2 e[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
-                    if (src[u] >= 0) e[u] = make_int2(A.indices[src[u]], __float_as_int(A.values[src[u]]));
+                    if (src[u] >= 0) e[u] = make_int2(A.indices[src[u]] | tag[u], __float_as_int(A.values[src[u]]));
 #pragma unroll
                 for (int u = 0; u < 4; ++u)
                     if (src[u] >= 0) stage[p0 + u * kCsrThreads] = e[u];
@@ -155,7 +160,7 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
 #pragma unroll
                     for (int u = 0; u < kFlight; ++u) e[u] = k < len[u] ? stage[off[u] + k] : make_int2(0, 0);
 #pragma unroll
-                    for (int u = 0; u < kFlight; ++u) f[u] = vec(e[u].x);
+                    for (int u = 0; u < kFlight; ++u) f[u] = vec(e[u].x & kColMask);
 #pragma unroll
                     for (int u = 0; u < kFlight; ++u) {
                         sa[u] = fmaf(__int_as_float(e[u].y), f[u].x, sa[u]);
@@ -176,34 +181,31 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
                 if (lane < kFlight && rl < g1) meta.coef[rl] = coef_of(rl, mine_a, mine_b);
             }
             __syncthreads();
-            // ---- scatter: rows in order.  Lane j of every wavefront keeps the length, staging offset and
-            //      coefficient of row w0+j in registers; each step broadcasts one row's triple from there, so
-            //      the only LDS traffic of a step is the (prefetched) entry read and the add of owned columns.
-            for (int w0 = g0; w0 < g1; w0 += kWave) {
-                const int cnt = min(kWave, g1 - w0);
-                int my_len = 0, my_off = 0, my_cf = 0;
-                if (lane < cnt) {
-                    my_len = meta.len[w0 + lane];
-                    my_off = meta.pre[w0 + lane] - base;
-                    my_cf = __float_as_int(meta.coef[w0 + lane]);
-                }
-                int len_n = __builtin_amdgcn_readlane(my_len, 0), off_n = __builtin_amdgcn_readlane(my_off, 0);
-                int2 en = make_int2(-1, 0);
-                if (lane < len_n) en = stage[off_n + lane];
-                for (int j = 0; j < cnt; ++j) {
-                    const int len_c = len_n, off_c = off_n;
-                    const int2 ec = en;
-                    const float cf = __int_as_float(__builtin_amdgcn_readlane(my_cf, j));
-                    en = make_int2(-1, 0);
-                    if (j + 1 < cnt) {
-                        len_n = __builtin_amdgcn_readlane(my_len, j + 1);
-                        off_n = __builtin_amdgcn_readlane(my_off, j + 1);
-                        if (lane < len_n) en = stage[off_n + lane];
+            // ---- scatter: kScatterWaves wavefronts each own a contiguous range of columns and stream over the
+            //      staged entries (which are in row order), adding coefficient*value for the entries in their
+            //      range with LDS float adds that return nothing.  All adds to one column come from one
+            //      wavefront, whose LDS operations execute in issue order, so every column receives its
+            //      terms in row order and nothing waits on a read-modify-write round trip.
+            if (wave < kScatterWaves) {
+                for (int p0 = lane; p0 < total; p0 += 4 * kWave) {       // four entries per lane in flight
+                    int2 e[4];
+                    float term[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int p = p0 + u * kWave;
+                        e[u] = stage[min(p, total - 1)];
+                        if (p >= total) e[u].x = kColMask;              // a column nobody owns
                     }
-                    if (ec.x >= lo && ec.x < hi) alpha[ec.x] += cf * __int_as_float(ec.y);
-                    for (int k = lane + kWave; k < len_c; k += kWave) {
-                        const int2 ek = stage[off_c + k];
-                        if (ek.x >= lo && ek.x < hi) alpha[ek.x] += cf * __int_as_float(ek.y);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) term[u] = meta.coef[(e[u].x >> kColBits) & (kCsrMaxRows - 1)];
+                    asm volatile("" : "+v"(term[0]), "+v"(term[1]), "+v"(term[2]), "+v"(term[3]));   // all four loads issued here,
+                                                                                                     // not inside the branches below
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) term[u] *= __int_as_float(e[u].y);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int c = e[u].x & kColMask;
+                        if (c >= lo && c < hi) atomicAdd(&alpha[c], term[u]);
                     }
                 }
             }
