@@ -116,6 +116,78 @@ __device__ __forceinline__ void decode_sum16(const uint32_t *__restrict__ packed
     }
 }
 
+// ---- quads: four consecutive coordinates 4q .. 4q+3 (one Philox block, one 16-byte access) -------
+// v is 16-byte aligned; coordinates past the end of the vector read as zero and are not written.
+__device__ __forceinline__ float4 load_quad(const float *v, int64_t q, int64_t d)
+{
+    if (4 * q + 3 < d) return reinterpret_cast<const float4 *>(v)[q];
+    float4 r = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (4 * q + 0 < d) r.x = v[4 * q + 0];
+    if (4 * q + 1 < d) r.y = v[4 * q + 1];
+    if (4 * q + 2 < d) r.z = v[4 * q + 2];
+    return r;
+}
+
+__device__ __forceinline__ void store_quad(float *v, int64_t q, int64_t d, float4 r)
+{
+    if (4 * q + 3 < d) {
+        reinterpret_cast<float4 *>(v)[q] = r;
+        return;
+    }
+    if (4 * q + 0 < d) v[4 * q + 0] = r.x;
+    if (4 * q + 1 < d) v[4 * q + 1] = r.y;
+    if (4 * q + 2 < d) v[4 * q + 2] = r.z;
+}
+
+// The four values of quad q of one message row: codes as floats (FIELD 2, 4, 8: the quad is a
+// byte, a half word or a word of the packed row) or the floats themselves (FIELD 32).
+template <int FIELD>
+__device__ __forceinline__ float4 quad_values(const uint32_t *__restrict__ row, int64_t q, int64_t d)
+{
+    if constexpr (FIELD == 32) {
+        return load_quad(reinterpret_cast<const float *>(row), q, d);
+    } else {
+        constexpr int kQuadsPerWord = 8 / FIELD;
+        const uint32_t w = row[q / kQuadsPerWord];
+        const unsigned sh = static_cast<unsigned>(q % kQuadsPerWord) * (4 * FIELD);
+        return make_float4(static_cast<float>(sext_field(w, sh, FIELD)), static_cast<float>(sext_field(w, sh + FIELD, FIELD)),
+                           static_cast<float>(sext_field(w, sh + 2 * FIELD, FIELD)),
+                           static_cast<float>(sext_field(w, sh + 3 * FIELD, FIELD)));
+    }
+}
+
+// Q_(delta,b) on quad q: the 4*FIELD code bits (coordinate 4q in the low field) and the number of
+// nonzero codes added to nz.  Coordinates past the end must be passed as 0.
+template <int FIELD>
+__device__ __forceinline__ uint32_t quantize_quad(float4 a, const Scale &s, const StreamKey &key, int64_t q, int &nz)
+{
+    constexpr uint32_t kMask = (1u << FIELD) - 1u;
+    if (s.inv_delta == 0.0f) return 0u;              // degenerate scale: all codes are zero
+    const uint4 r = stream_block(key, static_cast<uint32_t>(q));
+    const int k0 = quantize_one(a.x, s, r.x), k1 = quantize_one(a.y, s, r.y);
+    const int k2 = quantize_one(a.z, s, r.z), k3 = quantize_one(a.w, s, r.w);
+    nz += (k0 != 0) + (k1 != 0) + (k2 != 0) + (k3 != 0);
+    return (static_cast<uint32_t>(k0) & kMask) | ((static_cast<uint32_t>(k1) & kMask) << FIELD) |
+           ((static_cast<uint32_t>(k2) & kMask) << (2 * FIELD)) | ((static_cast<uint32_t>(k3) & kMask) << (3 * FIELD));
+}
+
+// Stores the code bits of quad q = q0 + lane, where q0 is a multiple of 64 common to the wavefront.
+// For FIELD < 8 the lanes of a pair (FIELD 4) or of a group of four (FIELD 2) first combine their
+// bits into one word with cross-lane moves, and the first lane of the group stores it.  Every lane
+// of the wavefront must make the call; lanes with q >= quads pass bits == 0.
+template <int FIELD>
+__device__ __forceinline__ void store_quad_bits(uint32_t bits, int64_t q, int64_t quads, uint32_t *__restrict__ out)
+{
+    constexpr int kQuadsPerWord = 8 / FIELD;             // 1, 2 or 4 lanes share a word
+    const int sub = static_cast<int>(q) & (kQuadsPerWord - 1);
+    if constexpr (kQuadsPerWord > 1) {
+        bits <<= (4 * FIELD) * sub;
+        bits |= dq_i2u(dpp_move_or_zero<0xb1, 0xf>(dq_u2i(bits)));                                   // lane ^ 1
+        if constexpr (kQuadsPerWord == 4) bits |= dq_i2u(dpp_move_or_zero<0x4e, 0xf>(dq_u2i(bits)));   // lane ^ 2
+    }
+    if (q < quads && sub == 0) out[q / kQuadsPerWord] = bits;
+}
+
 // prox of eta*l1*|.| : soft-threshold at kappa = eta*l1.
 __device__ __forceinline__ float soft_threshold(float z, float kappa)
 {

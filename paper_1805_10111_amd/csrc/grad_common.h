@@ -58,28 +58,6 @@ struct WorkerOut {
     uint32_t *status;       // nullable
 };
 
-// Coordinates 4q .. 4q+3 of a vector in LDS (16-byte aligned); zeros past the end.
-__device__ __forceinline__ float4 lds_quad(const float *v, int64_t q, int64_t d)
-{
-    if (4 * q + 3 < d) return reinterpret_cast<const float4 *>(v)[q];
-    float4 r = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    if (4 * q + 0 < d) r.x = v[4 * q + 0];
-    if (4 * q + 1 < d) r.y = v[4 * q + 1];
-    if (4 * q + 2 < d) r.z = v[4 * q + 2];
-    return r;
-}
-
-__device__ __forceinline__ void lds_quad_store(float *v, int64_t q, int64_t d, float4 r)
-{
-    if (4 * q + 3 < d) {
-        reinterpret_cast<float4 *>(v)[q] = r;
-        return;
-    }
-    if (4 * q + 0 < d) v[4 * q + 0] = r.x;
-    if (4 * q + 1 < d) v[4 * q + 1] = r.y;
-    if (4 * q + 2 < d) v[4 * q + 2] = r.z;
-}
-
 // Scratch: su >= blockDim.x/64 uint32, si >= blockDim.x/64 int.  alpha is 16-byte aligned.
 // Alg. 2, worker (ii)-(iii) when `sparsify`, else Alg. 1, worker (ii).
 // The unit of work is a quad of four consecutive coordinates (one Philox block, one 16-byte
@@ -95,7 +73,7 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
     const int64_t first = threadIdx.x - lane;           // quad of lane 0 in the first sweep (wave-uniform)
     uint32_t vmax = 0;
     for (int64_t q = threadIdx.x; q < quads; q += blockDim.x) {
-        const float4 a = lds_quad(alpha, q, d);
+        const float4 a = load_quad(alpha, q, d);
         vmax = max(max(vmax, abs_bits(a.x)), max(max(abs_bits(a.y), abs_bits(a.z)), abs_bits(a.w)));
     }
     vmax = block_max_u32(vmax, su);
@@ -105,14 +83,14 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
         sk.tag = DQ_TAG_SPARSIFY;
         uint32_t bmax = 0;
         for (int64_t q = threadIdx.x; q < quads; q += blockDim.x) {
-            float4 a = lds_quad(alpha, q, d);
+            float4 a = load_quad(alpha, q, d);
             const uint4 w = stream_block(sk, static_cast<uint32_t>(q));
             a.x = sparsify_one(a.x, rule, w.x);
             a.y = sparsify_one(a.y, rule, w.y);
             a.z = sparsify_one(a.z, rule, w.z);
             a.w = sparsify_one(a.w, rule, w.w);
             bmax = max(max(bmax, abs_bits(a.x)), max(max(abs_bits(a.y), abs_bits(a.z)), abs_bits(a.w)));
-            lds_quad_store(alpha, q, d, a);
+            store_quad(alpha, q, d, a);
         }
         vmax = block_max_u32(bmax, su);      // (barriers inside also publish the beta writes)
     }
@@ -132,8 +110,6 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
         }
         return;
     } else {
-        constexpr uint32_t kMask = (1u << FIELD) - 1u;
-        constexpr int kQuadsPerWord = 8 / FIELD;             // 1, 2 or 4 lanes share a word
         const Scale s = make_scale(__uint_as_float(vmax), b);
         if (threadIdx.x == 0) {
             out.delta_out[0] = s.delta;
@@ -142,26 +118,12 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
         key.tag = DQ_TAG_GRAD;
         int nz = 0;
         // every lane of a wavefront takes the same number of sweeps, so that the cross-lane
-        // moves below always see all lanes; lanes past the end contribute zero bits
+        // moves of the store always see all lanes; lanes past the end contribute zero bits
         for (int64_t q0 = first; q0 < quads; q0 += blockDim.x) {
             const int64_t q = q0 + lane;
             uint32_t bits = 0;
-            if (q < quads && s.inv_delta != 0.0f) {
-                const float4 a = lds_quad(alpha, q, d);
-                const uint4 r = stream_block(key, static_cast<uint32_t>(q));
-                const int k0 = quantize_one(a.x, s, r.x), k1 = quantize_one(a.y, s, r.y);
-                const int k2 = quantize_one(a.z, s, r.z), k3 = quantize_one(a.w, s, r.w);
-                nz += (k0 != 0) + (k1 != 0) + (k2 != 0) + (k3 != 0);
-                bits = (static_cast<uint32_t>(k0) & kMask) | ((static_cast<uint32_t>(k1) & kMask) << FIELD) |
-                       ((static_cast<uint32_t>(k2) & kMask) << (2 * FIELD)) |
-                       ((static_cast<uint32_t>(k3) & kMask) << (3 * FIELD));
-            }
-            if constexpr (kQuadsPerWord > 1) {
-                bits <<= (4 * FIELD) * (lane & (kQuadsPerWord - 1));
-                bits |= dq_i2u(dpp_move_or_zero<0xb1, 0xf>(dq_u2i(bits)));                   // lane ^ 1
-                if constexpr (kQuadsPerWord == 4) bits |= dq_i2u(dpp_move_or_zero<0x4e, 0xf>(dq_u2i(bits)));   // lane ^ 2
-            }
-            if (q < quads && (lane & (kQuadsPerWord - 1)) == 0) out.packed[q / kQuadsPerWord] = bits;
+            if (q < quads) bits = quantize_quad<FIELD>(load_quad(alpha, q, d), s, key, q, nz);
+            store_quad_bits<FIELD>(bits, q, quads, out.packed);
         }
         if (out.nnz_out) {
             nz = block_sum_i32(nz, si);

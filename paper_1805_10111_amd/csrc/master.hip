@@ -76,12 +76,14 @@ static int launch_master_update(bool acc, dim3 grid, hipStream_t st, const uint3
 }
 
 // ------------------------------------------------------------------ fused master step, one block
-// For d <= 16384*CH the whole master step is one block of 1024 threads: each thread owns CH
-// chunks of 16 coordinates, keeps the updated model in registers across the block-wide
-// ||x||_inf reduction and quantizes + packs it right away (Alg. 1, master (ii) then (i)).
+// For d <= 32768 the whole master step is one block of 1024 threads: thread t owns the quads
+// (four consecutive coordinates) t, t+1024, ... of the model, keeps their updated values in
+// registers across the block-wide ||x||_inf reduction and quantizes + packs them right away
+// (Alg. 1, master (ii) then (i)).  Consecutive lanes work on consecutive quads, so message words
+// and model vectors are read in whole cache lines and all threads are busy from d = 4096 up.
 constexpr int kFusedThreads = 1024;
 
-template <int FIELD, bool ACC, int CH>
+template <int FIELD, bool ACC, int NQ>
 __global__ __launch_bounds__(kFusedThreads) void master_fused_kernel(
     const uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words, const float *__restrict__ delta, int M,
     float scale, const float *__restrict__ g_snap, float *__restrict__ x, float *__restrict__ y,
@@ -90,81 +92,100 @@ __global__ __launch_bounds__(kFusedThreads) void master_fused_kernel(
     float *__restrict__ absmax_x_out, uint32_t *__restrict__ status)
 {
     __shared__ uint32_t scratch[kFusedThreads / kWave];
-    const int64_t chunks = (d + 15) / 16;
-    float xv[CH][16];
+    constexpr int kGroup = 8;                            // messages whose loads are in flight together
+    const int64_t quads = (d + 3) / 4;
+    float4 xv[NQ];                                       // the thread's quads threadIdx.x + 1024*k of the new model
     uint32_t amax = 0;
 #pragma unroll
-    for (int ch = 0; ch < CH; ++ch) {
-        const int64_t c = threadIdx.x + static_cast<int64_t>(kFusedThreads) * ch;
+    for (int k = 0; k < NQ; ++k) {
+        const int64_t q = threadIdx.x + static_cast<int64_t>(kFusedThreads) * k;
+        xv[k] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (q >= quads) continue;
+        // sum_m delta_m * code_m, messages in order (Alg. 1, master (ii))
+        float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        int m = 0;
+        for (; m + kGroup <= M; m += kGroup) {
+            float4 v[kGroup];
+            float dm[kGroup];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) xv[ch][j] = 0.0f;
-        if (c >= chunks) continue;
-        float acc[16];
-        decode_sum16<FIELD>(packed, ld_words, row_words, delta, M, c, d, acc);
-        const int64_t base = c * 16;
-        float gs[16], yv[16], xs[16], sm[16];
-        load16(g_snap, base, d, gs);
-        if (ACC) {
-            load16(y, base, d, yv);
-            load16(x_snap, base, d, xs);
-            if (xsum) load16(xsum, base, d, sm);
-        } else {
-            load16(x, base, d, xv[ch]);
-        }
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const float u = scale * acc[j] + gs[j];
-            if (ACC) {
-                yv[j] = soft_threshold(yv[j] - eta * u, kappa);
-                xv[ch][j] = xs[j] + theta * (yv[j] - xs[j]);
-                if (xsum) sm[j] = sm[j] + xv[ch][j];
-            } else {
-                xv[ch][j] = soft_threshold(xv[ch][j] - eta * u, kappa);
+            for (int u = 0; u < kGroup; ++u) {
+                v[u] = quad_values<FIELD>(packed + static_cast<int64_t>(m + u) * ld_words, q, d);
+                dm[u] = FIELD == 32 ? 1.0f : delta[m + u];
             }
-            if (base + j >= d) xv[ch][j] = 0.0f;
-            amax = max(amax, abs_bits(xv[ch][j]));
+#pragma unroll
+            for (int u = 0; u < kGroup; ++u) {
+                acc.x = fmaf(dm[u], v[u].x, acc.x);
+                acc.y = fmaf(dm[u], v[u].y, acc.y);
+                acc.z = fmaf(dm[u], v[u].z, acc.z);
+                acc.w = fmaf(dm[u], v[u].w, acc.w);
+            }
         }
-        store16(x, base, d, xv[ch]);
+        for (; m < M; ++m) {
+            const float4 v = quad_values<FIELD>(packed + static_cast<int64_t>(m) * ld_words, q, d);
+            const float dm = FIELD == 32 ? 1.0f : delta[m];
+            acc.x = fmaf(dm, v.x, acc.x);
+            acc.y = fmaf(dm, v.y, acc.y);
+            acc.z = fmaf(dm, v.z, acc.z);
+            acc.w = fmaf(dm, v.w, acc.w);
+        }
+        const float4 gs = load_quad(g_snap, q, d);
+        const float u4[4] = {scale * acc.x + gs.x, scale * acc.y + gs.y, scale * acc.z + gs.z, scale * acc.w + gs.w};
+        float xn[4];
         if (ACC) {
-            store16(y, base, d, yv);
-            if (xsum) store16(xsum, base, d, sm);
+            // Alg. 3: y <- prox(y - eta u), x <- snapshot + theta (y - snapshot), running sum of x
+            const float4 y4 = load_quad(y, q, d), s4 = load_quad(x_snap, q, d);
+            const float yo[4] = {y4.x, y4.y, y4.z, y4.w}, xs[4] = {s4.x, s4.y, s4.z, s4.w};
+            float yn[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                yn[e] = soft_threshold(yo[e] - eta * u4[e], kappa);
+                xn[e] = xs[e] + theta * (yn[e] - xs[e]);
+            }
+            store_quad(y, q, d, make_float4(yn[0], yn[1], yn[2], yn[3]));
+            if (xsum) {
+                const float4 sm = load_quad(xsum, q, d);
+                store_quad(xsum, q, d, make_float4(sm.x + xn[0], sm.y + xn[1], sm.z + xn[2], sm.w + xn[3]));
+            }
+        } else {
+            const float4 x4 = load_quad(x, q, d);
+            const float xo[4] = {x4.x, x4.y, x4.z, x4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) xn[e] = soft_threshold(xo[e] - eta * u4[e], kappa);
         }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (4 * q + e >= d) xn[e] = 0.0f;
+            amax = max(amax, abs_bits(xn[e]));
+        }
+        xv[k] = make_float4(xn[0], xn[1], xn[2], xn[3]);
+        store_quad(x, q, d, xv[k]);
     }
     amax = block_max_u32(amax, scratch);
     if (threadIdx.x == 0) absmax_x_out[0] = __uint_as_float(amax);
     if (b_x == 32) {
         if (threadIdx.x == 0) delta_x_out[0] = 1.0f;
 #pragma unroll
-        for (int ch = 0; ch < CH; ++ch) {
-            const int64_t c = threadIdx.x + static_cast<int64_t>(kFusedThreads) * ch;
-            if (c < chunks) store16(reinterpret_cast<float *>(xq_out), c * 16, d, xv[ch]);
+        for (int k = 0; k < NQ; ++k) {
+            const int64_t q = threadIdx.x + static_cast<int64_t>(kFusedThreads) * k;
+            if (q < quads) store_quad(reinterpret_cast<float *>(xq_out), q, d, xv[k]);
         }
         return;
     }
+    // Alg. 1, master (i) for the next round: quantize the new model
     const Scale s = make_scale(__uint_as_float(amax), b_x);
     if (threadIdx.x == 0) {
         delta_x_out[0] = s.delta;
         if (s.bad && status) atomicOr(status, 1u);
     }
     key.worker = DQ_MASTER_ID;
-    const int64_t xq_words = packed_words_dev(d, b_x);
+    int nz = 0;
 #pragma unroll
-    for (int ch = 0; ch < CH; ++ch) {
-        const int64_t c = threadIdx.x + static_cast<int64_t>(kFusedThreads) * ch;
-        if (c >= chunks) continue;
-        if (b_x == 8) {
-            uint32_t w[Words16<8>::n];
-            quantize16<8>(xv[ch], s, key, c, w);
-            store_words<8>(xq_out, c, xq_words, w);
-        } else if (b_x == 4) {
-            uint32_t w[Words16<4>::n];
-            quantize16<4>(xv[ch], s, key, c, w);
-            store_words<4>(xq_out, c, xq_words, w);
-        } else {
-            uint32_t w[Words16<2>::n];
-            quantize16<2>(xv[ch], s, key, c, w);
-            store_words<2>(xq_out, c, xq_words, w);
-        }
+    for (int k = 0; k < NQ; ++k) {                       // all lanes make every store call (cross-lane moves inside)
+        const int64_t q = threadIdx.x + static_cast<int64_t>(kFusedThreads) * k;
+        const bool in = q < quads;
+        if (b_x == 8) store_quad_bits<8>(in ? quantize_quad<8>(xv[k], s, key, q, nz) : 0u, q, quads, xq_out);
+        else if (b_x == 4) store_quad_bits<4>(in ? quantize_quad<4>(xv[k], s, key, q, nz) : 0u, q, quads, xq_out);
+        else store_quad_bits<2>(in ? quantize_quad<2>(xv[k], s, key, q, nz) : 0u, q, quads, xq_out);
     }
 }
 
@@ -176,10 +197,15 @@ static void launch_master_fused2(int ch, hipStream_t st, const uint32_t *packed,
                                  uint32_t *status)
 {
     const dim3 grid(1), block(kFusedThreads);
-    if (ch == 1)
-        master_fused_kernel<FIELD, ACC, 1><<<grid, block, 0, st>>>(packed, ld_words, row_words, delta, M, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
-    else
-        master_fused_kernel<FIELD, ACC, 2><<<grid, block, 0, st>>>(packed, ld_words, row_words, delta, M, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
+#define DQ_FUSED(NQ) master_fused_kernel<FIELD, ACC, NQ><<<grid, block, 0, st>>>(packed, ld_words, row_words, delta, M, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, b_x, key, xq_out, delta_x_out, absmax_x_out, status)
+    switch (ch) {                                        // quads per thread that cover d
+    case 1: DQ_FUSED(1); break;
+    case 2: DQ_FUSED(2); break;
+    case 3: case 4: DQ_FUSED(4); break;
+    case 5: case 6: DQ_FUSED(6); break;
+    default: DQ_FUSED(8); break;
+    }
+#undef DQ_FUSED
 }
 
 template <int FIELD>
@@ -344,7 +370,7 @@ extern "C" int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, cons
     const float kappa_f = eta * l1;
     if (d <= 16384 * 2) {
         // small model: the whole step in one block, one launch
-        const int ch = d <= 16384 ? 1 : 2;
+        const int ch = static_cast<int>(ceil_div(ceil_div(d, 4), kFusedThreads));     // 1..8
         const StreamKey mkey{static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), iter, 0u, DQ_TAG_MODEL};
         const bool accf = y != nullptr;
         const int Mf = static_cast<int>(M);
