@@ -77,6 +77,15 @@ def lib() -> C.CDLL:
         _lib.ref_pack.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
         _lib.ref_unpack.restype = None
         _lib.ref_unpack.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
+        _lib.ref_quantize_wide.restype = C.c_int
+        _lib.ref_quantize_wide.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_uint64, C.c_uint32, C.c_uint32,
+                                           C.c_uint32, C.c_void_p, C.c_void_p]
+        _lib.ref_pack_wide.restype = None
+        _lib.ref_pack_wide.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
+        _lib.ref_unpack_wide.restype = None
+        _lib.ref_unpack_wide.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
+        _lib.ref_dequantize_wide.restype = None
+        _lib.ref_dequantize_wide.argtypes = [C.c_void_p, C.c_float, C.c_int64, C.c_void_p]
         _lib.ref_sample_indices.restype = None
         _lib.ref_sample_indices.argtypes = [C.c_int64, C.c_int64, C.c_uint64, C.c_uint32, C.c_uint32, C.c_void_p]
         _lib.ref_objective.restype = C.c_double
@@ -212,6 +221,41 @@ def unpack(words, d: int, b: int) -> np.ndarray:
     codes = np.zeros(d, dtype=np.int8)
     lib().ref_unpack(_p(words), d, b, _p(codes))
     return codes
+
+
+# ---- any width 2 <= b <= 16 (int32 codes; fields may straddle words) -------------------
+def quantize_wide(v, b: int, seed: int, it: int, worker: int, tag: int = TAG_GRAD):
+    """Returns (codes int32[d], delta float32, status) for 2 <= b <= 16."""
+    assert 2 <= b <= 16
+    v = _f32(v)
+    codes = np.zeros(v.size, dtype=np.int32)
+    delta = np.zeros(1, dtype=np.float32)
+    st = lib().ref_quantize_wide(_p(v), v.size, b, seed, it, worker, tag, _p(codes), _p(delta))
+    return codes, delta[0], int(st)
+
+
+def pack_wide(codes, b: int) -> np.ndarray:
+    assert 2 <= b <= 16
+    codes = np.ascontiguousarray(codes, dtype=np.int32)
+    words = np.zeros(packed_words(codes.size, b), dtype=np.uint32)
+    lib().ref_pack_wide(_p(codes), codes.size, b, _p(words))
+    return words
+
+
+def unpack_wide(words, d: int, b: int) -> np.ndarray:
+    assert 2 <= b <= 16
+    words = np.ascontiguousarray(words, dtype=np.uint32)
+    assert words.size >= packed_words(d, b)
+    codes = np.zeros(d, dtype=np.int32)
+    lib().ref_unpack_wide(_p(words), d, b, _p(codes))
+    return codes
+
+
+def dequantize_wide(codes, delta) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.int32)
+    out = np.zeros(codes.size, dtype=np.float32)
+    lib().ref_dequantize_wide(_p(codes), np.float32(delta), codes.size, _p(out))
+    return out
 
 
 # ---------------------------------------------------------------------- problem

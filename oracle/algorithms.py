@@ -22,9 +22,9 @@ from typing import List, Optional
 
 import numpy as np
 
-from . import (MASTER_ID, TAG_GRAD, TAG_MODEL, RefProblem, acc_mix, acc_snapshot, dequantize,
-               full_grad, master_update, master_update_full, objective, pack, quantize, sample_indices,
-               sparsify, unpack, vr_grad)
+from . import (MASTER_ID, TAG_GRAD, TAG_MODEL, RefProblem, acc_mix, acc_snapshot, dequantize, dequantize_wide,
+               full_grad, master_update, master_update_full, objective, pack, pack_wide, quantize, quantize_wide,
+               sample_indices, sparsify, unpack, unpack_wide, vr_grad)
 
 
 @dataclass
@@ -47,9 +47,14 @@ def model_message(x: np.ndarray, x_snap: np.ndarray, b_x: int, seed: int, it: in
         return x_snap.copy(), None, np.float32(0), 1
     if b_x == 32:
         return x.copy(), x.view(np.uint32).copy(), np.float32(1), 32 * d
-    k, dx, _ = quantize(x, b_x, seed, it, MASTER_ID, TAG_MODEL)
-    words = pack(k, b_x)
-    q = dequantize(unpack(words, d, b_x), dx)
+    if b_x in (2, 4, 8):
+        k, dx, _ = quantize(x, b_x, seed, it, MASTER_ID, TAG_MODEL)
+        words = pack(k, b_x)
+        q = dequantize(unpack(words, d, b_x), dx)
+    else:                                            # any other width up to 16 bits (model-precision study, Section 5.2)
+        k, dx, _ = quantize_wide(x, b_x, seed, it, MASTER_ID, TAG_MODEL)
+        words = pack_wide(k, b_x)
+        q = dequantize_wide(unpack_wide(words, d, b_x), dx)
     return q, words, dx, 32 + b_x * d
 
 

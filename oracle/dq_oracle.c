@@ -133,8 +133,8 @@ float ref_delta(float amax, int b)
  * taken with probability p = t - z, i.e. when u < p (rule (i)); the result is
  * clamped to the end points (rule (ii), reachable only through rounding of t).
  * Returns 1 if the scale is not finite (NaN/Inf in v), else 0; codes are then 0. */
-int ref_quantize_given_uniforms(const float *v, int64_t d, int b, const float *u, int8_t *codes,
-                                float *delta_out)
+int ref_quantize_given_uniforms_wide(const float *v, int64_t d, int b, const float *u, int32_t *codes,
+                                     float *delta_out)
 {
     const int L = level_max(b);
     const int kmin = -(1 << (b - 1)), kmax = L;
@@ -153,12 +153,33 @@ int ref_quantize_given_uniforms(const float *v, int64_t d, int b, const float *u
         int k = (int)z + (u[i] < p ? 1 : 0);
         if (k < kmin) k = kmin;
         if (k > kmax) k = kmax;
-        codes[i] = (int8_t)k;
+        codes[i] = k;
     }
     return 0;
 }
 
+/* Codes of at most 8 bits in one byte each (2 <= b <= 8). */
+int ref_quantize_given_uniforms(const float *v, int64_t d, int b, const float *u, int8_t *codes,
+                                float *delta_out)
+{
+    int32_t *wide = (int32_t *)malloc(sizeof(int32_t) * (size_t)(d > 0 ? d : 1));
+    int st = ref_quantize_given_uniforms_wide(v, d, b, u, wide, delta_out);
+    for (int64_t i = 0; i < d; ++i) codes[i] = (int8_t)wide[i];
+    free(wide);
+    return st;
+}
+
 /* The same with u[i] drawn from stream (seed, iter, worker, tag) at coordinate i. */
+int ref_quantize_wide(const float *v, int64_t d, int b, uint64_t seed, uint32_t iter, uint32_t worker,
+                      uint32_t tag, int32_t *codes, float *delta_out)
+{
+    float *u = (float *)malloc(sizeof(float) * (size_t)(d > 0 ? d : 1));
+    for (int64_t i = 0; i < d; ++i) u[i] = ref_uniform(seed, iter, worker, tag, (uint64_t)i);
+    int st = ref_quantize_given_uniforms_wide(v, d, b, u, codes, delta_out);
+    free(u);
+    return st;
+}
+
 int ref_quantize(const float *v, int64_t d, int b, uint64_t seed, uint32_t iter, uint32_t worker,
                  uint32_t tag, int8_t *codes, float *delta_out)
 {
@@ -201,6 +222,44 @@ void ref_unpack(const uint32_t *words, int64_t d, int b, int8_t *codes)
         if (f >> (b - 1)) k -= (1 << b);              /* sign extension */
         codes[i] = (int8_t)k;
     }
+}
+
+/* Any width 2 <= b <= 16 (the model-precision study of Section 5.2 varies b_x from 2 to 11):
+ * the same layout, field i at bits [i*b, i*b+b) of the row read as one little-endian bit
+ * string; a field that does not fit in the rest of its word continues in the low bits of the
+ * next word. */
+void ref_pack_wide(const int32_t *codes, int64_t d, int b, uint32_t *words)
+{
+    int64_t nw = ref_packed_words(d, b);
+    uint32_t mask = (1u << b) - 1u;
+    for (int64_t w = 0; w < nw; ++w) words[w] = 0;
+    for (int64_t i = 0; i < d; ++i) {
+        int64_t bit = i * b;
+        int sh = (int)(bit % 32);
+        uint32_t f = (uint32_t)codes[i] & mask;
+        words[bit / 32] |= f << sh;
+        if (sh + b > 32) words[bit / 32 + 1] |= f >> (32 - sh);
+    }
+}
+
+void ref_unpack_wide(const uint32_t *words, int64_t d, int b, int32_t *codes)
+{
+    uint32_t mask = (1u << b) - 1u;
+    for (int64_t i = 0; i < d; ++i) {
+        int64_t bit = i * b;
+        int sh = (int)(bit % 32);
+        uint32_t f = words[bit / 32] >> sh;
+        if (sh + b > 32) f |= words[bit / 32 + 1] << (32 - sh);
+        f &= mask;
+        int k = (int)f;
+        if (f >> (b - 1)) k -= (1 << b);              /* sign extension */
+        codes[i] = k;
+    }
+}
+
+void ref_dequantize_wide(const int32_t *codes, float delta, int64_t d, float *v_out)
+{
+    for (int64_t i = 0; i < d; ++i) v_out[i] = delta * (float)codes[i];
 }
 
 /* Section 4.2: a sparsified message lists only the nonzero coordinates, each as its
