@@ -117,7 +117,12 @@ int32_t dq_dequantize(const int8_t *codes, int64_t ld_codes, const float *delta,
 /* Wire format of Section 3.1 (32 + b*d bits per vector: delta plus b bits per
  * coordinate).  Field i of a row = bits [(i*b)%32, (i*b)%32+b) of word
  * floor(i*b/32), two's complement, low bits first; unused tail bits are 0.
- * Rows of packed words have stride ld_words >= ceil(d*b/32).  b in {2,4,8}. */
+ * For a width that does not divide 32 the row is one little-endian bit string with field i at
+ * bits [i*b, i*b+b): a field may continue in the low bits of the next word (the model-precision
+ * study of Section 5.2 uses b_x from 2 to 11).
+ * Rows of packed words have stride ld_words >= ceil(d*b/32).  b in [2,8] here (int8 codes);
+ * dq_quantize_pack, dq_unpack_dequant_sum and the model message of the worker and master
+ * calls take any width in [2,16]. */
 int32_t dq_pack(const int8_t *codes, int64_t ld_codes, int64_t d, int64_t M, int32_t b,
                 uint32_t *packed_out, int64_t ld_words, void *stream);
 int32_t dq_unpack(const uint32_t *packed, int64_t ld_words, int64_t d, int64_t M, int32_t b,
@@ -137,9 +142,9 @@ int32_t dq_sparse_encode(const uint32_t *packed, int64_t ld_words, int64_t d, in
 int32_t dq_sparse_decode(const uint32_t *stream_in, int64_t ld_stream, const int32_t *nnz, int64_t d, int64_t M,
                          int32_t b, uint32_t *packed_out, int64_t ld_words, void *stream);
 
-/* dq_quantize followed by dq_pack in one pass (same bits as the two calls).
- * v 16-byte aligned and ld % 4 == 0 select the 128-bit path; otherwise a
- * scalar path is used.  packed_out rows are 16-byte aligned if ld_words % 4 == 0. */
+/* dq_quantize followed by dq_pack in one pass (same bits as the two calls), for any
+ * width b in [2,16] (2, 4 and 8 take the word-aligned fast path).
+ * v and packed_out 16-byte aligned; with M > 1, ld % 4 == 0 and ld_words % 4 == 0. */
 int32_t dq_quantize_pack(const float *v, int64_t d, int64_t M, int64_t ld, int32_t b,
                          float *absmax, int32_t absmax_given,
                          uint64_t seed, uint32_t iter, uint32_t tag, uint32_t worker0,
@@ -149,7 +154,7 @@ int32_t dq_quantize_pack(const float *v, int64_t d, int64_t M, int64_t ld, int32
 /* Master's receive side (Alg. 1, master (ii), first half): decode M packed
  * gradients and aggregate,  out[i] = scale * sum_{m<M} delta[m]*k_mi,
  * summed in the order m = 0..M-1 with fused multiply-adds, then one multiply
- * by scale (1/M for the mean over a synchronous round of M workers). */
+ * by scale (1/M for the mean over a synchronous round of M workers).  b in [2,16]. */
 int32_t dq_unpack_dequant_sum(const uint32_t *packed, int64_t ld_words, const float *delta,
                               int64_t d, int64_t M, int32_t b, float scale, float *out, void *stream);
 
@@ -173,8 +178,8 @@ int32_t dq_full_grad(const dq_problem *prob /*host*/, const float *x, float *g_o
 /* Worker step (i) of Alg. 1 for M workers with mini-batches idx[m*B .. m*B+B):
  *   alpha_m = (1/B) sum_{i in I_m} [grad f_i(q) - grad f_i(x_snap)],
  * q = delta_x * (codes unpacked from xq_packed) is the b_x-bit model the worker
- * received (Alg. 1, master (i)); b_x == 32 means xq_packed holds float32 values
- * of the model itself (no quantization; delta_x ignored).
+ * received (Alg. 1, master (i)), b_x in [2,16]; b_x == 32 means xq_packed holds float32
+ * values of the model itself (no quantization; delta_x ignored).
  * model_is_snapshot != 0 is the flag-bit case of Section 4.1 (q = x_snap): alpha = 0.
  * z_snap (nullable) = margins a_i.x_snap cached by dq_full_grad; if NULL they
  * are recomputed.  alpha_out rows have stride ld (ld % 4 == 0, 16-byte aligned).
@@ -204,7 +209,8 @@ int32_t dq_sparsify(const float *alpha, int64_t d, int64_t M, int64_t ld, const 
  * idx == NULL: the mini-batches are sampled inside the kernel, exactly as
  * dq_sample_indices(n, M, B, seed, iter, worker0, .) would produce them.
  * b == 32: no gradient quantization, packed_out rows receive alpha (or beta) as
- * float32 (ld_words >= d) and delta_out = 1. */
+ * float32 (ld_words >= d) and delta_out = 1.  Gradient widths: b in {2,4,8,32}
+ * (others in [2,8]: DQ_ERR_UNSUPPORTED). */
 int32_t dq_worker_step(const dq_problem *prob /*host*/, const int32_t *idx, int64_t M, int64_t B,
                        const uint32_t *xq_packed, const float *delta_x, int32_t b_x,
                        int32_t model_is_snapshot, const float *x_snap, const float *z_snap,
@@ -225,6 +231,8 @@ int32_t dq_worker_step(const dq_problem *prob /*host*/, const int32_t *idx, int6
  * delta_x_out[0] its scale and absmax_x_out[0] = ||x||_inf (scratch + output).
  * b == 32: `packed` holds M rows of float32 gradients (stride ld_words, delta
  * ignored).  b_x == 32: no model quantization, xq_packed_out receives x as float32.
+ * b in {2,4,8,32}; b_x in [2,16] or 32 (widths other than 2, 4, 8, 32 take a path of
+ * three launches instead of one).
  * All float32, in the order written; x, y, xsum are updated in place. */
 int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
                        float scale, const float *g_snap, float *x, float *y, const float *x_snap,
@@ -237,7 +245,7 @@ int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, const float *de
  * Alg. 3):  out[0] = E_Q ||Q_(delta_x,b)(x) - x||^2 over the rounding decisions, which is
  * delta_x^2 * sum_i p_i (1 - p_i) (proof of Lemma 5; nothing is sampled), and
  * out[1] = ||x - x_snap||^2.  The condition holds for a given mu iff out[0] <= mu * out[1]
- * (theta_s * mu for Alg. 3).  out: device double[2].  b in [2,8].  Diagnostic, one block. */
+ * (theta_s * mu for Alg. 3).  out: device double[2].  b in [2,16].  Diagnostic, one block. */
 int32_t dq_mu_terms(const float *x, const float *x_snap, int64_t d, int32_t b, double *out, void *stream);
 
 /* Start of an epoch of Alg. 3:  x_out = x_snap + theta*(y - x_snap)  (= theta*y + (1-theta)*x_snap). */

@@ -19,7 +19,7 @@ static int32_t check_problem(const dq_problem *p)
     return DQ_OK;
 }
 
-static bool model_bits_ok(int b) { return b == 2 || b == 4 || b == 8 || b == 32; }
+static bool gradient_bits_ok(int b) { return b == 2 || b == 4 || b == 8 || b == 32; }
 
 extern "C" int64_t dq_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64_t B)
 {
@@ -65,8 +65,7 @@ int32_t dq::worker_step_impl(const dq_problem *prob, const WorkerArgs &a, void *
     if (!a.idx && !a.packed) return DQ_ERR_INVALID_ARG;          // only dq_worker_step can sample in the kernel
     if (!a.model_is_snapshot) {
         if (!a.xq || !aligned16(a.xq)) return DQ_ERR_INVALID_ARG;
-        if (a.b_x < 2 || (a.b_x > 8 && a.b_x != 32)) return DQ_ERR_INVALID_ARG;
-        if (!model_bits_ok(a.b_x)) return DQ_ERR_UNSUPPORTED;
+        if (a.b_x < 2 || (a.b_x > 16 && a.b_x != 32)) return DQ_ERR_INVALID_ARG;
         if (a.b_x != 32 && !a.delta_x) return DQ_ERR_INVALID_ARG;
     }
     if (a.alpha_out && (!aligned16(a.alpha_out) || a.ld < prob->d || (a.M > 1 && a.ld % 4 != 0))) return DQ_ERR_INVALID_ARG;
@@ -97,7 +96,7 @@ extern "C" int32_t dq_worker_step(const dq_problem *prob, const int32_t *idx, in
 {
     if (!packed_out || !delta_out || !aligned16(packed_out) || !prob) return DQ_ERR_INVALID_ARG;
     if (b < 2 || (b > 8 && b != 32)) return DQ_ERR_INVALID_ARG;
-    if (!model_bits_ok(b)) return DQ_ERR_UNSUPPORTED;
+    if (!gradient_bits_ok(b)) return DQ_ERR_UNSUPPORTED;
     const int64_t row_words = b == 32 ? prob->d : packed_words(prob->d, b);
     if (ld_words < row_words || (M > 1 && ld_words % 4 != 0)) return DQ_ERR_INVALID_ARG;
     WorkerArgs a{};

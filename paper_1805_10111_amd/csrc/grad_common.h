@@ -45,8 +45,11 @@ __device__ __forceinline__ float model_value(const ModelMsg &q, int64_t j)
 {
     if (q.b_x == 32) return __uint_as_float(q.words[j]);
     const int64_t bit = j * q.b_x;
-    const int k = sext_field(q.words[bit >> 5], static_cast<unsigned>(bit & 31), static_cast<unsigned>(q.b_x));
-    return q.delta_x * static_cast<float>(k);
+    const unsigned sh = static_cast<unsigned>(bit & 31);
+    uint32_t f = q.words[bit >> 5] >> sh;
+    if (sh + q.b_x > 32) f |= q.words[(bit >> 5) + 1] << (32 - sh);      // widths that do not divide 32: the field
+                                                                        // continues in the next word of the row
+    return q.delta_x * static_cast<float>(sext_field(f, 0, static_cast<unsigned>(q.b_x)));
 }
 
 // ---- tail of a worker step on alpha[d] in LDS (one block per worker) -------------------

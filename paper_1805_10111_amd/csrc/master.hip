@@ -343,7 +343,7 @@ static inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream
 extern "C" int32_t dq_mu_terms(const float *x, const float *x_snap, int64_t d, int32_t b, double *out, void *stream)
 {
     if (d <= 0 || !x || !x_snap || !out) return DQ_ERR_INVALID_ARG;
-    if (b < 2 || b > 8) return DQ_ERR_INVALID_ARG;
+    if (b < 2 || b > 16) return DQ_ERR_INVALID_ARG;
     mu_terms_kernel<<<dim3(1), dim3(kSparsifyThreads), 0, as_stream(stream)>>>(x, x_snap, d, b, out);
     DQ_LAUNCH_CHECK();
     return DQ_OK;
@@ -360,7 +360,7 @@ extern "C" int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, cons
     if (b != 32 && !delta) return DQ_ERR_INVALID_ARG;
     if (y && !x_snap) return DQ_ERR_INVALID_ARG;
     if (b != 2 && b != 4 && b != 8 && b != 32) return (b >= 2 && b <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
-    if (b_x != 2 && b_x != 4 && b_x != 8 && b_x != 32) return (b_x >= 2 && b_x <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
+    if (b_x < 2 || (b_x > 16 && b_x != 32)) return DQ_ERR_INVALID_ARG;
     const int64_t row_words = b == 32 ? d : packed_words(d, b);
     if (ld_words < row_words || (M > 1 && ld_words % 4 != 0)) return DQ_ERR_INVALID_ARG;
     const void *ptrs[] = {packed, g_snap, x, y, x_snap, xsum, xq_packed_out};
@@ -368,7 +368,8 @@ extern "C" int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, cons
         if (p && !aligned16(p)) return DQ_ERR_INVALID_ARG;
     hipStream_t st = as_stream(stream);
     const float kappa_f = eta * l1;
-    if (d <= 16384 * 2) {
+    const bool word_aligned_bx = b_x == 2 || b_x == 4 || b_x == 8 || b_x == 32;
+    if (d <= 16384 * 2 && word_aligned_bx) {
         // small model: the whole step in one block, one launch
         const int ch = static_cast<int>(ceil_div(ceil_div(d, 4), kFusedThreads));     // 1..8
         const StreamKey mkey{static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), iter, 0u, DQ_TAG_MODEL};

@@ -78,6 +78,153 @@ int launch_absmax(const float *v, int64_t d, int64_t M, int64_t ld, float *absma
     return DQ_OK;
 }
 
+// ---------------------------------------------------------------- any width 2 <= b <= 16
+// The model-precision study of Section 5.2 varies b_x from 2 to 11, so fields may straddle the
+// 32-bit words of a packed row.  A group of 32 consecutive coordinates always occupies exactly b
+// whole words (words g*b .. g*b+b-1 of the row), so one thread takes one group and streams its
+// fields through a 64-bit shift register: no two threads ever touch the same word.
+constexpr int kGroupCoords = 32;
+
+static inline dim3 grid_for_groups(int64_t d, int64_t M)
+{
+    const int64_t groups = ceil_div(d > 0 ? d : 1, kGroupCoords);
+    return dim3(static_cast<unsigned>(ceil_div(groups, kThreads)), static_cast<unsigned>(M));
+}
+
+__global__ __launch_bounds__(kThreads) void quantize_pack_any_kernel(
+    const float *__restrict__ v, int64_t d, int64_t ld, const float *__restrict__ absmax, int b, StreamKey key,
+    uint32_t worker0, uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words,
+    float *__restrict__ delta_out, uint32_t *__restrict__ status)
+{
+    const int m = blockIdx.y;
+    const float *row = v + static_cast<int64_t>(m) * ld;
+    uint32_t *out = packed + static_cast<int64_t>(m) * ld_words;
+    const Scale s = make_scale(absmax[m], b);
+    key.worker = worker0 + static_cast<uint32_t>(m);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        delta_out[m] = s.delta;
+        if (s.bad && status) atomicOr(status, 1u);
+    }
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    const int64_t base = g * kGroupCoords;
+    if (base >= d) return;
+    const uint64_t mask = (1ull << b) - 1ull;
+    uint64_t window = 0;                     // bits not yet written, low bits first
+    int fill = 0;
+    int64_t wo = g * b;
+    for (int j = 0; j < kGroupCoords; j += 4) {
+        const float4 a = load_quad(row, (base + j) >> 2, d);          // zeros past the end -> code 0
+        const float av[4] = {a.x, a.y, a.z, a.w};
+        uint32_t rw[4] = {0u, 0u, 0u, 0u};
+        if (s.inv_delta != 0.0f && base + j < d) {
+            const uint4 r = stream_block(key, static_cast<uint32_t>((base + j) >> 2));
+            rw[0] = r.x; rw[1] = r.y; rw[2] = r.z; rw[3] = r.w;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int k = (s.inv_delta != 0.0f && base + j + e < d) ? quantize_one(av[e], s, rw[e]) : 0;
+            window |= (static_cast<uint64_t>(static_cast<uint32_t>(k)) & mask) << fill;
+            fill += b;
+            if (fill >= 32) {
+                if (wo < row_words) out[wo] = static_cast<uint32_t>(window);
+                ++wo;
+                window >>= 32;
+                fill -= 32;
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void unpack_dequant_sum_any_kernel(
+    const uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words, const float *__restrict__ delta,
+    int64_t d, int M, int b, float scale, float *__restrict__ out)
+{
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    const int64_t base = g * kGroupCoords;
+    if (base >= d) return;
+    float acc[kGroupCoords];
+#pragma unroll
+    for (int j = 0; j < kGroupCoords; ++j) acc[j] = 0.0f;
+    for (int m = 0; m < M; ++m) {
+        const uint32_t *row = packed + static_cast<int64_t>(m) * ld_words;
+        const float dm = delta[m];
+        uint64_t window = 0;
+        int fill = 0;
+        int64_t wi = g * b;
+#pragma unroll
+        for (int j = 0; j < kGroupCoords; ++j) {
+            if (fill < b) {
+                const uint32_t w = wi < row_words ? row[wi] : 0u;
+                ++wi;
+                window |= static_cast<uint64_t>(w) << fill;
+                fill += 32;
+            }
+            const int k = sext_field(static_cast<uint32_t>(window), 0, static_cast<unsigned>(b));
+            window >>= b;
+            fill -= b;
+            acc[j] = fmaf(dm, static_cast<float>(k), acc[j]);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < kGroupCoords; j += 4)
+        store_quad(out, (base + j) >> 2, d, make_float4(scale * acc[j], scale * acc[j + 1], scale * acc[j + 2], scale * acc[j + 3]));
+}
+
+// int8 codes <-> fields of any width 2 <= b <= 8
+__global__ __launch_bounds__(kThreads) void pack_any_kernel(const int8_t *__restrict__ codes, int64_t ld_codes, int64_t d,
+                                                            int b, uint32_t *__restrict__ packed, int64_t ld_words,
+                                                            int64_t row_words)
+{
+    const int m = blockIdx.y;
+    const int8_t *in = codes + static_cast<int64_t>(m) * ld_codes;
+    uint32_t *out = packed + static_cast<int64_t>(m) * ld_words;
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    const int64_t base = g * kGroupCoords;
+    if (base >= d) return;
+    const uint64_t mask = (1ull << b) - 1ull;
+    uint64_t window = 0;
+    int fill = 0;
+    int64_t wo = g * b;
+    for (int j = 0; j < kGroupCoords; ++j) {
+        const int k = base + j < d ? in[base + j] : 0;
+        window |= (static_cast<uint64_t>(static_cast<uint32_t>(k)) & mask) << fill;
+        fill += b;
+        if (fill >= 32) {
+            if (wo < row_words) out[wo] = static_cast<uint32_t>(window);
+            ++wo;
+            window >>= 32;
+            fill -= 32;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void unpack_any_kernel(const uint32_t *__restrict__ packed, int64_t ld_words,
+                                                              int64_t row_words, int64_t d, int b,
+                                                              int8_t *__restrict__ codes, int64_t ld_codes)
+{
+    const int m = blockIdx.y;
+    const uint32_t *row = packed + static_cast<int64_t>(m) * ld_words;
+    int8_t *out = codes + static_cast<int64_t>(m) * ld_codes;
+    const int64_t g = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    const int64_t base = g * kGroupCoords;
+    if (base >= d) return;
+    uint64_t window = 0;
+    int fill = 0;
+    int64_t wi = g * b;
+    for (int j = 0; j < kGroupCoords; ++j) {
+        if (fill < b) {
+            const uint32_t w = wi < row_words ? row[wi] : 0u;
+            ++wi;
+            window |= static_cast<uint64_t>(w) << fill;
+            fill += 32;
+        }
+        const int k = sext_field(static_cast<uint32_t>(window), 0, static_cast<unsigned>(b));
+        window >>= b;
+        fill -= b;
+        if (base + j < d) out[base + j] = static_cast<int8_t>(k);
+    }
+}
+
 // ---------------------------------------------------------------- quantize (+pack)
 // FIELD = width of the stored field (2, 4, 8 bits); `b` = bits of the code range.
 // With FIELD == 8 and any b in [2,8] the output words are four int8 codes each.
@@ -117,7 +264,10 @@ int launch_quantize_pack(const float *v, int64_t d, int64_t M, int64_t ld, int b
     case 8: quantize_pack_kernel<8><<<grid, block, 0, st>>>(v, d, ld, absmax, b, key, worker0, packed, ld_words, row_words, delta_out, status); break;
     case 4: quantize_pack_kernel<4><<<grid, block, 0, st>>>(v, d, ld, absmax, b, key, worker0, packed, ld_words, row_words, delta_out, status); break;
     case 2: quantize_pack_kernel<2><<<grid, block, 0, st>>>(v, d, ld, absmax, b, key, worker0, packed, ld_words, row_words, delta_out, status); break;
-    default: return DQ_ERR_UNSUPPORTED;
+    default:
+        if (field != b || b < 2 || b > 16) return DQ_ERR_UNSUPPORTED;
+        quantize_pack_any_kernel<<<grid_for_groups(d, M), block, 0, st>>>(v, d, ld, absmax, b, key, worker0, packed, ld_words, row_words, delta_out, status);
+        break;
     }
     DQ_LAUNCH_CHECK();
     return DQ_OK;
@@ -149,7 +299,10 @@ int launch_unpack_dequant_sum(const uint32_t *packed, int64_t ld_words, const fl
     case 8: unpack_dequant_sum_kernel<8><<<grid, block, 0, st>>>(packed, ld_words, row_words, delta, d, static_cast<int>(M), scale, out); break;
     case 4: unpack_dequant_sum_kernel<4><<<grid, block, 0, st>>>(packed, ld_words, row_words, delta, d, static_cast<int>(M), scale, out); break;
     case 2: unpack_dequant_sum_kernel<2><<<grid, block, 0, st>>>(packed, ld_words, row_words, delta, d, static_cast<int>(M), scale, out); break;
-    default: return DQ_ERR_UNSUPPORTED;
+    default:
+        if (b < 2 || b > 16) return DQ_ERR_UNSUPPORTED;
+        unpack_dequant_sum_any_kernel<<<grid_for_groups(d, 1), block, 0, st>>>(packed, ld_words, row_words, delta, d, static_cast<int>(M), b, scale, out);
+        break;
     }
     DQ_LAUNCH_CHECK();
     return DQ_OK;
@@ -259,7 +412,7 @@ static int32_t quantize_common(const float *v, int64_t d, int64_t M, int64_t ld,
                                uint32_t *status, void *stream)
 {
     if (d < 0 || M <= 0 || !absmax || !delta_out) return DQ_ERR_INVALID_ARG;
-    if (b < 2 || b > 8 || b > field) return DQ_ERR_INVALID_ARG;
+    if (b < 2 || b > 16 || b > field) return DQ_ERR_INVALID_ARG;
     const int64_t row_words = packed_words(d, field);
     if (d > 0) {
         if (!rows_ok(v, M, ld, d, 4)) return DQ_ERR_INVALID_ARG;
@@ -291,7 +444,7 @@ extern "C" int32_t dq_quantize_pack(const float *v, int64_t d, int64_t M, int64_
                                     uint32_t worker0, uint32_t *packed_out, int64_t ld_words, float *delta_out,
                                     uint32_t *status, void *stream)
 {
-    if (b != 2 && b != 4 && b != 8) return (b >= 2 && b <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
+    if (b < 2 || b > 16) return DQ_ERR_INVALID_ARG;
     return quantize_common(v, d, M, ld, b, b, absmax, absmax_given, seed, iter, tag, worker0, packed_out, ld_words,
                            delta_out, status, stream);
 }
@@ -313,7 +466,7 @@ extern "C" int32_t dq_pack(const int8_t *codes, int64_t ld_codes, int64_t d, int
                            uint32_t *packed_out, int64_t ld_words, void *stream)
 {
     if (d < 0 || M <= 0) return DQ_ERR_INVALID_ARG;
-    if (b != 2 && b != 4 && b != 8) return (b >= 2 && b <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
+    if (b < 2 || b > 8) return DQ_ERR_INVALID_ARG;
     if (d == 0) return DQ_OK;
     const int64_t row_words = packed_words(d, b);
     if ((ld_codes % 4) != 0) return DQ_ERR_INVALID_ARG;
@@ -324,7 +477,8 @@ extern "C" int32_t dq_pack(const int8_t *codes, int64_t ld_codes, int64_t d, int
     hipStream_t st = as_stream(stream);
     if (b == 8) pack_kernel<8><<<grid, block, 0, st>>>(cw, cld, crw, d, packed_out, ld_words, row_words);
     else if (b == 4) pack_kernel<4><<<grid, block, 0, st>>>(cw, cld, crw, d, packed_out, ld_words, row_words);
-    else pack_kernel<2><<<grid, block, 0, st>>>(cw, cld, crw, d, packed_out, ld_words, row_words);
+    else if (b == 2) pack_kernel<2><<<grid, block, 0, st>>>(cw, cld, crw, d, packed_out, ld_words, row_words);
+    else pack_any_kernel<<<grid_for_groups(d, M), block, 0, st>>>(codes, ld_codes, d, b, packed_out, ld_words, row_words);
     DQ_LAUNCH_CHECK();
     return DQ_OK;
 }
@@ -333,7 +487,7 @@ extern "C" int32_t dq_unpack(const uint32_t *packed, int64_t ld_words, int64_t d
                              int8_t *codes_out, int64_t ld_codes, void *stream)
 {
     if (d < 0 || M <= 0) return DQ_ERR_INVALID_ARG;
-    if (b != 2 && b != 4 && b != 8) return (b >= 2 && b <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
+    if (b < 2 || b > 8) return DQ_ERR_INVALID_ARG;
     if (d == 0) return DQ_OK;
     const int64_t row_words = packed_words(d, b);
     if (!rows_ok(packed, M, ld_words, row_words, 4) || !rows_ok(codes_out, M, ld_codes, d, 16)) return DQ_ERR_INVALID_ARG;
@@ -341,7 +495,8 @@ extern "C" int32_t dq_unpack(const uint32_t *packed, int64_t ld_words, int64_t d
     hipStream_t st = as_stream(stream);
     if (b == 8) unpack_kernel<8><<<grid, block, 0, st>>>(packed, ld_words, row_words, d, codes_out, ld_codes);
     else if (b == 4) unpack_kernel<4><<<grid, block, 0, st>>>(packed, ld_words, row_words, d, codes_out, ld_codes);
-    else unpack_kernel<2><<<grid, block, 0, st>>>(packed, ld_words, row_words, d, codes_out, ld_codes);
+    else if (b == 2) unpack_kernel<2><<<grid, block, 0, st>>>(packed, ld_words, row_words, d, codes_out, ld_codes);
+    else unpack_any_kernel<<<grid_for_groups(d, M), block, 0, st>>>(packed, ld_words, row_words, d, b, codes_out, ld_codes);
     DQ_LAUNCH_CHECK();
     return DQ_OK;
 }
@@ -350,7 +505,7 @@ extern "C" int32_t dq_unpack_dequant_sum(const uint32_t *packed, int64_t ld_word
                                          int64_t M, int32_t b, float scale, float *out, void *stream)
 {
     if (d < 0 || M <= 0 || !delta) return DQ_ERR_INVALID_ARG;
-    if (b != 2 && b != 4 && b != 8) return (b >= 2 && b <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
+    if (b < 2 || b > 16) return DQ_ERR_INVALID_ARG;
     if (d == 0) return DQ_OK;
     if (!rows_ok(packed, M, ld_words, packed_words(d, b), 4) || !out || !aligned16(out)) return DQ_ERR_INVALID_ARG;
     return launch_unpack_dequant_sum(packed, ld_words, delta, d, M, b, scale, out, as_stream(stream));

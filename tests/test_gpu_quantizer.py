@@ -157,13 +157,10 @@ def test_invalid_arguments(dq):
     v = torch.zeros(64, device="cuda")
     a = torch.zeros(1, device="cuda")
     p = torch.zeros(16, dtype=torch.int32, device="cuda")
-    for b in (1, 9, 0):
+    for b in (1, 17, 0):
         with pytest.raises(dq.DqError) as e:
             dq.dq_quantize_pack(v, b, a, False, 0, 0, 0, 0, p, a)
         assert e.value.code == dq.ERR_INVALID_ARG
-    with pytest.raises(dq.DqError) as e:
-        dq.dq_quantize_pack(v, 3, a, False, 0, 0, 0, 0, p, a)
-    assert e.value.code == dq.ERR_UNSUPPORTED
     with pytest.raises(dq.DqError) as e:          # misaligned input
         dq.dq_quantize_pack(v[1:], 4, a, False, 0, 0, 0, 0, p, a)
     assert e.value.code == dq.ERR_INVALID_ARG

@@ -52,8 +52,7 @@ def csr(n=72000, d=20958):
 
 def test_quantizer_argument_checks(lib):
     q = lambda b, v=P, d=64, M=1, ld=64, out=P, ldw=16: lib.dq_quantize_pack(v, d, M, ld, b, P, 0, 0, 0, 0, 0, out, ldw, P, None, None)
-    assert q(1) == INVALID and q(0) == INVALID and q(9) == INVALID and q(33) == INVALID
-    assert q(3) == UNSUPPORTED and q(5) == UNSUPPORTED            # valid code range, no packed layout
+    assert q(1) == INVALID and q(0) == INVALID and q(17) == INVALID and q(33) == INVALID      # widths 2..16 only
     assert q(8, v=None) == INVALID and q(8, out=None) == INVALID
     assert q(8, v=P + 4) == INVALID                                  # misaligned
     assert q(8, d=-1) == INVALID and q(8, M=0) == INVALID
@@ -61,10 +60,10 @@ def test_quantizer_argument_checks(lib):
     assert q(8, M=2, ld=66) == INVALID                               # stride not a multiple of 4
     assert q(8, d=64, ldw=15) == INVALID                             # packed row too short
     assert lib.dq_quantize(P, 64, 1, 64, 8, P, 0, 0, 0, 0, 0, P, 62, P, None, None) == INVALID
-    assert lib.dq_pack(P, 64, 64, 1, 3, P, 16, None) == UNSUPPORTED
+    assert lib.dq_pack(P, 64, 64, 1, 9, P, 16, None) == INVALID                         # int8 codes: at most 8 bits
     assert lib.dq_pack(P, 64, 64, 1, 1, P, 16, None) == INVALID
     assert lib.dq_unpack_dequant_sum(P, 16, None, 64, 1, 8, 1.0, P, None) == INVALID     # no delta
-    assert lib.dq_unpack_dequant_sum(P, 16, P, 64, 1, 7, 1.0, P, None) == UNSUPPORTED
+    assert lib.dq_unpack_dequant_sum(P, 16, P, 64, 1, 17, 1.0, P, None) == INVALID
     assert lib.dq_absmax(P, 64, 1, 64, None, None) == INVALID
     assert lib.dq_sample_indices(0, 1, 1, 0, 0, 0, P, None) == INVALID
     assert lib.dq_sample_indices(2**31, 1, 1, 0, 0, 0, P, None) == INVALID
@@ -73,8 +72,8 @@ def test_quantizer_argument_checks(lib):
 def test_master_argument_checks(lib):
     m = lambda b=8, bx=8, y=None, xs=P, d=64, ldw=16, delta=P: lib.dq_master_step(
         P, ldw, delta, 2, b, 0.5, P, P, y, xs, None, 0.1, 0.5, 0.0, d, bx, 0, 0, P, P, P, None, None)
-    assert m(b=3) == UNSUPPORTED and m(bx=5) == UNSUPPORTED
-    assert m(b=1) == INVALID and m(bx=64) == INVALID
+    assert m(b=3) == UNSUPPORTED                                     # gradient messages: 2, 4, 8 or 32 bits
+    assert m(b=1) == INVALID and m(bx=64) == INVALID and m(bx=17) == INVALID and m(bx=1) == INVALID
     assert m(y=P, xs=None) == INVALID                                # momentum update without a snapshot
     assert m(d=0) == INVALID and m(ldw=3) == INVALID and m(delta=None) == INVALID
     assert m(ldw=18) == INVALID                                      # M > 1 rows must keep 16-byte alignment
@@ -94,7 +93,7 @@ def test_problem_and_gradient_argument_checks(lib):
     assert lib.dq_full_grad(C.byref(none), P, P, None, None, P, 1 << 40, None) == INVALID
     w = lambda prob, b=8, bx=8, ldw=1024, ws=P, wsb=1 << 40, idx=None, xq=P: lib.dq_worker_step(
         C.byref(prob), idx, 32, 256, xq, P, bx, 0, P, None, 0, b, 0, 0, 0, P, ldw, P, None, None, 0, None, ws, wsb, None)
-    assert w(p, b=3) == UNSUPPORTED and w(p, b=16) == INVALID and w(p, bx=6) == UNSUPPORTED
+    assert w(p, b=3) == UNSUPPORTED and w(p, b=16) == INVALID and w(p, bx=17) == INVALID and w(p, bx=1) == INVALID
     assert w(p, ldw=1023) == INVALID and w(p, xq=None) == INVALID
     assert w(p, ws=None, wsb=0) == WORKSPACE and w(p, wsb=1024) == WORKSPACE
 
