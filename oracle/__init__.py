@@ -378,7 +378,7 @@ def sq_distance(x, x_snap) -> float:
     return float(lib().ref_sq_distance(_p(x), _p(x_snap), x.size))
 
 
-def smallest_bx(x, x_snap, mu: float, candidates=(2, 4, 8)) -> int:
+def smallest_bx(x, x_snap, mu: float, candidates=tuple(range(2, 17))) -> int:
     """Smallest b_x among `candidates` that satisfies condition (2) for this mu; 32 if none does."""
     r = sq_distance(x, x_snap)
     for b in sorted(candidates):

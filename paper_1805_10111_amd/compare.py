@@ -8,6 +8,13 @@ the threshold, and the saving relative to AsyFPG -- the quantity of Fig. 4 and T
 here on synthetic data.
 
     python -m paper_1805_10111_amd.compare --config C1 --epochs 6 --threshold 0.6
+
+With --mu-sweep it reports instead the study of the precision-loss parameter mu of Section 5.2 (right half of
+Table 1): AsyLPG is run once per model width b_x; for each width the run records, round by round, the smallest
+mu for which condition (2) holds (E||Q(x)-x||^2 / ||x-x_snap||^2), and the bits transmitted until the
+objective falls below the threshold.  A given mu then admits every width whose recorded ratio stays below it.
+
+    python -m paper_1805_10111_amd.compare --config C1 --mu-sweep --widths 2 3 4 5 6 8 10 --epochs 6
 """
 from __future__ import annotations
 
@@ -57,6 +64,39 @@ def run_comparison(cfg, prob, epochs: int, threshold: float, b: int, m: int | No
     return out
 
 
+def mu_sweep(cfg, prob, widths, epochs: int, threshold: float, b: int, m: int | None = None, seed: int = 0,
+             mus=(0.005, 0.01, 0.05, 0.1, 0.5, 2.0, 10.0, 50.0, 150.0, 800.0)):
+    """Per model width b_x: the mu that condition (2) needs (median and 90th percentile over the rounds after the
+    first of each epoch) and the bits to reach the threshold; per mu: the smallest admissible width."""
+    import numpy as np
+    import paper_1805_10111_amd as dq
+    from paper_1805_10111_amd.driver import DoubleQuantTrainer
+
+    P = dq.DeviceProblem.from_host(prob)
+    m = cfg.m if m is None else m
+    rows = {}
+    for b_x in sorted(widths):
+        tr = DoubleQuantTrainer(P, "asylpg", cfg.M, cfg.B, b_x, b, m, cfg.lr, seed=seed)
+        bits_at, objs, hit = [], [], None
+        for e in range(epochs):
+            tr.run_epoch(record_mu=True)
+            objs.append(tr.log.objectives[-1])
+            bits_at.append(tr.log.bits_up + cfg.M * tr.log.bits_down)
+        objs.append(tr.objective(tr.x_snap))
+        for e in range(epochs):
+            if objs[e + 1] < threshold:
+                hit = bits_at[e]
+                break
+        ratios = np.array([err / dist for (_, t, err, dist) in tr.mu_trace if dist > 0.0])
+        rows[b_x] = {"mu_needed_median": float(np.median(ratios)), "mu_needed_p90": float(np.quantile(ratios, 0.9)),
+                     "final_objective": round(objs[-1], 6), "bits_total": bits_at[-1], "bits_to_threshold": hit}
+    choice = {}
+    for mu in mus:
+        ok = [b_x for b_x in sorted(rows) if rows[b_x]["mu_needed_p90"] <= mu]
+        choice[str(mu)] = ok[0] if ok else None
+    return {"per_width": rows, "smallest_width_for_mu": choice}
+
+
 def main():
     import synth
     ap = argparse.ArgumentParser()
@@ -66,9 +106,16 @@ def main():
     ap.add_argument("--rounds", type=int, default=None, help="rounds per epoch (default: the config's)")
     ap.add_argument("--threshold", type=float, default=0.6)
     ap.add_argument("--bits", type=int, default=8, help="b of the quantized algorithms")
+    ap.add_argument("--mu-sweep", action="store_true", help="study of mu / b_x instead of the six-algorithm comparison")
+    ap.add_argument("--widths", type=int, nargs="+", default=[2, 3, 4, 5, 6, 7, 8, 9, 10, 11])
     args = ap.parse_args()
     cfg = synth.CONFIGS[args.config]
     prob = synth.make_problem(cfg, n=args.n)
+    if args.mu_sweep:
+        res = mu_sweep(cfg, prob, args.widths, args.epochs, args.threshold, args.bits, args.rounds)
+        print(json.dumps({"config": cfg.name, "n": prob.n, "d": prob.d, "M": cfg.M, "B": cfg.B, "threshold": args.threshold,
+                          "b": args.bits, "mu_sweep": res}, indent=1))
+        return
     res = run_comparison(cfg, prob, args.epochs, args.threshold, args.bits, args.rounds)
     print(json.dumps({"config": cfg.name, "n": prob.n, "d": prob.d, "M": cfg.M, "B": cfg.B, "threshold": args.threshold,
                       "b": args.bits, "results": res}, indent=1))

@@ -153,7 +153,7 @@ class DoubleQuantTrainer:
         return float(self.obj.item())
 
 
-def smallest_bx(x: torch.Tensor, x_snap: torch.Tensor, mu: float, candidates=(2, 4, 8)) -> int:
+def smallest_bx(x: torch.Tensor, x_snap: torch.Tensor, mu: float, candidates=tuple(range(2, 17))) -> int:
     """Smallest b_x among `candidates` for which condition (2) holds with this mu (32 if none does):
     the selection procedure behind the mu / b_x table of Section 5.2."""
     out = torch.zeros((len(candidates), 2), dtype=torch.float64, device=x.device)

@@ -175,4 +175,4 @@ def test_mu_terms_degenerate_and_bx_choice(dq):
     for mu in (1e-6, 1e-3, 0.05, 1.0, 100.0):
         assert smallest_bx(dev(x), dev(xs), mu) == oracle.smallest_bx(x, xs, mu)
     with pytest.raises(dq.DqError):
-        dq.dq_mu_terms(dev(x), dev(xs), 9, out)
+        dq.dq_mu_terms(dev(x), dev(xs), 17, out)

@@ -201,3 +201,21 @@ def test_mu_terms_any_width(dq):
         assert abs(r - oracle.sq_distance(x, xs)) <= 1e-9 * r
         assert prev is None or e < prev
         prev = e
+
+
+def test_mu_sweep_reproduces_the_trend_of_the_model_precision_study(dq):
+    """Section 5.2 (right half of Table 1): a larger mu admits a smaller b_x; each extra bit divides the mu that
+    condition (2) needs by about four; and the bits sent per epoch grow with b_x."""
+    from paper_1805_10111_amd.compare import mu_sweep
+    cfg = synth.CONFIGS["C1"]
+    p = synth.make_problem(cfg, n=600, d=200)
+    res = mu_sweep(cfg, p, widths=[3, 4, 5, 6, 8, 10], epochs=2, threshold=0.0, b=8, m=10, seed=1)
+    rows = res["per_width"]
+    need = [rows[w]["mu_needed_median"] for w in (3, 4, 5, 6, 8, 10)]
+    assert all(a > b for a, b in zip(need, need[1:]))
+    assert 8.0 < rows[4]["mu_needed_median"] / rows[6]["mu_needed_median"] < 32.0      # two bits: about 16x
+    bits = [rows[w]["bits_total"] for w in (3, 4, 5, 6, 8, 10)]
+    assert all(a < b for a, b in zip(bits, bits[1:]))
+    ch = res["smallest_width_for_mu"]
+    picked = [ch[k] for k in sorted(ch, key=float) if ch[k] is not None]
+    assert picked == sorted(picked, reverse=True)                  # larger mu, smaller (or equal) width

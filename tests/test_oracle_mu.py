@@ -68,7 +68,12 @@ def test_distance_and_bx_choice():
     assert oracle.smallest_bx(x, xs, mu=1.01 * e[2] / r) == 2
     assert oracle.smallest_bx(x, xs, mu=1.01 * e[4] / r) == 4
     assert oracle.smallest_bx(x, xs, mu=1.01 * e[8] / r) == 8
-    assert oracle.smallest_bx(x, xs, mu=0.5 * e[8] / r) == 32
+    assert oracle.smallest_bx(x, xs, mu=0.5 * e[8] / r, candidates=(2, 4, 8)) == 32
+    # every width from 2 to 16 is a candidate by default (Section 5.2 searches b_x over all of them):
+    # one more bit divides the expected error by about four
+    assert oracle.smallest_bx(x, xs, mu=0.5 * e[8] / r) == 9
+    assert oracle.smallest_bx(x, xs, mu=1.01 * oracle.expected_sq_error(x, 11) / r) == 11
+    assert oracle.smallest_bx(x, xs, mu=1e-3 * oracle.expected_sq_error(x, 16) / r) == 32
     k, dl, _ = oracle.quantize(x, 8, 1, 1, oracle.MASTER_ID, oracle.TAG_MODEL)
     realised, dist = oracle.mu_terms(k, dl, x, xs)
     assert np.isclose(dist, r) and abs(realised / e[8] - 1) < 0.2
