@@ -86,6 +86,12 @@ def lib() -> C.CDLL:
         _lib.ref_unpack_wide.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
         _lib.ref_dequantize_wide.restype = None
         _lib.ref_dequantize_wide.argtypes = [C.c_void_p, C.c_float, C.c_int64, C.c_void_p]
+        _lib.ref_master_update_each.restype = None
+        _lib.ref_master_update_each.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
+                                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_float]
+        _lib.ref_master_update_each_full.restype = None
+        _lib.ref_master_update_each_full.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
+                                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_float, C.c_float]
         _lib.ref_sample_indices.restype = None
         _lib.ref_sample_indices.argtypes = [C.c_int64, C.c_int64, C.c_uint64, C.c_uint32, C.c_uint32, C.c_void_p]
         _lib.ref_objective.restype = C.c_double
@@ -343,6 +349,27 @@ def master_update_full(grads, scale, g_snap, x, y=None, x_snap=None, xsum=None, 
         assert a is None or (a.dtype == np.float32 and a.flags.c_contiguous and a.size == d)
     lib().ref_master_update_full(_p(grads), M, d, np.float32(scale), _p(g_snap), _p(x), _p(y), _p(x_snap),
                                  _p(xsum), np.float32(eta), np.float32(theta), np.float32(l1))
+
+
+def master_update_each(codes, delta, g_snap, x, y=None, x_snap=None, xsum=None, eta=0.0, theta=0.0, l1=0.0) -> None:
+    """One master update per received gradient (the M messages of a round in worker order); in place."""
+    codes = np.ascontiguousarray(codes, dtype=np.int8)
+    M, d = codes.shape
+    delta = _f32(delta)
+    assert delta.size == M
+    for a in (g_snap, x, y, x_snap, xsum):
+        assert a is None or (a.dtype == np.float32 and a.flags.c_contiguous and a.size == d)
+    lib().ref_master_update_each(_p(codes), _p(delta), M, d, _p(g_snap), _p(x), _p(y), _p(x_snap), _p(xsum),
+                                 np.float32(eta), np.float32(theta), np.float32(l1))
+
+
+def master_update_each_full(grads, g_snap, x, y=None, x_snap=None, xsum=None, eta=0.0, theta=0.0, l1=0.0) -> None:
+    grads = np.ascontiguousarray(grads, dtype=np.float32)
+    M, d = grads.shape
+    for a in (g_snap, x, y, x_snap, xsum):
+        assert a is None or (a.dtype == np.float32 and a.flags.c_contiguous and a.size == d)
+    lib().ref_master_update_each_full(_p(grads), M, d, _p(g_snap), _p(x), _p(y), _p(x_snap), _p(xsum),
+                                      np.float32(eta), np.float32(theta), np.float32(l1))
 
 
 def acc_mix(y, x_snap, theta) -> np.ndarray:

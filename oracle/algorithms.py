@@ -10,6 +10,10 @@ Bounded delay (Assumption 3, Section 3.2) can be emulated: with ``tau > 0`` the 
 into tau+1 contiguous groups and group g computes its gradient on the model message of round
 t - g (of round 0 while t < g), i.e. on a model that is g rounds stale.
 
+With ``each=True`` the master follows its rule in Alg. 1 literally: every received gradient triggers
+its own update with the full step (the M messages of a round in worker order) instead of one update with
+their mean; the model is still sent once per round.  Alg. 3 then averages M*m iterates for the snapshot.
+
 ``b_x = 32`` / ``b = 32`` switch the corresponding quantization off (the message is the
 float32 vector, 32*d bits): with both off this is AsyFPG / Acc-AsyFPG, with only the model
 unquantized it is the gradient-quantized QSVRG arrangement of Section 5.1.
@@ -23,7 +27,7 @@ from typing import List, Optional
 import numpy as np
 
 from . import (MASTER_ID, TAG_GRAD, TAG_MODEL, RefProblem, acc_mix, acc_snapshot, dequantize, dequantize_wide,
-               full_grad, master_update, master_update_full, objective, pack, pack_wide, quantize, quantize_wide,
+               full_grad, master_update, master_update_each, master_update_each_full, master_update_full, objective, pack, pack_wide, quantize, quantize_wide,
                sample_indices, sparsify, unpack, unpack_wide, vr_grad)
 
 
@@ -95,7 +99,7 @@ def worker_delay(w: int, M: int, tau: int) -> int:
 
 
 def run(prob, algo: str, M: int, B: int, b_x: int, b: int, m: int, S: int, lr: float, seed: int = 0,
-        x0: Optional[np.ndarray] = None, eval_objective: bool = True, tau: int = 0) -> Trace:
+        x0: Optional[np.ndarray] = None, eval_objective: bool = True, tau: int = 0, each: bool = False) -> Trace:
     rp = RefProblem(prob)
     d = rp.d
     tr = Trace()
@@ -135,13 +139,17 @@ def run(prob, algo: str, M: int, B: int, b_x: int, b: int, m: int, S: int, lr: f
                 deltas[w] = dlt
                 tr.bits_up += bits
             yy, ss = (y, xsum) if algo == "acc" else (None, None)     # Alg. 3 / Alg. 1, master (ii)
-            if b == 32:
+            if each and b == 32:
+                master_update_each_full(grads, g_snap, x, yy, x_snap, ss, eta=eta, theta=theta, l1=rp.l1)
+            elif each:
+                master_update_each(codes, deltas, g_snap, x, yy, x_snap, ss, eta=eta, theta=theta, l1=rp.l1)
+            elif b == 32:
                 master_update_full(grads, np.float32(1.0 / M), g_snap, x, yy, x_snap, ss, eta=eta, theta=theta, l1=rp.l1)
             else:
                 master_update(codes, deltas, np.float32(1.0 / M), g_snap, x, yy, x_snap, ss, eta=eta, theta=theta,
                               l1=rp.l1)
         if algo == "acc":
-            x_snap = acc_snapshot(xsum, m)                      # Alg. 3, epoch end
+            x_snap = acc_snapshot(xsum, m * M if each else m)   # Alg. 3, epoch end: mean of the iterates
         else:
             x_snap = x.copy()                                   # Alg. 1, epoch end
     if eval_objective:

@@ -501,6 +501,35 @@ void ref_master_update_full(const float *grads, int64_t M, int64_t d, float scal
     }
 }
 
+/* Alg. 1, master (ii) (Alg. 3, master (ii) when y is given) taken one received gradient at a
+ * time, as the paper states the master's rule: every message triggers its own update of the
+ * model with the full step size.  The M messages of a round are applied in worker order:
+ *   for w:  u = delta_w * k_w + grad f(snapshot);   x <- prox(x - eta u)      (Alg. 1)
+ *           y <- prox(y - eta u);  x <- snapshot + theta (y - snapshot);  xsum += x   (Alg. 3)
+ * (xsum therefore gains M terms per call). */
+void ref_master_update_each(const int8_t *codes, const float *delta, int64_t M, int64_t d,
+                            const float *g_snap, float *x, float *y, const float *x_snap, float *xsum,
+                            float eta, float theta, float l1)
+{
+    const float kappa = eta * l1;
+    for (int64_t w = 0; w < M; ++w)
+        for (int64_t j = 0; j < d; ++j) {
+            float g = delta[w] * (float)codes[w * d + j];
+            master_apply(j, g, 1.0f, g_snap, x, y, x_snap, xsum, eta, theta, kappa);
+        }
+}
+
+/* The same with unquantized gradients (M rows of d floats). */
+void ref_master_update_each_full(const float *grads, int64_t M, int64_t d,
+                                 const float *g_snap, float *x, float *y, const float *x_snap, float *xsum,
+                                 float eta, float theta, float l1)
+{
+    const float kappa = eta * l1;
+    for (int64_t w = 0; w < M; ++w)
+        for (int64_t j = 0; j < d; ++j)
+            master_apply(j, grads[w * d + j], 1.0f, g_snap, x, y, x_snap, xsum, eta, theta, kappa);
+}
+
 /* Momentum mix used at the start of an epoch of Alg. 3, in the same
  * form as its master update:  x = xs + theta (y - xs)  ( = theta y + (1-theta) xs ). */
 void ref_acc_mix(const float *y, const float *x_snap, float theta, int64_t d, float *x_out)
