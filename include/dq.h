@@ -241,6 +241,19 @@ int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, const float *de
                        uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out,
                        uint32_t *status, void *stream);
 
+/* The master's rule of Alg. 1 (Alg. 3 with y != NULL) taken one received gradient at a time: the M
+ * messages are applied in worker order, each as its own update with the full step,
+ *   for m:  u = delta[m]*k_m + g_snap;  x <- prox_{eta h}(x - eta*u)
+ *           (Alg. 3: y <- prox_{eta h}(y - eta*u);  x <- x_snap + theta*(y - x_snap);  xsum += x, i.e. M terms per call),
+ * then the model is quantized and packed once, exactly as in dq_master_step.  Same arguments
+ * without `scale`, same limits. */
+int32_t dq_master_step_each(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
+                            const float *g_snap, float *x, float *y, const float *x_snap,
+                            float *xsum, float eta, float theta, float l1, int64_t d,
+                            int32_t b_x, uint64_t seed, uint32_t iter,
+                            uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out,
+                            uint32_t *status, void *stream);
+
 /* The two sides of the precision-loss condition on the model quantization (eq. (2); eq. (4) for
  * Alg. 3):  out[0] = E_Q ||Q_(delta_x,b)(x) - x||^2 over the rounding decisions, which is
  * delta_x^2 * sum_i p_i (1 - p_i) (proof of Lemma 5; nothing is sampled), and
@@ -269,6 +282,9 @@ typedef struct dq_run_config {
     int32_t tau;         /* emulated bounded delay (Assumption 3): 0 = every worker reads the current model;
                             tau > 0: the workers form tau+1 contiguous groups, worker w belongs to group
                             g = floor(w*(tau+1)/M) and reads the model message of round max(0, t-g) */
+    int32_t each;        /* 0: one master update per round with the mean of the M gradients (dq_master_step,
+                            scale 1/M); 1: one update per received gradient (dq_master_step_each); Alg. 3 then
+                            averages m*M iterates for its snapshot */
 } dq_run_config;
 
 /* Device buffers of a run (host struct holding device pointers; all caller-owned).
@@ -295,8 +311,8 @@ typedef struct dq_run_state {
 
 /* Enqueues rounds t0 .. t0+rounds-1 of epoch `epoch` (0-based) of Alg. 1, 2 or 3: per round the
  * worker side (dq_worker_step with in-kernel sampling; the flag-bit case of Section 4.1 at the
- * first round of an epoch whose start equals the snapshot) and the master side (dq_master_step,
- * mean over the M workers, model re-quantized for the next round).  Random streams use
+ * first round of an epoch whose start equals the snapshot) and the master side (dq_master_step with
+ * the mean over the M workers, or dq_master_step_each; model re-quantized for the next round).  Random streams use
  * iter = epoch*m + t.  eta, theta: step size and momentum weight of this epoch (theta unused by
  * Alg. 1/2).  The epoch prologue (dq_full_grad, dq_acc_mix / copy) and epilogue stay with the
  * caller.  worker_events (host array, nullable): 2*rounds hipEvent_t handles; for round k the

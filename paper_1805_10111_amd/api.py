@@ -48,7 +48,7 @@ class _Problem(C.Structure):
 
 class RunConfig(C.Structure):
     _fields_ = [("algo", C.c_int32), ("M", C.c_int64), ("B", C.c_int64), ("b_x", C.c_int32), ("b", C.c_int32),
-                ("m", C.c_int64), ("seed", C.c_uint64), ("tau", C.c_int32)]
+                ("m", C.c_int64), ("seed", C.c_uint64), ("tau", C.c_int32), ("each", C.c_int32)]
 
 
 class RunState(C.Structure):
@@ -83,6 +83,8 @@ _SIGS = {
                               _vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _i64, _vp]),
     "dq_master_step": (_i32, [_vp, _i64, _vp, _i64, _i32, _f32, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _i64,
                               _i32, _u64, _u32, _vp, _vp, _vp, _vp, _vp]),
+    "dq_master_step_each": (_i32, [_vp, _i64, _vp, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _i64,
+                                   _i32, _u64, _u32, _vp, _vp, _vp, _vp, _vp]),
     "dq_acc_mix": (_i32, [_vp, _vp, _f32, _i64, _vp, _vp]),
     "dq_acc_snapshot": (_i32, [_vp, _i64, _i64, _vp, _vp]),
     "dq_sparse_stream_words": (_i64, [_i64, _i32]),
@@ -316,6 +318,17 @@ def dq_master_step(packed, delta, M, b, scale, g_snap, x, y, x_snap, xsum, eta, 
         _ptr(absmax_x_out, torch.float32, "absmax_x_out"), _ptr(status, torch.int32, "status"), _stream()))
 
 
+def dq_master_step_each(packed, delta, M, b, g_snap, x, y, x_snap, xsum, eta, theta, l1, b_x, seed, it,
+                        xq_packed_out, delta_x_out, absmax_x_out, status=None) -> None:
+    d = x.numel()
+    _check("dq_master_step_each", _lib.dq_master_step_each(
+        _ptr(packed, None, "packed"), _row_stride(packed), _ptr(delta, torch.float32, "delta"), M, b,
+        _ptr(g_snap, torch.float32, "g_snap"), _ptr(x, torch.float32, "x"), _ptr(y, torch.float32, "y"),
+        _ptr(x_snap, torch.float32, "x_snap"), _ptr(xsum, torch.float32, "xsum"), eta, theta, l1, d, b_x, seed, it,
+        _ptr(xq_packed_out, None, "xq_packed_out"), _ptr(delta_x_out, torch.float32, "delta_x_out"),
+        _ptr(absmax_x_out, torch.float32, "absmax_x_out"), _ptr(status, torch.int32, "status"), _stream()))
+
+
 def dq_acc_mix(y, x_snap, theta, x_out) -> None:
     _check("dq_acc_mix", _lib.dq_acc_mix(_ptr(y, torch.float32, "y"), _ptr(x_snap, torch.float32, "x_snap"), theta,
                                          y.numel(), _ptr(x_out, torch.float32, "x_out"), _stream()))
@@ -367,6 +380,6 @@ __all__ = [
     "TAG_GRAD", "TAG_MODEL", "TAG_SPARSIFY", "TAG_SAMPLE", "MASTER_ID", "OP_FULL_GRAD", "OP_VR_GRAD",
     "dq_version", "dq_last_device_error", "dq_workspace_bytes", "dq_workspace_init", "new_workspace", "dq_absmax", "dq_quantize", "dq_dequantize",
     "dq_pack", "dq_unpack", "dq_quantize_pack", "dq_unpack_dequant_sum", "dq_sample_indices", "dq_full_grad",
-    "dq_vr_grad", "dq_sparsify", "dq_worker_step", "dq_master_step", "dq_acc_mix", "dq_acc_snapshot",
+    "dq_vr_grad", "dq_sparsify", "dq_worker_step", "dq_master_step", "dq_master_step_each", "dq_acc_mix", "dq_acc_snapshot",
     "dq_run_rounds", "dq_mu_terms", "dq_sparse_stream_words", "dq_sparse_encode", "dq_sparse_decode", "RunConfig", "RunState", "ALGO",
 ]

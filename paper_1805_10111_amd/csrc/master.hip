@@ -15,62 +15,134 @@ constexpr int kThreads = 256;
 
 // ------------------------------------------------------------------ master update
 // FIELD in {2,4,8}: packed codes; FIELD == 32: rows of float32 gradients (delta ignored).
-template <int FIELD, bool ACC>
-__global__ __launch_bounds__(kThreads) void master_update_kernel(
-    const uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words, const float *__restrict__ delta, int M,
-    float scale, const float *__restrict__ g_snap, float *__restrict__ x, float *__restrict__ y,
-    const float *__restrict__ x_snap, float *__restrict__ xsum, float eta, float theta, float kappa, int64_t d,
-    uint32_t *__restrict__ absmax_bits)
+struct MasterArgs {
+    const uint32_t *packed; int64_t ld_words, row_words;
+    const float *delta; int M;
+    float scale;              // mean mode: multiplies the sum of the M decoded gradients
+    int each;                 // != 0: one update per received gradient, in worker order, scale unused
+    const float *g_snap;
+    float *x, *y; const float *x_snap; float *xsum;
+    float eta, theta, kappa;
+    int64_t d;
+};
+
+// Alg. 1, master (ii) (Alg. 3 when ACC) for one direction u on a quad; the state is updated in registers.
+template <bool ACC>
+__device__ __forceinline__ void master_apply_quad(const float (&u)[4], float (&xn)[4], float (&yn)[4], const float (&xs)[4],
+                                                  float (&sm)[4], bool have_sum, float eta, float theta, float kappa)
 {
-    __shared__ uint32_t scratch[kThreads / kWave];
-    const int64_t chunks = (d + 15) / 16;
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
-    uint32_t amax = 0;
-    for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
-        float acc[16];
-        decode_sum16<FIELD>(packed, ld_words, row_words, delta, M, c, d, acc);
-        const int64_t base = c * 16;
-        float gs[16], xv[16], yv[16], xs[16], sm[16];
-        load16(g_snap, base, d, gs);
-        if (ACC) {
-            load16(y, base, d, yv);
-            load16(x_snap, base, d, xs);
-            if (xsum) load16(xsum, base, d, sm);
-        } else {
-            load16(x, base, d, xv);
-        }
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const float u = scale * acc[j] + gs[j];                 // u = Q-mean + grad f(snapshot)
-            if (ACC) {
-                yv[j] = soft_threshold(yv[j] - eta * u, kappa);     // y <- prox(y - eta u)
-                xv[j] = xs[j] + theta * (yv[j] - xs[j]);            // x <- snapshot + theta (y - snapshot)
-                if (xsum) sm[j] = sm[j] + xv[j];
-            } else {
-                xv[j] = soft_threshold(xv[j] - eta * u, kappa);     // x <- prox(x - eta u)
-            }
-            if (base + j < d) amax = max(amax, abs_bits(xv[j]));
-        }
-        store16(x, base, d, xv);
+    for (int e = 0; e < 4; ++e) {
         if (ACC) {
-            store16(y, base, d, yv);
-            if (xsum) store16(xsum, base, d, sm);
+            yn[e] = soft_threshold(yn[e] - eta * u[e], kappa);      // y <- prox(y - eta u)
+            xn[e] = xs[e] + theta * (yn[e] - xs[e]);                // x <- snapshot + theta (y - snapshot)
+            if (have_sum) sm[e] = sm[e] + xn[e];
+        } else {
+            xn[e] = soft_threshold(xn[e] - eta * u[e], kappa);      // x <- prox(x - eta u)
         }
     }
+}
+
+// The master update on quad q (coordinates 4q..4q+3): decodes the M messages, updates x (and y, xsum) in
+// memory and returns the new x (zeros past the end of the vector).
+template <int FIELD, bool ACC>
+__device__ __forceinline__ float4 master_quad(const MasterArgs &a, int64_t q)
+{
+    constexpr int kGroup = 8;                            // messages whose loads are in flight together
+    const int64_t d = a.d;
+    const float4 gs4 = load_quad(a.g_snap, q, d);
+    const float gs[4] = {gs4.x, gs4.y, gs4.z, gs4.w};
+    float xn[4] = {0.0f, 0.0f, 0.0f, 0.0f}, yn[4] = {0.0f, 0.0f, 0.0f, 0.0f}, xs[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    float sm[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    const bool have_sum = ACC && a.xsum != nullptr;
+    if (ACC) {
+        const float4 y4 = load_quad(a.y, q, d), s4 = load_quad(a.x_snap, q, d);
+        yn[0] = y4.x; yn[1] = y4.y; yn[2] = y4.z; yn[3] = y4.w;
+        xs[0] = s4.x; xs[1] = s4.y; xs[2] = s4.z; xs[3] = s4.w;
+        if (have_sum) {
+            const float4 t = load_quad(a.xsum, q, d);
+            sm[0] = t.x; sm[1] = t.y; sm[2] = t.z; sm[3] = t.w;
+        }
+    } else {
+        const float4 x4 = load_quad(a.x, q, d);
+        xn[0] = x4.x; xn[1] = x4.y; xn[2] = x4.z; xn[3] = x4.w;
+    }
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};             // mean mode: sum_m delta_m * code_m, messages in order
+    int m = 0;
+    for (; m + kGroup <= a.M; m += kGroup) {
+        float4 v[kGroup];
+        float dm[kGroup];
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u) {
+            v[u] = quad_values<FIELD>(a.packed + static_cast<int64_t>(m + u) * a.ld_words, q, d);
+            dm[u] = FIELD == 32 ? 1.0f : a.delta[m + u];
+        }
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u) {
+            const float vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+            if (a.each) {
+                const float dir[4] = {dm[u] * vv[0] + gs[0], dm[u] * vv[1] + gs[1], dm[u] * vv[2] + gs[2], dm[u] * vv[3] + gs[3]};
+                master_apply_quad<ACC>(dir, xn, yn, xs, sm, have_sum, a.eta, a.theta, a.kappa);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] = fmaf(dm[u], vv[e], acc[e]);
+            }
+        }
+    }
+    for (; m < a.M; ++m) {
+        const float4 v = quad_values<FIELD>(a.packed + static_cast<int64_t>(m) * a.ld_words, q, d);
+        const float dm = FIELD == 32 ? 1.0f : a.delta[m];
+        const float vv[4] = {v.x, v.y, v.z, v.w};
+        if (a.each) {
+            const float dir[4] = {dm * vv[0] + gs[0], dm * vv[1] + gs[1], dm * vv[2] + gs[2], dm * vv[3] + gs[3]};
+            master_apply_quad<ACC>(dir, xn, yn, xs, sm, have_sum, a.eta, a.theta, a.kappa);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] = fmaf(dm, vv[e], acc[e]);
+        }
+    }
+    if (!a.each) {
+        const float dir[4] = {a.scale * acc[0] + gs[0], a.scale * acc[1] + gs[1], a.scale * acc[2] + gs[2],
+                              a.scale * acc[3] + gs[3]};     // u = mean of the decoded gradients + grad f(snapshot)
+        master_apply_quad<ACC>(dir, xn, yn, xs, sm, have_sum, a.eta, a.theta, a.kappa);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        if (4 * q + e >= d) xn[e] = 0.0f;
+    const float4 xq4 = make_float4(xn[0], xn[1], xn[2], xn[3]);
+    store_quad(a.x, q, d, xq4);
+    if (ACC) {
+        store_quad(a.y, q, d, make_float4(yn[0], yn[1], yn[2], yn[3]));
+        if (have_sum) store_quad(a.xsum, q, d, make_float4(sm[0], sm[1], sm[2], sm[3]));
+    }
+    return xq4;
+}
+
+__device__ __forceinline__ uint32_t quad_abs_bits(float4 v)
+{
+    return max(max(abs_bits(v.x), abs_bits(v.y)), max(abs_bits(v.z), abs_bits(v.w)));
+}
+
+// Any model size: grid-stride over quads; ||x||_inf through one atomic max per block on the
+// magnitude bit pattern (absmax_bits must be zero on entry).
+template <int FIELD, bool ACC>
+__global__ __launch_bounds__(kThreads) void master_update_kernel(const MasterArgs a, uint32_t *__restrict__ absmax_bits)
+{
+    __shared__ uint32_t scratch[kThreads / kWave];
+    const int64_t quads = (a.d + 3) / 4;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    uint32_t amax = 0;
+    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; q < quads; q += stride)
+        amax = max(amax, quad_abs_bits(master_quad<FIELD, ACC>(a, q)));
     amax = block_max_u32(amax, scratch);
     if (threadIdx.x == 0 && amax != 0) atomicMax(absmax_bits, amax);
 }
 
 template <int FIELD>
-static int launch_master_update(bool acc, dim3 grid, hipStream_t st, const uint32_t *packed, int64_t ld_words,
-                                int64_t row_words, const float *delta, int M, float scale, const float *g_snap, float *x,
-                                float *y, const float *x_snap, float *xsum, float eta, float theta, float kappa,
-                                int64_t d, uint32_t *absmax_bits)
+static int launch_master_update(bool acc, dim3 grid, hipStream_t st, const MasterArgs &a, uint32_t *absmax_bits)
 {
-    if (acc)
-        master_update_kernel<FIELD, true><<<grid, dim3(kThreads), 0, st>>>(packed, ld_words, row_words, delta, M, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, absmax_bits);
-    else
-        master_update_kernel<FIELD, false><<<grid, dim3(kThreads), 0, st>>>(packed, ld_words, row_words, delta, M, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, absmax_bits);
+    if (acc) master_update_kernel<FIELD, true><<<grid, dim3(kThreads), 0, st>>>(a, absmax_bits);
+    else master_update_kernel<FIELD, false><<<grid, dim3(kThreads), 0, st>>>(a, absmax_bits);
     DQ_LAUNCH_CHECK();
     return DQ_OK;
 }
@@ -85,15 +157,11 @@ constexpr int kFusedThreads = 1024;
 
 template <int FIELD, bool ACC, int NQ>
 __global__ __launch_bounds__(kFusedThreads) void master_fused_kernel(
-    const uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words, const float *__restrict__ delta, int M,
-    float scale, const float *__restrict__ g_snap, float *__restrict__ x, float *__restrict__ y,
-    const float *__restrict__ x_snap, float *__restrict__ xsum, float eta, float theta, float kappa, int64_t d,
-    int b_x, StreamKey key, uint32_t *__restrict__ xq_out, float *__restrict__ delta_x_out,
+    const MasterArgs a, int b_x, StreamKey key, uint32_t *__restrict__ xq_out, float *__restrict__ delta_x_out,
     float *__restrict__ absmax_x_out, uint32_t *__restrict__ status)
 {
     __shared__ uint32_t scratch[kFusedThreads / kWave];
-    constexpr int kGroup = 8;                            // messages whose loads are in flight together
-    const int64_t quads = (d + 3) / 4;
+    const int64_t d = a.d, quads = (d + 3) / 4;
     float4 xv[NQ];                                       // the thread's quads threadIdx.x + 1024*k of the new model
     uint32_t amax = 0;
 #pragma unroll
@@ -101,64 +169,8 @@ __global__ __launch_bounds__(kFusedThreads) void master_fused_kernel(
         const int64_t q = threadIdx.x + static_cast<int64_t>(kFusedThreads) * k;
         xv[k] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         if (q >= quads) continue;
-        // sum_m delta_m * code_m, messages in order (Alg. 1, master (ii))
-        float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-        int m = 0;
-        for (; m + kGroup <= M; m += kGroup) {
-            float4 v[kGroup];
-            float dm[kGroup];
-#pragma unroll
-            for (int u = 0; u < kGroup; ++u) {
-                v[u] = quad_values<FIELD>(packed + static_cast<int64_t>(m + u) * ld_words, q, d);
-                dm[u] = FIELD == 32 ? 1.0f : delta[m + u];
-            }
-#pragma unroll
-            for (int u = 0; u < kGroup; ++u) {
-                acc.x = fmaf(dm[u], v[u].x, acc.x);
-                acc.y = fmaf(dm[u], v[u].y, acc.y);
-                acc.z = fmaf(dm[u], v[u].z, acc.z);
-                acc.w = fmaf(dm[u], v[u].w, acc.w);
-            }
-        }
-        for (; m < M; ++m) {
-            const float4 v = quad_values<FIELD>(packed + static_cast<int64_t>(m) * ld_words, q, d);
-            const float dm = FIELD == 32 ? 1.0f : delta[m];
-            acc.x = fmaf(dm, v.x, acc.x);
-            acc.y = fmaf(dm, v.y, acc.y);
-            acc.z = fmaf(dm, v.z, acc.z);
-            acc.w = fmaf(dm, v.w, acc.w);
-        }
-        const float4 gs = load_quad(g_snap, q, d);
-        const float u4[4] = {scale * acc.x + gs.x, scale * acc.y + gs.y, scale * acc.z + gs.z, scale * acc.w + gs.w};
-        float xn[4];
-        if (ACC) {
-            // Alg. 3: y <- prox(y - eta u), x <- snapshot + theta (y - snapshot), running sum of x
-            const float4 y4 = load_quad(y, q, d), s4 = load_quad(x_snap, q, d);
-            const float yo[4] = {y4.x, y4.y, y4.z, y4.w}, xs[4] = {s4.x, s4.y, s4.z, s4.w};
-            float yn[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                yn[e] = soft_threshold(yo[e] - eta * u4[e], kappa);
-                xn[e] = xs[e] + theta * (yn[e] - xs[e]);
-            }
-            store_quad(y, q, d, make_float4(yn[0], yn[1], yn[2], yn[3]));
-            if (xsum) {
-                const float4 sm = load_quad(xsum, q, d);
-                store_quad(xsum, q, d, make_float4(sm.x + xn[0], sm.y + xn[1], sm.z + xn[2], sm.w + xn[3]));
-            }
-        } else {
-            const float4 x4 = load_quad(x, q, d);
-            const float xo[4] = {x4.x, x4.y, x4.z, x4.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) xn[e] = soft_threshold(xo[e] - eta * u4[e], kappa);
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (4 * q + e >= d) xn[e] = 0.0f;
-            amax = max(amax, abs_bits(xn[e]));
-        }
-        xv[k] = make_float4(xn[0], xn[1], xn[2], xn[3]);
-        store_quad(x, q, d, xv[k]);
+        xv[k] = master_quad<FIELD, ACC>(a, q);
+        amax = max(amax, quad_abs_bits(xv[k]));
     }
     amax = block_max_u32(amax, scratch);
     if (threadIdx.x == 0) absmax_x_out[0] = __uint_as_float(amax);
@@ -190,14 +202,11 @@ __global__ __launch_bounds__(kFusedThreads) void master_fused_kernel(
 }
 
 template <int FIELD, bool ACC>
-static void launch_master_fused2(int ch, hipStream_t st, const uint32_t *packed, int64_t ld_words, int64_t row_words,
-                                 const float *delta, int M, float scale, const float *g_snap, float *x, float *y,
-                                 const float *x_snap, float *xsum, float eta, float theta, float kappa, int64_t d, int b_x,
-                                 const StreamKey &key, uint32_t *xq_out, float *delta_x_out, float *absmax_x_out,
-                                 uint32_t *status)
+static void launch_master_fused2(int ch, hipStream_t st, const MasterArgs &a, int b_x, const StreamKey &key,
+                                 uint32_t *xq_out, float *delta_x_out, float *absmax_x_out, uint32_t *status)
 {
     const dim3 grid(1), block(kFusedThreads);
-#define DQ_FUSED(NQ) master_fused_kernel<FIELD, ACC, NQ><<<grid, block, 0, st>>>(packed, ld_words, row_words, delta, M, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, b_x, key, xq_out, delta_x_out, absmax_x_out, status)
+#define DQ_FUSED(NQ) master_fused_kernel<FIELD, ACC, NQ><<<grid, block, 0, st>>>(a, b_x, key, xq_out, delta_x_out, absmax_x_out, status)
     switch (ch) {                                        // quads per thread that cover d
     case 1: DQ_FUSED(1); break;
     case 2: DQ_FUSED(2); break;
@@ -209,14 +218,11 @@ static void launch_master_fused2(int ch, hipStream_t st, const uint32_t *packed,
 }
 
 template <int FIELD>
-static int launch_master_fused(bool acc, int ch, hipStream_t st, const uint32_t *packed, int64_t ld_words,
-                               int64_t row_words, const float *delta, int M, float scale, const float *g_snap, float *x,
-                               float *y, const float *x_snap, float *xsum, float eta, float theta, float kappa, int64_t d,
-                               int b_x, const StreamKey &key, uint32_t *xq_out, float *delta_x_out, float *absmax_x_out,
-                               uint32_t *status)
+static int launch_master_fused(bool acc, int ch, hipStream_t st, const MasterArgs &a, int b_x, const StreamKey &key,
+                               uint32_t *xq_out, float *delta_x_out, float *absmax_x_out, uint32_t *status)
 {
-    if (acc) launch_master_fused2<FIELD, true>(ch, st, packed, ld_words, row_words, delta, M, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
-    else launch_master_fused2<FIELD, false>(ch, st, packed, ld_words, row_words, delta, M, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
+    if (acc) launch_master_fused2<FIELD, true>(ch, st, a, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
+    else launch_master_fused2<FIELD, false>(ch, st, a, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
     DQ_LAUNCH_CHECK();
     return DQ_OK;
 }
@@ -349,13 +355,13 @@ extern "C" int32_t dq_mu_terms(const float *x, const float *x_snap, int64_t d, i
     return DQ_OK;
 }
 
-extern "C" int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
-                                  float scale, const float *g_snap, float *x, float *y, const float *x_snap, float *xsum,
-                                  float eta, float theta, float l1, int64_t d, int32_t b_x, uint64_t seed, uint32_t iter,
-                                  uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out, uint32_t *status,
-                                  void *stream)
+static int32_t master_step_impl(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
+                                float scale, int each, const float *g_snap, float *x, float *y, const float *x_snap,
+                                float *xsum, float eta, float theta, float l1, int64_t d, int32_t b_x, uint64_t seed,
+                                uint32_t iter, uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out,
+                                uint32_t *status, void *stream)
 {
-    if (d <= 0 || M <= 0 || !packed || !g_snap || !x || !xq_packed_out || !delta_x_out || !absmax_x_out)
+    if (d <= 0 || M <= 0 || M > 0x7FFFFFFFll || !packed || !g_snap || !x || !xq_packed_out || !delta_x_out || !absmax_x_out)
         return DQ_ERR_INVALID_ARG;
     if (b != 32 && !delta) return DQ_ERR_INVALID_ARG;
     if (y && !x_snap) return DQ_ERR_INVALID_ARG;
@@ -367,33 +373,30 @@ extern "C" int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, cons
     for (const void *p : ptrs)
         if (p && !aligned16(p)) return DQ_ERR_INVALID_ARG;
     hipStream_t st = as_stream(stream);
-    const float kappa_f = eta * l1;
+    const MasterArgs a{packed, ld_words, row_words, delta, static_cast<int>(M), scale, each, g_snap,
+                       x, y, x_snap, xsum, eta, theta, eta * l1, d};
+    const StreamKey key{static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), iter, 0u, DQ_TAG_MODEL};
+    const bool acc = y != nullptr;
     const bool word_aligned_bx = b_x == 2 || b_x == 4 || b_x == 8 || b_x == 32;
     if (d <= 16384 * 2 && word_aligned_bx) {
         // small model: the whole step in one block, one launch
         const int ch = static_cast<int>(ceil_div(ceil_div(d, 4), kFusedThreads));     // 1..8
-        const StreamKey mkey{static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), iter, 0u, DQ_TAG_MODEL};
-        const bool accf = y != nullptr;
-        const int Mf = static_cast<int>(M);
         switch (b) {
-        case 8: return launch_master_fused<8>(accf, ch, st, packed, ld_words, row_words, delta, Mf, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa_f, d, b_x, mkey, xq_packed_out, delta_x_out, absmax_x_out, status);
-        case 4: return launch_master_fused<4>(accf, ch, st, packed, ld_words, row_words, delta, Mf, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa_f, d, b_x, mkey, xq_packed_out, delta_x_out, absmax_x_out, status);
-        case 2: return launch_master_fused<2>(accf, ch, st, packed, ld_words, row_words, delta, Mf, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa_f, d, b_x, mkey, xq_packed_out, delta_x_out, absmax_x_out, status);
-        default: return launch_master_fused<32>(accf, ch, st, packed, ld_words, row_words, delta, Mf, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa_f, d, b_x, mkey, xq_packed_out, delta_x_out, absmax_x_out, status);
+        case 8: return launch_master_fused<8>(acc, ch, st, a, b_x, key, xq_packed_out, delta_x_out, absmax_x_out, status);
+        case 4: return launch_master_fused<4>(acc, ch, st, a, b_x, key, xq_packed_out, delta_x_out, absmax_x_out, status);
+        case 2: return launch_master_fused<2>(acc, ch, st, a, b_x, key, xq_packed_out, delta_x_out, absmax_x_out, status);
+        default: return launch_master_fused<32>(acc, ch, st, a, b_x, key, xq_packed_out, delta_x_out, absmax_x_out, status);
         }
     }
     uint32_t *absmax_bits = reinterpret_cast<uint32_t *>(absmax_x_out);
     int rc = fill_u32(absmax_bits, 1, 0u, st);
     if (rc != DQ_OK) return rc;
-    const float kappa = eta * l1;
-    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(d, 16), kThreads)));
-    const bool acc = y != nullptr;
-    const int Mi = static_cast<int>(M);
+    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(d, 4), kThreads)));
     switch (b) {
-    case 8: rc = launch_master_update<8>(acc, grid, st, packed, ld_words, row_words, delta, Mi, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, absmax_bits); break;
-    case 4: rc = launch_master_update<4>(acc, grid, st, packed, ld_words, row_words, delta, Mi, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, absmax_bits); break;
-    case 2: rc = launch_master_update<2>(acc, grid, st, packed, ld_words, row_words, delta, Mi, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, absmax_bits); break;
-    default: rc = launch_master_update<32>(acc, grid, st, packed, ld_words, row_words, delta, Mi, scale, g_snap, x, y, x_snap, xsum, eta, theta, kappa, d, absmax_bits); break;
+    case 8: rc = launch_master_update<8>(acc, grid, st, a, absmax_bits); break;
+    case 4: rc = launch_master_update<4>(acc, grid, st, a, absmax_bits); break;
+    case 2: rc = launch_master_update<2>(acc, grid, st, a, absmax_bits); break;
+    default: rc = launch_master_update<32>(acc, grid, st, a, absmax_bits); break;
     }
     if (rc != DQ_OK) return rc;
     if (b_x == 32) {
@@ -403,9 +406,28 @@ extern "C" int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, cons
         DQ_LAUNCH_CHECK();
         return fill_u32(reinterpret_cast<uint32_t *>(delta_x_out), 1, 0x3F800000u, st);
     }
-    StreamKey key{static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), iter, 0u, DQ_TAG_MODEL};
     return launch_quantize_pack(x, d, 1, d, b_x, b_x, absmax_x_out, key, DQ_MASTER_ID, xq_packed_out,
                                 packed_words(d, b_x), delta_x_out, status, st);
+}
+
+extern "C" int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
+                                  float scale, const float *g_snap, float *x, float *y, const float *x_snap, float *xsum,
+                                  float eta, float theta, float l1, int64_t d, int32_t b_x, uint64_t seed, uint32_t iter,
+                                  uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out, uint32_t *status,
+                                  void *stream)
+{
+    return master_step_impl(packed, ld_words, delta, M, b, scale, 0, g_snap, x, y, x_snap, xsum, eta, theta, l1, d, b_x,
+                            seed, iter, xq_packed_out, delta_x_out, absmax_x_out, status, stream);
+}
+
+extern "C" int32_t dq_master_step_each(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
+                                       const float *g_snap, float *x, float *y, const float *x_snap, float *xsum,
+                                       float eta, float theta, float l1, int64_t d, int32_t b_x, uint64_t seed,
+                                       uint32_t iter, uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out,
+                                       uint32_t *status, void *stream)
+{
+    return master_step_impl(packed, ld_words, delta, M, b, 1.0f, 1, g_snap, x, y, x_snap, xsum, eta, theta, l1, d, b_x,
+                            seed, iter, xq_packed_out, delta_x_out, absmax_x_out, status, stream);
 }
 
 extern "C" int32_t dq_acc_mix(const float *y, const float *x_snap, float theta, int64_t d, float *x_out, void *stream)

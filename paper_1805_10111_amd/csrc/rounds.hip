@@ -22,7 +22,7 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
     }
     const bool acc = cfg->algo == DQ_ALGO_ACC;
     if (acc && (!st->y || !st->xsum)) return DQ_ERR_INVALID_ARG;
-    if (cfg->tau < 0 || cfg->tau >= cfg->M) return DQ_ERR_INVALID_ARG;
+    if (cfg->tau < 0 || cfg->tau >= cfg->M || (cfg->each != 0 && cfg->each != 1)) return DQ_ERR_INVALID_ARG;
     const int64_t slots = cfg->tau + 1;
     const int64_t xq_words = cfg->b_x == 32 ? prob->d : dq::packed_words(prob->d, cfg->b_x);
     if (slots > 1 && (st->xq_stride_words < xq_words || st->xq_stride_words % 4 != 0)) return DQ_ERR_INVALID_ARG;
@@ -69,10 +69,17 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
             if (rc != DQ_OK) return rc;
         }
         // master side; the new model is the message of round t+1
-        rc = dq_master_step(st->packed, st->ld_words, st->delta, cfg->M, cfg->b, scale, st->g_snap, st->x,
-                            acc ? st->y : nullptr, st->x_snap, acc ? st->xsum : nullptr, eta, theta, prob->l1, prob->d,
-                            cfg->b_x, cfg->seed, it + 1u, st->xq + ((t + 1) % slots) * st->xq_stride_words,
-                            st->delta_x + ((t + 1) % slots), st->absmax_x, st->status, stream);
+        uint32_t *xq_next = st->xq + ((t + 1) % slots) * st->xq_stride_words;
+        float *dx_next = st->delta_x + ((t + 1) % slots);
+        if (cfg->each)
+            rc = dq_master_step_each(st->packed, st->ld_words, st->delta, cfg->M, cfg->b, st->g_snap, st->x,
+                                     acc ? st->y : nullptr, st->x_snap, acc ? st->xsum : nullptr, eta, theta, prob->l1,
+                                     prob->d, cfg->b_x, cfg->seed, it + 1u, xq_next, dx_next, st->absmax_x, st->status,
+                                     stream);
+        else
+            rc = dq_master_step(st->packed, st->ld_words, st->delta, cfg->M, cfg->b, scale, st->g_snap, st->x,
+                                acc ? st->y : nullptr, st->x_snap, acc ? st->xsum : nullptr, eta, theta, prob->l1,
+                                prob->d, cfg->b_x, cfg->seed, it + 1u, xq_next, dx_next, st->absmax_x, st->status, stream);
         if (rc != DQ_OK) return rc;
     }
     return DQ_OK;

@@ -28,10 +28,11 @@ class DoubleQuantTrainer:
     """Device-resident state of one run plus the per-epoch call sequence."""
 
     def __init__(self, prob: dq.DeviceProblem, algo: str, M: int, B: int, b_x: int, b: int, m: int, lr: float,
-                 seed: int = 0, x0: Optional[torch.Tensor] = None, cache_margins: bool = True, tau: int = 0):
+                 seed: int = 0, x0: Optional[torch.Tensor] = None, cache_margins: bool = True, tau: int = 0,
+                 each: bool = False):
         assert algo in ("asylpg", "sparse", "acc")
         self.prob, self.algo, self.M, self.B, self.b_x, self.b, self.m = prob, algo, M, B, b_x, b, m
-        self.lr, self.seed, self.tau = float(lr), int(seed), int(tau)
+        self.lr, self.seed, self.tau, self.each = float(lr), int(seed), int(tau), bool(each)
         d, n, dev = prob.d, prob.n, prob.y.device
         f32 = dict(dtype=torch.float32, device=dev)
         i32 = dict(dtype=torch.int32, device=dev)
@@ -60,7 +61,8 @@ class DoubleQuantTrainer:
         self.log = RunLog()
         self.mu_trace = []
         p = lambda t: None if t is None else t.data_ptr()
-        self.cfg = dq.RunConfig(algo=dq.ALGO[algo], M=M, B=B, b_x=b_x, b=b, m=m, seed=self.seed, tau=self.tau)
+        self.cfg = dq.RunConfig(algo=dq.ALGO[algo], M=M, B=B, b_x=b_x, b=b, m=m, seed=self.seed, tau=self.tau,
+                                each=int(self.each))
         self.state = dq.RunState(
             x=p(self.x), x_snap=p(self.x_snap), y=p(self.y), xsum=p(self.xsum), g_snap=p(self.g_snap),
             z_snap=p(self.z_snap), xq=p(self.xq), delta_x=p(self.delta_x), absmax_x=p(self.absmax_x),
@@ -100,7 +102,7 @@ class DoubleQuantTrainer:
 
     def epoch_epilogue(self) -> None:
         if self.algo == "acc":
-            dq.dq_acc_snapshot(self.xsum, self.m, self.x_snap)
+            dq.dq_acc_snapshot(self.xsum, self.m * (self.M if self.each else 1), self.x_snap)
         else:
             self.x_snap.copy_(self.x)
         self.epoch_index += 1

@@ -220,3 +220,22 @@ def test_delay_argument_checks(dq):
     with pytest.raises(dq.DqError) as e:          # at most one delay group per worker
         tr.run_epoch()
     assert e.value.code == dq.ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("algo,b_x,b,tau", [("asylpg", 8, 8, 0), ("asylpg", 32, 32, 0), ("acc", 8, 8, 0), ("sparse", 8, 4, 0),
+                                             ("asylpg", 8, 8, 3)])
+def test_one_master_update_per_gradient_free_run(dq, algo, b_x, b, tau):
+    """Alg. 1 taken literally at the master: every message is its own update; with tau = M - 1 on top, worker w
+    computes on a model that is w rounds old -- the paper's asynchronous picture on one GPU."""
+    from paper_1805_10111_amd.driver import DoubleQuantTrainer
+    cfg = synth.CONFIGS["C1"]
+    p = synth.make_problem(cfg, n=600, d=200)
+    m, S, lr = 10, 2, 0.03
+    tr = DoubleQuantTrainer(dq.DeviceProblem.from_host(p), algo, cfg.M, cfg.B, b_x, b, m, lr, seed=5, tau=tau, each=True)
+    log = tr.run(S)
+    ref = alg.run(p, algo, cfg.M, cfg.B, b_x, b, m, S, lr, seed=5, tau=tau, each=True)
+    for a, r in zip(log.objectives, ref.objectives):
+        assert abs(a - r) <= TOL * abs(r)
+    assert log.bits_down == ref.bits_down
+    mean_mode = alg.run(p, algo, cfg.M, cfg.B, b_x, b, m, S, lr, seed=5, tau=tau)
+    assert abs(mean_mode.objectives[-1] - ref.objectives[-1]) > 1e-4          # the two aggregation rules differ

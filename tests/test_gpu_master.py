@@ -176,3 +176,55 @@ def test_mu_terms_degenerate_and_bx_choice(dq):
         assert smallest_bx(dev(x), dev(xs), mu) == oracle.smallest_bx(x, xs, mu)
     with pytest.raises(dq.DqError):
         dq.dq_mu_terms(dev(x), dev(xs), 17, out)
+
+
+@pytest.mark.parametrize("acc", [False, True])
+@pytest.mark.parametrize("b,bx", [(8, 8), (4, 8), (2, 4), (8, 11)])
+@pytest.mark.parametrize("M,d", [(1, 5), (4, 1000), (9, 4099), (32, 4096), (2, 40001)])
+def test_master_step_each_bit_exact(dq, acc, b, bx, M, d):
+    """One update per received gradient (Alg. 1, master (ii) applied message by message)."""
+    k, delta, pw = _messages(M, d, b, seed=M * 5 + d + b)
+    rng = np.random.default_rng(d + 1)
+    g = rng.standard_normal(d).astype(np.float32) * np.float32(0.1)
+    x0, xs, y0, sum0 = (rng.standard_normal(d).astype(np.float32) for _ in range(4))
+    eta, theta, l1 = np.float32(0.05), np.float32(0.4), np.float32(0.05)
+    seed, it = 31, 2
+    x_ref, y_ref, s_ref = x0.copy(), y0.copy(), sum0.copy()
+    if acc:
+        oracle.master_update_each(k, delta, g, x_ref, y_ref, xs, s_ref, eta=eta, theta=theta, l1=l1)
+    else:
+        oracle.master_update_each(k, delta, g, x_ref, eta=eta, l1=l1)
+    kx, dx, _ = oracle.quantize_wide(x_ref, bx, seed, it, oracle.MASTER_ID, oracle.TAG_MODEL)
+    x, y, xsum = dev(x0), dev(y0), dev(sum0)
+    nwx = dq.packed_words(d, bx)
+    xq = torch.full((nwx + 4,), -1, dtype=torch.int32, device="cuda")
+    dxo = torch.zeros(1, device="cuda")
+    amx = torch.zeros(1, device="cuda")
+    dq.dq_master_step_each(dev(pw.view(np.int32)), dev(delta), M, b, dev(g), x, y if acc else None, dev(xs),
+                           xsum if acc else None, float(eta), float(theta), float(l1), bx, seed, it, xq, dxo, amx)
+    assert np.array_equal(host(x).view(np.uint32), x_ref.view(np.uint32))
+    if acc:
+        assert np.array_equal(host(y).view(np.uint32), y_ref.view(np.uint32))
+        assert np.array_equal(host(xsum).view(np.uint32), s_ref.view(np.uint32))
+    assert host(dxo)[0] == dx and host(amx)[0] == oracle.absmax(x_ref)
+    assert np.array_equal(words(xq)[:nwx], oracle.pack_wide(kx, bx))
+    assert np.all(words(xq)[nwx:] == 0xFFFFFFFF)
+
+
+def test_master_step_each_float_messages(dq):
+    M, d = 5, 1003
+    rng = np.random.default_rng(8)
+    ld = 1004
+    grads = np.zeros((M, ld), dtype=np.float32)
+    grads[:, :d] = 0.1 * rng.standard_normal((M, d))
+    g = (0.1 * rng.standard_normal(d)).astype(np.float32)
+    x0 = rng.standard_normal(d).astype(np.float32)
+    x_ref = x0.copy()
+    oracle.master_update_each_full(grads[:, :d], g, x_ref, eta=0.1, l1=0.01)
+    x = dev(x0)
+    xq = torch.zeros(d, dtype=torch.int32, device="cuda")
+    one = torch.zeros(1, device="cuda")
+    dq.dq_master_step_each(dev(grads.view(np.int32))[:, :d], None, M, 32, dev(g), x, None, None, None, 0.1, 0.0, 0.01, 32,
+                           0, 0, xq, one, one.clone())
+    assert np.array_equal(host(x).view(np.uint32), x_ref.view(np.uint32))
+    assert np.array_equal(words(xq), x_ref.view(np.uint32))
