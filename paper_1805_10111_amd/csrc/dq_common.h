@@ -28,7 +28,6 @@ void set_last_error(hipError_t e);
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline int64_t packed_words(int64_t d, int b) { return (d * b + 31) / 32; }
-__device__ __forceinline__ int64_t packed_words_dev(int64_t d, int b) { return (d * b + 31) / 32; }
 
 // ---- Philox4x32-10 (Salmon et al., SC'11), from its published definition -------
 // Stream addressing: key = (seed_lo, seed_hi); counter = (coord/4, iter, worker, tag).
@@ -220,8 +219,5 @@ __device__ __forceinline__ int sext_field(uint32_t word, unsigned offset, unsign
 {
     return static_cast<int>(__builtin_amdgcn_sbfe(word, offset, width));
 }
-
-// Logistic pieces in float32.
-__device__ __forceinline__ float sigmoidf(float t) { return 1.0f / (1.0f + __expf(-t)); }
 
 }  // namespace dq

@@ -1,6 +1,8 @@
-// Per-thread building blocks shared by the quantizer, master and worker kernels:
-// 16-coordinate loads/stores, packed-word access, the decode-and-sum of the
-// master, the soft-threshold prox and the per-coordinate sparsifier rule.
+// Per-thread building blocks shared by the quantizer, master and worker kernels.
+// Two granularities: chunks of 16 coordinates (whole words for 2, 4 and 8-bit fields; the
+// streaming kernels over long vectors) and quads of 4 coordinates (one Philox block, one
+// 16-byte access; the one-block kernels, where consecutive lanes take consecutive quads).
+// Also the soft-threshold prox and the per-coordinate sparsifier rule.
 #pragma once
 
 #include "dq_common.h"
@@ -210,19 +212,6 @@ __device__ __forceinline__ float sparsify_one(float alpha, const SparsifyRule &r
     if (r.use_budget) p = fminf(a * r.c, 1.0f);
     else p = a / r.amax;
     return bernoulli(word, p) ? alpha / p : 0.0f;
-}
-
-// Eq. (3) on a thread's 16 coordinates (chunk c): in place alpha -> beta.
-__device__ __forceinline__ void sparsify16(float (&a)[16], const SparsifyRule &r, const StreamKey &key, int64_t c)
-{
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-        const uint4 w = stream_block(key, static_cast<uint32_t>(c * 4 + g));
-        a[4 * g + 0] = sparsify_one(a[4 * g + 0], r, w.x);
-        a[4 * g + 1] = sparsify_one(a[4 * g + 1], r, w.y);
-        a[4 * g + 2] = sparsify_one(a[4 * g + 2], r, w.z);
-        a[4 * g + 3] = sparsify_one(a[4 * g + 3], r, w.w);
-    }
 }
 
 // Q_(delta,b) on a thread's 16 coordinates (chunk c) packed into FIELD-bit fields.

@@ -5,13 +5,16 @@
 // bound; what matters is that one launch does the whole worker step and that the result
 // is reproducible.  One block of 1024 threads owns a worker: the gradient alpha (d floats)
 // lives in LDS for the whole step and never goes to memory.
-//   1. margins: one wavefront per row gathers q and the snapshot at the row's columns and
-//      reduces the two dot products; lane 0 forms the row's coefficient;
-//   2. the rows' entries, pre-multiplied by their coefficient, are staged in LDS;
-//   3. scatter: each wavefront owns a contiguous range of columns and walks the staged rows
-//      in order, adding the entries that fall in its range -- no two lanes ever add to the
-//      same address at once and every column sees its rows in index order, so no atomics
-//      are needed and the sum is deterministic;
+//   1. stage: the (column, value) pairs of the mini-batch rows are copied into LDS as one flat run
+//      (the row of an entry is found by bisection on the prefix sums of the row lengths and is
+//      kept in the bits above the column);
+//   2. margins: one wavefront per row, four rows in flight, gathers q and the snapshot at the
+//      row's columns and reduces the dot products; one lane per row forms its coefficient;
+//   3. scatter: a few wavefronts each own a contiguous range of columns and stream over the
+//      staged entries (which are in row order), adding coefficient*value for the entries in
+//      their range with LDS float adds that return nothing.  All adds to a column come from one
+//      wavefront, whose LDS operations execute in issue order, so every column receives its
+//      terms in row order: the sum is reproducible and nothing waits on a read-modify-write;
 //   4. the tail of the worker step (sparsify, scale, quantize, pack) runs from LDS.
 // The full gradient uses the same block procedure over many blocks, each leaving a partial
 // d-vector that a second kernel adds up in a fixed order.
@@ -85,12 +88,13 @@ __device__ __forceinline__ void csr_prefix_lengths(RowMeta &meta, int nrows)
 
 // Steps 1-3 for rows [0, nrows) described by `meta`, accumulating into alpha (LDS).
 // The rows are taken in groups that fit the staging buffer (`stage`, `cap` (column, value) entries):
-//   stage  : the group's (column, value) pairs are copied to LDS, one wavefront per row;
-//   margins: one wavefront per row (two rows in flight) reduces sum_k value_k * vec(column_k), where
-//            vec(c) returns {first, second} operands gathered from memory; lane 0 hands the two sums to
-//            coef_of(row, first_sum, second_sum), which returns the row's coefficient;
-//   scatter: each wavefront owns a contiguous range of columns and walks the staged rows in order,
-//            adding coefficient*value for the entries that fall in its range.
+//   stage  : the group's (column, value) pairs are copied to LDS as one flat run, four entries per thread
+//            in flight, the row number packed above the column;
+//   margins: one wavefront per row (kFlight rows in flight) reduces sum_k value_k * vec(column_k), where
+//            vec(c) returns {first, second} operands gathered from memory; lane u hands the sums of its
+//            u-th row to coef_of(row, first_sum, second_sum), which returns the row's coefficient;
+//   scatter: kScatterWaves wavefronts own a contiguous range of columns each and stream over the staged
+//            entries, adding coefficient*value for the entries that fall in their range.
 // A row longer than `cap` is handled alone, straight from memory.
 template <bool SECOND, typename VecFn, typename CoefFn>
 __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta, int nrows, float *alpha,
