@@ -231,8 +231,8 @@ int32_t dq_worker_step(const dq_problem *prob /*host*/, const int32_t *idx, int6
  * delta_x_out[0] its scale and absmax_x_out[0] = ||x||_inf (scratch + output).
  * b == 32: `packed` holds M rows of float32 gradients (stride ld_words, delta
  * ignored).  b_x == 32: no model quantization, xq_packed_out receives x as float32.
- * b in {2,4,8,32}; b_x in [2,16] or 32 (widths other than 2, 4, 8, 32 take a path of
- * three launches instead of one).
+ * b in {2,4,8,32}; b_x in [2,16] or 32.  One launch for d <= 8192 with b_x in {2,4,8,32}, else three
+ * (update with ||x||_inf, quantize + pack, and a one-word fill before them).
  * All float32, in the order written; x, y, xsum are updated in place. */
 int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
                        float scale, const float *g_snap, float *x, float *y, const float *x_snap,

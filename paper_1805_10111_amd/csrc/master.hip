@@ -148,12 +148,15 @@ static int launch_master_update(bool acc, dim3 grid, hipStream_t st, const Maste
 }
 
 // ------------------------------------------------------------------ fused master step, one block
-// For d <= 32768 the whole master step is one block of 1024 threads: thread t owns the quads
-// (four consecutive coordinates) t, t+1024, ... of the model, keeps their updated values in
+// For d <= kFusedMaxD the whole master step is one block of 1024 threads: thread t owns the quads
+// (four consecutive coordinates) t and t+1024 of the model, keeps their updated values in
 // registers across the block-wide ||x||_inf reduction and quantizes + packs them right away
 // (Alg. 1, master (ii) then (i)).  Consecutive lanes work on consecutive quads, so message words
 // and model vectors are read in whole cache lines and all threads are busy from d = 4096 up.
+// Beyond that size one compute unit doing all the Philox blocks is slower than three small
+// launches spread over the chip (measured at d = 20958: 12.8 us against about 8 us).
 constexpr int kFusedThreads = 1024;
+constexpr int64_t kFusedMaxD = 8192;
 
 template <int FIELD, bool ACC, int NQ>
 __global__ __launch_bounds__(kFusedThreads) void master_fused_kernel(
@@ -207,13 +210,8 @@ static void launch_master_fused2(int ch, hipStream_t st, const MasterArgs &a, in
 {
     const dim3 grid(1), block(kFusedThreads);
 #define DQ_FUSED(NQ) master_fused_kernel<FIELD, ACC, NQ><<<grid, block, 0, st>>>(a, b_x, key, xq_out, delta_x_out, absmax_x_out, status)
-    switch (ch) {                                        // quads per thread that cover d
-    case 1: DQ_FUSED(1); break;
-    case 2: DQ_FUSED(2); break;
-    case 3: case 4: DQ_FUSED(4); break;
-    case 5: case 6: DQ_FUSED(6); break;
-    default: DQ_FUSED(8); break;
-    }
+    if (ch == 1) DQ_FUSED(1);                           // quads per thread that cover d
+    else DQ_FUSED(2);
 #undef DQ_FUSED
 }
 
@@ -378,9 +376,9 @@ static int32_t master_step_impl(const uint32_t *packed, int64_t ld_words, const 
     const StreamKey key{static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), iter, 0u, DQ_TAG_MODEL};
     const bool acc = y != nullptr;
     const bool word_aligned_bx = b_x == 2 || b_x == 4 || b_x == 8 || b_x == 32;
-    if (d <= 16384 * 2 && word_aligned_bx) {
+    if (d <= kFusedMaxD && word_aligned_bx) {
         // small model: the whole step in one block, one launch
-        const int ch = static_cast<int>(ceil_div(ceil_div(d, 4), kFusedThreads));     // 1..8
+        const int ch = static_cast<int>(ceil_div(ceil_div(d, 4), kFusedThreads));     // 1 or 2
         switch (b) {
         case 8: return launch_master_fused<8>(acc, ch, st, a, b_x, key, xq_packed_out, delta_x_out, absmax_x_out, status);
         case 4: return launch_master_fused<4>(acc, ch, st, a, b_x, key, xq_packed_out, delta_x_out, absmax_x_out, status);
