@@ -254,6 +254,7 @@ struct CsrWorkerArgs {
     uint32_t *packed; int64_t ld_words, row_words;
     float *delta_out; int32_t *nnz_out; uint32_t *status;
     int cap;                       // staging capacity in entries
+    uint32_t *zero_word;           // nullable: set to 0 by one thread of the grid
 };
 
 __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorkerArgs a)
@@ -271,6 +272,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
 
     const int m = blockIdx.x;
     const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
+    if (a.zero_word && blockIdx.x == 0 && threadIdx.x == 0) *a.zero_word = 0u;
 
     // alpha starts as the dense part  l2*(q - snapshot); four coordinates per thread and step
     for (int64_t j = 4ll * threadIdx.x; j < d; j += 4ll * kCsrThreads) {
@@ -487,7 +489,7 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     k.key = StreamKey{static_cast<uint32_t>(a.seed), static_cast<uint32_t>(a.seed >> 32), a.iter, 0u, DQ_TAG_GRAD};
     k.worker0 = a.worker0;
     k.packed = a.packed; k.ld_words = a.ld_words; k.row_words = row_words;
-    k.delta_out = a.delta_out; k.nnz_out = a.nnz_out; k.status = a.status;
+    k.delta_out = a.delta_out; k.nnz_out = a.nnz_out; k.status = a.status; k.zero_word = a.zero_word;
     k.cap = cap;
     const size_t lds = static_cast<size_t>(pad4(d)) * 4 + static_cast<size_t>(cap) * 8;
     static bool attr_done = false;

@@ -130,6 +130,7 @@ struct VrDenseArgs {
     StreamKey key; uint32_t worker0;
     uint32_t *packed; int64_t ld_words, row_words;
     float *delta_out; int32_t *nnz_out; uint32_t *status;
+    uint32_t *zero_word;             // nullable: set to 0 by one thread of the grid
 };
 
 // dx = q - snapshot for the thread's columns (q: the dequantized model message); xs = the
@@ -235,6 +236,7 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
     const int m = blockIdx.y;
     const int64_t d = a.d;
     const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
+    if (a.zero_word && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.zero_word = 0u;
 
     // ---- rows of this block
     const int per = (a.B + a.P - 1) / a.P;
@@ -399,10 +401,11 @@ __global__ __launch_bounds__(kFinishThreads) void vr_dense_finish_kernel(const V
 __global__ __launch_bounds__(kRowThreads) void worker_zero_kernel(
     int64_t d, float *__restrict__ alpha_out, int64_t ld, float *__restrict__ absmax_out, float *__restrict__ l1norm_out,
     uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words, float *__restrict__ delta_out, float delta_value,
-    int32_t *__restrict__ nnz_out)
+    int32_t *__restrict__ nnz_out, uint32_t *__restrict__ zero_word)
 {
     const int m = blockIdx.y;
     const int64_t i = static_cast<int64_t>(blockIdx.x) * kRowThreads + threadIdx.x;
+    if (zero_word && i == 0 && m == 0) *zero_word = 0u;
     if (alpha_out && i < d) alpha_out[static_cast<int64_t>(m) * ld + i] = 0.0f;
     if (packed && i < row_words) packed[static_cast<int64_t>(m) * ld_words + i] = 0u;
     if (i == 0) {
@@ -418,7 +421,7 @@ int launch_worker_zero(const WorkerArgs &a, int64_t d, int64_t row_words, hipStr
     const int64_t span = row_words > d ? row_words : d;
     worker_zero_kernel<<<dim3(static_cast<unsigned>(ceil_div(span, kRowThreads)), static_cast<unsigned>(a.M)), dim3(kRowThreads), 0, st>>>(
         d, a.alpha_out, a.ld, a.absmax_out, a.l1norm_out, a.packed, a.ld_words, row_words, a.delta_out,
-        a.b == 32 ? 1.0f : 0.0f, a.nnz_out);
+        a.b == 32 ? 1.0f : 0.0f, a.nnz_out, a.zero_word);
     DQ_LAUNCH_CHECK();
     return DQ_OK;
 }
@@ -645,7 +648,7 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     k.key = StreamKey{static_cast<uint32_t>(a.seed), static_cast<uint32_t>(a.seed >> 32), a.iter, 0u, DQ_TAG_GRAD};
     k.worker0 = a.worker0;
     k.packed = a.packed; k.ld_words = a.ld_words; k.row_words = row_words;
-    k.delta_out = a.delta_out; k.nnz_out = a.nnz_out; k.status = a.status;
+    k.delta_out = a.delta_out; k.nnz_out = a.nnz_out; k.status = a.status; k.zero_word = a.zero_word;
     const dim3 grid(k.P, static_cast<unsigned>(a.M));
     const bool have_z = a.z_snap != nullptr;
     switch (nc) {

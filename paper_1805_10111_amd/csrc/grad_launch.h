@@ -29,10 +29,19 @@ struct WorkerArgs {
     void *ws;
     int64_t ws_bytes;
     hipEvent_t ev_after_stream;   // nullable: recorded right after the kernel that streams the feature rows
+    uint32_t *zero_word;          // nullable: one device word the worker kernel sets to 0 (dq_run_rounds uses it to
+                                  // prepare the master's ||x||_inf accumulator without a launch of its own)
 };
 
 // Validation + dispatch shared by dq_vr_grad, dq_worker_step and dq_run_rounds.
 int32_t worker_step_impl(const dq_problem *prob, const WorkerArgs &a, void *stream);
+
+// dq_master_step / dq_master_step_each (each != 0).  absmax_zeroed: *absmax_x_out already holds 0 (see zero_word).
+int32_t master_step_impl(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b, float scale,
+                         int each, const float *g_snap, float *x, float *y, const float *x_snap, float *xsum, float eta,
+                         float theta, float l1, int64_t d, int32_t b_x, uint64_t seed, uint32_t iter,
+                         uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out, uint32_t *status,
+                         bool absmax_zeroed, void *stream);
 
 int64_t dense_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64_t B);
 int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float *z_out, double *obj_out, void *ws,

@@ -3,6 +3,7 @@
 // stand-alone gradient sparsifier of eq. (3).
 #include "dq_common.h"
 #include "elementwise.h"
+#include "grad_launch.h"
 
 namespace dq {
 
@@ -353,11 +354,11 @@ extern "C" int32_t dq_mu_terms(const float *x, const float *x_snap, int64_t d, i
     return DQ_OK;
 }
 
-static int32_t master_step_impl(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
-                                float scale, int each, const float *g_snap, float *x, float *y, const float *x_snap,
-                                float *xsum, float eta, float theta, float l1, int64_t d, int32_t b_x, uint64_t seed,
-                                uint32_t iter, uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out,
-                                uint32_t *status, void *stream)
+int32_t dq::master_step_impl(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
+                             float scale, int each, const float *g_snap, float *x, float *y, const float *x_snap,
+                             float *xsum, float eta, float theta, float l1, int64_t d, int32_t b_x, uint64_t seed,
+                             uint32_t iter, uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out,
+                             uint32_t *status, bool absmax_zeroed, void *stream)
 {
     if (d <= 0 || M <= 0 || M > 0x7FFFFFFFll || !packed || !g_snap || !x || !xq_packed_out || !delta_x_out || !absmax_x_out)
         return DQ_ERR_INVALID_ARG;
@@ -387,7 +388,7 @@ static int32_t master_step_impl(const uint32_t *packed, int64_t ld_words, const 
         }
     }
     uint32_t *absmax_bits = reinterpret_cast<uint32_t *>(absmax_x_out);
-    int rc = fill_u32(absmax_bits, 1, 0u, st);
+    int rc = absmax_zeroed ? DQ_OK : fill_u32(absmax_bits, 1, 0u, st);
     if (rc != DQ_OK) return rc;
     const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(d, 4), kThreads)));
     switch (b) {
@@ -415,7 +416,7 @@ extern "C" int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, cons
                                   void *stream)
 {
     return master_step_impl(packed, ld_words, delta, M, b, scale, 0, g_snap, x, y, x_snap, xsum, eta, theta, l1, d, b_x,
-                            seed, iter, xq_packed_out, delta_x_out, absmax_x_out, status, stream);
+                            seed, iter, xq_packed_out, delta_x_out, absmax_x_out, status, false, stream);
 }
 
 extern "C" int32_t dq_master_step_each(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
@@ -425,7 +426,7 @@ extern "C" int32_t dq_master_step_each(const uint32_t *packed, int64_t ld_words,
                                        uint32_t *status, void *stream)
 {
     return master_step_impl(packed, ld_words, delta, M, b, 1.0f, 1, g_snap, x, y, x_snap, xsum, eta, theta, l1, d, b_x,
-                            seed, iter, xq_packed_out, delta_x_out, absmax_x_out, status, stream);
+                            seed, iter, xq_packed_out, delta_x_out, absmax_x_out, status, false, stream);
 }
 
 extern "C" int32_t dq_acc_mix(const float *y, const float *x_snap, float theta, int64_t d, float *x_out, void *stream)

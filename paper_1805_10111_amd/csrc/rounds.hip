@@ -13,7 +13,8 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
     if (!prob || !cfg || !st || epoch < 0 || t0 < 0 || rounds < 0 || cfg->m <= 0 || t0 + rounds > cfg->m)
         return DQ_ERR_INVALID_ARG;
     if (cfg->algo < DQ_ALGO_ASYLPG || cfg->algo > DQ_ALGO_ACC) return DQ_ERR_INVALID_ARG;
-    if (!st->packed || !st->delta || !st->xq || !st->x || !st->x_snap || !st->g_snap || !dq::aligned16(st->packed))
+    if (!st->packed || !st->delta || !st->xq || !st->x || !st->x_snap || !st->g_snap || !st->absmax_x ||
+        !dq::aligned16(st->packed))
         return DQ_ERR_INVALID_ARG;
     if (cfg->b != 2 && cfg->b != 4 && cfg->b != 8 && cfg->b != 32) return DQ_ERR_UNSUPPORTED;
     {
@@ -61,6 +62,7 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
             w.packed = st->packed + w_lo * st->ld_words; w.ld_words = st->ld_words; w.delta_out = st->delta + w_lo;
             w.nnz_out = st->nnz ? st->nnz + t * cfg->M + w_lo : nullptr; w.status = st->status;
             w.ws = st->ws; w.ws_bytes = st->ws_bytes;
+            if (g == 0) w.zero_word = reinterpret_cast<uint32_t *>(st->absmax_x);   // for the master's max below
             if (worker_events && g == 0) {
                 DQ_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(worker_events[2 * (t - t0)]), as_stream(stream)));
                 w.ev_after_stream = static_cast<hipEvent_t>(worker_events[2 * (t - t0) + 1]);
@@ -71,15 +73,10 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
         // master side; the new model is the message of round t+1
         uint32_t *xq_next = st->xq + ((t + 1) % slots) * st->xq_stride_words;
         float *dx_next = st->delta_x + ((t + 1) % slots);
-        if (cfg->each)
-            rc = dq_master_step_each(st->packed, st->ld_words, st->delta, cfg->M, cfg->b, st->g_snap, st->x,
-                                     acc ? st->y : nullptr, st->x_snap, acc ? st->xsum : nullptr, eta, theta, prob->l1,
-                                     prob->d, cfg->b_x, cfg->seed, it + 1u, xq_next, dx_next, st->absmax_x, st->status,
-                                     stream);
-        else
-            rc = dq_master_step(st->packed, st->ld_words, st->delta, cfg->M, cfg->b, scale, st->g_snap, st->x,
-                                acc ? st->y : nullptr, st->x_snap, acc ? st->xsum : nullptr, eta, theta, prob->l1,
-                                prob->d, cfg->b_x, cfg->seed, it + 1u, xq_next, dx_next, st->absmax_x, st->status, stream);
+        rc = dq::master_step_impl(st->packed, st->ld_words, st->delta, cfg->M, cfg->b, scale, cfg->each, st->g_snap, st->x,
+                                  acc ? st->y : nullptr, st->x_snap, acc ? st->xsum : nullptr, eta, theta, prob->l1,
+                                  prob->d, cfg->b_x, cfg->seed, it + 1u, xq_next, dx_next, st->absmax_x, st->status,
+                                  /*absmax_zeroed=*/true, stream);
         if (rc != DQ_OK) return rc;
     }
     return DQ_OK;
