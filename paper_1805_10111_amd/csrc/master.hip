@@ -20,7 +20,7 @@ struct MasterArgs {
     const uint32_t *packed; int64_t ld_words, row_words;
     const float *delta; int M;
     float scale;              // mean mode: multiplies the sum of the M decoded gradients
-    int each;                 // != 0: one update per received gradient, in worker order, scale unused
+    int each;                 // != 0: one update per received gradient, in worker order, scale unused (selects EACH)
     const float *g_snap;
     float *x, *y; const float *x_snap; float *xsum;
     float eta, theta, kappa;
@@ -46,7 +46,7 @@ __device__ __forceinline__ void master_apply_quad(const float (&u)[4], float (&x
 
 // The master update on quad q (coordinates 4q..4q+3): decodes the M messages, updates x (and y, xsum) in
 // memory and returns the new x (zeros past the end of the vector).
-template <int FIELD, bool ACC>
+template <int FIELD, bool ACC, bool EACH>
 __device__ __forceinline__ float4 master_quad(const MasterArgs &a, int64_t q)
 {
     constexpr int kGroup = 8;                            // messages whose loads are in flight together
@@ -81,7 +81,7 @@ __device__ __forceinline__ float4 master_quad(const MasterArgs &a, int64_t q)
 #pragma unroll
         for (int u = 0; u < kGroup; ++u) {
             const float vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
-            if (a.each) {
+            if (EACH) {
                 const float dir[4] = {dm[u] * vv[0] + gs[0], dm[u] * vv[1] + gs[1], dm[u] * vv[2] + gs[2], dm[u] * vv[3] + gs[3]};
                 master_apply_quad<ACC>(dir, xn, yn, xs, sm, have_sum, a.eta, a.theta, a.kappa);
             } else {
@@ -94,7 +94,7 @@ __device__ __forceinline__ float4 master_quad(const MasterArgs &a, int64_t q)
         const float4 v = quad_values<FIELD>(a.packed + static_cast<int64_t>(m) * a.ld_words, q, d);
         const float dm = FIELD == 32 ? 1.0f : a.delta[m];
         const float vv[4] = {v.x, v.y, v.z, v.w};
-        if (a.each) {
+        if (EACH) {
             const float dir[4] = {dm * vv[0] + gs[0], dm * vv[1] + gs[1], dm * vv[2] + gs[2], dm * vv[3] + gs[3]};
             master_apply_quad<ACC>(dir, xn, yn, xs, sm, have_sum, a.eta, a.theta, a.kappa);
         } else {
@@ -102,7 +102,7 @@ __device__ __forceinline__ float4 master_quad(const MasterArgs &a, int64_t q)
             for (int e = 0; e < 4; ++e) acc[e] = fmaf(dm, vv[e], acc[e]);
         }
     }
-    if (!a.each) {
+    if (!EACH) {
         const float dir[4] = {a.scale * acc[0] + gs[0], a.scale * acc[1] + gs[1], a.scale * acc[2] + gs[2],
                               a.scale * acc[3] + gs[3]};     // u = mean of the decoded gradients + grad f(snapshot)
         master_apply_quad<ACC>(dir, xn, yn, xs, sm, have_sum, a.eta, a.theta, a.kappa);
@@ -126,7 +126,7 @@ __device__ __forceinline__ uint32_t quad_abs_bits(float4 v)
 
 // Any model size: grid-stride over quads; ||x||_inf through one atomic max per block on the
 // magnitude bit pattern (absmax_bits must be zero on entry).
-template <int FIELD, bool ACC>
+template <int FIELD, bool ACC, bool EACH>
 __global__ __launch_bounds__(kThreads) void master_update_kernel(const MasterArgs a, uint32_t *__restrict__ absmax_bits)
 {
     __shared__ uint32_t scratch[kThreads / kWave];
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(kThreads) void master_update_kernel(const MasterArg
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
     uint32_t amax = 0;
     for (int64_t q = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; q < quads; q += stride)
-        amax = max(amax, quad_abs_bits(master_quad<FIELD, ACC>(a, q)));
+        amax = max(amax, quad_abs_bits(master_quad<FIELD, ACC, EACH>(a, q)));
     amax = block_max_u32(amax, scratch);
     if (threadIdx.x == 0 && amax != 0) atomicMax(absmax_bits, amax);
 }
@@ -142,8 +142,11 @@ __global__ __launch_bounds__(kThreads) void master_update_kernel(const MasterArg
 template <int FIELD>
 static int launch_master_update(bool acc, dim3 grid, hipStream_t st, const MasterArgs &a, uint32_t *absmax_bits)
 {
-    if (acc) master_update_kernel<FIELD, true><<<grid, dim3(kThreads), 0, st>>>(a, absmax_bits);
-    else master_update_kernel<FIELD, false><<<grid, dim3(kThreads), 0, st>>>(a, absmax_bits);
+    const dim3 block(kThreads);
+    if (acc && a.each) master_update_kernel<FIELD, true, true><<<grid, block, 0, st>>>(a, absmax_bits);
+    else if (acc) master_update_kernel<FIELD, true, false><<<grid, block, 0, st>>>(a, absmax_bits);
+    else if (a.each) master_update_kernel<FIELD, false, true><<<grid, block, 0, st>>>(a, absmax_bits);
+    else master_update_kernel<FIELD, false, false><<<grid, block, 0, st>>>(a, absmax_bits);
     DQ_LAUNCH_CHECK();
     return DQ_OK;
 }
@@ -159,7 +162,7 @@ static int launch_master_update(bool acc, dim3 grid, hipStream_t st, const Maste
 constexpr int kFusedThreads = 1024;
 constexpr int64_t kFusedMaxD = 8192;
 
-template <int FIELD, bool ACC, int NQ>
+template <int FIELD, bool ACC, bool EACH, int NQ>
 __global__ __launch_bounds__(kFusedThreads) void master_fused_kernel(
     const MasterArgs a, int b_x, StreamKey key, uint32_t *__restrict__ xq_out, float *__restrict__ delta_x_out,
     float *__restrict__ absmax_x_out, uint32_t *__restrict__ status)
@@ -173,7 +176,7 @@ __global__ __launch_bounds__(kFusedThreads) void master_fused_kernel(
         const int64_t q = threadIdx.x + static_cast<int64_t>(kFusedThreads) * k;
         xv[k] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         if (q >= quads) continue;
-        xv[k] = master_quad<FIELD, ACC>(a, q);
+        xv[k] = master_quad<FIELD, ACC, EACH>(a, q);
         amax = max(amax, quad_abs_bits(xv[k]));
     }
     amax = block_max_u32(amax, scratch);
@@ -205,12 +208,12 @@ __global__ __launch_bounds__(kFusedThreads) void master_fused_kernel(
     }
 }
 
-template <int FIELD, bool ACC>
+template <int FIELD, bool ACC, bool EACH>
 static void launch_master_fused2(int ch, hipStream_t st, const MasterArgs &a, int b_x, const StreamKey &key,
                                  uint32_t *xq_out, float *delta_x_out, float *absmax_x_out, uint32_t *status)
 {
     const dim3 grid(1), block(kFusedThreads);
-#define DQ_FUSED(NQ) master_fused_kernel<FIELD, ACC, NQ><<<grid, block, 0, st>>>(a, b_x, key, xq_out, delta_x_out, absmax_x_out, status)
+#define DQ_FUSED(NQ) master_fused_kernel<FIELD, ACC, EACH, NQ><<<grid, block, 0, st>>>(a, b_x, key, xq_out, delta_x_out, absmax_x_out, status)
     if (ch == 1) DQ_FUSED(1);                           // quads per thread that cover d
     else DQ_FUSED(2);
 #undef DQ_FUSED
@@ -220,8 +223,10 @@ template <int FIELD>
 static int launch_master_fused(bool acc, int ch, hipStream_t st, const MasterArgs &a, int b_x, const StreamKey &key,
                                uint32_t *xq_out, float *delta_x_out, float *absmax_x_out, uint32_t *status)
 {
-    if (acc) launch_master_fused2<FIELD, true>(ch, st, a, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
-    else launch_master_fused2<FIELD, false>(ch, st, a, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
+    if (acc && a.each) launch_master_fused2<FIELD, true, true>(ch, st, a, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
+    else if (acc) launch_master_fused2<FIELD, true, false>(ch, st, a, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
+    else if (a.each) launch_master_fused2<FIELD, false, true>(ch, st, a, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
+    else launch_master_fused2<FIELD, false, false>(ch, st, a, b_x, key, xq_out, delta_x_out, absmax_x_out, status);
     DQ_LAUNCH_CHECK();
     return DQ_OK;
 }
