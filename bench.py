@@ -83,17 +83,20 @@ def run_rounds(tr, rounds, events=None):
 
 def recorded_traffic(workload: str):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter passes
-    (profiles/traffic_<workload>.json), or None if the kernel sources changed since they were taken."""
+    (profiles/traffic_<workload>.json), or None if the kernel's sources (the translation unit that holds it
+    and the headers it includes, listed in the record) changed since the counters were taken."""
     import hashlib
     path = os.path.join(ROOT, "profiles", f"traffic_{workload.lower()}.json")
     if not os.path.exists(path):
         return None
     rec = json.load(open(path))
     h = hashlib.sha256()
-    csrc = os.path.join(ROOT, "paper_1805_10111_amd", "csrc")
-    for fn in sorted(os.listdir(csrc)):
-        h.update(open(os.path.join(csrc, fn), "rb").read())
-    return rec["traffic_bytes_per_launch"] if rec.get("csrc_sha256") == h.hexdigest() else None
+    try:
+        for rel in rec["sources"]:
+            h.update(open(os.path.join(ROOT, rel), "rb").read())
+    except (KeyError, OSError):
+        return None
+    return rec["traffic_bytes_per_launch"] if rec.get("sources_sha256") == h.hexdigest() else None
 
 
 def quantizer_leg(dq, torch):
