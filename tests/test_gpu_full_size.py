@@ -107,3 +107,51 @@ def test_one_round_at_full_size(dq, name):
     if acc:
         assert np.array_equal(host(yd), y_ref) and np.array_equal(host(sd), s_ref)
     assert np.array_equal(words(xq), oracle.pack(kx2, bx)) and host(dxo)[0] == dx2
+
+
+def test_full_size_model_width_11_and_per_gradient_master(dq):
+    """C2 at full size with a model message whose fields straddle words (b_x = 11) and the master applying
+    every gradient as its own update."""
+    cfg = synth.CONFIGS["C2"]
+    p = synth.make_problem(cfg)
+    P = dq.DeviceProblem.from_host(p)
+    rp = oracle.RefProblem(p)
+    d, n, M, B, b, bx = p.d, p.n, cfg.M, cfg.B, cfg.b, 11
+    rng = np.random.default_rng(2)
+    x_snap = (0.05 * rng.standard_normal(d)).astype(np.float32)
+    x = (x_snap + 0.01 * rng.standard_normal(d)).astype(np.float32)
+    seed, it = 9, 17
+    kx, dx, _ = oracle.quantize_wide(x, bx, seed, it, oracle.MASTER_ID, oracle.TAG_MODEL)
+    q = oracle.dequantize_wide(kx, dx)
+    xq = torch.zeros(dq.packed_words(d, bx), dtype=torch.int32, device="cuda")
+    dxo, amx = torch.zeros(1, device="cuda"), torch.zeros(1, device="cuda")
+    dq.dq_quantize_pack(dev(x), bx, amx, False, seed, it, dq.TAG_MODEL, dq.MASTER_ID, xq, dxo)
+    assert np.array_equal(words(xq), oracle.pack_wide(kx, bx)) and host(dxo)[0] == dx
+    # worker side on the 11-bit model
+    nw = dq.packed_words(d, b)
+    ldw = (nw + 3) // 4 * 4
+    packed = torch.zeros((M, ldw), dtype=torch.int32, device="cuda")
+    delta = torch.zeros(M, device="cuda")
+    alpha = torch.zeros((M, (d + 3) // 4 * 4), device="cuda")[:, :d]
+    ws = dq.new_workspace(dq.OP_VR_GRAD, P, M, B)
+    dq.dq_worker_step(P, None, M, B, xq, dxo, bx, False, dev(x_snap), None, False, b, seed, it, 0, packed, delta, None,
+                      alpha, None, ws)
+    pw = np.zeros((M, ldw), dtype=np.uint32)
+    codes = np.zeros((M, d), dtype=np.int8)
+    deltas = np.zeros(M, dtype=np.float32)
+    for w in range(M):
+        wd, dl, _, a_ref, _, _ = alg.worker_message(rp, q, x_snap, False, B, b, seed, it, w, False)
+        if w in (0, M - 1):
+            _close(host(alpha)[w], a_ref.astype(np.float64))
+        pw[w, :nw], codes[w], deltas[w] = wd, oracle.unpack(wd, d, b), dl
+    # master: one update per gradient, new model again at 11 bits, fed with the oracle's messages: bit-exact
+    g_ref = oracle.full_grad(rp, x_snap)
+    eta = np.float32(0.05)
+    x_ref = x.copy()
+    oracle.master_update_each(codes, deltas, g_ref, x_ref, eta=eta, l1=rp.l1)
+    kx2, dx2, _ = oracle.quantize_wide(x_ref, bx, seed, it + 1, oracle.MASTER_ID, oracle.TAG_MODEL)
+    xd = dev(x)
+    dq.dq_master_step_each(dev(pw.view(np.int32)), dev(deltas), M, b, dev(g_ref), xd, None, None, None, float(eta), 0.0,
+                           float(rp.l1), bx, seed, it + 1, xq, dxo, amx)
+    assert np.array_equal(host(xd).view(np.uint32), x_ref.view(np.uint32))
+    assert np.array_equal(words(xq), oracle.pack_wide(kx2, bx)) and host(dxo)[0] == dx2
