@@ -96,14 +96,16 @@ __device__ __forceinline__ void csr_prefix_lengths(RowMeta &meta, int nrows)
 //   scatter: kScatterWaves wavefronts own a contiguous range of columns each and stream over the staged
 //            entries, adding coefficient*value for the entries that fall in their range.
 // A row longer than `cap` is handled alone, straight from memory.
+// Only the columns of the window [c0, c1) are accumulated, into alpha[column - c0]: a vector too long for
+// LDS is built one window at a time (the caller repeats the call per window; margins are recomputed).
 template <bool SECOND, typename VecFn, typename CoefFn>
-__device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta, int nrows, float *alpha,
+__device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta, int nrows, float *alpha, int c0, int c1,
                                                  int2 *stage, int cap, int *sh_ctl, VecFn vec,
                                                  CoefFn coef_of)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int span = static_cast<int>((A.d + kScatterWaves - 1) / kScatterWaves);
-    const int lo = wave * span, hi = wave < kScatterWaves ? min(static_cast<int>(A.d), lo + span) : lo;
+    const int span = (c1 - c0 + kScatterWaves - 1) / kScatterWaves;
+    const int lo = c0 + wave * span, hi = wave < kScatterWaves ? min(c1, lo + span) : lo;
     int g0 = 0;
     while (g0 < nrows) {
         // group of consecutive rows that fits the staging buffer: rows g0..g1-1 with
@@ -209,7 +211,7 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
                         const int c = e[u].x & kColMask;
-                        if (c >= lo && c < hi) atomicAdd(&alpha[c], term[u]);
+                        if (c >= lo && c < hi) atomicAdd(&alpha[c - c0], term[u]);
                     }
                 }
             }
@@ -231,7 +233,7 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
             const float cf = meta.coef[g0];
             for (int k = lane; k < meta.len[g0]; k += kWave) {
                 const int c = A.indices[s + k];
-                if (c >= lo && c < hi) alpha[c] += cf * A.values[s + k];
+                if (c >= lo && c < hi) alpha[c - c0] += cf * A.values[s + k];
             }
         }
         __syncthreads();
@@ -255,6 +257,8 @@ struct CsrWorkerArgs {
     float *delta_out; int32_t *nnz_out; uint32_t *status;
     int cap;                       // staging capacity in entries
     uint32_t *zero_word;           // nullable: set to 0 by one thread of the grid
+    int win;                       // columns of the gradient held in LDS at a time (multiple of 4; >= d: all of it)
+    float *alpha_ws; int64_t ld_ws; // with several windows: M rows of workspace for the whole gradient, else null
 };
 
 __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorkerArgs a)
@@ -267,26 +271,14 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     __shared__ double sd[kCsrWaves];
     __shared__ int sh_ctl[2];
     const int64_t d = a.A.d;
-    float *alpha = lds;
-    int2 *stage = reinterpret_cast<int2 *>(lds + ((d + 3) / 4) * 4);
+    const int win = a.win;                                     // columns per window, a multiple of 4
+    float *alpha = lds;                                        // the window of the gradient being built
+    int2 *stage = reinterpret_cast<int2 *>(lds + win);
 
     const int m = blockIdx.x;
     const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
     if (a.zero_word && blockIdx.x == 0 && threadIdx.x == 0) *a.zero_word = 0u;
-
-    // alpha starts as the dense part  l2*(q - snapshot); four coordinates per thread and step
-    for (int64_t j = 4ll * threadIdx.x; j < d; j += 4ll * kCsrThreads) {
-        if (j + 3 < d && a.b_x == 8) {
-            const float4 xs = *reinterpret_cast<const float4 *>(a.x_snap + j);
-            const uint32_t w = a.xq[j >> 2];
-            alpha[j + 0] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 0, 8)) - xs.x);
-            alpha[j + 1] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 8, 8)) - xs.y);
-            alpha[j + 2] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 16, 8)) - xs.z);
-            alpha[j + 3] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 24, 8)) - xs.w);
-        } else {
-            for (int64_t e = j; e < min(d, j + 4); ++e) alpha[e] = a.l2 * (model_value(msg, e) - a.x_snap[e]);
-        }
-    }
+    float *alpha_row = a.alpha_ws ? a.alpha_ws + static_cast<int64_t>(m) * a.ld_ws : nullptr;   // only with several windows
 
     const float fB = static_cast<float>(a.B);
     const bool have_z = a.z_snap != nullptr;
@@ -299,41 +291,69 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
         if (have_z) zs = meta.z[r];
         return vr_slope_diff(sh_y[r], zs, dz) / fB;
     };
-    for (int r0 = 0; r0 < a.B; r0 += kCsrMaxRows) {                     // passes of at most kCsrMaxRows rows
-        const int nrows = min(kCsrMaxRows, a.B - r0);
-        if (static_cast<int>(threadIdx.x) < nrows) {
-            const int r = r0 + threadIdx.x;
-            int64_t i;
-            if (a.idx) {
-                i = a.idx[static_cast<int64_t>(m) * a.B + r];
+    for (int64_t c0 = 0; c0 < d; c0 += win) {
+        const int64_t c1 = min(d, c0 + win);
+        // the window starts as the dense part  l2*(q - snapshot); four coordinates per thread and step
+        for (int64_t j = c0 + 4ll * threadIdx.x; j < c1; j += 4ll * kCsrThreads) {
+            float *dst = alpha + (j - c0);
+            if (j + 3 < d && a.b_x == 8) {
+                const float4 xs = *reinterpret_cast<const float4 *>(a.x_snap + j);
+                const uint32_t w = a.xq[j >> 2];
+                dst[0] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 0, 8)) - xs.x);
+                dst[1] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 8, 8)) - xs.y);
+                dst[2] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 16, 8)) - xs.z);
+                dst[3] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 24, 8)) - xs.w);
             } else {
-                StreamKey sk = a.key;
-                sk.worker = a.worker0 + static_cast<uint32_t>(m);
-                sk.tag = DQ_TAG_SAMPLE;
-                i = __umulhi(stream_word(sk, static_cast<uint64_t>(r)), static_cast<uint32_t>(a.A.n));
+                for (int64_t e = j; e < min(d, j + 4); ++e) dst[e - j] = a.l2 * (model_value(msg, e) - a.x_snap[e]);
             }
-            const bool ok = static_cast<uint64_t>(i) < static_cast<uint64_t>(a.A.n);
-            meta.row[threadIdx.x] = ok ? static_cast<int>(i) : -1;
-            const int64_t s = ok ? a.A.indptr[i] : 0;
-            meta.start[threadIdx.x] = s;
-            meta.len[threadIdx.x] = ok ? static_cast<int>(a.A.indptr[i + 1] - s) : 0;
-            sh_y[threadIdx.x] = ok ? a.A.y[i] : 1.0f;
-            meta.z[threadIdx.x] = (ok && have_z) ? a.z_snap[i] : 0.0f;
         }
-        csr_prefix_lengths(meta, nrows);
-        if (have_z) csr_process_rows<false>(a.A, meta, nrows, alpha, stage, a.cap, sh_ctl, vec, coef_of);
-        else csr_process_rows<true>(a.A, meta, nrows, alpha, stage, a.cap, sh_ctl, vec, coef_of);
+        for (int r0 = 0; r0 < a.B; r0 += kCsrMaxRows) {                     // passes of at most kCsrMaxRows rows
+            const int nrows = min(kCsrMaxRows, a.B - r0);
+            if (static_cast<int>(threadIdx.x) < nrows) {
+                const int r = r0 + threadIdx.x;
+                int64_t i;
+                if (a.idx) {
+                    i = a.idx[static_cast<int64_t>(m) * a.B + r];
+                } else {
+                    StreamKey sk = a.key;
+                    sk.worker = a.worker0 + static_cast<uint32_t>(m);
+                    sk.tag = DQ_TAG_SAMPLE;
+                    i = __umulhi(stream_word(sk, static_cast<uint64_t>(r)), static_cast<uint32_t>(a.A.n));
+                }
+                const bool ok = static_cast<uint64_t>(i) < static_cast<uint64_t>(a.A.n);
+                meta.row[threadIdx.x] = ok ? static_cast<int>(i) : -1;
+                const int64_t s = ok ? a.A.indptr[i] : 0;
+                meta.start[threadIdx.x] = s;
+                meta.len[threadIdx.x] = ok ? static_cast<int>(a.A.indptr[i + 1] - s) : 0;
+                sh_y[threadIdx.x] = ok ? a.A.y[i] : 1.0f;
+                meta.z[threadIdx.x] = (ok && have_z) ? a.z_snap[i] : 0.0f;
+            }
+            csr_prefix_lengths(meta, nrows);
+            if (have_z)
+                csr_process_rows<false>(a.A, meta, nrows, alpha, static_cast<int>(c0), static_cast<int>(c1), stage, a.cap,
+                                        sh_ctl, vec, coef_of);
+            else
+                csr_process_rows<true>(a.A, meta, nrows, alpha, static_cast<int>(c0), static_cast<int>(c1), stage, a.cap,
+                                       sh_ctl, vec, coef_of);
+        }
+        if (alpha_row) {                                       // several windows: the finished one goes to memory
+            for (int64_t j = c0 + threadIdx.x; j < c1; j += kCsrThreads) alpha_row[j] = alpha[j - c0];
+            __syncthreads();
+        }
     }
+    // the whole gradient: in LDS when it fits in one window, else in this worker's workspace row (the block's own
+    // writes, visible to all its threads after the barrier above)
+    float *av = alpha_row ? alpha_row : alpha;
 
     // 4. outputs
     if (a.alpha_out)
-        for (int64_t j = threadIdx.x; j < d; j += kCsrThreads) a.alpha_out[static_cast<int64_t>(m) * a.ld + j] = alpha[j];
+        for (int64_t j = threadIdx.x; j < d; j += kCsrThreads) a.alpha_out[static_cast<int64_t>(m) * a.ld + j] = av[j];
     if (!a.packed) {
         uint32_t vmax = 0;
         double s1 = 0.0;
         for (int64_t j = threadIdx.x; j < d; j += kCsrThreads) {
-            vmax = max(vmax, abs_bits(alpha[j]));
-            s1 += static_cast<double>(fabsf(alpha[j]));
+            vmax = max(vmax, abs_bits(av[j]));
+            s1 += static_cast<double>(fabsf(av[j]));
         }
         vmax = block_max_u32(vmax, su);
         if (threadIdx.x == 0) a.absmax_out[m] = __uint_as_float(vmax);
@@ -348,10 +368,10 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     const WorkerOut out{a.packed + static_cast<int64_t>(m) * a.ld_words, a.row_words, a.delta_out + m,
                         a.nnz_out ? a.nnz_out + m : nullptr, a.status};
     switch (a.b) {
-    case 2: worker_tail_from_lds<2>(alpha, d, a.sparsify != 0, a.b, key, out, su, si); break;
-    case 4: worker_tail_from_lds<4>(alpha, d, a.sparsify != 0, a.b, key, out, su, si); break;
-    case 32: worker_tail_from_lds<32>(alpha, d, a.sparsify != 0, a.b, key, out, su, si); break;
-    default: worker_tail_from_lds<8>(alpha, d, a.sparsify != 0, a.b, key, out, su, si); break;
+    case 2: worker_tail_from_lds<2>(av, d, a.sparsify != 0, a.b, key, out, su, si); break;
+    case 4: worker_tail_from_lds<4>(av, d, a.sparsify != 0, a.b, key, out, su, si); break;
+    case 32: worker_tail_from_lds<32>(av, d, a.sparsify != 0, a.b, key, out, su, si); break;
+    default: worker_tail_from_lds<8>(av, d, a.sparsify != 0, a.b, key, out, su, si); break;
     }
 }
 
@@ -359,43 +379,52 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
 // grid (P): block p owns rows [p*per, (p+1)*per), processed kCsrMaxRows at a time.
 __global__ __launch_bounds__(kCsrThreads) void csr_full_partial_kernel(
     const CsrView A, const float *__restrict__ x, float *__restrict__ z_out, float *__restrict__ partial, int64_t ldp,
-    double *__restrict__ loss_partial, int cap)
+    double *__restrict__ loss_partial, int cap, int win)
 {
     extern __shared__ __align__(16) float lds[];
     __shared__ RowMeta meta;
     __shared__ double sh_loss[kCsrWaves];
     __shared__ int sh_ctl[2];
-    const int64_t d = A.d;
-    float *acc = lds;
-    int2 *stage = reinterpret_cast<int2 *>(lds + ((d + 3) / 4) * 4);
+    float *acc = lds;                                    // the window [c0, c1) of this block's partial sum
+    int2 *stage = reinterpret_cast<int2 *>(lds + win);
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    for (int64_t j = threadIdx.x; j < ldp; j += kCsrThreads) acc[j] = 0.0f;
     const int64_t per = (A.n + gridDim.x - 1) / gridDim.x;
     const int64_t i0 = blockIdx.x * per, i1 = min(A.n, i0 + per);
     const float fn = static_cast<float>(A.n);
     double loss = 0.0;                                   // the lanes that evaluate row scalars add to theirs
-    for (int64_t ib = i0; ib < i1; ib += kCsrMaxRows) {
-        const int nrows = static_cast<int>(min<int64_t>(kCsrMaxRows, i1 - ib));
-        if (static_cast<int>(threadIdx.x) < nrows) {
-            const int64_t i = ib + threadIdx.x;
-            const int64_t s = A.indptr[i];
-            meta.row[threadIdx.x] = static_cast<int>(i);
-            meta.start[threadIdx.x] = s;
-            meta.len[threadIdx.x] = static_cast<int>(A.indptr[i + 1] - s);
+    float *mine = partial + static_cast<int64_t>(blockIdx.x) * ldp;
+    for (int64_t c0 = 0; c0 < ldp; c0 += win) {          // one window when the vector fits in LDS
+        const int64_t c1 = min(ldp, c0 + win);
+        for (int64_t j = threadIdx.x; j < c1 - c0; j += kCsrThreads) acc[j] = 0.0f;
+        const bool first = c0 == 0;                      // margins and losses are recorded once
+        for (int64_t ib = i0; ib < i1; ib += kCsrMaxRows) {
+            const int nrows = static_cast<int>(min<int64_t>(kCsrMaxRows, i1 - ib));
+            if (static_cast<int>(threadIdx.x) < nrows) {
+                const int64_t i = ib + threadIdx.x;
+                const int64_t s = A.indptr[i];
+                meta.row[threadIdx.x] = static_cast<int>(i);
+                meta.start[threadIdx.x] = s;
+                meta.len[threadIdx.x] = static_cast<int>(A.indptr[i + 1] - s);
+            }
+            csr_prefix_lengths(meta, nrows);
+            const int64_t ib_now = ib;
+            auto vec = [&](int c) { return make_float2(x[c], 0.0f); };
+            auto coef_of = [&](int r, float z, float) {
+                const int64_t i = ib_now + r;
+                const float y = A.y[i];
+                if (first) {
+                    if (z_out) z_out[i] = z;
+                    loss += static_cast<double>(logistic_loss(y * z));
+                }
+                return logistic_slope(y, z) / fn;
+            };
+            csr_process_rows<false>(A, meta, nrows, acc, static_cast<int>(c0), static_cast<int>(min(A.d, c1)), stage, cap,
+                                    sh_ctl, vec, coef_of);
         }
-        csr_prefix_lengths(meta, nrows);
-        const int64_t ib_now = ib;
-        auto vec = [&](int c) { return make_float2(x[c], 0.0f); };
-        auto coef_of = [&](int r, float z, float) {
-            const int64_t i = ib_now + r;
-            const float y = A.y[i];
-            if (z_out) z_out[i] = z;
-            loss += static_cast<double>(logistic_loss(y * z));
-            return logistic_slope(y, z) / fn;
-        };
-        csr_process_rows<false>(A, meta, nrows, acc, stage, cap, sh_ctl, vec, coef_of);
+        __syncthreads();
+        for (int64_t j = c0 + threadIdx.x; j < c1; j += kCsrThreads) mine[j] = acc[j - c0];
+        __syncthreads();
     }
-    for (int64_t j = threadIdx.x; j < ldp; j += kCsrThreads) partial[static_cast<int64_t>(blockIdx.x) * ldp + j] = acc[j];
     loss = wave_sum_f64(loss);
     if (lane == 0) sh_loss[wave] = loss;
     __syncthreads();
@@ -414,13 +443,29 @@ int launch_worker_zero(const WorkerArgs &a, int64_t d, int64_t row_words, hipStr
 // ------------------------------------------------------------------ host side
 static int64_t pad4(int64_t d) { return (d + 3) / 4 * 4; }
 
-// Staging capacity (entries) that fits next to the d-vector; 0 if the vector itself does not fit.
-static int csr_stage_cap(int64_t d)
+// LDS plan for a d-vector plus the staging buffer.  When both fit, the vector is one window; otherwise it is built
+// in several equal windows (multiples of 4 columns) that leave room for at least kMinStage staged entries.
+// Columns carry the row number in the bits above kColBits while staged, hence the limit on d.
+constexpr int64_t kMinStage = 4096;
+struct CsrPlan {
+    int win;        // columns per window
+    int cap;        // staged (column, value) entries
+    int nwin;
+};
+
+static bool csr_plan(int64_t d, CsrPlan &p)
 {
-    const int64_t left = kLdsBudget - kCsrFixedLds - pad4(d) * 4;
-    if (left < 8 * 512) return 0;
-    const int64_t cap = left / 8;
-    return static_cast<int>(cap > 8192 ? 8192 : cap);
+    if (d > (1ll << kColBits)) return false;
+    const int64_t budget = kLdsBudget - kCsrFixedLds;                     // bytes for window + staging
+    int64_t nwin = 1;
+    if (pad4(d) * 4 + 8 * 512 > budget) nwin = ceil_div(pad4(d) * 4, budget - 8 * kMinStage);
+    const int64_t win = pad4(ceil_div(pad4(d), nwin));
+    int64_t cap = (budget - win * 4) / 8;
+    if (cap > 8192) cap = 8192;
+    p.win = static_cast<int>(win);
+    p.cap = static_cast<int>(cap);
+    p.nwin = static_cast<int>(ceil_div(pad4(d), win));
+    return true;
 }
 
 static int64_t csr_full_splits(int64_t n)
@@ -431,13 +476,16 @@ static int64_t csr_full_splits(int64_t n)
     return P;
 }
 
-int64_t csr_workspace_bytes(int32_t op, const dq_problem *prob, int64_t, int64_t)
+int64_t csr_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64_t)
 {
+    CsrPlan plan;
+    if (!csr_plan(prob->d, plan)) return DQ_ERR_UNSUPPORTED;
     if (op == DQ_OP_FULL_GRAD) {
         const int64_t P = csr_full_splits(prob->n);
         return P * pad4(prob->d) * 4 + P * 8;
     }
-    return 0;                                    // the worker step keeps everything in LDS
+    // the worker step keeps the gradient in LDS when it fits; otherwise each worker has a row of workspace
+    return plan.nwin > 1 ? M * pad4(prob->d) * 4 : 0;
 }
 
 // Kernels that use more than 64 KB of dynamic LDS must be told so once (the limit is raised to the budget).
@@ -456,19 +504,19 @@ int csr_full_grad(const dq_problem *prob, const float *x, float *g_out, float *z
                   int64_t ws_bytes, hipStream_t st)
 {
     const int64_t d = prob->d, n = prob->n;
-    const int cap = csr_stage_cap(d);
-    if (cap == 0) return DQ_ERR_UNSUPPORTED;
+    CsrPlan plan;
+    if (!csr_plan(d, plan)) return DQ_ERR_UNSUPPORTED;
     if (ws_bytes < csr_workspace_bytes(DQ_OP_FULL_GRAD, prob, 0, 0) || !ws) return DQ_ERR_WORKSPACE;
     const int64_t ldp = pad4(d);
     const int P = static_cast<int>(csr_full_splits(n));
     float *partial = static_cast<float *>(ws);
     double *loss_partial = reinterpret_cast<double *>(partial + static_cast<int64_t>(P) * ldp);
-    const size_t lds = static_cast<size_t>(ldp) * 4 + static_cast<size_t>(cap) * 8;
+    const size_t lds = static_cast<size_t>(plan.win) * 4 + static_cast<size_t>(plan.cap) * 8;
     static bool attr_done = false;
     int rc = allow_big_lds(csr_full_partial_kernel, attr_done);
     if (rc != DQ_OK) return rc;
     const CsrView A{prob->indptr, prob->indices, prob->values, prob->y, n, d};
-    csr_full_partial_kernel<<<dim3(P), dim3(kCsrThreads), lds, st>>>(A, x, z_out, partial, ldp, loss_partial, cap);
+    csr_full_partial_kernel<<<dim3(P), dim3(kCsrThreads), lds, st>>>(A, x, z_out, partial, ldp, loss_partial, plan.cap, plan.win);
     DQ_LAUNCH_CHECK();
     return launch_full_finish(partial, P, ldp, n, d, x, prob->l2, prob->l1, loss_partial, g_out, obj_out, st);
 }
@@ -476,10 +524,11 @@ int csr_full_grad(const dq_problem *prob, const float *x, float *g_out, float *z
 int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
 {
     const int64_t d = prob->d;
-    const int cap = csr_stage_cap(d);
-    if (cap == 0) return DQ_ERR_UNSUPPORTED;
+    CsrPlan plan;
+    if (!csr_plan(d, plan)) return DQ_ERR_UNSUPPORTED;
     const int64_t row_words = a.packed ? (a.b == 32 ? d : packed_words(d, a.b)) : 0;
     if (a.model_is_snapshot) return launch_worker_zero(a, d, row_words, st);
+    if (plan.nwin > 1 && (!a.ws || a.ws_bytes < a.M * pad4(d) * 4)) return DQ_ERR_WORKSPACE;
     CsrWorkerArgs k{};
     k.A = CsrView{prob->indptr, prob->indices, prob->values, prob->y, prob->n, d};
     k.idx = a.idx; k.B = static_cast<int>(a.B);
@@ -490,8 +539,9 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     k.worker0 = a.worker0;
     k.packed = a.packed; k.ld_words = a.ld_words; k.row_words = row_words;
     k.delta_out = a.delta_out; k.nnz_out = a.nnz_out; k.status = a.status; k.zero_word = a.zero_word;
-    k.cap = cap;
-    const size_t lds = static_cast<size_t>(pad4(d)) * 4 + static_cast<size_t>(cap) * 8;
+    k.cap = plan.cap; k.win = plan.win;
+    k.alpha_ws = plan.nwin > 1 ? static_cast<float *>(a.ws) : nullptr; k.ld_ws = pad4(d);
+    const size_t lds = static_cast<size_t>(plan.win) * 4 + static_cast<size_t>(plan.cap) * 8;
     static bool attr_done = false;
     int rc = allow_big_lds(csr_worker_kernel, attr_done);
     if (rc != DQ_OK) return rc;

@@ -239,3 +239,19 @@ def test_one_master_update_per_gradient_free_run(dq, algo, b_x, b, tau):
     assert log.bits_down == ref.bits_down
     mean_mode = alg.run(p, algo, cfg.M, cfg.B, b_x, b, m, S, lr, seed=5, tau=tau)
     assert abs(mean_mode.objectives[-1] - ref.objectives[-1]) > 1e-4          # the two aggregation rules differ
+
+
+@pytest.mark.parametrize("algo,b", [("asylpg", 8), ("sparse", 4)])
+def test_free_run_on_a_model_wider_than_the_on_chip_buffer(dq, algo, b):
+    """rcv1-like width (47,236 features): the CSR worker builds its gradient in two column windows."""
+    from paper_1805_10111_amd.driver import DoubleQuantTrainer
+    p = synth.sparse_text_logistic(1500, 47236, mean_nnz=75.0, seed=4, l2=1e-4, l1=1e-5)
+    M, B, m, S, lr = 4, 16, 6, 2, 0.1
+    tr = DoubleQuantTrainer(dq.DeviceProblem.from_host(p), algo, M, B, 8, b, m, lr, seed=2)
+    log = tr.run(S)
+    ref = alg.run(p, algo, M, B, 8, b, m, S, lr, seed=2)
+    for a, r in zip(log.objectives, ref.objectives):
+        assert abs(a - r) <= TOL * abs(r)
+    assert log.bits_down == ref.bits_down
+    if algo == "asylpg":
+        assert log.bits_up == ref.bits_up

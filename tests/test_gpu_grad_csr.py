@@ -45,6 +45,8 @@ def _problems():
         "tiny": synth.sparse_text_logistic(60, 50, mean_nnz=6.0, seed=2, l2=1e-2),
         "long": _long_rows_problem(),
         "mid": synth.sparse_text_logistic(500, 4099, mean_nnz=30.0, seed=3),
+        # rcv1-like width (47,236 features): the gradient does not fit in LDS and is built in two column windows
+        "wide": synth.sparse_text_logistic(1500, 47236, mean_nnz=75.0, seed=4),
     }
 
 
@@ -61,7 +63,7 @@ def _model(rng, d, b_x, x_snap, spread=0.05):
     return oracle.pack(k, b_x), dx, oracle.dequantize(k, dx)
 
 
-@pytest.mark.parametrize("name", ["text", "tiny", "long", "mid"])
+@pytest.mark.parametrize("name", ["text", "tiny", "long", "mid", "wide"])
 def test_full_grad(dq, problems, name):
     p = problems[name]
     P = dq.DeviceProblem.from_host(p)
@@ -83,7 +85,7 @@ def test_full_grad(dq, problems, name):
 
 @pytest.mark.parametrize("have_z", [True, False])
 @pytest.mark.parametrize("b_x", [8, 2, 32])
-@pytest.mark.parametrize("name,M,B", [("text", 8, 32), ("tiny", 3, 5), ("long", 2, 40), ("mid", 4, 300)])
+@pytest.mark.parametrize("name,M,B", [("text", 8, 32), ("tiny", 3, 5), ("long", 2, 40), ("mid", 4, 300), ("wide", 5, 48)])
 def test_vr_grad(dq, problems, name, M, B, b_x, have_z):
     p = problems[name]
     P = dq.DeviceProblem.from_host(p)
@@ -103,8 +105,9 @@ def test_vr_grad(dq, problems, name, M, B, b_x, have_z):
     alpha = torch.full((M, ld), 5.0, device="cuda")[:, :d]
     amax = torch.zeros(M, device="cuda")
     l1n = torch.zeros(M, device="cuda")
+    ws = dq.new_workspace(dq.OP_VR_GRAD, P, M, B)          # empty unless the gradient is wider than the on-chip buffer
     dq.dq_vr_grad(P, dev(idx), M, B, dev(xq.view(np.int32)), dev(np.array([dx], dtype=np.float32)), b_x, False,
-                  dev(x_snap), z_snap, alpha, amax, l1n, None)
+                  dev(x_snap), z_snap, alpha, amax, l1n, ws)
     for w in range(M):
         want = oracle.vr_grad(rp, idx[w], q, x_snap).astype(np.float64)
         got = host(alpha)[w]
@@ -114,13 +117,13 @@ def test_vr_grad(dq, problems, name, M, B, b_x, have_z):
     # deterministic
     alpha2 = torch.zeros((M, ld), device="cuda")[:, :d]
     dq.dq_vr_grad(P, dev(idx), M, B, dev(xq.view(np.int32)), dev(np.array([dx], dtype=np.float32)), b_x, False,
-                  dev(x_snap), z_snap, alpha2, amax, None, None)
+                  dev(x_snap), z_snap, alpha2, amax, None, ws)
     assert torch.equal(alpha, alpha2)
 
 
 @pytest.mark.parametrize("sparsify", [False, True])
 @pytest.mark.parametrize("b", [8, 4])
-@pytest.mark.parametrize("name,M,B", [("text", 16, 64), ("tiny", 2, 7), ("long", 2, 12)])
+@pytest.mark.parametrize("name,M,B", [("text", 16, 64), ("tiny", 2, 7), ("long", 2, 12), ("wide", 4, 40)])
 def test_worker_step(dq, problems, name, M, B, b, sparsify):
     p = problems[name]
     P = dq.DeviceProblem.from_host(p)
@@ -141,12 +144,13 @@ def test_worker_step(dq, problems, name, M, B, b, sparsify):
     nnz = torch.zeros(M, dtype=torch.int32, device="cuda")
     status = torch.zeros(1, dtype=torch.int32, device="cuda")
     alpha_f = torch.zeros((M, ld), device="cuda")[:, :d]
+    ws = dq.new_workspace(dq.OP_VR_GRAD, P, M, B)
     dq.dq_worker_step(P, None, M, B, xq_d, dx_d, 8, False, xs_d, None, sparsify, b, seed, it, w0, packed, delta, nnz,
-                      alpha_f, status, None)
+                      alpha_f, status, ws)
     # unfused chain of the same library with explicit indices: bit for bit
     alpha = torch.zeros((M, ld), device="cuda")[:, :d]
     amax = torch.zeros(M, device="cuda")
-    dq.dq_vr_grad(P, dev(idx), M, B, xq_d, dx_d, 8, False, xs_d, None, alpha, amax, None, None)
+    dq.dq_vr_grad(P, dev(idx), M, B, xq_d, dx_d, 8, False, xs_d, None, alpha, amax, None, ws)
     assert torch.equal(alpha, alpha_f)
     v = alpha
     if sparsify:
@@ -184,12 +188,23 @@ def test_flag_bit_round_and_limits(dq, problems):
     dq.dq_worker_step(P, None, M, B, None, None, 8, True, torch.zeros(d, device="cuda"), None, True, 4, 1, 1, 0,
                       packed, delta, None, None, None, None)
     assert not words(packed)[:, : dq.packed_words(d, 4)].any() and not host(delta).any()
-    # a model too wide for the on-chip gradient buffer is refused, not mangled
-    big = synth.Problem(n=2, d=60000, y=np.ones(2, dtype=np.float32), l2=0.0, l1=0.0,
+    # more columns than the staged entries can address: refused, not mangled
+    wide = (1 << 20) + 8
+    big = synth.Problem(n=2, d=wide, y=np.ones(2, dtype=np.float32), l2=0.0, l1=0.0,
                         indptr=np.array([0, 1, 2], dtype=np.int64), indices=np.array([0, 5], dtype=np.int32),
                         values=np.ones(2, dtype=np.float32))
     Pb = dq.DeviceProblem.from_host(big)
-    x = torch.zeros(60000, device="cuda")
+    x = torch.zeros(wide, device="cuda")
     with pytest.raises(dq.DqError) as e:
         dq.dq_full_grad(Pb, x, x.clone(), None, None, torch.zeros(1 << 22, device="cuda"))
     assert e.value.code == dq.ERR_UNSUPPORTED
+    # a gradient that does not fit on chip needs the worker workspace
+    pw = problems["wide"]
+    Pw = dq.DeviceProblem.from_host(pw)
+    assert dq.dq_workspace_bytes(dq.OP_VR_GRAD, Pw, 3, 4) == 3 * ((pw.d + 3) // 4 * 4) * 4
+    with pytest.raises(dq.DqError) as e:
+        dq.dq_worker_step(Pw, None, 3, 4, torch.zeros(pw.d, dtype=torch.int32, device="cuda"), torch.ones(1, device="cuda"),
+                          8, False, torch.zeros(pw.d, device="cuda"), None, False, 8, 1, 1, 0,
+                          torch.zeros((3, 11812), dtype=torch.int32, device="cuda"), torch.zeros(3, device="cuda"),
+                          None, None, None, None)
+    assert e.value.code == dq.ERR_WORKSPACE
