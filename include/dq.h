@@ -22,8 +22,10 @@
  *  - Alignment: vectors of floats / words that are read or written with
  *    128-bit accesses must be 16-byte aligned and row strides (`ld`, `lda`,
  *    in elements) multiples of 4; the comments say where this is required.
- *  - b is the number of bits per coordinate.  Packed buffers support
- *    b in {2,4,8}; unpacked int8 codes support any b in [2,8].
+ *  - b is the number of bits per coordinate.  Packed buffers: any b in [2,16] for
+ *    dq_quantize_pack, dq_unpack_dequant_sum and the model message (b_x); gradient
+ *    messages of the worker / master calls use b in {2,4,8} (or 32 = float32, not
+ *    quantized); unpacked int8 codes support any b in [2,8].
  *  - `status` (nullable) is a device uint32 that is OR-ed into, never cleared:
  *    bit 0 = a scale delta was not finite (NaN/Inf in the input vector).
  *  - Random streams are addressed, not stateful: (seed, iter, worker, tag,
