@@ -297,7 +297,11 @@ typedef struct dq_run_config {
  * xq + s*xq_stride_words (each ceil(d*b_x/32) words, or d floats; 16-byte aligned slots);
  * delta_x: float[tau+1], one scale per slot; absmax_x: float[1].  The message of round t lives in
  * slot t mod (tau+1).  packed: M rows of ld_words words; delta: float[M];
- * nnz: int32[m*M] nonzero codes per round and worker, nullable.  ws: DQ_OP_VR_GRAD workspace. */
+ * nnz: int32[m*M] nonzero codes per round and worker, nullable.  ws: DQ_OP_VR_GRAD workspace.
+ * wire (nullable, Alg. 2 with b in {2,4,8} only): M rows of ld_wire >= dq_sparse_stream_words(d, b) words.  When
+ * given, every round really sends the sparse message of Section 4.2: the workers' packed codes are encoded into
+ * `wire` (dq_sparse_encode), then the master's input is rebuilt from `wire` alone (dq_sparse_decode); wire_nnz:
+ * int32[M], required with wire. */
 typedef struct dq_run_state {
     float *x, *x_snap, *y, *xsum, *g_snap;
     const float *z_snap;
@@ -311,6 +315,9 @@ typedef struct dq_run_state {
     void *ws;
     int64_t ws_bytes;
     int64_t xq_stride_words;
+    uint32_t *wire;
+    int64_t ld_wire;
+    int32_t *wire_nnz;
 } dq_run_state;
 
 /* Enqueues rounds t0 .. t0+rounds-1 of epoch `epoch` (0-based) of Alg. 1, 2 or 3: per round the

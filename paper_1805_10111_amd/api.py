@@ -56,7 +56,7 @@ class RunState(C.Structure):
                 ("g_snap", C.c_void_p), ("z_snap", C.c_void_p), ("xq", C.c_void_p), ("delta_x", C.c_void_p),
                 ("absmax_x", C.c_void_p), ("packed", C.c_void_p), ("ld_words", C.c_int64), ("delta", C.c_void_p),
                 ("nnz", C.c_void_p), ("status", C.c_void_p), ("ws", C.c_void_p), ("ws_bytes", C.c_int64),
-                ("xq_stride_words", C.c_int64)]
+                ("xq_stride_words", C.c_int64), ("wire", C.c_void_p), ("ld_wire", C.c_int64), ("wire_nnz", C.c_void_p)]
 
 
 ALGO = {"asylpg": 0, "sparse": 1, "acc": 2}

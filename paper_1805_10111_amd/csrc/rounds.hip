@@ -23,6 +23,7 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
     }
     const bool acc = cfg->algo == DQ_ALGO_ACC;
     if (acc && (!st->y || !st->xsum)) return DQ_ERR_INVALID_ARG;
+    if (st->wire && !st->wire_nnz) return DQ_ERR_INVALID_ARG;
     if (cfg->tau < 0 || cfg->tau >= cfg->M || (cfg->each != 0 && cfg->each != 1)) return DQ_ERR_INVALID_ARG;
     const int64_t slots = cfg->tau + 1;
     const int64_t xq_words = cfg->b_x == 32 ? prob->d : dq::packed_words(prob->d, cfg->b_x);
@@ -68,6 +69,13 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
                 w.ev_after_stream = static_cast<hipEvent_t>(worker_events[2 * (t - t0) + 1]);
             }
             rc = dq::worker_step_impl(prob, w, stream);
+            if (rc != DQ_OK) return rc;
+        }
+        // Section 4.2 on request: the sparsified messages cross to the master as (position, value) streams
+        if (st->wire && cfg->algo == DQ_ALGO_SPARSE && cfg->b != 32) {
+            rc = dq_sparse_encode(st->packed, st->ld_words, prob->d, cfg->M, cfg->b, st->wire, st->ld_wire, st->wire_nnz, stream);
+            if (rc != DQ_OK) return rc;
+            rc = dq_sparse_decode(st->wire, st->ld_wire, st->wire_nnz, prob->d, cfg->M, cfg->b, st->packed, st->ld_words, stream);
             if (rc != DQ_OK) return rc;
         }
         // master side; the new model is the message of round t+1

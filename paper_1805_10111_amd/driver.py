@@ -29,7 +29,7 @@ class DoubleQuantTrainer:
 
     def __init__(self, prob: dq.DeviceProblem, algo: str, M: int, B: int, b_x: int, b: int, m: int, lr: float,
                  seed: int = 0, x0: Optional[torch.Tensor] = None, cache_margins: bool = True, tau: int = 0,
-                 each: bool = False):
+                 each: bool = False, sparse_wire: bool = False):
         assert algo in ("asylpg", "sparse", "acc")
         self.prob, self.algo, self.M, self.B, self.b_x, self.b, self.m = prob, algo, M, B, b_x, b, m
         self.lr, self.seed, self.tau, self.each = float(lr), int(seed), int(tau), bool(each)
@@ -58,6 +58,13 @@ class DoubleQuantTrainer:
         self.ws = dq.new_workspace(dq.OP_VR_GRAD, prob, M, B)
         self.epoch_index = 0
         self.theta, self.eta = 0.0, self.lr
+        # Section 4.2 on request (Alg. 2 only): the messages really pass through the sparse (position, value) format
+        self.wire = self.wire_nnz = None
+        if sparse_wire:
+            assert algo == "sparse" and b in (2, 4, 8)
+            self.ld_wire = (dq.dq_sparse_stream_words(d, b) + 3) // 4 * 4
+            self.wire = torch.zeros((M, self.ld_wire), **i32)
+            self.wire_nnz = torch.zeros(M, **i32)
         self.log = RunLog()
         self.mu_trace = []
         p = lambda t: None if t is None else t.data_ptr()
@@ -67,7 +74,8 @@ class DoubleQuantTrainer:
             x=p(self.x), x_snap=p(self.x_snap), y=p(self.y), xsum=p(self.xsum), g_snap=p(self.g_snap),
             z_snap=p(self.z_snap), xq=p(self.xq), delta_x=p(self.delta_x), absmax_x=p(self.absmax_x),
             packed=p(self.packed), ld_words=self.ld_words, delta=p(self.delta), nnz=p(self.nnz),
-            status=p(self.status), ws=p(self.ws), ws_bytes=self.ws.numel() * 4, xq_stride_words=self.xq_stride)
+            status=p(self.status), ws=p(self.ws), ws_bytes=self.ws.numel() * 4, xq_stride_words=self.xq_stride,
+            wire=p(self.wire), ld_wire=0 if self.wire is None else self.ld_wire, wire_nnz=p(self.wire_nnz))
 
     # -- one epoch ---------------------------------------------------------------------------
     def epoch_prologue(self) -> None:

@@ -255,3 +255,22 @@ def test_free_run_on_a_model_wider_than_the_on_chip_buffer(dq, algo, b):
     assert log.bits_down == ref.bits_down
     if algo == "asylpg":
         assert log.bits_up == ref.bits_up
+
+
+def test_sparse_messages_through_the_wire_format(dq):
+    """Alg. 2 with every message really encoded as (position, value) entries (Section 4.2) and decoded again
+    before the master uses it: same trajectory bit for bit, and the entry counts are the ones the bit counter uses."""
+    from paper_1805_10111_amd.driver import DoubleQuantTrainer
+    cfg = synth.CONFIGS["C3"]
+    p = synth.make_problem(cfg, n=3000)
+    P = dq.DeviceProblem.from_host(p)
+    m, S = 6, 2
+    a = DoubleQuantTrainer(P, "sparse", cfg.M, cfg.B, cfg.b_x, cfg.b, m, cfg.lr, seed=3)
+    b = DoubleQuantTrainer(P, "sparse", cfg.M, cfg.B, cfg.b_x, cfg.b, m, cfg.lr, seed=3, sparse_wire=True)
+    la, lb = a.run(S), b.run(S)
+    assert torch.equal(a.x_snap, b.x_snap) and la.bits_up == lb.bits_up and la.objectives == lb.objectives
+    assert torch.equal(b.wire_nnz, b.nnz[m - 1])                       # entries of the last round's messages
+    used = (host(b.wire_nnz).astype(np.int64) * (15 + cfg.b) + 31) // 32      # ceil(log2 20958) = 15 position bits
+    w = words(b.wire)
+    for r in range(cfg.M):
+        assert not w[r, used[r]:].any() and (used[r] == 0 or w[r, :used[r]].any())
