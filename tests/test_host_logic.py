@@ -112,3 +112,10 @@ def test_workspace_sizes(lib):
     assert lib.dq_workspace_bytes(3, C.byref(p), 1, 1) == INVALID
     assert lib.dq_workspace_bytes(2, C.byref(p), 0, 256) == INVALID
     assert lib.dq_workspace_bytes(1, None, 0, 0) == INVALID
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
