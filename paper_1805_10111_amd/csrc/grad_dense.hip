@@ -228,7 +228,10 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
     __shared__ float sh_red[2 * kRowWaves * R * 2];
     __shared__ int sh_row[kMaxRowsPerBlock];
     __shared__ float sh_y[kMaxRowsPerBlock], sh_z[kMaxRowsPerBlock];
-    __shared__ __align__(16) float sh_alpha[4 * kRowThreads * NC];
+    // the in-kernel tail (one block owns the worker's whole mini-batch) exists for rows of up to 4096 floats;
+    // wider rows always go through the partial sums and the second kernel
+    constexpr bool kOwnTail = NC <= 4;
+    __shared__ __align__(16) float sh_alpha[kOwnTail ? 4 * kRowThreads * NC : 4];
     __shared__ uint32_t su[kRowWaves];
     __shared__ int si[kRowWaves];
     __shared__ double sd[kRowWaves];
@@ -318,11 +321,11 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
         compute_batch(rb, row);
     }
 
-    if (a.P > 1) {          // several blocks per worker: leave the partial sum for vr_dense_finish_kernel
+    if (a.P > 1 || !kOwnTail) {          // leave the partial sum for vr_dense_finish_kernel
         store_cols<NC>(a.partial + (static_cast<int64_t>(m) * a.P + blockIdx.x) * a.ldp, a.ldp, acc);
         return;
     }
-    worker_finish<NC>(a, m, acc, dx, sh_alpha, su, si, sd);
+    if constexpr (kOwnTail) worker_finish<NC>(a, m, acc, dx, sh_alpha, su, si, sd);
 }
 
 // Second stage when a worker's mini-batch was split over P > 1 blocks.  grid (M), 1024
@@ -559,7 +562,8 @@ int launch_full_finish(const float *partial, int P, int64_t ldp, int64_t n, int6
 }
 
 // ------------------------------------------------------------------ host side
-static int dense_nc(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 4096 ? 4 : 0; }
+// float4 columns per thread that cover a row: rows of up to 16384 floats are supported
+static int dense_nc(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 4096 ? 4 : d <= 8192 ? 8 : d <= 16384 ? 16 : 0; }
 
 int64_t dense_vr_splits(int64_t M, int64_t B)
 {
@@ -616,7 +620,9 @@ int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float 
     switch (nc) {
     case 1: full_dense_partial_kernel<1, 8><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
     case 2: full_dense_partial_kernel<2, 4><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
-    default: full_dense_partial_kernel<4, 4><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
+    case 4: full_dense_partial_kernel<4, 4><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
+    case 8: full_dense_partial_kernel<8, 2><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
+    default: full_dense_partial_kernel<16, 1><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
     }
     DQ_LAUNCH_CHECK();
     return launch_full_finish(partial, P, ldp, n, d, x, prob->l2, prob->l1, loss_partial, g_out, obj_out, st);
@@ -654,6 +660,8 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     switch (nc) {
     case 1: launch_vr<1, 8>(have_z, grid, st, k); break;
     case 2: launch_vr<2, 4>(have_z, grid, st, k); break;
+    case 8: launch_vr<8, 2>(have_z, grid, st, k); break;
+    case 16: launch_vr<16, 1>(have_z, grid, st, k); break;
     default: {
         static const int rows = [] { const char *e = getenv("DQ_VR_ROWS"); return e ? atoi(e) : 4; }();
         if (rows == 8) launch_vr<4, 8>(have_z, grid, st, k);
@@ -664,8 +672,15 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     }
     DQ_LAUNCH_CHECK();
     if (a.ev_after_stream) DQ_HIP_TRY(hipEventRecord(a.ev_after_stream, st));
-    if (k.P > 1) {
-        vr_dense_finish_kernel<<<dim3(static_cast<unsigned>(a.M)), dim3(kFinishThreads), static_cast<size_t>(d) * sizeof(float), st>>>(k);
+    if (k.P > 1 || nc > 4) {
+        const size_t lds = static_cast<size_t>(d) * sizeof(float);
+        static bool big_lds_allowed = false;             // more than 64 KB of dynamic LDS has to be requested once
+        if (lds > 48 * 1024 && !big_lds_allowed) {
+            DQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(vr_dense_finish_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4));
+            big_lds_allowed = true;
+        }
+        vr_dense_finish_kernel<<<dim3(static_cast<unsigned>(a.M)), dim3(kFinishThreads), lds, st>>>(k);
         DQ_LAUNCH_CHECK();
     }
     return DQ_OK;

@@ -43,7 +43,7 @@ def _model(rng, d, b_x, x_snap, spread=0.05):
     return oracle.pack(k, b_x), dx, oracle.dequantize(k, dx)
 
 
-PROBLEMS = [(2000, 1000), (37, 13), (300, 4096), (129, 2048), (64, 1027)]
+PROBLEMS = [(2000, 1000), (37, 13), (300, 4096), (129, 2048), (64, 1027), (150, 6000), (90, 16384), (70, 12003)]
 
 
 @pytest.mark.parametrize("n,d", PROBLEMS)
@@ -75,7 +75,8 @@ def test_full_grad(dq, n, d):
 
 @pytest.mark.parametrize("have_z", [True, False])
 @pytest.mark.parametrize("b_x", [8, 4, 32])
-@pytest.mark.parametrize("n,d,M,B", [(2000, 1000, 4, 16), (300, 4096, 3, 40), (64, 1027, 2, 5), (500, 2048, 33, 7)])
+@pytest.mark.parametrize("n,d,M,B", [(2000, 1000, 4, 16), (300, 4096, 3, 40), (64, 1027, 2, 5), (500, 2048, 33, 7),
+                                     (150, 6000, 3, 40), (90, 16384, 2, 9), (70, 12003, 2, 33)])
 def test_vr_grad(dq, n, d, M, B, b_x, have_z):
     p = synth.dense_logistic(n, d, seed=d, l2=1e-3)
     P = dq.DeviceProblem.from_host(p) if d % 4 == 0 else None
@@ -134,7 +135,8 @@ def test_vr_grad_flag_bit_and_bad_index(dq):
 
 @pytest.mark.parametrize("sparsify", [False, True])
 @pytest.mark.parametrize("b", [8, 4, 2])
-@pytest.mark.parametrize("n,d,M,B", [(2000, 1000, 4, 16), (300, 4096, 5, 64), (64, 1027, 2, 5)])
+@pytest.mark.parametrize("n,d,M,B", [(2000, 1000, 4, 16), (300, 4096, 5, 64), (64, 1027, 2, 5), (150, 6000, 3, 40),
+                                     (90, 16384, 2, 9)])
 def test_worker_step(dq, n, d, M, B, b, sparsify):
     p = synth.dense_logistic(n, d, seed=d + 1, l2=1e-3)
     lda = (d + 3) // 4 * 4
@@ -241,12 +243,12 @@ def test_worker_step_full_precision_message(dq):
 
 
 def test_unsupported_and_invalid(dq):
-    p = synth.dense_logistic(20, 5000, seed=0)
+    p = synth.dense_logistic(20, 16388, seed=0)
     P = dq.DeviceProblem.from_host(p)
-    x = torch.zeros(5000, device="cuda")
+    x = torch.zeros(16388, device="cuda")
     with pytest.raises(dq.DqError) as e:
         dq.dq_full_grad(P, x, x.clone(), None, None, torch.zeros(1 << 20, device="cuda"))
-    assert e.value.code == dq.ERR_UNSUPPORTED             # dense rows wider than 4096 have no kernel yet
+    assert e.value.code == dq.ERR_UNSUPPORTED             # dense rows wider than 16384 floats have no kernel
     p = synth.dense_logistic(20, 64, seed=0)
     P = dq.DeviceProblem.from_host(p)
     x = torch.zeros(64, device="cuda")

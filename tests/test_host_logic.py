@@ -85,7 +85,7 @@ def test_problem_and_gradient_argument_checks(lib):
     assert lib.dq_full_grad(C.byref(p), None, P, None, None, P, 1 << 40, None) == INVALID
     bad = dense(lda=4095)
     assert lib.dq_full_grad(C.byref(bad), P, P, None, None, P, 1 << 40, None) == INVALID
-    wide = dense(d=5000, lda=5000)
+    wide = dense(d=20000, lda=20000)               # dense rows of more than 16384 floats
     assert lib.dq_full_grad(C.byref(wide), P, P, None, None, P, 1 << 40, None) == UNSUPPORTED
     huge = csr(d=(1 << 20) + 4)                    # staged entries address at most 2^20 columns
     assert lib.dq_full_grad(C.byref(huge), P, P, None, None, P, 1 << 40, None) == UNSUPPORTED
