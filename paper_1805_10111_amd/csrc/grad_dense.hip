@@ -658,8 +658,8 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     const dim3 grid(k.P, static_cast<unsigned>(a.M));
     const bool have_z = a.z_snap != nullptr;
     switch (nc) {
-    case 1: launch_vr<1, 8>(have_z, grid, st, k); break;
-    case 2: launch_vr<2, 4>(have_z, grid, st, k); break;
+    case 1: launch_vr<1, 16>(have_z, grid, st, k); break;
+    case 2: launch_vr<2, 8>(have_z, grid, st, k); break;
     case 8: launch_vr<8, 2>(have_z, grid, st, k); break;
     case 16: launch_vr<16, 1>(have_z, grid, st, k); break;
     default: {
