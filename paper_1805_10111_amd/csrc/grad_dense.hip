@@ -498,18 +498,20 @@ __global__ __launch_bounds__(kRowThreads) void full_dense_partial_kernel(
     }
 }
 
-// g = sum_p partial_p + l2*x.  Block (64 x 16): thread (tx, ty) adds partials ty, ty+16, ... of
-// float4 column blockIdx.x*64 + tx; the 16 sub-sums are then added in ty order.
+// g = sum_p partial_p + l2*x.  Block (16 x 64): thread (tx, ty) adds partials ty, ty+64, ... of
+// float4 column blockIdx.x*16 + tx; the 64 sub-sums are then added in two fixed steps (8 threads add
+// 8 each, one adds those 8).  Narrow column tiles keep many compute units busy (d = 4096: 64 blocks).
 // Block 0 also writes P(x) = loss/n + (l2/2)||x||^2 + l1||x||_1.
-constexpr int kFinishY = 16;
-__global__ __launch_bounds__(kWave *kFinishY) void full_finish_kernel(
+constexpr int kFinishX = 16, kFinishY = 64;
+__global__ __launch_bounds__(kFinishX *kFinishY) void full_finish_kernel(
     const float *__restrict__ partial, int P, int64_t ldp, int64_t n, int64_t d, const float *__restrict__ x, float l2,
     float l1, const double *__restrict__ loss_partial, float *__restrict__ g_out, double *__restrict__ obj_out)
 {
-    __shared__ float4 sh[kFinishY][kWave];
-    __shared__ double sdl[kFinishY * 3];
+    __shared__ float4 sh[kFinishY][kFinishX];
+    __shared__ float4 sh2[8][kFinishX];
+    __shared__ double sdl[(kFinishX * kFinishY / kWave) * 3];
     const int tx = threadIdx.x, ty = threadIdx.y;
-    const int64_t k = static_cast<int64_t>(blockIdx.x) * kWave + tx;      // float4 index
+    const int64_t k = static_cast<int64_t>(blockIdx.x) * kFinishX + tx;      // float4 index
     const int64_t col = 4 * k;
     float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     if (col < ldp) {
@@ -520,10 +522,19 @@ __global__ __launch_bounds__(kWave *kFinishY) void full_finish_kernel(
     }
     sh[ty][tx] = s;
     __syncthreads();
+    if (ty < 8) {
+        float4 t = sh[ty][tx];
+        for (int j = 1; j < kFinishY / 8; ++j) {
+            const float4 u = sh[ty + 8 * j][tx];
+            t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
+        }
+        sh2[ty][tx] = t;
+    }
+    __syncthreads();
     if (ty == 0 && col < d) {
-        float4 t = sh[0][tx];
-        for (int j = 1; j < kFinishY; ++j) {
-            t.x += sh[j][tx].x; t.y += sh[j][tx].y; t.z += sh[j][tx].z; t.w += sh[j][tx].w;
+        float4 t = sh2[0][tx];
+        for (int j = 1; j < 8; ++j) {
+            t.x += sh2[j][tx].x; t.y += sh2[j][tx].y; t.z += sh2[j][tx].z; t.w += sh2[j][tx].w;
         }
         const float v[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
@@ -531,7 +542,7 @@ __global__ __launch_bounds__(kWave *kFinishY) void full_finish_kernel(
             if (col + e < d) g_out[col + e] = v[e] + l2 * x[col + e];
     }
     if (blockIdx.x == 0 && obj_out) {
-        const int tid = ty * kWave + tx, nt = kWave * kFinishY;
+        const int tid = ty * kFinishX + tx, nt = kFinishX * kFinishY;
         double loss = 0.0, sq = 0.0, ab = 0.0;
         for (int p = tid; p < P; p += nt) loss += loss_partial[p];
         for (int64_t j = tid; j < d; j += nt) {
@@ -542,11 +553,11 @@ __global__ __launch_bounds__(kWave *kFinishY) void full_finish_kernel(
         loss = wave_sum_f64(loss);
         sq = wave_sum_f64(sq);
         ab = wave_sum_f64(ab);
-        if (tx == 0) { sdl[ty * 3] = loss; sdl[ty * 3 + 1] = sq; sdl[ty * 3 + 2] = ab; }
+        if ((tid & (kWave - 1)) == 0) { const int w = tid / kWave; sdl[w * 3] = loss; sdl[w * 3 + 1] = sq; sdl[w * 3 + 2] = ab; }
         __syncthreads();
         if (tid == 0) {
             double L = 0.0, S = 0.0, A = 0.0;
-            for (int j = 0; j < kFinishY; ++j) { L += sdl[j * 3]; S += sdl[j * 3 + 1]; A += sdl[j * 3 + 2]; }
+            for (int j = 0; j < nt / kWave; ++j) { L += sdl[j * 3]; S += sdl[j * 3 + 1]; A += sdl[j * 3 + 2]; }
             obj_out[0] = L / static_cast<double>(n) + 0.5 * static_cast<double>(l2) * S + static_cast<double>(l1) * A;
         }
     }
@@ -555,7 +566,7 @@ __global__ __launch_bounds__(kWave *kFinishY) void full_finish_kernel(
 int launch_full_finish(const float *partial, int P, int64_t ldp, int64_t n, int64_t d, const float *x, float l2, float l1,
                        const double *loss_partial, float *g_out, double *obj_out, hipStream_t st)
 {
-    full_finish_kernel<<<dim3(static_cast<unsigned>(ceil_div(ceil_div(d, 4), kWave))), dim3(kWave, kFinishY), 0, st>>>(
+    full_finish_kernel<<<dim3(static_cast<unsigned>(ceil_div(ceil_div(d, 4), kFinishX))), dim3(kFinishX, kFinishY), 0, st>>>(
         partial, P, ldp, n, d, x, l2, l1, loss_partial, g_out, obj_out);
     DQ_LAUNCH_CHECK();
     return DQ_OK;
