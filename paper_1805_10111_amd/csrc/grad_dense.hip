@@ -29,14 +29,22 @@ constexpr int kRowWaves = kRowThreads / kWave;
 constexpr int kMaxRowsPerBlock = 256;            // mini-batch rows a block may own (LDS metadata)
 
 // Thread's share of a row: float4 columns tid + 256*c, c < NC; zero past d.
-template <int NC>
+// STREAM: the row is read once and not again soon (the gathered rows of a mini-batch), so the load is
+// marked non-temporal; the contiguous sweep of the full gradient is faster without the mark (measured).
+template <int NC, bool STREAM = false>
 __device__ __forceinline__ void load_cols(const float *__restrict__ row, int64_t d, float4 (&a)[NC])
 {
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
         if (col + 3 < d) {
-            a[c] = *reinterpret_cast<const float4 *>(row + col);
+            if constexpr (STREAM) {
+                typedef float v4f __attribute__((ext_vector_type(4)));
+                const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(row + col));
+                a[c] = make_float4(t.x, t.y, t.z, t.w);
+            } else {
+                a[c] = *reinterpret_cast<const float4 *>(row + col);
+            }
         } else {
             a[c].x = col + 0 < d ? row[col + 0] : 0.0f;
             a[c].y = col + 1 < d ? row[col + 1] : 0.0f;
@@ -268,7 +276,7 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int i = rb + r < nrows ? sh_row[rb + r] : -1;
-            if (i >= 0) load_cols<NC>(a.X + static_cast<int64_t>(i) * a.lda, d, row[r]);
+            if (i >= 0) load_cols<NC, true>(a.X + static_cast<int64_t>(i) * a.lda, d, row[r]);
             else zero_cols<NC>(row[r]);
         }
     };
