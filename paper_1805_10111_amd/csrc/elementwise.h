@@ -15,7 +15,26 @@ struct Words16 {
     static constexpr int n = 16 * FIELD / 32;
 };
 
-template <int FIELD>
+// 16-byte accesses marked non-temporal: for data that is touched once by a kernel streaming over a long
+// vector (measured on this part: a plain read of 1 GiB goes from 5.6 to 6.1 TB/s with the mark).
+typedef float dq_v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t dq_v4u __attribute__((ext_vector_type(4)));
+typedef uint32_t dq_v2u __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float4 load_f4_stream(const float *p)
+{
+    const dq_v4f t = __builtin_nontemporal_load(reinterpret_cast<const dq_v4f *>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+
+__device__ __forceinline__ void store_f4_stream(float *p, float4 v)
+{
+    dq_v4f t;
+    t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
+    __builtin_nontemporal_store(t, reinterpret_cast<dq_v4f *>(p));
+}
+
+template <int FIELD, bool STREAM = false>
 __device__ __forceinline__ void load_words(const uint32_t *__restrict__ row, int64_t c, int64_t row_words,
                                            uint32_t (&w)[Words16<FIELD>::n])
 {
@@ -25,14 +44,24 @@ __device__ __forceinline__ void load_words(const uint32_t *__restrict__ row, int
         if constexpr (kWords >= 4) {
 #pragma unroll
             for (int q = 0; q < kWords / 4; ++q) {
-                const uint4 t = reinterpret_cast<const uint4 *>(row + w0)[q];
-                w[4 * q] = t.x; w[4 * q + 1] = t.y; w[4 * q + 2] = t.z; w[4 * q + 3] = t.w;
+                if constexpr (STREAM) {
+                    const dq_v4u t = __builtin_nontemporal_load(reinterpret_cast<const dq_v4u *>(row + w0) + q);
+                    w[4 * q] = t.x; w[4 * q + 1] = t.y; w[4 * q + 2] = t.z; w[4 * q + 3] = t.w;
+                } else {
+                    const uint4 t = reinterpret_cast<const uint4 *>(row + w0)[q];
+                    w[4 * q] = t.x; w[4 * q + 1] = t.y; w[4 * q + 2] = t.z; w[4 * q + 3] = t.w;
+                }
             }
         } else if constexpr (kWords == 2) {
-            const uint2 t = reinterpret_cast<const uint2 *>(row + w0)[0];
-            w[0] = t.x; w[1] = t.y;
+            if constexpr (STREAM) {
+                const dq_v2u t = __builtin_nontemporal_load(reinterpret_cast<const dq_v2u *>(row + w0));
+                w[0] = t.x; w[1] = t.y;
+            } else {
+                const uint2 t = reinterpret_cast<const uint2 *>(row + w0)[0];
+                w[0] = t.x; w[1] = t.y;
+            }
         } else {
-            w[0] = row[w0];
+            w[0] = STREAM ? __builtin_nontemporal_load(row + w0) : row[w0];
         }
     } else {
 #pragma unroll
@@ -55,13 +84,14 @@ __device__ __forceinline__ float value_of(const uint32_t (&w)[Words16<FIELD>::n]
     else return static_cast<float>(code_of<FIELD>(w, j));
 }
 
+template <bool STREAM = false>
 __device__ __forceinline__ void load16(const float *__restrict__ src, int64_t base, int64_t d, float (&a)[16])
 {
     if (base + 16 <= d) {
         const float4 *p = reinterpret_cast<const float4 *>(src + base);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const float4 t = p[q];
+            const float4 t = STREAM ? load_f4_stream(src + base + 4 * q) : p[q];
             a[4 * q] = t.x; a[4 * q + 1] = t.y; a[4 * q + 2] = t.z; a[4 * q + 3] = t.w;
         }
     } else {
@@ -70,9 +100,16 @@ __device__ __forceinline__ void load16(const float *__restrict__ src, int64_t ba
     }
 }
 
+template <bool STREAM = false>
 __device__ __forceinline__ void store16(float *__restrict__ out, int64_t base, int64_t d, const float (&a)[16])
 {
     if (base + 16 <= d) {
+        if constexpr (STREAM) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                store_f4_stream(out + base + 4 * q, make_float4(a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]));
+            return;
+        }
         float4 *p = reinterpret_cast<float4 *>(out + base);
         p[0] = make_float4(a[0], a[1], a[2], a[3]);
         p[1] = make_float4(a[4], a[5], a[6], a[7]);
@@ -87,7 +124,7 @@ __device__ __forceinline__ void store16(float *__restrict__ out, int64_t base, i
 
 // Alg. 1, master (ii), receive side: acc[j] = sum_{m<M} delta[m] * k_m[16c + j], m ascending, one fma each.
 // For FIELD == 32 the rows hold float32 values and delta is taken as 1.
-template <int FIELD>
+template <int FIELD, bool STREAM = false>
 __device__ __forceinline__ void decode_sum16(const uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words,
                                              const float *__restrict__ delta, int M, int64_t c, int64_t d, float (&acc)[16])
 {
@@ -101,7 +138,7 @@ __device__ __forceinline__ void decode_sum16(const uint32_t *__restrict__ packed
         float dm[kGroup];
 #pragma unroll
         for (int u = 0; u < kGroup; ++u) {
-            load_words<FIELD>(packed + static_cast<int64_t>(m + u) * ld_words, c, row_words, w[u]);
+            load_words<FIELD, STREAM>(packed + static_cast<int64_t>(m + u) * ld_words, c, row_words, w[u]);
             dm[u] = FIELD == 32 ? 1.0f : delta[m + u];
         }
 #pragma unroll
@@ -111,7 +148,7 @@ __device__ __forceinline__ void decode_sum16(const uint32_t *__restrict__ packed
     }
     for (; m < M; ++m) {
         uint32_t w[Words16<FIELD>::n];
-        load_words<FIELD>(packed + static_cast<int64_t>(m) * ld_words, c, row_words, w);
+        load_words<FIELD, STREAM>(packed + static_cast<int64_t>(m) * ld_words, c, row_words, w);
         const float dm = FIELD == 32 ? 1.0f : delta[m];
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[j] = fmaf(dm, value_of<FIELD>(w, j), acc[j]);

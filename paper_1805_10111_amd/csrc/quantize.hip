@@ -43,21 +43,27 @@ __global__ __launch_bounds__(kThreads) void absmax_kernel(const float *__restric
 {
     __shared__ uint32_t scratch[kThreads / kWave];
     const float *row = v + static_cast<int64_t>(blockIdx.y) * ld;
-    const int64_t chunks = (d + kCoordsPerThread - 1) / kCoordsPerThread;
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    // a block sweeps tiles of 4 x 256 quads; within a tile consecutive lanes read consecutive quads
+    const int64_t quads = (d + 3) / 4;
+    const int64_t tiles = (quads + 4 * kThreads - 1) / (4 * kThreads);
     uint32_t m = 0;
-    for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
-        const int64_t base = c * kCoordsPerThread;
-        if (base + kCoordsPerThread <= d) {
-            const float4 *p = reinterpret_cast<const float4 *>(row + base);
-            const float4 a0 = p[0], a1 = p[1], a2 = p[2], a3 = p[3];
-            m = max(m, max(max(abs_bits(a0.x), abs_bits(a0.y)), max(abs_bits(a0.z), abs_bits(a0.w))));
-            m = max(m, max(max(abs_bits(a1.x), abs_bits(a1.y)), max(abs_bits(a1.z), abs_bits(a1.w))));
-            m = max(m, max(max(abs_bits(a2.x), abs_bits(a2.y)), max(abs_bits(a2.z), abs_bits(a2.w))));
-            m = max(m, max(max(abs_bits(a3.x), abs_bits(a3.y)), max(abs_bits(a3.z), abs_bits(a3.w))));
-        } else {
-            for (int64_t i = base; i < d; ++i) m = max(m, abs_bits(row[i]));
+    for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
+        const int64_t q0 = t * 4 * kThreads + threadIdx.x;
+        float4 a[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int64_t q = q0 + k * kThreads;
+            if (4 * q + 3 < d) {
+                typedef float v4f __attribute__((ext_vector_type(4)));
+                const v4f t4 = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(row) + q);
+                a[k] = make_float4(t4.x, t4.y, t4.z, t4.w);
+            } else {
+                a[k] = q < quads ? load_quad(row, q, d) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            }
         }
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            m = max(m, max(max(abs_bits(a[k].x), abs_bits(a[k].y)), max(abs_bits(a[k].z), abs_bits(a[k].w))));
     }
     m = block_max_u32(m, scratch);
     if (threadIdx.x == 0 && m != 0) atomicMax(absmax_bits + blockIdx.y, m);
@@ -283,10 +289,10 @@ __global__ __launch_bounds__(kThreads) void unpack_dequant_sum_kernel(
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
     for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
         float acc[16];
-        decode_sum16<FIELD>(packed, ld_words, row_words, delta, M, c, d, acc);
+        decode_sum16<FIELD, true>(packed, ld_words, row_words, delta, M, c, d, acc);
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[j] = scale * acc[j];
-        store16(out, c * kCoordsPerThread, d, acc);
+        store16<false>(out, c * kCoordsPerThread, d, acc);
     }
 }
 
