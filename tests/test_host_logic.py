@@ -103,7 +103,7 @@ def test_workspace_sizes(lib):
     full = lib.dq_workspace_bytes(1, C.byref(p), 0, 0)
     vr = lib.dq_workspace_bytes(2, C.byref(p), 32, 256)
     assert full % 16 == 0 and vr % 16 == 0
-    assert full >= 1024 * 4096 * 4                     # up to 1024 partial d-vectors
+    assert full >= 512 * 4096 * 4                      # up to 512 partial d-vectors
     assert vr == 32 * 16 * 4096 * 4                    # M * P * d floats with P = 512/M blocks per worker
     small = dense(n=2000, d=1000)
     assert lib.dq_workspace_bytes(2, C.byref(small), 4, 16) == 4 * 1 * 1000 * 4       # small batch: one block per worker
