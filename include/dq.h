@@ -60,7 +60,8 @@ extern "C" {
 /* Finite-sum problem of eq. (1) with logistic loss (Section 5.1).
  * layout 0: dense row-major features, row i at dense + i*lda, lda % 4 == 0,
  *           dense 16-byte aligned.
- * layout 1: CSR; indptr[n+1], indices sorted and unique within a row.
+ * layout 1: CSR; indptr[n+1], indices sorted and unique within a row; indices and values must
+ *           be non-null even when the matrix has no nonzeros (they are then never read).
  * y[n] holds +1/-1.  l2 multiplies ||x||^2/2 inside every f_i (smooth part),
  * l1 multiplies ||x||_1 in h (handled by the prox). */
 typedef struct dq_problem {

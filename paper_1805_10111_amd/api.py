@@ -178,8 +178,13 @@ class DeviceProblem:
     def from_host(cls, prob, device="cuda") -> "DeviceProblem":
         """Upload a host problem (numpy arrays: see synth.Problem)."""
         t = lambda a: None if a is None else torch.from_numpy(a).to(device)
+
+        def entries(a):                      # a matrix without nonzeros still needs non-null entry arrays
+            if a is None:
+                return None
+            return t(a) if a.size else torch.zeros(1, dtype=torch.from_numpy(a).dtype, device=device)
         return cls(n=prob.n, d=prob.d, y=t(prob.y), l2=float(prob.l2), l1=float(prob.l1), dense=t(prob.dense),
-                   indptr=t(prob.indptr), indices=t(prob.indices), values=t(prob.values))
+                   indptr=t(prob.indptr), indices=entries(prob.indices), values=entries(prob.values))
 
 
 # ------------------------------------------------------------------ plumbing
