@@ -199,7 +199,7 @@ def cpu_baseline(cfg, prob, seconds):
 def main():
     args = parse()
     if args.gpus != 1:
-        print(f"bench.py: this build runs on one GPU (the M workers are a batch dimension on it); "
+        print(f"bench.py: the library runs on one GPU (the M workers are a batch dimension on it); "
               f"--gpus {args.gpus} is not supported", file=sys.stderr)
         sys.exit(2)
     import numpy as np

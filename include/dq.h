@@ -46,7 +46,7 @@ extern "C" {
 
 #define DQ_OK                0
 #define DQ_ERR_INVALID_ARG  (-1)  /* null / misaligned pointer, size <= 0, b out of range */
-#define DQ_ERR_UNSUPPORTED  (-2)  /* valid request this build has no kernel for */
+#define DQ_ERR_UNSUPPORTED  (-2)  /* valid request the library has no kernel for */
 #define DQ_ERR_WORKSPACE    (-3)  /* workspace smaller than dq_workspace_bytes() */
 #define DQ_ERR_DEVICE       (-4)  /* a HIP call failed; see dq_last_device_error() */
 

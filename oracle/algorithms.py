@@ -3,7 +3,7 @@
 The M workers of the parameter-server network are taken as one synchronous round:
 all M read the same quantized model, the master averages the M decoded gradients and
 takes one proximal step (the paper applies gradients one at a time with bounded
-staleness; a round with zero staleness is this build's reading).  The iteration
+staleness; a round with zero staleness is the reading taken here).  The iteration
 counter ``it = epoch_index * m + t`` addresses the random streams.
 
 Bounded delay (Assumption 3, Section 3.2) can be emulated: with ``tau > 0`` the M workers are split

@@ -32,7 +32,7 @@
 /* Counter-based random numbers: Philox4x32-10 (Salmon, Moraes, Dror, Shaw,   */
 /* "Parallel random numbers: as easy as 1, 2, 3", SC'11), written from its    */
 /* published definition.  The paper only says "with probability"; the stream  */
-/* addressing below (what goes in the key and the counter) is this build's.   */
+/* addressing below (what goes in the key and the counter) is a choice made here. */
 /* ------------------------------------------------------------------------- */
 
 enum { REF_TAG_GRAD = 0, REF_TAG_MODEL = 1, REF_TAG_SPARSIFY = 2, REF_TAG_SAMPLE = 3 };
@@ -311,7 +311,7 @@ void ref_sparse_decode(const uint32_t *words, int64_t nnz, int64_t d, int b, int
 /*   f_i(x) = log(1 + exp(-y_i a_i.x)) + (l2/2)||x||^2   (smooth part)        */
 /*   h(x)   = l1 ||x||_1                                  (prox part)         */
 /* Section 5.1 uses logistic regression with L1 and L2 weights; putting the   */
-/* L2 term in f and the L1 term in h is this build's reading.                 */
+/* L2 term in f and the L1 term in h is the reading taken here.                */
 /* Rows are dense (row-major, leading dimension lda) or CSR.                  */
 /* ------------------------------------------------------------------------- */
 

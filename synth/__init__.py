@@ -167,7 +167,7 @@ class Config:
     seed: int = 0
 
 
-# The five workloads.  lr, m and S for C2..C4 are choices of this build (the paper
+# The five workloads.  lr, m and S for C2..C4 are choices made here (the paper
 # tunes lr on a grid and uses m = ceil(n/B)); they are listed in the design notes.
 CONFIGS = {
     "C1": Config("C1", "asylpg", n=2000, d=1000, M=4, B=16, b_x=8, b=8, m=500, S=1,
