@@ -86,7 +86,8 @@ __device__ __forceinline__ void csr_prefix_lengths(RowMeta &meta, int nrows)
     __syncthreads();
 }
 
-// Steps 1-3 for rows [0, nrows) described by `meta`, accumulating into alpha (LDS).
+// Stage, margins and scatter (the first three phases of the file header) for rows [0, nrows) described by `meta`,
+// accumulating into alpha (LDS).
 // The rows are taken in groups that fit the staging buffer (`stage`, `cap` (column, value) entries):
 //   stage  : the group's (column, value) pairs are copied to LDS as one flat run, four entries per thread
 //            in flight, the row number packed above the column;
