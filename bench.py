@@ -242,8 +242,21 @@ def main():
         inner_rounds += tr.m
         tr.epoch_epilogue()
 
+    # what an event bracket reads with nothing inside it (the cost of the bracket itself on a busy stream):
+    # pairs of events recorded back to back right after a round's kernels
+    tr.epoch_prologue()
+    empty = []
+    for k in range(min(tr.m, 24)):
+        tr.rounds(k, 1)
+        ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ea.record(); eb.record()
+        empty.append((ea, eb))
+    torch.cuda.synchronize()
+    bracket_s = float(np.median([ea.elapsed_time(eb) for ea, eb in empty])) * 1e-3
+
     # dominant kernel: the row-streaming kernel of the worker step (all M workers in one launch);
-    # flag-bit rounds read no rows and are skipped
+    # flag-bit rounds read no rows and are skipped.  The bracket reading is used as it is (an upper bound of the
+    # kernel's own duration: the empty bracket is reported next to it).
     durs = [e0.elapsed_time(e1) * 1e-3 for e0, e1, flag in events if not flag]
     k_avg = float(np.mean(durs))
     if prob.dense is not None:
@@ -272,7 +285,8 @@ def main():
         "roofline": {"bound": "hbm", "kernel": KERNEL_NAME[prob.is_csr],
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": recorded_traffic(cfg.name),
-                     "bytes_per_launch": alg_bytes, "avg_launch_us": round(k_avg * 1e6, 2)},
+                     "bytes_per_launch": alg_bytes, "avg_launch_us": round(k_avg * 1e6, 2),
+                     "empty_bracket_us": round(bracket_s * 1e6, 2)},
     }
     del tr, P
     torch.cuda.empty_cache()
