@@ -106,19 +106,23 @@ def main():
     ap.add_argument("--rounds", type=int, default=None, help="rounds per epoch (default: the config's)")
     ap.add_argument("--threshold", type=float, default=0.6)
     ap.add_argument("--bits", type=int, default=8, help="b of the quantized algorithms")
+    ap.add_argument("--lr", type=float, default=None, help="step size (default: the config's; the paper tunes it per data set)")
     ap.add_argument("--mu-sweep", action="store_true", help="study of mu / b_x instead of the six-algorithm comparison")
     ap.add_argument("--widths", type=int, nargs="+", default=[2, 3, 4, 5, 6, 7, 8, 9, 10, 11])
     args = ap.parse_args()
     cfg = synth.CONFIGS[args.config]
+    if args.lr is not None:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, lr=args.lr)
     prob = synth.make_problem(cfg, n=args.n)
     if args.mu_sweep:
         res = mu_sweep(cfg, prob, args.widths, args.epochs, args.threshold, args.bits, args.rounds)
         print(json.dumps({"config": cfg.name, "n": prob.n, "d": prob.d, "M": cfg.M, "B": cfg.B, "threshold": args.threshold,
-                          "b": args.bits, "mu_sweep": res}, indent=1))
+                          "b": args.bits, "lr": cfg.lr, "mu_sweep": res}, indent=1))
         return
     res = run_comparison(cfg, prob, args.epochs, args.threshold, args.bits, args.rounds)
     print(json.dumps({"config": cfg.name, "n": prob.n, "d": prob.d, "M": cfg.M, "B": cfg.B, "threshold": args.threshold,
-                      "b": args.bits, "results": res}, indent=1))
+                      "b": args.bits, "lr": cfg.lr, "results": res}, indent=1))
 
 
 if __name__ == "__main__":
