@@ -67,11 +67,18 @@ struct WorkerOut {
 // LDS access per lane, consecutive lanes on consecutive quads).  A quad yields 4*FIELD code
 // bits; for FIELD < 8 the lanes of a pair (FIELD 4) or of a group of four (FIELD 2) combine
 // theirs into one word with cross-lane moves, and the first lane of the group stores it.
+// Several blocks may hold identical copies of alpha (the CSR worker step launches `nslices` of them per worker when
+// compute units would otherwise idle): each repeats the norms and the sparsifier on the whole vector, which gives
+// every block the same scale, and quantizes + packs only its own slice of the quads.  out.nnz_out must then be null.
 template <int FIELD>
 __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bool sparsify, int b, StreamKey key,
-                                                     const WorkerOut &out, uint32_t *su, int *si)
+                                                     const WorkerOut &out, uint32_t *su, int *si, int slice = 0,
+                                                     int nslices = 1)
 {
     const int64_t quads = (d + 3) / 4;
+    // slice boundaries are multiples of 64 quads, so no packed word is shared between two slices
+    const int64_t per = ((quads + nslices - 1) / nslices + kWave - 1) / kWave * kWave;
+    const int64_t q_lo = min(quads, per * slice), q_hi = min(quads, q_lo + per);
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t first = threadIdx.x - lane;           // quad of lane 0 in the first sweep (wave-uniform)
     uint32_t vmax = 0;
@@ -100,6 +107,7 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
     if constexpr (FIELD == 32) {
         // no gradient quantization (the full-precision comparison runs of Section 5.1):
         // the message is the float32 vector itself and its scale is 1
+        if (slice != 0) return;                      // the float32 message is copied by the first block alone
         if (threadIdx.x == 0) out.delta_out[0] = 1.0f;
         int nzf = 0;
         for (int64_t i = threadIdx.x; i < d; i += blockDim.x) {
@@ -114,7 +122,7 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
         return;
     } else {
         const Scale s = make_scale(__uint_as_float(vmax), b);
-        if (threadIdx.x == 0) {
+        if (threadIdx.x == 0 && slice == 0) {
             out.delta_out[0] = s.delta;
             if (s.bad && out.status) atomicOr(out.status, 1u);
         }
@@ -122,11 +130,11 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
         int nz = 0;
         // every lane of a wavefront takes the same number of sweeps, so that the cross-lane
         // moves of the store always see all lanes; lanes past the end contribute zero bits
-        for (int64_t q0 = first; q0 < quads; q0 += blockDim.x) {
+        for (int64_t q0 = q_lo + first; q0 < q_hi; q0 += blockDim.x) {
             const int64_t q = q0 + lane;
             uint32_t bits = 0;
-            if (q < quads) bits = quantize_quad<FIELD>(load_quad(alpha, q, d), s, key, q, nz);
-            store_quad_bits<FIELD>(bits, q, quads, out.packed);
+            if (q < q_hi) bits = quantize_quad<FIELD>(load_quad(alpha, q, d), s, key, q, nz);
+            store_quad_bits<FIELD>(bits, q, q_hi, out.packed);
         }
         if (out.nnz_out) {
             nz = block_sum_i32(nz, si);

@@ -278,7 +278,8 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
 
     const int m = blockIdx.x;
     const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
-    if (a.zero_word && blockIdx.x == 0 && threadIdx.x == 0) *a.zero_word = 0u;
+    const int slice = blockIdx.y, nslices = gridDim.y;       // identical copies of the worker; they share only the tail
+    if (a.zero_word && blockIdx.x == 0 && slice == 0 && threadIdx.x == 0) *a.zero_word = 0u;
     float *alpha_row = a.alpha_ws ? a.alpha_ws + static_cast<int64_t>(m) * a.ld_ws : nullptr;   // only with several windows
 
     const float fB = static_cast<float>(a.B);
@@ -347,7 +348,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     float *av = alpha_row ? alpha_row : alpha;
 
     // 4. outputs
-    if (a.alpha_out)
+    if (a.alpha_out && slice == 0)
         for (int64_t j = threadIdx.x; j < d; j += kCsrThreads) a.alpha_out[static_cast<int64_t>(m) * a.ld + j] = av[j];
     if (!a.packed) {
         uint32_t vmax = 0;
@@ -369,10 +370,10 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     const WorkerOut out{a.packed + static_cast<int64_t>(m) * a.ld_words, a.row_words, a.delta_out + m,
                         a.nnz_out ? a.nnz_out + m : nullptr, a.status};
     switch (a.b) {
-    case 2: worker_tail_from_lds<2>(av, d, a.sparsify != 0, a.b, key, out, su, si); break;
-    case 4: worker_tail_from_lds<4>(av, d, a.sparsify != 0, a.b, key, out, su, si); break;
-    case 32: worker_tail_from_lds<32>(av, d, a.sparsify != 0, a.b, key, out, su, si); break;
-    default: worker_tail_from_lds<8>(av, d, a.sparsify != 0, a.b, key, out, su, si); break;
+    case 2: worker_tail_from_lds<2>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
+    case 4: worker_tail_from_lds<4>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
+    case 32: worker_tail_from_lds<32>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
+    default: worker_tail_from_lds<8>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
     }
 }
 
@@ -546,7 +547,12 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     static bool attr_done = false;
     int rc = allow_big_lds(csr_worker_kernel, attr_done);
     if (rc != DQ_OK) return rc;
-    csr_worker_kernel<<<dim3(static_cast<unsigned>(a.M)), dim3(kCsrThreads), lds, st>>>(k);
+    // Few workers leave most compute units idle while each block spends a third of its time on the Philox rounds of
+    // the final quantization: then several identical blocks per worker share that part (not when the nonzero count is
+    // wanted, which would need a sum across blocks, nor when the gradient lives in the per-worker workspace row).
+    unsigned slices = 1;
+    if (a.packed && !a.nnz_out && plan.nwin == 1 && a.b != 32 && d >= 4096 && a.M * 4 <= 128) slices = 4;
+    csr_worker_kernel<<<dim3(static_cast<unsigned>(a.M), slices), dim3(kCsrThreads), lds, st>>>(k);
     DQ_LAUNCH_CHECK();
     if (a.ev_after_stream) DQ_HIP_TRY(hipEventRecord(a.ev_after_stream, st));
     return DQ_OK;

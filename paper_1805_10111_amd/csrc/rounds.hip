@@ -61,7 +61,9 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
             w.sparsify = cfg->algo == DQ_ALGO_SPARSE; w.b = cfg->b; w.seed = cfg->seed; w.iter = it;
             w.worker0 = static_cast<uint32_t>(w_lo);
             w.packed = st->packed + w_lo * st->ld_words; w.ld_words = st->ld_words; w.delta_out = st->delta + w_lo;
-            w.nnz_out = st->nnz ? st->nnz + t * cfg->M + w_lo : nullptr; w.status = st->status;
+            // nonzero counts are what the sparse message size is computed from; the other algorithms do not need them
+            w.nnz_out = (st->nnz && cfg->algo == DQ_ALGO_SPARSE) ? st->nnz + t * cfg->M + w_lo : nullptr;
+            w.status = st->status;
             w.ws = st->ws; w.ws_bytes = st->ws_bytes;
             if (g == 0) w.zero_word = reinterpret_cast<uint32_t *>(st->absmax_x);   // for the master's max below
             if (worker_events && g == 0) {

@@ -208,3 +208,29 @@ def test_flag_bit_round_and_limits(dq, problems):
                           torch.zeros((3, 11812), dtype=torch.int32, device="cuda"), torch.zeros(3, device="cuda"),
                           None, None, None, None)
     assert e.value.code == dq.ERR_WORKSPACE
+
+
+@pytest.mark.parametrize("sparsify", [False, True])
+@pytest.mark.parametrize("b", [8, 4, 2])
+def test_worker_step_without_nonzero_counts_uses_several_blocks_per_worker(dq, problems, b, sparsify):
+    """Without nnz_out the final quantization of a worker is shared by several identical blocks: same bits."""
+    p = problems["text"]
+    P = dq.DeviceProblem.from_host(p)
+    d, n = p.d, p.n
+    M, B = 5, 40
+    rng = np.random.default_rng(8)
+    x_snap = (0.3 * rng.standard_normal(d)).astype(np.float32)
+    xq, dx, _ = _model(rng, d, 8, x_snap)
+    xs_d, xq_d, dx_d = dev(x_snap), dev(xq.view(np.int32)), dev(np.array([dx], dtype=np.float32))
+    nw = dq.packed_words(d, b)
+    ldw = (nw + 3) // 4 * 4
+    outs = []
+    for want_nnz in (True, False):
+        packed = torch.full((M, ldw), -1, dtype=torch.int32, device="cuda")
+        delta = torch.zeros(M, device="cuda")
+        nnz = torch.zeros(M, dtype=torch.int32, device="cuda") if want_nnz else None
+        dq.dq_worker_step(P, None, M, B, xq_d, dx_d, 8, False, xs_d, None, sparsify, b, 5, 6, 7, packed, delta, nnz,
+                          None, None, None)
+        outs.append((packed, delta))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    assert np.all(words(outs[1][0])[:, nw:] == 0xFFFFFFFF)
