@@ -69,7 +69,10 @@ struct WorkerOut {
 // theirs into one word with cross-lane moves, and the first lane of the group stores it.
 // Several blocks may hold identical copies of alpha (the CSR worker step launches `nslices` of them per worker when
 // compute units would otherwise idle): each repeats the norms and the sparsifier on the whole vector, which gives
-// every block the same scale, and quantizes + packs only its own slice of the quads.  out.nnz_out must then be null.
+// every block the same scale, and quantizes + packs only its own slice of the quads.  The number of nonzero codes
+// is then only available after the sparsifier with b >= 4, where it equals the number of kept coordinates: a kept
+// coordinate has magnitude ||alpha||_inf up to two roundings, hence |t| > L - 1 >= 2 and a nonzero code whatever the
+// rounding decision, and a dropped one is exactly zero.  Otherwise out.nnz_out must be null when nslices > 1.
 template <int FIELD>
 __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bool sparsify, int b, StreamKey key,
                                                      const WorkerOut &out, uint32_t *su, int *si, int slice = 0,
@@ -92,6 +95,7 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
         StreamKey sk = key;
         sk.tag = DQ_TAG_SPARSIFY;
         uint32_t bmax = 0;
+        int kept = 0;
         for (int64_t q = threadIdx.x; q < quads; q += blockDim.x) {
             float4 a = load_quad(alpha, q, d);
             const uint4 w = stream_block(sk, static_cast<uint32_t>(q));
@@ -100,9 +104,14 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
             a.z = sparsify_one(a.z, rule, w.z);
             a.w = sparsify_one(a.w, rule, w.w);
             bmax = max(max(bmax, abs_bits(a.x)), max(max(abs_bits(a.y), abs_bits(a.z)), abs_bits(a.w)));
+            kept += (a.x != 0.0f) + (a.y != 0.0f) + (a.z != 0.0f) + (a.w != 0.0f);
             store_quad(alpha, q, d, a);
         }
         vmax = block_max_u32(bmax, su);      // (barriers inside also publish the beta writes)
+        if (nslices > 1 && out.nnz_out) {    // see above: equals the number of nonzero codes (b >= 4)
+            kept = block_sum_i32(kept, si);
+            if (threadIdx.x == 0 && slice == 0) out.nnz_out[0] = kept;
+        }
     }
     if constexpr (FIELD == 32) {
         // no gradient quantization (the full-precision comparison runs of Section 5.1):
@@ -136,7 +145,7 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
             if (q < q_hi) bits = quantize_quad<FIELD>(load_quad(alpha, q, d), s, key, q, nz);
             store_quad_bits<FIELD>(bits, q, q_hi, out.packed);
         }
-        if (out.nnz_out) {
+        if (out.nnz_out && nslices == 1) {
             nz = block_sum_i32(nz, si);
             if (threadIdx.x == 0) out.nnz_out[0] = nz;
         }

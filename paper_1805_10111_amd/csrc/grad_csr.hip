@@ -549,9 +549,10 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     if (rc != DQ_OK) return rc;
     // Few workers leave most compute units idle while each block spends a third of its time on the Philox rounds of
     // the final quantization: then several identical blocks per worker share that part (not when the nonzero count is
-    // wanted, which would need a sum across blocks, nor when the gradient lives in the per-worker workspace row).
+    // wanted and would need a sum across blocks, nor when the gradient lives in the per-worker workspace row).
+    const bool count_ok = !a.nnz_out || (a.sparsify && a.b >= 4);      // after the sparsifier: count = kept coordinates
     unsigned slices = 1;
-    if (a.packed && !a.nnz_out && plan.nwin == 1 && a.b != 32 && d >= 4096 && a.M * 4 <= 128) slices = 4;
+    if (a.packed && count_ok && plan.nwin == 1 && a.b != 32 && d >= 4096 && a.M * 4 <= 128) slices = a.M * 8 <= 128 ? 8 : 4;
     csr_worker_kernel<<<dim3(static_cast<unsigned>(a.M), slices), dim3(kCsrThreads), lds, st>>>(k);
     DQ_LAUNCH_CHECK();
     if (a.ev_after_stream) DQ_HIP_TRY(hipEventRecord(a.ev_after_stream, st));
