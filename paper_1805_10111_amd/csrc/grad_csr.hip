@@ -293,6 +293,34 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
         if (have_z) zs = meta.z[r];
         return vr_slope_diff(sh_y[r], zs, dz) / fB;
     };
+    // the rows of one pass: which sample, where its entries start, how many, its label and cached margin
+    struct RowInfo { int row; int64_t start; int len; float y, z; };
+    auto row_info = [&](int r0) {
+        RowInfo ri{-1, 0, 0, 1.0f, 0.0f};
+        const int nrows = min(kCsrMaxRows, a.B - r0);
+        if (static_cast<int>(threadIdx.x) < nrows) {
+            const int r = r0 + threadIdx.x;
+            int64_t i;
+            if (a.idx) {
+                i = a.idx[static_cast<int64_t>(m) * a.B + r];
+            } else {
+                StreamKey sk = a.key;
+                sk.worker = a.worker0 + static_cast<uint32_t>(m);
+                sk.tag = DQ_TAG_SAMPLE;
+                i = __umulhi(stream_word(sk, static_cast<uint64_t>(r)), static_cast<uint32_t>(a.A.n));
+            }
+            if (static_cast<uint64_t>(i) < static_cast<uint64_t>(a.A.n)) {
+                ri.row = static_cast<int>(i);
+                ri.start = a.A.indptr[i];
+                ri.len = static_cast<int>(a.A.indptr[i + 1] - ri.start);
+                ri.y = a.A.y[i];
+                ri.z = have_z ? a.z_snap[i] : 0.0f;
+            }
+        }
+        return ri;
+    };
+    // the first pass's rows are requested before the window is initialised: both sets of loads are in flight together
+    const RowInfo first_rows = row_info(0);
     for (int64_t c0 = 0; c0 < d; c0 += win) {
         const int64_t c1 = min(d, c0 + win);
         // the window starts as the dense part  l2*(q - snapshot); four coordinates per thread and step
@@ -311,24 +339,13 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
         }
         for (int r0 = 0; r0 < a.B; r0 += kCsrMaxRows) {                     // passes of at most kCsrMaxRows rows
             const int nrows = min(kCsrMaxRows, a.B - r0);
+            const RowInfo ri = r0 == 0 ? first_rows : row_info(r0);
             if (static_cast<int>(threadIdx.x) < nrows) {
-                const int r = r0 + threadIdx.x;
-                int64_t i;
-                if (a.idx) {
-                    i = a.idx[static_cast<int64_t>(m) * a.B + r];
-                } else {
-                    StreamKey sk = a.key;
-                    sk.worker = a.worker0 + static_cast<uint32_t>(m);
-                    sk.tag = DQ_TAG_SAMPLE;
-                    i = __umulhi(stream_word(sk, static_cast<uint64_t>(r)), static_cast<uint32_t>(a.A.n));
-                }
-                const bool ok = static_cast<uint64_t>(i) < static_cast<uint64_t>(a.A.n);
-                meta.row[threadIdx.x] = ok ? static_cast<int>(i) : -1;
-                const int64_t s = ok ? a.A.indptr[i] : 0;
-                meta.start[threadIdx.x] = s;
-                meta.len[threadIdx.x] = ok ? static_cast<int>(a.A.indptr[i + 1] - s) : 0;
-                sh_y[threadIdx.x] = ok ? a.A.y[i] : 1.0f;
-                meta.z[threadIdx.x] = (ok && have_z) ? a.z_snap[i] : 0.0f;
+                meta.row[threadIdx.x] = ri.row;
+                meta.start[threadIdx.x] = ri.start;
+                meta.len[threadIdx.x] = ri.len;
+                sh_y[threadIdx.x] = ri.y;
+                meta.z[threadIdx.x] = ri.z;
             }
             csr_prefix_lengths(meta, nrows);
             if (have_z)
