@@ -159,6 +159,9 @@ __device__ __forceinline__ void decode_sum16(const uint32_t *__restrict__ packed
 // v is 16-byte aligned; coordinates past the end of the vector read as zero and are not written.
 __device__ __forceinline__ float4 load_quad(const float *v, int64_t q, int64_t d)
 {
+    // d a multiple of 4 (the same for every thread, so this branch is not a divergent one): every quad is whole.
+    // Only the per-lane test below makes the compiler wait for earlier loads before the next one is issued.
+    if ((d & 3) == 0) return reinterpret_cast<const float4 *>(v)[q];
     if (4 * q + 3 < d) return reinterpret_cast<const float4 *>(v)[q];
     float4 r = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     if (4 * q + 0 < d) r.x = v[4 * q + 0];
@@ -180,19 +183,44 @@ __device__ __forceinline__ void store_quad(float *v, int64_t q, int64_t d, float
 
 // The four values of quad q of one message row: codes as floats (FIELD 2, 4, 8: the quad is a
 // byte, a half word or a word of the packed row) or the floats themselves (FIELD 32).
+// In two steps, so that the loads of many rows can be in flight together: what is fetched (the word that holds
+// the quad, or the four floats), then its four values.
+template <int FIELD>
+struct QuadRaw {
+    uint32_t w;
+};
+template <>
+struct QuadRaw<32> {
+    float4 v;
+};
+
+template <int FIELD>
+__device__ __forceinline__ QuadRaw<FIELD> quad_request(const uint32_t *__restrict__ row, int64_t q, int64_t d)
+{
+    QuadRaw<FIELD> r;
+    if constexpr (FIELD == 32) r.v = load_quad(reinterpret_cast<const float *>(row), q, d);
+    else r.w = row[static_cast<uint32_t>(q / (8 / FIELD))];     // 32-bit index: the row pointer stays a scalar base
+    return r;
+}
+
+template <int FIELD>
+__device__ __forceinline__ float4 quad_decode(const QuadRaw<FIELD> &r, int64_t q)
+{
+    if constexpr (FIELD == 32) {
+        return r.v;
+    } else {
+        constexpr int kQuadsPerWord = 8 / FIELD;
+        const unsigned sh = static_cast<unsigned>(q % kQuadsPerWord) * (4 * FIELD);
+        return make_float4(static_cast<float>(sext_field(r.w, sh, FIELD)), static_cast<float>(sext_field(r.w, sh + FIELD, FIELD)),
+                           static_cast<float>(sext_field(r.w, sh + 2 * FIELD, FIELD)),
+                           static_cast<float>(sext_field(r.w, sh + 3 * FIELD, FIELD)));
+    }
+}
+
 template <int FIELD>
 __device__ __forceinline__ float4 quad_values(const uint32_t *__restrict__ row, int64_t q, int64_t d)
 {
-    if constexpr (FIELD == 32) {
-        return load_quad(reinterpret_cast<const float *>(row), q, d);
-    } else {
-        constexpr int kQuadsPerWord = 8 / FIELD;
-        const uint32_t w = row[q / kQuadsPerWord];
-        const unsigned sh = static_cast<unsigned>(q % kQuadsPerWord) * (4 * FIELD);
-        return make_float4(static_cast<float>(sext_field(w, sh, FIELD)), static_cast<float>(sext_field(w, sh + FIELD, FIELD)),
-                           static_cast<float>(sext_field(w, sh + 2 * FIELD, FIELD)),
-                           static_cast<float>(sext_field(w, sh + 3 * FIELD, FIELD)));
-    }
+    return quad_decode<FIELD>(quad_request<FIELD>(row, q, d), q);
 }
 
 // Q_(delta,b) on quad q: the 4*FIELD code bits (coordinate 4q in the low field) and the number of

@@ -52,6 +52,68 @@ __device__ __forceinline__ float model_value(const ModelMsg &q, int64_t j)
     return q.delta_x * static_cast<float>(sext_field(f, 0, static_cast<unsigned>(q.b_x)));
 }
 
+// The same for the four coordinates col..col+3 (col a multiple of 4), in two steps so that a caller can have the
+// words in flight together with its other loads.  The code bits of such a quad start at bit col*b_x of the message
+// and lie in at most four consecutive words for every width (b_x = 32: exactly four).  The request has no branch:
+// a word index past `last_word` (the last word of the message) repeats that word, which no coordinate below d needs.
+struct ModelQuad {
+    uint32_t w[4];
+};
+
+__device__ __forceinline__ ModelQuad model_quad_request(const ModelMsg &q, int64_t col, int64_t last_word)
+{
+    ModelQuad r;
+    if (q.b_x == 8) {                      // (the width is the same for every thread) the quad is one word
+        r.w[0] = q.words[min(col >> 2, last_word)];
+        r.w[1] = r.w[2] = r.w[3] = 0u;
+        return r;
+    }
+    const int64_t first = (col * q.b_x) >> 5;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) r.w[k] = q.words[min(first + k, last_word)];
+    return r;
+}
+
+// Values of coordinates col..col+3 from the requested words; coordinates at or past d read as 0.
+__device__ __forceinline__ void model_quad_values(const ModelMsg &q, const ModelQuad &r, int64_t col, int64_t d, float (&v)[4])
+{
+    if (q.b_x == 8) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            v[e] = col + e < d ? q.delta_x * static_cast<float>(sext_field(r.w[0], 8u * e, 8u)) : 0.0f;
+        return;
+    }
+    const unsigned shift = static_cast<unsigned>((col * q.b_x) & 31);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const unsigned f = shift + static_cast<unsigned>(e * q.b_x);
+        const unsigned wi = f >> 5, sh = f & 31u;
+        const uint32_t lo = wi == 0 ? r.w[0] : wi == 1 ? r.w[1] : wi == 2 ? r.w[2] : r.w[3];
+        const uint32_t hi = wi == 0 ? r.w[1] : wi == 1 ? r.w[2] : wi == 2 ? r.w[3] : 0u;
+        const uint32_t bits = __funnelshift_r(lo, hi, sh);                 // bits f.. of the four words
+        const float val = q.b_x == 32 ? __uint_as_float(bits)
+                                      : q.delta_x * static_cast<float>(sext_field(bits, 0, static_cast<unsigned>(q.b_x)));
+        v[e] = col + e < d ? val : 0.0f;
+    }
+}
+
+// v[col..col+3] of a vector of d floats (v 16-byte aligned, col a multiple of 4), coordinates at or past d reading
+// as 0, without a per-lane branch (clamped loads), so that the request can stay in flight next to others.
+__device__ __forceinline__ float4 load4_or_zero(const float *__restrict__ v, int64_t col, int64_t d)
+{
+    if ((d & 3) == 0) {                    // (the same for every thread) whole quads only: one 16-byte load
+        const float4 t = *reinterpret_cast<const float4 *>(v + min(col, d - 4));
+        return col < d ? t : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    }
+    float r[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float t = v[min(col + e, d - 1)];
+        r[e] = col + e < d ? t : 0.0f;
+    }
+    return make_float4(r[0], r[1], r[2], r[3]);
+}
+
 // ---- tail of a worker step on alpha[d] in LDS (one block per worker) -------------------
 struct WorkerOut {
     uint32_t *packed;       // row of packed words

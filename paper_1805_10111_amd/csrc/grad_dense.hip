@@ -31,13 +31,15 @@ constexpr int kMaxRowsPerBlock = 256;            // mini-batch rows a block may 
 // Thread's share of a row: float4 columns tid + 256*c, c < NC; zero past d.
 // STREAM: the row is read once and not again soon (the gathered rows of a mini-batch), so the load is
 // marked non-temporal; the contiguous sweep of the full gradient is faster without the mark (measured).
-template <int NC, bool STREAM = false>
+// FULL: d equals 4 * kRowThreads * NC, every column of every thread is a whole float4 inside the row and the loads
+// carry no condition at all.
+template <int NC, bool STREAM = false, bool FULL = false>
 __device__ __forceinline__ void load_cols(const float *__restrict__ row, int64_t d, float4 (&a)[NC])
 {
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
-        if (col + 3 < d) {
+        if (FULL || col + 3 < d) {
             if constexpr (STREAM) {
                 typedef float v4f __attribute__((ext_vector_type(4)));
                 const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(row + col));
@@ -128,6 +130,7 @@ struct VrDenseArgs {
     const int32_t *idx;              // nullable: sampled in the kernel
     int B, P;
     const uint32_t *xq; const float *delta_x; int b_x;
+    int64_t model_last_word;         // index of the last word of the model message
     const float *x_snap, *z_snap;
     float l2;
     float *partial; int64_t ldp;
@@ -141,38 +144,40 @@ struct VrDenseArgs {
     uint32_t *zero_word;             // nullable: set to 0 by one thread of the grid
 };
 
-// dx = q - snapshot for the thread's columns (q: the dequantized model message); xs = the
-// snapshot itself when HAVE_Z is false (margins at the snapshot must then be recomputed).
-template <int NC, bool HAVE_Z>
-__device__ __forceinline__ void model_minus_snapshot(const VrDenseArgs &a, const ModelMsg &msg, float4 (&dx)[NC],
-                                                     float4 (&xs)[HAVE_Z ? 1 : NC])
+// The thread's columns of the model message and of the snapshot, requested without waiting for anything (the
+// requests have no dependence on the rows, so a kernel issues them first and they are back before they are needed).
+template <int NC>
+struct ModelCols {
+    ModelQuad mq[NC];
+    float4 xs[NC];
+};
+
+template <int NC, bool FULL>
+__device__ __forceinline__ void request_model_cols(const VrDenseArgs &a, const ModelMsg &msg, ModelCols<NC> &mc)
 {
     const int64_t d = a.d;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
-        float q[4], s[4];
-        if (col + 3 < d) {
-            const float4 t = *reinterpret_cast<const float4 *>(a.x_snap + col);
-            s[0] = t.x; s[1] = t.y; s[2] = t.z; s[3] = t.w;
-            if (a.b_x == 8) {
-                const uint32_t w = a.xq[col >> 2];
+        mc.mq[c] = model_quad_request(msg, col, a.model_last_word);
+        if constexpr (FULL) mc.xs[c] = *reinterpret_cast<const float4 *>(a.x_snap + col);
+        else mc.xs[c] = load4_or_zero(a.x_snap, col, d);
+    }
+}
+
+// dx = q - snapshot for the thread's columns (q: the dequantized model message); xs = the
+// snapshot itself when HAVE_Z is false (margins at the snapshot must then be recomputed).
+template <int NC, bool HAVE_Z>
+__device__ __forceinline__ void model_minus_snapshot(const VrDenseArgs &a, const ModelMsg &msg, const ModelCols<NC> &mc,
+                                                     float4 (&dx)[NC], float4 (&xs)[HAVE_Z ? 1 : NC])
+{
 #pragma unroll
-                for (int e = 0; e < 4; ++e) q[e] = msg.delta_x * static_cast<float>(sext_field(w, 8 * e, 8));
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) q[e] = model_value(msg, col + e);
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bool in = col + e < d;
-                s[e] = in ? a.x_snap[col + e] : 0.0f;
-                q[e] = in ? model_value(msg, col + e) : 0.0f;
-            }
-        }
-        dx[c] = make_float4(q[0] - s[0], q[1] - s[1], q[2] - s[2], q[3] - s[3]);
-        if constexpr (!HAVE_Z) xs[c] = make_float4(s[0], s[1], s[2], s[3]);
+    for (int c = 0; c < NC; ++c) {
+        const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
+        float q[4];
+        model_quad_values(msg, mc.mq[c], col, a.d, q);
+        dx[c] = make_float4(q[0] - mc.xs[c].x, q[1] - mc.xs[c].y, q[2] - mc.xs[c].z, q[3] - mc.xs[c].w);
+        if constexpr (!HAVE_Z) xs[c] = mc.xs[c];
     }
 }
 
@@ -231,7 +236,7 @@ __device__ __forceinline__ void worker_finish(const VrDenseArgs &a, int m, const
     worker_outputs(a, m, sh_alpha, su, si, sd);
 }
 
-template <int NC, int R, bool HAVE_Z>
+template <int NC, int R, bool HAVE_Z, bool FULL>
 __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs a)
 {
     __shared__ float sh_red[2 * kRowWaves * R * 2];
@@ -249,6 +254,11 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
     const int64_t d = a.d;
     const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
     if (a.zero_word && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.zero_word = 0u;
+
+    // ---- the thread's columns of the model message and of the snapshot are requested first: they depend on
+    //      nothing and are back by the time the row numbers are
+    ModelCols<NC> mc;
+    request_model_cols<NC, FULL>(a, msg, mc);
 
     // ---- rows of this block
     const int per = (a.B + a.P - 1) / a.P;
@@ -277,7 +287,7 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int i = rb + r < nrows ? sh_row[rb + r] : -1;
-            if (i >= 0) load_cols<NC, true>(a.X + static_cast<int64_t>(i) * a.lda, d, row[r]);
+            if (i >= 0) load_cols<NC, true, FULL>(a.X + static_cast<int64_t>(i) * a.lda, d, row[r]);
             else zero_cols<NC>(row[r]);
         }
     };
@@ -310,8 +320,9 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
         }
     };
 
-    // ---- the first batch of rows is requested before anything else is fetched; the labels and cached
-    //      margins of the rows and q - snapshot (the thread's columns) arrive while those loads are in flight
+    // ---- the first batch of rows is requested as soon as the row numbers are known; the labels and cached
+    //      margins of the rows arrive while those loads are in flight, and q - snapshot is formed from words
+    //      that are already here
     float4 row[R][NC];
     load_batch(0, row);
     if (static_cast<int>(threadIdx.x) < nrows) {
@@ -319,7 +330,7 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
         sh_y[threadIdx.x] = i >= 0 ? a.y[i] : 1.0f;
         sh_z[threadIdx.x] = (i >= 0 && HAVE_Z) ? a.z_snap[i] : 0.0f;
     }
-    model_minus_snapshot<NC, HAVE_Z>(a, msg, dx, xs);
+    model_minus_snapshot<NC, HAVE_Z>(a, msg, mc, dx, xs);
     zero_cols<NC>(acc);
     __syncthreads();
 
@@ -353,28 +364,11 @@ __global__ __launch_bounds__(kFinishThreads) void vr_dense_finish_kernel(const V
     const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
     const float *base = a.partial + static_cast<int64_t>(m) * a.P * a.ldp;
     for (int64_t col = 4ll * threadIdx.x; col < a.ldp; col += 4ll * kFinishThreads) {
-        // everything this column group needs is requested up front: the model words, the snapshot
-        // and the partial sums (sixteen at a time)
-        float q[4], xs[4];
-        if (col + 3 < d) {
-            const float4 t = *reinterpret_cast<const float4 *>(a.x_snap + col);
-            xs[0] = t.x; xs[1] = t.y; xs[2] = t.z; xs[3] = t.w;
-            if (a.b_x == 8) {
-                const uint32_t w = a.xq[col >> 2];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) q[e] = msg.delta_x * static_cast<float>(sext_field(w, 8 * e, 8));
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) q[e] = model_value(msg, col + e);
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const bool in = col + e < d;
-                xs[e] = in ? a.x_snap[col + e] : 0.0f;
-                q[e] = in ? model_value(msg, col + e) : 0.0f;
-            }
-        }
+        // everything this column group needs is requested up front, none of it behind a branch that waits: the
+        // model words, the snapshot and (below) the partial sums, sixteen at a time
+        const ModelQuad mq = model_quad_request(msg, col, a.model_last_word);
+        const float4 xs4 = load4_or_zero(a.x_snap, col, d);
+        const float xs[4] = {xs4.x, xs4.y, xs4.z, xs4.w};
         float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         int p = 0;
         for (; p + 16 <= a.P; p += 16) {
@@ -396,6 +390,8 @@ __global__ __launch_bounds__(kFinishThreads) void vr_dense_finish_kernel(const V
             s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
         }
         const float acc[4] = {s.x, s.y, s.z, s.w};
+        float q[4];
+        model_quad_values(msg, mq, col, d, q);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             if (col + e < d) {
@@ -652,8 +648,14 @@ int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float 
 template <int NC, int R>
 static void launch_vr(bool have_z, dim3 grid, hipStream_t st, const VrDenseArgs &k)
 {
-    if (have_z) vr_dense_kernel<NC, R, true><<<grid, dim3(kRowThreads), 0, st>>>(k);
-    else vr_dense_kernel<NC, R, false><<<grid, dim3(kRowThreads), 0, st>>>(k);
+    const bool full = k.d == 4ll * kRowThreads * NC;       // every thread's columns are whole float4s of the row
+    if (have_z) {
+        if (full) vr_dense_kernel<NC, R, true, true><<<grid, dim3(kRowThreads), 0, st>>>(k);
+        else vr_dense_kernel<NC, R, true, false><<<grid, dim3(kRowThreads), 0, st>>>(k);
+    } else {
+        if (full) vr_dense_kernel<NC, R, false, true><<<grid, dim3(kRowThreads), 0, st>>>(k);
+        else vr_dense_kernel<NC, R, false, false><<<grid, dim3(kRowThreads), 0, st>>>(k);
+    }
 }
 
 int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
@@ -668,6 +670,7 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     k.X = prob->dense; k.lda = prob->lda; k.n = prob->n; k.d = d; k.y = prob->y;
     k.idx = a.idx; k.B = static_cast<int>(a.B); k.P = static_cast<int>(dense_vr_splits(a.M, a.B));
     k.xq = a.xq; k.delta_x = a.delta_x; k.b_x = a.b_x; k.x_snap = a.x_snap; k.z_snap = a.z_snap; k.l2 = prob->l2;
+    k.model_last_word = (a.b_x == 32 ? d : packed_words(d, a.b_x)) - 1;
     k.partial = static_cast<float *>(a.ws);
     k.ldp = pad4(d);
     k.alpha_out = a.alpha_out; k.ld = a.ld; k.absmax_out = a.absmax_out; k.l1norm_out = a.l1norm_out;

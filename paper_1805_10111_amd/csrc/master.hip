@@ -1,6 +1,8 @@
 // Master side of a round (Alg. 1, master (ii) then (i); Alg. 3 momentum update),
 // the epoch-boundary vector operations of Alg. 3, mini-batch index sampling and the
 // stand-alone gradient sparsifier of eq. (3).
+#include <type_traits>
+
 #include "dq_common.h"
 #include "elementwise.h"
 #include "grad_launch.h"
@@ -49,7 +51,6 @@ __device__ __forceinline__ void master_apply_quad(const float (&u)[4], float (&x
 template <int FIELD, bool ACC, bool EACH>
 __device__ __forceinline__ float4 master_quad(const MasterArgs &a, int64_t q)
 {
-    constexpr int kGroup = 8;                            // messages whose loads are in flight together
     const int64_t d = a.d;
     const float4 gs4 = load_quad(a.g_snap, q, d);
     const float gs[4] = {gs4.x, gs4.y, gs4.z, gs4.w};
@@ -69,39 +70,38 @@ __device__ __forceinline__ float4 master_quad(const MasterArgs &a, int64_t q)
         xn[0] = x4.x; xn[1] = x4.y; xn[2] = x4.z; xn[3] = x4.w;
     }
     float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};             // mean mode: sum_m delta_m * code_m, messages in order
-    int m = 0;
-    for (; m + kGroup <= a.M; m += kGroup) {
-        float4 v[kGroup];
-        float dm[kGroup];
+    // The words of a group of messages are requested together, then decoded and applied in message order; groups
+    // of 32, then of 8, then single messages.  The one block of the fused step is bound by the number of
+    // instructions it issues, so a group has no per-message test and the message rows are addressed from a
+    // uniform base.
+    const auto group = [&](int m, auto width) {
+        constexpr int G = decltype(width)::value;
+        QuadRaw<FIELD> raw[G];
+        float dm[G];
 #pragma unroll
-        for (int u = 0; u < kGroup; ++u) {
-            v[u] = quad_values<FIELD>(a.packed + static_cast<int64_t>(m + u) * a.ld_words, q, d);
+        for (int u = 0; u < G; ++u) {
+            raw[u] = quad_request<FIELD>(a.packed + static_cast<int64_t>(m + u) * a.ld_words, q, d);
             dm[u] = FIELD == 32 ? 1.0f : a.delta[m + u];
         }
 #pragma unroll
-        for (int u = 0; u < kGroup; ++u) {
-            const float vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+        for (int u = 0; u < G; ++u) {
+            const float4 v = quad_decode<FIELD>(raw[u], q);
+            const float vv[4] = {v.x, v.y, v.z, v.w};
             if (EACH) {
-                const float dir[4] = {dm[u] * vv[0] + gs[0], dm[u] * vv[1] + gs[1], dm[u] * vv[2] + gs[2], dm[u] * vv[3] + gs[3]};
+                const float dir[4] = {dm[u] * vv[0] + gs[0], dm[u] * vv[1] + gs[1], dm[u] * vv[2] + gs[2],
+                                      dm[u] * vv[3] + gs[3]};
                 master_apply_quad<ACC>(dir, xn, yn, xs, sm, have_sum, a.eta, a.theta, a.kappa);
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) acc[e] = fmaf(dm[u], vv[e], acc[e]);
             }
         }
-    }
-    for (; m < a.M; ++m) {
-        const float4 v = quad_values<FIELD>(a.packed + static_cast<int64_t>(m) * a.ld_words, q, d);
-        const float dm = FIELD == 32 ? 1.0f : a.delta[m];
-        const float vv[4] = {v.x, v.y, v.z, v.w};
-        if (EACH) {
-            const float dir[4] = {dm * vv[0] + gs[0], dm * vv[1] + gs[1], dm * vv[2] + gs[2], dm * vv[3] + gs[3]};
-            master_apply_quad<ACC>(dir, xn, yn, xs, sm, have_sum, a.eta, a.theta, a.kappa);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[e] = fmaf(dm, vv[e], acc[e]);
-        }
-    }
+    };
+    int m = 0;
+    if constexpr (FIELD != 32 && !EACH)                   // (the per-message update needs the registers itself)
+        for (; m + 32 <= a.M; m += 32) group(m, std::integral_constant<int, 32>{});
+    for (; m + 8 <= a.M; m += 8) group(m, std::integral_constant<int, 8>{});
+    for (; m < a.M; ++m) group(m, std::integral_constant<int, 1>{});
     if (!EACH) {
         const float dir[4] = {a.scale * acc[0] + gs[0], a.scale * acc[1] + gs[1], a.scale * acc[2] + gs[2],
                               a.scale * acc[3] + gs[3]};     // u = mean of the decoded gradients + grad f(snapshot)
