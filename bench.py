@@ -49,7 +49,7 @@ def run_rounds(tr, rounds, events=None):
     """Advance the trainer by `rounds` rounds, running epoch prologues/epilogues at their cadence.
 
     `events`: optional list that receives (start, end, is_flag_round) for the bracketed rounds, the two
-    torch events being recorded by the library on the launch stream right before / after the kernel that
+    torch events being handed to the library as the start and stop events of the launch of the kernel that
     streams the feature rows (the dominant kernel of a round).
     """
     import torch
@@ -61,12 +61,12 @@ def run_rounds(tr, rounds, events=None):
         if events is None:
             tr.rounds(tr._t, take)
         else:
-            # an event pair costs ~5 us of stream time each, so only every EVENT_STRIDE-th round is bracketed
+            # only every EVENT_STRIDE-th round is bracketed (a launch that carries events is a little slower)
             k = 0
             while k < take:
                 if (done + k) % EVENT_STRIDE == EVENT_STRIDE - 1:
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record(); e1.record()            # instantiates the HIP events; the library re-records them
+                    e0.record(); e1.record()            # instantiates the HIP events; the launch overwrites them
                     tr.rounds(tr._t + k, 1, [e0.cuda_event, e1.cuda_event])
                     events.append((e0, e1, tr.is_flag_round(tr._t + k)))
                     k += 1
@@ -242,21 +242,9 @@ def main():
         inner_rounds += tr.m
         tr.epoch_epilogue()
 
-    # what an event bracket reads with nothing inside it (the cost of the bracket itself on a busy stream):
-    # pairs of events recorded back to back right after a round's kernels
-    tr.epoch_prologue()
-    empty = []
-    for k in range(min(tr.m, 24)):
-        tr.rounds(k, 1)
-        ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        ea.record(); eb.record()
-        empty.append((ea, eb))
-    torch.cuda.synchronize()
-    bracket_s = float(np.median([ea.elapsed_time(eb) for ea, eb in empty])) * 1e-3
-
     # dominant kernel: the row-streaming kernel of the worker step (all M workers in one launch);
-    # flag-bit rounds read no rows and are skipped.  The bracket reading is used as it is (an upper bound of the
-    # kernel's own duration: the empty bracket is reported next to it).
+    # flag-bit rounds read no rows and are skipped.  The two events are the start and stop events of that launch
+    # (hipExtLaunchKernel inside the library), i.e. the kernel's own duration on the launch stream.
     durs = [e0.elapsed_time(e1) * 1e-3 for e0, e1, flag in events if not flag]
     k_avg = float(np.mean(durs))
     if prob.dense is not None:
@@ -286,7 +274,7 @@ def main():
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": recorded_traffic(cfg.name),
                      "bytes_per_launch": alg_bytes, "avg_launch_us": round(k_avg * 1e6, 2),
-                     "empty_bracket_us": round(bracket_s * 1e6, 2)},
+                     "timing": "start/stop HIP events of the kernel's launch, every 8th round of the timed region"},
     }
     del tr, P
     torch.cuda.empty_cache()

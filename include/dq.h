@@ -330,10 +330,12 @@ typedef struct dq_run_state {
  * the mean over the M workers, or dq_master_step_each; model re-quantized for the next round).  Random streams use
  * iter = epoch*m + t.  eta, theta: step size and momentum weight of this epoch (theta unused by
  * Alg. 1/2).  The epoch prologue (dq_full_grad, dq_acc_mix / copy) and epilogue stay with the
- * caller.  worker_events (host array, nullable): 2*rounds hipEvent_t handles; for round k the
- * pair [2k], [2k+1] is recorded on `stream` right before and right after the kernel of the
- * worker step that streams the feature rows (its first kernel; for CSR its only one; with
- * tau > 0 the one of the first worker group). */
+ * caller.  worker_events (host array, nullable): 2*rounds hipEvent_t handles created by the caller; for
+ * round k the pair [2k], [2k+1] receives the start and the end time of the kernel of the worker step
+ * that streams the feature rows (its first kernel; for CSR its only one; with tau > 0 the one of the
+ * first worker group): they are the start and stop events of that launch (hipExtLaunchKernel), so
+ * hipEventElapsedTime over the pair is the kernel's own duration.  A flag-bit round leaves its pair
+ * untouched. */
 int32_t dq_run_rounds(const dq_problem *prob /*host*/, const dq_run_config *cfg /*host*/, const dq_run_state *st /*host*/,
                       int64_t epoch, int64_t t0, int64_t rounds, float eta, float theta,
                       void **worker_events /*host*/, void *stream);

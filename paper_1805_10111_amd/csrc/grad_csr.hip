@@ -18,6 +18,8 @@
 //   4. the tail of the worker step (sparsify, scale, quantize, pack) runs from LDS.
 // The full gradient uses the same block procedure over many blocks, each leaving a partial
 // d-vector that a second kernel adds up in a fixed order.
+#include <hip/hip_ext.h>
+
 #include "dq_common.h"
 #include "elementwise.h"
 #include "grad_common.h"
@@ -570,9 +572,12 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     const bool count_ok = !a.nnz_out || (a.sparsify && a.b >= 4);      // after the sparsifier: count = kept coordinates
     unsigned slices = 1;
     if (a.packed && count_ok && plan.nwin == 1 && a.b != 32 && d >= 4096 && a.M * 4 <= 128) slices = a.M * 8 <= 128 ? 8 : 4;
-    csr_worker_kernel<<<dim3(static_cast<unsigned>(a.M), slices), dim3(kCsrThreads), lds, st>>>(k);
+    if (a.ev_start && a.ev_stop)      // the kernel's own start and end times go to the two events
+        hipExtLaunchKernelGGL(csr_worker_kernel, dim3(static_cast<unsigned>(a.M), slices), dim3(kCsrThreads),
+                              static_cast<uint32_t>(lds), st, a.ev_start, a.ev_stop, 0u, k);
+    else
+        csr_worker_kernel<<<dim3(static_cast<unsigned>(a.M), slices), dim3(kCsrThreads), lds, st>>>(k);
     DQ_LAUNCH_CHECK();
-    if (a.ev_after_stream) DQ_HIP_TRY(hipEventRecord(a.ev_after_stream, st));
     return DQ_OK;
 }
 

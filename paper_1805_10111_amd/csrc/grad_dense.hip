@@ -17,6 +17,8 @@
 // Either way the summation order is fixed, so results are run-to-run deterministic.
 #include <cstdlib>
 
+#include <hip/hip_ext.h>
+
 #include "dq_common.h"
 #include "elementwise.h"
 #include "grad_common.h"
@@ -645,16 +647,27 @@ int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float 
     return launch_full_finish(partial, P, ldp, n, d, x, prob->l2, prob->l1, loss_partial, g_out, obj_out, st);
 }
 
+// A launch whose start and end times go to the two events (when given): the kernel's own time stamps, without the
+// stream time a pair of recorded events adds around it.
+template <typename K>
+static void launch_timed(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t st, hipEvent_t ev_start, hipEvent_t ev_stop,
+                         const VrDenseArgs &k)
+{
+    if (ev_start && ev_stop) hipExtLaunchKernelGGL(kernel, grid, block, static_cast<uint32_t>(lds), st, ev_start, ev_stop, 0u, k);
+    else kernel<<<grid, block, lds, st>>>(k);
+}
+
 template <int NC, int R>
-static void launch_vr(bool have_z, dim3 grid, hipStream_t st, const VrDenseArgs &k)
+static void launch_vr(bool have_z, dim3 grid, hipStream_t st, const VrDenseArgs &k, hipEvent_t e0, hipEvent_t e1)
 {
     const bool full = k.d == 4ll * kRowThreads * NC;       // every thread's columns are whole float4s of the row
+    const dim3 block(kRowThreads);
     if (have_z) {
-        if (full) vr_dense_kernel<NC, R, true, true><<<grid, dim3(kRowThreads), 0, st>>>(k);
-        else vr_dense_kernel<NC, R, true, false><<<grid, dim3(kRowThreads), 0, st>>>(k);
+        if (full) launch_timed(vr_dense_kernel<NC, R, true, true>, grid, block, 0, st, e0, e1, k);
+        else launch_timed(vr_dense_kernel<NC, R, true, false>, grid, block, 0, st, e0, e1, k);
     } else {
-        if (full) vr_dense_kernel<NC, R, false, true><<<grid, dim3(kRowThreads), 0, st>>>(k);
-        else vr_dense_kernel<NC, R, false, false><<<grid, dim3(kRowThreads), 0, st>>>(k);
+        if (full) launch_timed(vr_dense_kernel<NC, R, false, true>, grid, block, 0, st, e0, e1, k);
+        else launch_timed(vr_dense_kernel<NC, R, false, false>, grid, block, 0, st, e0, e1, k);
     }
 }
 
@@ -682,20 +695,19 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     const dim3 grid(k.P, static_cast<unsigned>(a.M));
     const bool have_z = a.z_snap != nullptr;
     switch (nc) {
-    case 1: launch_vr<1, 16>(have_z, grid, st, k); break;
-    case 2: launch_vr<2, 8>(have_z, grid, st, k); break;
-    case 8: launch_vr<8, 2>(have_z, grid, st, k); break;
-    case 16: launch_vr<16, 1>(have_z, grid, st, k); break;
+    case 1: launch_vr<1, 16>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
+    case 2: launch_vr<2, 8>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
+    case 8: launch_vr<8, 2>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
+    case 16: launch_vr<16, 1>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
     default: {
         static const int rows = [] { const char *e = getenv("DQ_VR_ROWS"); return e ? atoi(e) : 4; }();
-        if (rows == 8) launch_vr<4, 8>(have_z, grid, st, k);
-        else if (rows == 2) launch_vr<4, 2>(have_z, grid, st, k);
-        else launch_vr<4, 4>(have_z, grid, st, k);
+        if (rows == 8) launch_vr<4, 8>(have_z, grid, st, k, a.ev_start, a.ev_stop);
+        else if (rows == 2) launch_vr<4, 2>(have_z, grid, st, k, a.ev_start, a.ev_stop);
+        else launch_vr<4, 4>(have_z, grid, st, k, a.ev_start, a.ev_stop);
         break;
     }
     }
     DQ_LAUNCH_CHECK();
-    if (a.ev_after_stream) DQ_HIP_TRY(hipEventRecord(a.ev_after_stream, st));
     if (k.P > 1 || nc > 4) {
         const size_t lds = static_cast<size_t>(d) * sizeof(float);
         static bool big_lds_allowed = false;             // more than 64 KB of dynamic LDS has to be requested once

@@ -28,7 +28,8 @@ struct WorkerArgs {
     uint32_t *status;
     void *ws;
     int64_t ws_bytes;
-    hipEvent_t ev_after_stream;   // nullable: recorded right after the kernel that streams the feature rows
+    hipEvent_t ev_start, ev_stop; // nullable (both or none): receive the start and the end time of the kernel that
+                                  // streams the feature rows (start/stop events of an extended launch)
     uint32_t *zero_word;          // nullable: one device word the worker kernel sets to 0 (dq_run_rounds uses it to
                                   // prepare the master's ||x||_inf accumulator without a launch of its own)
 };

@@ -67,8 +67,8 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
             w.ws = st->ws; w.ws_bytes = st->ws_bytes;
             if (g == 0) w.zero_word = reinterpret_cast<uint32_t *>(st->absmax_x);   // for the master's max below
             if (worker_events && g == 0) {
-                DQ_HIP_TRY(hipEventRecord(static_cast<hipEvent_t>(worker_events[2 * (t - t0)]), as_stream(stream)));
-                w.ev_after_stream = static_cast<hipEvent_t>(worker_events[2 * (t - t0) + 1]);
+                w.ev_start = static_cast<hipEvent_t>(worker_events[2 * (t - t0)]);
+                w.ev_stop = static_cast<hipEvent_t>(worker_events[2 * (t - t0) + 1]);
             }
             rc = dq::worker_step_impl(prob, w, stream);
             if (rc != DQ_OK) return rc;

@@ -140,6 +140,30 @@ def test_runs_are_reproducible(dq):
     assert not torch.equal(a.x_snap, c.x_snap)
 
 
+@pytest.mark.parametrize("name", ["C1", "C4", "C2"])
+def test_kernel_events_time_the_worker_kernel_and_change_nothing(dq, name):
+    """dq_run_rounds with worker_events: each pair receives the start and end of the row-streaming kernel's launch
+    (a positive duration far below a millisecond on these sizes) and the round computes exactly what it computes
+    without events."""
+    cfg, p, m = _small(name)
+    m = min(m, 6)
+    a = _trainer(dq, p, cfg, m, seed=3)
+    b = _trainer(dq, p, cfg, m, seed=3)
+    a.epoch_prologue(); b.epoch_prologue()
+    pairs = []
+    for t in range(m):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); e1.record()                       # creates the HIP events
+        a.rounds(t, 1, [e0.cuda_event, e1.cuda_event])
+        pairs.append((e0, e1, a.is_flag_round(t)))
+    b.rounds(0, m)
+    torch.cuda.synchronize()
+    assert torch.equal(a.x, b.x) and torch.equal(a.packed, b.packed) and torch.equal(a.delta, b.delta)
+    timed = [e0.elapsed_time(e1) for e0, e1, flag in pairs if not flag]
+    assert len(timed) >= m - 1
+    assert all(1e-4 < ms < 1.0 for ms in timed), timed
+
+
 @pytest.mark.parametrize("algo,b_x,b", [("asylpg", 32, 32), ("acc", 32, 32), ("asylpg", 32, 8), ("asylpg", 8, 32),
                                         ("sparse", 32, 4)])
 def test_unquantized_modes_free_run(dq, algo, b_x, b):
