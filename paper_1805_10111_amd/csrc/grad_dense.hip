@@ -7,9 +7,10 @@
 // built around reading each feature row exactly once.  A block of 256 threads owns a
 // group of rows of one worker; thread t holds float4 columns t, t+256, ... of R rows at
 // a time in registers (R*NC float4), so R full rows (R*16 KB at d = 4096) are in flight
-// per block.  The R margins are reduced through LDS with one barrier per batch, the
-// coefficients are formed redundantly by every thread, and coef*row is accumulated into
-// NC float4 registers per thread.  When one block owns a worker's whole mini-batch it
+// per block -- twice that where the worker kernel keeps two such batches, one being
+// reduced while the other is in flight.  The R margins are reduced through LDS with one
+// barrier per batch, the coefficients are formed by R lanes and read back wave-uniformly,
+// and coef*row is accumulated into NC float4 registers per thread.  When one block owns a worker's whole mini-batch it
 // goes straight on to the tail of the worker step; otherwise each block writes its
 // partial sum and a second small kernel adds the partial sums in a fixed order and runs
 // the tail (the kernel boundary is what makes the partial sums visible across the
@@ -238,7 +239,7 @@ __device__ __forceinline__ void worker_finish(const VrDenseArgs &a, int m, const
     worker_outputs(a, m, sh_alpha, su, si, sd);
 }
 
-template <int NC, int R, bool HAVE_Z, bool FULL>
+template <int NC, int R, bool HAVE_Z, bool FULL, bool DB = false>
 __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs a)
 {
     __shared__ float sh_red[2 * kRowWaves * R * 2];
@@ -266,6 +267,7 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
     const int per = (a.B + a.P - 1) / a.P;
     const int r0 = blockIdx.x * per;
     const int nrows = max(0, min(a.B, r0 + per) - r0);
+    bool row_ok = true;
     if (static_cast<int>(threadIdx.x) < nrows) {
         const int r = r0 + threadIdx.x;
         int64_t i;
@@ -277,10 +279,12 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
             sk.tag = DQ_TAG_SAMPLE;
             i = __umulhi(stream_word(sk, static_cast<uint64_t>(r)), static_cast<uint32_t>(a.n));
         }
-        const bool ok = static_cast<uint64_t>(i) < static_cast<uint64_t>(a.n);   // out-of-range index: ignored
-        sh_row[threadIdx.x] = ok ? static_cast<int>(i) : -1;
+        row_ok = static_cast<uint64_t>(i) < static_cast<uint64_t>(a.n);           // out-of-range index: ignored
+        sh_row[threadIdx.x] = row_ok ? static_cast<int>(i) : -1;
     }
-    __syncthreads();
+    // whole batches of valid rows only (the usual case): the row loads then carry no condition, so a wait for one
+    // batch can leave the loads of the next one in flight
+    const bool plain = __syncthreads_and(row_ok) && nrows > 0 && nrows % R == 0;
 
     float4 dx[NC], xs[HAVE_Z ? 1 : NC], acc[NC];
     const float fB = static_cast<float>(a.B);
@@ -291,6 +295,13 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
             const int i = rb + r < nrows ? sh_row[rb + r] : -1;
             if (i >= 0) load_cols<NC, true, FULL>(a.X + static_cast<int64_t>(i) * a.lda, d, row[r]);
             else zero_cols<NC>(row[r]);
+        }
+    };
+    auto load_rows = [&](int rb, float4 (&row)[R][NC]) {          // `plain` blocks only
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int i = __builtin_amdgcn_readfirstlane(sh_row[rb + r]);
+            load_cols<NC, true, FULL>(a.X + static_cast<int64_t>(i) * a.lda, d, row[r]);
         }
     };
     auto compute_batch = [&](int rb, const float4 (&row)[R][NC]) {
@@ -326,7 +337,8 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
     //      margins of the rows arrive while those loads are in flight, and q - snapshot is formed from words
     //      that are already here
     float4 row[R][NC];
-    load_batch(0, row);
+    if (plain) load_rows(0, row);
+    else load_batch(0, row);
     if (static_cast<int>(threadIdx.x) < nrows) {
         const int i = sh_row[threadIdx.x];
         sh_y[threadIdx.x] = i >= 0 ? a.y[i] : 1.0f;
@@ -336,11 +348,32 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
     zero_cols<NC>(acc);
     __syncthreads();
 
-    // ---- stream the rows, R at a time.  (No software prefetch beyond the first batch: a block owns
-    //      only a few batches, and a second row buffer costs a resident block per compute unit.)
-    for (int rb = 0; rb < nrows; rb += R) {
-        if (rb > 0) load_batch(rb, row);
+    // ---- stream the rows, R at a time
+    if (DB && plain && nrows % (2 * R) == 0) {
+        // two row buffers: while one batch is reduced the next one is in flight (the last pair of batches is peeled
+        // off, so that no load of the loop sits behind a condition)
+        float4 row2[R][NC];
+        int rb = 0;
+        for (; rb + 2 * R < nrows; rb += 2 * R) {
+            load_rows(rb + R, row2);
+            compute_batch(rb, row);
+            load_rows(rb + 2 * R, row);
+            compute_batch(rb + R, row2);
+        }
+        load_rows(rb + R, row2);
         compute_batch(rb, row);
+        compute_batch(rb + R, row2);
+    } else if (plain) {
+        compute_batch(0, row);
+        for (int rb = R; rb < nrows; rb += R) {
+            load_rows(rb, row);
+            compute_batch(rb, row);
+        }
+    } else {
+        for (int rb = 0; rb < nrows; rb += R) {
+            if (rb > 0) load_batch(rb, row);
+            compute_batch(rb, row);
+        }
     }
 
     if (a.P > 1 || !kOwnTail) {          // leave the partial sum for vr_dense_finish_kernel
@@ -379,6 +412,13 @@ __global__ __launch_bounds__(kFinishThreads) void vr_dense_finish_kernel(const V
             for (int u = 0; u < 16; ++u) t[u] = *reinterpret_cast<const float4 *>(base + (p + u) * a.ldp + col);
 #pragma unroll
             for (int u = 0; u < 16; ++u) { s.x += t[u].x; s.y += t[u].y; s.z += t[u].z; s.w += t[u].w; }
+        }
+        for (; p + 8 <= a.P; p += 8) {
+            float4 t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = *reinterpret_cast<const float4 *>(base + (p + u) * a.ldp + col);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { s.x += t[u].x; s.y += t[u].y; s.z += t[u].z; s.w += t[u].w; }
         }
         for (; p + 4 <= a.P; p += 4) {
             float4 t[4];
@@ -584,15 +624,19 @@ int launch_full_finish(const float *partial, int P, int64_t ldp, int64_t n, int6
 // float4 columns per thread that cover a row: rows of up to 16384 floats are supported
 static int dense_nc(int64_t d) { return d <= 1024 ? 1 : d <= 2048 ? 2 : d <= 4096 ? 4 : d <= 8192 ? 8 : d <= 16384 ? 16 : 0; }
 
-int64_t dense_vr_splits(int64_t M, int64_t B)
+int64_t dense_vr_splits(int64_t M, int64_t B, int64_t d)
 {
     // blocks per worker.  A mini-batch of at most 32 rows stays in one block, which then runs the
     // whole worker step in a single launch; larger ones are split so that about 512 blocks
-    // (two per compute unit) stream rows, each owning at least 4 of them.
-    static const int64_t target = [] {
+    // (two per compute unit) stream rows, each owning at least 4 of them.  Rows of 2049..4096 floats
+    // are streamed with two row buffers per block (see dense_worker): one block per compute unit
+    // then, and a whole number of batch pairs per block.
+    static const int64_t forced = [] {
         const char *e = getenv("DQ_VR_BLOCKS");
-        return e ? atoll(e) : 512ll;
+        return e ? atoll(e) : 0ll;
     }();
+    const bool two_buffers = dense_nc(d) == 4;
+    const int64_t target = forced > 0 ? forced : two_buffers ? 256 : 512;
     if (B <= 32) return 1;
     int64_t P = ceil_div(target, M);
     const int64_t by_rows = ceil_div(B, 4);
@@ -600,6 +644,7 @@ int64_t dense_vr_splits(int64_t M, int64_t B)
     const int64_t need = ceil_div(B, kMaxRowsPerBlock);        // a block owns at most kMaxRowsPerBlock rows
     if (P < need) P = need;
     if (P < 1) P = 1;
+    if (two_buffers) P = ceil_div(B, ceil_div(ceil_div(B, P), 4) * 4);   // rows per block: a multiple of 4
     return P;
 }
 
@@ -621,7 +666,7 @@ int64_t dense_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int
         const int64_t P = dense_full_splits(prob->n);
         return P * ldp * 4 + P * 8;
     }
-    return M * dense_vr_splits(M, B) * ldp * 4;
+    return M * dense_vr_splits(M, B, prob->d) * ldp * 4;
 }
 
 int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float *z_out, double *obj_out, void *ws,
@@ -657,17 +702,17 @@ static void launch_timed(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_
     else kernel<<<grid, block, lds, st>>>(k);
 }
 
-template <int NC, int R>
+template <int NC, int R, bool DB = false>
 static void launch_vr(bool have_z, dim3 grid, hipStream_t st, const VrDenseArgs &k, hipEvent_t e0, hipEvent_t e1)
 {
     const bool full = k.d == 4ll * kRowThreads * NC;       // every thread's columns are whole float4s of the row
     const dim3 block(kRowThreads);
     if (have_z) {
-        if (full) launch_timed(vr_dense_kernel<NC, R, true, true>, grid, block, 0, st, e0, e1, k);
-        else launch_timed(vr_dense_kernel<NC, R, true, false>, grid, block, 0, st, e0, e1, k);
+        if (full) launch_timed(vr_dense_kernel<NC, R, true, true, DB>, grid, block, 0, st, e0, e1, k);
+        else launch_timed(vr_dense_kernel<NC, R, true, false, DB>, grid, block, 0, st, e0, e1, k);
     } else {
-        if (full) launch_timed(vr_dense_kernel<NC, R, false, true>, grid, block, 0, st, e0, e1, k);
-        else launch_timed(vr_dense_kernel<NC, R, false, false>, grid, block, 0, st, e0, e1, k);
+        if (full) launch_timed(vr_dense_kernel<NC, R, false, true, DB>, grid, block, 0, st, e0, e1, k);
+        else launch_timed(vr_dense_kernel<NC, R, false, false, DB>, grid, block, 0, st, e0, e1, k);
     }
 }
 
@@ -681,7 +726,7 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     if (a.ws_bytes < dense_workspace_bytes(DQ_OP_VR_GRAD, prob, a.M, a.B) || !a.ws) return DQ_ERR_WORKSPACE;
     VrDenseArgs k{};
     k.X = prob->dense; k.lda = prob->lda; k.n = prob->n; k.d = d; k.y = prob->y;
-    k.idx = a.idx; k.B = static_cast<int>(a.B); k.P = static_cast<int>(dense_vr_splits(a.M, a.B));
+    k.idx = a.idx; k.B = static_cast<int>(a.B); k.P = static_cast<int>(dense_vr_splits(a.M, a.B, d));
     k.xq = a.xq; k.delta_x = a.delta_x; k.b_x = a.b_x; k.x_snap = a.x_snap; k.z_snap = a.z_snap; k.l2 = prob->l2;
     k.model_last_word = (a.b_x == 32 ? d : packed_words(d, a.b_x)) - 1;
     k.partial = static_cast<float *>(a.ws);
@@ -699,13 +744,13 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     case 2: launch_vr<2, 8>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
     case 8: launch_vr<8, 2>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
     case 16: launch_vr<16, 1>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
-    default: {
-        static const int rows = [] { const char *e = getenv("DQ_VR_ROWS"); return e ? atoi(e) : 4; }();
-        if (rows == 8) launch_vr<4, 8>(have_z, grid, st, k, a.ev_start, a.ev_stop);
-        else if (rows == 2) launch_vr<4, 2>(have_z, grid, st, k, a.ev_start, a.ev_stop);
-        else launch_vr<4, 4>(have_z, grid, st, k, a.ev_start, a.ev_stop);
+    default:
+        // rows of 2049..4096 floats: two rows per batch and two row buffers, so that a batch is reduced while the
+        // next one is in flight, one block per compute unit (measured against four rows per batch, one buffer, two
+        // blocks per unit at d = 4096, M = 32, B = 256: 26.3 + 6.4 us against 27.3 + 7.2 us for the two kernels of the
+        // worker step -- half as many partial sums to write and to add)
+        launch_vr<4, 2, true>(have_z, grid, st, k, a.ev_start, a.ev_stop);
         break;
-    }
     }
     DQ_LAUNCH_CHECK();
     if (k.P > 1 || nc > 4) {

@@ -133,6 +133,39 @@ def test_vr_grad_flag_bit_and_bad_index(dq):
     assert np.isfinite(host(alpha)).all()
 
 
+@pytest.mark.parametrize("bad", [False, True])
+@pytest.mark.parametrize("d,M,B", [(4096, 2, 256), (4096, 1, 71), (3000, 2, 70), (4096, 32, 64), (2052, 3, 44)])
+def test_vr_grad_row_streaming_paths(dq, d, M, B, bad):
+    """Rows of 2049..4096 floats are streamed with two row buffers when a block owns whole pairs of batches of valid
+    rows, with one buffer when it owns whole batches, and through the checked loop otherwise (ragged last block,
+    indices outside [0, n)).  Every path against the oracle; a skipped index contributes nothing but still counts
+    in the 1/B of the mean."""
+    n = 400
+    p = synth.dense_logistic(n, d, seed=d + B, l2=1e-3)
+    P = dq.DeviceProblem.from_host(p)
+    rp = oracle.RefProblem(p)
+    rng = np.random.default_rng(B)
+    x_snap = (0.3 * rng.standard_normal(d)).astype(np.float32)
+    xq, dx, q = _model(rng, d, 8, x_snap)
+    idx = np.stack([oracle.sample_indices(n, B, 17, 3, w) for w in range(M)]).astype(np.int64)
+    if bad:                                              # a few rows of every worker are out of range
+        for w in range(M):
+            pos = rng.choice(B, size=max(1, B // 9), replace=False)
+            idx[w, pos] = rng.choice([-1, n, n + 5, 2 ** 31 - 1], size=pos.size)
+    _, z_ref = oracle.full_grad(rp, x_snap, want_margins=True)
+    alpha = torch.full((M, d), 5.0, device="cuda")
+    amax = torch.zeros(M, device="cuda")
+    ws = _ws(dq, dq.OP_VR_GRAD, P, M, B)
+    dq.dq_vr_grad(P, dev(idx.astype(np.int32)), M, B, dev(xq.view(np.int32)), dev(np.array([dx], dtype=np.float32)), 8, False,
+                  dev(x_snap), dev(z_ref), alpha, amax, None, ws)
+    dense_part = p.l2 * (q.astype(np.float64) - x_snap.astype(np.float64))
+    for w in range(M):
+        ok = idx[w][(idx[w] >= 0) & (idx[w] < n)]
+        want = (oracle.vr_grad(rp, ok.astype(np.int32), q, x_snap).astype(np.float64) - dense_part) * (ok.size / B) + dense_part
+        _close(host(alpha)[w], want, tol=2e-5 if bad else TOL)   # (the oracle's float32 output is rescaled here)
+        assert host(amax)[w] == np.abs(host(alpha)[w]).max()
+
+
 @pytest.mark.parametrize("sparsify", [False, True])
 @pytest.mark.parametrize("b", [8, 4, 2])
 @pytest.mark.parametrize("n,d,M,B", [(2000, 1000, 4, 16), (300, 4096, 5, 64), (64, 1027, 2, 5), (150, 6000, 3, 40),

@@ -104,7 +104,7 @@ def test_workspace_sizes(lib):
     vr = lib.dq_workspace_bytes(2, C.byref(p), 32, 256)
     assert full % 16 == 0 and vr % 16 == 0
     assert full >= 512 * 4096 * 4                      # up to 512 partial d-vectors
-    assert vr == 32 * 16 * 4096 * 4                    # M * P * d floats with P = 512/M blocks per worker
+    assert vr == 32 * 8 * 4096 * 4                     # M * P * d floats with P = 256/M blocks per worker at d = 4096
     small = dense(n=2000, d=1000)
     assert lib.dq_workspace_bytes(2, C.byref(small), 4, 16) == 4 * 1 * 1000 * 4       # small batch: one block per worker
     assert lib.dq_workspace_bytes(2, C.byref(csr()), 8, 32) == 0      # the CSR worker step lives in LDS
