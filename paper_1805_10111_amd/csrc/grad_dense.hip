@@ -478,46 +478,57 @@ int launch_worker_zero(const WorkerArgs &a, int64_t d, int64_t row_words, hipStr
 }
 
 // ------------------------------------------------------------------ epoch prologue: partial sums
-// grid (P).  Block p owns rows [p*per, (p+1)*per).
-template <int NC, int R>
+// grid (P).  Block p owns rows [p*per, (p+1)*per) and takes them in chunks of kFullChunk rows: the labels of a
+// chunk are brought into LDS first and its margins leave through LDS afterwards, so that the loop over the
+// chunk's rows contains no memory access but the row loads themselves, none of them behind a condition -- only
+// then can a wait for one batch leave the loads of the next batch in flight (two row buffers).
+constexpr int kFullChunk = 1024;
+
+template <int NC, int R, bool FULL>
 __global__ __launch_bounds__(kRowThreads) void full_dense_partial_kernel(
     const float *__restrict__ X, int64_t lda, int64_t n, int64_t d, const float *__restrict__ yv,
     const float *__restrict__ x, float *__restrict__ z_out, float *__restrict__ partial, int64_t ldp,
     double *__restrict__ loss_partial)
 {
     __shared__ float sh_red[2 * kRowWaves * R];
+    __shared__ float sh_y[kFullChunk], sh_z[kFullChunk];
     const int64_t per = (n + gridDim.x - 1) / gridDim.x;
     const int64_t i0 = blockIdx.x * per, i1 = min(n, i0 + per);
     float4 xv[NC], acc[NC];
     zero_cols<NC>(acc);
-    load_cols<NC>(x, d, xv);
+    load_cols<NC, false, FULL>(x, d, xv);
     const float fn = static_cast<float>(n);
     double loss = 0.0;
     int buf = 0;
+    auto load_rows = [&](int64_t ib, float4 (&row)[R][NC]) {          // rows ib .. ib+R-1 all exist
+#pragma unroll
+        for (int r = 0; r < R; ++r) load_cols<NC, false, FULL>(X + (ib + r) * lda, d, row[r]);
+    };
     auto load_batch = [&](int64_t ib, float4 (&row)[R][NC]) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            if (ib + r < i1) load_cols<NC>(X + (ib + r) * lda, d, row[r]);
+            if (ib + r < i1) load_cols<NC, false, FULL>(X + (ib + r) * lda, d, row[r]);
             else zero_cols<NC>(row[r]);
         }
     };
-    auto compute_batch = [&](int64_t ib, const float4 (&row)[R][NC]) {
+    // rows c0 + rel .. of the current chunk (cn rows); labels in sh_y, margins to sh_z
+    auto compute_batch = [&](int rel, int cn, const float4 (&row)[R][NC]) {
         float z[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) z[r] = dot_cols<NC>(row[r], xv);
         block_sum_R<R>(z, sh_red, buf);
-        // lane r evaluates row ib + r (slope, loss) once; wave 0 also records margin and loss
+        // lane r evaluates row rel + r (slope, loss) once; wave 0 also records margin and loss
         const int lane = threadIdx.x & (kWave - 1);
         float zl = z[0];
 #pragma unroll
         for (int r = 1; r < R; ++r) zl = lane == r ? z[r] : zl;
         float coef_l = 0.0f;
-        if (lane < R && ib + lane < i1) {
-            const float y = yv[ib + lane];
+        if (lane < R && rel + lane < cn) {
+            const float y = sh_y[rel + lane];
             coef_l = logistic_slope(y, zl) / fn;
             if (threadIdx.x < R) {
                 loss += static_cast<double>(logistic_loss(y * zl));
-                if (z_out) z_out[ib + lane] = zl;
+                sh_z[rel + lane] = zl;
             }
         }
 #pragma unroll
@@ -526,18 +537,34 @@ __global__ __launch_bounds__(kRowThreads) void full_dense_partial_kernel(
             axpy_cols<NC>(coef, row[r], acc);
         }
     };
-    if (i0 < i1) {
+    for (int64_t c0 = i0; c0 < i1; c0 += kFullChunk) {
+        const int cn = static_cast<int>(min<int64_t>(kFullChunk, i1 - c0));
+        for (int t = threadIdx.x; t < cn; t += kRowThreads) sh_y[t] = yv[c0 + t];
+        __syncthreads();
         float4 rowA[R][NC], rowB[R][NC];
-        load_batch(i0, rowA);
-        for (int64_t ib = i0; ib < i1; ib += 2 * R) {
-            const bool more1 = ib + R < i1, more2 = ib + 2 * R < i1;
-            if (more1) load_batch(ib + R, rowB);
-            compute_batch(ib, rowA);
-            if (more1) {
-                if (more2) load_batch(ib + 2 * R, rowA);
-                compute_batch(ib + R, rowB);
+        const int fast = cn / (2 * R) * (2 * R);             // whole pairs of batches
+        int rel = 0;
+        if (fast > 0) {
+            load_rows(c0, rowA);
+            for (; rel + 2 * R < fast; rel += 2 * R) {
+                load_rows(c0 + rel + R, rowB);
+                compute_batch(rel, cn, rowA);
+                load_rows(c0 + rel + 2 * R, rowA);
+                compute_batch(rel + R, cn, rowB);
             }
+            load_rows(c0 + rel + R, rowB);
+            compute_batch(rel, cn, rowA);
+            compute_batch(rel + R, cn, rowB);
+            rel += 2 * R;
         }
+        for (; rel < cn; rel += R) {                          // the last rows of the block
+            load_batch(c0 + rel, rowA);
+            compute_batch(rel, cn, rowA);
+        }
+        __syncthreads();
+        if (z_out)
+            for (int t = threadIdx.x; t < cn; t += kRowThreads) z_out[c0 + t] = sh_z[t];
+        __syncthreads();
     }
     store_cols<NC>(partial + static_cast<int64_t>(blockIdx.x) * ldp, ldp, acc);
     if (threadIdx.x < kWave) {                       // lanes 0..R-1 of wave 0 hold the block's loss terms
@@ -681,13 +708,20 @@ int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float 
     float *partial = static_cast<float *>(ws);
     double *loss_partial = reinterpret_cast<double *>(partial + static_cast<int64_t>(P) * ldp);
     const dim3 grid(P), block(kRowThreads);
+    const bool full = d == 4ll * kRowThreads * nc;          // every thread's columns are whole float4s of the row
+#define DQ_FULL(NC, R)                                                                                              \
+    do {                                                                                                            \
+        if (full) full_dense_partial_kernel<NC, R, true><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); \
+        else full_dense_partial_kernel<NC, R, false><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); \
+    } while (0)
     switch (nc) {
-    case 1: full_dense_partial_kernel<1, 8><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
-    case 2: full_dense_partial_kernel<2, 4><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
-    case 4: full_dense_partial_kernel<4, 4><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
-    case 8: full_dense_partial_kernel<8, 2><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
-    default: full_dense_partial_kernel<16, 1><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); break;
+    case 1: DQ_FULL(1, 8); break;
+    case 2: DQ_FULL(2, 4); break;
+    case 4: DQ_FULL(4, 4); break;
+    case 8: DQ_FULL(8, 2); break;
+    default: DQ_FULL(16, 1); break;
     }
+#undef DQ_FULL
     DQ_LAUNCH_CHECK();
     return launch_full_finish(partial, P, ldp, n, d, x, prob->l2, prob->l1, loss_partial, g_out, obj_out, st);
 }
