@@ -655,14 +655,14 @@ int64_t dense_vr_splits(int64_t M, int64_t B, int64_t d)
 {
     // blocks per worker.  A mini-batch of at most 32 rows stays in one block, which then runs the
     // whole worker step in a single launch; larger ones are split so that about 512 blocks
-    // (two per compute unit) stream rows, each owning at least 4 of them.  Rows of 2049..4096 floats
+    // (two per compute unit) stream rows, each owning at least 4 of them.  Rows wider than 1024 floats
     // are streamed with two row buffers per block (see dense_worker): one block per compute unit
     // then, and a whole number of batch pairs per block.
     static const int64_t forced = [] {
         const char *e = getenv("DQ_VR_BLOCKS");
         return e ? atoll(e) : 0ll;
     }();
-    const bool two_buffers = dense_nc(d) == 4;
+    const bool two_buffers = dense_nc(d) >= 2;
     const int64_t target = forced > 0 ? forced : two_buffers ? 256 : 512;
     if (B <= 32) return 1;
     int64_t P = ceil_div(target, M);
@@ -773,18 +773,17 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     k.delta_out = a.delta_out; k.nnz_out = a.nnz_out; k.status = a.status; k.zero_word = a.zero_word;
     const dim3 grid(k.P, static_cast<unsigned>(a.M));
     const bool have_z = a.z_snap != nullptr;
+    // Rows wider than 1024 floats are streamed with two row buffers, one block per compute unit: a batch is reduced
+    // while the next one is in flight, and half as many partial sums are written and added again.  Measured for the
+    // two kernels of the worker step at M = 32 and 134 MB of rows, against one buffer and two blocks per unit:
+    // d = 2048 31.6 against 32.4 us, d = 4096 32.1 against 34.5 us, d = 8192 36.3 against 40.8 us, d = 16384 44.7
+    // against 61.7 us; at d = 1024 one buffer of 16 rows is faster (34.9 against 42.4 us).
     switch (nc) {
     case 1: launch_vr<1, 16>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
-    case 2: launch_vr<2, 8>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
-    case 8: launch_vr<8, 2>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
-    case 16: launch_vr<16, 1>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
-    default:
-        // rows of 2049..4096 floats: two rows per batch and two row buffers, so that a batch is reduced while the
-        // next one is in flight, one block per compute unit (measured against four rows per batch, one buffer, two
-        // blocks per unit at d = 4096, M = 32, B = 256: 26.3 + 6.4 us against 27.3 + 7.2 us for the two kernels of the
-        // worker step -- half as many partial sums to write and to add)
-        launch_vr<4, 2, true>(have_z, grid, st, k, a.ev_start, a.ev_stop);
-        break;
+    case 2: launch_vr<2, 4, true>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
+    case 4: launch_vr<4, 2, true>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
+    case 8: launch_vr<8, 1, true>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
+    default: launch_vr<16, 1, true>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
     }
     DQ_LAUNCH_CHECK();
     if (k.P > 1 || nc > 4) {
