@@ -136,6 +136,28 @@ def test_unpack_dequant_sum_bit_exact(dq, b, M, d):
     assert np.array_equal(host(out), x)
 
 
+@pytest.mark.parametrize("b", [2, 4, 8])
+def test_unpack_dequant_sum_with_extreme_scales(dq, b):
+    """Scales that are zero, huge, or so small that a sixteenth of them is not a normal number (the 4-bit decode
+    multiplies by delta/16 only where that is exact) still give the oracle's sum bit for bit."""
+    M, d = 11, 4099
+    rng = np.random.default_rng(b)
+    k = rng.integers(-(2 ** (b - 1)), 2 ** (b - 1), size=(M, d)).astype(np.int8)
+    delta = np.array([0.0, 2.0 ** -101, 2.0 ** -99, 2.0 ** -120, 2.0 ** -126, 2.0 ** -130, 3e-42, 1.0, 2.0 ** 100, 1e-3,
+                      2.0 ** -100], dtype=np.float32)
+    nw = dq.packed_words(d, b)
+    ldw = (nw + 3) // 4 * 4
+    pw = np.zeros((M, ldw), dtype=np.uint32)
+    for m in range(M):
+        pw[m, :nw] = oracle.pack(k[m], b)
+    for order in (np.arange(M), np.arange(M)[::-1].copy()):                 # small terms first, and last
+        out = torch.zeros(d, device="cuda")
+        dq.dq_unpack_dequant_sum(dev(pw[order].view(np.int32)), dev(delta[order]), d, b, 1.0, out)
+        x = np.zeros(d, dtype=np.float32)
+        oracle.master_update(k[order], delta[order], np.float32(1.0), np.zeros(d, dtype=np.float32), x, eta=-1.0, l1=0.0)
+        assert np.array_equal(host(out).view(np.uint32), x.view(np.uint32))
+
+
 def test_degenerate_vectors(dq):
     d = 100
     for fill, want_status in [(0.0, 0), (np.nan, 1), (np.inf, 1), (1e-44, 0)]:
