@@ -140,6 +140,37 @@ def test_runs_are_reproducible(dq):
     assert not torch.equal(a.x_snap, c.x_snap)
 
 
+@pytest.mark.parametrize("algo,b,d,M,B", [("acc", 8, 4096, 32, 256), ("asylpg", 4, 4096, 16, 64), ("sparse", 4, 3000, 8, 128),
+                                          ("acc", 2, 2048, 32, 128), ("asylpg", 8, 1500, 4, 64)])
+def test_rounds_enqueued_together_equal_rounds_enqueued_one_by_one(dq, algo, b, d, M, B):
+    """How the rounds of an epoch are spread over dq_run_rounds calls (3 + 4 rounds, or one round per call) must not
+    matter: every vector and every message comes out identical, bit for bit."""
+    from paper_1805_10111_amd.driver import DoubleQuantTrainer
+    p = synth.dense_logistic(600, d, seed=d + M, l2=1e-3)
+    P = dq.DeviceProblem.from_host(p)
+    m = 7
+    runs = []
+    for together in (True, False):
+        tr = DoubleQuantTrainer(P, algo, M, B, 8, b, m, 0.1, seed=9)
+        for _ in range(2):
+            tr.epoch_prologue()
+            if together:
+                tr.rounds(0, 3)
+                tr.rounds(3, m - 3)
+            else:
+                for t in range(m):
+                    tr.rounds(t, 1)
+            tr.epoch_epilogue()
+        torch.cuda.synchronize()
+        runs.append(tr)
+    a, c = runs
+    for name in ("x", "x_snap", "packed", "delta", "xq", "delta_x", "absmax_x"):
+        assert torch.equal(getattr(a, name), getattr(c, name)), name
+    if algo == "acc":
+        assert torch.equal(a.y, c.y) and torch.equal(a.xsum, c.xsum)
+    assert np.isfinite(host(a.x)).all() and host(a.x).any()
+
+
 @pytest.mark.parametrize("name", ["C1", "C4", "C2"])
 def test_kernel_events_time_the_worker_kernel_and_change_nothing(dq, name):
     """dq_run_rounds with worker_events: each pair receives the start and end of the row-streaming kernel's launch
