@@ -94,16 +94,18 @@ __device__ __forceinline__ void csr_prefix_lengths(RowMeta &meta, int nrows)
 //   stage  : the group's (column, value) pairs are copied to LDS as one flat run, four entries per thread
 //            in flight, the row number packed above the column;
 //   margins: one wavefront per row (kFlight rows in flight) reduces sum_k value_k * vec(column_k), where
-//            vec(c) returns {first, second} operands gathered from memory; lane u hands the sums of its
+//            vec_val(vec_req(c), c) returns {first, second} operands gathered from memory -- vec_req only requests
+//            (no branch, no use of what it loads), so the gathers of all rows in flight wait for memory once;
+//            lane u hands the sums of its
 //            u-th row to coef_of(row, first_sum, second_sum), which returns the row's coefficient;
 //   scatter: kScatterWaves wavefronts own a contiguous range of columns each and stream over the staged
 //            entries, adding coefficient*value for the entries that fall in their range.
 // A row longer than `cap` is handled alone, straight from memory.
 // Only the columns of the window [c0, c1) are accumulated, into alpha[column - c0]: a vector too long for
 // LDS is built one window at a time (the caller repeats the call per window; margins are recomputed).
-template <bool SECOND, typename VecFn, typename CoefFn>
+template <bool SECOND, typename VecReq, typename VecVal, typename CoefFn>
 __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta, int nrows, float *alpha, int c0, int c1,
-                                                 int2 *stage, int cap, int *sh_ctl, VecFn vec,
+                                                 int2 *stage, int cap, int *sh_ctl, VecReq vec_req, VecVal vec_val,
                                                  CoefFn coef_of)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
@@ -166,10 +168,13 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
                 for (int k = lane; k < maxlen; k += kWave) {
                     int2 e[kFlight];
                     float2 f[kFlight];
+                    decltype(vec_req(0)) raw[kFlight];
 #pragma unroll
                     for (int u = 0; u < kFlight; ++u) e[u] = k < len[u] ? stage[off[u] + k] : make_int2(0, 0);
 #pragma unroll
-                    for (int u = 0; u < kFlight; ++u) f[u] = vec(e[u].x & kColMask);
+                    for (int u = 0; u < kFlight; ++u) raw[u] = vec_req(e[u].x & kColMask);
+#pragma unroll
+                    for (int u = 0; u < kFlight; ++u) f[u] = vec_val(raw[u], e[u].x & kColMask);
 #pragma unroll
                     for (int u = 0; u < kFlight; ++u) {
                         sa[u] = fmaf(__int_as_float(e[u].y), f[u].x, sa[u]);
@@ -223,7 +228,8 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
             const int64_t s = meta.start[g0];
             float a1 = 0.0f, b1 = 0.0f;
             for (int k = lane; k < meta.len[g0]; k += kWave) {
-                const float2 f = vec(A.indices[s + k]);
+                const int ck = A.indices[s + k];
+                const float2 f = vec_val(vec_req(ck), ck);
                 const float v = A.values[s + k];
                 a1 = fmaf(v, f.x, a1);
                 if (SECOND) b1 = fmaf(v, f.y, b1);
@@ -250,6 +256,7 @@ struct CsrWorkerArgs {
     const int32_t *idx;
     int B;
     const uint32_t *xq; const float *delta_x; int b_x;
+    int64_t model_last_word;       // index of the last word of the model message
     const float *x_snap, *z_snap;
     float l2;
     float *alpha_out; int64_t ld;
@@ -286,9 +293,18 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
 
     const float fB = static_cast<float>(a.B);
     const bool have_z = a.z_snap != nullptr;
-    auto vec = [&](int c) {
-        const float xc = a.x_snap[c];
-        return make_float2(model_value(msg, c) - xc, xc);
+    // the model value and the snapshot at column c: the field of column c starts at bit c*b_x of the message and
+    // may continue in the next word; both words and the snapshot value are requested without any condition
+    struct Gather { uint32_t w0, w1; float xs; };
+    auto vec_req = [&](int c) {
+        const int w = (c * a.b_x) >> 5;
+        return Gather{a.xq[w], a.xq[min(static_cast<int64_t>(w) + 1, a.model_last_word)], a.x_snap[c]};
+    };
+    auto vec_val = [&](const Gather &g, int c) {
+        const uint32_t bits = __funnelshift_r(g.w0, g.w1, static_cast<unsigned>(c * a.b_x) & 31u);
+        const float q = a.b_x == 32 ? __uint_as_float(bits)
+                                    : msg.delta_x * static_cast<float>(sext_field(bits, 0, static_cast<unsigned>(a.b_x)));
+        return make_float2(q - g.xs, g.xs);
     };
     auto coef_of = [&](int r, float dz, float zs) {
         if (meta.row[r] < 0) return 0.0f;
@@ -352,10 +368,10 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
             csr_prefix_lengths(meta, nrows);
             if (have_z)
                 csr_process_rows<false>(a.A, meta, nrows, alpha, static_cast<int>(c0), static_cast<int>(c1), stage, a.cap,
-                                        sh_ctl, vec, coef_of);
+                                        sh_ctl, vec_req, vec_val, coef_of);
             else
                 csr_process_rows<true>(a.A, meta, nrows, alpha, static_cast<int>(c0), static_cast<int>(c1), stage, a.cap,
-                                       sh_ctl, vec, coef_of);
+                                       sh_ctl, vec_req, vec_val, coef_of);
         }
         if (alpha_row) {                                       // several windows: the finished one goes to memory
             for (int64_t j = c0 + threadIdx.x; j < c1; j += kCsrThreads) alpha_row[j] = alpha[j - c0];
@@ -429,7 +445,8 @@ __global__ __launch_bounds__(kCsrThreads) void csr_full_partial_kernel(
             }
             csr_prefix_lengths(meta, nrows);
             const int64_t ib_now = ib;
-            auto vec = [&](int c) { return make_float2(x[c], 0.0f); };
+            auto vec_req = [&](int c) { return x[c]; };
+            auto vec_val = [&](float xc, int) { return make_float2(xc, 0.0f); };
             auto coef_of = [&](int r, float z, float) {
                 const int64_t i = ib_now + r;
                 const float y = A.y[i];
@@ -440,7 +457,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_full_partial_kernel(
                 return logistic_slope(y, z) / fn;
             };
             csr_process_rows<false>(A, meta, nrows, acc, static_cast<int>(c0), static_cast<int>(min(A.d, c1)), stage, cap,
-                                    sh_ctl, vec, coef_of);
+                                    sh_ctl, vec_req, vec_val, coef_of);
         }
         __syncthreads();
         for (int64_t j = c0 + threadIdx.x; j < c1; j += kCsrThreads) mine[j] = acc[j - c0];
@@ -554,6 +571,7 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     k.A = CsrView{prob->indptr, prob->indices, prob->values, prob->y, prob->n, d};
     k.idx = a.idx; k.B = static_cast<int>(a.B);
     k.xq = a.xq; k.delta_x = a.delta_x; k.b_x = a.b_x; k.x_snap = a.x_snap; k.z_snap = a.z_snap; k.l2 = prob->l2;
+    k.model_last_word = (a.b_x == 32 ? prob->d : packed_words(prob->d, a.b_x)) - 1;
     k.alpha_out = a.alpha_out; k.ld = a.ld; k.absmax_out = a.absmax_out; k.l1norm_out = a.l1norm_out;
     k.sparsify = a.sparsify; k.b = a.b;
     k.key = StreamKey{static_cast<uint32_t>(a.seed), static_cast<uint32_t>(a.seed >> 32), a.iter, 0u, DQ_TAG_GRAD};
