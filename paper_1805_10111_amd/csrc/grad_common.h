@@ -114,6 +114,47 @@ __device__ __forceinline__ float4 load4_or_zero(const float *__restrict__ v, int
     return make_float4(r[0], r[1], r[2], r[3]);
 }
 
+// Alg. 2, worker (ii) on one slice of the quads, for a worker whose identical blocks (one per slice) each hold the whole
+// alpha in `alpha`: the block finds ||alpha||_inf over the whole vector like every other, sparsifies the quads of its own
+// slice only, writes them to beta_row (memory) and leaves the slice's largest magnitude and its number of kept
+// coordinates in part_max[0], part_kept[0]; a later kernel (quantize_pack_kernel with parts) combines the slices.  The
+// slice boundaries are those of worker_tail_from_lds.  su, si: one entry per wavefront of the block.
+__device__ __forceinline__ void sparsify_slice_from_lds(const float *alpha, int64_t d, StreamKey key, int slice, int nslices,
+                                                        float *__restrict__ beta_row, float *__restrict__ part_max,
+                                                        int32_t *__restrict__ part_kept, uint32_t *su, int *si)
+{
+    const int64_t quads = (d + 3) / 4;
+    const int64_t per = ((quads + nslices - 1) / nslices + kWave - 1) / kWave * kWave;
+    const int64_t q_lo = min(quads, per * slice), q_hi = min(quads, q_lo + per);
+    uint32_t vmax = 0;
+    for (int64_t q = threadIdx.x; q < quads; q += blockDim.x) {
+        const float4 a = load_quad(alpha, q, d);
+        vmax = max(max(vmax, abs_bits(a.x)), max(max(abs_bits(a.y), abs_bits(a.z)), abs_bits(a.w)));
+    }
+    vmax = block_max_u32(vmax, su);
+    const SparsifyRule rule{__uint_as_float(vmax), 0.0f, false};
+    key.tag = DQ_TAG_SPARSIFY;
+    uint32_t bmax = 0;
+    int kept = 0;
+    for (int64_t q = q_lo + threadIdx.x; q < q_hi; q += blockDim.x) {
+        float4 a = load_quad(alpha, q, d);
+        const uint4 w = stream_block(key, static_cast<uint32_t>(q));
+        a.x = sparsify_one(a.x, rule, w.x);
+        a.y = sparsify_one(a.y, rule, w.y);
+        a.z = sparsify_one(a.z, rule, w.z);
+        a.w = sparsify_one(a.w, rule, w.w);
+        bmax = max(max(bmax, abs_bits(a.x)), max(max(abs_bits(a.y), abs_bits(a.z)), abs_bits(a.w)));
+        kept += (a.x != 0.0f) + (a.y != 0.0f) + (a.z != 0.0f) + (a.w != 0.0f);
+        store_quad(beta_row, q, d, a);
+    }
+    bmax = block_max_u32(bmax, su);
+    kept = block_sum_i32(kept, si);
+    if (threadIdx.x == 0) {
+        part_max[0] = __uint_as_float(bmax);
+        part_kept[0] = kept;
+    }
+}
+
 // ---- tail of a worker step on alpha[d] in LDS (one block per worker) -------------------
 struct WorkerOut {
     uint32_t *packed;       // row of packed words

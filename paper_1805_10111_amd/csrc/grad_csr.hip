@@ -269,6 +269,9 @@ struct CsrWorkerArgs {
     uint32_t *zero_word;           // nullable: set to 0 by one thread of the grid
     int win;                       // columns of the gradient held in LDS at a time (multiple of 4; >= d: all of it)
     float *alpha_ws; int64_t ld_ws; // with several windows: M rows of workspace for the whole gradient, else null
+    // sparsifier split over the identical blocks of a worker (beta_ws != null): each block sparsifies its slice into
+    // row m of beta_ws and leaves the slice's largest magnitude and kept count; the quantization is a second launch
+    float *beta_ws; float *part_max; int32_t *part_kept;
 };
 
 __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorkerArgs a)
@@ -402,6 +405,12 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     }
     StreamKey key = a.key;
     key.worker = a.worker0 + static_cast<uint32_t>(m);
+    if (a.beta_ws) {
+        sparsify_slice_from_lds(av, d, key, slice, nslices, a.beta_ws + static_cast<int64_t>(m) * a.ld_ws,
+                                a.part_max + static_cast<int64_t>(m) * nslices + slice,
+                                a.part_kept + static_cast<int64_t>(m) * nslices + slice, su, si);
+        return;
+    }
     const WorkerOut out{a.packed + static_cast<int64_t>(m) * a.ld_words, a.row_words, a.delta_out + m,
                         a.nnz_out ? a.nnz_out + m : nullptr, a.status};
     switch (a.b) {
@@ -477,6 +486,10 @@ __global__ __launch_bounds__(kCsrThreads) void csr_full_partial_kernel(
 int launch_full_finish(const float *partial, int P, int64_t ldp, int64_t n, int64_t d, const float *x, float l2, float l1,
                        const double *loss_partial, float *g_out, double *obj_out, hipStream_t st);
 int launch_worker_zero(const WorkerArgs &a, int64_t d, int64_t row_words, hipStream_t st);
+int launch_quantize_pack_parts(const float *v, int64_t d, int64_t M, int64_t ld, int b, int field, const float *absmax,
+                               int parts, const int32_t *count_parts, int32_t *count_out, const StreamKey &key,
+                               uint32_t worker0, uint32_t *packed, int64_t ld_words, float *delta_out, uint32_t *status,
+                               hipStream_t st);
 
 // ------------------------------------------------------------------ host side
 static int64_t pad4(int64_t d) { return (d + 3) / 4 * 4; }
@@ -514,6 +527,8 @@ static int64_t csr_full_splits(int64_t n)
     return P;
 }
 
+constexpr int kMaxSlices = 8;       // identical blocks per worker that share the tail of a worker step
+
 int64_t csr_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64_t)
 {
     CsrPlan plan;
@@ -522,8 +537,9 @@ int64_t csr_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64
         const int64_t P = csr_full_splits(prob->n);
         return P * pad4(prob->d) * 4 + P * 8;
     }
-    // the worker step keeps the gradient in LDS when it fits; otherwise each worker has a row of workspace
-    return plan.nwin > 1 ? M * pad4(prob->d) * 4 : 0;
+    // a row per worker: the whole gradient when it does not fit in LDS, else the sparsified gradient when the
+    // sparsifier is split over several blocks per worker (see csr_worker); then 8 values + 8 counts per worker
+    return M * pad4(prob->d) * 4 + M * kMaxSlices * 8;
 }
 
 // Kernels that use more than 64 KB of dynamic LDS must be told so once (the limit is raised to the budget).
@@ -590,12 +606,27 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     const bool count_ok = !a.nnz_out || (a.sparsify && a.b >= 4);      // after the sparsifier: count = kept coordinates
     unsigned slices = 1;
     if (a.packed && count_ok && plan.nwin == 1 && a.b != 32 && d >= 4096 && a.M * 4 <= 128) slices = a.M * 8 <= 128 ? 8 : 4;
+    // After the sparsifier the scale is ||beta||_inf, which needs every coordinate's random decision: sharing only the
+    // quantization would leave each identical block a whole Philox-and-two-divisions pass over the vector (9 of the
+    // 33 us of the step at d = 20958).  With workspace for a row per worker each block sparsifies its own slice into
+    // memory instead and the quantization becomes a second launch that takes the scale from the slices' maxima.
+    const bool split_sparsifier = slices > 1 && a.sparsify && a.ws &&
+                                  a.ws_bytes >= csr_workspace_bytes(DQ_OP_VR_GRAD, prob, a.M, a.B);
+    if (split_sparsifier) {
+        k.beta_ws = static_cast<float *>(a.ws);
+        k.part_max = k.beta_ws + a.M * k.ld_ws;
+        k.part_kept = reinterpret_cast<int32_t *>(k.part_max + a.M * kMaxSlices);
+    }
     if (a.ev_start && a.ev_stop)      // the kernel's own start and end times go to the two events
         hipExtLaunchKernelGGL(csr_worker_kernel, dim3(static_cast<unsigned>(a.M), slices), dim3(kCsrThreads),
                               static_cast<uint32_t>(lds), st, a.ev_start, a.ev_stop, 0u, k);
     else
         csr_worker_kernel<<<dim3(static_cast<unsigned>(a.M), slices), dim3(kCsrThreads), lds, st>>>(k);
     DQ_LAUNCH_CHECK();
+    if (split_sparsifier)
+        return launch_quantize_pack_parts(k.beta_ws, d, a.M, k.ld_ws, a.b, a.b, k.part_max, static_cast<int>(slices),
+                                          a.nnz_out ? k.part_kept : nullptr, a.nnz_out, k.key, a.worker0, a.packed,
+                                          a.ld_words, a.delta_out, a.status, st);
     return DQ_OK;
 }
 

@@ -238,16 +238,29 @@ template <int FIELD>
 __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(
     const float *__restrict__ v, int64_t d, int64_t ld, const float *__restrict__ absmax, int b, StreamKey key,
     uint32_t worker0, uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words,
-    float *__restrict__ delta_out, uint32_t *__restrict__ status)
+    float *__restrict__ delta_out, uint32_t *__restrict__ status, int parts, const int32_t *__restrict__ count_parts,
+    int32_t *__restrict__ count_out)
 {
     const int m = blockIdx.y;
     const float *row = v + static_cast<int64_t>(m) * ld;
     uint32_t *out = packed + static_cast<int64_t>(m) * ld_words;
-    const Scale s = make_scale(absmax[m], b);
+    // the largest magnitude of row m, or the largest of the `parts` values that the producers of its slices left
+    // (magnitudes compare like their bit patterns, and so does a NaN that has to reach the status word)
+    float amax = absmax[static_cast<int64_t>(m) * parts];
+    for (int p = 1; p < parts; ++p) {
+        const float t = absmax[static_cast<int64_t>(m) * parts + p];
+        amax = __float_as_uint(t) > __float_as_uint(amax) ? t : amax;
+    }
+    const Scale s = make_scale(amax, b);
     key.worker = worker0 + static_cast<uint32_t>(m);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         delta_out[m] = s.delta;
         if (s.bad && status) atomicOr(status, 1u);
+        if (count_out) {                                   // a per-slice count summed on the way (see csr_worker)
+            int c = 0;
+            for (int p = 0; p < parts; ++p) c += count_parts[static_cast<int64_t>(m) * parts + p];
+            count_out[m] = c;
+        }
     }
     const int64_t chunks = (d + kCoordsPerThread - 1) / kCoordsPerThread;
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
@@ -260,18 +273,34 @@ __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(
     }
 }
 
+int launch_quantize_pack_parts(const float *v, int64_t d, int64_t M, int64_t ld, int b, int field, const float *absmax,
+                               int parts, const int32_t *count_parts, int32_t *count_out, const StreamKey &key,
+                               uint32_t worker0, uint32_t *packed, int64_t ld_words, float *delta_out, uint32_t *status,
+                               hipStream_t st);
+
 int launch_quantize_pack(const float *v, int64_t d, int64_t M, int64_t ld, int b, int field,
                          const float *absmax, const StreamKey &key, uint32_t worker0,
                          uint32_t *packed, int64_t ld_words, float *delta_out, uint32_t *status, hipStream_t st)
 {
+    return launch_quantize_pack_parts(v, d, M, ld, b, field, absmax, 1, nullptr, nullptr, key, worker0, packed, ld_words,
+                                      delta_out, status, st);
+}
+
+// absmax holds `parts` values per row (the row's scale comes from their maximum); count_parts / count_out: optional
+// per-slice counts and where their sum per row goes (widths 2, 4, 8 only).
+int launch_quantize_pack_parts(const float *v, int64_t d, int64_t M, int64_t ld, int b, int field, const float *absmax,
+                               int parts, const int32_t *count_parts, int32_t *count_out, const StreamKey &key,
+                               uint32_t worker0, uint32_t *packed, int64_t ld_words, float *delta_out, uint32_t *status,
+                               hipStream_t st)
+{
     const int64_t row_words = packed_words(d, field);
     const dim3 grid = grid_for(d, M), block(kThreads);
     switch (field) {
-    case 8: quantize_pack_kernel<8><<<grid, block, 0, st>>>(v, d, ld, absmax, b, key, worker0, packed, ld_words, row_words, delta_out, status); break;
-    case 4: quantize_pack_kernel<4><<<grid, block, 0, st>>>(v, d, ld, absmax, b, key, worker0, packed, ld_words, row_words, delta_out, status); break;
-    case 2: quantize_pack_kernel<2><<<grid, block, 0, st>>>(v, d, ld, absmax, b, key, worker0, packed, ld_words, row_words, delta_out, status); break;
+    case 8: quantize_pack_kernel<8><<<grid, block, 0, st>>>(v, d, ld, absmax, b, key, worker0, packed, ld_words, row_words, delta_out, status, parts, count_parts, count_out); break;
+    case 4: quantize_pack_kernel<4><<<grid, block, 0, st>>>(v, d, ld, absmax, b, key, worker0, packed, ld_words, row_words, delta_out, status, parts, count_parts, count_out); break;
+    case 2: quantize_pack_kernel<2><<<grid, block, 0, st>>>(v, d, ld, absmax, b, key, worker0, packed, ld_words, row_words, delta_out, status, parts, count_parts, count_out); break;
     default:
-        if (field != b || b < 2 || b > 16) return DQ_ERR_UNSUPPORTED;
+        if (field != b || b < 2 || b > 16 || parts != 1 || count_out) return DQ_ERR_UNSUPPORTED;
         quantize_pack_any_kernel<<<grid_for_groups(d, M), block, 0, st>>>(v, d, ld, absmax, b, key, worker0, packed, ld_words, row_words, delta_out, status);
         break;
     }

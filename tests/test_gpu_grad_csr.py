@@ -105,7 +105,7 @@ def test_vr_grad(dq, problems, name, M, B, b_x, have_z):
     alpha = torch.full((M, ld), 5.0, device="cuda")[:, :d]
     amax = torch.zeros(M, device="cuda")
     l1n = torch.zeros(M, device="cuda")
-    ws = dq.new_workspace(dq.OP_VR_GRAD, P, M, B)          # empty unless the gradient is wider than the on-chip buffer
+    ws = dq.new_workspace(dq.OP_VR_GRAD, P, M, B)          # a row per worker (wide gradients; split sparsifier)
     dq.dq_vr_grad(P, dev(idx), M, B, dev(xq.view(np.int32)), dev(np.array([dx], dtype=np.float32)), b_x, False,
                   dev(x_snap), z_snap, alpha, amax, l1n, ws)
     for w in range(M):
@@ -201,7 +201,7 @@ def test_flag_bit_round_and_limits(dq, problems):
     # a gradient that does not fit on chip needs the worker workspace
     pw = problems["wide"]
     Pw = dq.DeviceProblem.from_host(pw)
-    assert dq.dq_workspace_bytes(dq.OP_VR_GRAD, Pw, 3, 4) == 3 * ((pw.d + 3) // 4 * 4) * 4
+    assert dq.dq_workspace_bytes(dq.OP_VR_GRAD, Pw, 3, 4) == 3 * ((pw.d + 3) // 4 * 4) * 4 + 3 * 8 * 8
     with pytest.raises(dq.DqError) as e:
         dq.dq_worker_step(Pw, None, 3, 4, torch.zeros(pw.d, dtype=torch.int32, device="cuda"), torch.ones(1, device="cuda"),
                           8, False, torch.zeros(pw.d, device="cuda"), None, False, 8, 1, 1, 0,
@@ -234,3 +234,35 @@ def test_worker_step_without_nonzero_counts_uses_several_blocks_per_worker(dq, p
         outs.append((packed, delta))
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
     assert np.all(words(outs[1][0])[:, nw:] == 0xFFFFFFFF)
+
+
+@pytest.mark.parametrize("b,want_nnz", [(8, True), (4, True), (4, False), (2, False)])
+@pytest.mark.parametrize("M,B", [(5, 40), (16, 64)])
+def test_sparsifier_split_over_the_blocks_of_a_worker(dq, problems, b, want_nnz, M, B):
+    """With a workspace, the identical blocks of a worker sparsify one slice each into memory and a second launch
+    quantizes with the scale taken from the slices' maxima; without one the step is a single launch.  Same packed
+    words, scales and kept counts either way, and the oracle's counts."""
+    p = problems["text"]
+    P = dq.DeviceProblem.from_host(p)
+    d = p.d
+    rng = np.random.default_rng(80 + b)
+    x_snap = (0.3 * rng.standard_normal(d)).astype(np.float32)
+    xq, dx, _ = _model(rng, d, 8, x_snap)
+    xs_d, xq_d, dx_d = dev(x_snap), dev(xq.view(np.int32)), dev(np.array([dx], dtype=np.float32))
+    nw = dq.packed_words(d, b)
+    ldw = (nw + 3) // 4 * 4
+    outs = []
+    for ws in (dq.new_workspace(dq.OP_VR_GRAD, P, M, B), None):
+        packed = torch.full((M, ldw), -1, dtype=torch.int32, device="cuda")
+        delta = torch.zeros(M, device="cuda")
+        nnz = torch.full((M,), -7, dtype=torch.int32, device="cuda") if want_nnz else None
+        dq.dq_worker_step(P, None, M, B, xq_d, dx_d, 8, False, xs_d, None, True, b, 5, 6, 7, packed, delta, nnz,
+                          None, None, ws)
+        outs.append((packed, delta, nnz))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    assert np.all(words(outs[0][0])[:, nw:] == 0xFFFFFFFF)
+    assert host(outs[0][1]).all()                                       # every worker has a nonzero scale
+    if want_nnz:
+        assert torch.equal(outs[0][2], outs[1][2])
+        codes = np.stack([oracle.unpack(words(outs[0][0])[w, :nw], d, b) for w in range(M)])
+        assert np.array_equal(host(outs[0][2]), np.count_nonzero(codes, axis=1))
