@@ -43,7 +43,9 @@ def _model(rng, d, b_x, x_snap, spread=0.05):
     return oracle.pack(k, b_x), dx, oracle.dequantize(k, dx)
 
 
-PROBLEMS = [(2000, 1000), (37, 13), (300, 4096), (129, 2048), (64, 1027), (150, 6000), (90, 16384), (70, 12003)]
+# (the last two give a block more rows than one chunk of labels/margins holds: 1024, then a ragged remainder)
+PROBLEMS = [(2000, 1000), (37, 13), (300, 4096), (129, 2048), (64, 1027), (150, 6000), (90, 16384), (70, 12003),
+            (600011, 8), (1100000, 5)]
 
 
 @pytest.mark.parametrize("n,d", PROBLEMS)
