@@ -115,18 +115,22 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
     while (g0 < nrows) {
         // group of consecutive rows that fits the staging buffer: rows g0..g1-1 with
         // pre[g1] - pre[g0] <= cap; a first row longer than cap is taken alone, unstaged
-        if (threadIdx.x == 0) {
-            sh_ctl[0] = nrows;
-            sh_ctl[1] = meta.len[g0] > cap;
-        }
-        __syncthreads();
         const int base = meta.pre[g0];
-        if (static_cast<int>(threadIdx.x) >= g0 && static_cast<int>(threadIdx.x) < nrows &&
-            meta.pre[threadIdx.x + 1] - base > cap)
-            atomicMin(&sh_ctl[0], max(static_cast<int>(threadIdx.x), g0 + 1));
-        __syncthreads();
-        const int g1 = sh_ctl[0];
-        const bool direct = sh_ctl[1] != 0;
+        int g1 = nrows;
+        bool direct = false;
+        if (meta.pre[nrows] - base > cap) {            // (the same for every thread) not all remaining rows fit
+            if (threadIdx.x == 0) {
+                sh_ctl[0] = nrows;
+                sh_ctl[1] = meta.len[g0] > cap;
+            }
+            __syncthreads();
+            if (static_cast<int>(threadIdx.x) >= g0 && static_cast<int>(threadIdx.x) < nrows &&
+                meta.pre[threadIdx.x + 1] - base > cap)
+                atomicMin(&sh_ctl[0], max(static_cast<int>(threadIdx.x), g0 + 1));
+            __syncthreads();
+            g1 = sh_ctl[0];
+            direct = sh_ctl[1] != 0;
+        }
         if (!direct) {
             // ---- stage: flat copy of the group's entries; the row of an entry by bisection on pre[]
             const int total = meta.pre[g1] - base;
