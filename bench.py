@@ -108,14 +108,18 @@ def quantizer_leg(dq, torch):
     absmax = torch.zeros(1, device="cuda")
     delta = torch.zeros(M, device="cuda")
 
-    def timed(fn, reps=5):
+    def timed(fn, reps=5, groups=3):
+        """Seconds per call: the median over `groups` measurements of `reps` back-to-back calls each."""
         fn(); torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record(); torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps * 1e-3
+        per_call = []
+        for _ in range(groups):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record(); torch.cuda.synchronize()
+            per_call.append(e0.elapsed_time(e1) / reps * 1e-3)
+        return sorted(per_call)[len(per_call) // 2]
 
     t = timed(lambda: dq.dq_absmax(v, absmax))
     out["absmax"] = {"GB/s": round(N * 4 / t * 1e-9, 1), "us": round(t * 1e6, 1)}
