@@ -236,12 +236,14 @@ def test_worker_step_without_nonzero_counts_uses_several_blocks_per_worker(dq, p
     assert np.all(words(outs[1][0])[:, nw:] == 0xFFFFFFFF)
 
 
-@pytest.mark.parametrize("b,want_nnz", [(8, True), (4, True), (4, False), (2, False)])
-@pytest.mark.parametrize("M,B", [(5, 40), (16, 64)])
-def test_sparsifier_split_over_the_blocks_of_a_worker(dq, problems, b, want_nnz, M, B):
-    """With a workspace, the identical blocks of a worker sparsify one slice each into memory and a second launch
-    quantizes with the scale taken from the slices' maxima; without one the step is a single launch.  Same packed
-    words, scales and kept counts either way, and the oracle's counts."""
+@pytest.mark.parametrize("sparsify,b,want_nnz", [(True, 8, True), (True, 4, True), (True, 4, False), (True, 2, False),
+                                                  (False, 8, False), (False, 4, False), (False, 2, False)])
+@pytest.mark.parametrize("M,B", [(5, 40), (16, 64), (3, 300)])
+def test_worker_step_with_and_without_workspace(dq, problems, sparsify, b, want_nnz, M, B):
+    """With a workspace and few workers, the identical blocks of a worker sparsify one slice each into memory and a
+    second launch quantizes with the scale taken from the slices' maxima; without one (and without the sparsifier)
+    the step is a single launch.  Same packed words, scales and kept counts either way, the oracle's counts, and
+    the same gradient when it is asked for."""
     p = problems["text"]
     P = dq.DeviceProblem.from_host(p)
     d = p.d
@@ -256,10 +258,12 @@ def test_sparsifier_split_over_the_blocks_of_a_worker(dq, problems, b, want_nnz,
         packed = torch.full((M, ldw), -1, dtype=torch.int32, device="cuda")
         delta = torch.zeros(M, device="cuda")
         nnz = torch.full((M,), -7, dtype=torch.int32, device="cuda") if want_nnz else None
-        dq.dq_worker_step(P, None, M, B, xq_d, dx_d, 8, False, xs_d, None, True, b, 5, 6, 7, packed, delta, nnz,
-                          None, None, ws)
-        outs.append((packed, delta, nnz))
+        alpha = torch.full((M, (d + 3) // 4 * 4), 9.0, device="cuda")[:, :d]
+        dq.dq_worker_step(P, None, M, B, xq_d, dx_d, 8, False, xs_d, None, sparsify, b, 5, 6, 7, packed, delta, nnz,
+                          alpha, None, ws)
+        outs.append((packed, delta, nnz, alpha))
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    assert torch.equal(outs[0][3], outs[1][3])
     assert np.all(words(outs[0][0])[:, nw:] == 0xFFFFFFFF)
     assert host(outs[0][1]).all()                                       # every worker has a nonzero scale
     if want_nnz:
