@@ -329,3 +329,33 @@ def test_sparse_messages_through_the_wire_format(dq):
     w = words(b.wire)
     for r in range(cfg.M):
         assert not w[r, used[r]:].any() and (used[r] == 0 or w[r, :used[r]].any())
+
+
+@pytest.mark.parametrize("name", ["C1", "C4", "C3"])
+def test_rounds_replayed_from_a_captured_graph(dq, name):
+    """dq_run_rounds only enqueues kernels (no allocation, no memset), so a caller may capture an epoch's rounds
+    into a graph.  Every replay -- with eager work of the program between replays -- must give what the same
+    rounds give when enqueued directly."""
+    cfg, p, m = _small(name)
+    m = min(m, 8)
+    eager = _trainer(dq, p, cfg, m, seed=4)
+    graph = _trainer(dq, p, cfg, m, seed=4)
+    for tr in (eager, graph):
+        tr.epoch_prologue()
+        tr.rounds(0, m)                                  # warm-up: one-time function attributes are set outside the capture
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            graph.rounds(0, m)
+    torch.cuda.synchronize()
+    scratch = torch.zeros(1 << 16, device="cuda")
+    for rep in range(3):
+        eager.rounds(0, m)
+        g.replay()
+        scratch.add_(1.0)                                # the program's own eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(eager.x, graph.x) and torch.equal(eager.packed, graph.packed), rep
+        assert torch.equal(eager.delta, graph.delta) and torch.equal(eager.xq, graph.xq), rep
+    assert np.isfinite(host(graph.x)).all()
