@@ -47,6 +47,8 @@ def _problems():
         "mid": synth.sparse_text_logistic(500, 4099, mean_nnz=30.0, seed=3),
         # rcv1-like width (47,236 features): the gradient does not fit in LDS and is built in two column windows
         "wide": synth.sparse_text_logistic(1500, 47236, mean_nnz=75.0, seed=4),
+        # the widest model the CSR kernels take (2^20 columns): about thirty column windows per worker step
+        "widest": synth.sparse_text_logistic(300, 1 << 20, mean_nnz=40.0, seed=5),
     }
 
 
@@ -63,7 +65,7 @@ def _model(rng, d, b_x, x_snap, spread=0.05):
     return oracle.pack(k, b_x), dx, oracle.dequantize(k, dx)
 
 
-@pytest.mark.parametrize("name", ["text", "tiny", "long", "mid", "wide"])
+@pytest.mark.parametrize("name", ["text", "tiny", "long", "mid", "wide", "widest"])
 def test_full_grad(dq, problems, name):
     p = problems[name]
     P = dq.DeviceProblem.from_host(p)
@@ -85,7 +87,8 @@ def test_full_grad(dq, problems, name):
 
 @pytest.mark.parametrize("have_z", [True, False])
 @pytest.mark.parametrize("b_x", [8, 2, 32])
-@pytest.mark.parametrize("name,M,B", [("text", 8, 32), ("tiny", 3, 5), ("long", 2, 40), ("mid", 4, 300), ("wide", 5, 48)])
+@pytest.mark.parametrize("name,M,B", [("text", 8, 32), ("tiny", 3, 5), ("long", 2, 40), ("mid", 4, 300), ("wide", 5, 48),
+                                      ("widest", 2, 12)])
 def test_vr_grad(dq, problems, name, M, B, b_x, have_z):
     p = problems[name]
     P = dq.DeviceProblem.from_host(p)
@@ -123,7 +126,7 @@ def test_vr_grad(dq, problems, name, M, B, b_x, have_z):
 
 @pytest.mark.parametrize("sparsify", [False, True])
 @pytest.mark.parametrize("b", [8, 4])
-@pytest.mark.parametrize("name,M,B", [("text", 16, 64), ("tiny", 2, 7), ("long", 2, 12), ("wide", 4, 40)])
+@pytest.mark.parametrize("name,M,B", [("text", 16, 64), ("tiny", 2, 7), ("long", 2, 12), ("wide", 4, 40), ("widest", 2, 9)])
 def test_worker_step(dq, problems, name, M, B, b, sparsify):
     p = problems[name]
     P = dq.DeviceProblem.from_host(p)
