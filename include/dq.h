@@ -85,8 +85,8 @@ const char *dq_version(void);
 int32_t dq_last_device_error(void);
 /* Bytes of device workspace `op` needs for this problem with M workers of batch B
  * (a multiple of 16, possibly 0; negative = DQ_ERR_*).  Workspaces are 16-byte aligned.
- * Limits that make a problem DQ_ERR_UNSUPPORTED: dense rows wider than 16384 floats; CSR with more
- * than 2^20 columns. */
+ * Limits that make a problem DQ_ERR_UNSUPPORTED: dense rows wider than 16384 floats; CSR with 2^20
+ * columns or more. */
 int64_t dq_workspace_bytes(int32_t op, const dq_problem *prob /*host*/, int64_t M, int64_t B);
 /* Zero-fills a workspace (optional: no operation needs initialised workspace memory;
  * provided so that a caller can keep its buffers defined).  Two calls that share a

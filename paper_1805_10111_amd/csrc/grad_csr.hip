@@ -212,7 +212,7 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
                     for (int u = 0; u < 4; ++u) {
                         const int p = p0 + u * kWave;
                         e[u] = stage[min(p, total - 1)];
-                        if (p >= total) e[u].x = -1;                    // past the end: no column (see the test below)
+                        if (p >= total) e[u].x = kColMask;              // a column nobody owns: models have fewer than 2^20
                     }
 #pragma unroll
                     for (int u = 0; u < 4; ++u) term[u] = meta.coef[(e[u].x >> kColBits) & (kCsrMaxRows - 1)];
@@ -222,7 +222,7 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
                     for (int u = 0; u < 4; ++u) term[u] *= __int_as_float(e[u].y);
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
-                        const int c = e[u].x < 0 ? -1 : e[u].x & kColMask;      // (every column up to 2^20 - 1 is a real one)
+                        const int c = e[u].x & kColMask;
                         if (c >= lo && c < hi) atomicAdd(&alpha[c - c0], term[u]);
                     }
                 }
@@ -510,7 +510,7 @@ struct CsrPlan {
 
 static bool csr_plan(int64_t d, CsrPlan &p)
 {
-    if (d > (1ll << kColBits)) return false;
+    if (d >= (1ll << kColBits)) return false;      // column 2^20 - 1 marks the end of the staged entries in the scatter
     const int64_t budget = kLdsBudget - kCsrFixedLds;                     // bytes for window + staging
     int64_t nwin = 1;
     if (pad4(d) * 4 + 8 * 512 > budget) nwin = ceil_div(pad4(d) * 4, budget - 8 * kMinStage);

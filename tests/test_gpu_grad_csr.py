@@ -39,6 +39,16 @@ def _long_rows_problem(n=40, d=20958, seed=0):
     return synth.Problem(n=n, d=d, y=y, l2=1e-3, l1=1e-4, indptr=indptr, indices=indices, values=values)
 
 
+def _widest_problem():
+    """2^20 - 1 columns, and the last column (the largest index a staged entry can carry) present in several rows."""
+    p = synth.sparse_text_logistic(300, (1 << 20) - 1, mean_nnz=40.0, seed=5)
+    indices = p.indices.copy()
+    for r in range(0, 300, 7):
+        if p.indptr[r + 1] > p.indptr[r]:
+            indices[p.indptr[r + 1] - 1] = p.d - 1          # rows stay sorted: the last entry gets the last column
+    return synth.Problem(n=p.n, d=p.d, y=p.y, l2=p.l2, l1=p.l1, indptr=p.indptr, indices=indices, values=p.values)
+
+
 def _problems():
     return {
         "text": synth.sparse_text_logistic(3000, 20958, seed=1),
@@ -47,8 +57,8 @@ def _problems():
         "mid": synth.sparse_text_logistic(500, 4099, mean_nnz=30.0, seed=3),
         # rcv1-like width (47,236 features): the gradient does not fit in LDS and is built in two column windows
         "wide": synth.sparse_text_logistic(1500, 47236, mean_nnz=75.0, seed=4),
-        # the widest model the CSR kernels take (2^20 columns): about thirty column windows per worker step
-        "widest": synth.sparse_text_logistic(300, 1 << 20, mean_nnz=40.0, seed=5),
+        # the widest model the CSR kernels take (2^20 - 1 columns): about thirty column windows per worker step
+        "widest": _widest_problem(),
     }
 
 
@@ -192,7 +202,7 @@ def test_flag_bit_round_and_limits(dq, problems):
                       packed, delta, None, None, None, None)
     assert not words(packed)[:, : dq.packed_words(d, 4)].any() and not host(delta).any()
     # more columns than the staged entries can address: refused, not mangled
-    wide = (1 << 20) + 8
+    wide = 1 << 20
     big = synth.Problem(n=2, d=wide, y=np.ones(2, dtype=np.float32), l2=0.0, l1=0.0,
                         indptr=np.array([0, 1, 2], dtype=np.int64), indices=np.array([0, 5], dtype=np.int32),
                         values=np.ones(2, dtype=np.float32))

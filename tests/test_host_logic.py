@@ -87,7 +87,7 @@ def test_problem_and_gradient_argument_checks(lib):
     assert lib.dq_full_grad(C.byref(bad), P, P, None, None, P, 1 << 40, None) == INVALID
     wide = dense(d=20000, lda=20000)               # dense rows of more than 16384 floats
     assert lib.dq_full_grad(C.byref(wide), P, P, None, None, P, 1 << 40, None) == UNSUPPORTED
-    huge = csr(d=(1 << 20) + 4)                    # staged entries address at most 2^20 columns
+    huge = csr(d=1 << 20)                          # staged entries address fewer than 2^20 columns
     assert lib.dq_full_grad(C.byref(huge), P, P, None, None, P, 1 << 40, None) == UNSUPPORTED
     none = Problem(layout=2, n=1, d=1, y=P)
     assert lib.dq_full_grad(C.byref(none), P, P, None, None, P, 1 << 40, None) == INVALID
