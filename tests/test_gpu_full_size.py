@@ -155,3 +155,58 @@ def test_full_size_model_width_11_and_per_gradient_master(dq):
                            float(rp.l1), bx, seed, it + 1, xq, dxo, amx)
     assert np.array_equal(host(xd).view(np.uint32), x_ref.view(np.uint32))
     assert np.array_equal(words(xq), oracle.pack_wide(kx2, bx)) and host(dxo)[0] == dx2
+
+
+def test_dense_matrix_beyond_2_to_31_elements(dq):
+    """A dense matrix of 655,360 x 4096 floats (10.7 GB): element offsets pass 2^31 and byte offsets 2^33.  The
+    device matrix is a seeded block of 8192 rows repeated 80 times, so the oracle can work on the block: row i
+    of the matrix is row i mod 8192 of the block, and the mean over all rows equals the mean over the block."""
+    nb, reps, d = 8192, 80, 4096
+    p = synth.dense_logistic(nb, d, seed=3, l2=1e-4)
+    rp = oracle.RefProblem(p)
+    n = nb * reps
+    X = dev(p.dense).repeat(reps, 1)
+    assert X.numel() > 2 ** 31 and X.is_contiguous()
+    P = dq.DeviceProblem(n=n, d=d, y=dev(p.y).repeat(reps), l2=p.l2, l1=p.l1, dense=X)
+    rng = np.random.default_rng(4)
+    x_snap = (0.05 * rng.standard_normal(d)).astype(np.float32)
+    # ---- whole gradient and margins
+    g = torch.zeros(d, device="cuda")
+    z = torch.zeros(n, device="cuda")
+    obj = torch.zeros(1, dtype=torch.float64, device="cuda")
+    dq.dq_full_grad(P, dev(x_snap), g, z, obj, dq.new_workspace(dq.OP_FULL_GRAD, P))
+    g_ref, z_ref = oracle.full_grad(rp, x_snap, want_margins=True)
+    _close(host(g), g_ref.astype(np.float64))
+    zh = host(z).reshape(reps, nb)
+    _close(zh[0], z_ref.astype(np.float64))
+    assert all(np.array_equal(zh[r], zh[0]) for r in range(1, reps))
+    assert abs(host(obj)[0] - oracle.objective(rp, x_snap)) <= TOL * oracle.objective(rp, x_snap)
+    # ---- worker gradients from rows in the last 8192 (offsets of 2.6e9 elements and more), given and drawn
+    M, B, bx = 8, 64, 8
+    x = (x_snap + 0.01 * rng.standard_normal(d)).astype(np.float32)
+    kx, dx, _ = oracle.quantize(x, bx, 5, 0, oracle.MASTER_ID, oracle.TAG_MODEL)
+    q = oracle.dequantize(kx, dx)
+    xq = dev(oracle.pack(kx, bx).view(np.int32))
+    idx_small = rng.integers(0, nb, size=(M, B))
+    idx = idx_small + (n - nb)
+    alpha = torch.zeros((M, d), device="cuda")
+    amax = torch.zeros(M, device="cuda")
+    ws = dq.new_workspace(dq.OP_VR_GRAD, P, M, B)
+    dq.dq_vr_grad(P, dev(idx.astype(np.int32)), M, B, xq, dev(np.array([dx], dtype=np.float32)), bx, False, dev(x_snap), z,
+                  alpha, amax, None, ws)
+    for w in range(M):
+        _close(host(alpha)[w], oracle.vr_grad(rp, idx_small[w].astype(np.int32), q, x_snap).astype(np.float64))
+    # rows drawn in the kernel (worker step): uniform on [0, n), four in five past element 2^31 / 4
+    b, nw = 8, dq.packed_words(d, 8)
+    packed = torch.zeros((M, nw), dtype=torch.int32, device="cuda")
+    delta = torch.zeros(M, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    dq.dq_worker_step(P, None, M, B, xq, dev(np.array([dx], dtype=np.float32)), bx, False, dev(x_snap), z, False, b, 11, 2, 0,
+                      packed, delta, None, alpha, status, ws)
+    assert host(status)[0] == 0
+    for w in (0, M - 1):
+        drawn = oracle.sample_indices(n, B, 11, 2, w)
+        assert drawn.max() >= nb * (reps // 2)
+        a_ref = oracle.vr_grad(rp, (drawn % nb).astype(np.int32), q, x_snap)
+        _close(host(alpha)[w], a_ref.astype(np.float64))
+        assert abs(host(delta)[w] - np.abs(a_ref).max() / 127) <= 2e-5 * host(delta)[w]
