@@ -210,3 +210,46 @@ def test_dense_matrix_beyond_2_to_31_elements(dq):
         a_ref = oracle.vr_grad(rp, (drawn % nb).astype(np.int32), q, x_snap)
         _close(host(alpha)[w], a_ref.astype(np.float64))
         assert abs(host(delta)[w] - np.abs(a_ref).max() / 127) <= 2e-5 * host(delta)[w]
+
+
+def test_csr_matrix_beyond_2_to_31_entries(dq):
+    """A CSR matrix with 2.2e9 stored entries (entry offsets pass 2^31): a seeded block of 12,000 rows repeated 3500
+    times on the device; the oracle works on the block (row i of the matrix is row i mod 12,000 of the block)."""
+    nb, reps, d = 12000, 3500, 20958
+    p = synth.sparse_text_logistic(nb, d, mean_nnz=52.0, seed=8)
+    rp = oracle.RefProblem(p)
+    nnz_b = int(p.indptr[-1])
+    n = nb * reps
+    assert nnz_b * reps > 2 ** 31
+    shifts = torch.arange(reps, device="cuda", dtype=torch.int64) * nnz_b
+    indptr = torch.cat([(dev(p.indptr[:-1])[None, :] + shifts[:, None]).reshape(-1),
+                        torch.tensor([nnz_b * reps], device="cuda", dtype=torch.int64)])
+    P = dq.DeviceProblem(n=n, d=d, y=dev(p.y).repeat(reps), l2=p.l2, l1=p.l1, indptr=indptr,
+                         indices=dev(p.indices).repeat(reps), values=dev(p.values).repeat(reps))
+    rng = np.random.default_rng(4)
+    x_snap = (0.05 * rng.standard_normal(d)).astype(np.float32)
+    g = torch.zeros(d, device="cuda")
+    z = torch.zeros(n, device="cuda")
+    obj = torch.zeros(1, dtype=torch.float64, device="cuda")
+    dq.dq_full_grad(P, dev(x_snap), g, z, obj, dq.new_workspace(dq.OP_FULL_GRAD, P))
+    g_ref, z_ref = oracle.full_grad(rp, x_snap, want_margins=True)
+    _close(host(g), g_ref.astype(np.float64))
+    zh = host(z).reshape(reps, nb)
+    _close(zh[0], z_ref.astype(np.float64))
+    assert np.array_equal(zh[-1], zh[0]) and np.array_equal(zh[reps // 2], zh[0])
+    assert abs(host(obj)[0] - oracle.objective(rp, x_snap)) <= TOL * oracle.objective(rp, x_snap)
+    # ---- worker gradients from rows of the last block (entry offsets of 2.2e9)
+    M, B, bx = 8, 32, 8
+    x = (x_snap + 0.01 * rng.standard_normal(d)).astype(np.float32)
+    kx, dx, _ = oracle.quantize(x, bx, 5, 0, oracle.MASTER_ID, oracle.TAG_MODEL)
+    q = oracle.dequantize(kx, dx)
+    xq = dev(oracle.pack(kx, bx).view(np.int32))
+    idx_small = rng.integers(0, nb, size=(M, B))
+    idx = idx_small + (n - nb)
+    alpha = torch.zeros((M, (d + 3) // 4 * 4), device="cuda")[:, :d]
+    amax = torch.zeros(M, device="cuda")
+    ws = dq.new_workspace(dq.OP_VR_GRAD, P, M, B)
+    dq.dq_vr_grad(P, dev(idx.astype(np.int32)), M, B, xq, dev(np.array([dx], dtype=np.float32)), bx, False, dev(x_snap), z,
+                  alpha, amax, None, ws)
+    for w in range(M):
+        _close(host(alpha)[w], oracle.vr_grad(rp, idx_small[w].astype(np.int32), q, x_snap).astype(np.float64))
