@@ -123,17 +123,55 @@ __device__ __forceinline__ void store16(float *__restrict__ out, int64_t base, i
 }
 
 // acc[j] = fma(dm, code j of the thread's words, acc[j]) for its 16 coordinates.
-// For 4-bit fields the sign-extending bit-field extract per code is avoided: one shift and two masks move the low
-// and the high nibbles of a word to the top of their bytes, where each reads as the signed byte 16*k, which
-// converts to float in one instruction; the product with dm/16 is the same real number as dm*k, so the fused
-// multiply-add rounds to the same result bit for bit as long as dm/16 is exact, i.e. dm is zero or not within a
-// factor 2^26 of the smallest normal number -- otherwise the plain path is taken.  (Measured at M = 16 on 2^28
-// coordinates: 5.26 -> 5.73 TB/s.  The same idea for 2-bit fields, four masks per word, was slower: 4.76 -> 4.20.)
-template <int FIELD>
+// SCALED (2- and 4-bit fields): the sign-extending bit-field extract per code is avoided.  One shift and one mask
+// per field position move that field of every byte to the top of its byte, where it reads as the signed byte 64*k
+// (16*k), which converts to float in one instruction; the product with dm/64 (dm/16) is the same real number as
+// dm*k, so the fused multiply-add rounds to the same result bit for bit as long as the division is exact, i.e. dm
+// is zero or not within a factor 2^26 of the smallest normal number.  The caller tests that once for all scales
+// (a test per call would make the two paths meet after every worker, and the accumulators would be copied there).
+// Measured at M = 16 on 2^28 coordinates: 4-bit 5.26 -> 5.73 TB/s, 2-bit 4.76 -> 5.1 TB/s.
+// float(signed byte N of r), one instruction (sub-dword source select with sign extension)
+template <int N>
+__device__ __forceinline__ float signed_byte_to_float(uint32_t r)
+{
+    float f;
+    if constexpr (N == 0) asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0" : "=v"(f) : "v"(r));
+    else if constexpr (N == 1) asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1" : "=v"(f) : "v"(r));
+    else if constexpr (N == 2) asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2" : "=v"(f) : "v"(r));
+    else asm("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3" : "=v"(f) : "v"(r));
+    return f;
+}
+
+template <int FIELD, bool SCALED>
 __device__ __forceinline__ void fold_codes16(float dm, const uint32_t (&w)[Words16<FIELD>::n], float (&acc)[16])
 {
-    if constexpr (FIELD == 4) {
-        if (dm == 0.0f || fabsf(dm) >= 0x1p-100f) {                  // (dm is the same for every thread)
+    if constexpr (FIELD == 2 && SCALED) {
+        {
+            const float ds = dm * 0.015625f;
+            // field t of every byte moved to the top of its byte: the signed byte 64*k of coordinates t, 4+t, 8+t, 12+t
+            const uint32_t r0 = (w[0] << 6) & 0xC0C0C0C0u, r1 = (w[0] << 4) & 0xC0C0C0C0u,
+                           r2 = (w[0] << 2) & 0xC0C0C0C0u, r3 = w[0] & 0xC0C0C0C0u;
+            acc[0] = fmaf(ds, signed_byte_to_float<0>(r0), acc[0]);
+            acc[1] = fmaf(ds, signed_byte_to_float<0>(r1), acc[1]);
+            acc[2] = fmaf(ds, signed_byte_to_float<0>(r2), acc[2]);
+            acc[3] = fmaf(ds, signed_byte_to_float<0>(r3), acc[3]);
+            acc[4] = fmaf(ds, signed_byte_to_float<1>(r0), acc[4]);
+            acc[5] = fmaf(ds, signed_byte_to_float<1>(r1), acc[5]);
+            acc[6] = fmaf(ds, signed_byte_to_float<1>(r2), acc[6]);
+            acc[7] = fmaf(ds, signed_byte_to_float<1>(r3), acc[7]);
+            acc[8] = fmaf(ds, signed_byte_to_float<2>(r0), acc[8]);
+            acc[9] = fmaf(ds, signed_byte_to_float<2>(r1), acc[9]);
+            acc[10] = fmaf(ds, signed_byte_to_float<2>(r2), acc[10]);
+            acc[11] = fmaf(ds, signed_byte_to_float<2>(r3), acc[11]);
+            acc[12] = fmaf(ds, signed_byte_to_float<3>(r0), acc[12]);
+            acc[13] = fmaf(ds, signed_byte_to_float<3>(r1), acc[13]);
+            acc[14] = fmaf(ds, signed_byte_to_float<3>(r2), acc[14]);
+            acc[15] = fmaf(ds, signed_byte_to_float<3>(r3), acc[15]);
+            return;
+        }
+    }
+    if constexpr (FIELD == 4 && SCALED) {
+        {
             const float ds = dm * 0.0625f;
 #pragma unroll
             for (int i = 0; i < Words16<FIELD>::n; ++i) {
@@ -153,12 +191,14 @@ __device__ __forceinline__ void fold_codes16(float dm, const uint32_t (&w)[Words
 
 // Alg. 1, master (ii), receive side: acc[j] = sum_{m<M} delta[m] * k_m[16c + j], m ascending, one fma each.
 // For FIELD == 32 the rows hold float32 values and delta is taken as 1.
-template <int FIELD, bool STREAM = false>
-__device__ __forceinline__ void decode_sum16(const uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words,
-                                             const float *__restrict__ delta, int M, int64_t c, int64_t d, float (&acc)[16])
+// True when the byte-scaled decode of 2- and 4-bit fields is exact for this scale: delta/64 (delta/16) must be
+// computed without rounding, i.e. delta is zero or far enough above the smallest normal number.
+__device__ __forceinline__ bool scale_divides_exactly(float dm) { return dm == 0.0f || fabsf(dm) >= 0x1p-100f; }
+
+template <int FIELD, bool STREAM, bool SCALED>
+__device__ __forceinline__ void decode_sum16_impl(const uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words,
+                                                  const float *__restrict__ delta, int M, int64_t c, float (&acc)[16])
 {
-#pragma unroll
-    for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
     // the words of 8 workers are requested together, then folded in in worker order
     constexpr int kGroup = FIELD == 32 ? 2 : 8;
     int m = 0;
@@ -171,14 +211,41 @@ __device__ __forceinline__ void decode_sum16(const uint32_t *__restrict__ packed
             dm[u] = FIELD == 32 ? 1.0f : delta[m + u];
         }
 #pragma unroll
-        for (int u = 0; u < kGroup; ++u) fold_codes16<FIELD>(dm[u], w[u], acc);
+        for (int u = 0; u < kGroup; ++u) fold_codes16<FIELD, SCALED>(dm[u], w[u], acc);
     }
     for (; m < M; ++m) {
         uint32_t w[Words16<FIELD>::n];
         load_words<FIELD, STREAM>(packed + static_cast<int64_t>(m) * ld_words, c, row_words, w);
         const float dm = FIELD == 32 ? 1.0f : delta[m];
-        fold_codes16<FIELD>(dm, w, acc);
+        fold_codes16<FIELD, SCALED>(dm, w, acc);
     }
+}
+
+// Alg. 1, master (ii), receive side: acc[j] = sum_{m<M} delta[m] * k_m[16c + j], m ascending, one fma each.
+// For FIELD == 32 the rows hold float32 values and delta is taken as 1.
+// `scaled`: every delta[m] passes scale_divides_exactly (the same for all threads; ignored unless FIELD is 2 or 4).
+template <int FIELD, bool STREAM = false>
+__device__ __forceinline__ void decode_sum16(const uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words,
+                                             const float *__restrict__ delta, int M, int64_t c, int64_t d, bool scaled,
+                                             float (&acc)[16])
+{
+#pragma unroll
+    for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
+    if constexpr (FIELD == 2 || FIELD == 4) {
+        if (scaled) {
+            decode_sum16_impl<FIELD, STREAM, true>(packed, ld_words, row_words, delta, M, c, acc);
+            return;
+        }
+    }
+    decode_sum16_impl<FIELD, STREAM, false>(packed, ld_words, row_words, delta, M, c, acc);
+}
+
+// The test for `scaled` above, over all M scales (every thread gets the same answer).
+__device__ __forceinline__ bool scales_divide_exactly(const float *__restrict__ delta, int M)
+{
+    bool ok = true;
+    for (int m = 0; m < M; ++m) ok = ok && scale_divides_exactly(delta[m]);
+    return ok;
 }
 
 // ---- quads: four consecutive coordinates 4q .. 4q+3 (one Philox block, one 16-byte access) -------

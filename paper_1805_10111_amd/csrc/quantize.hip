@@ -316,9 +316,10 @@ __global__ __launch_bounds__(kThreads) void unpack_dequant_sum_kernel(
 {
     const int64_t chunks = (d + kCoordsPerThread - 1) / kCoordsPerThread;
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    const bool scaled = (FIELD == 2 || FIELD == 4) && scales_divide_exactly(delta, M);
     for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
         float acc[16];
-        decode_sum16<FIELD, true>(packed, ld_words, row_words, delta, M, c, d, acc);
+        decode_sum16<FIELD, true>(packed, ld_words, row_words, delta, M, c, d, scaled, acc);
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[j] = scale * acc[j];
         store16<false>(out, c * kCoordsPerThread, d, acc);
