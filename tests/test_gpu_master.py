@@ -30,7 +30,8 @@ def _messages(M, d, b, seed):
 
 @pytest.mark.parametrize("acc", [False, True])
 @pytest.mark.parametrize("b,bx", [(8, 8), (4, 8), (2, 4), (8, 2)])
-@pytest.mark.parametrize("M,d", [(1, 5), (4, 1000), (8, 20958), (32, 4096), (3, 4099), (2, 8192), (2, 8193), (2, 16400), (2, 40001)])
+@pytest.mark.parametrize("M,d", [(1, 5), (4, 1000), (8, 20958), (32, 4096), (3, 4099), (2, 8192), (2, 8193), (2, 16400), (2, 40001),
+                                 (45, 4100), (70, 333), (41, 9000)])
 def test_master_step_bit_exact(dq, acc, b, bx, M, d):
     k, delta, pw = _messages(M, d, b, seed=M * 7 + d + b)
     rng = np.random.default_rng(d)
@@ -180,7 +181,7 @@ def test_mu_terms_degenerate_and_bx_choice(dq):
 
 @pytest.mark.parametrize("acc", [False, True])
 @pytest.mark.parametrize("b,bx", [(8, 8), (4, 8), (2, 4), (8, 11)])
-@pytest.mark.parametrize("M,d", [(1, 5), (4, 1000), (9, 4099), (32, 4096), (2, 40001)])
+@pytest.mark.parametrize("M,d", [(1, 5), (4, 1000), (9, 4099), (32, 4096), (2, 40001), (19, 333), (45, 4100)])
 def test_master_step_each_bit_exact(dq, acc, b, bx, M, d):
     """One update per received gradient (Alg. 1, master (ii) applied message by message)."""
     k, delta, pw = _messages(M, d, b, seed=M * 5 + d + b)

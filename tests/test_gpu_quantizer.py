@@ -117,7 +117,7 @@ def test_pack_unpack_roundtrip(dq, b):
 
 
 @pytest.mark.parametrize("b", [2, 4, 8])
-@pytest.mark.parametrize("M,d", [(1, 17), (4, 1000), (16, 20958), (32, 4096)])
+@pytest.mark.parametrize("M,d", [(1, 17), (4, 1000), (16, 20958), (32, 4096), (21, 777), (45, 100003)])
 def test_unpack_dequant_sum_bit_exact(dq, b, M, d):
     rng = np.random.default_rng(M * d + b)
     k = rng.integers(-(2 ** (b - 1)), 2 ** (b - 1), size=(M, d)).astype(np.int8)
