@@ -83,7 +83,7 @@ __device__ __forceinline__ bool bernoulli(uint32_t word, float p)
 struct Scale {
     float delta;      // amax / L, or 0 (degenerate), or non-finite
     float inv_delta;  // L / amax (0 when codes must be all zero)
-    int kmin, kmax;
+    float tmin, tmax; // code range -2^(b-1) .. L as floats
     bool bad;         // non-finite delta
 };
 
@@ -91,8 +91,8 @@ __device__ __forceinline__ Scale make_scale(float amax, int b)
 {
     Scale s;
     const int L = (1 << (b - 1)) - 1;
-    s.kmin = -(1 << (b - 1));
-    s.kmax = L;
+    s.tmin = -static_cast<float>(1 << (b - 1));
+    s.tmax = static_cast<float>(L);
     float delta = amax / static_cast<float>(L);
     s.bad = !(delta == delta) || delta > FLT_MAX;           // NaN or Inf
     if (s.bad) {
@@ -111,13 +111,13 @@ __device__ __forceinline__ Scale make_scale(float amax, int b)
 // One coordinate of Q_(delta,b): returns the integer code.
 __device__ __forceinline__ int quantize_one(float v, const Scale &s, uint32_t word)
 {
-    const float t = v * s.inv_delta;
+    // The code is clamped to [-2^(b-1), L].  Clamping v/delta to that range first (one three-operand median) gives
+    // the same code as clamping the rounded integer: inside the range nothing changes (floor(t) + 1 <= L for
+    // t < L, and t = L has p = 0), and outside it t becomes a bound, whose code is that bound.
+    const float t = __builtin_amdgcn_fmed3f(v * s.inv_delta, s.tmin, s.tmax);
     const float z = floorf(t);
     const float p = t - z;
-    int k = static_cast<int>(z) + (bernoulli(word, p) ? 1 : 0);
-    k = max(k, s.kmin);
-    k = min(k, s.kmax);
-    return k;
+    return static_cast<int>(z) + (bernoulli(word, p) ? 1 : 0);
 }
 
 // ---- magnitude bit pattern: monotone in |v| for non-NaN, NaN sorts above Inf ----

@@ -316,19 +316,41 @@ __device__ __forceinline__ float4 quad_values(const uint32_t *__restrict__ row, 
     return quad_decode<FIELD>(quad_request<FIELD>(row, q, d), q);
 }
 
+// Four codes, each within the two's-complement range of a FIELD-bit field, as 4*FIELD bits (first code lowest).
+// Bytes: two byte permutes and an or.  Narrower fields: the codes plus 2^(FIELD-1) are non-negative, so they are
+// shifted into place without masking off sign bits; flipping the top bit of every field afterwards (kFieldTops, which
+// the caller may apply once per word instead: FLIP = false) turns k + 2^(FIELD-1) into the two's-complement field.
+template <int FIELD>
+struct FieldTops {
+    static constexpr uint32_t quad = (1u << (FIELD - 1)) * (1u | (1u << FIELD) | (1u << (2 * FIELD)) | (1u << (3 * FIELD)));
+    static constexpr uint32_t word = FIELD == 8 ? quad : FIELD == 4 ? quad * 0x10001u : quad * 0x01010101u;
+};
+
+template <int FIELD, bool FLIP = true>
+__device__ __forceinline__ uint32_t pack4(int k0, int k1, int k2, int k3)
+{
+    if constexpr (FIELD == 8) {
+        return __builtin_amdgcn_perm(static_cast<uint32_t>(k1), static_cast<uint32_t>(k0), 0x0c0c0400u) |
+               __builtin_amdgcn_perm(static_cast<uint32_t>(k3), static_cast<uint32_t>(k2), 0x04000c0cu);
+    } else {
+        constexpr int kBias = 1 << (FIELD - 1);
+        const uint32_t u = static_cast<uint32_t>(k0 + kBias) | (static_cast<uint32_t>(k1 + kBias) << FIELD) |
+                           (static_cast<uint32_t>(k2 + kBias) << (2 * FIELD)) | (static_cast<uint32_t>(k3 + kBias) << (3 * FIELD));
+        return FLIP ? u ^ FieldTops<FIELD>::quad : u;
+    }
+}
+
 // Q_(delta,b) on quad q: the 4*FIELD code bits (coordinate 4q in the low field) and the number of
 // nonzero codes added to nz.  Coordinates past the end must be passed as 0.
 template <int FIELD>
 __device__ __forceinline__ uint32_t quantize_quad(float4 a, const Scale &s, const StreamKey &key, int64_t q, int &nz)
 {
-    constexpr uint32_t kMask = (1u << FIELD) - 1u;
     if (s.inv_delta == 0.0f) return 0u;              // degenerate scale: all codes are zero
     const uint4 r = stream_block(key, static_cast<uint32_t>(q));
     const int k0 = quantize_one(a.x, s, r.x), k1 = quantize_one(a.y, s, r.y);
     const int k2 = quantize_one(a.z, s, r.z), k3 = quantize_one(a.w, s, r.w);
     nz += (k0 != 0) + (k1 != 0) + (k2 != 0) + (k3 != 0);
-    return (static_cast<uint32_t>(k0) & kMask) | ((static_cast<uint32_t>(k1) & kMask) << FIELD) |
-           ((static_cast<uint32_t>(k2) & kMask) << (2 * FIELD)) | ((static_cast<uint32_t>(k3) & kMask) << (3 * FIELD));
+    return pack4<FIELD>(k0, k1, k2, k3);
 }
 
 // Stores the code bits of quad q = q0 + lane, where q0 is a multiple of 64 common to the wavefront.
@@ -379,7 +401,6 @@ template <int FIELD>
 __device__ __forceinline__ int quantize16(const float (&v)[16], const Scale &s, const StreamKey &key, int64_t c,
                                           uint32_t (&w)[Words16<FIELD>::n])
 {
-    constexpr uint32_t kMask = (1u << FIELD) - 1u;
     int nz = 0;
 #pragma unroll
     for (int i = 0; i < Words16<FIELD>::n; ++i) w[i] = 0u;
@@ -387,14 +408,14 @@ __device__ __forceinline__ int quantize16(const float (&v)[16], const Scale &s, 
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         const uint4 r = stream_block(key, static_cast<uint32_t>(c * 4 + g));
-        const uint32_t rw[4] = {r.x, r.y, r.z, r.w};
+        const int k0 = quantize_one(v[4 * g], s, r.x), k1 = quantize_one(v[4 * g + 1], s, r.y);
+        const int k2 = quantize_one(v[4 * g + 2], s, r.z), k3 = quantize_one(v[4 * g + 3], s, r.w);
+        nz += (k0 != 0) + (k1 != 0) + (k2 != 0) + (k3 != 0);
+        w[(4 * g * FIELD) / 32] |= pack4<FIELD, false>(k0, k1, k2, k3) << ((4 * g * FIELD) % 32);
+    }
+    if constexpr (FIELD != 8) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int j = g * 4 + e;
-            const int k = quantize_one(v[j], s, rw[e]);
-            nz += k != 0 ? 1 : 0;
-            w[(j * FIELD) / 32] |= (static_cast<uint32_t>(k) & kMask) << ((j * FIELD) % 32);
-        }
+        for (int i = 0; i < Words16<FIELD>::n; ++i) w[i] ^= FieldTops<FIELD>::word;
     }
     return nz;
 }
