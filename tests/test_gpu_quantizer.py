@@ -99,6 +99,30 @@ def test_absmax_given_is_used(dq):
 
 
 @pytest.mark.parametrize("b", [2, 4, 8])
+def test_scale_smaller_than_the_vector_clamps_like_the_rule(dq, b):
+    """A caller-supplied ||v||_inf below the true maximum (outside the paper's definition, which always takes the
+    true one): values beyond the scale get the end codes of the b-bit range, -2^(b-1) and 2^(b-1)-1, and all others
+    the code of the rule of Section 3.1 with the stream's uniform variates.  The expected codes apply that rule in
+    float32 with the oracle's variates; the oracle's own quantizer always derives the scale from the vector."""
+    d = 4099
+    v = _vec(d, 3)
+    amax = np.float32(0.05) * oracle.absmax(v)
+    L = np.float32(2 ** (b - 1) - 1)
+    inv_delta = L / amax
+    t = (v * inv_delta).astype(np.float32)
+    z = np.floor(t)
+    p = (t - z).astype(np.float32)
+    u = oracle.uniform_range(9, 4, 2, oracle.TAG_GRAD, 0, d)
+    want = np.clip(z.astype(np.int64) + (u < p), -(2 ** (b - 1)), 2 ** (b - 1) - 1)
+    assert (np.abs(t) > L + 2).sum() > 50                     # the case is really exercised
+    codes = torch.zeros((1, 4112), dtype=torch.int8, device="cuda")[:, :d]
+    delta = torch.zeros(1, device="cuda")
+    dq.dq_quantize(dev(v)[None, :], b, dev(np.array([amax], dtype=np.float32)), True, 9, 4, dq.TAG_GRAD, 2, codes, delta)
+    assert np.array_equal(host(codes)[0].astype(np.int64), want)
+    assert host(delta)[0] == oracle.delta_of(amax, b)
+
+
+@pytest.mark.parametrize("b", [2, 4, 8])
 def test_pack_unpack_roundtrip(dq, b):
     M, d = 3, 1001
     rng = np.random.default_rng(b)
