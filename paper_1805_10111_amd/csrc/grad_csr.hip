@@ -304,8 +304,8 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     // may continue in the next word; both words and the snapshot value are requested without any condition
     struct Gather { uint32_t w0, w1; float xs; };
     auto vec_req = [&](int c) {
-        const int w = (c * a.b_x) >> 5;
-        return Gather{a.xq[w], a.xq[min(static_cast<int64_t>(w) + 1, a.model_last_word)], a.x_snap[c]};
+        const int w = (c * a.b_x) >> 5, last = static_cast<int>(a.model_last_word);   // (fewer than 2^20 words)
+        return Gather{a.xq[w], a.xq[w + 1 < last ? w + 1 : last], a.x_snap[c]};
     };
     auto vec_val = [&](const Gather &g, int c) {
         const uint32_t bits = __funnelshift_r(g.w0, g.w1, static_cast<unsigned>(c * a.b_x) & 31u);
