@@ -90,3 +90,45 @@ def test_argument_checks(dq):
     with pytest.raises(dq.DqError) as e:                 # stream larger than the on-chip buffer
         dq.dq_sparse_encode(big, 200000, 8, torch.zeros(300000, dtype=torch.int32, device="cuda"), n)
     assert e.value.code == dq.ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("b", [2, 4, 8])
+def test_longest_message_the_encoder_takes(dq, b):
+    """The encoder assembles a worker's stream in the on-chip buffer (36864 words): the largest d whose full
+    stream fits, with one row that has no zero code at all (the stream is at capacity), one empty row and one in
+    between; one coordinate more is refused."""
+    limit = 36 * 1024
+    lo, hi = 1, 1 << 21
+    while hi - lo > 1:                                   # largest d with sparse_stream_words(d, b) <= limit
+        mid = (lo + hi) // 2
+        lo, hi = (mid, hi) if oracle.sparse_stream_words(mid, b) <= limit else (lo, mid)
+    d = lo
+    assert oracle.sparse_stream_words(d, b) <= limit < oracle.sparse_stream_words(d + 1, b)
+    rng = np.random.default_rng(b)
+    M = 3
+    nw = dq.packed_words(d, b)
+    ldw = (nw + 3) // 4 * 4
+    cap = dq.dq_sparse_stream_words(d, b)
+    codes = rng.integers(-(2 ** (b - 1)), 2 ** (b - 1), size=(M, d)).astype(np.int8)
+    codes[0][codes[0] == 0] = 1                          # every coordinate present
+    codes[1][:] = 0
+    codes[2, rng.random(d) < 0.7] = 0
+    pw = np.zeros((M, ldw), dtype=np.uint32)
+    for m in range(M):
+        pw[m, :nw] = oracle.pack(codes[m], b)
+    stream = torch.full((M, cap), -1, dtype=torch.int32, device="cuda")
+    nnz = torch.full((M,), -1, dtype=torch.int32, device="cuda")
+    dq.dq_sparse_encode(dev(pw.view(np.int32)), d, b, stream, nnz)
+    for m in range(M):
+        want, k = oracle.sparse_encode(codes[m], b)
+        assert host(nnz)[m] == k and (m != 0 or k == d)
+        assert np.array_equal(words(stream)[m, :cap], want)
+    back = torch.full((M, ldw), -1, dtype=torch.int32, device="cuda")
+    dq.dq_sparse_decode(stream, nnz, d, b, back)
+    assert np.array_equal(words(back)[:, :nw], pw[:, :nw])
+    d1 = d + 1
+    nw1 = dq.packed_words(d1, b)
+    with pytest.raises(dq.DqError) as e:
+        dq.dq_sparse_encode(torch.zeros((nw1 + 3) // 4 * 4, dtype=torch.int32, device="cuda"), d1, b,
+                            torch.zeros(dq.dq_sparse_stream_words(d1, b), dtype=torch.int32, device="cuda"), nnz[:1])
+    assert e.value.code == dq.ERR_UNSUPPORTED
