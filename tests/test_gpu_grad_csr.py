@@ -57,6 +57,10 @@ def _problems():
         "mid": synth.sparse_text_logistic(500, 4099, mean_nnz=30.0, seed=3),
         # rcv1-like width (47,236 features): the gradient does not fit in LDS and is built in two column windows
         "wide": synth.sparse_text_logistic(1500, 47236, mean_nnz=75.0, seed=4),
+        # the widest model whose gradient is one window in LDS (little room is left for staging entries: rows go in
+        # small groups, and rows longer than the staging buffer straight from memory), and the first that takes two
+        "lastone": synth.sparse_text_logistic(400, 35328, mean_nnz=120.0, seed=6),
+        "firsttwo": synth.sparse_text_logistic(400, 35329, mean_nnz=120.0, seed=7),
         # the widest model the CSR kernels take (2^20 - 1 columns): about thirty column windows per worker step
         "widest": _widest_problem(),
     }
@@ -75,7 +79,7 @@ def _model(rng, d, b_x, x_snap, spread=0.05):
     return oracle.pack(k, b_x), dx, oracle.dequantize(k, dx)
 
 
-@pytest.mark.parametrize("name", ["text", "tiny", "long", "mid", "wide", "widest"])
+@pytest.mark.parametrize("name", ["text", "tiny", "long", "mid", "wide", "lastone", "firsttwo", "widest"])
 def test_full_grad(dq, problems, name):
     p = problems[name]
     P = dq.DeviceProblem.from_host(p)
@@ -98,7 +102,7 @@ def test_full_grad(dq, problems, name):
 @pytest.mark.parametrize("have_z", [True, False])
 @pytest.mark.parametrize("b_x", [8, 2, 32])
 @pytest.mark.parametrize("name,M,B", [("text", 8, 32), ("tiny", 3, 5), ("long", 2, 40), ("mid", 4, 300), ("wide", 5, 48),
-                                      ("widest", 2, 12)])
+                                      ("lastone", 3, 40), ("firsttwo", 3, 40), ("widest", 2, 12)])
 def test_vr_grad(dq, problems, name, M, B, b_x, have_z):
     p = problems[name]
     P = dq.DeviceProblem.from_host(p)
@@ -136,7 +140,8 @@ def test_vr_grad(dq, problems, name, M, B, b_x, have_z):
 
 @pytest.mark.parametrize("sparsify", [False, True])
 @pytest.mark.parametrize("b", [8, 4])
-@pytest.mark.parametrize("name,M,B", [("text", 16, 64), ("tiny", 2, 7), ("long", 2, 12), ("wide", 4, 40), ("widest", 2, 9)])
+@pytest.mark.parametrize("name,M,B", [("text", 16, 64), ("tiny", 2, 7), ("long", 2, 12), ("wide", 4, 40), ("lastone", 3, 33),
+                                      ("firsttwo", 3, 33), ("widest", 2, 9)])
 def test_worker_step(dq, problems, name, M, B, b, sparsify):
     p = problems[name]
     P = dq.DeviceProblem.from_host(p)
