@@ -138,7 +138,8 @@ def test_vr_grad_flag_bit_and_bad_index(dq):
 @pytest.mark.parametrize("bad", [False, True])
 @pytest.mark.parametrize("d,M,B", [(4096, 2, 256), (4096, 1, 71), (3000, 2, 70), (4096, 32, 64), (2052, 3, 44),
                                    (2048, 2, 70), (1500, 3, 64), (8192, 2, 40), (6000, 2, 70), (16384, 2, 36),
-                                   (12000, 1, 33), (4096, 1, 65536), (2048, 1, 40000)])
+                                   (12000, 1, 33), (4096, 1, 65536), (2048, 1, 40000),
+                                   (1024, 3, 64), (1028, 2, 40), (4100, 2, 40), (8196, 2, 36), (16380, 1, 34)])
 def test_vr_grad_row_streaming_paths(dq, d, M, B, bad):
     """Rows wider than 1024 floats are streamed with two row buffers when a block owns whole pairs of batches of valid
     rows, with one buffer when it owns whole batches, and through the checked loop otherwise (ragged last block,
