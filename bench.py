@@ -121,6 +121,11 @@ def quantizer_leg(dq, torch):
             per_call.append(e0.elapsed_time(e1) / reps * 1e-3)
         return sorted(per_call)[len(per_call) // 2]
 
+    # what plain device kernels reach on the same box, for scale: a 1 GiB copy (read + write) and a 1 GiB read
+    w = torch.empty_like(v)
+    t = timed(lambda: w.copy_(v))
+    out["plain_copy_1GiB"] = {"GB/s": round(2 * N * 4 / t * 1e-9, 1), "us": round(t * 1e6, 1)}
+    del w
     t = timed(lambda: dq.dq_absmax(v, absmax))
     out["absmax"] = {"GB/s": round(N * 4 / t * 1e-9, 1), "us": round(t * 1e6, 1)}
     for b in (8, 4, 2):
