@@ -300,6 +300,9 @@ def main():
                    "inner_loop_only": {"worker_steps_per_s": round(cfg.M * inner_rounds / inner_s, 1),
                                        "us_per_round": round(inner_s / inner_rounds * 1e6, 2),
                                        "note": "rounds of whole epochs with the full gradient outside the clock"}},
+        "mfma": {"used": False, "why": "the contractions of the path are rows x [d x 2] and [d x rows] x 1: a matrix-core tile "
+                                       "would be mostly padding, float32 matrix and vector peaks are equal, and the "
+                                       "kernel is bound by the single read of the rows"},
         "roofline": {"bound": "hbm", "kernel": KERNEL_NAME[prob.is_csr],
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": recorded_traffic(cfg.name),
