@@ -3,14 +3,15 @@
 
 A step is one synchronous round of the whole path for all M workers: model message ->
 variance-reduced mini-batch gradients -> stochastic quantization -> packing -> master
-decode/aggregate -> prox or momentum update -> model re-quantization, with the epoch
-prologue (full gradient) executed inside the timed region at its real cadence (every m
-rounds).  Inputs are resident in HBM before the clock starts.
+decode/aggregate -> prox or momentum update -> model re-quantization.  The clock is a pair
+of HIP events around every run of consecutive rounds; the epoch prologue (full gradient,
+once per m rounds) runs at its real cadence but outside the clock and is reported apart.
+Inputs are resident in HBM before the clock starts.
 
-Prints ONE JSON line: worker-steps/s (= M * rounds / time) on the accelerated dense
-workload (config C4), the roofline figures of the dominant kernel measured with HIP
-events on the launch stream, the quantizer microbenchmark (config C5) as extra fields,
-and the CPU oracle timed on a bounded sample of the same workload.
+Prints ONE JSON line: worker-steps/s (= M * rounds / time of the round loop) on the
+accelerated dense workload (config C4), the roofline figures of the dominant kernel from
+the start/stop events of its own launches, the quantizer microbenchmark (config C5) as
+extra fields, and the CPU oracle timed on bounded samples of the same workloads.
 """
 from __future__ import annotations
 
@@ -24,7 +25,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-EVENT_STRIDE = 8          # rounds between HIP-event brackets around the dominant kernel
+EVENT_STRIDE = 4          # every EVENT_STRIDE-th round of the kernel-timing epochs carries launch events
+KERNEL_EPOCHS = 8         # epochs run after the timed region for the dominant kernel's own duration
+MIN_WARM_EPOCHS = 3       # whole epochs before the clock starts
+MIN_TIMED_EPOCHS = 10     # epochs' worth of rounds that the reported median rests on
 KERNEL_NAME = {False: "vr_dense_kernel (variance-reduced gradient, all M workers)",
                True: "csr_worker_kernel (whole worker step, all M workers)"}
 
@@ -45,40 +49,97 @@ def parse():
     return ap.parse_args()
 
 
-def run_rounds(tr, rounds, events=None):
+def run_rounds(tr, rounds, loop_events=None, prologue_events=None):
     """Advance the trainer by `rounds` rounds, running epoch prologues/epilogues at their cadence.
 
-    `events`: optional list that receives (start, end, is_flag_round) for the bracketed rounds, the two
-    torch events being handed to the library as the start and stop events of the launch of the kernel that
-    streams the feature rows (the dominant kernel of a round).
+    The round loop (Alg. 1-3, inner `for t`: model message, worker steps, master step) and the epoch prologue
+    (full gradient at the snapshot) are timed apart: every contiguous run of rounds inside one epoch is bracketed
+    by a pair of events appended to `loop_events` (the prologue and the epilogue lie outside every pair), and every
+    prologue by a pair appended to `prologue_events`.
     """
     import torch
+
+    def pair():
+        return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     done = 0
     while done < rounds:
         if tr._t == 0:
+            if prologue_events is not None:
+                p0, p1 = pair()
+                p0.record()
             tr.epoch_prologue()
+            if prologue_events is not None:
+                p1.record()
+                prologue_events.append((p0, p1))
         take = min(rounds - done, tr.m - tr._t)
-        if events is None:
-            tr.rounds(tr._t, take)
-        else:
-            # only every EVENT_STRIDE-th round is bracketed (a launch that carries events is a little slower)
-            k = 0
-            while k < take:
-                if (done + k) % EVENT_STRIDE == EVENT_STRIDE - 1:
-                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    e0.record(); e1.record()            # instantiates the HIP events; the launch overwrites them
-                    tr.rounds(tr._t + k, 1, [e0.cuda_event, e1.cuda_event])
-                    events.append((e0, e1, tr.is_flag_round(tr._t + k)))
-                    k += 1
-                else:
-                    run = min(take - k, EVENT_STRIDE - 1 - (done + k) % EVENT_STRIDE)
-                    tr.rounds(tr._t + k, run)
-                    k += run
+        if loop_events is not None:
+            e0, e1 = pair()
+            e0.record()
+        tr.rounds(tr._t, take)
+        if loop_events is not None:
+            e1.record()
+            loop_events.append((e0, e1, take))
         tr._t += take
         done += take
         if tr._t == tr.m:
             tr.epoch_epilogue()
             tr._t = 0
+
+
+def time_round_loop(tr, torch, steps, warmup):
+    """Times the round loop (Alg. 1-3, inner `for t`) with events on the launch stream around whole runs of rounds;
+    the epoch prologue (full gradient) and epilogue lie outside every bracket and are timed apart.  A measurement is
+    `steps` consecutive rounds; it is repeated until at least MIN_TIMED_EPOCHS epochs' worth of rounds have been
+    timed, and the caller reports the median measurement.  Warm-up: the `warmup` rounds asked for, and at least
+    MIN_WARM_EPOCHS whole epochs.  Leaves the trainer at the start of an epoch."""
+    m = tr.m
+    run_rounds(tr, max(warmup, MIN_WARM_EPOCHS * m))
+    torch.cuda.synchronize()
+    repeats = max(1, -(-MIN_TIMED_EPOCHS * m // steps))
+    per_repeat, prologue_events = [], []
+    t0 = time.perf_counter()
+    for _ in range(repeats):
+        ev = []
+        run_rounds(tr, steps, ev, prologue_events)
+        per_repeat.append(ev)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    if int(tr.status.item()) != 0:
+        raise FloatingPointError("non-finite quantization scale during the benchmark")
+    loop_s = sorted(sum(e0.elapsed_time(e1) for e0, e1, _ in ev) * 1e-3 for ev in per_repeat)
+    prologues = sorted(p0.elapsed_time(p1) * 1e-3 for p0, p1 in prologue_events)
+    while tr._t != 0:                   # finish the epoch that the last measurement ended in
+        run_rounds(tr, 1)
+    return {"loop_s": loop_s, "median_s": loop_s[len(loop_s) // 2], "repeats": repeats, "wall_s": wall,
+            "prologues": prologues, "prologue_s": prologues[len(prologues) // 2] if prologues else None,
+            "warm_rounds": max(warmup, MIN_WARM_EPOCHS * m)}
+
+
+def kernel_durations(tr, epochs, stride):
+    """Own duration of the dominant kernel (the one that streams the feature rows of all M workers): every
+    `stride`-th round of `epochs` further epochs is enqueued by a call of its own that hands the library two events,
+    which it uses as the start and stop events of that launch (hipExtLaunchKernel), i.e. the kernel's time stamps on
+    the launch stream.  Flag-bit rounds read no rows and are skipped.  Returns seconds per launch (list)."""
+    import torch
+    events = []
+    for _ in range(epochs):
+        assert tr._t == 0
+        tr.epoch_prologue()
+        t = 0
+        while t < tr.m:
+            if t % stride == stride - 1 and not tr.is_flag_round(t):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(); e1.record()            # instantiates the HIP events; the launch overwrites them
+                tr.rounds(t, 1, [e0.cuda_event, e1.cuda_event])
+                events.append((e0, e1))
+                t += 1
+            else:
+                run = min(tr.m - t, stride - 1 - t % stride)
+                tr.rounds(t, run)
+                t += run
+        tr.epoch_epilogue()
+    torch.cuda.synchronize()
+    return [e0.elapsed_time(e1) * 1e-3 for e0, e1 in events]
 
 
 def recorded_traffic(workload: str):
@@ -154,16 +215,13 @@ def other_configs_leg(dq, torch, synth, Trainer, skip):
         prob = synth.make_problem(cfg)
         tr = Trainer(dq.DeviceProblem.from_host(prob), cfg.algo, cfg.M, cfg.B, cfg.b_x, cfg.b, cfg.m, cfg.lr, seed=cfg.seed)
         tr._t = 0
-        run_rounds(tr, cfg.m)                      # one epoch of warm-up
-        torch.cuda.synchronize()
-        rounds = 2 * cfg.m
-        t0 = time.perf_counter()
-        run_rounds(tr, rounds)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
+        rounds = cfg.m                              # a measurement = one epoch of rounds
+        meas = time_round_loop(tr, torch, rounds, 0)
+        dt = meas["median_s"]
         out[name] = {"us_per_round": round(dt / rounds * 1e6, 2), "worker_steps_per_s": round(cfg.M * rounds / dt, 1),
-                     "rounds": rounds, "M": cfg.M, "B": cfg.B, "d": prob.d,
-                     "note": "launch/latency-bound: under 3 MB of traffic per round"}
+                     "rounds_per_measurement": rounds, "repeats": meas["repeats"], "M": cfg.M, "B": cfg.B, "d": prob.d,
+                     "prologue_us": round(meas["prologue_s"] * 1e6, 1),
+                     "note": "launch/latency-bound: under 3 MB of traffic per round; round loop only, as `value`"}
         del tr
     return out
 
@@ -226,6 +284,68 @@ def cpu_baseline(cfg, prob, seconds):
     return out
 
 
+def cpu_baseline_quantizer(log2n=24, M=16):
+    """The oracle on config C5's three stages (scale reduction, quantize + pack, decode-and-sum over M messages) at
+    b in {2, 4, 8}: GB/s of the same algorithmic bytes as the GPU figures, on a slice of 2^log2n coordinates of the
+    same vector, on one thread and with contiguous chunks of the vector on all host threads (coordinates are
+    independent and the random streams addressed, so chunking changes no result; a chunk draws its variates with the
+    oracle's range generator and carries the global largest magnitude as one extra coordinate)."""
+    import numpy as np
+    import oracle
+    import synth
+    from concurrent.futures import ThreadPoolExecutor
+    n = 1 << log2n
+    v = synth.mixture_vector(n, seed=0)
+    threads = max(1, min(16, len(os.sched_getaffinity(0))))
+    bounds = [n * i // threads // 32 * 32 for i in range(threads)] + [n]
+    chunks = list(zip(bounds[:-1], bounds[1:]))
+    out = {"unit": "GB/s", "kind": "oracle", "cores": [1, threads],
+           "sample": f"the first 2^{log2n} of config C5's 2^28 coordinates, M={M} messages for the decode; each stage "
+                     f"once on one thread and once with {threads} contiguous chunks on {threads} threads; gcc -O2"}
+
+    def clock(fn):
+        t0 = time.perf_counter()
+        r = fn()
+        return time.perf_counter() - t0, r
+
+    def both(name, nbytes, one, chunked, pool):
+        t1, r1 = clock(one)
+        tn, rn = clock(lambda: list(pool.map(chunked, chunks)))
+        out[name] = {"one_thread": round(nbytes / t1 * 1e-9, 3), "all_threads": round(nbytes / tn * 1e-9, 3)}
+        return r1, rn
+
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        amax, parts = both("absmax", 4 * n, lambda: oracle.absmax(v), lambda c: oracle.absmax(v[c[0]:c[1]]), pool)
+        assert amax == max(parts)
+        for b in (8, 4, 2):
+            def quantize_all():
+                k, delta, _ = oracle.quantize(v, b, 0, 0, 3)
+                return oracle.pack(k, b), delta
+
+            def quantize_chunk(c):
+                lo, hi = c
+                u = np.concatenate([oracle.uniform_range(0, 0, 3, oracle.TAG_GRAD, lo, hi - lo),
+                                    np.array([0.5], dtype=np.float32)])
+                k, delta, _ = oracle.quantize_given_uniforms(np.concatenate([v[lo:hi], np.array([amax], dtype=np.float32)]), b, u)
+                return oracle.pack(k[:-1], b), delta
+            (words, delta), per_chunk = both(f"quantize_pack_b{b}", n * (4 + b / 8), quantize_all, quantize_chunk, pool)
+            assert np.array_equal(words, np.concatenate([w for w, _ in per_chunk]))
+            rows = np.tile(words, (M, 1))              # M messages (the decode's cost does not depend on their content)
+            deltas = np.full(M, delta, dtype=np.float32)
+            zeros = np.zeros(n, dtype=np.float32)
+
+            def decode(lo, hi):
+                codes = np.stack([oracle.unpack(rows[w, lo * b // 32:hi * b // 32], hi - lo, b) for w in range(M)])
+                x = np.zeros(hi - lo, dtype=np.float32)
+                # x <- x - eta*(scale*sum_m delta_m k_m + 0) with eta = -1: the aggregated vector itself
+                oracle.master_update(codes, deltas, np.float32(1.0 / M), zeros[lo:hi], x, eta=-1.0, l1=0.0)
+                return x
+            whole, per_chunk = both(f"unpack_dequant_sum_b{b}_M{M}", n * (M * b / 8 + 4), lambda: decode(0, n),
+                                    lambda c: decode(c[0], c[1]), pool)
+            assert np.array_equal(whole, np.concatenate(per_chunk))
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -247,35 +367,14 @@ def main():
     tr = DoubleQuantTrainer(P, cfg.algo, cfg.M, cfg.B, cfg.b_x, cfg.b, cfg.m, cfg.lr, seed=cfg.seed)
     tr._t = 0
 
-    run_rounds(tr, args.warmup)
-    torch.cuda.synchronize()
-    events = []
-    t0 = time.perf_counter()
-    run_rounds(tr, args.steps, events)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    if int(tr.status.item()) != 0:
-        raise FloatingPointError("non-finite quantization scale during the benchmark")
+    m = cfg.m
+    meas = time_round_loop(tr, torch, args.steps, args.warmup)
+    loop_s, dt, prologue, prologue_s, repeats, wall = (meas[k] for k in ("loop_s", "median_s", "prologue_s", "prologues",
+                                                                          "repeats", "wall_s"))
 
-    # the same rounds without the epoch prologue (rate of the inner loop alone): whole epochs, prologue outside
-    # the clock, no event brackets
-    while tr._t != 0:
-        run_rounds(tr, 1)
-    inner_s, inner_rounds = 0.0, 0
-    for _ in range(max(1, min(8, args.steps // cfg.m))):
-        tr.epoch_prologue()
-        torch.cuda.synchronize()
-        ti = time.perf_counter()
-        tr.rounds(0, tr.m)
-        torch.cuda.synchronize()
-        inner_s += time.perf_counter() - ti
-        inner_rounds += tr.m
-        tr.epoch_epilogue()
-
-    # dominant kernel: the row-streaming kernel of the worker step (all M workers in one launch);
-    # flag-bit rounds read no rows and are skipped.  The two events are the start and stop events of that launch
-    # (hipExtLaunchKernel inside the library), i.e. the kernel's own duration on the launch stream.
-    durs = [e0.elapsed_time(e1) * 1e-3 for e0, e1, flag in events if not flag]
+    # ---- dominant kernel: the row-streaming kernel of the worker step (all M workers in one launch), in rounds of
+    # its own after the timed region (a launch that carries events is a little slower than one that does not)
+    durs = kernel_durations(tr, KERNEL_EPOCHS, EVENT_STRIDE)
     k_avg = float(np.mean(durs))
     if prob.dense is not None:
         rows_bytes = cfg.M * cfg.B * prob.d * 4
@@ -284,6 +383,7 @@ def main():
     per_worker = tr.xq_words * 4 + prob.d * 4 + tr.row_words * 4 + cfg.B * 8
     alg_bytes = rows_bytes + cfg.M * per_worker
     achieved = alg_bytes / k_avg * 1e-9
+    us_round = dt / args.steps * 1e6
 
     result = {
         "metric": "quantized VR-gradient worker-steps/s + quantize/pack GB/s (% of HBM peak)",
@@ -295,19 +395,30 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: {cfg.algo} logistic, n={prob.n}, d={prob.d}, M={cfg.M}, B={cfg.B}, "
                                f"b_x={cfg.b_x}, b={cfg.b}, m={cfg.m} rounds/epoch, "
-                               f"{'CSR' if prob.is_csr else 'dense fp32'}; full gradient every m rounds inside the timed region",
-                   "seed": cfg.seed, "datagen_s": round(t_gen, 1),
-                   "inner_loop_only": {"worker_steps_per_s": round(cfg.M * inner_rounds / inner_s, 1),
-                                       "us_per_round": round(inner_s / inner_rounds * 1e6, 2),
-                                       "note": "rounds of whole epochs with the full gradient outside the clock"}},
+                               f"{'CSR' if prob.is_csr else 'dense fp32'}; a step is one round of the inner loop "
+                               f"(model message, M worker steps, master step); the epoch prologue (full gradient) "
+                               f"is outside the clock and reported in `epoch`",
+                   "seed": cfg.seed, "datagen_s": round(t_gen, 1)},
+        "timing": {"clock": "HIP events on the launch stream around every run of consecutive rounds of an epoch",
+                   "measurement": f"{args.steps} consecutive rounds", "repeats": repeats, "reported": "median",
+                   "us_per_round_min_median_max": [round(x / args.steps * 1e6, 2) for x in
+                                                   (loop_s[0], dt, loop_s[-1])],
+                   "warm_rounds": meas["warm_rounds"],
+                   "wall_s_all_repeats_with_prologues": round(wall, 4)},
+        "epoch": None if prologue is None else {
+            "prologue_us": round(prologue * 1e6, 1), "prologues_timed": len(prologue_s),
+            "worker_steps_per_s_with_prologue": round(cfg.M * m / (m * dt / args.steps + prologue), 1),
+            "note": "prologue = full gradient at the snapshot (+ the momentum mix of Alg. 3), once per m rounds"},
         "mfma": {"used": False, "why": "the contractions of the path are rows x [d x 2] and [d x rows] x 1: a matrix-core tile "
                                        "would be mostly padding, float32 matrix and vector peaks are equal, and the "
                                        "kernel is bound by the single read of the rows"},
         "roofline": {"bound": "hbm", "kernel": KERNEL_NAME[prob.is_csr],
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": recorded_traffic(cfg.name),
-                     "bytes_per_launch": alg_bytes, "avg_launch_us": round(k_avg * 1e6, 2),
-                     "timing": "start/stop HIP events of the kernel's launch, every 8th round of the timed region"},
+                     "bytes_per_launch": alg_bytes, "avg_launch_us": round(k_avg * 1e6, 2), "launches_timed": len(durs),
+                     "timing": f"start/stop HIP events of the kernel's launch, every {EVENT_STRIDE}th round of "
+                               f"{KERNEL_EPOCHS} epochs after the timed region",
+                     "round_frac": round(alg_bytes / (us_round * 1e-6) * 1e-9 / HBM_PEAK_GBS, 4)},
     }
     del tr, P
     torch.cuda.empty_cache()
@@ -324,6 +435,8 @@ def main():
         result["quantizer_C5"] = quantizer_leg(dq, torch)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, prob, args.cpu_seconds)
+        if not args.no_quantizer:
+            result["cpu_baseline"]["quantizer_C5"] = cpu_baseline_quantizer()
     print(json.dumps(result))
 
 
