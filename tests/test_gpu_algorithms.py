@@ -131,6 +131,28 @@ def test_free_run_objectives(dq, name):
     assert rel < 1e-3, rel       # free-running trajectories differ by a few flipped roundings
 
 
+def test_flag_bit_rule_when_an_update_leaves_the_model_at_the_snapshot(dq):
+    """Section 4.1 sends one flag bit when the model equals the snapshot.  The library decides that from where a round
+    stands in the epoch (first round of an epoch that starts at the snapshot); the oracle compares the two vectors bit
+    for bit at every round.  The two rules part only when an update returns the model to the snapshot exactly -- here a
+    prox that zeroes every step from a zero start.  What must hold then: the same iterates and gradient messages
+    (the quantized model of an all-zero vector is the snapshot itself, so the workers' gradients vanish either way),
+    and a download count that differs by exactly the model messages the library sends where the oracle sends flags."""
+    from paper_1805_10111_amd.driver import DoubleQuantTrainer
+    n, d, M, B, m, S = 400, 256, 4, 8, 6, 2
+    p = synth.dense_logistic(n, d, seed=4, l2=1e-4, l1=10.0)          # l1 far above any gradient entry: prox gives 0
+    tr = DoubleQuantTrainer(dq.DeviceProblem.from_host(p), "asylpg", M, B, 8, 8, m, 0.1, seed=2)
+    log = tr.run(S)
+    ref = alg.run(p, "asylpg", M, B, 8, 8, m, S, 0.1, seed=2)
+    assert not host(tr.x).any() and not ref.x.any()                    # the model never leaves the snapshot
+    assert not host(tr.delta).any() and not words(tr.packed).any()     # all-zero gradient messages, scale 0
+    for a, b in zip(log.objectives, ref.objectives):
+        assert abs(a - b) <= TOL * abs(b)
+    assert log.bits_up == ref.bits_up
+    assert ref.bits_down == S * m                                      # the oracle: a flag bit every round
+    assert log.bits_down == S * (1 + (m - 1) * (32 + 8 * d))           # the library: a flag at the epoch start only
+
+
 def test_runs_are_reproducible(dq):
     cfg, p, m = _small("C1")
     a = _trainer(dq, p, cfg, 10, seed=5); a.run(2)

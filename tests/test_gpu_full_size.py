@@ -80,6 +80,15 @@ def test_one_round_at_full_size(dq, name):
         assert host(nnz)[w] == np.count_nonzero(k)
         flips += int(np.count_nonzero(k != k_ref))
     assert flips <= max(3, 2e-3 * 3 * d), flips
+    # the direct check, every worker: the oracle's sparsifier and quantizer applied to the gradient the GPU itself
+    # computed give the GPU's message word for word
+    for w in range(M):
+        a_gpu = host(alpha)[w]
+        v_o = oracle.sparsify(a_gpu, seed, it, w)[0] if sparse else a_gpu
+        k_o, d_o, _ = oracle.quantize(v_o, b, seed, it, w)
+        assert host(delta)[w] == d_o
+        assert np.array_equal(words(packed)[w, :nw], oracle.pack(k_o, b))
+        assert host(nnz)[w] == np.count_nonzero(k_o)
     # ---- master (ii)+(i) at full M, fed with the oracle's messages: bit-exact
     codes = np.zeros((M, d), dtype=np.int8)
     deltas = np.zeros(M, dtype=np.float32)

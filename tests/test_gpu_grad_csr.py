@@ -195,6 +195,15 @@ def test_worker_step(dq, problems, name, M, B, b, sparsify):
         if not sparsify:
             assert diff.max() <= 1
     assert flips <= max(3, 2e-3 * M * d), flips
+    # the direct check: the oracle's sparsifier and quantizer applied to the gradient the GPU itself computed give
+    # the GPU's message word for word (identical quantizer inputs => identical codes, no flips)
+    for w in range(M):
+        a_gpu = host(alpha_f)[w]
+        v_o = oracle.sparsify(a_gpu, seed, it, w0 + w)[0] if sparsify else a_gpu
+        k_o, d_o, _ = oracle.quantize(v_o, b, seed, it, w0 + w)
+        assert host(delta)[w] == d_o
+        assert np.array_equal(words(packed)[w, :nw], oracle.pack(k_o, b))
+        assert host(nnz)[w] == np.count_nonzero(k_o)
 
 
 def test_flag_bit_round_and_limits(dq, problems):

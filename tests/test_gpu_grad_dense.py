@@ -234,6 +234,15 @@ def test_worker_step(dq, n, d, M, B, b, sparsify):
             # a flipped keep decision changes a code by the full level; count them
             flips += int(np.count_nonzero(diff))
     assert flips <= max(3, 2e-3 * M * d), flips          # decisions flipped by sub-tolerance differences
+    # the direct check: the oracle's sparsifier and quantizer applied to the gradient the GPU itself computed give
+    # the GPU's message word for word (identical quantizer inputs => identical codes, no flips)
+    for w in range(M):
+        a_gpu = host(alpha_f)[w]
+        v_o = oracle.sparsify(a_gpu, seed, it, w0 + w)[0] if sparsify else a_gpu
+        k_o, d_o, _ = oracle.quantize(v_o, b, seed, it, w0 + w)
+        assert host(delta)[w] == d_o
+        assert np.array_equal(words(packed)[w, :nw], oracle.pack(k_o, b))
+        assert host(nnz)[w] == np.count_nonzero(k_o)
 
 
 def test_worker_step_samples_its_own_minibatch(dq):

@@ -235,7 +235,7 @@ def test_full_size_vector_sampled(dq):
     v = torch.where(wide, v, v * 0.01).contiguous()
     del wide
     amax_ref = float(v.abs().max().item())
-    for b in (8, 2):
+    for b in (8, 4, 2):
         nw = dq.packed_words(N, b)
         packed = torch.zeros(nw, dtype=torch.int32, device="cuda")
         absmax = torch.zeros(1, device="cuda")
@@ -257,3 +257,44 @@ def test_full_size_vector_sampled(dq):
             assert dlt == host(delta)[0]
             assert np.array_equal(got, want[:4096])
         del packed
+
+
+def test_full_size_decode_and_sum_sampled(dq):
+    """Alg. 1, master (ii) at the size and in the launch shape of the quantizer benchmark: M = 16 messages of 2^28
+    coordinates each (row offsets beyond 4 GB), b in {8, 4, 2}; the messages are the library's own quantization of one
+    vector under 16 worker ids, the scales are made distinct.  The oracle unpacks sampled windows of every message,
+    aggregates them and must agree bit for bit; the words of two messages are checked against the oracle as well."""
+    N, M = 1 << 28, 16
+    g = torch.Generator(device="cuda").manual_seed(1)
+    v = torch.randn(N, device="cuda", generator=g)
+    wide = torch.rand(N, device="cuda", generator=g) < 0.1
+    v = torch.where(wide, v, v * 0.01).contiguous()
+    del wide
+    amax_ref = np.float32(v.abs().max().item())
+    absmax = torch.full((1,), float(amax_ref), device="cuda")
+    scale = float(np.float32(1.0 / M))
+    for b in (8, 4, 2):
+        nw = dq.packed_words(N, b)
+        packed = torch.zeros((M, nw), dtype=torch.int32, device="cuda")
+        delta = torch.zeros(M, device="cuda")
+        for w in range(M):
+            dq.dq_quantize_pack(v, b, absmax, True, 7, 2, dq.TAG_GRAD, w, packed[w], delta[w:w + 1])
+        assert np.all(host(delta) == oracle.delta_of(amax_ref, b))
+        delta *= torch.linspace(0.5, 1.5, M, device="cuda")           # distinct scales per message
+        res = torch.zeros(N, device="cuda")
+        dq.dq_unpack_dequant_sum(packed, delta, N, b, scale, res)
+        dl = host(delta)
+        rng = np.random.default_rng(100 + b)
+        starts = [0, N - 4096] + [int(s) // 16 * 16 for s in rng.integers(0, N - 4096, size=6)]
+        for s in starts:
+            lo, hi = s * b // 32, (s + 4096) * b // 32
+            codes = np.stack([oracle.unpack(words(packed[w, lo:hi]), 4096, b) for w in range(M)])
+            x = np.zeros(4096, dtype=np.float32)
+            oracle.master_update(codes, dl, np.float32(1.0 / M), np.zeros(4096, dtype=np.float32), x, eta=-1.0, l1=0.0)
+            assert np.array_equal(host(res[s:s + 4096]).view(np.uint32), x.view(np.uint32)), (b, s)
+            for w in (0, M - 1):                                      # the message itself, against the oracle's quantizer
+                win = np.concatenate([host(v[s:s + 4096]), np.array([amax_ref], dtype=np.float32)])
+                u = np.concatenate([oracle.uniform_range(7, 2, w, oracle.TAG_GRAD, s, 4096), np.array([0.5], dtype=np.float32)])
+                want, _, _ = oracle.quantize_given_uniforms(win, b, u)
+                assert np.array_equal(codes[w], want[:4096]), (b, s, w)
+        del packed, res
