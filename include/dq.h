@@ -13,7 +13,10 @@
  *    The dq_problem struct itself lives in host memory and holds device pointers.
  *  - The caller owns every buffer.  The library allocates nothing, frees
  *    nothing, and keeps no state between calls except a thread-local record of
- *    the last HIP error (dq_last_device_error).
+ *    the last HIP error (dq_last_device_error) and the fact that a kernel's
+ *    launch attribute (its on-chip memory limit) has been raised, which happens
+ *    once per process on first use and is safe from concurrent threads.  No
+ *    environment variable is read.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls only enqueue work and return; results, including scalars (delta,
  *    norms, counts, status), land in device memory.  The caller synchronises.
@@ -270,10 +273,28 @@ int32_t dq_master_step_each(const uint32_t *packed, int64_t ld_words, const floa
  * (theta_s * mu for Alg. 3).  out: device double[2].  b in [2,16].  Diagnostic, one block. */
 int32_t dq_mu_terms(const float *x, const float *x_snap, int64_t d, int32_t b, double *out, void *stream);
 
+/* Parameters of epoch s = 1, 2, ... of Alg. 3 as Section 5.1 sets them: theta_s = 2/(s+2), eta_s = lr/theta_s,
+ * both in float32.  theta_out, eta_out: HOST pointers.  s < 1: DQ_ERR_INVALID_ARG. */
+int32_t dq_acc_params(float lr, int64_t s, float *theta_out /*host*/, float *eta_out /*host*/);
+
 /* Start of an epoch of Alg. 3:  x_out = x_snap + theta*(y - x_snap)  (= theta*y + (1-theta)*x_snap). */
 int32_t dq_acc_mix(const float *y, const float *x_snap, float theta, int64_t d, float *x_out, void *stream);
 /* End of an epoch of Alg. 3:  x_snap_out = xsum / m. */
 int32_t dq_acc_snapshot(const float *xsum, int64_t m, int64_t d, float *x_snap_out, void *stream);
+
+/* ---- message sizes ---------------------------------------------------------------- */
+
+/* Bits on the wire of one message (host arithmetic, nothing is enqueued); negative = DQ_ERR_INVALID_ARG.
+ * DQ_MSG_DENSE : Section 3.1, a vector of d coordinates at b bits each plus its 32-bit scale, 32 + b*d;
+ *                b == 32 (not quantized): 32*d.  nnz is ignored.
+ * DQ_MSG_FLAG  : Section 4.1, the model equals the snapshot and the master sends one flag bit: 1.
+ * DQ_MSG_SPARSE: Section 4.2, the scale plus ceil(log2 d) position bits and b value bits per nonzero code,
+ *                32 + nnz*(ceil(log2 d) + b); b == 32: nnz*(ceil(log2 d) + 32) (no scale).  0 <= nnz <= d.
+ * b in [2,16] or 32. */
+#define DQ_MSG_DENSE   0
+#define DQ_MSG_FLAG    1
+#define DQ_MSG_SPARSE  2
+int64_t dq_message_bits(int32_t kind, int64_t d, int32_t b, int64_t nnz);
 
 /* ---- inner loop ------------------------------------------------------------------ */
 
@@ -330,8 +351,10 @@ typedef struct dq_run_state {
  * first round of an epoch whose start equals the snapshot) and the master side (dq_master_step with
  * the mean over the M workers, or dq_master_step_each; model re-quantized for the next round).  Random streams use
  * iter = epoch*m + t.  eta, theta: step size and momentum weight of this epoch (theta unused by
- * Alg. 1/2).  The epoch prologue (dq_full_grad, dq_acc_mix / copy) and epilogue stay with the
- * caller.  worker_events (host array, nullable): 2*rounds hipEvent_t handles created by the caller; for
+ * Alg. 1/2; for Alg. 3 they are dq_acc_params(lr, epoch + 1, ...)).  The epoch prologue (dq_full_grad,
+ * dq_acc_mix / copy) and epilogue stay with the caller.  Everything is validated before the first launch
+ * (null or misaligned state pointers, a workspace smaller than dq_workspace_bytes(DQ_OP_VR_GRAD, prob, M, B),
+ * which covers every worker group of a delayed run).  worker_events (host array, nullable): 2*rounds hipEvent_t handles created by the caller; for
  * round k the pair [2k], [2k+1] receives the start and the end time of the kernel of the worker step
  * that streams the feature rows (its first kernel; for CSR its only one; with tau > 0 the one of the
  * first worker group): they are the start and stop events of that launch (hipExtLaunchKernel), so

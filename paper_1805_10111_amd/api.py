@@ -85,6 +85,8 @@ _SIGS = {
                               _i32, _u64, _u32, _vp, _vp, _vp, _vp, _vp]),
     "dq_master_step_each": (_i32, [_vp, _i64, _vp, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _i64,
                                    _i32, _u64, _u32, _vp, _vp, _vp, _vp, _vp]),
+    "dq_acc_params": (_i32, [_f32, _i64, _vp, _vp]),
+    "dq_message_bits": (_i64, [_i32, _i64, _i32, _i64]),
     "dq_acc_mix": (_i32, [_vp, _vp, _f32, _i64, _vp, _vp]),
     "dq_acc_snapshot": (_i32, [_vp, _i64, _i64, _vp, _vp]),
     "dq_sparse_stream_words": (_i64, [_i64, _i32]),
@@ -334,6 +336,23 @@ def dq_master_step_each(packed, delta, M, b, g_snap, x, y, x_snap, xsum, eta, th
         _ptr(absmax_x_out, torch.float32, "absmax_x_out"), _ptr(status, torch.int32, "status"), _stream()))
 
 
+def dq_acc_params(lr: float, s: int):
+    """(theta_s, eta_s) of epoch s >= 1 of Alg. 3, as float32 values."""
+    theta, eta = C.c_float(), C.c_float()
+    _check("dq_acc_params", _lib.dq_acc_params(lr, s, C.byref(theta), C.byref(eta)))
+    return theta.value, eta.value
+
+
+MSG_DENSE, MSG_FLAG, MSG_SPARSE = 0, 1, 2
+
+
+def dq_message_bits(kind: int, d: int, b: int, nnz: int = 0) -> int:
+    bits = int(_lib.dq_message_bits(kind, d, b, nnz))
+    if bits < 0:
+        raise DqError("dq_message_bits", bits)
+    return bits
+
+
 def dq_acc_mix(y, x_snap, theta, x_out) -> None:
     _check("dq_acc_mix", _lib.dq_acc_mix(_ptr(y, torch.float32, "y"), _ptr(x_snap, torch.float32, "x_snap"), theta,
                                          y.numel(), _ptr(x_out, torch.float32, "x_out"), _stream()))
@@ -386,5 +405,5 @@ __all__ = [
     "dq_version", "dq_last_device_error", "dq_workspace_bytes", "dq_workspace_init", "new_workspace", "dq_absmax", "dq_quantize", "dq_dequantize",
     "dq_pack", "dq_unpack", "dq_quantize_pack", "dq_unpack_dequant_sum", "dq_sample_indices", "dq_full_grad",
     "dq_vr_grad", "dq_sparsify", "dq_worker_step", "dq_master_step", "dq_master_step_each", "dq_acc_mix", "dq_acc_snapshot",
-    "dq_run_rounds", "dq_mu_terms", "dq_sparse_stream_words", "dq_sparse_encode", "dq_sparse_decode", "RunConfig", "RunState", "ALGO",
+    "dq_run_rounds", "dq_mu_terms", "dq_acc_params", "dq_message_bits", "MSG_DENSE", "MSG_FLAG", "MSG_SPARSE", "dq_sparse_stream_words", "dq_sparse_encode", "dq_sparse_decode", "RunConfig", "RunState", "ALGO",
 ]

@@ -18,6 +18,8 @@
 //   4. the tail of the worker step (sparsify, scale, quantize, pack) runs from LDS.
 // The full gradient uses the same block procedure over many blocks, each leaving a partial
 // d-vector that a second kernel adds up in a fixed order.
+#include <mutex>
+
 #include <hip/hip_ext.h>
 
 #include "dq_common.h"
@@ -548,13 +550,13 @@ int64_t csr_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64
 
 // Kernels that use more than 64 KB of dynamic LDS must be told so once (the limit is raised to the budget).
 template <typename K>
-static int allow_big_lds(K kernel, bool &done)
+static int allow_big_lds(K kernel, std::once_flag &once, hipError_t &once_rc)
 {
-    if (!done) {
-        DQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(kLdsBudget - kCsrFixedLds)));
-        done = true;
-    }
+    std::call_once(once, [&] {
+        once_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      static_cast<int>(kLdsBudget - kCsrFixedLds));
+    });
+    DQ_HIP_TRY(once_rc);
     return DQ_OK;
 }
 
@@ -570,8 +572,9 @@ int csr_full_grad(const dq_problem *prob, const float *x, float *g_out, float *z
     float *partial = static_cast<float *>(ws);
     double *loss_partial = reinterpret_cast<double *>(partial + static_cast<int64_t>(P) * ldp);
     const size_t lds = static_cast<size_t>(plan.win) * 4 + static_cast<size_t>(plan.cap) * 8;
-    static bool attr_done = false;
-    int rc = allow_big_lds(csr_full_partial_kernel, attr_done);
+    static std::once_flag attr_once;
+    static hipError_t attr_rc = hipSuccess;
+    int rc = allow_big_lds(csr_full_partial_kernel, attr_once, attr_rc);
     if (rc != DQ_OK) return rc;
     const CsrView A{prob->indptr, prob->indices, prob->values, prob->y, n, d};
     csr_full_partial_kernel<<<dim3(P), dim3(kCsrThreads), lds, st>>>(A, x, z_out, partial, ldp, loss_partial, plan.cap, plan.win);
@@ -601,8 +604,9 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     k.cap = plan.cap; k.win = plan.win;
     k.alpha_ws = plan.nwin > 1 ? static_cast<float *>(a.ws) : nullptr; k.ld_ws = pad4(d);
     const size_t lds = static_cast<size_t>(plan.win) * 4 + static_cast<size_t>(plan.cap) * 8;
-    static bool attr_done = false;
-    int rc = allow_big_lds(csr_worker_kernel, attr_done);
+    static std::once_flag attr_once;
+    static hipError_t attr_rc = hipSuccess;
+    int rc = allow_big_lds(csr_worker_kernel, attr_once, attr_rc);
     if (rc != DQ_OK) return rc;
     // Few workers leave most compute units idle while each block spends a third of its time on the Philox rounds of
     // the final quantization: then several identical blocks per worker share that part (not when the nonzero count is

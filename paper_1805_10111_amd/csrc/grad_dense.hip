@@ -16,7 +16,8 @@
 // the tail (the kernel boundary is what makes the partial sums visible across the
 // chip's L2 slices; a per-block device-scope fence was measured to cost far more).
 // Either way the summation order is fixed, so results are run-to-run deterministic.
-#include <cstdlib>
+#include <algorithm>
+#include <mutex>
 
 #include <hip/hip_ext.h>
 
@@ -667,12 +668,8 @@ int64_t dense_vr_splits(int64_t M, int64_t B, int64_t d)
     // (two per compute unit) stream rows, each owning at least 4 of them.  Rows wider than 1024 floats
     // are streamed with two row buffers per block (see dense_worker): one block per compute unit
     // then, and a whole number of batch pairs per block.
-    static const int64_t forced = [] {
-        const char *e = getenv("DQ_VR_BLOCKS");
-        return e ? atoll(e) : 0ll;
-    }();
     const bool two_buffers = dense_nc(d) >= 2;
-    const int64_t target = forced > 0 ? forced : two_buffers ? 256 : 512;
+    const int64_t target = two_buffers ? 256 : 512;
     if (B <= 32) return 1;
     int64_t P = ceil_div(target, M);
     const int64_t by_rows = ceil_div(B, 4);
@@ -702,7 +699,11 @@ int64_t dense_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int
         const int64_t P = dense_full_splits(prob->n);
         return P * ldp * 4 + P * 8;
     }
-    return M * dense_vr_splits(M, B, prob->d) * ldp * 4;
+    // dq_run_rounds with a bounded delay runs the worker step on contiguous groups of the M workers with this same
+    // workspace, and a smaller group may be split over more blocks per worker: the size covers every group size
+    int64_t rows = 0;
+    for (int64_t g = 1; g <= M; ++g) rows = std::max(rows, g * dense_vr_splits(g, B, prob->d));
+    return rows * ldp * 4;
 }
 
 int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float *z_out, double *obj_out, void *ws,
@@ -797,11 +798,14 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     DQ_LAUNCH_CHECK();
     if (k.P > 1 || nc > 4) {
         const size_t lds = static_cast<size_t>(d) * sizeof(float);
-        static bool big_lds_allowed = false;             // more than 64 KB of dynamic LDS has to be requested once
-        if (lds > 48 * 1024 && !big_lds_allowed) {
-            DQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(vr_dense_finish_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4));
-            big_lds_allowed = true;
+        if (lds > 48 * 1024) {                            // more than 64 KB of dynamic LDS has to be requested once
+            static std::once_flag once;
+            static hipError_t once_rc = hipSuccess;
+            std::call_once(once, [] {
+                once_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(vr_dense_finish_kernel),
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4);
+            });
+            DQ_HIP_TRY(once_rc);
         }
         // with few workers, identical blocks share the final quantization of a worker (see worker_tail_from_lds)
         // (measured at d = 4096, M = 32: two blocks per worker 0.65 us faster than one, four or eight no better)

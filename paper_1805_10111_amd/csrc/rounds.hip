@@ -13,9 +13,13 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
     if (!prob || !cfg || !st || epoch < 0 || t0 < 0 || rounds < 0 || cfg->m <= 0 || t0 + rounds > cfg->m)
         return DQ_ERR_INVALID_ARG;
     if (cfg->algo < DQ_ALGO_ASYLPG || cfg->algo > DQ_ALGO_ACC) return DQ_ERR_INVALID_ARG;
-    if (!st->packed || !st->delta || !st->xq || !st->x || !st->x_snap || !st->g_snap || !st->absmax_x ||
-        !dq::aligned16(st->packed))
+    if (!st->packed || !st->delta || !st->xq || !st->delta_x || !st->x || !st->x_snap || !st->g_snap || !st->absmax_x ||
+        !dq::aligned16(st->packed) || !dq::aligned16(st->xq))
         return DQ_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(st->status) & 3u) || (reinterpret_cast<uintptr_t>(st->nnz) & 3u) ||
+        (reinterpret_cast<uintptr_t>(st->delta) & 3u) || (reinterpret_cast<uintptr_t>(st->delta_x) & 3u))
+        return DQ_ERR_INVALID_ARG;
+    if (cfg->M <= 0 || cfg->B <= 0) return DQ_ERR_INVALID_ARG;
     if (cfg->b != 2 && cfg->b != 4 && cfg->b != 8 && cfg->b != 32) return DQ_ERR_UNSUPPORTED;
     {
         const int64_t row_words = cfg->b == 32 ? prob->d : dq::packed_words(prob->d, cfg->b);
@@ -28,6 +32,12 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
     const int64_t slots = cfg->tau + 1;
     const int64_t xq_words = cfg->b_x == 32 ? prob->d : dq::packed_words(prob->d, cfg->b_x);
     if (slots > 1 && (st->xq_stride_words < xq_words || st->xq_stride_words % 4 != 0)) return DQ_ERR_INVALID_ARG;
+    {
+        // the workspace is checked once, for every worker group of the call, before anything is enqueued
+        const int64_t need = dq_workspace_bytes(DQ_OP_VR_GRAD, prob, cfg->M, cfg->B);
+        if (need < 0) return static_cast<int32_t>(need);
+        if (need > 0 && (!st->ws || st->ws_bytes < need)) return DQ_ERR_WORKSPACE;
+    }
     const float scale = 1.0f / static_cast<float>(cfg->M);
     // the model equals the snapshot bit for bit at the first round of an epoch of Alg. 1/2 and of the
     // first epoch of Alg. 3: flag-bit case of Section 4.1
@@ -90,4 +100,32 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
         if (rc != DQ_OK) return rc;
     }
     return DQ_OK;
+}
+
+// Section 5.1 (parameters of Alg. 3 as used in the experiments): theta_s = 2/(s+2), eta_s = lr/theta_s, in float32.
+extern "C" int32_t dq_acc_params(float lr, int64_t s, float *theta_out, float *eta_out)
+{
+    if (s < 1 || !theta_out || !eta_out) return DQ_ERR_INVALID_ARG;
+    const float theta = static_cast<float>(2.0 / static_cast<double>(s + 2));
+    *theta_out = theta;
+    *eta_out = lr / theta;
+    return DQ_OK;
+}
+
+// Message sizes: Section 3.1 (32 + b*d bits for a quantized vector, 32*d unquantized), Section 4.1 (one flag bit
+// when the model equals the snapshot), Section 4.2 (scale + position and value per nonzero of a sparsified vector).
+extern "C" int64_t dq_message_bits(int32_t kind, int64_t d, int32_t b, int64_t nnz)
+{
+    if (d <= 0 || b < 2 || (b > 16 && b != 32)) return DQ_ERR_INVALID_ARG;
+    switch (kind) {
+    case DQ_MSG_DENSE: return b == 32 ? 32 * d : 32 + static_cast<int64_t>(b) * d;
+    case DQ_MSG_FLAG: return 1;
+    case DQ_MSG_SPARSE: {
+        if (nnz < 0 || nnz > d) return DQ_ERR_INVALID_ARG;
+        int pos = 0;
+        while ((1ll << pos) < d) ++pos;                       // ceil(log2 d) position bits
+        return (b == 32 ? 0 : 32) + nnz * (pos + b);
+    }
+    default: return DQ_ERR_INVALID_ARG;
+    }
 }

@@ -3,6 +3,8 @@
 // Encoder: packed dense codes -> entry stream (order-preserving compaction); decoder: the inverse.
 // One block of 1024 threads per worker; the stream (encoder) or the dense row (decoder) is
 // assembled in LDS with bitwise-OR atomics on disjoint bits (order-free, hence deterministic).
+#include <mutex>
+
 #include "dq_common.h"
 #include "elementwise.h"
 
@@ -119,14 +121,17 @@ __global__ __launch_bounds__(kWireThreads) void sparse_decode_kernel(
     for (int64_t w = threadIdx.x; w < row_words; w += kWireThreads) out[w] = sh_row[w];
 }
 
-template <typename K>
-static int allow_lds(K kernel, bool &done)
+template <auto kernel>
+static int allow_lds()
 {
-    if (!done) {
-        DQ_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(kWireLdsWords * 4)));
-        done = true;
-    }
+    // one flag and one result per kernel (every instantiation has its own): set once per process, safely from any thread
+    static std::once_flag once;
+    static hipError_t once_rc = hipSuccess;
+    std::call_once(once, [&] {
+        once_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      static_cast<int>(kWireLdsWords * 4));
+    });
+    DQ_HIP_TRY(once_rc);
     return DQ_OK;
 }
 
@@ -153,11 +158,10 @@ extern "C" int32_t dq_sparse_encode(const uint32_t *packed, int64_t ld_words, in
     const size_t lds = static_cast<size_t>(cap) * 4;
     const dim3 grid(static_cast<unsigned>(M)), block(kWireThreads);
     hipStream_t st = as_stream(stream);
-    static bool a8 = false, a4 = false, a2 = false;
     int rc;
-    if (b == 8) { if ((rc = allow_lds(sparse_encode_kernel<8>, a8)) != DQ_OK) return rc; sparse_encode_kernel<8><<<grid, block, lds, st>>>(packed, ld_words, row_words, d, pb, stream_out, ld_stream, cap, nnz_out); }
-    else if (b == 4) { if ((rc = allow_lds(sparse_encode_kernel<4>, a4)) != DQ_OK) return rc; sparse_encode_kernel<4><<<grid, block, lds, st>>>(packed, ld_words, row_words, d, pb, stream_out, ld_stream, cap, nnz_out); }
-    else { if ((rc = allow_lds(sparse_encode_kernel<2>, a2)) != DQ_OK) return rc; sparse_encode_kernel<2><<<grid, block, lds, st>>>(packed, ld_words, row_words, d, pb, stream_out, ld_stream, cap, nnz_out); }
+    if (b == 8) { if ((rc = allow_lds<sparse_encode_kernel<8>>()) != DQ_OK) return rc; sparse_encode_kernel<8><<<grid, block, lds, st>>>(packed, ld_words, row_words, d, pb, stream_out, ld_stream, cap, nnz_out); }
+    else if (b == 4) { if ((rc = allow_lds<sparse_encode_kernel<4>>()) != DQ_OK) return rc; sparse_encode_kernel<4><<<grid, block, lds, st>>>(packed, ld_words, row_words, d, pb, stream_out, ld_stream, cap, nnz_out); }
+    else { if ((rc = allow_lds<sparse_encode_kernel<2>>()) != DQ_OK) return rc; sparse_encode_kernel<2><<<grid, block, lds, st>>>(packed, ld_words, row_words, d, pb, stream_out, ld_stream, cap, nnz_out); }
     DQ_LAUNCH_CHECK();
     return DQ_OK;
 }
@@ -174,11 +178,10 @@ extern "C" int32_t dq_sparse_decode(const uint32_t *stream_in, int64_t ld_stream
     const size_t lds = static_cast<size_t>(row_words) * 4;
     const dim3 grid(static_cast<unsigned>(M)), block(kWireThreads);
     hipStream_t st = as_stream(stream);
-    static bool a8 = false, a4 = false, a2 = false;
     int rc;
-    if (b == 8) { if ((rc = allow_lds(sparse_decode_kernel<8>, a8)) != DQ_OK) return rc; sparse_decode_kernel<8><<<grid, block, lds, st>>>(stream_in, ld_stream, nnz, d, pb, packed_out, ld_words, row_words); }
-    else if (b == 4) { if ((rc = allow_lds(sparse_decode_kernel<4>, a4)) != DQ_OK) return rc; sparse_decode_kernel<4><<<grid, block, lds, st>>>(stream_in, ld_stream, nnz, d, pb, packed_out, ld_words, row_words); }
-    else { if ((rc = allow_lds(sparse_decode_kernel<2>, a2)) != DQ_OK) return rc; sparse_decode_kernel<2><<<grid, block, lds, st>>>(stream_in, ld_stream, nnz, d, pb, packed_out, ld_words, row_words); }
+    if (b == 8) { if ((rc = allow_lds<sparse_decode_kernel<8>>()) != DQ_OK) return rc; sparse_decode_kernel<8><<<grid, block, lds, st>>>(stream_in, ld_stream, nnz, d, pb, packed_out, ld_words, row_words); }
+    else if (b == 4) { if ((rc = allow_lds<sparse_decode_kernel<4>>()) != DQ_OK) return rc; sparse_decode_kernel<4><<<grid, block, lds, st>>>(stream_in, ld_stream, nnz, d, pb, packed_out, ld_words, row_words); }
+    else { if ((rc = allow_lds<sparse_decode_kernel<2>>()) != DQ_OK) return rc; sparse_decode_kernel<2><<<grid, block, lds, st>>>(stream_in, ld_stream, nnz, d, pb, packed_out, ld_words, row_words); }
     DQ_LAUNCH_CHECK();
     return DQ_OK;
 }

@@ -7,7 +7,6 @@ proximal (or momentum) step.  ``it = epoch * m + t`` addresses the random stream
 """
 from __future__ import annotations
 
-import math
 from dataclasses import dataclass, field
 from typing import List, Optional
 
@@ -82,10 +81,7 @@ class DoubleQuantTrainer:
         """Epoch start of Alg. 1 / Alg. 3 and the full gradient at the snapshot."""
         e = self.epoch_index
         if self.algo == "acc":
-            s = e + 1
-            self.theta = 2.0 / (s + 2)                                  # Section 5.1: theta_s = 2/(s+2)
-            self.eta = float(torch.tensor(self.lr, dtype=torch.float32) /
-                             torch.tensor(self.theta, dtype=torch.float32))   # eta_s = lr/theta_s in float32
+            self.theta, self.eta = dq.dq_acc_params(self.lr, e + 1)        # Section 5.1: theta_s, eta_s
             dq.dq_acc_mix(self.y, self.x_snap, self.theta, self.x)
             self.xsum.zero_()
         else:
@@ -139,15 +135,13 @@ class DoubleQuantTrainer:
         d, M, m = self.prob.d, self.M, self.m
         self.log.objectives.append(float(self.obj.item()))
         self.log.rounds += m
-        model_bits = 32 * d if self.b_x == 32 else 32 + self.b_x * d
         for flag in flags:
-            self.log.bits_down += 1 if flag else model_bits
+            self.log.bits_down += dq.dq_message_bits(dq.MSG_FLAG if flag else dq.MSG_DENSE, d, self.b_x)
         if self.algo == "sparse":
-            nz = int(self.nnz.sum().item())
-            header = 0 if self.b == 32 else 32
-            self.log.bits_up += header * m * M + nz * (math.ceil(math.log2(d)) + self.b)
+            self.log.bits_up += sum(dq.dq_message_bits(dq.MSG_SPARSE, d, self.b, nz)
+                                    for nz in self.nnz.flatten().tolist())
         else:
-            self.log.bits_up += m * M * (32 * d if self.b == 32 else 32 + self.b * d)
+            self.log.bits_up += m * M * dq.dq_message_bits(dq.MSG_DENSE, d, self.b)
 
     def run(self, S: int) -> RunLog:
         for _ in range(S):

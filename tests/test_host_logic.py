@@ -39,7 +39,24 @@ def lib():
     L.dq_sample_indices.argtypes = [i64, i64, i64, u64, u32, u32, v, v]
     L.dq_worker_step.argtypes = [v, v, i64, i64, v, v, i32, i32, v, v, i32, i32, u64, u32, u32, v, i64, v, v, v, i64, v,
                                  v, i64, v]
+    L.dq_run_rounds.argtypes = [v, v, v, i64, i64, i64, f32, f32, v, v]
+    L.dq_acc_params.argtypes = [f32, i64, v, v]
+    L.dq_message_bits.restype = C.c_int64
+    L.dq_message_bits.argtypes = [i32, i64, i32, i64]
     return L
+
+
+class RunConfig(C.Structure):
+    _fields_ = [("algo", C.c_int32), ("M", C.c_int64), ("B", C.c_int64), ("b_x", C.c_int32), ("b", C.c_int32),
+                ("m", C.c_int64), ("seed", C.c_uint64), ("tau", C.c_int32), ("each", C.c_int32)]
+
+
+class RunState(C.Structure):
+    _fields_ = [("x", C.c_void_p), ("x_snap", C.c_void_p), ("y", C.c_void_p), ("xsum", C.c_void_p),
+                ("g_snap", C.c_void_p), ("z_snap", C.c_void_p), ("xq", C.c_void_p), ("delta_x", C.c_void_p),
+                ("absmax_x", C.c_void_p), ("packed", C.c_void_p), ("ld_words", C.c_int64), ("delta", C.c_void_p),
+                ("nnz", C.c_void_p), ("status", C.c_void_p), ("ws", C.c_void_p), ("ws_bytes", C.c_int64),
+                ("xq_stride_words", C.c_int64), ("wire", C.c_void_p), ("ld_wire", C.c_int64), ("wire_nnz", C.c_void_p)]
 
 
 def dense(n=200000, d=4096, lda=None):
@@ -104,7 +121,12 @@ def test_workspace_sizes(lib):
     vr = lib.dq_workspace_bytes(2, C.byref(p), 32, 256)
     assert full % 16 == 0 and vr % 16 == 0
     assert full >= 512 * 4096 * 4                      # up to 512 partial d-vectors
-    assert vr == 32 * 8 * 4096 * 4                     # M * P * d floats with P = 256/M blocks per worker at d = 4096
+    assert vr >= 32 * 8 * 4096 * 4                     # M * P * d floats with P = 256/M blocks per worker at d = 4096
+    # ... and no less than any smaller group of the workers needs (a delayed run steps the groups with this workspace)
+    assert all(lib.dq_workspace_bytes(2, C.byref(p), g, 256) <= vr for g in range(1, 33))
+    big = dense(d=4096)
+    assert all(lib.dq_workspace_bytes(2, C.byref(big), g, 256) <= lib.dq_workspace_bytes(2, C.byref(big), 256, 256)
+               for g in (1, 2, 85, 86, 128, 255))
     small = dense(n=2000, d=1000)
     assert lib.dq_workspace_bytes(2, C.byref(small), 4, 16) == 4 * 1 * 1000 * 4       # small batch: one block per worker
     assert lib.dq_workspace_bytes(2, C.byref(csr()), 8, 32) == 8 * 20960 * 4 + 8 * 8 * 8   # a row per worker + slice results
@@ -112,6 +134,47 @@ def test_workspace_sizes(lib):
     assert lib.dq_workspace_bytes(3, C.byref(p), 1, 1) == INVALID
     assert lib.dq_workspace_bytes(2, C.byref(p), 0, 256) == INVALID
     assert lib.dq_workspace_bytes(1, None, 0, 0) == INVALID
+
+
+def test_run_rounds_rejects_before_launching(lib):
+    """Every rejected call returns before anything is enqueued (the pointers here are never dereferenced)."""
+    p = dense()
+    ws_need = lib.dq_workspace_bytes(2, C.byref(p), 32, 256)
+
+    def call(tau=0, **over):
+        cfg = RunConfig(algo=2, M=32, B=256, b_x=8, b=8, m=25, seed=0, tau=tau, each=0)
+        st = RunState(x=P, x_snap=P, y=P, xsum=P, g_snap=P, z_snap=None, xq=P, delta_x=P, absmax_x=P, packed=P,
+                      ld_words=1024, delta=P, nnz=None, status=None, ws=P, ws_bytes=ws_need, xq_stride_words=1024)
+        for k, val in over.items():
+            setattr(st, k, val)
+        return lib.dq_run_rounds(C.byref(p), C.byref(cfg), C.byref(st), 0, 0, 1, 0.1, 0.5, None, None)
+    assert call(delta_x=None) == INVALID                    # the scale of the model message has nowhere to go
+    assert call(tau=2, delta_x=None) == INVALID             # (with a delay, slot arithmetic on a null base is not a pointer)
+    assert call(xq=None) == INVALID and call(packed=None) == INVALID and call(y=None) == INVALID
+    assert call(status=P + 2) == INVALID and call(nnz=P + 1) == INVALID and call(xq=P + 4) == INVALID
+    assert call(ws=None) == WORKSPACE and call(ws_bytes=ws_need - 16) == WORKSPACE
+    assert call(tau=2, ws_bytes=32 * 8 * 4096 * 4 - 16) == WORKSPACE     # too small for a group: known up front
+    assert call(tau=32) == INVALID
+
+
+def test_acc_params_and_message_bits(lib):
+    import numpy as np
+    th, et = C.c_float(), C.c_float()
+    for s in (1, 2, 3, 10):
+        assert lib.dq_acc_params(0.1, s, C.byref(th), C.byref(et)) == OK
+        theta = np.float32(2.0 / (s + 2))                          # Section 5.1
+        assert th.value == float(theta) and et.value == float(np.float32(0.1) / theta)
+    assert lib.dq_acc_params(0.1, 0, C.byref(th), C.byref(et)) == INVALID
+    assert lib.dq_acc_params(0.1, 1, None, C.byref(et)) == INVALID
+    bits = lib.dq_message_bits
+    assert bits(0, 1000, 8, 0) == 32 + 8 * 1000 and bits(0, 1000, 32, 0) == 32 * 1000        # Section 3.1
+    assert bits(0, 20958, 11, 0) == 32 + 11 * 20958
+    assert bits(1, 1000, 8, 0) == 1                                                        # Section 4.1
+    assert bits(2, 20958, 4, 100) == 32 + 100 * (15 + 4)                                   # Section 4.2: ceil(log2 20958) = 15
+    assert bits(2, 4096, 8, 7) == 32 + 7 * (12 + 8) and bits(2, 4097, 8, 7) == 32 + 7 * (13 + 8)
+    assert bits(2, 1000, 32, 5) == 5 * (10 + 32)
+    assert bits(2, 1000, 4, 1001) == INVALID and bits(3, 1000, 4, 0) == INVALID and bits(0, 1000, 1, 0) == INVALID
+    assert bits(0, 0, 8, 0) == INVALID and bits(0, 1000, 17, 0) == INVALID
 
 
 def test_bench_refuses_more_than_one_gpu():
