@@ -231,6 +231,22 @@ int32_t dq_worker_step(const dq_problem *prob /*host*/, const int32_t *idx, int6
                        float *alpha_out, int64_t ld, uint32_t *status,
                        void *ws, int64_t ws_bytes, void *stream);
 
+/* dq_worker_step for callers that cannot allocate device memory or hand over a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without ws / ws_bytes, same
+ * results bit for bit.  The partial sums and per-worker rows that dq_worker_step passes through `ws` live in a
+ * workspace of DQ_STATIC_WS_BYTES bytes built into the library, one copy per GPU, held until the process ends;
+ * nothing is allocated or freed by the call.  A problem whose dq_workspace_bytes(DQ_OP_VR_GRAD, prob, M, B) exceeds
+ * DQ_STATIC_WS_BYTES returns DQ_ERR_WORKSPACE and enqueues nothing.  All calls on one GPU share that workspace:
+ * calls that may overlap on the GPU (different streams without an ordering between them) race; calls on one
+ * stream, or otherwise ordered, are safe, and no call depends on what an earlier one left there. */
+#define DQ_STATIC_WS_BYTES  (8ll << 20)
+int32_t dq_worker_step_static(const dq_problem *prob /*host*/, const int32_t *idx, int64_t M, int64_t B,
+                              const uint32_t *xq_packed, const float *delta_x, int32_t b_x,
+                              int32_t model_is_snapshot, const float *x_snap, const float *z_snap,
+                              int32_t sparsify, int32_t b, uint64_t seed, uint32_t iter, uint32_t worker0,
+                              uint32_t *packed_out, int64_t ld_words, float *delta_out, int32_t *nnz_out,
+                              float *alpha_out, int64_t ld, uint32_t *status, void *stream);
+
 /* ---- master --------------------------------------------------------------------- */
 
 /* Master step for one synchronous round of M workers (Alg. 1, master (ii) and (i);

@@ -81,6 +81,8 @@ _SIGS = {
     "dq_sparsify": (_i32, [_vp, _i64, _i64, _i64, _vp, _u64, _u32, _u32, _vp, _i64, _vp, _vp, _vp]),
     "dq_worker_step": (_i32, [_vp, _vp, _i64, _i64, _vp, _vp, _i32, _i32, _vp, _vp, _i32, _i32, _u64, _u32, _u32,
                               _vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _i64, _vp]),
+    "dq_worker_step_static": (_i32, [_vp, _vp, _i64, _i64, _vp, _vp, _i32, _i32, _vp, _vp, _i32, _i32, _u64, _u32, _u32,
+                                     _vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp]),
     "dq_master_step": (_i32, [_vp, _i64, _vp, _i64, _i32, _f32, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _i64,
                               _i32, _u64, _u32, _vp, _vp, _vp, _vp, _vp]),
     "dq_master_step_each": (_i32, [_vp, _i64, _vp, _i64, _i32, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _f32, _i64,
@@ -313,6 +315,22 @@ def dq_worker_step(prob: DeviceProblem, idx, M, B, xq_packed, delta_x, b_x, mode
         0 if alpha_out is None else _row_stride(alpha_out), _ptr(status, torch.int32, "status"), wp, wb, _stream()))
 
 
+STATIC_WS_BYTES = 8 << 20
+
+
+def dq_worker_step_static(prob: DeviceProblem, idx, M, B, xq_packed, delta_x, b_x, model_is_snapshot, x_snap, z_snap,
+                          sparsify, b, seed, it, worker0, packed_out, delta_out, nnz_out=None, alpha_out=None,
+                          status=None) -> None:
+    """dq_worker_step on the library's built-in workspace (the call allocates nothing)."""
+    _check("dq_worker_step_static", _lib.dq_worker_step_static(
+        prob.ptr, _ptr(idx, torch.int32, "idx"), M, B, _ptr(xq_packed, None, "xq_packed"),
+        _ptr(delta_x, torch.float32, "delta_x"), b_x, int(model_is_snapshot), _ptr(x_snap, torch.float32, "x_snap"),
+        _ptr(z_snap, torch.float32, "z_snap"), int(sparsify), b, seed, it, worker0,
+        _ptr(packed_out, torch.int32, "packed_out"), _row_stride(packed_out), _ptr(delta_out, torch.float32, "delta_out"),
+        _ptr(nnz_out, torch.int32, "nnz_out"), _ptr(alpha_out, torch.float32, "alpha_out"),
+        0 if alpha_out is None else _row_stride(alpha_out), _ptr(status, torch.int32, "status"), _stream()))
+
+
 # ------------------------------------------------------------------ master
 def dq_master_step(packed, delta, M, b, scale, g_snap, x, y, x_snap, xsum, eta, theta, l1, b_x, seed, it,
                    xq_packed_out, delta_x_out, absmax_x_out, status=None) -> None:
@@ -404,6 +422,6 @@ __all__ = [
     "TAG_GRAD", "TAG_MODEL", "TAG_SPARSIFY", "TAG_SAMPLE", "MASTER_ID", "OP_FULL_GRAD", "OP_VR_GRAD",
     "dq_version", "dq_last_device_error", "dq_workspace_bytes", "dq_workspace_init", "new_workspace", "dq_absmax", "dq_quantize", "dq_dequantize",
     "dq_pack", "dq_unpack", "dq_quantize_pack", "dq_unpack_dequant_sum", "dq_sample_indices", "dq_full_grad",
-    "dq_vr_grad", "dq_sparsify", "dq_worker_step", "dq_master_step", "dq_master_step_each", "dq_acc_mix", "dq_acc_snapshot",
+    "dq_vr_grad", "dq_sparsify", "dq_worker_step", "dq_worker_step_static", "STATIC_WS_BYTES", "dq_master_step", "dq_master_step_each", "dq_acc_mix", "dq_acc_snapshot",
     "dq_run_rounds", "dq_mu_terms", "dq_acc_params", "dq_message_bits", "MSG_DENSE", "MSG_FLAG", "MSG_SPARSE", "dq_sparse_stream_words", "dq_sparse_encode", "dq_sparse_decode", "RunConfig", "RunState", "ALGO",
 ]

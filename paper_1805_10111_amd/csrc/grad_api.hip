@@ -1,8 +1,36 @@
 // C ABI of the gradient entry points: argument validation and dispatch on the feature layout.
+#include <mutex>
+
 #include "dq_common.h"
 #include "grad_launch.h"
 
 using namespace dq;
+
+// Workspace of dq_worker_step_static: one array per GPU inside the library's code object, alive until the process
+// ends.  In host code the array's name only stands for the symbol; its device address is asked for once per device
+// (hipGetSymbolAddress with that device current) and that pointer is what kernels receive.
+constexpr int64_t kStaticWsBytes = DQ_STATIC_WS_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticWsBytes];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+static int32_t static_workspace(void **out)
+{
+    int dev = 0;
+    DQ_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return DQ_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        DQ_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return DQ_ERR_DEVICE;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DQ_OK;
+}
 
 static inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 
@@ -107,4 +135,22 @@ extern "C" int32_t dq_worker_step(const dq_problem *prob, const int32_t *idx, in
     a.packed = packed_out; a.ld_words = ld_words; a.delta_out = delta_out; a.nnz_out = nnz_out; a.status = status;
     a.ws = ws; a.ws_bytes = ws_bytes;
     return worker_step_impl(prob, a, stream);
+}
+
+extern "C" int32_t dq_worker_step_static(const dq_problem *prob, const int32_t *idx, int64_t M, int64_t B,
+                                         const uint32_t *xq_packed, const float *delta_x, int32_t b_x,
+                                         int32_t model_is_snapshot, const float *x_snap, const float *z_snap,
+                                         int32_t sparsify, int32_t b, uint64_t seed, uint32_t iter, uint32_t worker0,
+                                         uint32_t *packed_out, int64_t ld_words, float *delta_out, int32_t *nnz_out,
+                                         float *alpha_out, int64_t ld, uint32_t *status, void *stream)
+{
+    const int64_t need = dq_workspace_bytes(DQ_OP_VR_GRAD, prob, M, B);
+    if (need < 0) return static_cast<int32_t>(need);
+    if (need > kStaticWsBytes) return DQ_ERR_WORKSPACE;          // beyond the built-in workspace: use dq_worker_step
+    void *ws = nullptr;
+    const int32_t rc = static_workspace(&ws);
+    if (rc != DQ_OK) return rc;
+    return dq_worker_step(prob, idx, M, B, xq_packed, delta_x, b_x, model_is_snapshot, x_snap, z_snap, sparsify, b, seed,
+                          iter, worker0, packed_out, ld_words, delta_out, nnz_out, alpha_out, ld, status, ws,
+                          kStaticWsBytes, stream);
 }

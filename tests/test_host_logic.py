@@ -177,6 +177,19 @@ def test_acc_params_and_message_bits(lib):
     assert bits(0, 0, 8, 0) == INVALID and bits(0, 1000, 17, 0) == INVALID
 
 
+def test_static_worker_step_rejects_what_does_not_fit(lib):
+    lib.dq_worker_step_static.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p, C.c_int32,
+                                          C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_uint64, C.c_uint32,
+                                          C.c_uint32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64,
+                                          C.c_void_p, C.c_void_p]
+    wide = dense(n=1000, d=16384)
+    assert lib.dq_workspace_bytes(2, C.byref(wide), 64, 256) > 8 << 20
+    call = lambda prob, M, B: lib.dq_worker_step_static(C.byref(prob), None, M, B, P, P, 8, 0, P, None, 0, 8, 0, 0, 0, P,
+                                                        4096, P, None, None, 0, None, None)
+    assert call(wide, 64, 256) == WORKSPACE                 # beyond the built-in workspace: nothing is enqueued
+    assert call(dense(), 0, 256) == INVALID
+
+
 def test_bench_refuses_more_than_one_gpu():
     import subprocess, sys
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
