@@ -32,17 +32,17 @@ constexpr int kRowThreads = 256;
 constexpr int kRowWaves = kRowThreads / kWave;
 constexpr int kMaxRowsPerBlock = 256;            // mini-batch rows a block may own (LDS metadata)
 
-// Thread's share of a row: float4 columns tid + 256*c, c < NC; zero past d.
+// Thread's share of a row: float4 columns tid + T*c, c < NC (T threads per block); zero past d.
 // STREAM: the row is read once and not again soon (the gathered rows of a mini-batch), so the load is
 // marked non-temporal; the contiguous sweep of the full gradient is faster without the mark (measured).
-// FULL: d equals 4 * kRowThreads * NC, every column of every thread is a whole float4 inside the row and the loads
+// FULL: d equals 4 * T * NC, every column of every thread is a whole float4 inside the row and the loads
 // carry no condition at all.
-template <int NC, bool STREAM = false, bool FULL = false>
+template <int NC, bool STREAM = false, bool FULL = false, int T = kRowThreads>
 __device__ __forceinline__ void load_cols(const float *__restrict__ row, int64_t d, float4 (&a)[NC])
 {
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-        const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
+        const int64_t col = 4ll * (threadIdx.x + T * c);
         if (FULL || col + 3 < d) {
             if constexpr (STREAM) {
                 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -93,24 +93,25 @@ __device__ __forceinline__ void axpy_cols(float coef, const float4 (&a)[NC], flo
     }
 }
 
-template <int NC>
+template <int NC, int T = kRowThreads>
 __device__ __forceinline__ void store_cols(float *__restrict__ dst, int64_t ldp, const float4 (&a)[NC])
 {
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-        const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
+        const int64_t col = 4ll * (threadIdx.x + T * c);
         if (col < ldp) *reinterpret_cast<float4 *>(dst + col) = a[c];       // ldp is a multiple of 4
     }
 }
 
-// Block-wide sums of R per-thread values: wave butterflies, then the 4 wave sums are
-// added in wave order by every thread.  `sh` holds 2 buffers of [kRowWaves][R] floats and
+// Block-wide sums of R per-thread values: wave butterflies, then the wave sums are
+// added in wave order by every thread.  `sh` holds 2 buffers of [T / 64][R] floats and
 // is used alternately, so one barrier per call is enough.
-template <int R>
+template <int R, int T = kRowThreads>
 __device__ __forceinline__ void block_sum_R(float (&v)[R], float *sh, int &buf)
 {
+    constexpr int kWaves = T / kWave;
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    float *mine = sh + buf * (kRowWaves * R);
+    float *mine = sh + buf * (kWaves * R);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const float s = wave_sum_f32(v[r]);
@@ -121,7 +122,7 @@ __device__ __forceinline__ void block_sum_R(float (&v)[R], float *sh, int &buf)
     for (int r = 0; r < R; ++r) {
         float s = mine[r];
 #pragma unroll
-        for (int w = 1; w < kRowWaves; ++w) s += mine[w * R + r];
+        for (int w = 1; w < kWaves; ++w) s += mine[w * R + r];
         v[r] = s;
     }
     buf ^= 1;
@@ -156,13 +157,13 @@ struct ModelCols {
     float4 xs[NC];
 };
 
-template <int NC, bool FULL>
+template <int NC, bool FULL, int T>
 __device__ __forceinline__ void request_model_cols(const VrDenseArgs &a, const ModelMsg &msg, ModelCols<NC> &mc)
 {
     const int64_t d = a.d;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-        const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
+        const int64_t col = 4ll * (threadIdx.x + T * c);
         mc.mq[c] = model_quad_request(msg, col, a.model_last_word);
         if constexpr (FULL) mc.xs[c] = *reinterpret_cast<const float4 *>(a.x_snap + col);
         else mc.xs[c] = load4_or_zero(a.x_snap, col, d);
@@ -171,13 +172,13 @@ __device__ __forceinline__ void request_model_cols(const VrDenseArgs &a, const M
 
 // dx = q - snapshot for the thread's columns (q: the dequantized model message); xs = the
 // snapshot itself when HAVE_Z is false (margins at the snapshot must then be recomputed).
-template <int NC, bool HAVE_Z>
+template <int NC, bool HAVE_Z, int T>
 __device__ __forceinline__ void model_minus_snapshot(const VrDenseArgs &a, const ModelMsg &msg, const ModelCols<NC> &mc,
                                                      float4 (&dx)[NC], float4 (&xs)[HAVE_Z ? 1 : NC])
 {
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-        const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
+        const int64_t col = 4ll * (threadIdx.x + T * c);
         float q[4];
         model_quad_values(msg, mc.mq[c], col, a.d, q);
         dx[c] = make_float4(q[0] - mc.xs[c].x, q[1] - mc.xs[c].y, q[2] - mc.xs[c].z, q[3] - mc.xs[c].w);
@@ -219,14 +220,14 @@ __device__ __forceinline__ void worker_outputs(const VrDenseArgs &a, int m, floa
 }
 
 // One block owned the whole mini-batch of worker m: alpha = acc + l2*(q - snapshot), then the outputs.
-template <int NC>
+template <int NC, int T>
 __device__ __forceinline__ void worker_finish(const VrDenseArgs &a, int m, const float4 (&acc)[NC], const float4 (&dx)[NC],
                                               float *sh_alpha, uint32_t *su, int *si, double *sd)
 {
     const int64_t d = a.d;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
-        const int64_t col = 4ll * (threadIdx.x + kRowThreads * c);
+        const int64_t col = 4ll * (threadIdx.x + T * c);
         const float v[4] = {acc[c].x + a.l2 * dx[c].x, acc[c].y + a.l2 * dx[c].y, acc[c].z + a.l2 * dx[c].z,
                             acc[c].w + a.l2 * dx[c].w};
 #pragma unroll
@@ -240,19 +241,20 @@ __device__ __forceinline__ void worker_finish(const VrDenseArgs &a, int m, const
     worker_outputs(a, m, sh_alpha, su, si, sd);
 }
 
-template <int NC, int R, bool HAVE_Z, bool FULL, bool DB = false>
-__global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs a)
+template <int NC, int R, bool HAVE_Z, bool FULL, bool DB = false, int T = kRowThreads>
+__global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
 {
-    __shared__ float sh_red[2 * kRowWaves * R * 2];
+    constexpr int kWaves = T / kWave;
+    __shared__ float sh_red[2 * kWaves * R * 2];
     __shared__ int sh_row[kMaxRowsPerBlock];
     __shared__ float sh_y[kMaxRowsPerBlock], sh_z[kMaxRowsPerBlock];
     // the in-kernel tail (one block owns the worker's whole mini-batch) exists for rows of up to 4096 floats;
     // wider rows always go through the partial sums and the second kernel
-    constexpr bool kOwnTail = NC <= 4;
-    __shared__ __align__(16) float sh_alpha[kOwnTail ? 4 * kRowThreads * NC : 4];
-    __shared__ uint32_t su[kRowWaves];
-    __shared__ int si[kRowWaves];
-    __shared__ double sd[kRowWaves];
+    constexpr bool kOwnTail = NC * T <= 1024;
+    __shared__ __align__(16) float sh_alpha[kOwnTail ? 4 * T * NC : 4];
+    __shared__ uint32_t su[kWaves];
+    __shared__ int si[kWaves];
+    __shared__ double sd[kWaves];
 
     // Workgroups go to the eight dies of the part in turn (linear workgroup number mod 8), and each die has its own
     // L2.  With a multiple of 8 workers the blocks of worker m all run on die m mod 8 -- the die that block m of
@@ -271,7 +273,7 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
     // ---- the thread's columns of the model message and of the snapshot are requested first: they depend on
     //      nothing and are back by the time the row numbers are
     ModelCols<NC> mc;
-    request_model_cols<NC, FULL>(a, msg, mc);
+    request_model_cols<NC, FULL, T>(a, msg, mc);
 
     // ---- rows of this block
     const int per = (a.B + a.P - 1) / a.P;
@@ -303,7 +305,7 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int i = rb + r < nrows ? sh_row[rb + r] : -1;
-            if (i >= 0) load_cols<NC, true, FULL>(a.X + static_cast<int64_t>(i) * a.lda, d, row[r]);
+            if (i >= 0) load_cols<NC, true, FULL, T>(a.X + static_cast<int64_t>(i) * a.lda, d, row[r]);
             else zero_cols<NC>(row[r]);
         }
     };
@@ -311,7 +313,7 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int i = __builtin_amdgcn_readfirstlane(sh_row[rb + r]);
-            load_cols<NC, true, FULL>(a.X + static_cast<int64_t>(i) * a.lda, d, row[r]);
+            load_cols<NC, true, FULL, T>(a.X + static_cast<int64_t>(i) * a.lda, d, row[r]);
         }
     };
     auto compute_batch = [&](int rb, const float4 (&row)[R][NC]) {
@@ -321,7 +323,7 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
             dots[r] = dot_cols<NC>(row[r], dx);
             if constexpr (!HAVE_Z) dots[R + r] = dot_cols<NC>(row[r], xs);
         }
-        block_sum_R<HAVE_Z ? R : 2 * R>(dots, sh_red, buf);
+        block_sum_R<HAVE_Z ? R : 2 * R, T>(dots, sh_red, buf);
         // lane r of every wave evaluates the coefficient of row rb + r once (exp, expm1 and the
         // division are the expensive part of a batch); the R results are then read back wave-uniformly
         const int lane = threadIdx.x & (kWave - 1);
@@ -354,7 +356,7 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
         sh_y[threadIdx.x] = i >= 0 ? a.y[i] : 1.0f;
         sh_z[threadIdx.x] = (i >= 0 && HAVE_Z) ? a.z_snap[i] : 0.0f;
     }
-    model_minus_snapshot<NC, HAVE_Z>(a, msg, mc, dx, xs);
+    model_minus_snapshot<NC, HAVE_Z, T>(a, msg, mc, dx, xs);
     zero_cols<NC>(acc);
     __syncthreads();
 
@@ -387,10 +389,10 @@ __global__ __launch_bounds__(kRowThreads) void vr_dense_kernel(const VrDenseArgs
     }
 
     if (a.P > 1 || !kOwnTail) {          // leave the partial sum for vr_dense_finish_kernel
-        store_cols<NC>(a.partial + (static_cast<int64_t>(m) * a.P + part) * a.ldp, a.ldp, acc);
+        store_cols<NC, T>(a.partial + (static_cast<int64_t>(m) * a.P + part) * a.ldp, a.ldp, acc);
         return;
     }
-    if constexpr (kOwnTail) worker_finish<NC>(a, m, acc, dx, sh_alpha, su, si, sd);
+    if constexpr (kOwnTail) worker_finish<NC, T>(a, m, acc, dx, sh_alpha, su, si, sd);
 }
 
 // Second stage when a worker's mini-batch was split over P > 1 blocks.  grid (M), 1024
@@ -746,17 +748,17 @@ static void launch_timed(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_
     else kernel<<<grid, block, lds, st>>>(k);
 }
 
-template <int NC, int R, bool DB = false>
+template <int NC, int R, bool DB = false, int T = kRowThreads>
 static void launch_vr(bool have_z, dim3 grid, hipStream_t st, const VrDenseArgs &k, hipEvent_t e0, hipEvent_t e1)
 {
-    const bool full = k.d == 4ll * kRowThreads * NC;       // every thread's columns are whole float4s of the row
-    const dim3 block(kRowThreads);
+    const bool full = k.d == 4ll * T * NC;       // every thread's columns are whole float4s of the row
+    const dim3 block(T);
     if (have_z) {
-        if (full) launch_timed(vr_dense_kernel<NC, R, true, true, DB>, grid, block, 0, st, e0, e1, k);
-        else launch_timed(vr_dense_kernel<NC, R, true, false, DB>, grid, block, 0, st, e0, e1, k);
+        if (full) launch_timed(vr_dense_kernel<NC, R, true, true, DB, T>, grid, block, 0, st, e0, e1, k);
+        else launch_timed(vr_dense_kernel<NC, R, true, false, DB, T>, grid, block, 0, st, e0, e1, k);
     } else {
-        if (full) launch_timed(vr_dense_kernel<NC, R, false, true, DB>, grid, block, 0, st, e0, e1, k);
-        else launch_timed(vr_dense_kernel<NC, R, false, false, DB>, grid, block, 0, st, e0, e1, k);
+        if (full) launch_timed(vr_dense_kernel<NC, R, false, true, DB, T>, grid, block, 0, st, e0, e1, k);
+        else launch_timed(vr_dense_kernel<NC, R, false, false, DB, T>, grid, block, 0, st, e0, e1, k);
     }
 }
 
@@ -791,7 +793,7 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     switch (nc) {
     case 1: launch_vr<1, 16>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
     case 2: launch_vr<2, 4, true>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
-    case 4: launch_vr<4, 2, true>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
+    case 4: launch_vr<2, 2, true, 512>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;   // 512 threads, 2 columns each
     case 8: launch_vr<8, 1, true>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
     default: launch_vr<16, 1, true>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
     }
