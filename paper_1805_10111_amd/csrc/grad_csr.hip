@@ -300,7 +300,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     if (a.zero_word && blockIdx.x == 0 && slice == 0 && threadIdx.x == 0) *a.zero_word = 0u;
     float *alpha_row = a.alpha_ws ? a.alpha_ws + static_cast<int64_t>(m) * a.ld_ws : nullptr;   // only with several windows
 
-    const float fB = static_cast<float>(a.B);
+    const float inv_B = 1.0f / static_cast<float>(a.B);      // the mean over the mini-batch, as one multiplication per row
     const bool have_z = a.z_snap != nullptr;
     // the model value and the snapshot at column c: the field of column c starts at bit c*b_x of the message and
     // may continue in the next word; both words and the snapshot value are requested without any condition
@@ -318,7 +318,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     auto coef_of = [&](int r, float dz, float zs) {
         if (meta.row[r] < 0) return 0.0f;
         if (have_z) zs = meta.z[r];
-        return vr_slope_diff(sh_y[r], zs, dz) / fB;
+        return vr_slope_diff(sh_y[r], zs, dz) * inv_B;
     };
     // the rows of one pass: which sample, where its entries start, how many, its label and cached margin
     struct RowInfo { int row; int64_t start; int len; float y, z; };

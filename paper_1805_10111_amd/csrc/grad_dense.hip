@@ -299,7 +299,7 @@ __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
     const bool plain = __syncthreads_and(row_ok) && nrows > 0 && nrows % R == 0;
 
     float4 dx[NC], xs[HAVE_Z ? 1 : NC], acc[NC];
-    const float fB = static_cast<float>(a.B);
+    const float inv_B = 1.0f / static_cast<float>(a.B);      // the mean over the mini-batch, as one multiplication per row
     int buf = 0;
     auto load_batch = [&](int rb, float4 (&row)[R][NC]) {
 #pragma unroll
@@ -336,7 +336,7 @@ __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
         float coef_l = 0.0f;
         if (lane < R && rb + lane < nrows && sh_row[rb + lane] >= 0) {
             if constexpr (HAVE_Z) zs = sh_z[rb + lane];
-            coef_l = vr_slope_diff(sh_y[rb + lane], zs, dz) / fB;
+            coef_l = vr_slope_diff(sh_y[rb + lane], zs, dz) * inv_B;
         }
 #pragma unroll
         for (int r = 0; r < R; ++r) {
