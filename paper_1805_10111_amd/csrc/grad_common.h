@@ -86,10 +86,11 @@ struct ModelQuad {
     uint32_t w[4];
 };
 
+template <bool MODEL8 = false>
 __device__ __forceinline__ ModelQuad model_quad_request(const ModelMsg &q, int64_t col, int64_t last_word)
 {
     ModelQuad r;
-    if (q.b_x == 8) {                      // (the width is the same for every thread) the quad is one word
+    if (MODEL8 || q.b_x == 8) {            // (the width is the same for every thread) the quad is one word
         r.w[0] = q.words[min(col >> 2, last_word)];
         r.w[1] = r.w[2] = r.w[3] = 0u;
         return r;
@@ -101,9 +102,10 @@ __device__ __forceinline__ ModelQuad model_quad_request(const ModelMsg &q, int64
 }
 
 // Values of coordinates col..col+3 from the requested words; coordinates at or past d read as 0.
+template <bool MODEL8 = false>
 __device__ __forceinline__ void model_quad_values(const ModelMsg &q, const ModelQuad &r, int64_t col, int64_t d, float (&v)[4])
 {
-    if (q.b_x == 8) {
+    if (MODEL8 || q.b_x == 8) {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
             v[e] = col + e < d ? q.delta_x * static_cast<float>(sext_field(r.w[0], 8u * e, 8u)) : 0.0f;

@@ -30,7 +30,7 @@ namespace dq {
 
 constexpr int kRowThreads = 256;
 constexpr int kRowWaves = kRowThreads / kWave;
-constexpr int kMaxRowsPerBlock = 256;            // mini-batch rows a block may own (LDS metadata)
+constexpr int kMaxRowsPerBlock = 64;             // mini-batch rows a block may own: lane j of a wavefront keeps row j
 
 // Thread's share of a row: float4 columns tid + T*c, c < NC (T threads per block); zero past d.
 // STREAM: the row is read once and not again soon (the gathered rows of a mini-batch), so the load is
@@ -147,6 +147,7 @@ struct VrDenseArgs {
     uint32_t *packed; int64_t ld_words, row_words;
     float *delta_out; int32_t *nnz_out; uint32_t *status;
     uint32_t *zero_word;             // nullable: set to 0 by one thread of the grid
+    int die_major;                   // grid is (8, P, M / 8) instead of (P, M): see vr_dense_kernel
 };
 
 // The thread's columns of the model message and of the snapshot, requested without waiting for anything (the
@@ -157,14 +158,14 @@ struct ModelCols {
     float4 xs[NC];
 };
 
-template <int NC, bool FULL, int T>
+template <int NC, bool FULL, int T, bool MODEL8>
 __device__ __forceinline__ void request_model_cols(const VrDenseArgs &a, const ModelMsg &msg, ModelCols<NC> &mc)
 {
     const int64_t d = a.d;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         const int64_t col = 4ll * (threadIdx.x + T * c);
-        mc.mq[c] = model_quad_request(msg, col, a.model_last_word);
+        mc.mq[c] = model_quad_request<MODEL8>(msg, col, a.model_last_word);
         if constexpr (FULL) mc.xs[c] = *reinterpret_cast<const float4 *>(a.x_snap + col);
         else mc.xs[c] = load4_or_zero(a.x_snap, col, d);
     }
@@ -172,7 +173,7 @@ __device__ __forceinline__ void request_model_cols(const VrDenseArgs &a, const M
 
 // dx = q - snapshot for the thread's columns (q: the dequantized model message); xs = the
 // snapshot itself when HAVE_Z is false (margins at the snapshot must then be recomputed).
-template <int NC, bool HAVE_Z, int T>
+template <int NC, bool HAVE_Z, int T, bool MODEL8>
 __device__ __forceinline__ void model_minus_snapshot(const VrDenseArgs &a, const ModelMsg &msg, const ModelCols<NC> &mc,
                                                      float4 (&dx)[NC], float4 (&xs)[HAVE_Z ? 1 : NC])
 {
@@ -180,7 +181,7 @@ __device__ __forceinline__ void model_minus_snapshot(const VrDenseArgs &a, const
     for (int c = 0; c < NC; ++c) {
         const int64_t col = 4ll * (threadIdx.x + T * c);
         float q[4];
-        model_quad_values(msg, mc.mq[c], col, a.d, q);
+        model_quad_values<MODEL8>(msg, mc.mq[c], col, a.d, q);
         dx[c] = make_float4(q[0] - mc.xs[c].x, q[1] - mc.xs[c].y, q[2] - mc.xs[c].z, q[3] - mc.xs[c].w);
         if constexpr (!HAVE_Z) xs[c] = mc.xs[c];
     }
@@ -241,13 +242,26 @@ __device__ __forceinline__ void worker_finish(const VrDenseArgs &a, int m, const
     worker_outputs(a, m, sh_alpha, su, si, sd);
 }
 
-template <int NC, int R, bool HAVE_Z, bool FULL, bool DB = false, int T = kRowThreads>
+// A zero the compiler cannot see through: an address formed with it is a per-lane address, so the load is a vector
+// load (counted with the other vector loads of the prologue) and not a scalar one, whose wait would also hold up
+// the scalar loads of the kernel arguments behind it.
+__device__ __forceinline__ int opaque_zero()
+{
+    int z;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(z));
+    return z;
+}
+
+// MODEL8: the model message has 8-bit fields (one word per quad of coordinates); otherwise any width, or float32.
+// DB: 0 one row buffer; 1 two row buffers where a block's rows allow it (decided in the kernel: all rows valid, a
+// whole number of batch pairs); 2 two row buffers, the host vouching for that (mini-batches drawn in the kernel,
+// the same even number of batches in every block): the kernel then holds no branch at all between its first
+// instruction and the loop, and the compiler keeps the requests in the order written.
+template <int NC, int R, bool HAVE_Z, bool FULL, int DB, int T, bool MODEL8>
 __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
 {
     constexpr int kWaves = T / kWave;
     __shared__ float sh_red[2 * kWaves * R * 2];
-    __shared__ int sh_row[kMaxRowsPerBlock];
-    __shared__ float sh_y[kMaxRowsPerBlock], sh_z[kMaxRowsPerBlock];
     // the in-kernel tail (one block owns the worker's whole mini-batch) exists for rows of up to 4096 floats;
     // wider rows always go through the partial sums and the second kernel
     constexpr bool kOwnTail = NC * T <= 1024;
@@ -260,30 +274,31 @@ __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
     // L2.  With a multiple of 8 workers the blocks of worker m all run on die m mod 8 -- the die that block m of
     // the second kernel runs on, which then finds most of their partial sums in its L2 (measured at M = 32,
     // d = 4096: second kernel 6.1 -> 5.75 us).
-    int m = blockIdx.y, part = blockIdx.x;
-    if ((gridDim.y & 7u) == 0u) {
-        const unsigned lin = blockIdx.x + gridDim.x * blockIdx.y;
-        m = static_cast<int>((lin & 7u) + 8u * (lin / (8u * gridDim.x)));
-        part = static_cast<int>((lin >> 3) % gridDim.x);
+    // Such a launch has the grid (8, P, M / 8): the linear workgroup number is x + 8 (y + P z), so x is the die.
+    int m = blockIdx.y, part = blockIdx.x;                 // grid (P, M)
+    if (a.die_major) {
+        m = static_cast<int>(blockIdx.x + 8u * blockIdx.z);
+        part = static_cast<int>(blockIdx.y);
     }
     const int64_t d = a.d;
-    const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
-    if (a.zero_word && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *a.zero_word = 0u;
+    const int lane = threadIdx.x & (kWave - 1);
+    if (a.zero_word && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x == 0) *a.zero_word = 0u;
 
-    // ---- the thread's columns of the model message and of the snapshot are requested first: they depend on
-    //      nothing and are back by the time the row numbers are
-    ModelCols<NC> mc;
-    request_model_cols<NC, FULL, T>(a, msg, mc);
-
-    // ---- rows of this block
+    // ---- The order of the prologue is the order in which memory is asked for.  Nothing of a round is on the chip
+    //      when the kernel starts, and every dependent request costs a trip to memory, so the feature rows -- the
+    //      134 MB that the kernel exists to stream -- are requested before anything else: the row numbers need no
+    //      memory (they are drawn here, lane j of every wavefront draws and keeps row j of the block, at most 64
+    //      rows per block; no shared memory and no barrier), the first batch of rows is requested, and only then the
+    //      model message, the snapshot, the scale, labels and cached margins, all without a condition and none of
+    //      them waited for before the second batch of rows is in flight too.
     const int per = (a.B + a.P - 1) / a.P;
     const int r0 = part * per;
-    const int nrows = max(0, min(a.B, r0 + per) - r0);
-    bool row_ok = true;
-    if (static_cast<int>(threadIdx.x) < nrows) {
-        const int r = r0 + threadIdx.x;
+    const int nrows = max(0, min(a.B, r0 + per) - r0);        // at most kMaxRowsPerBlock = 64 (the host sees to it)
+    int my_row = -1;
+    if (lane < nrows) {
+        const int r = r0 + lane;
         int64_t i;
-        if (a.idx) {
+        if (DB != 2 && a.idx) {
             i = a.idx[static_cast<int64_t>(m) * a.B + r];
         } else {
             StreamKey sk = a.key;
@@ -291,30 +306,30 @@ __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
             sk.tag = DQ_TAG_SAMPLE;
             i = __umulhi(stream_word(sk, static_cast<uint64_t>(r)), static_cast<uint32_t>(a.n));
         }
-        row_ok = static_cast<uint64_t>(i) < static_cast<uint64_t>(a.n);           // out-of-range index: ignored
-        sh_row[threadIdx.x] = row_ok ? static_cast<int>(i) : -1;
+        my_row = static_cast<uint64_t>(i) < static_cast<uint64_t>(a.n) ? static_cast<int>(i) : -1;   // out of range: ignored
     }
     // whole batches of valid rows only (the usual case): the row loads then carry no condition, so a wait for one
-    // batch can leave the loads of the next one in flight
-    const bool plain = __syncthreads_and(row_ok) && nrows > 0 && nrows % R == 0;
+    // batch can leave the loads of the next one in flight.  (Every wavefront holds the same row numbers and takes
+    // the same decision.)
+    const bool plain = DB == 2 || (nrows > 0 && nrows % R == 0 && __all(lane >= nrows || my_row >= 0));
+    const auto row_number = [&](int j) { return __builtin_amdgcn_readlane(my_row, j); };      // j < 64, wave-uniform
 
     float4 dx[NC], xs[HAVE_Z ? 1 : NC], acc[NC];
     const float inv_B = 1.0f / static_cast<float>(a.B);      // the mean over the mini-batch, as one multiplication per row
+    float yv, zv;                                            // label and cached margin of row `lane`
     int buf = 0;
     auto load_batch = [&](int rb, float4 (&row)[R][NC]) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const int i = rb + r < nrows ? sh_row[rb + r] : -1;
+            const int i = rb + r < nrows ? row_number(rb + r) : -1;
             if (i >= 0) load_cols<NC, true, FULL, T>(a.X + static_cast<int64_t>(i) * a.lda, d, row[r]);
             else zero_cols<NC>(row[r]);
         }
     };
     auto load_rows = [&](int rb, float4 (&row)[R][NC]) {          // `plain` blocks only
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int i = __builtin_amdgcn_readfirstlane(sh_row[rb + r]);
-            load_cols<NC, true, FULL, T>(a.X + static_cast<int64_t>(i) * a.lda, d, row[r]);
-        }
+        for (int r = 0; r < R; ++r)
+            load_cols<NC, true, FULL, T>(a.X + static_cast<int64_t>(row_number(rb + r)) * a.lda, d, row[r]);
     };
     auto compute_batch = [&](int rb, const float4 (&row)[R][NC]) {
         float dots[HAVE_Z ? R : 2 * R];
@@ -324,20 +339,29 @@ __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
             if constexpr (!HAVE_Z) dots[R + r] = dot_cols<NC>(row[r], xs);
         }
         block_sum_R<HAVE_Z ? R : 2 * R, T>(dots, sh_red, buf);
-        // lane r of every wave evaluates the coefficient of row rb + r once (exp, expm1 and the
-        // division are the expensive part of a batch); the R results are then read back wave-uniformly
-        const int lane = threadIdx.x & (kWave - 1);
+        // lane r of every wave evaluates the coefficient of row rb + r once (the exponentials and reciprocals are
+        // the expensive part of a batch); the R results are then read back wave-uniformly.  Row number, label and
+        // margin of row rb + r sit in lane rb + r and are brought over as wave-uniform values.
         float dz = dots[0], zs = HAVE_Z ? 0.0f : dots[HAVE_Z ? 0 : R];
+        float yl = 1.0f;
+        int il = -1;
 #pragma unroll
-        for (int r = 1; r < R; ++r) {
+        for (int r = 0; r < R; ++r) {
+            const int src = min(rb + r, kWave - 1);
+            const int ir = rb + r < nrows ? __builtin_amdgcn_readlane(my_row, src) : -1;
+            const float yr = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(yv), src));
+            il = lane == r ? ir : il;
+            yl = lane == r ? yr : yl;
             dz = lane == r ? dots[r] : dz;
-            if constexpr (!HAVE_Z) zs = lane == r ? dots[R + r] : zs;
+            if constexpr (HAVE_Z) {
+                const float zr = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(zv), src));
+                zs = lane == r ? zr : zs;
+            } else {
+                zs = lane == r ? dots[R + r] : zs;
+            }
         }
         float coef_l = 0.0f;
-        if (lane < R && rb + lane < nrows && sh_row[rb + lane] >= 0) {
-            if constexpr (HAVE_Z) zs = sh_z[rb + lane];
-            coef_l = vr_slope_diff(sh_y[rb + lane], zs, dz) * inv_B;
-        }
+        if (lane < R && (DB == 2 || il >= 0)) coef_l = vr_slope_diff(yl, zs, dz) * inv_B;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const float coef = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(coef_l), r));
@@ -345,43 +369,44 @@ __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
         }
     };
 
-    // ---- the first batch of rows is requested as soon as the row numbers are known; the labels and cached
-    //      margins of the rows arrive while those loads are in flight, and q - snapshot is formed from words
-    //      that are already here
     float4 row[R][NC];
-    if (plain) load_rows(0, row);
+    if (DB == 2 || plain) load_rows(0, row);
     else load_batch(0, row);
-    if (static_cast<int>(threadIdx.x) < nrows) {
-        const int i = sh_row[threadIdx.x];
-        sh_y[threadIdx.x] = i >= 0 ? a.y[i] : 1.0f;
-        sh_z[threadIdx.x] = (i >= 0 && HAVE_Z) ? a.z_snap[i] : 0.0f;
+    const int zero = opaque_zero();
+    const ModelMsg msg{a.xq, a.delta_x[zero], a.b_x};          // (b_x = 32: a valid dummy address, the value is unused)
+    ModelCols<NC> mc;
+    request_model_cols<NC, FULL, T, MODEL8>(a, msg, mc);
+    {
+        const int i = max(my_row, 0);                          // lanes without a row ask for sample 0; nothing reads
+        yv = a.y[i];                                           // their values (a select here would be the first use
+        zv = HAVE_Z ? a.z_snap[i] : 0.0f;                      // of the loads and put a wait in front of the next rows)
     }
-    model_minus_snapshot<NC, HAVE_Z, T>(a, msg, mc, dx, xs);
     zero_cols<NC>(acc);
-    __syncthreads();
 
     // ---- stream the rows, R at a time
-    if (DB && plain && nrows % (2 * R) == 0) {
-        // two row buffers: while one batch is reduced the next one is in flight (the last pair of batches is peeled
-        // off, so that no load of the loop sits behind a condition)
+    if (DB == 2 || (DB == 1 && plain && nrows % (2 * R) == 0)) {
+        // two row buffers: while one batch is reduced the other one is in flight; no load sits behind a condition
         float4 row2[R][NC];
+        load_rows(R, row2);
+        model_minus_snapshot<NC, HAVE_Z, T, MODEL8>(a, msg, mc, dx, xs);
         int rb = 0;
         for (; rb + 2 * R < nrows; rb += 2 * R) {
-            load_rows(rb + R, row2);
             compute_batch(rb, row);
             load_rows(rb + 2 * R, row);
             compute_batch(rb + R, row2);
+            load_rows(rb + 3 * R, row2);
         }
-        load_rows(rb + R, row2);
         compute_batch(rb, row);
         compute_batch(rb + R, row2);
     } else if (plain) {
+        model_minus_snapshot<NC, HAVE_Z, T, MODEL8>(a, msg, mc, dx, xs);
         compute_batch(0, row);
         for (int rb = R; rb < nrows; rb += R) {
             load_rows(rb, row);
             compute_batch(rb, row);
         }
     } else {
+        model_minus_snapshot<NC, HAVE_Z, T, MODEL8>(a, msg, mc, dx, xs);
         for (int rb = 0; rb < nrows; rb += R) {
             if (rb > 0) load_batch(rb, row);
             compute_batch(rb, row);
@@ -748,17 +773,40 @@ static void launch_timed(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_
     else kernel<<<grid, block, lds, st>>>(k);
 }
 
-template <int NC, int R, bool DB = false, int T = kRowThreads>
-static void launch_vr(bool have_z, dim3 grid, hipStream_t st, const VrDenseArgs &k, hipEvent_t e0, hipEvent_t e1)
+template <int NC, int R, int DB, int T, bool HAVE_Z, bool MODEL8>
+static void launch_vr2(dim3 grid, hipStream_t st, const VrDenseArgs &k, hipEvent_t e0, hipEvent_t e1)
 {
     const bool full = k.d == 4ll * T * NC;       // every thread's columns are whole float4s of the row
     const dim3 block(T);
+    if (full) launch_timed(vr_dense_kernel<NC, R, HAVE_Z, true, DB, T, MODEL8>, grid, block, 0, st, e0, e1, k);
+    else launch_timed(vr_dense_kernel<NC, R, HAVE_Z, false, DB, T, MODEL8>, grid, block, 0, st, e0, e1, k);
+}
+
+template <int NC, int R, int DB, int T>
+static void launch_vr1(bool have_z, dim3 grid, hipStream_t st, const VrDenseArgs &k, hipEvent_t e0, hipEvent_t e1)
+{
+    const bool model8 = k.b_x == 8;
     if (have_z) {
-        if (full) launch_timed(vr_dense_kernel<NC, R, true, true, DB, T>, grid, block, 0, st, e0, e1, k);
-        else launch_timed(vr_dense_kernel<NC, R, true, false, DB, T>, grid, block, 0, st, e0, e1, k);
+        if (model8) launch_vr2<NC, R, DB, T, true, true>(grid, st, k, e0, e1);
+        else launch_vr2<NC, R, DB, T, true, false>(grid, st, k, e0, e1);
     } else {
-        if (full) launch_timed(vr_dense_kernel<NC, R, false, true, DB, T>, grid, block, 0, st, e0, e1, k);
-        else launch_timed(vr_dense_kernel<NC, R, false, false, DB, T>, grid, block, 0, st, e0, e1, k);
+        if (model8) launch_vr2<NC, R, DB, T, false, true>(grid, st, k, e0, e1);
+        else launch_vr2<NC, R, DB, T, false, false>(grid, st, k, e0, e1);
+    }
+}
+
+// two_buffers: the row width has a two-buffer kernel at all; then the static form (DB = 2) is taken when the
+// mini-batches are drawn in the kernel (every row number valid) and every block owns the same whole number of
+// batch pairs, else the form that decides per block.
+template <int NC, int R, bool TWO = false, int T = kRowThreads>
+static void launch_vr(bool have_z, dim3 grid, hipStream_t st, const VrDenseArgs &k, hipEvent_t e0, hipEvent_t e1)
+{
+    if constexpr (TWO) {
+        const int per = (k.B + k.P - 1) / k.P;
+        if (!k.idx && k.B % k.P == 0 && per % (2 * R) == 0) launch_vr1<NC, R, 2, T>(have_z, grid, st, k, e0, e1);
+        else launch_vr1<NC, R, 1, T>(have_z, grid, st, k, e0, e1);
+    } else {
+        launch_vr1<NC, R, 0, T>(have_z, grid, st, k, e0, e1);
     }
 }
 
@@ -773,7 +821,8 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     VrDenseArgs k{};
     k.X = prob->dense; k.lda = prob->lda; k.n = prob->n; k.d = d; k.y = prob->y;
     k.idx = a.idx; k.B = static_cast<int>(a.B); k.P = static_cast<int>(dense_vr_splits(a.M, a.B, d));
-    k.xq = a.xq; k.delta_x = a.delta_x; k.b_x = a.b_x; k.x_snap = a.x_snap; k.z_snap = a.z_snap; k.l2 = prob->l2;
+    k.xq = a.xq; k.b_x = a.b_x; k.x_snap = a.x_snap; k.z_snap = a.z_snap; k.l2 = prob->l2;
+    k.delta_x = a.b_x == 32 ? a.x_snap : a.delta_x;      // float32 model: no scale; the kernels read a valid dummy
     k.model_last_word = (a.b_x == 32 ? d : packed_words(d, a.b_x)) - 1;
     k.partial = static_cast<float *>(a.ws);
     k.ldp = pad4(d);
@@ -783,7 +832,8 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     k.worker0 = a.worker0;
     k.packed = a.packed; k.ld_words = a.ld_words; k.row_words = row_words;
     k.delta_out = a.delta_out; k.nnz_out = a.nnz_out; k.status = a.status; k.zero_word = a.zero_word;
-    const dim3 grid(k.P, static_cast<unsigned>(a.M));
+    k.die_major = a.M % 8 == 0 && a.M / 8 <= 65535;
+    const dim3 grid = k.die_major ? dim3(8, k.P, static_cast<unsigned>(a.M / 8)) : dim3(k.P, static_cast<unsigned>(a.M));
     const bool have_z = a.z_snap != nullptr;
     // Rows wider than 1024 floats are streamed with two row buffers, one block per compute unit: a batch is reduced
     // while the next one is in flight, and half as many partial sums are written and added again.  Measured for the
