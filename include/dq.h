@@ -337,7 +337,8 @@ typedef struct dq_run_config {
  * x, x_snap, g_snap: float[d].  y, xsum: float[d], Alg. 3 only.  z_snap: float[n] margins at the
  * snapshot from dq_full_grad, nullable.  xq: ring of tau+1 model messages, slot s at
  * xq + s*xq_stride_words (each ceil(d*b_x/32) words, or d floats; 16-byte aligned slots);
- * delta_x: float[tau+1], one scale per slot; absmax_x: float[1].  The message of round t lives in
+ * delta_x: float[tau+1], one scale per slot; absmax_x: float[2] (scratch: the largest magnitude of the model after
+ * the last two rounds, in alternating entries).  The message of round t lives in
  * slot t mod (tau+1).  packed: M rows of ld_words words; delta: float[M];
  * nnz: int32[m*M] nonzero codes per round and worker (written by Alg. 2 only), nullable.  ws: DQ_OP_VR_GRAD workspace.
  * wire (nullable, Alg. 2 with b in {2,4,8} only): M rows of ld_wire >= dq_sparse_stream_words(d, b) words.  When

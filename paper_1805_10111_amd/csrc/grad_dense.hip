@@ -148,24 +148,39 @@ struct VrDenseArgs {
     float *delta_out; int32_t *nnz_out; uint32_t *status;
     uint32_t *zero_word;             // nullable: set to 0 by one thread of the grid
     int die_major;                   // grid is (8, P, M / 8) instead of (P, M): see vr_dense_kernel
+    // MODEL == 2 (Alg. 1, master (i) done here): the model itself, its largest magnitude, the master's stream, and
+    // where one block leaves the message (xq_out words, delta_x_out[0])
+    const float *x_model, *absmax_model;
+    StreamKey model_key;
+    uint32_t *xq_out; float *delta_x_out;
 };
 
-// The thread's columns of the model message and of the snapshot, requested without waiting for anything (the
-// requests have no dependence on the rows, so a kernel issues them first and they are back before they are needed).
+// The thread's columns of the model message (or, MODEL == 2, of the model itself) and of the snapshot, requested
+// without waiting for anything (the requests have no dependence on the rows and stay in flight next to them).
+// MODEL: 0 message of any width or float32; 1 message with 8-bit fields (one word per quad of coordinates);
+// 2 the float32 model, which the kernel quantizes to b_x bits itself.
 template <int NC>
 struct ModelCols {
     ModelQuad mq[NC];
+    float4 xv[NC];
     float4 xs[NC];
+    float amax;
 };
 
-template <int NC, bool FULL, int T, bool MODEL8>
-__device__ __forceinline__ void request_model_cols(const VrDenseArgs &a, const ModelMsg &msg, ModelCols<NC> &mc)
+template <int NC, bool FULL, int T, int MODEL>
+__device__ __forceinline__ void request_model_cols(const VrDenseArgs &a, const ModelMsg &msg, int zero, ModelCols<NC> &mc)
 {
     const int64_t d = a.d;
+    if constexpr (MODEL == 2) mc.amax = a.absmax_model[zero];
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         const int64_t col = 4ll * (threadIdx.x + T * c);
-        mc.mq[c] = model_quad_request<MODEL8>(msg, col, a.model_last_word);
+        if constexpr (MODEL == 2) {
+            if constexpr (FULL) mc.xv[c] = *reinterpret_cast<const float4 *>(a.x_model + col);
+            else mc.xv[c] = load4_or_zero(a.x_model, col, d);
+        } else {
+            mc.mq[c] = model_quad_request<MODEL == 1>(msg, col, a.model_last_word);
+        }
         if constexpr (FULL) mc.xs[c] = *reinterpret_cast<const float4 *>(a.x_snap + col);
         else mc.xs[c] = load4_or_zero(a.x_snap, col, d);
     }
@@ -173,15 +188,47 @@ __device__ __forceinline__ void request_model_cols(const VrDenseArgs &a, const M
 
 // dx = q - snapshot for the thread's columns (q: the dequantized model message); xs = the
 // snapshot itself when HAVE_Z is false (margins at the snapshot must then be recomputed).
-template <int NC, bool HAVE_Z, int T, bool MODEL8>
+// MODEL == 2: q = Q_(delta_x, b_x)(x) is formed here, exactly as the master would have (Section 3.1; Alg. 1,
+// master (i): scale from ||x||_inf, the master's random stream, quad by quad), and the block that `store` names
+// also leaves the packed message and its scale in memory for the kernels and calls that come after.
+template <int NC, bool HAVE_Z, int T, int MODEL>
 __device__ __forceinline__ void model_minus_snapshot(const VrDenseArgs &a, const ModelMsg &msg, const ModelCols<NC> &mc,
-                                                     float4 (&dx)[NC], float4 (&xs)[HAVE_Z ? 1 : NC])
+                                                     bool store, float4 (&dx)[NC], float4 (&xs)[HAVE_Z ? 1 : NC])
 {
+    if constexpr (MODEL == 2) {
+        const Scale s = make_scale(mc.amax, a.b_x);
+        const int64_t quads = (a.d + 3) / 4;
+        if (store && threadIdx.x == 0) {
+            a.delta_x_out[0] = s.delta;
+            if (s.bad && a.status) atomicOr(a.status, 1u);
+        }
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const int64_t qd = threadIdx.x + T * c;                  // quad of coordinates 4 qd .. 4 qd + 3
+            int k[4] = {0, 0, 0, 0};
+            if (s.inv_delta != 0.0f) {
+                const uint4 r = stream_block(a.model_key, static_cast<uint32_t>(qd));
+                k[0] = quantize_one(mc.xv[c].x, s, r.x); k[1] = quantize_one(mc.xv[c].y, s, r.y);
+                k[2] = quantize_one(mc.xv[c].z, s, r.z); k[3] = quantize_one(mc.xv[c].w, s, r.w);
+            }
+            // (coordinates past the end were loaded as 0, have code 0 and a zero snapshot entry: dx = 0 there)
+            dx[c] = make_float4(s.delta * static_cast<float>(k[0]) - mc.xs[c].x, s.delta * static_cast<float>(k[1]) - mc.xs[c].y,
+                                s.delta * static_cast<float>(k[2]) - mc.xs[c].z, s.delta * static_cast<float>(k[3]) - mc.xs[c].w);
+            if constexpr (!HAVE_Z) xs[c] = mc.xs[c];
+            if (store) {                                             // (the same for every thread of the block)
+                const bool in = qd < quads;
+                if (a.b_x == 8) store_quad_bits<8>(in ? pack4<8>(k[0], k[1], k[2], k[3]) : 0u, qd, quads, a.xq_out);
+                else if (a.b_x == 4) store_quad_bits<4>(in ? pack4<4>(k[0], k[1], k[2], k[3]) : 0u, qd, quads, a.xq_out);
+                else store_quad_bits<2>(in ? pack4<2>(k[0], k[1], k[2], k[3]) : 0u, qd, quads, a.xq_out);
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         const int64_t col = 4ll * (threadIdx.x + T * c);
         float q[4];
-        model_quad_values<MODEL8>(msg, mc.mq[c], col, a.d, q);
+        model_quad_values<MODEL == 1>(msg, mc.mq[c], col, a.d, q);
         dx[c] = make_float4(q[0] - mc.xs[c].x, q[1] - mc.xs[c].y, q[2] - mc.xs[c].z, q[3] - mc.xs[c].w);
         if constexpr (!HAVE_Z) xs[c] = mc.xs[c];
     }
@@ -252,12 +299,12 @@ __device__ __forceinline__ int opaque_zero()
     return z;
 }
 
-// MODEL8: the model message has 8-bit fields (one word per quad of coordinates); otherwise any width, or float32.
+// MODEL: where the model comes from (see ModelCols).
 // DB: 0 one row buffer; 1 two row buffers where a block's rows allow it (decided in the kernel: all rows valid, a
 // whole number of batch pairs); 2 two row buffers, the host vouching for that (mini-batches drawn in the kernel,
 // the same even number of batches in every block): the kernel then holds no branch at all between its first
 // instruction and the loop, and the compiler keeps the requests in the order written.
-template <int NC, int R, bool HAVE_Z, bool FULL, int DB, int T, bool MODEL8>
+template <int NC, int R, bool HAVE_Z, bool FULL, int DB, int T, int MODEL>
 __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
 {
     constexpr int kWaves = T / kWave;
@@ -373,9 +420,11 @@ __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
     if (DB == 2 || plain) load_rows(0, row);
     else load_batch(0, row);
     const int zero = opaque_zero();
-    const ModelMsg msg{a.xq, a.delta_x[zero], a.b_x};          // (b_x = 32: a valid dummy address, the value is unused)
+    // (b_x = 32: delta_x is a valid dummy address and the value unused; MODEL == 2: the scale is formed here)
+    const ModelMsg msg{a.xq, MODEL == 2 ? 0.0f : a.delta_x[zero], a.b_x};
     ModelCols<NC> mc;
-    request_model_cols<NC, FULL, T, MODEL8>(a, msg, mc);
+    request_model_cols<NC, FULL, T, MODEL>(a, msg, zero, mc);
+    const bool store_model = MODEL == 2 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0;
     {
         const int i = max(my_row, 0);                          // lanes without a row ask for sample 0; nothing reads
         yv = a.y[i];                                           // their values (a select here would be the first use
@@ -388,7 +437,7 @@ __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
         // two row buffers: while one batch is reduced the other one is in flight; no load sits behind a condition
         float4 row2[R][NC];
         load_rows(R, row2);
-        model_minus_snapshot<NC, HAVE_Z, T, MODEL8>(a, msg, mc, dx, xs);
+        model_minus_snapshot<NC, HAVE_Z, T, MODEL>(a, msg, mc, store_model, dx, xs);
         int rb = 0;
         for (; rb + 2 * R < nrows; rb += 2 * R) {
             compute_batch(rb, row);
@@ -399,14 +448,14 @@ __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
         compute_batch(rb, row);
         compute_batch(rb + R, row2);
     } else if (plain) {
-        model_minus_snapshot<NC, HAVE_Z, T, MODEL8>(a, msg, mc, dx, xs);
+        model_minus_snapshot<NC, HAVE_Z, T, MODEL>(a, msg, mc, store_model, dx, xs);
         compute_batch(0, row);
         for (int rb = R; rb < nrows; rb += R) {
             load_rows(rb, row);
             compute_batch(rb, row);
         }
     } else {
-        model_minus_snapshot<NC, HAVE_Z, T, MODEL8>(a, msg, mc, dx, xs);
+        model_minus_snapshot<NC, HAVE_Z, T, MODEL>(a, msg, mc, store_model, dx, xs);
         for (int rb = 0; rb < nrows; rb += R) {
             if (rb > 0) load_batch(rb, row);
             compute_batch(rb, row);
@@ -773,41 +822,58 @@ static void launch_timed(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_
     else kernel<<<grid, block, lds, st>>>(k);
 }
 
-template <int NC, int R, int DB, int T, bool HAVE_Z, bool MODEL8>
+template <int NC, int R, int DB, int T, bool HAVE_Z, int MODEL>
 static void launch_vr2(dim3 grid, hipStream_t st, const VrDenseArgs &k, hipEvent_t e0, hipEvent_t e1)
 {
     const bool full = k.d == 4ll * T * NC;       // every thread's columns are whole float4s of the row
     const dim3 block(T);
-    if (full) launch_timed(vr_dense_kernel<NC, R, HAVE_Z, true, DB, T, MODEL8>, grid, block, 0, st, e0, e1, k);
-    else launch_timed(vr_dense_kernel<NC, R, HAVE_Z, false, DB, T, MODEL8>, grid, block, 0, st, e0, e1, k);
+    if (full) launch_timed(vr_dense_kernel<NC, R, HAVE_Z, true, DB, T, MODEL>, grid, block, 0, st, e0, e1, k);
+    else launch_timed(vr_dense_kernel<NC, R, HAVE_Z, false, DB, T, MODEL>, grid, block, 0, st, e0, e1, k);
 }
 
 template <int NC, int R, int DB, int T>
 static void launch_vr1(bool have_z, dim3 grid, hipStream_t st, const VrDenseArgs &k, hipEvent_t e0, hipEvent_t e1)
 {
     const bool model8 = k.b_x == 8;
+    if constexpr (DB == 2) {
+        if (k.x_model) {                          // (dense_model_fusable: cached margins, static two-buffer form)
+            launch_vr2<NC, R, DB, T, true, 2>(grid, st, k, e0, e1);
+            return;
+        }
+    }
     if (have_z) {
-        if (model8) launch_vr2<NC, R, DB, T, true, true>(grid, st, k, e0, e1);
-        else launch_vr2<NC, R, DB, T, true, false>(grid, st, k, e0, e1);
+        if (model8) launch_vr2<NC, R, DB, T, true, 1>(grid, st, k, e0, e1);
+        else launch_vr2<NC, R, DB, T, true, 0>(grid, st, k, e0, e1);
     } else {
-        if (model8) launch_vr2<NC, R, DB, T, false, true>(grid, st, k, e0, e1);
-        else launch_vr2<NC, R, DB, T, false, false>(grid, st, k, e0, e1);
+        if (model8) launch_vr2<NC, R, DB, T, false, 1>(grid, st, k, e0, e1);
+        else launch_vr2<NC, R, DB, T, false, 0>(grid, st, k, e0, e1);
     }
 }
 
 // two_buffers: the row width has a two-buffer kernel at all; then the static form (DB = 2) is taken when the
 // mini-batches are drawn in the kernel (every row number valid) and every block owns the same whole number of
 // batch pairs, else the form that decides per block.
+static bool static_two_buffers(int64_t B, int64_t P, int R) { return B % P == 0 && (B / P) % (2 * R) == 0; }
+
 template <int NC, int R, bool TWO = false, int T = kRowThreads>
 static void launch_vr(bool have_z, dim3 grid, hipStream_t st, const VrDenseArgs &k, hipEvent_t e0, hipEvent_t e1)
 {
     if constexpr (TWO) {
-        const int per = (k.B + k.P - 1) / k.P;
-        if (!k.idx && k.B % k.P == 0 && per % (2 * R) == 0) launch_vr1<NC, R, 2, T>(have_z, grid, st, k, e0, e1);
+        if (!k.idx && static_two_buffers(k.B, k.P, R)) launch_vr1<NC, R, 2, T>(have_z, grid, st, k, e0, e1);
         else launch_vr1<NC, R, 1, T>(have_z, grid, st, k, e0, e1);
     } else {
         launch_vr1<NC, R, 0, T>(have_z, grid, st, k, e0, e1);
     }
+}
+
+// Rows per batch of the two-buffer kernels, by float4 columns per 256 threads (0: no two-buffer kernel).
+static int two_buffer_rows(int nc) { return nc == 2 ? 4 : nc == 4 ? 2 : nc >= 8 ? 1 : 0; }
+
+bool dense_model_fusable(const dq_problem *prob, int64_t M, int64_t B, int b_x, bool have_z)
+{
+    if (prob->layout != 0 || !have_z || (b_x != 2 && b_x != 4 && b_x != 8)) return false;
+    const int R = two_buffer_rows(dense_nc(prob->d));
+    return R > 0 && static_two_buffers(B, dense_vr_splits(M, B, prob->d), R);
 }
 
 int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
@@ -832,6 +898,13 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     k.worker0 = a.worker0;
     k.packed = a.packed; k.ld_words = a.ld_words; k.row_words = row_words;
     k.delta_out = a.delta_out; k.nnz_out = a.nnz_out; k.status = a.status; k.zero_word = a.zero_word;
+    if (a.x_model) {
+        if (!a.absmax_model || a.idx || !a.packed || !dense_model_fusable(prob, a.M, a.B, a.b_x, a.z_snap != nullptr))
+            return DQ_ERR_INVALID_ARG;
+        k.x_model = a.x_model; k.absmax_model = a.absmax_model;
+        k.model_key = StreamKey{static_cast<uint32_t>(a.seed), static_cast<uint32_t>(a.seed >> 32), a.iter, DQ_MASTER_ID, DQ_TAG_MODEL};
+        k.xq_out = const_cast<uint32_t *>(a.xq); k.delta_x_out = const_cast<float *>(a.delta_x);
+    }
     k.die_major = a.M % 8 == 0 && a.M / 8 <= 65535;
     const dim3 grid = k.die_major ? dim3(8, k.P, static_cast<unsigned>(a.M / 8)) : dim3(k.P, static_cast<unsigned>(a.M));
     const bool have_z = a.z_snap != nullptr;

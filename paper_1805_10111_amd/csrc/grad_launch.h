@@ -32,7 +32,21 @@ struct WorkerArgs {
                                   // streams the feature rows (start/stop events of an extended launch)
     uint32_t *zero_word;          // nullable: one device word the worker kernel sets to 0 (dq_run_rounds uses it to
                                   // prepare the master's ||x||_inf accumulator without a launch of its own)
+    // Alg. 1, master (i) done by the worker kernel itself (dq_run_rounds, dense features): when x_model is given the
+    // kernel that streams the rows quantizes the model x_model[d] with scale ||x||_inf = *absmax_model and the master's
+    // stream (seed, iter, DQ_MASTER_ID, DQ_TAG_MODEL) -- every block for its own use, one block also storing the
+    // message to `xq` and its scale to `delta_x`, which are then outputs of the call.  Needs dense_model_fusable().
+    const float *x_model, *absmax_model;
 };
+
+// Whether the dense worker step can take the model from x_model (see WorkerArgs) for this shape.
+bool dense_model_fusable(const dq_problem *prob, int64_t M, int64_t B, int b_x, bool have_z);
+
+// Alg. 1, master (ii) alone (Alg. 3 with y): decode + aggregate + prox / momentum update, spread over the chip, with
+// ||x||_inf accumulated into *absmax_bits (bit pattern, must hold 0 on entry).  No model quantization.
+int32_t master_update_impl(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b, float scale,
+                           int each, const float *g_snap, float *x, float *y, const float *x_snap, float *xsum, float eta,
+                           float theta, float l1, int64_t d, uint32_t *absmax_bits, void *stream);
 
 // Validation + dispatch shared by dq_vr_grad, dq_worker_step and dq_run_rounds.
 int32_t worker_step_impl(const dq_problem *prob, const WorkerArgs &a, void *stream);

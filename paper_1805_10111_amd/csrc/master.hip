@@ -126,27 +126,27 @@ __device__ __forceinline__ uint32_t quad_abs_bits(float4 v)
 
 // Any model size: grid-stride over quads; ||x||_inf through one atomic max per block on the
 // magnitude bit pattern (absmax_bits must be zero on entry).
-template <int FIELD, bool ACC, bool EACH>
-__global__ __launch_bounds__(kThreads) void master_update_kernel(const MasterArgs a, uint32_t *__restrict__ absmax_bits)
+template <int FIELD, bool ACC, bool EACH, int TB = kThreads>
+__global__ __launch_bounds__(TB) void master_update_kernel(const MasterArgs a, uint32_t *__restrict__ absmax_bits)
 {
-    __shared__ uint32_t scratch[kThreads / kWave];
+    __shared__ uint32_t scratch[TB / kWave];
     const int64_t quads = (a.d + 3) / 4;
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * TB;
     uint32_t amax = 0;
-    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; q < quads; q += stride)
+    for (int64_t q = static_cast<int64_t>(blockIdx.x) * TB + threadIdx.x; q < quads; q += stride)
         amax = max(amax, quad_abs_bits(master_quad<FIELD, ACC, EACH>(a, q)));
     amax = block_max_u32(amax, scratch);
     if (threadIdx.x == 0 && amax != 0) atomicMax(absmax_bits, amax);
 }
 
-template <int FIELD>
+template <int FIELD, int TB = kThreads>
 static int launch_master_update(bool acc, dim3 grid, hipStream_t st, const MasterArgs &a, uint32_t *absmax_bits)
 {
-    const dim3 block(kThreads);
-    if (acc && a.each) master_update_kernel<FIELD, true, true><<<grid, block, 0, st>>>(a, absmax_bits);
-    else if (acc) master_update_kernel<FIELD, true, false><<<grid, block, 0, st>>>(a, absmax_bits);
-    else if (a.each) master_update_kernel<FIELD, false, true><<<grid, block, 0, st>>>(a, absmax_bits);
-    else master_update_kernel<FIELD, false, false><<<grid, block, 0, st>>>(a, absmax_bits);
+    const dim3 block(TB);
+    if (acc && a.each) master_update_kernel<FIELD, true, true, TB><<<grid, block, 0, st>>>(a, absmax_bits);
+    else if (acc) master_update_kernel<FIELD, true, false, TB><<<grid, block, 0, st>>>(a, absmax_bits);
+    else if (a.each) master_update_kernel<FIELD, false, true, TB><<<grid, block, 0, st>>>(a, absmax_bits);
+    else master_update_kernel<FIELD, false, false, TB><<<grid, block, 0, st>>>(a, absmax_bits);
     DQ_LAUNCH_CHECK();
     return DQ_OK;
 }
@@ -359,23 +359,60 @@ extern "C" int32_t dq_mu_terms(const float *x, const float *x_snap, int64_t d, i
     return DQ_OK;
 }
 
+static int32_t check_master_args(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
+                                 const float *g_snap, const float *x, const float *y, const float *x_snap,
+                                 const float *xsum, int64_t d)
+{
+    if (d <= 0 || M <= 0 || M > 0x7FFFFFFFll || !packed || !g_snap || !x) return DQ_ERR_INVALID_ARG;
+    if (b != 32 && !delta) return DQ_ERR_INVALID_ARG;
+    if (y && !x_snap) return DQ_ERR_INVALID_ARG;
+    if (b != 2 && b != 4 && b != 8 && b != 32) return (b >= 2 && b <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
+    const int64_t row_words = b == 32 ? d : packed_words(d, b);
+    if (ld_words < row_words || (M > 1 && ld_words % 4 != 0)) return DQ_ERR_INVALID_ARG;
+    const void *ptrs[] = {packed, g_snap, x, y, x_snap, xsum};
+    for (const void *p : ptrs)
+        if (p && !aligned16(p)) return DQ_ERR_INVALID_ARG;
+    return DQ_OK;
+}
+
+// One wavefront per block: at d = 4096 the 1024 quads of the model are 16 blocks on 16 compute units.
+constexpr int kRoundThreads = 64;
+
+int32_t dq::master_update_impl(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
+                               float scale, int each, const float *g_snap, float *x, float *y, const float *x_snap,
+                               float *xsum, float eta, float theta, float l1, int64_t d, uint32_t *absmax_bits,
+                               void *stream)
+{
+    const int32_t rc = check_master_args(packed, ld_words, delta, M, b, g_snap, x, y, x_snap, xsum, d);
+    if (rc != DQ_OK) return rc;
+    if (!absmax_bits) return DQ_ERR_INVALID_ARG;
+    const int64_t row_words = b == 32 ? d : packed_words(d, b);
+    const MasterArgs a{packed, ld_words, row_words, delta, static_cast<int>(M), scale, each, g_snap,
+                       x, y, x_snap, xsum, eta, theta, eta * l1, d};
+    const bool acc = y != nullptr;
+    int64_t blocks = ceil_div(ceil_div(d, 4), kRoundThreads);
+    if (blocks > 4096) blocks = 4096;                                  // grid-stride beyond
+    const dim3 grid(static_cast<unsigned>(blocks));
+    hipStream_t st = as_stream(stream);
+    switch (b) {
+    case 8: return launch_master_update<8, kRoundThreads>(acc, grid, st, a, absmax_bits);
+    case 4: return launch_master_update<4, kRoundThreads>(acc, grid, st, a, absmax_bits);
+    case 2: return launch_master_update<2, kRoundThreads>(acc, grid, st, a, absmax_bits);
+    default: return launch_master_update<32, kRoundThreads>(acc, grid, st, a, absmax_bits);
+    }
+}
+
 int32_t dq::master_step_impl(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
                              float scale, int each, const float *g_snap, float *x, float *y, const float *x_snap,
                              float *xsum, float eta, float theta, float l1, int64_t d, int32_t b_x, uint64_t seed,
                              uint32_t iter, uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out,
                              uint32_t *status, bool absmax_zeroed, void *stream)
 {
-    if (d <= 0 || M <= 0 || M > 0x7FFFFFFFll || !packed || !g_snap || !x || !xq_packed_out || !delta_x_out || !absmax_x_out)
-        return DQ_ERR_INVALID_ARG;
-    if (b != 32 && !delta) return DQ_ERR_INVALID_ARG;
-    if (y && !x_snap) return DQ_ERR_INVALID_ARG;
-    if (b != 2 && b != 4 && b != 8 && b != 32) return (b >= 2 && b <= 8) ? DQ_ERR_UNSUPPORTED : DQ_ERR_INVALID_ARG;
+    int32_t rc0 = check_master_args(packed, ld_words, delta, M, b, g_snap, x, y, x_snap, xsum, d);
+    if (rc0 != DQ_OK) return rc0;
+    if (!xq_packed_out || !delta_x_out || !absmax_x_out || !aligned16(xq_packed_out)) return DQ_ERR_INVALID_ARG;
     if (b_x < 2 || (b_x > 16 && b_x != 32)) return DQ_ERR_INVALID_ARG;
     const int64_t row_words = b == 32 ? d : packed_words(d, b);
-    if (ld_words < row_words || (M > 1 && ld_words % 4 != 0)) return DQ_ERR_INVALID_ARG;
-    const void *ptrs[] = {packed, g_snap, x, y, x_snap, xsum, xq_packed_out};
-    for (const void *p : ptrs)
-        if (p && !aligned16(p)) return DQ_ERR_INVALID_ARG;
     hipStream_t st = as_stream(stream);
     const MasterArgs a{packed, ld_words, row_words, delta, static_cast<int>(M), scale, each, g_snap,
                        x, y, x_snap, xsum, eta, theta, eta * l1, d};

@@ -42,6 +42,13 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
     // the model equals the snapshot bit for bit at the first round of an epoch of Alg. 1/2 and of the
     // first epoch of Alg. 3: flag-bit case of Section 4.1
     const bool start_is_snapshot = !acc || epoch == 0;
+    // Alg. 1, master (i) without a launch of its own: between two rounds of one call the master kernel stops at the
+    // update and ||x||_inf (spread over the chip), and the next round's row-streaming kernel quantizes the model in
+    // its prologue, while its first rows are on their way -- every block for itself, one of them storing the message.
+    // The two slots of absmax_x alternate: the kernel that reads one clears the other for the master of its round.
+    const bool fusable = cfg->tau == 0 && cfg->b_x != 32 &&
+                         dq::dense_model_fusable(prob, cfg->M, cfg->B, cfg->b_x, st->z_snap != nullptr);
+    bool model_pending = false;          // the model of this round is still x itself (not yet a message)
     for (int64_t t = t0; t < t0 + rounds; ++t) {
         const uint32_t it = static_cast<uint32_t>(epoch * cfg->m + t);
         uint32_t *xq_now = st->xq + (t % slots) * st->xq_stride_words;
@@ -75,7 +82,11 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
             w.nnz_out = (st->nnz && cfg->algo == DQ_ALGO_SPARSE) ? st->nnz + t * cfg->M + w_lo : nullptr;
             w.status = st->status;
             w.ws = st->ws; w.ws_bytes = st->ws_bytes;
-            if (g == 0) w.zero_word = reinterpret_cast<uint32_t *>(st->absmax_x);   // for the master's max below
+            if (g == 0) w.zero_word = reinterpret_cast<uint32_t *>(st->absmax_x + (t & 1));   // for the master's max below
+            if (model_pending) {                  // (fusable: a single group)
+                w.x_model = st->x;
+                w.absmax_model = st->absmax_x + ((t - 1) & 1);
+            }
             if (worker_events && g == 0) {
                 w.ev_start = static_cast<hipEvent_t>(worker_events[2 * (t - t0)]);
                 w.ev_stop = static_cast<hipEvent_t>(worker_events[2 * (t - t0) + 1]);
@@ -93,10 +104,16 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
         // master side; the new model is the message of round t+1
         uint32_t *xq_next = st->xq + ((t + 1) % slots) * st->xq_stride_words;
         float *dx_next = st->delta_x + ((t + 1) % slots);
-        rc = dq::master_step_impl(st->packed, st->ld_words, st->delta, cfg->M, cfg->b, scale, cfg->each, st->g_snap, st->x,
-                                  acc ? st->y : nullptr, st->x_snap, acc ? st->xsum : nullptr, eta, theta, prob->l1,
-                                  prob->d, cfg->b_x, cfg->seed, it + 1u, xq_next, dx_next, st->absmax_x, st->status,
-                                  /*absmax_zeroed=*/true, stream);
+        model_pending = fusable && t + 1 < t0 + rounds;
+        if (model_pending)
+            rc = dq::master_update_impl(st->packed, st->ld_words, st->delta, cfg->M, cfg->b, scale, cfg->each, st->g_snap,
+                                        st->x, acc ? st->y : nullptr, st->x_snap, acc ? st->xsum : nullptr, eta, theta,
+                                        prob->l1, prob->d, reinterpret_cast<uint32_t *>(st->absmax_x + (t & 1)), stream);
+        else
+            rc = dq::master_step_impl(st->packed, st->ld_words, st->delta, cfg->M, cfg->b, scale, cfg->each, st->g_snap,
+                                      st->x, acc ? st->y : nullptr, st->x_snap, acc ? st->xsum : nullptr, eta, theta,
+                                      prob->l1, prob->d, cfg->b_x, cfg->seed, it + 1u, xq_next, dx_next,
+                                      st->absmax_x + (t & 1), st->status, /*absmax_zeroed=*/true, stream);
         if (rc != DQ_OK) return rc;
     }
     return DQ_OK;

@@ -46,7 +46,7 @@ class DoubleQuantTrainer:
         self.xq_stride = (self.xq_words + 3) // 4 * 4
         self.xq = torch.zeros((self.tau + 1) * self.xq_stride, **i32)     # ring of the last tau+1 model messages
         self.delta_x = torch.zeros(self.tau + 1, **f32)
-        self.absmax_x = torch.zeros(1, **f32)
+        self.absmax_x = torch.zeros(2, **f32)
         self.row_words = d if b == 32 else dq.packed_words(d, b)
         self.ld_words = (self.row_words + 3) // 4 * 4
         self.packed = torch.zeros((M, self.ld_words), **i32)

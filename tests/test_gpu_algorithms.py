@@ -162,18 +162,23 @@ def test_runs_are_reproducible(dq):
     assert not torch.equal(a.x_snap, c.x_snap)
 
 
-@pytest.mark.parametrize("algo,b,d,M,B", [("acc", 8, 4096, 32, 256), ("asylpg", 4, 4096, 16, 64), ("sparse", 4, 3000, 8, 128),
-                                          ("acc", 2, 2048, 32, 128), ("asylpg", 8, 1500, 4, 64)])
-def test_rounds_enqueued_together_equal_rounds_enqueued_one_by_one(dq, algo, b, d, M, B):
+@pytest.mark.parametrize("algo,b,d,M,B,b_x", [("acc", 8, 4096, 32, 256, 8), ("asylpg", 4, 4096, 16, 64, 8),
+                                              ("sparse", 4, 3000, 8, 128, 8), ("acc", 2, 2048, 32, 128, 8),
+                                              ("asylpg", 8, 1500, 4, 64, 8), ("asylpg", 8, 4096, 8, 64, 4),
+                                              ("acc", 4, 2048, 16, 64, 2), ("acc", 8, 8192, 8, 32, 8),
+                                              ("asylpg", 8, 6004, 8, 16, 4), ("acc", 8, 4096, 32, 256, 11)])
+def test_rounds_enqueued_together_equal_rounds_enqueued_one_by_one(dq, algo, b, d, M, B, b_x):
     """How the rounds of an epoch are spread over dq_run_rounds calls (3 + 4 rounds, or one round per call) must not
-    matter: every vector and every message comes out identical, bit for bit."""
+    matter: every vector and every message comes out identical, bit for bit.  (Between the rounds of one call the
+    model is quantized by the next round's row-streaming kernel instead of the master's: one round per call never
+    takes that path, several rounds per call do wherever the shape allows it.)"""
     from paper_1805_10111_amd.driver import DoubleQuantTrainer
     p = synth.dense_logistic(600, d, seed=d + M, l2=1e-3)
     P = dq.DeviceProblem.from_host(p)
     m = 7
     runs = []
     for together in (True, False):
-        tr = DoubleQuantTrainer(P, algo, M, B, 8, b, m, 0.1, seed=9)
+        tr = DoubleQuantTrainer(P, algo, M, B, b_x, b, m, 0.1, seed=9)
         for _ in range(2):
             tr.epoch_prologue()
             if together:
