@@ -474,6 +474,10 @@ __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
 // p = 0..P-1 (loads issued eight at a time), adds l2*(q - snapshot), leaves alpha in LDS
 // and the block runs the tail of the worker step.
 constexpr int kFinishThreads = 1024;
+// MODEL8: the model message has 8-bit fields; WANT_ALPHA: the gradient itself is also stored (dq_vr_grad, tests).
+// The kernel is a chain of latencies (launch, one trip to memory, two block reductions, the Philox rounds), so all
+// of its memory requests are made up front and none of them sits behind a branch that would have to wait first.
+template <bool MODEL8, bool WANT_ALPHA>
 __global__ __launch_bounds__(kFinishThreads) void vr_dense_finish_kernel(const VrDenseArgs a)
 {
     extern __shared__ __align__(16) float sh_alpha_dyn[];
@@ -482,22 +486,24 @@ __global__ __launch_bounds__(kFinishThreads) void vr_dense_finish_kernel(const V
     __shared__ double sd[kFinishThreads / kWave];
     const int m = blockIdx.x;
     const int64_t d = a.d;
-    const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
+    const ModelMsg msg{a.xq, a.delta_x[opaque_zero()], a.b_x};     // (b_x = 32: a valid dummy address, value unused)
     const float *base = a.partial + static_cast<int64_t>(m) * a.P * a.ldp;
     for (int64_t col = 4ll * threadIdx.x; col < a.ldp; col += 4ll * kFinishThreads) {
-        // everything this column group needs is requested up front, none of it behind a branch that waits: the
-        // model words, the snapshot and (below) the partial sums, sixteen at a time
-        const ModelQuad mq = model_quad_request(msg, col, a.model_last_word);
-        const float4 xs4 = load4_or_zero(a.x_snap, col, d);
-        const float xs[4] = {xs4.x, xs4.y, xs4.z, xs4.w};
         float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         int p = 0;
-        for (; p + 16 <= a.P; p += 16) {
-            float4 t[16];
+        float4 first[8];
+        const bool eight = a.P >= 8;                                // (the same for every thread)
+        if (eight) {
 #pragma unroll
-            for (int u = 0; u < 16; ++u) t[u] = *reinterpret_cast<const float4 *>(base + (p + u) * a.ldp + col);
+            for (int u = 0; u < 8; ++u) first[u] = *reinterpret_cast<const float4 *>(base + u * a.ldp + col);
+        }
+        const ModelQuad mq = model_quad_request<MODEL8>(msg, col, a.model_last_word);
+        const float4 xs4 = load4_or_zero(a.x_snap, col, d);
+        const float xs[4] = {xs4.x, xs4.y, xs4.z, xs4.w};
+        if (eight) {
 #pragma unroll
-            for (int u = 0; u < 16; ++u) { s.x += t[u].x; s.y += t[u].y; s.z += t[u].z; s.w += t[u].w; }
+            for (int u = 0; u < 8; ++u) { s.x += first[u].x; s.y += first[u].y; s.z += first[u].z; s.w += first[u].w; }
+            p = 8;
         }
         for (; p + 8 <= a.P; p += 8) {
             float4 t[8];
@@ -517,16 +523,13 @@ __global__ __launch_bounds__(kFinishThreads) void vr_dense_finish_kernel(const V
             const float4 t = *reinterpret_cast<const float4 *>(base + p * a.ldp + col);
             s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
         }
-        const float acc[4] = {s.x, s.y, s.z, s.w};
         float q[4];
-        model_quad_values(msg, mq, col, d, q);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (col + e < d) {
-                const float v = acc[e] + a.l2 * (q[e] - xs[e]);
-                sh_alpha_dyn[col + e] = v;
-                if (a.alpha_out && blockIdx.y == 0) a.alpha_out[static_cast<int64_t>(m) * a.ld + col + e] = v;
-            }
+        model_quad_values<MODEL8>(msg, mq, col, d, q);
+        const float4 v = make_float4(s.x + a.l2 * (q[0] - xs[0]), s.y + a.l2 * (q[1] - xs[1]), s.z + a.l2 * (q[2] - xs[2]),
+                                     s.w + a.l2 * (q[3] - xs[3]));
+        store_quad(sh_alpha_dyn, col >> 2, d, v);
+        if constexpr (WANT_ALPHA) {
+            if (blockIdx.y == 0) store_quad(a.alpha_out + static_cast<int64_t>(m) * a.ld, col >> 2, d, v);
         }
     }
     __syncthreads();
@@ -927,8 +930,13 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
             static std::once_flag once;
             static hipError_t once_rc = hipSuccess;
             std::call_once(once, [] {
-                once_rc = hipFuncSetAttribute(reinterpret_cast<const void *>(vr_dense_finish_kernel),
-                                              hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4);
+                for (const void *f : {reinterpret_cast<const void *>(vr_dense_finish_kernel<false, false>),
+                                      reinterpret_cast<const void *>(vr_dense_finish_kernel<false, true>),
+                                      reinterpret_cast<const void *>(vr_dense_finish_kernel<true, false>),
+                                      reinterpret_cast<const void *>(vr_dense_finish_kernel<true, true>)}) {
+                    const hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 16384 * 4);
+                    if (e != hipSuccess) once_rc = e;
+                }
             });
             DQ_HIP_TRY(once_rc);
         }
@@ -936,7 +944,14 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
         // (measured at d = 4096, M = 32: two blocks per worker 0.65 us faster than one, four or eight no better)
         const bool count_ok = !a.nnz_out || (a.sparsify && a.b >= 4);
         const unsigned slices = (a.packed && count_ok && a.b != 32 && d >= 2048 && a.M <= 128) ? 2u : 1u;
-        vr_dense_finish_kernel<<<dim3(static_cast<unsigned>(a.M), slices), dim3(kFinishThreads), lds, st>>>(k);
+        const dim3 fgrid(static_cast<unsigned>(a.M), slices), fblock(kFinishThreads);
+        if (a.b_x == 8) {
+            if (a.alpha_out) vr_dense_finish_kernel<true, true><<<fgrid, fblock, lds, st>>>(k);
+            else vr_dense_finish_kernel<true, false><<<fgrid, fblock, lds, st>>>(k);
+        } else {
+            if (a.alpha_out) vr_dense_finish_kernel<false, true><<<fgrid, fblock, lds, st>>>(k);
+            else vr_dense_finish_kernel<false, false><<<fgrid, fblock, lds, st>>>(k);
+        }
         DQ_LAUNCH_CHECK();
     }
     return DQ_OK;
