@@ -108,7 +108,9 @@ __device__ __forceinline__ Scale make_scale(float amax, int b)
     return s;
 }
 
-// One coordinate of Q_(delta,b): returns the integer code.
+// One coordinate of Q_(delta,b): returns the integer code plus BIAS (a bias rides for free on the add-with-carry
+// that applies the rounding decision; the packers of 2- and 4-bit fields want codes made non-negative that way).
+template <int BIAS = 0>
 __device__ __forceinline__ int quantize_one(float v, const Scale &s, uint32_t word)
 {
     // The code is clamped to [-2^(b-1), L].  Clamping v/delta to that range first (one three-operand median) gives
@@ -117,7 +119,7 @@ __device__ __forceinline__ int quantize_one(float v, const Scale &s, uint32_t wo
     const float t = __builtin_amdgcn_fmed3f(v * s.inv_delta, s.tmin, s.tmax);
     const float z = floorf(t);
     const float p = t - z;
-    return static_cast<int>(z) + (bernoulli(word, p) ? 1 : 0);
+    return static_cast<int>(z) + BIAS + (bernoulli(word, p) ? 1 : 0);
 }
 
 // ---- magnitude bit pattern: monotone in |v| for non-NaN, NaN sorts above Inf ----

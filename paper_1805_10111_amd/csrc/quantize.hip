@@ -50,14 +50,13 @@ __global__ __launch_bounds__(kThreads) void absmax_kernel(const float *__restric
     for (int64_t t = blockIdx.x; t < tiles; t += gridDim.x) {
         const int64_t q0 = t * 4 * kThreads + threadIdx.x;
         float4 a[4];
+        if ((t + 1) * 16 * kThreads <= d) {                  // a whole tile (the same for every thread): no condition
+#pragma unroll                                               // on any load, so all four are in flight together
+            for (int k = 0; k < 4; ++k) a[k] = load_f4_stream(row + 4 * (q0 + k * kThreads));
+        } else {
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int64_t q = q0 + k * kThreads;
-            if (4 * q + 3 < d) {
-                typedef float v4f __attribute__((ext_vector_type(4)));
-                const v4f t4 = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(row) + q);
-                a[k] = make_float4(t4.x, t4.y, t4.z, t4.w);
-            } else {
+            for (int k = 0; k < 4; ++k) {
+                const int64_t q = q0 + k * kThreads;
                 a[k] = q < quads ? load_quad(row, q, d) : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
             }
         }
@@ -76,7 +75,8 @@ int launch_absmax(const float *v, int64_t d, int64_t M, int64_t ld, float *absma
     if (d > 0) {
         // every block ends in one atomic on the row's slot: keep the grid small (grid-stride loop)
         dim3 grid = grid_for(d, M);
-        const unsigned cap = static_cast<unsigned>(ceil_div(4096, M));
+        const unsigned cap = static_cast<unsigned>(ceil_div(1024, M));   // (measured on 2^28 coordinates: 1024 blocks 152 us,
+                                                                         // 4096 blocks 169 us, 16384 blocks 239 us)
         if (grid.x > cap) grid.x = cap;
         absmax_kernel<<<grid, dim3(kThreads), 0, st>>>(v, d, ld, reinterpret_cast<uint32_t *>(absmax_out));
         DQ_LAUNCH_CHECK();
@@ -231,10 +231,63 @@ __global__ __launch_bounds__(kThreads) void unpack_any_kernel(const uint32_t *__
     }
 }
 
+// ---------------------------------------------------------------- lane-contiguous access for 16 coordinates per thread
+// A thread of the streaming kernels owns 16 consecutive coordinates (64 bytes), so that it emits whole words for
+// every field width.  Read or written directly, that is four 16-byte accesses per lane at a lane stride of 64
+// bytes: every instruction touches 64 different cache lines, a sixth of a line each.  Measured on 1 GiB with plain
+// kernels: stores of that shape reach 3.6 TB/s against 6.1 TB/s for stores in which consecutive lanes write
+// consecutive 16 bytes (a wavefront writes 1 KB of whole lines per instruction), loads 4.1 against 7.1 TB/s
+// (non-temporal).  So memory is always accessed lane-contiguously -- quad 64 u + lane of the wavefront's tile of
+// 256 quads by access u -- and the 4 KB tile is transposed through LDS (no barrier: a wavefront only exchanges
+// data with itself).  Slot of quad q in the tile, skewed so that neither direction has bank conflicts: q + q / 8.
+constexpr int kTileSlots = 256 + 256 / 8;                 // float4 slots per wavefront
+
+__device__ __forceinline__ int tile_slot(int q) { return q + (q >> 3); }
+
+// The thread's 16 coordinates (quads 4 lane .. 4 lane + 3 of the tile that starts at `tile`, whole and inside the
+// vector) from lane-contiguous non-temporal loads.
+__device__ __forceinline__ void load16_tile(const float *__restrict__ tile, float4 *__restrict__ lds, int lane, float (&a)[16])
+{
+    float4 t[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) t[u] = load_f4_stream(tile + 4 * (64 * u + lane));
+#pragma unroll
+    for (int u = 0; u < 4; ++u) lds[tile_slot(64 * u + lane)] = t[u];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const float4 v = lds[tile_slot(4 * lane + u)];
+        a[4 * u] = v.x; a[4 * u + 1] = v.y; a[4 * u + 2] = v.z; a[4 * u + 3] = v.w;
+    }
+    __builtin_amdgcn_wave_barrier();                      // the tile is free again only when every lane has read
+}
+
+// The inverse: the thread's 16 values leave as lane-contiguous 16-byte stores.
+__device__ __forceinline__ void store16_tile(float *__restrict__ tile, float4 *__restrict__ lds, int lane, const float (&a)[16])
+{
+#pragma unroll
+    for (int u = 0; u < 4; ++u) lds[tile_slot(4 * lane + u)] = make_float4(a[4 * u], a[4 * u + 1], a[4 * u + 2], a[4 * u + 3]);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    float4 t[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) t[u] = lds[tile_slot(64 * u + lane)];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) *reinterpret_cast<float4 *>(tile + 4 * (64 * u + lane)) = t[u];
+    __builtin_amdgcn_wave_barrier();
+}
+
 // ---------------------------------------------------------------- quantize (+pack)
 // FIELD = width of the stored field (2, 4, 8 bits); `b` = bits of the code range.
 // With FIELD == 8 and any b in [2,8] the output words are four int8 codes each.
-template <int FIELD>
+// TILE: the input is read lane-contiguously and transposed through LDS (see load16_tile).  Measured on 2^28
+// coordinates it pays for 8-bit fields only (228 -> 220 us); with narrower fields, whose packing costs more
+// arithmetic, the kernel is bound by instruction issue and the exchange costs more than the better access pattern
+// brings (4 bits 214 -> 217 us, 2 bits 197 -> 212 us).
+template <int FIELD, bool TILE = FIELD == 8>
 __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(
     const float *__restrict__ v, int64_t d, int64_t ld, const float *__restrict__ absmax, int b, StreamKey key,
     uint32_t worker0, uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words,
@@ -262,11 +315,21 @@ __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(
             count_out[m] = c;
         }
     }
+    __shared__ float4 tiles[kThreads / kWave][kTileSlots];
+    const int lane = threadIdx.x & (kWave - 1);
+    float4 *lds = tiles[threadIdx.x / kWave];
     const int64_t chunks = (d + kCoordsPerThread - 1) / kCoordsPerThread;
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
-    for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
+    // (the loop bound is the same for the whole wavefront: its lanes go through the tile exchange together)
+    for (int64_t c0 = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x - lane; c0 < chunks; c0 += stride) {
+        const int64_t c = c0 + lane;
         float a[16];
-        load16(row, c * kCoordsPerThread, d, a);             // coordinates past d read as 0 -> code 0
+        if (TILE && (c0 + kWave) * kCoordsPerThread <= d) {          // the wavefront's 1024 coordinates are all there
+            load16_tile(row + c0 * kCoordsPerThread, lds, lane, a);
+        } else {
+            if (c >= chunks) continue;
+            load16(row, c * kCoordsPerThread, d, a);         // coordinates past d read as 0 -> code 0
+        }
         uint32_t w[Words16<FIELD>::n];
         quantize16<FIELD>(a, s, key, c, w);
         store_words<FIELD>(out, c, row_words, w);
@@ -314,15 +377,22 @@ __global__ __launch_bounds__(kThreads) void unpack_dequant_sum_kernel(
     const uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words, const float *__restrict__ delta,
     int64_t d, int M, float scale, float *__restrict__ out)
 {
+    __shared__ float4 tiles[kThreads / kWave][kTileSlots];
+    const int lane = threadIdx.x & (kWave - 1);
+    float4 *lds = tiles[threadIdx.x / kWave];
     const int64_t chunks = (d + kCoordsPerThread - 1) / kCoordsPerThread;
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
     const bool scaled = (FIELD == 2 || FIELD == 4) && scales_divide_exactly(delta, M);
-    for (int64_t c = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; c < chunks; c += stride) {
+    for (int64_t c0 = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x - lane; c0 < chunks; c0 += stride) {
+        const int64_t c = c0 + lane;
+        const bool whole = (c0 + kWave) * kCoordsPerThread <= d;     // the wavefront's 1024 coordinates are all there
+        if (!whole && c >= chunks) continue;
         float acc[16];
         decode_sum16<FIELD, true>(packed, ld_words, row_words, delta, M, c, d, scaled, acc);
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[j] = scale * acc[j];
-        store16<false>(out, c * kCoordsPerThread, d, acc);
+        if (whole) store16_tile(out + c0 * kCoordsPerThread, lds, lane, acc);
+        else store16<false>(out, c * kCoordsPerThread, d, acc);
     }
 }
 
