@@ -116,27 +116,25 @@ def time_round_loop(tr, torch, steps, warmup):
 
 
 def kernel_durations(tr, epochs, stride):
-    """Own duration of the dominant kernel (the one that streams the feature rows of all M workers): every
-    `stride`-th round of `epochs` further epochs is enqueued by a call of its own that hands the library two events,
-    which it uses as the start and stop events of that launch (hipExtLaunchKernel), i.e. the kernel's time stamps on
-    the launch stream.  Flag-bit rounds read no rows and are skipped.  Returns seconds per launch (list)."""
+    """Own duration of the dominant kernel (the one that streams the feature rows of all M workers): in `epochs`
+    further epochs, each enqueued by one call like the timed region, every `stride`-th round hands the library two
+    events, which it uses as the start and stop events of that launch (hipExtLaunchKernel), i.e. the kernel's time
+    stamps on the launch stream.  Flag-bit rounds read no rows and are skipped.  Returns seconds per launch (list)."""
     import torch
     events = []
     for _ in range(epochs):
         assert tr._t == 0
         tr.epoch_prologue()
-        t = 0
-        while t < tr.m:
+        handles = []
+        for t in range(tr.m):
             if t % stride == stride - 1 and not tr.is_flag_round(t):
                 e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 e0.record(); e1.record()            # instantiates the HIP events; the launch overwrites them
-                tr.rounds(t, 1, [e0.cuda_event, e1.cuda_event])
                 events.append((e0, e1))
-                t += 1
+                handles += [e0.cuda_event, e1.cuda_event]
             else:
-                run = min(tr.m - t, stride - 1 - t % stride)
-                tr.rounds(t, run)
-                t += run
+                handles += [None, None]
+        tr.rounds(0, tr.m, handles)
         tr.epoch_epilogue()
     torch.cuda.synchronize()
     return [e0.elapsed_time(e1) * 1e-3 for e0, e1 in events]

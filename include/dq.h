@@ -376,7 +376,8 @@ typedef struct dq_run_state {
  * that streams the feature rows (its first kernel; for CSR its only one; with tau > 0 the one of the
  * first worker group): they are the start and stop events of that launch (hipExtLaunchKernel), so
  * hipEventElapsedTime over the pair is the kernel's own duration.  A flag-bit round leaves its pair
- * untouched.  Pass null while `stream` is being captured into a graph. */
+ * untouched; a pair of null handles makes that round's launch a plain one.  Pass null while `stream` is being
+ * captured into a graph. */
 int32_t dq_run_rounds(const dq_problem *prob /*host*/, const dq_run_config *cfg /*host*/, const dq_run_state *st /*host*/,
                       int64_t epoch, int64_t t0, int64_t rounds, float eta, float theta,
                       void **worker_events /*host*/, void *stream);

@@ -407,7 +407,7 @@ def dq_mu_terms(x, x_snap, b, out) -> None:
 
 def dq_run_rounds(prob: DeviceProblem, cfg: RunConfig, state: RunState, epoch: int, t0: int, rounds: int,
                   eta: float, theta: float, worker_events=None) -> None:
-    """worker_events: optional list of 2*rounds raw hipEvent_t handles (ints)."""
+    """worker_events: optional list of 2*rounds raw hipEvent_t handles (ints; None for a round without events)."""
     ev = None
     if worker_events is not None:
         assert len(worker_events) == 2 * rounds

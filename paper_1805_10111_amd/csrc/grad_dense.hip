@@ -335,9 +335,19 @@ __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
     //      when the kernel starts, and every dependent request costs a trip to memory, so the feature rows -- the
     //      134 MB that the kernel exists to stream -- are requested before anything else: the row numbers need no
     //      memory (they are drawn here, lane j of every wavefront draws and keeps row j of the block, at most 64
-    //      rows per block; no shared memory and no barrier), the first batch of rows is requested, and only then the
-    //      model message, the snapshot, the scale, labels and cached margins, all without a condition and none of
-    //      them waited for before the second batch of rows is in flight too.
+    //      rows per block; no shared memory and no barrier), the first batch of rows is requested, and only then
+    //      labels and cached margins, all without a condition and none of them waited for before the second batch
+    //      of rows is in flight too.
+    //      The few small requests that depend on nothing at all -- the thread's columns of the model (message or
+    //      vector), of the snapshot, and the scale -- go out while the row numbers are being drawn: they are the
+    //      oldest requests, so the wait for them does not wait for rows, and the model is decoded (or quantized)
+    //      while the first rows are still on their way.
+    const int zero = opaque_zero();
+    // (b_x = 32: delta_x is a valid dummy address and the value unused; MODEL == 2: the scale is formed here)
+    const ModelMsg msg{a.xq, MODEL == 2 ? 0.0f : a.delta_x[zero], a.b_x};
+    ModelCols<NC> mc;
+    request_model_cols<NC, FULL, T, MODEL>(a, msg, zero, mc);
+    const bool store_model = MODEL == 2 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0;
     const int per = (a.B + a.P - 1) / a.P;
     const int r0 = part * per;
     const int nrows = max(0, min(a.B, r0 + per) - r0);        // at most kMaxRowsPerBlock = 64 (the host sees to it)
@@ -419,12 +429,6 @@ __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
     float4 row[R][NC];
     if (DB == 2 || plain) load_rows(0, row);
     else load_batch(0, row);
-    const int zero = opaque_zero();
-    // (b_x = 32: delta_x is a valid dummy address and the value unused; MODEL == 2: the scale is formed here)
-    const ModelMsg msg{a.xq, MODEL == 2 ? 0.0f : a.delta_x[zero], a.b_x};
-    ModelCols<NC> mc;
-    request_model_cols<NC, FULL, T, MODEL>(a, msg, zero, mc);
-    const bool store_model = MODEL == 2 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0;
     {
         const int i = max(my_row, 0);                          // lanes without a row ask for sample 0; nothing reads
         yv = a.y[i];                                           // their values (a select here would be the first use

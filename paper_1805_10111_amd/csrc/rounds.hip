@@ -87,7 +87,7 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
                 w.x_model = st->x;
                 w.absmax_model = st->absmax_x + ((t - 1) & 1);
             }
-            if (worker_events && g == 0) {
+            if (worker_events && g == 0) {                       // (a null pair: this round's launch is a plain one)
                 w.ev_start = static_cast<hipEvent_t>(worker_events[2 * (t - t0)]);
                 w.ev_stop = static_cast<hipEvent_t>(worker_events[2 * (t - t0) + 1]);
             }
