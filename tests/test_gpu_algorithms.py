@@ -198,6 +198,36 @@ def test_rounds_enqueued_together_equal_rounds_enqueued_one_by_one(dq, algo, b, 
     assert np.isfinite(host(a.x)).all() and host(a.x).any()
 
 
+@pytest.mark.parametrize("algo,b,M,B,b_x", [("asylpg", 8, 8, 32, 8), ("sparse", 4, 16, 64, 8), ("asylpg", 4, 3, 20, 4),
+                                            ("sparse", 8, 40, 16, 2), ("asylpg", 8, 8, 32, 11)])
+def test_rounds_enqueued_together_equal_rounds_enqueued_one_by_one_sparse_features(dq, algo, b, M, B, b_x):
+    """The same for CSR features (the shape of configs C2 and C3): with several rounds per call the worker kernel
+    quantizes the model itself, coordinate by coordinate where it gathers one, and must reproduce the messages,
+    scales and iterates of rounds enqueued one per call bit for bit."""
+    from paper_1805_10111_amd.driver import DoubleQuantTrainer
+    p = synth.make_problem(synth.CONFIGS["C2"], n=3000)
+    P = dq.DeviceProblem.from_host(p)
+    m = 6
+    runs = []
+    for together in (True, False):
+        tr = DoubleQuantTrainer(P, algo, M, B, b_x, b, m, 0.5, seed=4)
+        for _ in range(2):
+            tr.epoch_prologue()
+            if together:
+                tr.rounds(0, 4)
+                tr.rounds(4, m - 4)
+            else:
+                for t in range(m):
+                    tr.rounds(t, 1)
+            tr.epoch_epilogue()
+        torch.cuda.synchronize()
+        runs.append(tr)
+    a, c = runs
+    for name in ("x", "x_snap", "packed", "delta", "xq", "delta_x", "absmax_x", "nnz"):
+        assert torch.equal(getattr(a, name), getattr(c, name)), name
+    assert np.isfinite(host(a.x)).all() and host(a.x).any() and host(a.status)[0] == 0
+
+
 @pytest.mark.parametrize("name", ["C1", "C4", "C2"])
 def test_kernel_events_time_the_worker_kernel_and_change_nothing(dq, name):
     """dq_run_rounds with worker_events: each pair receives the start and end of the row-streaming kernel's launch
