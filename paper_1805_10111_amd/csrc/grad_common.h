@@ -42,6 +42,19 @@ __device__ __forceinline__ float expm1_small(float e)
     return e * p;
 }
 
+// The slope and the loss with the hardware exponential, reciprocal and logarithm (the row-streaming kernels evaluate
+// them on a few lanes while every other lane of the block waits).  Relative error of the slope about 1e-6 for
+// margins up to ~15; absolute error of the loss about 1e-7 -- both far inside the 1e-5 of the gradients and the
+// objective.
+__device__ __forceinline__ float logistic_slope_fast(float y, float z) { return -y * fast_rcp(1.0f + fast_exp(y * z)); }
+
+__device__ __forceinline__ float logistic_loss_fast(float m)
+{
+    // log(1 + exp(-|m|)) + max(-m, 0); the logarithm's argument lies in [1, 2]
+    const float t = __builtin_amdgcn_logf(1.0f + fast_exp(-fabsf(m))) * 0.693147180559945309f;
+    return t + fmaxf(-m, 0.0f);
+}
+
 // slope(z_snap + dz) - slope(z_snap): the scalar of the variance-reduced difference
 // grad f_i(q) - grad f_i(snapshot) (Alg. 1, worker (i)) along a_i.  When the model is
 // close to the snapshot the two slopes agree in most digits, so the difference is

@@ -577,30 +577,30 @@ int launch_worker_zero(const WorkerArgs &a, int64_t d, int64_t row_words, hipStr
 // then can a wait for one batch leave the loads of the next batch in flight (two row buffers).
 constexpr int kFullChunk = 1024;
 
-template <int NC, int R, bool FULL>
-__global__ __launch_bounds__(kRowThreads) void full_dense_partial_kernel(
+template <int NC, int R, bool FULL, int T = kRowThreads, bool STREAM = false>
+__global__ __launch_bounds__(T) void full_dense_partial_kernel(
     const float *__restrict__ X, int64_t lda, int64_t n, int64_t d, const float *__restrict__ yv,
     const float *__restrict__ x, float *__restrict__ z_out, float *__restrict__ partial, int64_t ldp,
     double *__restrict__ loss_partial)
 {
-    __shared__ float sh_red[2 * kRowWaves * R];
+    __shared__ float sh_red[2 * (T / kWave) * R];
     __shared__ float sh_y[kFullChunk], sh_z[kFullChunk];
     const int64_t per = (n + gridDim.x - 1) / gridDim.x;
     const int64_t i0 = blockIdx.x * per, i1 = min(n, i0 + per);
     float4 xv[NC], acc[NC];
     zero_cols<NC>(acc);
-    load_cols<NC, false, FULL>(x, d, xv);
-    const float fn = static_cast<float>(n);
+    load_cols<NC, false, FULL, T>(x, d, xv);
+    const float inv_n = 1.0f / static_cast<float>(n);
     double loss = 0.0;
     int buf = 0;
     auto load_rows = [&](int64_t ib, float4 (&row)[R][NC]) {          // rows ib .. ib+R-1 all exist
 #pragma unroll
-        for (int r = 0; r < R; ++r) load_cols<NC, false, FULL>(X + (ib + r) * lda, d, row[r]);
+        for (int r = 0; r < R; ++r) load_cols<NC, STREAM, FULL, T>(X + (ib + r) * lda, d, row[r]);
     };
     auto load_batch = [&](int64_t ib, float4 (&row)[R][NC]) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            if (ib + r < i1) load_cols<NC, false, FULL>(X + (ib + r) * lda, d, row[r]);
+            if (ib + r < i1) load_cols<NC, STREAM, FULL, T>(X + (ib + r) * lda, d, row[r]);
             else zero_cols<NC>(row[r]);
         }
     };
@@ -609,7 +609,7 @@ __global__ __launch_bounds__(kRowThreads) void full_dense_partial_kernel(
         float z[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) z[r] = dot_cols<NC>(row[r], xv);
-        block_sum_R<R>(z, sh_red, buf);
+        block_sum_R<R, T>(z, sh_red, buf);
         // lane r evaluates row rel + r (slope, loss) once; wave 0 also records margin and loss
         const int lane = threadIdx.x & (kWave - 1);
         float zl = z[0];
@@ -618,9 +618,9 @@ __global__ __launch_bounds__(kRowThreads) void full_dense_partial_kernel(
         float coef_l = 0.0f;
         if (lane < R && rel + lane < cn) {
             const float y = sh_y[rel + lane];
-            coef_l = logistic_slope(y, zl) / fn;
+            coef_l = logistic_slope_fast(y, zl) * inv_n;
             if (threadIdx.x < R) {
-                loss += static_cast<double>(logistic_loss(y * zl));
+                loss += static_cast<double>(logistic_loss_fast(y * zl));
                 sh_z[rel + lane] = zl;
             }
         }
@@ -632,7 +632,7 @@ __global__ __launch_bounds__(kRowThreads) void full_dense_partial_kernel(
     };
     for (int64_t c0 = i0; c0 < i1; c0 += kFullChunk) {
         const int cn = static_cast<int>(min<int64_t>(kFullChunk, i1 - c0));
-        for (int t = threadIdx.x; t < cn; t += kRowThreads) sh_y[t] = yv[c0 + t];
+        for (int t = threadIdx.x; t < cn; t += T) sh_y[t] = yv[c0 + t];
         __syncthreads();
         float4 rowA[R][NC], rowB[R][NC];
         const int fast = cn / (2 * R) * (2 * R);             // whole pairs of batches
@@ -656,10 +656,10 @@ __global__ __launch_bounds__(kRowThreads) void full_dense_partial_kernel(
         }
         __syncthreads();
         if (z_out)
-            for (int t = threadIdx.x; t < cn; t += kRowThreads) z_out[c0 + t] = sh_z[t];
+            for (int t = threadIdx.x; t < cn; t += T) z_out[c0 + t] = sh_z[t];
         __syncthreads();
     }
-    store_cols<NC>(partial + static_cast<int64_t>(blockIdx.x) * ldp, ldp, acc);
+    store_cols<NC, T>(partial + static_cast<int64_t>(blockIdx.x) * ldp, ldp, acc);
     if (threadIdx.x < kWave) {                       // lanes 0..R-1 of wave 0 hold the block's loss terms
         loss = wave_sum_f64(loss);
         if (threadIdx.x == 0) loss_partial[blockIdx.x] = loss;
@@ -764,9 +764,16 @@ int64_t dense_vr_splits(int64_t M, int64_t B, int64_t d)
     return P;
 }
 
-int64_t dense_full_splits(int64_t n)
+// rows whose every float4 column is whole for 512 threads: the widths with a 512-thread full-gradient kernel
+static bool dense_full_wide(int64_t d) { return d == 2048 || d == 4096 || d == 8192 || d == 16384; }
+
+int64_t dense_full_splits(int64_t n, int64_t d)
 {
     int64_t P = ceil_div(n, 16);
+    if (dense_full_wide(d)) {
+        if (P > 256) P = 256;       // one block of 512 threads per compute unit
+        return P < 1 ? 1 : P;
+    }
     if (P > 512) P = 512;           // two blocks per compute unit; 256 ... 2048 measured within 6 % of each other
     if (P < 1) P = 1;
     return P;
@@ -779,7 +786,7 @@ int64_t dense_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int
 {
     const int64_t ldp = pad4(prob->d);
     if (op == DQ_OP_FULL_GRAD) {
-        const int64_t P = dense_full_splits(prob->n);
+        const int64_t P = dense_full_splits(prob->n, prob->d);
         return P * ldp * 4 + P * 8;
     }
     // dq_run_rounds with a bounded delay runs the worker step on contiguous groups of the M workers with this same
@@ -797,7 +804,7 @@ int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float 
     if (nc == 0) return DQ_ERR_UNSUPPORTED;
     if (ws_bytes < dense_workspace_bytes(DQ_OP_FULL_GRAD, prob, 0, 0) || !ws) return DQ_ERR_WORKSPACE;
     const int64_t ldp = pad4(d);
-    const int P = static_cast<int>(dense_full_splits(n));
+    const int P = static_cast<int>(dense_full_splits(n, d));
     float *partial = static_cast<float *>(ws);
     double *loss_partial = reinterpret_cast<double *>(partial + static_cast<int64_t>(P) * ldp);
     const dim3 grid(P), block(kRowThreads);
@@ -807,6 +814,21 @@ int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float 
         if (full) full_dense_partial_kernel<NC, R, true><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); \
         else full_dense_partial_kernel<NC, R, false><<<grid, block, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial); \
     } while (0)
+    // Rows of 2048, 4096, 8192 or 16384 floats (every thread's columns whole): 512 threads per block, one block per
+    // compute unit, non-temporal loads.  Measured on 1.6-3.3 GB of rows against 256 threads, two blocks per unit and
+    // plain loads: 280 -> 240 us, 540 -> 479 us (6.84 TB/s), 282 -> 243 us, 294 -> 253 us.  (For other widths the
+    // same change is a loss -- 299 -> 439 us at 3000 floats -- and they keep the kernels below.)
+    if (dense_full_wide(d)) {
+        const dim3 b512(512);
+#define DQ_F512(NC, R) full_dense_partial_kernel<NC, R, true, 512, true><<<grid, b512, 0, st>>>(prob->dense, prob->lda, n, d, prob->y, x, z_out, partial, ldp, loss_partial)
+        if (nc == 2) DQ_F512(1, 8);
+        else if (nc == 4) DQ_F512(2, 4);
+        else if (nc == 8) DQ_F512(4, 2);
+        else DQ_F512(8, 1);
+#undef DQ_F512
+        DQ_LAUNCH_CHECK();
+        return launch_full_finish(partial, P, ldp, n, d, x, prob->l2, prob->l1, loss_partial, g_out, obj_out, st);
+    }
     switch (nc) {
     case 1: DQ_FULL(1, 8); break;
     case 2: DQ_FULL(2, 4); break;
@@ -922,10 +944,10 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     // against 61.7 us; at d = 1024 one buffer of 16 rows is faster (34.9 against 42.4 us).
     switch (nc) {
     case 1: launch_vr<1, 16>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
-    case 2: launch_vr<2, 4, true>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
-    case 4: launch_vr<2, 2, true, 512>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;   // 512 threads, 2 columns each
-    case 8: launch_vr<8, 1, true>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
-    default: launch_vr<16, 1, true>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
+    case 2: launch_vr<1, 4, true, 512>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;   // 512 threads from here on
+    case 4: launch_vr<2, 2, true, 512>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
+    case 8: launch_vr<4, 1, true, 512>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
+    default: launch_vr<8, 1, true, 512>(have_z, grid, st, k, a.ev_start, a.ev_stop); break;
     }
     DQ_LAUNCH_CHECK();
     if (k.P > 1 || nc > 4) {

@@ -120,7 +120,7 @@ def test_workspace_sizes(lib):
     full = lib.dq_workspace_bytes(1, C.byref(p), 0, 0)
     vr = lib.dq_workspace_bytes(2, C.byref(p), 32, 256)
     assert full % 16 == 0 and vr % 16 == 0
-    assert full >= 512 * 4096 * 4                      # up to 512 partial d-vectors
+    assert full >= 256 * 4096 * 4                      # 256 partial d-vectors at this width (up to 512 at others)
     assert vr >= 32 * 8 * 4096 * 4                     # M * P * d floats with P = 256/M blocks per worker at d = 4096
     # ... and no less than any smaller group of the workers needs (a delayed run steps the groups with this workspace)
     assert all(lib.dq_workspace_bytes(2, C.byref(p), g, 256) <= vr for g in range(1, 33))
