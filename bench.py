@@ -115,29 +115,70 @@ def time_round_loop(tr, torch, steps, warmup):
             "warm_rounds": max(warmup, MIN_WARM_EPOCHS * m)}
 
 
+class _TimingEvents:
+    """HIP events made for timing only (hipEventDisableSystemFence), straight from the HIP runtime the process already
+    has loaded.  A launch whose stop event is an ordinary one ends with a system-scope release of the caches, which a
+    plain launch does not, and reads about a microsecond longer; with this flag the launch that carries the events
+    is the launch the timed region runs.  torch.cuda.Event cannot set the flag."""
+    DISABLE_SYSTEM_FENCE = 0x20000000
+
+    def __init__(self):
+        import ctypes
+        path = None
+        for line in open("/proc/self/maps"):
+            if "libamdhip64" in line:
+                path = line.split()[-1]
+                break
+        if path is None:
+            raise OSError("the HIP runtime is not loaded")
+        self.C, self.hip, self.handles = ctypes, ctypes.CDLL(path), []
+
+    def new(self):
+        e = self.C.c_void_p()
+        rc = self.hip.hipEventCreateWithFlags(self.C.byref(e), self.C.c_uint(self.DISABLE_SYSTEM_FENCE))
+        if rc != 0:
+            raise OSError(f"hipEventCreateWithFlags returned {rc}")
+        self.handles.append(e)
+        return e
+
+    def elapsed_s(self, e0, e1):
+        ms = self.C.c_float()
+        rc = self.hip.hipEventElapsedTime(self.C.byref(ms), e0, e1)
+        if rc != 0:
+            raise OSError(f"hipEventElapsedTime returned {rc}")
+        return ms.value * 1e-3
+
+    def close(self):
+        for e in self.handles:
+            self.hip.hipEventDestroy(e)
+        self.handles = []
+
+
 def kernel_durations(tr, epochs, stride):
     """Own duration of the dominant kernel (the one that streams the feature rows of all M workers): in `epochs`
     further epochs, each enqueued by one call like the timed region, every `stride`-th round hands the library two
     events, which it uses as the start and stop events of that launch (hipExtLaunchKernel), i.e. the kernel's time
     stamps on the launch stream.  Flag-bit rounds read no rows and are skipped.  Returns seconds per launch (list)."""
     import torch
-    events = []
+    ev = _TimingEvents()
+    pairs = []
     for _ in range(epochs):
         assert tr._t == 0
         tr.epoch_prologue()
         handles = []
         for t in range(tr.m):
             if t % stride == stride - 1 and not tr.is_flag_round(t):
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record(); e1.record()            # instantiates the HIP events; the launch overwrites them
-                events.append((e0, e1))
-                handles += [e0.cuda_event, e1.cuda_event]
+                e0, e1 = ev.new(), ev.new()
+                pairs.append((e0, e1))
+                handles += [e0.value, e1.value]
             else:
                 handles += [None, None]
         tr.rounds(0, tr.m, handles)
         tr.epoch_epilogue()
     torch.cuda.synchronize()
-    return [e0.elapsed_time(e1) * 1e-3 for e0, e1 in events]
+    out = [ev.elapsed_s(e0, e1) for e0, e1 in pairs]
+    ev.close()
+    return out
 
 
 def recorded_traffic(workload: str):
