@@ -191,6 +191,33 @@ __device__ __forceinline__ uint32_t block_max_u32(uint32_t v, uint32_t *scratch)
     return r;
 }
 
+// ---- values left per slice by several producers of one row -----------------------
+// A row's largest magnitude / count arrives as up to kMaxParts values.  All of them are requested at once (an index
+// past the last one re-reads the last one): a loop that stops at `parts` would wait for every load before the next.
+constexpr int kMaxParts = 8;
+
+__device__ __forceinline__ float parts_absmax(const float *__restrict__ v, int parts)
+{
+    float t[kMaxParts];
+#pragma unroll
+    for (int s = 0; s < kMaxParts; ++s) t[s] = v[min(s, parts - 1)];
+    float amax = t[0];                 // (magnitudes compare like their bit patterns, and so does a NaN)
+#pragma unroll
+    for (int s = 1; s < kMaxParts; ++s) amax = __float_as_uint(t[s]) > __float_as_uint(amax) ? t[s] : amax;
+    return amax;
+}
+
+__device__ __forceinline__ int parts_sum(const int32_t *__restrict__ v, int parts)
+{
+    int t[kMaxParts];
+#pragma unroll
+    for (int s = 0; s < kMaxParts; ++s) t[s] = v[min(s, parts - 1)];
+    int sum = 0;
+#pragma unroll
+    for (int s = 0; s < kMaxParts; ++s) sum += s < parts ? t[s] : 0;
+    return sum;
+}
+
 __device__ __forceinline__ double block_sum_f64(double v, double *scratch)
 {
     v = wave_sum_f64(v);

@@ -533,7 +533,7 @@ static int64_t csr_full_splits(int64_t n)
     return P;
 }
 
-constexpr int kMaxSlices = 8;       // identical blocks per worker that share the tail of a worker step
+constexpr int kMaxSlices = kMaxParts;       // identical blocks per worker that share the tail of a worker step
 
 int64_t csr_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64_t)
 {
@@ -631,6 +631,11 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     else
         csr_worker_kernel<<<dim3(static_cast<unsigned>(a.M), slices), dim3(kCsrThreads), lds, st>>>(k);
     DQ_LAUNCH_CHECK();
+    if (a.deferred) *a.deferred = SparsifiedParts{nullptr, 0, nullptr, nullptr, 0};
+    if (split_sparsifier && a.deferred) {             // the master quantizes while it aggregates
+        *a.deferred = SparsifiedParts{k.beta_ws, k.ld_ws, k.part_max, k.part_kept, static_cast<int>(slices)};
+        return DQ_OK;
+    }
     if (split_sparsifier)
         return launch_quantize_pack_parts(k.beta_ws, d, a.M, k.ld_ws, a.b, a.b, k.part_max, static_cast<int>(slices),
                                           a.nnz_out ? k.part_kept : nullptr, a.nnz_out, k.key, a.worker0, a.packed,

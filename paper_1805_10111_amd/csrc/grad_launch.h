@@ -5,6 +5,13 @@
 
 namespace dq {
 
+// M sparsified gradients as the split sparsifier leaves them in the workspace: rows of ld floats, and per worker
+// `parts` slice maxima (the scale is ||beta||_inf, their largest) and kept counts.
+struct SparsifiedParts {
+    const float *beta; int64_t ld;
+    const float *part_max; const int32_t *part_kept; int parts;
+};
+
 struct WorkerArgs {
     const int32_t *idx;
     int64_t M, B;
@@ -40,6 +47,11 @@ struct WorkerArgs {
     // quantizing the 20958-coordinate model for itself, and again per gathered entry, made the worker kernel 4.5 us
     // longer, more than the 4.2 us launch it saves -- not kept.)
     const float *x_model, *absmax_model;
+    // Alg. 2 with the sparsifier split over several blocks per worker (CSR features): when `deferred` is given and the
+    // step takes that route, it stops after the sparsifier -- no message is quantized, `packed`, `delta_out` and
+    // `nnz_out` stay untouched -- and describes what it left in *deferred for master_step_from_parts_impl, which
+    // quantizes while it aggregates.  deferred->parts == 0 on return: the step was a complete one.
+    SparsifiedParts *deferred;
 };
 
 // Whether the dense worker step can take the model from x_model (see WorkerArgs) for this shape.
@@ -60,6 +72,16 @@ int32_t master_step_impl(const uint32_t *packed, int64_t ld_words, const float *
                          float theta, float l1, int64_t d, int32_t b_x, uint64_t seed, uint32_t iter,
                          uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out, uint32_t *status,
                          bool absmax_zeroed, void *stream);
+
+// The master step of a round of Alg. 2 whose workers deferred their quantization (WorkerArgs::deferred): one kernel
+// quantizes the M sparsified gradients with the workers' streams (seed, worker_iter, worker0 + m, DQ_TAG_GRAD), stores the
+// messages, scales and nonzero counts exactly as the worker step would have, and applies the master update; the model
+// quantization follows as in master_step_impl.  nnz_out nullable.
+int32_t master_step_from_parts_impl(const SparsifiedParts &parts, uint32_t worker0, uint32_t worker_iter, uint32_t *packed, int64_t ld_words,
+                                    float *delta_out, int32_t *nnz_out, int64_t M, int32_t b, float scale, int each,
+                                    const float *g_snap, float *x, float eta, float l1, int64_t d, int32_t b_x,
+                                    uint64_t seed, uint32_t iter, uint32_t *xq_packed_out, float *delta_x_out,
+                                    float *absmax_x_out, uint32_t *status, bool absmax_zeroed, void *stream);
 
 int64_t dense_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64_t B);
 int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float *z_out, double *obj_out, void *ws,

@@ -151,6 +151,139 @@ static int launch_master_update(bool acc, dim3 grid, hipStream_t st, const Maste
     return DQ_OK;
 }
 
+// ------------------------------------------------------------------ Alg. 2: quantization inside the master update
+// The workers of a round left their sparsified gradients beta_m unquantized (SparsifiedParts).  A block of 16 x 16
+// threads takes 16 quads of the model: thread (worker lane, quad lane) quantizes its worker's quad -- scale
+// ||beta_m||_inf from the slice maxima, the worker's own Philox stream -- stores the message bits and leaves the four
+// codes in LDS; after the barrier the threads of worker lane 0 aggregate delta_m * code_m in worker order and
+// update the model exactly as master_quad does.  More than 16 workers take several passes over two LDS buffers.
+constexpr int kPartsWorkers = 16, kPartsQuads = 16;
+
+struct PartsArgs {
+    SparsifiedParts in;
+    int b; StreamKey key; uint32_t worker0;
+    uint32_t *packed;                                    // rows of MasterArgs::ld_words words
+    float *delta_out; int32_t *nnz_out; uint32_t *status;
+};
+
+template <int FIELD, bool EACH>
+__global__ __launch_bounds__(kPartsWorkers * kPartsQuads) void master_from_parts_kernel(const MasterArgs a, const PartsArgs p,
+                                                                                       uint32_t *__restrict__ absmax_bits)
+{
+    __shared__ float4 codes[2][kPartsWorkers][kPartsQuads];
+    __shared__ float deltas[2][kPartsWorkers];
+    const int ql = threadIdx.x % kPartsQuads, wl = threadIdx.x / kPartsQuads;
+    const int64_t d = a.d, quads = (d + 3) / 4;
+    if (blockIdx.x == gridDim.x - 1) {
+        // one block more than the quads need: what a worker step reports per message (scale, status, nonzeros =
+        // coordinates its sparsifier kept), off the path of the blocks that do the arithmetic
+        for (int m = threadIdx.x; m < a.M; m += kPartsWorkers * kPartsQuads) {
+            const Scale s = make_scale(parts_absmax(p.in.part_max + static_cast<int64_t>(m) * p.in.parts, p.in.parts), p.b);
+            p.delta_out[m] = s.delta;
+            if (s.bad && p.status) atomicOr(p.status, 1u);
+            if (p.nnz_out) p.nnz_out[m] = parts_sum(p.in.part_kept + static_cast<int64_t>(m) * p.in.parts, p.in.parts);
+        }
+        return;
+    }
+    const int64_t q = static_cast<int64_t>(blockIdx.x) * kPartsQuads + ql;
+    const bool inside = q < quads;
+    constexpr int kB = CodeBias<FIELD>::value;
+    float gs[4] = {0.0f, 0.0f, 0.0f, 0.0f}, xn[4] = {0.0f, 0.0f, 0.0f, 0.0f}, acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    float unused_y[4] = {0.0f, 0.0f, 0.0f, 0.0f}, unused_s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    const float unused_xs[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (wl == 0 && inside) {
+        // requested here, looked at only after the first barrier: whole quads, or single elements at clamped
+        // positions where the vector ends inside the quad (what was read past d is discarded there)
+        const int64_t i = 4 * q, last = d - 1;
+        if ((d & 3) == 0) {
+            const float4 g4 = reinterpret_cast<const float4 *>(a.g_snap)[q], x4 = reinterpret_cast<const float4 *>(a.x)[q];
+            gs[0] = g4.x; gs[1] = g4.y; gs[2] = g4.z; gs[3] = g4.w;
+            xn[0] = x4.x; xn[1] = x4.y; xn[2] = x4.z; xn[3] = x4.w;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                gs[e] = a.g_snap[min(i + e, last)];
+                xn[e] = a.x[min(i + e, last)];
+            }
+        }
+    }
+    for (int m0 = 0; m0 < a.M; m0 += kPartsWorkers) {
+        const int buf = (m0 / kPartsWorkers) & 1;
+        const int m = m0 + wl;
+        const bool live = m < a.M;
+        float4 c = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        uint32_t bits = 0;
+        if (live) {
+            // everything is requested before anything is waited for: slice maxima and the quad; the random bits do
+            // not depend on either
+            const float amax = parts_absmax(p.in.part_max + static_cast<int64_t>(m) * p.in.parts, p.in.parts);
+            // (rows are padded to whole quads; what lies past d is not part of the vector)
+            float4 v = reinterpret_cast<const float4 *>(p.in.beta + static_cast<int64_t>(m) * p.in.ld)[inside ? q : 0];
+            v.y = 4 * q + 1 < d ? v.y : 0.0f;
+            v.z = 4 * q + 2 < d ? v.z : 0.0f;
+            v.w = 4 * q + 3 < d ? v.w : 0.0f;
+            StreamKey key = p.key;
+            key.worker = p.worker0 + static_cast<uint32_t>(m);
+            const uint4 r = stream_block(key, static_cast<uint32_t>(q));
+            const Scale s = make_scale(amax, p.b);
+            if (ql == 0) deltas[buf][wl] = s.delta;
+            if (inside && s.inv_delta != 0.0f) {         // (a degenerate scale: every code is zero)
+                const int k0 = quantize_one<kB>(v.x, s, r.x), k1 = quantize_one<kB>(v.y, s, r.y);
+                const int k2 = quantize_one<kB>(v.z, s, r.z), k3 = quantize_one<kB>(v.w, s, r.w);
+                bits = pack4<FIELD, true, FIELD != 8>(k0, k1, k2, k3);
+                c = make_float4(static_cast<float>(k0 - kB), static_cast<float>(k1 - kB), static_cast<float>(k2 - kB),
+                                static_cast<float>(k3 - kB));
+            }
+        }
+        // (every lane makes the call; the lanes that share a word belong to one worker and to neighbouring quads)
+        store_quad_bits<FIELD>(bits, live ? q : quads, quads, p.packed + static_cast<int64_t>(live ? m : 0) * a.ld_words);
+        codes[buf][wl][ql] = c;
+        __syncthreads();
+        if (wl == 0 && inside) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (4 * q + e >= d) gs[e] = xn[e] = 0.0f;
+            const auto apply = [&](int u) {
+                const float4 v = codes[buf][u][ql];
+                const float dm = deltas[buf][u];
+                const float vv[4] = {v.x, v.y, v.z, v.w};
+                if (EACH) {
+                    const float dir[4] = {dm * vv[0] + gs[0], dm * vv[1] + gs[1], dm * vv[2] + gs[2], dm * vv[3] + gs[3]};
+                    master_apply_quad<false>(dir, xn, unused_y, unused_xs, unused_s, false, a.eta, a.theta, a.kappa);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[e] = fmaf(dm, vv[e], acc[e]);
+                }
+            };
+            const int count = min(kPartsWorkers, a.M - m0);
+            if (count == kPartsWorkers) {                // a full pass: all LDS reads go out together
+#pragma unroll
+                for (int u = 0; u < kPartsWorkers; ++u) apply(u);
+            } else {
+                for (int u = 0; u < count; ++u) apply(u);
+            }
+        }
+    }
+    uint32_t amax = 0;
+    if (wl == 0 && inside) {
+        if (!EACH) {
+            const float dir[4] = {a.scale * acc[0] + gs[0], a.scale * acc[1] + gs[1], a.scale * acc[2] + gs[2],
+                                  a.scale * acc[3] + gs[3]};
+            master_apply_quad<false>(dir, xn, unused_y, unused_xs, unused_s, false, a.eta, a.theta, a.kappa);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (4 * q + e >= d) xn[e] = 0.0f;
+        const float4 x4 = make_float4(xn[0], xn[1], xn[2], xn[3]);
+        store_quad(a.x, q, d, x4);
+        amax = quad_abs_bits(x4);
+    }
+    if (threadIdx.x < kWave) {                           // (worker lane 0 lies in the first wavefront)
+        amax = wave_max_u32(amax);
+        if (threadIdx.x == 0 && amax != 0) atomicMax(absmax_bits, amax);
+    }
+}
+
 // ------------------------------------------------------------------ fused master step, one block
 // For d <= kFusedMaxD the whole master step is one block of 1024 threads: thread t owns the quads
 // (four consecutive coordinates) t and t+1024 of the model, keeps their updated values in
@@ -375,6 +508,21 @@ static int32_t check_master_args(const uint32_t *packed, int64_t ld_words, const
     return DQ_OK;
 }
 
+// Alg. 1, master (i) once ||x||_inf is known: the message (and its scale) of the updated model.
+static int model_message(const float *x, int64_t d, int32_t b_x, const StreamKey &key, uint32_t *xq_packed_out,
+                         float *delta_x_out, const float *absmax_x, uint32_t *status, hipStream_t st)
+{
+    if (b_x == 32) {
+        // full-precision model: "packed" output is x itself, delta is 1
+        copy_f32_kernel<<<dim3(static_cast<unsigned>(ceil_div(d, kThreads))), dim3(kThreads), 0, st>>>(
+            x, reinterpret_cast<float *>(xq_packed_out), d);
+        DQ_LAUNCH_CHECK();
+        return fill_u32(reinterpret_cast<uint32_t *>(delta_x_out), 1, 0x3F800000u, st);
+    }
+    return launch_quantize_pack(x, d, 1, d, b_x, b_x, absmax_x, key, DQ_MASTER_ID, xq_packed_out,
+                                packed_words(d, b_x), delta_x_out, status, st);
+}
+
 // One wavefront per block: at d = 4096 the 1024 quads of the model are 16 blocks on 16 compute units.
 constexpr int kRoundThreads = 64;
 
@@ -440,15 +588,43 @@ int32_t dq::master_step_impl(const uint32_t *packed, int64_t ld_words, const flo
     default: rc = launch_master_update<32>(acc, grid, st, a, absmax_bits); break;
     }
     if (rc != DQ_OK) return rc;
-    if (b_x == 32) {
-        // full-precision model: "packed" output is x itself, delta is 1
-        copy_f32_kernel<<<dim3(static_cast<unsigned>(ceil_div(d, kThreads))), dim3(kThreads), 0, st>>>(
-            x, reinterpret_cast<float *>(xq_packed_out), d);
-        DQ_LAUNCH_CHECK();
-        return fill_u32(reinterpret_cast<uint32_t *>(delta_x_out), 1, 0x3F800000u, st);
+    return model_message(x, d, b_x, key, xq_packed_out, delta_x_out, absmax_x_out, status, st);
+}
+
+int32_t dq::master_step_from_parts_impl(const SparsifiedParts &parts, uint32_t worker0, uint32_t worker_iter, uint32_t *packed, int64_t ld_words,
+                                        float *delta_out, int32_t *nnz_out, int64_t M, int32_t b, float scale, int each,
+                                        const float *g_snap, float *x, float eta, float l1, int64_t d, int32_t b_x,
+                                        uint64_t seed, uint32_t iter, uint32_t *xq_packed_out, float *delta_x_out,
+                                        float *absmax_x_out, uint32_t *status, bool absmax_zeroed, void *stream)
+{
+    int32_t rc0 = check_master_args(packed, ld_words, delta_out, M, b, g_snap, x, nullptr, nullptr, nullptr, d);
+    if (rc0 != DQ_OK) return rc0;
+    if (b == 32 || !parts.beta || !parts.part_max || !parts.part_kept || parts.parts <= 0 || parts.parts > kMaxParts || parts.ld < (d + 3) / 4 * 4 ||
+        parts.ld % 4 != 0 || !aligned16(parts.beta))
+        return DQ_ERR_INVALID_ARG;
+    if (!xq_packed_out || !delta_x_out || !absmax_x_out || !aligned16(xq_packed_out)) return DQ_ERR_INVALID_ARG;
+    if (b_x < 2 || (b_x > 16 && b_x != 32)) return DQ_ERR_INVALID_ARG;
+    hipStream_t st = as_stream(stream);
+    const MasterArgs a{packed, ld_words, packed_words(d, b), delta_out, static_cast<int>(M), scale, each, g_snap,
+                       x, nullptr, nullptr, nullptr, eta, 0.0f, eta * l1, d};
+    const StreamKey wkey{static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), worker_iter, 0u, DQ_TAG_GRAD};
+    const PartsArgs p{parts, b, wkey, worker0, packed, delta_out, nnz_out, status};
+    uint32_t *absmax_bits = reinterpret_cast<uint32_t *>(absmax_x_out);
+    int rc = absmax_zeroed ? DQ_OK : fill_u32(absmax_bits, 1, 0u, st);
+    if (rc != DQ_OK) return rc;
+    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(d, 4), kPartsQuads)) + 1u), block(kPartsWorkers * kPartsQuads);
+#define DQ_PARTS(FIELD)                                                                        \
+    if (each) master_from_parts_kernel<FIELD, true><<<grid, block, 0, st>>>(a, p, absmax_bits); \
+    else master_from_parts_kernel<FIELD, false><<<grid, block, 0, st>>>(a, p, absmax_bits)
+    switch (b) {
+    case 8: DQ_PARTS(8); break;
+    case 4: DQ_PARTS(4); break;
+    default: DQ_PARTS(2); break;
     }
-    return launch_quantize_pack(x, d, 1, d, b_x, b_x, absmax_x_out, key, DQ_MASTER_ID, xq_packed_out,
-                                packed_words(d, b_x), delta_x_out, status, st);
+#undef DQ_PARTS
+    DQ_LAUNCH_CHECK();
+    const StreamKey key{static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), iter, 0u, DQ_TAG_MODEL};
+    return model_message(x, d, b_x, key, xq_packed_out, delta_x_out, absmax_x_out, status, st);
 }
 
 extern "C" int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,

@@ -299,21 +299,14 @@ __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(
     uint32_t *out = packed + static_cast<int64_t>(m) * ld_words;
     // the largest magnitude of row m, or the largest of the `parts` values that the producers of its slices left
     // (magnitudes compare like their bit patterns, and so does a NaN that has to reach the status word)
-    float amax = absmax[static_cast<int64_t>(m) * parts];
-    for (int p = 1; p < parts; ++p) {
-        const float t = absmax[static_cast<int64_t>(m) * parts + p];
-        amax = __float_as_uint(t) > __float_as_uint(amax) ? t : amax;
-    }
+    const float amax = parts_absmax(absmax + static_cast<int64_t>(m) * parts, parts);
     const Scale s = make_scale(amax, b);
     key.worker = worker0 + static_cast<uint32_t>(m);
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         delta_out[m] = s.delta;
         if (s.bad && status) atomicOr(status, 1u);
-        if (count_out) {                                   // a per-slice count summed on the way (see csr_worker)
-            int c = 0;
-            for (int p = 0; p < parts; ++p) c += count_parts[static_cast<int64_t>(m) * parts + p];
-            count_out[m] = c;
-        }
+        // a per-slice count summed on the way (see csr_worker)
+        if (count_out) count_out[m] = parts_sum(count_parts + static_cast<int64_t>(m) * parts, parts);
     }
     __shared__ float4 tiles[kThreads / kWave][kTileSlots];
     const int lane = threadIdx.x & (kWave - 1);
@@ -356,6 +349,7 @@ int launch_quantize_pack_parts(const float *v, int64_t d, int64_t M, int64_t ld,
                                uint32_t worker0, uint32_t *packed, int64_t ld_words, float *delta_out, uint32_t *status,
                                hipStream_t st)
 {
+    if (parts < 1 || parts > kMaxParts) return DQ_ERR_INVALID_ARG;
     const int64_t row_words = packed_words(d, field);
     const dim3 grid = grid_for(d, M), block(kThreads);
     switch (field) {

@@ -48,6 +48,9 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
     // The two slots of absmax_x alternate: the kernel that reads one clears the other for the master of its round.
     const bool fusable = cfg->tau == 0 && cfg->b_x != 32 &&
                          dq::dense_model_fusable(prob, cfg->M, cfg->B, cfg->b_x, st->z_snap != nullptr);
+    // Alg. 2, one group of workers, messages not crossing as (position, value) streams: a worker step whose sparsifier
+    // is split over several blocks leaves the quantization of its messages to the master kernel (one launch less)
+    const bool defer_ok = cfg->algo == DQ_ALGO_SPARSE && cfg->b != 32 && cfg->tau == 0 && !st->wire;
     bool model_pending = false;          // the model of this round is still x itself (not yet a message)
     for (int64_t t = t0; t < t0 + rounds; ++t) {
         const uint32_t it = static_cast<uint32_t>(epoch * cfg->m + t);
@@ -66,6 +69,7 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
             }
         }
         // worker side: group g of the workers is g rounds behind (g = 0 only when tau = 0)
+        dq::SparsifiedParts parts{nullptr, 0, nullptr, nullptr, 0};
         for (int64_t g = 0; g < slots; ++g) {
             const int64_t w_lo = dq::ceil_div(g * cfg->M, slots), w_hi = dq::ceil_div((g + 1) * cfg->M, slots);
             if (w_hi <= w_lo) continue;
@@ -87,6 +91,7 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
                 w.x_model = st->x;
                 w.absmax_model = st->absmax_x + ((t - 1) & 1);
             }
+            if (defer_ok) w.deferred = &parts;
             if (worker_events && g == 0) {                       // (a null pair: this round's launch is a plain one)
                 w.ev_start = static_cast<hipEvent_t>(worker_events[2 * (t - t0)]);
                 w.ev_stop = static_cast<hipEvent_t>(worker_events[2 * (t - t0) + 1]);
@@ -105,7 +110,13 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
         uint32_t *xq_next = st->xq + ((t + 1) % slots) * st->xq_stride_words;
         float *dx_next = st->delta_x + ((t + 1) % slots);
         model_pending = fusable && t + 1 < t0 + rounds;
-        if (model_pending)
+        if (parts.parts > 0)
+            rc = dq::master_step_from_parts_impl(parts, 0u, it, st->packed, st->ld_words, st->delta,
+                                                 st->nnz ? st->nnz + t * cfg->M : nullptr, cfg->M, cfg->b, scale, cfg->each,
+                                                 st->g_snap, st->x, eta, prob->l1, prob->d, cfg->b_x, cfg->seed, it + 1u,
+                                                 xq_next, dx_next, st->absmax_x + (t & 1), st->status,
+                                                 /*absmax_zeroed=*/true, stream);
+        else if (model_pending)
             rc = dq::master_update_impl(st->packed, st->ld_words, st->delta, cfg->M, cfg->b, scale, cfg->each, st->g_snap,
                                         st->x, acc ? st->y : nullptr, st->x_snap, acc ? st->xsum : nullptr, eta, theta,
                                         prob->l1, prob->d, reinterpret_cast<uint32_t *>(st->absmax_x + (t & 1)), stream);

@@ -228,6 +228,40 @@ def test_rounds_enqueued_together_equal_rounds_enqueued_one_by_one_sparse_featur
     assert np.isfinite(host(a.x)).all() and host(a.x).any() and host(a.status)[0] == 0
 
 
+@pytest.mark.parametrize("b,M,each,b_x", [(4, 16, False, 8), (8, 24, False, 8), (4, 5, True, 4), (8, 32, True, 32),
+                                           (2, 8, False, 8)])
+def test_master_that_quantizes_the_sparsified_gradients_equals_the_separate_steps(dq, b, M, each, b_x):
+    """Alg. 2 on CSR features wide enough for the sparsifier to be split over several blocks per worker: inside
+    dq_run_rounds the master kernel quantizes the workers' sparsified gradients while it aggregates them.  A round
+    enqueued that way must leave messages, scales, nonzero counts, the model and the model's message bit for bit
+    as dq_worker_step followed by dq_master_step do, which quantize in a launch of their own (M = 24 and 32: more
+    workers than one pass of the kernel takes; b = 2: the route is not taken, both sides are the separate steps)."""
+    from paper_1805_10111_amd.driver import DoubleQuantTrainer
+    p = synth.make_problem(synth.CONFIGS["C3"], n=3000)
+    P = dq.DeviceProblem.from_host(p)
+    B, m, seed = 32, 4, 9
+    one = DoubleQuantTrainer(P, "sparse", M, B, b_x, b, m, 0.5, seed=seed, each=each)
+    two = DoubleQuantTrainer(P, "sparse", M, B, b_x, b, m, 0.5, seed=seed, each=each)
+    one.epoch_prologue(); two.epoch_prologue()
+    one.rounds(0, 3)
+    idx = torch.empty(M * B, dtype=torch.int32, device="cuda")
+    for t in range(3):
+        if t == 0:
+            two.rounds(0, 1)                               # (the model is the snapshot: all-zero messages)
+            continue
+        dq.dq_sample_indices(P.n, M, B, seed, t, 0, idx)
+        dq.dq_worker_step(P, idx, M, B, two.xq, two.delta_x, b_x, False, two.x_snap, two.z_snap, True, b, seed, t, 0,
+                          two.packed, two.delta, nnz_out=two.nnz[t], status=two.status, ws=two.ws)
+        step = dq.dq_master_step_each if each else dq.dq_master_step
+        args = (two.packed, two.delta, M, b) + (() if each else (float(np.float32(1) / np.float32(M)),))
+        step(*args, two.g_snap, two.x, None, two.x_snap, None, two.eta, 0.0, P.l1, b_x, seed, t + 1,
+             two.xq, two.delta_x, two.absmax_x[t & 1:], two.status)
+    torch.cuda.synchronize()
+    for name in ("packed", "delta", "nnz", "x", "xq", "delta_x", "status"):
+        assert torch.equal(getattr(one, name), getattr(two, name)), name
+    assert host(one.x).any() and host(one.packed).any() and host(one.nnz)[1:3].all() and host(one.status)[0] == 0
+
+
 @pytest.mark.parametrize("name", ["C1", "C4", "C2"])
 def test_kernel_events_time_the_worker_kernel_and_change_nothing(dq, name):
     """dq_run_rounds with worker_events: each pair receives the start and end of the row-streaming kernel's launch
