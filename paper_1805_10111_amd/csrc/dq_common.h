@@ -178,17 +178,37 @@ __device__ __forceinline__ double wave_sum_f64(double v)
     return v;
 }
 
-// Block-wide max of a uint32; `scratch` has >= blockDim.x/64 entries. Result in all threads.
+// Block-wide reductions; `scratch` has >= blockDim.x/64 entries (at most 64 wavefronts).  Result in all threads.
+// Every wavefront leaves its value in scratch, then every wavefront reduces those (one LDS read per lane and a second
+// cross-lane reduction) -- a loop over scratch would wait for one LDS read after the other.
 __device__ __forceinline__ uint32_t block_max_u32(uint32_t v, uint32_t *scratch)
 {
     v = wave_max_u32(v);
-    const int wave = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
     __syncthreads();
-    if ((threadIdx.x & (kWave - 1)) == 0) scratch[wave] = v;
+    if (lane == 0) scratch[wave] = v;
     __syncthreads();
-    uint32_t r = scratch[0];
-    for (int w = 1; w < nw; ++w) r = max(r, scratch[w]);
-    return r;
+    return wave_max_u32(lane < nw ? scratch[lane] : 0u);
+}
+
+__device__ __forceinline__ double block_sum_f64(double v, double *scratch)
+{
+    v = wave_sum_f64(v);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
+    __syncthreads();
+    if (lane == 0) scratch[wave] = v;
+    __syncthreads();
+    return wave_sum_f64(lane < nw ? scratch[lane] : 0.0);
+}
+
+__device__ __forceinline__ int block_sum_i32(int v, int *scratch)
+{
+    v = wave_sum_i32(v);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
+    __syncthreads();
+    if (lane == 0) scratch[wave] = v;
+    __syncthreads();
+    return wave_sum_i32(lane < nw ? scratch[lane] : 0);
 }
 
 // ---- values left per slice by several producers of one row -----------------------
@@ -216,30 +236,6 @@ __device__ __forceinline__ int parts_sum(const int32_t *__restrict__ v, int part
 #pragma unroll
     for (int s = 0; s < kMaxParts; ++s) sum += s < parts ? t[s] : 0;
     return sum;
-}
-
-__device__ __forceinline__ double block_sum_f64(double v, double *scratch)
-{
-    v = wave_sum_f64(v);
-    const int wave = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
-    __syncthreads();
-    if ((threadIdx.x & (kWave - 1)) == 0) scratch[wave] = v;
-    __syncthreads();
-    double r = scratch[0];
-    for (int w = 1; w < nw; ++w) r += scratch[w];
-    return r;
-}
-
-__device__ __forceinline__ int block_sum_i32(int v, int *scratch)
-{
-    v = wave_sum_i32(v);
-    const int wave = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
-    __syncthreads();
-    if ((threadIdx.x & (kWave - 1)) == 0) scratch[wave] = v;
-    __syncthreads();
-    int r = scratch[0];
-    for (int w = 1; w < nw; ++w) r += scratch[w];
-    return r;
 }
 
 // Sign-extended bit field [offset, offset+width) of a word.  (The builtin returns its

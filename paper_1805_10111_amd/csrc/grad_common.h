@@ -160,6 +160,8 @@ __device__ __forceinline__ float4 load4_or_zero(const float *__restrict__ v, int
 // slice only, writes them to beta_row (memory) and leaves the slice's largest magnitude and its number of kept
 // coordinates in part_max[0], part_kept[0]; a later kernel (quantize_pack_kernel with parts) combines the slices.  The
 // slice boundaries are those of worker_tail_from_lds.  su, si: one entry per wavefront of the block.
+// WHOLE: alpha is padded with zeros to whole quads (read as 16-byte values without a test per lane).
+template <bool WHOLE = false>
 __device__ __forceinline__ void sparsify_slice_from_lds(const float *alpha, int64_t d, StreamKey key, int slice, int nslices,
                                                         float *__restrict__ beta_row, float *__restrict__ part_max,
                                                         int32_t *__restrict__ part_kept, uint32_t *su, int *si)
@@ -167,9 +169,10 @@ __device__ __forceinline__ void sparsify_slice_from_lds(const float *alpha, int6
     const int64_t quads = (d + 3) / 4;
     const int64_t per = ((quads + nslices - 1) / nslices + kWave - 1) / kWave * kWave;
     const int64_t q_lo = min(quads, per * slice), q_hi = min(quads, q_lo + per);
+    const auto quad = [&](int64_t q) { return WHOLE ? reinterpret_cast<const float4 *>(alpha)[q] : load_quad(alpha, q, d); };
     uint32_t vmax = 0;
     for (int64_t q = threadIdx.x; q < quads; q += blockDim.x) {
-        const float4 a = load_quad(alpha, q, d);
+        const float4 a = quad(q);
         vmax = max(max(vmax, abs_bits(a.x)), max(max(abs_bits(a.y), abs_bits(a.z)), abs_bits(a.w)));
     }
     vmax = block_max_u32(vmax, su);
@@ -178,7 +181,7 @@ __device__ __forceinline__ void sparsify_slice_from_lds(const float *alpha, int6
     uint32_t bmax = 0;
     int kept = 0;
     for (int64_t q = q_lo + threadIdx.x; q < q_hi; q += blockDim.x) {
-        float4 a = load_quad(alpha, q, d);
+        float4 a = quad(q);
         const uint4 w = stream_block(key, static_cast<uint32_t>(q));
         a.x = sparsify_one(a.x, rule, w.x);
         a.y = sparsify_one(a.y, rule, w.y);
@@ -217,7 +220,7 @@ struct WorkerOut {
 // is then only available after the sparsifier with b >= 4, where it equals the number of kept coordinates: a kept
 // coordinate has magnitude ||alpha||_inf up to two roundings, hence |t| > L - 1 >= 2 and a nonzero code whatever the
 // rounding decision, and a dropped one is exactly zero.  Otherwise out.nnz_out must be null when nslices > 1.
-template <int FIELD>
+template <int FIELD, bool WHOLE = false>
 __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bool sparsify, int b, StreamKey key,
                                                      const WorkerOut &out, uint32_t *su, int *si, int slice = 0,
                                                      int nslices = 1)
@@ -228,9 +231,11 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
     const int64_t q_lo = min(quads, per * slice), q_hi = min(quads, q_lo + per);
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t first = threadIdx.x - lane;           // quad of lane 0 in the first sweep (wave-uniform)
+    // WHOLE: alpha is padded with zeros to whole quads
+    const auto quad = [&](int64_t q) { return WHOLE ? reinterpret_cast<const float4 *>(alpha)[q] : load_quad(alpha, q, d); };
     uint32_t vmax = 0;
     for (int64_t q = threadIdx.x; q < quads; q += blockDim.x) {
-        const float4 a = load_quad(alpha, q, d);
+        const float4 a = quad(q);
         vmax = max(max(vmax, abs_bits(a.x)), max(max(abs_bits(a.y), abs_bits(a.z)), abs_bits(a.w)));
     }
     vmax = block_max_u32(vmax, su);
@@ -241,7 +246,7 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
         uint32_t bmax = 0;
         int kept = 0;
         for (int64_t q = threadIdx.x; q < quads; q += blockDim.x) {
-            float4 a = load_quad(alpha, q, d);
+            float4 a = quad(q);
             const uint4 w = stream_block(sk, static_cast<uint32_t>(q));
             a.x = sparsify_one(a.x, rule, w.x);
             a.y = sparsify_one(a.y, rule, w.y);
@@ -249,7 +254,8 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
             a.w = sparsify_one(a.w, rule, w.w);
             bmax = max(max(bmax, abs_bits(a.x)), max(max(abs_bits(a.y), abs_bits(a.z)), abs_bits(a.w)));
             kept += (a.x != 0.0f) + (a.y != 0.0f) + (a.z != 0.0f) + (a.w != 0.0f);
-            store_quad(alpha, q, d, a);
+            if (WHOLE) reinterpret_cast<float4 *>(alpha)[q] = a;          // (a zero stays zero)
+            else store_quad(alpha, q, d, a);
         }
         vmax = block_max_u32(bmax, su);      // (barriers inside also publish the beta writes)
         if (nslices > 1 && out.nnz_out) {    // see above: equals the number of nonzero codes (b >= 4)
@@ -286,7 +292,7 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
         for (int64_t q0 = q_lo + first; q0 < q_hi; q0 += blockDim.x) {
             const int64_t q = q0 + lane;
             uint32_t bits = 0;
-            if (q < q_hi) bits = quantize_quad<FIELD>(load_quad(alpha, q, d), s, key, q, nz);
+            if (q < q_hi) bits = quantize_quad<FIELD>(quad(q), s, key, q, nz);
             store_quad_bits<FIELD>(bits, q, q_hi, out.packed);
         }
         if (out.nnz_out && nslices == 1) {

@@ -5,16 +5,16 @@
 // bound; what matters is that one launch does the whole worker step and that the result
 // is reproducible.  One block of 1024 threads owns a worker: the gradient alpha (d floats)
 // lives in LDS for the whole step and never goes to memory.
-//   1. stage: the (column, value) pairs of the mini-batch rows are copied into LDS as one flat run
-//      (the row of an entry is found by bisection on the prefix sums of the row lengths and is
-//      kept in the bits above the column);
-//   2. margins: one wavefront per row, four rows in flight, gathers q and the snapshot at the
-//      row's columns and reduces the dot products; one lane per row forms its coefficient;
-//   3. scatter: a few wavefronts each own a contiguous range of columns and stream over the
-//      staged entries (which are in row order), adding coefficient*value for the entries in
-//      their range with LDS float adds that return nothing.  All adds to a column come from one
-//      wavefront, whose LDS operations execute in issue order, so every column receives its
-//      terms in row order: the sum is reproducible and nothing waits on a read-modify-write;
+//   1. stage: the (column, value) pairs of the mini-batch rows are copied into LDS as one flat run, spread evenly
+//      over the threads whatever the row lengths (the row of an entry is found by a fixed number of halving steps
+//      on the prefix sums of the row lengths and is kept in the bits above the column); the thread that copies an
+//      entry also gathers the model and the snapshot at its column and leaves value * operand next to it -- two
+//      trips to memory for the whole mini-batch, however long its longest row;
+//   2. margins: one wavefront per row, four rows in flight, adds up the products of its row from LDS; one lane per
+//      row forms its coefficient;
+//   3. scatter: every thread adds coefficient*value of the entries it staged to the columns' accumulators in LDS --
+//      integer atomic adds of fixed-point terms (see FixedAcc), whose sum does not depend on the order of the adds:
+//      the result is reproducible whichever wavefront gets there first;
 //   4. the tail of the worker step (sparsify, scale, quantize, pack) runs from LDS.
 // The full gradient uses the same block procedure over many blocks, each leaving a partial
 // d-vector that a second kernel adds up in a fixed order.
@@ -31,10 +31,11 @@ namespace dq {
 
 constexpr int kCsrThreads = 1024;
 constexpr int kCsrWaves = kCsrThreads / kWave;
-constexpr int kScatterWaves = 4;                 // wavefronts that add rows into the LDS vector (one per SIMD)
 constexpr int kColBits = 20;                     // staged entries carry column | row << kColBits
 constexpr int kColMask = (1 << kColBits) - 1;
 constexpr int kFlight = 4;                       // rows a wavefront reduces at the same time
+constexpr int kStageFlight = 4;                  // entries a thread stages at the same time
+constexpr int kFlushRows = 1024;                 // rows between two flushes of the fixed-point sums (full gradient)
 constexpr int kCsrMaxRows = 256;                 // rows a block handles per pass (LDS metadata)
 constexpr int64_t kLdsBudget = 152 * 1024;       // of the 160 KB per compute unit
 constexpr int64_t kCsrFixedLds = 10 * 1024;      // static arrays below, rounded up
@@ -90,29 +91,110 @@ __device__ __forceinline__ void csr_prefix_lengths(RowMeta &meta, int nrows)
     __syncthreads();
 }
 
+// The staging buffer in LDS: `cap` entries of (column | row << kColBits, value), and per entry value * first operand
+// (prod_a) and, for callers that need a second sum, value * second operand (prod_b, else null).
+struct CsrStage {
+    int2 *entry;
+    float *prod_a, *prod_b;
+    int cap;
+};
+
+__device__ __forceinline__ CsrStage csr_stage_in(float *after_window, int cap, bool second)
+{
+    CsrStage sg;
+    sg.entry = reinterpret_cast<int2 *>(after_window);
+    sg.prod_a = after_window + 2 * static_cast<int64_t>(cap);
+    sg.prod_b = second ? sg.prod_a + cap : nullptr;
+    sg.cap = cap;
+    return sg;
+}
+
+// ---- fixed-point accumulation of the scattered terms
+// LDS float atomic adds take about three cycles per lane on this part (measured: the 3328 adds of a 64-row
+// mini-batch take 4.3-4.9 us however they are spread over wavefronts), integer ones a fifteenth of that, and an
+// integer sum does not depend on the order of its terms.  So coefficient * value is accumulated in int32 as a multiple
+// of the unit 2^-k, with k from a bound on the magnitude any column's sum can have reached: the sum over the groups
+// of rows added so far of (sum of the group's |coefficient|) * (the group's largest |value|), times 2^k, stays
+// <= 2^30, so a sum cannot overflow.  The coefficients of the variance-reduced gradient shrink with the distance
+// between model and snapshot, and the unit shrinks with them.  A term is rounded to the nearest unit, i.e. within
+// 2^-31 of that bound -- float32 addition loses up to 2^-25 of the partial sum per term, which is coarser for sums of
+// the bound's order and finer for much smaller ones; either way far inside the tolerance of the gradient.  When a
+// further group of rows raises the bound past a power of two, the window is first rescaled to the coarser unit.
+// A value or coefficient that is not finite poisons the block: its result is NaN.
+struct FixedAcc {
+    float bound;            // see above; 0 while nothing but zeros has been added
+    int k;                  // the unit is 2^-k
+};
+
+// k with bound * 2^k <= 2^30 (clamped so that 2^k and 2^-k are normal numbers)
+__device__ __forceinline__ int fixed_exponent(float bound)
+{
+    int e = 0;
+    (void)frexpf(bound, &e);                 // bound = m * 2^e with 0.5 <= m < 1; e = 0 for bound = 0
+    return max(-100, min(100, 30 - e));
+}
+
+// A group of rows whose terms are bounded by group_bound (in sum, per column) is about to be added to acc[0..ncols):
+// coarsen the unit if need be.  Every thread calls it with the same arguments, after a barrier that follows all
+// earlier adds; a rescaled window is published by the barrier inside.
+__device__ __forceinline__ void fixed_admit(FixedAcc &fx, float group_bound, int *acc, int ncols, int *poison)
+{
+    if (!(group_bound <= FLT_MAX)) {         // Inf or NaN among the values or coefficients
+        if (threadIdx.x == 0) *poison = 1;
+        return;
+    }
+    const float bound = fx.bound + group_bound;
+    const int k_new = fixed_exponent(bound);
+    if (fx.bound > 0.0f && k_new < fx.k) {
+        const int sh = fx.k - k_new;
+        for (int j = threadIdx.x; j < ncols; j += kCsrThreads)
+            acc[j] = sh >= 31 ? 0 : (acc[j] + (1 << (sh - 1))) >> sh;       // nearest multiple of the new unit
+        __syncthreads();
+    }
+    if (!(fx.bound > 0.0f) || k_new < fx.k) fx.k = k_new;
+    fx.bound = bound;
+}
+
+// sum of |coef[r0..r1)| (at most kCsrMaxRows of them), the same value in every thread of the block
+__device__ __forceinline__ float coef_abs_sum(const float *coef, int r0, int r1)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    float t = 0.0f;
+#pragma unroll
+    for (int u = 0; u < kCsrMaxRows / kWave; ++u) {
+        const int r = r0 + lane + kWave * u;
+        const float c = coef[min(r, kCsrMaxRows - 1)];
+        t += r < r1 ? fabsf(c) : 0.0f;
+    }
+    return wave_sum_f32(t);
+}
+
+__device__ __forceinline__ int fixed_term(float coef, float value, float two_k)
+{
+    return __float2int_rn(coef * value * two_k);          // (the scaling by a power of two is exact)
+}
+
 // Stage, margins and scatter (the first three phases of the file header) for rows [0, nrows) described by `meta`,
-// accumulating into alpha (LDS).
-// The rows are taken in groups that fit the staging buffer (`stage`, `cap` (column, value) entries):
-//   stage  : the group's (column, value) pairs are copied to LDS as one flat run, four entries per thread
-//            in flight, the row number packed above the column;
-//   margins: one wavefront per row (kFlight rows in flight) reduces sum_k value_k * vec(column_k), where
-//            vec_val(vec_req(c), c) returns {first, second} operands gathered from memory -- vec_req only requests
-//            (no branch, no use of what it loads), so the gathers of all rows in flight wait for memory once;
-//            lane u hands the sums of its
+// accumulating into acc (LDS, fixed point, see FixedAcc).
+// The rows are taken in groups that fit the staging buffer:
+//   stage  : the group's (column, value) pairs are copied to LDS as one flat run, kStageFlight entries per thread in
+//            flight, the row number packed above the column; vec_val(vec_req(c), c) returns the {first, second}
+//            operands of column c gathered from memory -- vec_req only requests (no branch, no use of what it
+//            loads), so a thread's gathers wait for memory once -- and value * operand is staged with the entry;
+//   margins: one wavefront per row (kFlight rows in flight) adds up its row's products; lane u hands the sums of its
 //            u-th row to coef_of(row, first_sum, second_sum), which returns the row's coefficient;
-//   scatter: kScatterWaves wavefronts own a contiguous range of columns each and stream over the staged
-//            entries, adding coefficient*value for the entries that fall in their range.
+//   scatter: every thread adds coefficient*value of its share of the staged entries to acc[column - c0].
 // A row longer than `cap` is handled alone, straight from memory.
-// Only the columns of the window [c0, c1) are accumulated, into alpha[column - c0]: a vector too long for
-// LDS is built one window at a time (the caller repeats the call per window; margins are recomputed).
+// Only the columns of the window [c0, c1) are accumulated: a vector too long for LDS is built one window at a
+// time (the caller repeats the call per window; margins are recomputed).
 template <bool SECOND, typename VecReq, typename VecVal, typename CoefFn>
-__device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta, int nrows, float *alpha, int c0, int c1,
-                                                 int2 *stage, int cap, int *sh_ctl, VecReq vec_req, VecVal vec_val,
-                                                 CoefFn coef_of)
+__device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta, int nrows, int *acc, int c0, int c1,
+                                                 const CsrStage &sg, FixedAcc &fx, uint32_t *su, int *sh_ctl, int *poison,
+                                                 VecReq vec_req, VecVal vec_val, CoefFn coef_of)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    const int span = (c1 - c0 + kScatterWaves - 1) / kScatterWaves;
-    const int lo = c0 + wave * span, hi = wave < kScatterWaves ? min(c1, lo + span) : lo;
+    const int cap = sg.cap;
+    int2 *stage = sg.entry;
     int g0 = 0;
     while (g0 < nrows) {
         // group of consecutive rows that fits the staging buffer: rows g0..g1-1 with
@@ -134,31 +216,49 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
             direct = sh_ctl[1] != 0;
         }
         if (!direct) {
-            // ---- stage: flat copy of the group's entries; the row of an entry by bisection on pre[]
+            // ---- stage: flat copy of the group's entries with their products
             const int total = meta.pre[g1] - base;
-            for (int p0 = threadIdx.x; p0 < total; p0 += 4 * kCsrThreads) {     // four entries per thread in flight
-                int64_t src[4];
-                int tag[4];                                         // row number, shifted above the column bits
+            uint32_t vmax = 0;
+            for (int p0 = threadIdx.x; p0 < total; p0 += kStageFlight * kCsrThreads) {
+                int64_t src[kStageFlight];
+                int tag[kStageFlight], col[kStageFlight];
+                float val[kStageFlight];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int p = p0 + u * kCsrThreads;
-                    int lo_r = g0, hi_r = g1;                       // pre[lo_r] - base <= p < pre[hi_r] - base
-                    while (hi_r - lo_r > 1) {
-                        const int mid = (lo_r + hi_r) >> 1;
-                        if (meta.pre[mid] - base <= p) lo_r = mid; else hi_r = mid;
+                for (int u = 0; u < kStageFlight; ++u) {
+                    // (a position past the end repeats the last entry and is not stored: no load sits behind a test)
+                    const int p = min(p0 + u * kCsrThreads, total - 1);
+                    // the row of entry p: the last r in [g0, g1) with pre[r] - base <= p, by halving steps of fixed number
+                    int r = g0;
+#pragma unroll
+                    for (int step = kCsrMaxRows / 2; step >= 1; step >>= 1) {
+                        const int cand = r + step;
+                        const int first = meta.pre[min(cand, g1)] - base;
+                        r = (cand < g1 && first <= p) ? cand : r;
                     }
-                    src[u] = p < total ? meta.start[lo_r] + (p - (meta.pre[lo_r] - base)) : -1;
-                    tag[u] = lo_r << kColBits;
+                    src[u] = meta.start[r] + (p - (meta.pre[r] - base));
+                    tag[u] = r << kColBits;
                 }
-                int2 e[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (src[u] >= 0) e[u] = make_int2(A.indices[src[u]] | tag[u], __float_as_int(A.values[src[u]]));
+                for (int u = 0; u < kStageFlight; ++u) {
+                    col[u] = A.indices[src[u]];
+                    val[u] = A.values[src[u]];
+                }
+                decltype(vec_req(0)) raw[kStageFlight];
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    if (src[u] >= 0) stage[p0 + u * kCsrThreads] = e[u];
+                for (int u = 0; u < kStageFlight; ++u) raw[u] = vec_req(col[u]);
+#pragma unroll
+                for (int u = 0; u < kStageFlight; ++u) {
+                    const int p = p0 + u * kCsrThreads;
+                    const float2 f = vec_val(raw[u], col[u]);
+                    vmax = max(vmax, abs_bits(val[u]));
+                    if (p < total) {
+                        stage[p] = make_int2(col[u] | tag[u], __float_as_int(val[u]));
+                        sg.prod_a[p] = val[u] * f.x;
+                        if (SECOND) sg.prod_b[p] = val[u] * f.y;
+                    }
+                }
             }
-            __syncthreads();
+            vmax = block_max_u32(vmax, su);            // (its barriers also publish the staged entries)
             // ---- margins and coefficients: four rows per wavefront in flight; lane u evaluates row u's scalar
             for (int r = g0 + wave; r < g1; r += kFlight * kCsrWaves) {
                 int len[kFlight], off[kFlight], maxlen = 0;
@@ -171,20 +271,18 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
                     maxlen = max(maxlen, len[u]);
                     sa[u] = sb[u] = 0.0f;
                 }
-                for (int k = lane; k < maxlen; k += kWave) {
-                    int2 e[kFlight];
-                    float2 f[kFlight];
-                    decltype(vec_req(0)) raw[kFlight];
-#pragma unroll
-                    for (int u = 0; u < kFlight; ++u) e[u] = k < len[u] ? stage[off[u] + k] : make_int2(0, 0);
-#pragma unroll
-                    for (int u = 0; u < kFlight; ++u) raw[u] = vec_req(e[u].x & kColMask);
-#pragma unroll
-                    for (int u = 0; u < kFlight; ++u) f[u] = vec_val(raw[u], e[u].x & kColMask);
+                for (int k = lane; k < maxlen; k += kWave) {           // (maxlen > 0 implies total > 0)
+                    float pa[kFlight], pb[kFlight];
 #pragma unroll
                     for (int u = 0; u < kFlight; ++u) {
-                        sa[u] = fmaf(__int_as_float(e[u].y), f[u].x, sa[u]);
-                        if (SECOND) sb[u] = fmaf(__int_as_float(e[u].y), f[u].y, sb[u]);
+                        const int at = min(off[u] + k, total - 1);
+                        pa[u] = sg.prod_a[at];
+                        pb[u] = SECOND ? sg.prod_b[at] : 0.0f;
+                    }
+#pragma unroll
+                    for (int u = 0; u < kFlight; ++u) {
+                        sa[u] += k < len[u] ? pa[u] : 0.0f;
+                        if (SECOND) sb[u] += k < len[u] ? pb[u] : 0.0f;
                     }
                 }
                 float mine_a = 0.0f, mine_b = 0.0f;
@@ -198,57 +296,54 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
                     }
                 }
                 const int rl = r + lane * kCsrWaves;
-                if (lane < kFlight && rl < g1) meta.coef[rl] = coef_of(rl, mine_a, mine_b);
+                if (lane < kFlight && rl < g1) {
+                    const float cf = coef_of(rl, mine_a, mine_b);
+                    meta.coef[rl] = cf;
+                }
             }
             __syncthreads();
-            // ---- scatter: kScatterWaves wavefronts each own a contiguous range of columns and stream over the
-            //      staged entries (which are in row order), adding coefficient*value for the entries in their
-            //      range with LDS float adds that return nothing.  All adds to one column come from one
-            //      wavefront, whose LDS operations execute in issue order, so every column receives its
-            //      terms in row order and nothing waits on a read-modify-write round trip.
-            if (wave < kScatterWaves) {
-                for (int p0 = lane; p0 < total; p0 += 4 * kWave) {       // four entries per lane in flight
-                    int2 e[4];
-                    float term[4];
+            // ---- scatter: fixed-point terms, integer atomic adds
+            fixed_admit(fx, coef_abs_sum(meta.coef, g0, g1) * __uint_as_float(vmax), acc, c1 - c0, poison);
+            const float two_k = ldexpf(1.0f, fx.k);
+            for (int p0 = threadIdx.x; p0 < total; p0 += kStageFlight * kCsrThreads) {
+                int2 e[kStageFlight];
+                float cf[kStageFlight];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int p = p0 + u * kWave;
-                        e[u] = stage[min(p, total - 1)];
-                        if (p >= total) e[u].x = kColMask;              // a column nobody owns: models have fewer than 2^20
-                    }
+                for (int u = 0; u < kStageFlight; ++u) e[u] = stage[min(p0 + u * kCsrThreads, total - 1)];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) term[u] = meta.coef[(e[u].x >> kColBits) & (kCsrMaxRows - 1)];
-                    asm volatile("" : "+v"(term[0]), "+v"(term[1]), "+v"(term[2]), "+v"(term[3]));   // all four loads issued here,
-                                                                                                     // not inside the branches below
+                for (int u = 0; u < kStageFlight; ++u) cf[u] = meta.coef[(e[u].x >> kColBits) & (kCsrMaxRows - 1)];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) term[u] *= __int_as_float(e[u].y);
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int c = e[u].x & kColMask;
-                        if (c >= lo && c < hi) atomicAdd(&alpha[c - c0], term[u]);
-                    }
+                for (int u = 0; u < kStageFlight; ++u) {
+                    const int c = e[u].x & kColMask;
+                    if (p0 + u * kCsrThreads < total && c >= c0 && c < c1)
+                        atomicAdd(&acc[c - c0], fixed_term(cf[u], __int_as_float(e[u].y), two_k));
                 }
             }
         } else {
             // ---- one very long row, straight from memory (every wavefront computes the same sums)
             const int64_t s = meta.start[g0];
             float a1 = 0.0f, b1 = 0.0f;
+            uint32_t vmax = 0;
             for (int k = lane; k < meta.len[g0]; k += kWave) {
                 const int ck = A.indices[s + k];
                 const float2 f = vec_val(vec_req(ck), ck);
                 const float v = A.values[s + k];
-                a1 = fmaf(v, f.x, a1);
-                if (SECOND) b1 = fmaf(v, f.y, b1);
+                vmax = max(vmax, abs_bits(v));
+                a1 += v * f.x;
+                if (SECOND) b1 += v * f.y;
             }
             a1 = wave_sum_f32(a1);
             if (SECOND) b1 = wave_sum_f32(b1);
+            vmax = wave_max_u32(vmax);                 // (the same in every wavefront)
             __syncthreads();
             if (threadIdx.x == 0) meta.coef[g0] = coef_of(g0, a1, b1);
             __syncthreads();
             const float cf = meta.coef[g0];
-            for (int k = lane; k < meta.len[g0]; k += kWave) {
+            fixed_admit(fx, fabsf(cf) * __uint_as_float(vmax), acc, c1 - c0, poison);
+            const float two_k = ldexpf(1.0f, fx.k);
+            for (int k = threadIdx.x; k < meta.len[g0]; k += kCsrThreads) {
                 const int c = A.indices[s + k];
-                if (c >= lo && c < hi) alpha[c - c0] += cf * A.values[s + k];
+                if (c >= c0 && c < c1) atomicAdd(&acc[c - c0], fixed_term(cf, A.values[s + k], two_k));
             }
         }
         __syncthreads();
@@ -289,10 +384,13 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     __shared__ int si[kCsrWaves];
     __shared__ double sd[kCsrWaves];
     __shared__ int sh_ctl[2];
+    __shared__ int sh_poison;
     const int64_t d = a.A.d;
     const int win = a.win;                                     // columns per window, a multiple of 4
-    float *alpha = lds;                                        // the window of the gradient being built
-    int2 *stage = reinterpret_cast<int2 *>(lds + win);
+    float *alpha = lds;                                        // the window of the gradient being built: fixed-point sums
+    int *acc = reinterpret_cast<int *>(lds);                   // while the rows are added, float32 afterwards
+    if (threadIdx.x == 0) sh_poison = 0;                       // (published by the barriers of the first row pass)
+    const CsrStage sg = csr_stage_in(lds + win, a.cap, a.z_snap == nullptr);
 
     const int m = blockIdx.x;
     const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
@@ -346,27 +444,15 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
         }
         return ri;
     };
-    // the first pass's rows are requested before the window is initialised: both sets of loads are in flight together
-    const RowInfo first_rows = row_info(0);
     for (int64_t c0 = 0; c0 < d; c0 += win) {
         const int64_t c1 = min(d, c0 + win);
-        // the window starts as the dense part  l2*(q - snapshot); four coordinates per thread and step
-        for (int64_t j = c0 + 4ll * threadIdx.x; j < c1; j += 4ll * kCsrThreads) {
-            float *dst = alpha + (j - c0);
-            if (j + 3 < d && a.b_x == 8) {
-                const float4 xs = *reinterpret_cast<const float4 *>(a.x_snap + j);
-                const uint32_t w = a.xq[j >> 2];
-                dst[0] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 0, 8)) - xs.x);
-                dst[1] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 8, 8)) - xs.y);
-                dst[2] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 16, 8)) - xs.z);
-                dst[3] = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w, 24, 8)) - xs.w);
-            } else {
-                for (int64_t e = j; e < min(d, j + 4); ++e) dst[e - j] = a.l2 * (model_value(msg, e) - a.x_snap[e]);
-            }
-        }
+        const int64_t c1p = min((d + 3) / 4 * 4, c0 + win);     // the window, up to a whole quad past the end of the vector
+        for (int64_t j = 4ll * threadIdx.x; j < c1p - c0; j += 4ll * kCsrThreads)
+            *reinterpret_cast<int4 *>(acc + j) = make_int4(0, 0, 0, 0);
+        FixedAcc fx{0.0f, 0};
         for (int r0 = 0; r0 < a.B; r0 += kCsrMaxRows) {                     // passes of at most kCsrMaxRows rows
             const int nrows = min(kCsrMaxRows, a.B - r0);
-            const RowInfo ri = r0 == 0 ? first_rows : row_info(r0);
+            const RowInfo ri = row_info(r0);
             if (static_cast<int>(threadIdx.x) < nrows) {
                 meta.row[threadIdx.x] = ri.row;
                 meta.start[threadIdx.x] = ri.start;
@@ -376,19 +462,62 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
             }
             csr_prefix_lengths(meta, nrows);
             if (have_z)
-                csr_process_rows<false>(a.A, meta, nrows, alpha, static_cast<int>(c0), static_cast<int>(c1), stage, a.cap,
-                                        sh_ctl, vec_req, vec_val, coef_of);
+                csr_process_rows<false>(a.A, meta, nrows, acc, static_cast<int>(c0), static_cast<int>(c1), sg, fx, su, sh_ctl,
+                                        &sh_poison, vec_req, vec_val, coef_of);
             else
-                csr_process_rows<true>(a.A, meta, nrows, alpha, static_cast<int>(c0), static_cast<int>(c1), stage, a.cap,
-                                       sh_ctl, vec_req, vec_val, coef_of);
+                csr_process_rows<true>(a.A, meta, nrows, acc, static_cast<int>(c0), static_cast<int>(c1), sg, fx, su, sh_ctl,
+                                       &sh_poison, vec_req, vec_val, coef_of);
+        }
+        // the window becomes float32: the dense part  l2*(q - snapshot)  plus the accumulated sums, zero past the end
+        // of the vector; four coordinates per thread and step, the loads of kInitFlight steps requested together (at
+        // clamped positions: a load behind a per-lane test would be waited for before the next one is issued)
+        {
+            constexpr int kInitFlight = 3;
+            const bool bytes = a.b_x == 8 && d >= 4;
+            const int64_t last_quad = (d - 4) / 4 * 4;       // the last whole quad of the vector starts here
+            const float unit = sh_poison ? __uint_as_float(0x7FC00000u) : ldexpf(1.0f, -fx.k);
+            for (int64_t j0 = c0 + 4ll * threadIdx.x; j0 < c1p; j0 += 4ll * kCsrThreads * kInitFlight) {
+                float4 xs[kInitFlight];
+                uint32_t w[kInitFlight];
+                if (bytes) {
+#pragma unroll
+                    for (int u = 0; u < kInitFlight; ++u) {
+                        const int64_t jc = min(j0 + 4ll * kCsrThreads * u, last_quad);
+                        xs[u] = *reinterpret_cast<const float4 *>(a.x_snap + jc);
+                        w[u] = a.xq[jc >> 2];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < kInitFlight; ++u) {
+                    const int64_t j = j0 + 4ll * kCsrThreads * u;
+                    if (j >= c1p) break;
+                    const int4 sum = *reinterpret_cast<const int4 *>(acc + (j - c0));
+                    float4 v;
+                    if (bytes && j + 3 < d) {
+                        v.x = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w[u], 0, 8)) - xs[u].x);
+                        v.y = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w[u], 8, 8)) - xs[u].y);
+                        v.z = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w[u], 16, 8)) - xs[u].z);
+                        v.w = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w[u], 24, 8)) - xs[u].w);
+                    } else {
+                        float t[4];
+                        for (int e = 0; e < 4; ++e) t[e] = j + e < d ? a.l2 * (model_value(msg, j + e) - a.x_snap[j + e]) : 0.0f;
+                        v = make_float4(t[0], t[1], t[2], t[3]);
+                    }
+                    // (nothing was added past the end of the vector: the sums there are zero)
+                    v.x += static_cast<float>(sum.x) * unit; v.y += static_cast<float>(sum.y) * unit;
+                    v.z += static_cast<float>(sum.z) * unit; v.w += static_cast<float>(sum.w) * unit;
+                    *reinterpret_cast<float4 *>(alpha + (j - c0)) = v;
+                }
+            }
+            __syncthreads();
         }
         if (alpha_row) {                                       // several windows: the finished one goes to memory
-            for (int64_t j = c0 + threadIdx.x; j < c1; j += kCsrThreads) alpha_row[j] = alpha[j - c0];
+            for (int64_t j = c0 + threadIdx.x; j < c1p; j += kCsrThreads) alpha_row[j] = alpha[j - c0];
             __syncthreads();
         }
     }
-    // the whole gradient: in LDS when it fits in one window, else in this worker's workspace row (the block's own
-    // writes, visible to all its threads after the barrier above)
+    // the whole gradient, padded with zeros to a whole quad: in LDS when it fits in one window, else in this worker's
+    // workspace row (the block's own writes, visible to all its threads after the barrier above)
     float *av = alpha_row ? alpha_row : alpha;
 
     // 4. outputs
@@ -412,7 +541,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     StreamKey key = a.key;
     key.worker = a.worker0 + static_cast<uint32_t>(m);
     if (a.beta_ws) {
-        sparsify_slice_from_lds(av, d, key, slice, nslices, a.beta_ws + static_cast<int64_t>(m) * a.ld_ws,
+        sparsify_slice_from_lds<true>(av, d, key, slice, nslices, a.beta_ws + static_cast<int64_t>(m) * a.ld_ws,
                                 a.part_max + static_cast<int64_t>(m) * nslices + slice,
                                 a.part_kept + static_cast<int64_t>(m) * nslices + slice, su, si);
         return;
@@ -420,10 +549,10 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     const WorkerOut out{a.packed + static_cast<int64_t>(m) * a.ld_words, a.row_words, a.delta_out + m,
                         a.nnz_out ? a.nnz_out + m : nullptr, a.status};
     switch (a.b) {
-    case 2: worker_tail_from_lds<2>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
-    case 4: worker_tail_from_lds<4>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
-    case 32: worker_tail_from_lds<32>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
-    default: worker_tail_from_lds<8>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
+    case 2: worker_tail_from_lds<2, true>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
+    case 4: worker_tail_from_lds<4, true>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
+    case 32: worker_tail_from_lds<32, true>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
+    default: worker_tail_from_lds<8, true>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
     }
 }
 
@@ -436,9 +565,12 @@ __global__ __launch_bounds__(kCsrThreads) void csr_full_partial_kernel(
     extern __shared__ __align__(16) float lds[];
     __shared__ RowMeta meta;
     __shared__ double sh_loss[kCsrWaves];
+    __shared__ uint32_t su[kCsrWaves];
     __shared__ int sh_ctl[2];
-    float *acc = lds;                                    // the window [c0, c1) of this block's partial sum
-    int2 *stage = reinterpret_cast<int2 *>(lds + win);
+    __shared__ int sh_poison;
+    int *acc = reinterpret_cast<int *>(lds);             // the window [c0, c1) of this block's partial sum, fixed point
+    const CsrStage sg = csr_stage_in(lds + win, cap, false);
+    if (threadIdx.x == 0) sh_poison = 0;                 // (published by the barriers of the first row pass)
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int64_t per = (A.n + gridDim.x - 1) / gridDim.x;
     const int64_t i0 = blockIdx.x * per, i1 = min(A.n, i0 + per);
@@ -447,8 +579,14 @@ __global__ __launch_bounds__(kCsrThreads) void csr_full_partial_kernel(
     float *mine = partial + static_cast<int64_t>(blockIdx.x) * ldp;
     for (int64_t c0 = 0; c0 < ldp; c0 += win) {          // one window when the vector fits in LDS
         const int64_t c1 = min(ldp, c0 + win);
-        for (int64_t j = threadIdx.x; j < c1 - c0; j += kCsrThreads) acc[j] = 0.0f;
+        for (int64_t j = threadIdx.x; j < c1 - c0; j += kCsrThreads) acc[j] = 0;
+        FixedAcc fx{0.0f, 0};
         const bool first = c0 == 0;                      // margins and losses are recorded once
+        // The fixed-point sums go to this block's float32 partial vector at the end, and in between whenever
+        // kFlushRows rows have been added: a term is rounded relative to the bound of everything in the accumulator,
+        // which grows with the number of rows, so that number is kept small.
+        int since_flush = 0;
+        bool wrote = false;
         for (int64_t ib = i0; ib < i1; ib += kCsrMaxRows) {
             const int nrows = static_cast<int>(min<int64_t>(kCsrMaxRows, i1 - ib));
             if (static_cast<int>(threadIdx.x) < nrows) {
@@ -471,11 +609,24 @@ __global__ __launch_bounds__(kCsrThreads) void csr_full_partial_kernel(
                 }
                 return logistic_slope(y, z) / fn;
             };
-            csr_process_rows<false>(A, meta, nrows, acc, static_cast<int>(c0), static_cast<int>(min(A.d, c1)), stage, cap,
-                                    sh_ctl, vec_req, vec_val, coef_of);
+            csr_process_rows<false>(A, meta, nrows, acc, static_cast<int>(c0), static_cast<int>(min(A.d, c1)), sg, fx, su,
+                                    sh_ctl, &sh_poison, vec_req, vec_val, coef_of);
+            since_flush += nrows;
+            if (since_flush >= kFlushRows || ib + kCsrMaxRows >= i1) {         // (ends with a barrier: all adds are in)
+                const float unit = sh_poison ? __uint_as_float(0x7FC00000u) : ldexpf(1.0f, -fx.k);
+                for (int64_t j = c0 + threadIdx.x; j < c1; j += kCsrThreads) {
+                    const float v = static_cast<float>(acc[j - c0]) * unit;
+                    mine[j] = wrote ? mine[j] + v : v;
+                    acc[j - c0] = 0;
+                }
+                __syncthreads();
+                fx = FixedAcc{0.0f, 0};
+                since_flush = 0;
+                wrote = true;
+            }
         }
-        __syncthreads();
-        for (int64_t j = c0 + threadIdx.x; j < c1; j += kCsrThreads) mine[j] = acc[j - c0];
+        if (!wrote)                                      // a block without rows
+            for (int64_t j = c0 + threadIdx.x; j < c1; j += kCsrThreads) mine[j] = 0.0f;
         __syncthreads();
     }
     loss = wave_sum_f64(loss);
@@ -508,17 +659,21 @@ struct CsrPlan {
     int win;        // columns per window
     int cap;        // staged (column, value) entries
     int nwin;
+    size_t lds;     // bytes of dynamic LDS: window + staging
 };
 
-static bool csr_plan(int64_t d, CsrPlan &p)
+// A staged entry takes 12 bytes of LDS, 16 when the caller needs two sums per row (see CsrStage).
+static bool csr_plan(int64_t d, bool second, CsrPlan &p)
 {
     if (d >= (1ll << kColBits)) return false;      // column 2^20 - 1 marks the end of the staged entries in the scatter
     const int64_t budget = kLdsBudget - kCsrFixedLds;                     // bytes for window + staging
+    const int64_t each = second ? 16 : 12;
     int64_t nwin = 1;
-    if (pad4(d) * 4 + 8 * 512 > budget) nwin = ceil_div(pad4(d) * 4, budget - 8 * kMinStage);
+    if (pad4(d) * 4 + each * 512 > budget) nwin = ceil_div(pad4(d) * 4, budget - each * kMinStage);
     const int64_t win = pad4(ceil_div(pad4(d), nwin));
-    int64_t cap = (budget - win * 4) / 8;
+    int64_t cap = (budget - win * 4) / each;
     if (cap > 8192) cap = 8192;
+    p.lds = static_cast<size_t>(win * 4 + cap * each);
     p.win = static_cast<int>(win);
     p.cap = static_cast<int>(cap);
     p.nwin = static_cast<int>(ceil_div(pad4(d), win));
@@ -538,7 +693,7 @@ constexpr int kMaxSlices = kMaxParts;       // identical blocks per worker that 
 int64_t csr_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64_t)
 {
     CsrPlan plan;
-    if (!csr_plan(prob->d, plan)) return DQ_ERR_UNSUPPORTED;
+    if (!csr_plan(prob->d, true, plan)) return DQ_ERR_UNSUPPORTED;
     if (op == DQ_OP_FULL_GRAD) {
         const int64_t P = csr_full_splits(prob->n);
         return P * pad4(prob->d) * 4 + P * 8;
@@ -565,13 +720,13 @@ int csr_full_grad(const dq_problem *prob, const float *x, float *g_out, float *z
 {
     const int64_t d = prob->d, n = prob->n;
     CsrPlan plan;
-    if (!csr_plan(d, plan)) return DQ_ERR_UNSUPPORTED;
+    if (!csr_plan(d, false, plan)) return DQ_ERR_UNSUPPORTED;
     if (ws_bytes < csr_workspace_bytes(DQ_OP_FULL_GRAD, prob, 0, 0) || !ws) return DQ_ERR_WORKSPACE;
     const int64_t ldp = pad4(d);
     const int P = static_cast<int>(csr_full_splits(n));
     float *partial = static_cast<float *>(ws);
     double *loss_partial = reinterpret_cast<double *>(partial + static_cast<int64_t>(P) * ldp);
-    const size_t lds = static_cast<size_t>(plan.win) * 4 + static_cast<size_t>(plan.cap) * 8;
+    const size_t lds = plan.lds;
     static std::once_flag attr_once;
     static hipError_t attr_rc = hipSuccess;
     int rc = allow_big_lds(csr_full_partial_kernel, attr_once, attr_rc);
@@ -586,7 +741,7 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
 {
     const int64_t d = prob->d;
     CsrPlan plan;
-    if (!csr_plan(d, plan)) return DQ_ERR_UNSUPPORTED;
+    if (!csr_plan(d, a.z_snap == nullptr, plan)) return DQ_ERR_UNSUPPORTED;
     const int64_t row_words = a.packed ? (a.b == 32 ? d : packed_words(d, a.b)) : 0;
     if (a.model_is_snapshot) return launch_worker_zero(a, d, row_words, st);
     if (plan.nwin > 1 && (!a.ws || a.ws_bytes < a.M * pad4(d) * 4)) return DQ_ERR_WORKSPACE;
@@ -603,7 +758,7 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     k.delta_out = a.delta_out; k.nnz_out = a.nnz_out; k.status = a.status; k.zero_word = a.zero_word;
     k.cap = plan.cap; k.win = plan.win;
     k.alpha_ws = plan.nwin > 1 ? static_cast<float *>(a.ws) : nullptr; k.ld_ws = pad4(d);
-    const size_t lds = static_cast<size_t>(plan.win) * 4 + static_cast<size_t>(plan.cap) * 8;
+    const size_t lds = plan.lds;
     static std::once_flag attr_once;
     static hipError_t attr_rc = hipSuccess;
     int rc = allow_big_lds(csr_worker_kernel, attr_once, attr_rc);
