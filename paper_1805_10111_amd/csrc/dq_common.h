@@ -211,6 +211,22 @@ __device__ __forceinline__ int block_sum_i32(int v, int *scratch)
     return wave_sum_i32(lane < nw ? scratch[lane] : 0);
 }
 
+// Both at once (one pair of barriers): m becomes the block-wide max, s the block-wide sum.
+__device__ __forceinline__ void block_max_u32_sum_i32(uint32_t &m, int &s, uint32_t *scratch_m, int *scratch_s)
+{
+    m = wave_max_u32(m);
+    s = wave_sum_i32(s);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
+    __syncthreads();
+    if (lane == 0) {
+        scratch_m[wave] = m;
+        scratch_s[wave] = s;
+    }
+    __syncthreads();
+    m = wave_max_u32(lane < nw ? scratch_m[lane] : 0u);
+    s = wave_sum_i32(lane < nw ? scratch_s[lane] : 0);
+}
+
 // ---- values left per slice by several producers of one row -----------------------
 // A row's largest magnitude / count arrives as up to kMaxParts values.  All of them are requested at once (an index
 // past the last one re-reads the last one): a loop that stops at `parts` would wait for every load before the next.

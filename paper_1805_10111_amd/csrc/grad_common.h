@@ -164,17 +164,20 @@ __device__ __forceinline__ float4 load4_or_zero(const float *__restrict__ v, int
 template <bool WHOLE = false>
 __device__ __forceinline__ void sparsify_slice_from_lds(const float *alpha, int64_t d, StreamKey key, int slice, int nslices,
                                                         float *__restrict__ beta_row, float *__restrict__ part_max,
-                                                        int32_t *__restrict__ part_kept, uint32_t *su, int *si)
+                                                        int32_t *__restrict__ part_kept, uint32_t *su, int *si,
+                                                        const uint32_t *seen_max = nullptr)
 {
     const int64_t quads = (d + 3) / 4;
     const int64_t per = ((quads + nslices - 1) / nslices + kWave - 1) / kWave * kWave;
     const int64_t q_lo = min(quads, per * slice), q_hi = min(quads, q_lo + per);
     const auto quad = [&](int64_t q) { return WHOLE ? reinterpret_cast<const float4 *>(alpha)[q] : load_quad(alpha, q, d); };
-    uint32_t vmax = 0;
-    for (int64_t q = threadIdx.x; q < quads; q += blockDim.x) {
-        const float4 a = quad(q);
-        vmax = max(max(vmax, abs_bits(a.x)), max(max(abs_bits(a.y), abs_bits(a.z)), abs_bits(a.w)));
-    }
+    // seen_max: the caller's threads have already seen every coordinate (each its share): their maxima
+    uint32_t vmax = seen_max ? *seen_max : 0u;
+    if (!seen_max)
+        for (int64_t q = threadIdx.x; q < quads; q += blockDim.x) {
+            const float4 a = quad(q);
+            vmax = max(max(vmax, abs_bits(a.x)), max(max(abs_bits(a.y), abs_bits(a.z)), abs_bits(a.w)));
+        }
     vmax = block_max_u32(vmax, su);
     const SparsifyRule rule{__uint_as_float(vmax), 0.0f, false};
     key.tag = DQ_TAG_SPARSIFY;
@@ -191,8 +194,7 @@ __device__ __forceinline__ void sparsify_slice_from_lds(const float *alpha, int6
         kept += (a.x != 0.0f) + (a.y != 0.0f) + (a.z != 0.0f) + (a.w != 0.0f);
         store_quad(beta_row, q, d, a);
     }
-    bmax = block_max_u32(bmax, su);
-    kept = block_sum_i32(kept, si);
+    block_max_u32_sum_i32(bmax, kept, su, si);
     if (threadIdx.x == 0) {
         part_max[0] = __uint_as_float(bmax);
         part_kept[0] = kept;
@@ -223,7 +225,7 @@ struct WorkerOut {
 template <int FIELD, bool WHOLE = false>
 __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bool sparsify, int b, StreamKey key,
                                                      const WorkerOut &out, uint32_t *su, int *si, int slice = 0,
-                                                     int nslices = 1)
+                                                     int nslices = 1, const uint32_t *seen_max = nullptr)
 {
     const int64_t quads = (d + 3) / 4;
     // slice boundaries are multiples of 64 quads, so no packed word is shared between two slices
@@ -233,11 +235,13 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
     const int64_t first = threadIdx.x - lane;           // quad of lane 0 in the first sweep (wave-uniform)
     // WHOLE: alpha is padded with zeros to whole quads
     const auto quad = [&](int64_t q) { return WHOLE ? reinterpret_cast<const float4 *>(alpha)[q] : load_quad(alpha, q, d); };
-    uint32_t vmax = 0;
-    for (int64_t q = threadIdx.x; q < quads; q += blockDim.x) {
-        const float4 a = quad(q);
-        vmax = max(max(vmax, abs_bits(a.x)), max(max(abs_bits(a.y), abs_bits(a.z)), abs_bits(a.w)));
-    }
+    // seen_max: the caller's threads have already seen every coordinate (each its share): their maxima
+    uint32_t vmax = seen_max ? *seen_max : 0u;
+    if (!seen_max)
+        for (int64_t q = threadIdx.x; q < quads; q += blockDim.x) {
+            const float4 a = quad(q);
+            vmax = max(max(vmax, abs_bits(a.x)), max(max(abs_bits(a.y), abs_bits(a.z)), abs_bits(a.w)));
+        }
     vmax = block_max_u32(vmax, su);
     if (sparsify) {
         SparsifyRule rule{__uint_as_float(vmax), 0.0f, false};

@@ -37,6 +37,8 @@ constexpr int kFlight = 4;                       // rows a wavefront reduces at 
 constexpr int kStageFlight = 4;                  // entries a thread stages at the same time
 constexpr int kFlushRows = 1024;                 // rows between two flushes of the fixed-point sums (full gradient)
 constexpr int kCsrMaxRows = 256;                 // rows a block handles per pass (LDS metadata)
+constexpr int kMaxStage = 8192;                  // most entries the staging buffer is given
+constexpr int kChunkSlots = kMaxStage / kWave;   // see RowMeta::chunk_row
 constexpr int64_t kLdsBudget = 152 * 1024;       // of the 160 KB per compute unit
 constexpr int64_t kCsrFixedLds = 10 * 1024;      // static arrays below, rounded up
 
@@ -56,6 +58,7 @@ struct RowMeta {
     int pre[kCsrMaxRows + 1];    // exclusive prefix sum of len
     float coef[kCsrMaxRows];
     float z[kCsrMaxRows];        // cached margin at the snapshot (worker step only)
+    int chunk_row[kChunkSlots];  // the row that holds entry 64 c of the rows' concatenation, for the entries below 64 * kChunkSlots
 };
 
 // Fills meta.pre with the exclusive prefix sums of meta.len[0..nrows) (pre[nrows] = total).
@@ -87,6 +90,12 @@ __device__ __forceinline__ void csr_prefix_lengths(RowMeta &meta, int nrows)
             run += v[u];
         }
         if (lane == kWave - 1) meta.pre[kCsrMaxRows] = run;
+    }
+    __syncthreads();
+    // every row leaves its number at the multiples of 64 that it holds (an empty row holds none)
+    if (static_cast<int>(threadIdx.x) < nrows) {
+        const int lo = meta.pre[threadIdx.x], hi = meta.pre[threadIdx.x + 1];
+        for (int c = (lo + kWave - 1) / kWave; c * kWave < hi && c < kChunkSlots; ++c) meta.chunk_row[c] = threadIdx.x;
     }
     __syncthreads();
 }
@@ -174,6 +183,41 @@ __device__ __forceinline__ int fixed_term(float coef, float value, float two_k)
     return __float2int_rn(coef * value * two_k);          // (the scaling by a power of two is exact)
 }
 
+// The row of staged position p: the last r in [g0, g1) with pre[r] - base <= p, by halving steps of fixed number.
+__device__ __forceinline__ int csr_row_of(const RowMeta &meta, int g0, int g1, int base, int p)
+{
+    int r = g0;
+#pragma unroll
+    for (int step = kCsrMaxRows / 2; step >= 1; step >>= 1) {
+        const int cand = r + step;
+        const int first = meta.pre[min(cand, g1)] - base;
+        r = (cand < g1 && first <= p) ? cand : r;
+    }
+    return r;
+}
+
+// The same for the 64 consecutive positions P + lane of a wavefront when the group starts at row 0 (base = 0) and P is a
+// multiple of 64, from the table of the rows at the multiples of 64 (RowMeta::chunk_row): the row of P is read there,
+// and a lane's row lies as many rows further as start at or before its position among the next kNextRows (their
+// starts are the same few LDS words for the whole wavefront).  More rows than that starting inside the chunk (short
+// rows) is left to csr_row_of.  `p` = min(P + lane, total - 1).
+constexpr int kNextRows = 4;
+__device__ __forceinline__ int csr_row_in_chunk(const RowMeta &meta, int g1, int P, int p)
+{
+    const int r0 = meta.chunk_row[P >> 6];
+    const int beyond = r0 + kNextRows + 1;
+    if (beyond < g1 && meta.pre[min(beyond, kCsrMaxRows)] <= P + kWave - 1)       // (the same for all lanes)
+        return csr_row_of(meta, 0, g1, 0, p);
+    int r = r0;
+#pragma unroll
+    for (int j = 1; j <= kNextRows; ++j) {
+        const int rj = r0 + j;
+        const int first = meta.pre[min(rj, kCsrMaxRows)];
+        r += (rj < g1 && first <= p) ? 1 : 0;
+    }
+    return r;
+}
+
 // Stage, margins and scatter (the first three phases of the file header) for rows [0, nrows) described by `meta`,
 // accumulating into acc (LDS, fixed point, see FixedAcc).
 // The rows are taken in groups that fit the staging buffer:
@@ -219,23 +263,20 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
             // ---- stage: flat copy of the group's entries with their products
             const int total = meta.pre[g1] - base;
             uint32_t vmax = 0;
-            for (int p0 = threadIdx.x; p0 < total; p0 += kStageFlight * kCsrThreads) {
+            // (the loop bound is the same for a whole wavefront: its lanes find their rows together)
+            for (int p0 = threadIdx.x; p0 - lane < total; p0 += kStageFlight * kCsrThreads) {
                 int64_t src[kStageFlight];
                 int tag[kStageFlight], col[kStageFlight];
                 float val[kStageFlight];
 #pragma unroll
                 for (int u = 0; u < kStageFlight; ++u) {
                     // (a position past the end repeats the last entry and is not stored: no load sits behind a test)
-                    const int p = min(p0 + u * kCsrThreads, total - 1);
-                    // the row of entry p: the last r in [g0, g1) with pre[r] - base <= p, by halving steps of fixed number
-                    int r = g0;
-#pragma unroll
-                    for (int step = kCsrMaxRows / 2; step >= 1; step >>= 1) {
-                        const int cand = r + step;
-                        const int first = meta.pre[min(cand, g1)] - base;
-                        r = (cand < g1 && first <= p) ? cand : r;
-                    }
-                    src[u] = meta.start[r] + (p - (meta.pre[r] - base));
+                    const int P = p0 - lane + u * kCsrThreads;         // the wavefront's 64 positions start here
+                    const int p = min(P + lane, total - 1);
+                    const int r = P >= total ? g1 - 1
+                                  : g0 == 0  ? csr_row_in_chunk(meta, g1, P, p)
+                                             : csr_row_of(meta, g0, g1, base, p);
+                    src[u] = P < total ? meta.start[r] + (p - (meta.pre[r] - base)) : src[0];    // (u = 0 is inside)
                     tag[u] = r << kColBits;
                 }
 #pragma unroll
@@ -400,12 +441,14 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
 
     const float inv_B = 1.0f / static_cast<float>(a.B);      // the mean over the mini-batch, as one multiplication per row
     const bool have_z = a.z_snap != nullptr;
+    uint32_t seen_max = 0;                                     // largest magnitude among the coordinates this thread finishes
     // the model value and the snapshot at column c: the field of column c starts at bit c*b_x of the message and
     // may continue in the next word; both words and the snapshot value are requested without any condition
     struct Gather { uint32_t w0, w1; float xs; };
+    const bool straddles = (32 % a.b_x) != 0;                 // (the same for every thread) else a field lies in one word
     auto vec_req = [&](int c) {
         const int w = (c * a.b_x) >> 5, last = static_cast<int>(a.model_last_word);   // (fewer than 2^20 words)
-        return Gather{a.xq[w], a.xq[w + 1 < last ? w + 1 : last], a.x_snap[c]};
+        return Gather{a.xq[w], straddles ? a.xq[w + 1 < last ? w + 1 : last] : 0u, a.x_snap[c]};
     };
     auto vec_val = [&](const Gather &g, int c) {
         const uint32_t bits = __funnelshift_r(g.w0, g.w1, static_cast<unsigned>(c * a.b_x) & 31u);
@@ -447,12 +490,13 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     for (int64_t c0 = 0; c0 < d; c0 += win) {
         const int64_t c1 = min(d, c0 + win);
         const int64_t c1p = min((d + 3) / 4 * 4, c0 + win);     // the window, up to a whole quad past the end of the vector
-        for (int64_t j = 4ll * threadIdx.x; j < c1p - c0; j += 4ll * kCsrThreads)
-            *reinterpret_cast<int4 *>(acc + j) = make_int4(0, 0, 0, 0);
         FixedAcc fx{0.0f, 0};
         for (int r0 = 0; r0 < a.B; r0 += kCsrMaxRows) {                     // passes of at most kCsrMaxRows rows
             const int nrows = min(kCsrMaxRows, a.B - r0);
             const RowInfo ri = row_info(r0);
+            if (r0 == 0)                                       // (the window is cleared while the row loads are on their way)
+                for (int64_t j = 4ll * threadIdx.x; j < c1p - c0; j += 4ll * kCsrThreads)
+                    *reinterpret_cast<int4 *>(acc + j) = make_int4(0, 0, 0, 0);
             if (static_cast<int>(threadIdx.x) < nrows) {
                 meta.row[threadIdx.x] = ri.row;
                 meta.start[threadIdx.x] = ri.start;
@@ -469,45 +513,49 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
                                        &sh_poison, vec_req, vec_val, coef_of);
         }
         // the window becomes float32: the dense part  l2*(q - snapshot)  plus the accumulated sums, zero past the end
-        // of the vector; four coordinates per thread and step, the loads of kInitFlight steps requested together (at
-        // clamped positions: a load behind a per-lane test would be waited for before the next one is issued)
+        // of the vector; four coordinates per thread and step
         {
-            constexpr int kInitFlight = 3;
-            const bool bytes = a.b_x == 8 && d >= 4;
-            const int64_t last_quad = (d - 4) / 4 * 4;       // the last whole quad of the vector starts here
             const float unit = sh_poison ? __uint_as_float(0x7FC00000u) : ldexpf(1.0f, -fx.k);
-            for (int64_t j0 = c0 + 4ll * threadIdx.x; j0 < c1p; j0 += 4ll * kCsrThreads * kInitFlight) {
-                float4 xs[kInitFlight];
-                uint32_t w[kInitFlight];
-                if (bytes) {
+            // (nothing was added past the end of the vector: the sums there are zero)
+            const auto finish_quad = [&](int64_t j, float4 v) {
+                const int4 sum = *reinterpret_cast<const int4 *>(acc + (j - c0));
+                v.x += static_cast<float>(sum.x) * unit; v.y += static_cast<float>(sum.y) * unit;
+                v.z += static_cast<float>(sum.z) * unit; v.w += static_cast<float>(sum.w) * unit;
+                *reinterpret_cast<float4 *>(alpha + (j - c0)) = v;
+                seen_max = max(max(seen_max, abs_bits(v.x)), max(max(abs_bits(v.y), abs_bits(v.z)), abs_bits(v.w)));
+            };
+            const auto slow_quad = [&](int64_t j) {
+                float t[4];
+                for (int e = 0; e < 4; ++e) t[e] = j + e < d ? a.l2 * (model_value(msg, j + e) - a.x_snap[j + e]) : 0.0f;
+                finish_quad(j, make_float4(t[0], t[1], t[2], t[3]));
+            };
+            const int64_t whole = min(c1p, d / 4 * 4);            // whole quads of the vector end here
+            if (a.b_x == 8) {
+                // the loads of kInitFlight steps are requested together (at clamped positions: a load behind a
+                // per-lane test would be waited for before the next one is issued)
+                constexpr int kInitFlight = 6;
+                for (int64_t j0 = c0 + 4ll * threadIdx.x; j0 < whole; j0 += 4ll * kCsrThreads * kInitFlight) {
+                    float4 xs[kInitFlight];
+                    uint32_t w[kInitFlight];
 #pragma unroll
                     for (int u = 0; u < kInitFlight; ++u) {
-                        const int64_t jc = min(j0 + 4ll * kCsrThreads * u, last_quad);
+                        const int64_t jc = min(j0 + 4ll * kCsrThreads * u, whole - 4);
                         xs[u] = *reinterpret_cast<const float4 *>(a.x_snap + jc);
                         w[u] = a.xq[jc >> 2];
                     }
-                }
 #pragma unroll
-                for (int u = 0; u < kInitFlight; ++u) {
-                    const int64_t j = j0 + 4ll * kCsrThreads * u;
-                    if (j >= c1p) break;
-                    const int4 sum = *reinterpret_cast<const int4 *>(acc + (j - c0));
-                    float4 v;
-                    if (bytes && j + 3 < d) {
-                        v.x = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w[u], 0, 8)) - xs[u].x);
-                        v.y = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w[u], 8, 8)) - xs[u].y);
-                        v.z = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w[u], 16, 8)) - xs[u].z);
-                        v.w = a.l2 * (msg.delta_x * static_cast<float>(sext_field(w[u], 24, 8)) - xs[u].w);
-                    } else {
-                        float t[4];
-                        for (int e = 0; e < 4; ++e) t[e] = j + e < d ? a.l2 * (model_value(msg, j + e) - a.x_snap[j + e]) : 0.0f;
-                        v = make_float4(t[0], t[1], t[2], t[3]);
+                    for (int u = 0; u < kInitFlight; ++u) {
+                        const int64_t j = j0 + 4ll * kCsrThreads * u;
+                        if (j < whole)
+                            finish_quad(j, make_float4(a.l2 * (msg.delta_x * static_cast<float>(sext_field(w[u], 0, 8)) - xs[u].x),
+                                                       a.l2 * (msg.delta_x * static_cast<float>(sext_field(w[u], 8, 8)) - xs[u].y),
+                                                       a.l2 * (msg.delta_x * static_cast<float>(sext_field(w[u], 16, 8)) - xs[u].z),
+                                                       a.l2 * (msg.delta_x * static_cast<float>(sext_field(w[u], 24, 8)) - xs[u].w)));
                     }
-                    // (nothing was added past the end of the vector: the sums there are zero)
-                    v.x += static_cast<float>(sum.x) * unit; v.y += static_cast<float>(sum.y) * unit;
-                    v.z += static_cast<float>(sum.z) * unit; v.w += static_cast<float>(sum.w) * unit;
-                    *reinterpret_cast<float4 *>(alpha + (j - c0)) = v;
                 }
+                if (threadIdx.x == 0 && whole >= c0 && whole < c1p) slow_quad(whole);      // the vector ends inside a quad
+            } else {
+                for (int64_t j = c0 + 4ll * threadIdx.x; j < c1p; j += 4ll * kCsrThreads) slow_quad(j);
             }
             __syncthreads();
         }
@@ -542,17 +590,17 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     key.worker = a.worker0 + static_cast<uint32_t>(m);
     if (a.beta_ws) {
         sparsify_slice_from_lds<true>(av, d, key, slice, nslices, a.beta_ws + static_cast<int64_t>(m) * a.ld_ws,
-                                a.part_max + static_cast<int64_t>(m) * nslices + slice,
-                                a.part_kept + static_cast<int64_t>(m) * nslices + slice, su, si);
+                                      a.part_max + static_cast<int64_t>(m) * nslices + slice,
+                                      a.part_kept + static_cast<int64_t>(m) * nslices + slice, su, si, &seen_max);
         return;
     }
     const WorkerOut out{a.packed + static_cast<int64_t>(m) * a.ld_words, a.row_words, a.delta_out + m,
                         a.nnz_out ? a.nnz_out + m : nullptr, a.status};
     switch (a.b) {
-    case 2: worker_tail_from_lds<2, true>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
-    case 4: worker_tail_from_lds<4, true>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
-    case 32: worker_tail_from_lds<32, true>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
-    default: worker_tail_from_lds<8, true>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices); break;
+    case 2: worker_tail_from_lds<2, true>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices, &seen_max); break;
+    case 4: worker_tail_from_lds<4, true>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices, &seen_max); break;
+    case 32: worker_tail_from_lds<32, true>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices, &seen_max); break;
+    default: worker_tail_from_lds<8, true>(av, d, a.sparsify != 0, a.b, key, out, su, si, slice, nslices, &seen_max); break;
     }
 }
 
@@ -672,7 +720,7 @@ static bool csr_plan(int64_t d, bool second, CsrPlan &p)
     if (pad4(d) * 4 + each * 512 > budget) nwin = ceil_div(pad4(d) * 4, budget - each * kMinStage);
     const int64_t win = pad4(ceil_div(pad4(d), nwin));
     int64_t cap = (budget - win * 4) / each;
-    if (cap > 8192) cap = 8192;
+    if (cap > kMaxStage) cap = kMaxStage;
     p.lds = static_cast<size_t>(win * 4 + cap * each);
     p.win = static_cast<int>(win);
     p.cap = static_cast<int>(cap);
