@@ -138,6 +138,107 @@ def test_vr_grad(dq, problems, name, M, B, b_x, have_z):
     assert torch.equal(alpha, alpha2)
 
 
+def _csr(rows, d, y=None, l2=1e-3, l1=1e-4):
+    """Problem from a list of (columns, values) rows."""
+    n = len(rows)
+    indptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum([len(c) for c, _ in rows], out=indptr[1:])
+    indices = np.concatenate([np.asarray(c, dtype=np.int32) for c, _ in rows])
+    values = np.concatenate([np.asarray(v, dtype=np.float32) for _, v in rows])
+    if y is None:
+        y = np.where(np.arange(n) % 3 == 0, -1.0, 1.0).astype(np.float32)
+    return synth.Problem(n=n, d=d, y=y, l2=l2, l1=l1, indptr=indptr, indices=indices, values=values)
+
+
+def _vr_grad_case(dq, p, M, B, idx, spread, b_x=8):
+    P = dq.DeviceProblem.from_host(p)
+    rp = oracle.RefProblem(p)
+    d = p.d
+    rng = np.random.default_rng(12)
+    x_snap = (0.3 * rng.standard_normal(d)).astype(np.float32)
+    xq, dx, q = _model(rng, d, b_x, x_snap, spread=spread)
+    _, z_ref = oracle.full_grad(rp, x_snap, want_margins=True)
+    ld = (d + 3) // 4 * 4
+    alpha = torch.zeros((M, ld), device="cuda")[:, :d]
+    amax = torch.zeros(M, device="cuda")
+    ws = dq.new_workspace(dq.OP_VR_GRAD, P, M, B)
+    dq.dq_vr_grad(P, dev(idx.astype(np.int32)), M, B, dev(xq.view(np.int32)), dev(np.array([dx], dtype=np.float32)), b_x,
+                  False, dev(x_snap), dev(z_ref), alpha, amax, None, ws)
+    return host(alpha), [oracle.vr_grad(rp, idx[w].astype(np.int32), q, x_snap).astype(np.float64) for w in range(M)]
+
+
+@pytest.mark.parametrize("spread", [0.05, 1e-4])
+def test_vr_grad_many_rows_meet_in_one_column(dq, spread):
+    """Every row of a 700-row mini-batch (three passes of the kernel over its rows) has columns 7 and 4098 next to a few
+    others, with signs that cancel: the sums of those columns are built from 700 terms each, far below the bound the
+    fixed-point unit of the accumulator is derived from -- with the model close to the snapshot (small coefficients) as
+    well as far from it.  The tolerance stays 1e-5 of the largest entry."""
+    rng = np.random.default_rng(3)
+    d, n = 4101, 900
+    rows = []
+    for i in range(n):
+        extra = np.sort(rng.choice(np.arange(8, 4098), size=rng.integers(0, 6), replace=False))
+        cols = np.concatenate([[7], extra, [4098]])
+        vals = rng.standard_normal(cols.size) * 0.3
+        vals[0] = 0.5 * (1 if i % 2 else -1)
+        rows.append((cols, vals))
+    p = _csr(rows, d)
+    idx = np.stack([rng.permutation(n)[:700] for _ in range(2)])
+    got, want = _vr_grad_case(dq, p, 2, 700, idx, spread)
+    for w in range(2):
+        _close(got[w], want[w])
+
+
+def test_vr_grad_values_of_very_different_size(dq):
+    """Rows whose values differ by twelve orders of magnitude, the largest ones arriving in the last of three passes:
+    the accumulator is rescaled to a coarser unit on the way and the result keeps the tolerance (relative to the
+    largest entry of the gradient)."""
+    rng = np.random.default_rng(4)
+    d, n = 5000, 600
+    rows = []
+    for i in range(n):
+        cols = np.sort(rng.choice(d, size=rng.integers(1, 40), replace=False))
+        scale = 10.0 ** (-9 + 12 * i / n)
+        rows.append((cols, rng.standard_normal(cols.size) * scale))
+    p = _csr(rows, d)
+    idx = np.stack([np.arange(n)])                   # in order: the large values come last
+    got, want = _vr_grad_case(dq, p, 1, n, idx, 0.05)
+    _close(got[0], want[0])
+
+
+def test_a_value_that_is_not_a_number_poisons_its_worker_only(dq):
+    """One NaN among the matrix values: the gradient of the worker whose mini-batch holds that row is NaN throughout,
+    its largest magnitude is reported as NaN, and the fused step raises the status flag; the other worker is exact."""
+    p0 = synth.sparse_text_logistic(300, 4099, mean_nnz=30.0, seed=3)
+    values = p0.values.copy()
+    bad_row = 17
+    values[p0.indptr[bad_row] + 1] = np.nan
+    p = synth.Problem(n=p0.n, d=p0.d, y=p0.y, l2=p0.l2, l1=p0.l1, indptr=p0.indptr, indices=p0.indices, values=values)
+    M, B = 2, 20
+    idx = np.stack([np.arange(0, B), np.arange(100, 100 + B)])           # worker 0 holds the row, worker 1 does not
+    P = dq.DeviceProblem.from_host(p)
+    rp = oracle.RefProblem(p0)
+    d = p.d
+    rng = np.random.default_rng(12)
+    x_snap = (0.3 * rng.standard_normal(d)).astype(np.float32)
+    xq, dx, q = _model(rng, d, 8, x_snap)
+    ld = (d + 3) // 4 * 4
+    alpha = torch.zeros((M, ld), device="cuda")[:, :d]
+    amax = torch.zeros(M, device="cuda")
+    ws = dq.new_workspace(dq.OP_VR_GRAD, P, M, B)
+    xq_d, dx_d, xs_d = dev(xq.view(np.int32)), dev(np.array([dx], dtype=np.float32)), dev(x_snap)
+    dq.dq_vr_grad(P, dev(idx.astype(np.int32)), M, B, xq_d, dx_d, 8, False, xs_d, None, alpha, amax, None, ws)
+    assert np.isnan(host(alpha)[0]).all() and np.isnan(host(amax)[0])
+    _close(host(alpha)[1], oracle.vr_grad(rp, idx[1].astype(np.int32), q, x_snap).astype(np.float64))
+    nw = dq.packed_words(d, 8)
+    packed = torch.zeros((M, (nw + 3) // 4 * 4), dtype=torch.int32, device="cuda")
+    delta = torch.zeros(M, device="cuda")
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    dq.dq_worker_step(P, dev(idx.astype(np.int32)), M, B, xq_d, dx_d, 8, False, xs_d, None, False, 8, 5, 1, 0, packed, delta,
+                      None, None, status, ws)
+    assert host(status)[0] & 1 and np.isnan(host(delta)[0]) and np.isfinite(host(delta)[1])
+
+
 @pytest.mark.parametrize("sparsify", [False, True])
 @pytest.mark.parametrize("b", [8, 4])
 @pytest.mark.parametrize("name,M,B", [("text", 16, 64), ("tiny", 2, 7), ("long", 2, 12), ("wide", 4, 40), ("lastone", 3, 33),
