@@ -178,8 +178,10 @@ int32_t dq_sample_indices(int64_t n, int64_t M, int64_t B, uint64_t seed, uint32
  *   g_out = (1/n) sum_i grad f_i(x) = (1/n) sum_i s_i a_i + l2*x,
  *   s_i = -y_i / (1 + exp(y_i a_i.x)).
  * z_out (nullable, float[n]) receives the margins a_i.x; obj_out (nullable,
- * double[1]) receives P(x) of eq. (1).  Deterministic (fixed summation order
- * for a given problem shape). */
+ * double[1]) receives P(x) of eq. (1).  Deterministic for a given problem shape (dense features: float32
+ * sums in a fixed order; CSR features: the sums over rows are accumulated per column in fixed point -- int32
+ * multiples of a power of two chosen so that no sum can overflow, flushed to float32 every 1024 rows -- and do
+ * not depend on the order of the additions; a term is rounded to within 2^-31 of the bound of its column's sum). */
 int32_t dq_full_grad(const dq_problem *prob /*host*/, const float *x, float *g_out, float *z_out,
                      double *obj_out, void *ws, int64_t ws_bytes, void *stream);
 
@@ -191,7 +193,10 @@ int32_t dq_full_grad(const dq_problem *prob /*host*/, const float *x, float *g_o
  * model_is_snapshot != 0 is the flag-bit case of Section 4.1 (q = x_snap): alpha = 0.
  * z_snap (nullable) = margins a_i.x_snap cached by dq_full_grad; if NULL they
  * are recomputed.  alpha_out rows have stride ld (ld % 4 == 0, 16-byte aligned).
- * absmax_out[M] = ||alpha_m||_inf; l1norm_out (nullable) [M] = ||alpha_m||_1. */
+ * absmax_out[M] = ||alpha_m||_inf; l1norm_out (nullable) [M] = ||alpha_m||_1.
+ * CSR features: the sum over the mini-batch is accumulated in fixed point as in dq_full_grad (bit-reproducible;
+ * the bound, hence the unit, follows the size of the coefficients, which shrink as q approaches x_snap); a NaN
+ * or Inf among the values, labels or cached margins of a mini-batch makes the whole alpha_m NaN. */
 int32_t dq_vr_grad(const dq_problem *prob /*host*/, const int32_t *idx, int64_t M, int64_t B,
                    const uint32_t *xq_packed, const float *delta_x, int32_t b_x,
                    int32_t model_is_snapshot, const float *x_snap, const float *z_snap,

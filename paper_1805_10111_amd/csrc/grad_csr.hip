@@ -6,8 +6,8 @@
 // is reproducible.  One block of 1024 threads owns a worker: the gradient alpha (d floats)
 // lives in LDS for the whole step and never goes to memory.
 //   1. stage: the (column, value) pairs of the mini-batch rows are copied into LDS as one flat run, spread evenly
-//      over the threads whatever the row lengths (the row of an entry is found by a fixed number of halving steps
-//      on the prefix sums of the row lengths and is kept in the bits above the column); the thread that copies an
+//      over the threads whatever the row lengths (the row of an entry comes from a table of the rows at every 64th
+//      entry plus the starts of the next few rows, and is kept in the bits above the column); the thread that copies an
 //      entry also gathers the model and the snapshot at its column and leaves value * operand next to it -- two
 //      trips to memory for the whole mini-batch, however long its longest row;
 //   2. margins: one wavefront per row, four rows in flight, adds up the products of its row from LDS; one lane per
@@ -15,7 +15,8 @@
 //   3. scatter: every thread adds coefficient*value of the entries it staged to the columns' accumulators in LDS --
 //      integer atomic adds of fixed-point terms (see FixedAcc), whose sum does not depend on the order of the adds:
 //      the result is reproducible whichever wavefront gets there first;
-//   4. the tail of the worker step (sparsify, scale, quantize, pack) runs from LDS.
+//   4. the accumulators become float32 in place, the dense part l2*(q - snapshot) added, and the tail of the worker
+//      step (sparsify, scale, quantize, pack) runs from LDS.
 // The full gradient uses the same block procedure over many blocks, each leaving a partial
 // d-vector that a second kernel adds up in a fixed order.
 #include <mutex>
@@ -713,7 +714,7 @@ struct CsrPlan {
 // A staged entry takes 12 bytes of LDS, 16 when the caller needs two sums per row (see CsrStage).
 static bool csr_plan(int64_t d, bool second, CsrPlan &p)
 {
-    if (d >= (1ll << kColBits)) return false;      // column 2^20 - 1 marks the end of the staged entries in the scatter
+    if (d >= (1ll << kColBits)) return false;      // a staged entry keeps its row number above kColBits column bits
     const int64_t budget = kLdsBudget - kCsrFixedLds;                     // bytes for window + staging
     const int64_t each = second ? 16 : 12;
     int64_t nwin = 1;
