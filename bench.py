@@ -244,6 +244,30 @@ def quantizer_leg(dq, torch):
     return out
 
 
+def graph_replay_us_per_round(tr, torch, rounds, repeats=10):
+    """The rounds of one epoch captured once into a graph (dq_run_rounds only enqueues kernels) and replayed:
+    microseconds per round, median over `repeats` replays timed with events on the replaying stream."""
+    tr.epoch_prologue()
+    tr.rounds(0, rounds)                                 # one-time kernel attributes are set outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            tr.rounds(0, rounds)
+    torch.cuda.synchronize()
+    times = []
+    for _ in range(repeats):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1))
+    times.sort()
+    return times[len(times) // 2] / rounds * 1e3
+
+
 def other_configs_leg(dq, torch, synth, Trainer, skip):
     """Rounds of the small, launch-bound configs (C1-C3): microseconds per round and worker-steps/s."""
     out = {}
@@ -260,7 +284,9 @@ def other_configs_leg(dq, torch, synth, Trainer, skip):
         out[name] = {"us_per_round": round(dt / rounds * 1e6, 2), "worker_steps_per_s": round(cfg.M * rounds / dt, 1),
                      "rounds_per_measurement": rounds, "repeats": meas["repeats"], "M": cfg.M, "B": cfg.B, "d": prob.d,
                      "prologue_us": round(meas["prologue_s"] * 1e6, 1),
-                     "note": "launch/latency-bound: under 3 MB of traffic per round; round loop only, as `value`"}
+                     "us_per_round_graph_replay": round(graph_replay_us_per_round(tr, torch, rounds), 2),
+                     "note": "launch/latency-bound: under 3 MB of traffic per round; round loop only, as `value`; "
+                             "graph_replay: the same rounds captured once and replayed"}
         del tr
     return out
 
