@@ -306,4 +306,32 @@ __device__ __forceinline__ void worker_tail_from_lds(float *alpha, int64_t d, bo
     }
 }
 
+// The same tail (without sparsifier, b in {2, 4, 8}) when the block's threads hold the whole gradient in registers, thread t
+// the quad t (coordinates past d are zero): no trip through LDS, one block reduction for the scale.
+template <int FIELD>
+__device__ __forceinline__ void worker_tail_one_quad(float4 v, int64_t d, int b, StreamKey key, const WorkerOut &out,
+                                                     uint32_t *su, int *si, int slice, int nslices)
+{
+    const int64_t quads = (d + 3) / 4;
+    const int64_t per = ((quads + nslices - 1) / nslices + kWave - 1) / kWave * kWave;       // as in worker_tail_from_lds
+    const int64_t q_lo = min(quads, per * slice), q_hi = min(quads, q_lo + per);
+    const int64_t q = threadIdx.x;
+    const uint32_t vmax = block_max_u32(max(max(abs_bits(v.x), abs_bits(v.y)), max(abs_bits(v.z), abs_bits(v.w))), su);
+    const Scale s = make_scale(__uint_as_float(vmax), b);
+    if (threadIdx.x == 0 && slice == 0) {
+        out.delta_out[0] = s.delta;
+        if (s.bad && out.status) atomicOr(out.status, 1u);
+    }
+    key.tag = DQ_TAG_GRAD;
+    int nz = 0;
+    uint32_t bits = 0;
+    if (q >= q_lo && q < q_hi) bits = quantize_quad<FIELD>(v, s, key, q, nz);
+    // (slices begin at multiples of 64 quads: the lanes that share a word are all inside or all outside)
+    store_quad_bits<FIELD>(bits, q >= q_lo ? q : q_hi, q_hi, out.packed);
+    if (out.nnz_out && nslices == 1) {
+        nz = block_sum_i32(nz, si);
+        if (threadIdx.x == 0) out.nnz_out[0] = nz;
+    }
+}
+
 }  // namespace dq

@@ -273,6 +273,24 @@ __device__ __forceinline__ void worker_finish(const VrDenseArgs &a, int m, const
                                               float *sh_alpha, uint32_t *su, int *si, double *sd)
 {
     const int64_t d = a.d;
+    if constexpr (NC == 1) {
+        // thread t holds quad t of the whole gradient (zeros past d): the plain quantization runs from the registers
+        if (a.packed && !a.sparsify && a.b != 32) {            // (the same for every thread)
+            const float4 v = make_float4(acc[0].x + a.l2 * dx[0].x, acc[0].y + a.l2 * dx[0].y, acc[0].z + a.l2 * dx[0].z,
+                                         acc[0].w + a.l2 * dx[0].w);
+            if (a.alpha_out) store_quad(a.alpha_out + static_cast<int64_t>(m) * a.ld, threadIdx.x, d, v);
+            StreamKey key = a.key;
+            key.worker = a.worker0 + static_cast<uint32_t>(m);
+            const WorkerOut out{a.packed + static_cast<int64_t>(m) * a.ld_words, a.row_words, a.delta_out + m,
+                                a.nnz_out ? a.nnz_out + m : nullptr, a.status};
+            switch (a.b) {
+            case 2: worker_tail_one_quad<2>(v, d, a.b, key, out, su, si, 0, 1); break;
+            case 4: worker_tail_one_quad<4>(v, d, a.b, key, out, su, si, 0, 1); break;
+            default: worker_tail_one_quad<8>(v, d, a.b, key, out, su, si, 0, 1); break;
+            }
+            return;
+        }
+    }
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         const int64_t col = 4ll * (threadIdx.x + T * c);
@@ -492,6 +510,10 @@ __global__ __launch_bounds__(kFinishThreads) void vr_dense_finish_kernel(const V
     const int64_t d = a.d;
     const ModelMsg msg{a.xq, a.delta_x[opaque_zero()], a.b_x};     // (b_x = 32: a valid dummy address, value unused)
     const float *base = a.partial + static_cast<int64_t>(m) * a.P * a.ldp;
+    // one sweep covers the vector and the tail is the plain quantization: then thread t keeps quad t in registers and the
+    // tail runs from there (no trip through LDS)
+    const bool in_registers = a.ldp <= 4ll * kFinishThreads && a.packed && !a.sparsify && a.b != 32;
+    float4 mine = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     for (int64_t col = 4ll * threadIdx.x; col < a.ldp; col += 4ll * kFinishThreads) {
         float4 s = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
         int p = 0;
@@ -531,10 +553,23 @@ __global__ __launch_bounds__(kFinishThreads) void vr_dense_finish_kernel(const V
         model_quad_values<MODEL8>(msg, mq, col, d, q);
         const float4 v = make_float4(s.x + a.l2 * (q[0] - xs[0]), s.y + a.l2 * (q[1] - xs[1]), s.z + a.l2 * (q[2] - xs[2]),
                                      s.w + a.l2 * (q[3] - xs[3]));
-        store_quad(sh_alpha_dyn, col >> 2, d, v);
         if constexpr (WANT_ALPHA) {
             if (blockIdx.y == 0) store_quad(a.alpha_out + static_cast<int64_t>(m) * a.ld, col >> 2, d, v);
         }
+        if (in_registers) mine = v;
+        else store_quad(sh_alpha_dyn, col >> 2, d, v);
+    }
+    if (in_registers) {                  // (the same for every thread of the block)
+        StreamKey key = a.key;
+        key.worker = a.worker0 + static_cast<uint32_t>(m);
+        const WorkerOut out{a.packed + static_cast<int64_t>(m) * a.ld_words, a.row_words, a.delta_out + m,
+                            a.nnz_out ? a.nnz_out + m : nullptr, a.status};
+        switch (a.b) {
+        case 2: worker_tail_one_quad<2>(mine, d, a.b, key, out, su, si, blockIdx.y, gridDim.y); break;
+        case 4: worker_tail_one_quad<4>(mine, d, a.b, key, out, su, si, blockIdx.y, gridDim.y); break;
+        default: worker_tail_one_quad<8>(mine, d, a.b, key, out, su, si, blockIdx.y, gridDim.y); break;
+        }
+        return;
     }
     __syncthreads();
     // gridDim.y identical blocks per worker: each has the whole alpha and quantizes its own slice of it
