@@ -231,7 +231,8 @@ def test_rounds_enqueued_together_equal_rounds_enqueued_one_by_one_sparse_featur
 @pytest.mark.parametrize("b,M,each,b_x,counts", [(4, 16, False, 8, True), (8, 24, False, 8, True), (4, 5, True, 4, True),
                                                   (8, 32, True, 32, True), (2, 8, False, 8, True), (2, 8, False, 8, False),
                                                   (4, 20, False, 8, False)])
-def test_master_that_quantizes_the_sparsified_gradients_equals_the_separate_steps(dq, b, M, each, b_x, counts):
+@pytest.mark.parametrize("shape", ["C3", "ragged"])
+def test_master_that_quantizes_the_sparsified_gradients_equals_the_separate_steps(dq, b, M, each, b_x, counts, shape):
     """Alg. 2 on CSR features wide enough for the sparsifier to be split over several blocks per worker: inside
     dq_run_rounds the master kernel quantizes the workers' sparsified gradients while it aggregates them.  A round
     enqueued that way must leave messages, scales, nonzero counts, the model and the model's message bit for bit
@@ -239,7 +240,9 @@ def test_master_that_quantizes_the_sparsified_gradients_equals_the_separate_step
     workers than one pass of the kernel takes; b = 2 with nonzero counts: the route is not taken, both sides are the
     separate steps; without counts (`nnz` null in the run state) 2-bit messages take it too)."""
     from paper_1805_10111_amd.driver import DoubleQuantTrainer
-    p = synth.make_problem(synth.CONFIGS["C3"], n=3000)
+    # ("ragged": 4099 columns, the narrowest kind of model the route is taken for, its last quad one coordinate long)
+    p = synth.make_problem(synth.CONFIGS["C3"], n=3000) if shape == "C3" else \
+        synth.sparse_text_logistic(500, 4099, mean_nnz=30.0, seed=3)
     P = dq.DeviceProblem.from_host(p)
     B, m, seed = 32, 4, 9
     one = DoubleQuantTrainer(P, "sparse", M, B, b_x, b, m, 0.5, seed=seed, each=each)
