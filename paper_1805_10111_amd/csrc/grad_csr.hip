@@ -415,8 +415,11 @@ struct CsrWorkerArgs {
     // sparsifier split over the identical blocks of a worker (beta_ws != null): each block sparsifies its slice into
     // row m of beta_ws and leaves the slice's largest magnitude and kept count; the quantization is a second launch
     float *beta_ws; float *part_max; int32_t *part_kept;
+    const float *model_diff;       // nullable: (decoded model) - snapshot for every column, see WorkerArgs::model_diff
 };
 
+// DIFF: the model comes as a.model_diff (one float per column) instead of the message and the snapshot.
+template <bool DIFF>
 __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorkerArgs a)
 {
     extern __shared__ __align__(16) float lds[];
@@ -445,13 +448,18 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     uint32_t seen_max = 0;                                     // largest magnitude among the coordinates this thread finishes
     // the model value and the snapshot at column c: the field of column c starts at bit c*b_x of the message and
     // may continue in the next word; both words and the snapshot value are requested without any condition
-    struct Gather { uint32_t w0, w1; float xs; };
+    struct Gather { uint32_t w0, w1; float xs, diff; };
     const bool straddles = (32 % a.b_x) != 0;                 // (the same for every thread) else a field lies in one word
     auto vec_req = [&](int c) {
-        const int w = (c * a.b_x) >> 5, last = static_cast<int>(a.model_last_word);   // (fewer than 2^20 words)
-        return Gather{a.xq[w], straddles ? a.xq[w + 1 < last ? w + 1 : last] : 0u, a.x_snap[c]};
+        if constexpr (DIFF) {
+            return Gather{0u, 0u, a.x_snap[c], a.model_diff[c]};     // (the snapshot value is only used without cached margins)
+        } else {
+            const int w = (c * a.b_x) >> 5, last = static_cast<int>(a.model_last_word);   // (fewer than 2^20 words)
+            return Gather{a.xq[w], straddles ? a.xq[w + 1 < last ? w + 1 : last] : 0u, a.x_snap[c], 0.0f};
+        }
     };
     auto vec_val = [&](const Gather &g, int c) {
+        if constexpr (DIFF) return make_float2(g.diff, g.xs);
         const uint32_t bits = __funnelshift_r(g.w0, g.w1, static_cast<unsigned>(c * a.b_x) & 31u);
         const float q = a.b_x == 32 ? __uint_as_float(bits)
                                     : msg.delta_x * static_cast<float>(sext_field(bits, 0, static_cast<unsigned>(a.b_x)));
@@ -527,11 +535,29 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
             };
             const auto slow_quad = [&](int64_t j) {
                 float t[4];
-                for (int e = 0; e < 4; ++e) t[e] = j + e < d ? a.l2 * (model_value(msg, j + e) - a.x_snap[j + e]) : 0.0f;
+                for (int e = 0; e < 4; ++e) {
+                    if constexpr (DIFF) t[e] = j + e < d ? a.l2 * a.model_diff[j + e] : 0.0f;
+                    else t[e] = j + e < d ? a.l2 * (model_value(msg, j + e) - a.x_snap[j + e]) : 0.0f;
+                }
                 finish_quad(j, make_float4(t[0], t[1], t[2], t[3]));
             };
             const int64_t whole = min(c1p, d / 4 * 4);            // whole quads of the vector end here
-            if (a.b_x == 8) {
+            if constexpr (DIFF) {
+                constexpr int kInitFlight = 6;                   // (as below: requested together, at clamped positions)
+                for (int64_t j0 = c0 + 4ll * threadIdx.x; j0 < whole; j0 += 4ll * kCsrThreads * kInitFlight) {
+                    float4 df[kInitFlight];
+#pragma unroll
+                    for (int u = 0; u < kInitFlight; ++u)
+                        df[u] = *reinterpret_cast<const float4 *>(
+                            a.model_diff + min<int64_t>(j0 + 4ll * kCsrThreads * u, whole - 4));
+#pragma unroll
+                    for (int u = 0; u < kInitFlight; ++u) {
+                        const int64_t j = j0 + 4ll * kCsrThreads * u;
+                        if (j < whole) finish_quad(j, make_float4(a.l2 * df[u].x, a.l2 * df[u].y, a.l2 * df[u].z, a.l2 * df[u].w));
+                    }
+                }
+                if (threadIdx.x == 0 && whole >= c0 && whole < c1p) slow_quad(whole);      // the vector ends inside a quad
+            } else if (a.b_x == 8) {
                 // the loads of kInitFlight steps are requested together (at clamped positions: a load behind a
                 // per-lane test would be waited for before the next one is issued)
                 constexpr int kInitFlight = 6;
@@ -748,7 +774,13 @@ int64_t csr_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64
         return P * pad4(prob->d) * 4 + P * 8;
     }
     // a row per worker: the whole gradient when it does not fit in LDS, else the sparsified gradient when the
-    // sparsifier is split over several blocks per worker (see csr_worker); then 8 values + 8 counts per worker
+    // sparsifier is split over several blocks per worker (see csr_worker); then 8 values + 8 counts per worker; then
+    // one more row, in which dq_run_rounds keeps (decoded model) - snapshot between two rounds of a call
+    return csr_model_diff_offset(prob, M) + pad4(prob->d) * 4;
+}
+
+int64_t csr_model_diff_offset(const dq_problem *prob, int64_t M)
+{
     return M * pad4(prob->d) * 4 + M * kMaxSlices * 8;
 }
 
@@ -808,9 +840,11 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     k.cap = plan.cap; k.win = plan.win;
     k.alpha_ws = plan.nwin > 1 ? static_cast<float *>(a.ws) : nullptr; k.ld_ws = pad4(d);
     const size_t lds = plan.lds;
-    static std::once_flag attr_once;
-    static hipError_t attr_rc = hipSuccess;
-    int rc = allow_big_lds(csr_worker_kernel, attr_once, attr_rc);
+    k.model_diff = a.b_x == 32 ? nullptr : a.model_diff;
+    static std::once_flag attr_once, attr_once_diff;
+    static hipError_t attr_rc = hipSuccess, attr_rc_diff = hipSuccess;
+    int rc = k.model_diff ? allow_big_lds(csr_worker_kernel<true>, attr_once_diff, attr_rc_diff)
+                          : allow_big_lds(csr_worker_kernel<false>, attr_once, attr_rc);
     if (rc != DQ_OK) return rc;
     // Few workers leave most compute units idle while each block spends a third of its time on the Philox rounds of
     // the final quantization: then several identical blocks per worker share that part (not when the nonzero count is
@@ -829,11 +863,12 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
         k.part_max = k.beta_ws + a.M * k.ld_ws;
         k.part_kept = reinterpret_cast<int32_t *>(k.part_max + a.M * kMaxSlices);
     }
+    const dim3 grid(static_cast<unsigned>(a.M), slices), block(kCsrThreads);
+    const auto kernel = k.model_diff ? csr_worker_kernel<true> : csr_worker_kernel<false>;
     if (a.ev_start && a.ev_stop)      // the kernel's own start and end times go to the two events
-        hipExtLaunchKernelGGL(csr_worker_kernel, dim3(static_cast<unsigned>(a.M), slices), dim3(kCsrThreads),
-                              static_cast<uint32_t>(lds), st, a.ev_start, a.ev_stop, 0u, k);
+        hipExtLaunchKernelGGL(kernel, grid, block, static_cast<uint32_t>(lds), st, a.ev_start, a.ev_stop, 0u, k);
     else
-        csr_worker_kernel<<<dim3(static_cast<unsigned>(a.M), slices), dim3(kCsrThreads), lds, st>>>(k);
+        kernel<<<grid, block, lds, st>>>(k);
     DQ_LAUNCH_CHECK();
     if (a.deferred) *a.deferred = SparsifiedParts{nullptr, 0, nullptr, nullptr, 0};
     if (split_sparsifier && a.deferred) {             // the master quantizes while it aggregates

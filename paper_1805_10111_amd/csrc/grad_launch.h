@@ -52,6 +52,10 @@ struct WorkerArgs {
     // `nnz_out` stay untouched -- and describes what it left in *deferred for master_step_from_parts_impl, which
     // quantizes while it aggregates.  deferred->parts == 0 on return: the step was a complete one.
     SparsifiedParts *deferred;
+    // CSR features (nullable): model_diff[c] = (model as decoded from `xq`) - x_snap[c] for every column, formed by
+    // the master of the previous round (master_leaves_model_diff) in exactly the worker's arithmetic; the worker then
+    // reads one float per column instead of decoding the message and subtracting the snapshot.
+    const float *model_diff;
 };
 
 // Whether the dense worker step can take the model from x_model (see WorkerArgs) for this shape.
@@ -71,7 +75,12 @@ int32_t master_step_impl(const uint32_t *packed, int64_t ld_words, const float *
                          int each, const float *g_snap, float *x, float *y, const float *x_snap, float *xsum, float eta,
                          float theta, float l1, int64_t d, int32_t b_x, uint64_t seed, uint32_t iter,
                          uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out, uint32_t *status,
-                         bool absmax_zeroed, void *stream);
+                         bool absmax_zeroed, void *stream, float *model_diff_out = nullptr);
+
+// model_diff_out (nullable, d floats; master_step_impl and master_step_from_parts_impl): the master also leaves
+// Q(x) - x_snap, the difference every worker of the next round needs (WorkerArgs::model_diff) -- when it quantizes the
+// model in a launch of its own with a message width of 2, 4 or 8 bits, which this function tells beforehand.
+bool master_leaves_model_diff(int64_t d, int32_t b_x, bool from_parts);
 
 // The master step of a round of Alg. 2 whose workers deferred their quantization (WorkerArgs::deferred): one kernel
 // quantizes the M sparsified gradients with the workers' streams (seed, worker_iter, worker0 + m, DQ_TAG_GRAD), stores the
@@ -81,7 +90,8 @@ int32_t master_step_from_parts_impl(const SparsifiedParts &parts, uint32_t worke
                                     float *delta_out, int32_t *nnz_out, int64_t M, int32_t b, float scale, int each,
                                     const float *g_snap, float *x, float eta, float l1, int64_t d, int32_t b_x,
                                     uint64_t seed, uint32_t iter, uint32_t *xq_packed_out, float *delta_x_out,
-                                    float *absmax_x_out, uint32_t *status, bool absmax_zeroed, void *stream);
+                                    float *absmax_x_out, uint32_t *status, bool absmax_zeroed, void *stream,
+                                    const float *x_snap = nullptr, float *model_diff_out = nullptr);
 
 int64_t dense_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64_t B);
 int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float *z_out, double *obj_out, void *ws,
@@ -89,6 +99,8 @@ int dense_full_grad(const dq_problem *prob, const float *x, float *g_out, float 
 int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st);
 
 int64_t csr_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64_t B);
+// where in a DQ_OP_VR_GRAD workspace of a CSR problem dq_run_rounds keeps the d floats of WorkerArgs::model_diff
+int64_t csr_model_diff_offset(const dq_problem *prob, int64_t M);
 int csr_full_grad(const dq_problem *prob, const float *x, float *g_out, float *z_out, double *obj_out, void *ws,
                   int64_t ws_bytes, hipStream_t st);
 int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st);

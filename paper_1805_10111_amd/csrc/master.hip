@@ -13,6 +13,9 @@ int fill_u32(uint32_t *p, int64_t n, uint32_t value, hipStream_t st);
 int launch_quantize_pack(const float *v, int64_t d, int64_t M, int64_t ld, int b, int field, const float *absmax,
                          const StreamKey &key, uint32_t worker0, uint32_t *packed, int64_t ld_words, float *delta_out,
                          uint32_t *status, hipStream_t st);
+int launch_quantize_pack_model_diff(const float *x, int64_t d, int b_x, const float *absmax, const StreamKey &key,
+                                    uint32_t *packed, float *delta_out, uint32_t *status, const float *x_snap,
+                                    float *diff_out, hipStream_t st);
 
 constexpr int kThreads = 256;
 
@@ -509,9 +512,14 @@ static int32_t check_master_args(const uint32_t *packed, int64_t ld_words, const
 }
 
 // Alg. 1, master (i) once ||x||_inf is known: the message (and its scale) of the updated model.
+// diff_out (nullable, with x_snap; message widths 2, 4, 8): also receives Q(x) - x_snap, see master_leaves_model_diff.
 static int model_message(const float *x, int64_t d, int32_t b_x, const StreamKey &key, uint32_t *xq_packed_out,
-                         float *delta_x_out, const float *absmax_x, uint32_t *status, hipStream_t st)
+                         float *delta_x_out, const float *absmax_x, uint32_t *status, hipStream_t st,
+                         const float *x_snap = nullptr, float *diff_out = nullptr)
 {
+    if (diff_out && x_snap && (b_x == 2 || b_x == 4 || b_x == 8))
+        return launch_quantize_pack_model_diff(x, d, b_x, absmax_x, key, xq_packed_out, delta_x_out, status, x_snap,
+                                               diff_out, st);
     if (b_x == 32) {
         // full-precision model: "packed" output is x itself, delta is 1
         copy_f32_kernel<<<dim3(static_cast<unsigned>(ceil_div(d, kThreads))), dim3(kThreads), 0, st>>>(
@@ -554,7 +562,7 @@ int32_t dq::master_step_impl(const uint32_t *packed, int64_t ld_words, const flo
                              float scale, int each, const float *g_snap, float *x, float *y, const float *x_snap,
                              float *xsum, float eta, float theta, float l1, int64_t d, int32_t b_x, uint64_t seed,
                              uint32_t iter, uint32_t *xq_packed_out, float *delta_x_out, float *absmax_x_out,
-                             uint32_t *status, bool absmax_zeroed, void *stream)
+                             uint32_t *status, bool absmax_zeroed, void *stream, float *model_diff_out)
 {
     int32_t rc0 = check_master_args(packed, ld_words, delta, M, b, g_snap, x, y, x_snap, xsum, d);
     if (rc0 != DQ_OK) return rc0;
@@ -588,14 +596,20 @@ int32_t dq::master_step_impl(const uint32_t *packed, int64_t ld_words, const flo
     default: rc = launch_master_update<32>(acc, grid, st, a, absmax_bits); break;
     }
     if (rc != DQ_OK) return rc;
-    return model_message(x, d, b_x, key, xq_packed_out, delta_x_out, absmax_x_out, status, st);
+    return model_message(x, d, b_x, key, xq_packed_out, delta_x_out, absmax_x_out, status, st, x_snap, model_diff_out);
+}
+
+bool dq::master_leaves_model_diff(int64_t d, int32_t b_x, bool from_parts)
+{
+    return (b_x == 2 || b_x == 4 || b_x == 8) && (from_parts || d > kFusedMaxD);
 }
 
 int32_t dq::master_step_from_parts_impl(const SparsifiedParts &parts, uint32_t worker0, uint32_t worker_iter, uint32_t *packed, int64_t ld_words,
                                         float *delta_out, int32_t *nnz_out, int64_t M, int32_t b, float scale, int each,
                                         const float *g_snap, float *x, float eta, float l1, int64_t d, int32_t b_x,
                                         uint64_t seed, uint32_t iter, uint32_t *xq_packed_out, float *delta_x_out,
-                                        float *absmax_x_out, uint32_t *status, bool absmax_zeroed, void *stream)
+                                        float *absmax_x_out, uint32_t *status, bool absmax_zeroed, void *stream,
+                                        const float *x_snap, float *model_diff_out)
 {
     int32_t rc0 = check_master_args(packed, ld_words, delta_out, M, b, g_snap, x, nullptr, nullptr, nullptr, d);
     if (rc0 != DQ_OK) return rc0;
@@ -624,7 +638,7 @@ int32_t dq::master_step_from_parts_impl(const SparsifiedParts &parts, uint32_t w
 #undef DQ_PARTS
     DQ_LAUNCH_CHECK();
     const StreamKey key{static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), iter, 0u, DQ_TAG_MODEL};
-    return model_message(x, d, b_x, key, xq_packed_out, delta_x_out, absmax_x_out, status, st);
+    return model_message(x, d, b_x, key, xq_packed_out, delta_x_out, absmax_x_out, status, st, x_snap, model_diff_out);
 }
 
 extern "C" int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
@@ -634,7 +648,7 @@ extern "C" int32_t dq_master_step(const uint32_t *packed, int64_t ld_words, cons
                                   void *stream)
 {
     return master_step_impl(packed, ld_words, delta, M, b, scale, 0, g_snap, x, y, x_snap, xsum, eta, theta, l1, d, b_x,
-                            seed, iter, xq_packed_out, delta_x_out, absmax_x_out, status, false, stream);
+                            seed, iter, xq_packed_out, delta_x_out, absmax_x_out, status, false, stream, nullptr);
 }
 
 extern "C" int32_t dq_master_step_each(const uint32_t *packed, int64_t ld_words, const float *delta, int64_t M, int32_t b,
@@ -644,7 +658,7 @@ extern "C" int32_t dq_master_step_each(const uint32_t *packed, int64_t ld_words,
                                        uint32_t *status, void *stream)
 {
     return master_step_impl(packed, ld_words, delta, M, b, 1.0f, 1, g_snap, x, y, x_snap, xsum, eta, theta, l1, d, b_x,
-                            seed, iter, xq_packed_out, delta_x_out, absmax_x_out, status, false, stream);
+                            seed, iter, xq_packed_out, delta_x_out, absmax_x_out, status, false, stream, nullptr);
 }
 
 extern "C" int32_t dq_acc_mix(const float *y, const float *x_snap, float theta, int64_t d, float *x_out, void *stream)

@@ -287,12 +287,15 @@ __device__ __forceinline__ void store16_tile(float *__restrict__ tile, float4 *_
 // coordinates it pays for 8-bit fields only (228 -> 220 us); with narrower fields, whose packing costs more
 // arithmetic, the kernel is bound by instruction issue and the exchange costs more than the better access pattern
 // brings (4 bits 214 -> 217 us, 2 bits 197 -> 212 us).
-template <int FIELD, bool TILE = FIELD == 8>
+// DIFF (one row, the model message of Alg. 1, master (i)): the kernel also leaves what it quantized minus another
+// vector, diff_out[i] = delta * code_i - diff_from[i] -- the model a worker decodes minus the snapshot, which every
+// worker of the next round would otherwise form again, per column it touches, from the message.
+template <int FIELD, bool TILE = FIELD == 8, bool DIFF = false>
 __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(
     const float *__restrict__ v, int64_t d, int64_t ld, const float *__restrict__ absmax, int b, StreamKey key,
     uint32_t worker0, uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words,
     float *__restrict__ delta_out, uint32_t *__restrict__ status, int parts, const int32_t *__restrict__ count_parts,
-    int32_t *__restrict__ count_out)
+    int32_t *__restrict__ count_out, const float *__restrict__ diff_from = nullptr, float *__restrict__ diff_out = nullptr)
 {
     const int m = blockIdx.y;
     const float *row = v + static_cast<int64_t>(m) * ld;
@@ -323,9 +326,16 @@ __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(
             if (c >= chunks) continue;
             load16(row, c * kCoordsPerThread, d, a);         // coordinates past d read as 0 -> code 0
         }
+        float other[16];
+        if constexpr (DIFF) load16(diff_from, c * kCoordsPerThread, d, other);      // (requested before the Philox rounds)
         uint32_t w[Words16<FIELD>::n];
         quantize16<FIELD>(a, s, key, c, w);
         store_words<FIELD>(out, c, row_words, w);
+        if constexpr (DIFF) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) other[j] = s.delta * static_cast<float>(code_of<FIELD>(w, j)) - other[j];
+            store16<false>(diff_out, c * kCoordsPerThread, d, other);
+        }
     }
 }
 
@@ -340,6 +350,23 @@ int launch_quantize_pack(const float *v, int64_t d, int64_t M, int64_t ld, int b
 {
     return launch_quantize_pack_parts(v, d, M, ld, b, field, absmax, 1, nullptr, nullptr, key, worker0, packed, ld_words,
                                       delta_out, status, st);
+}
+
+// The model message (one row) together with diff_out = Q(x) - x_snap (see DIFF); widths 2, 4, 8.
+int launch_quantize_pack_model_diff(const float *x, int64_t d, int b_x, const float *absmax, const StreamKey &key,
+                                    uint32_t *packed, float *delta_out, uint32_t *status, const float *x_snap,
+                                    float *diff_out, hipStream_t st)
+{
+    const int64_t row_words = packed_words(d, b_x);
+    const dim3 grid = grid_for(d, 1), block(kThreads);
+    switch (b_x) {
+    case 8: quantize_pack_kernel<8, false, true><<<grid, block, 0, st>>>(x, d, d, absmax, b_x, key, DQ_MASTER_ID, packed, row_words, row_words, delta_out, status, 1, nullptr, nullptr, x_snap, diff_out); break;
+    case 4: quantize_pack_kernel<4, false, true><<<grid, block, 0, st>>>(x, d, d, absmax, b_x, key, DQ_MASTER_ID, packed, row_words, row_words, delta_out, status, 1, nullptr, nullptr, x_snap, diff_out); break;
+    case 2: quantize_pack_kernel<2, false, true><<<grid, block, 0, st>>>(x, d, d, absmax, b_x, key, DQ_MASTER_ID, packed, row_words, row_words, delta_out, status, 1, nullptr, nullptr, x_snap, diff_out); break;
+    default: return DQ_ERR_UNSUPPORTED;
+    }
+    DQ_LAUNCH_CHECK();
+    return DQ_OK;
 }
 
 // absmax holds `parts` values per row (the row's scale comes from their maximum); count_parts / count_out: optional

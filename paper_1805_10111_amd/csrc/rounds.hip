@@ -51,6 +51,15 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
     // Alg. 2, one group of workers, messages not crossing as (position, value) streams: a worker step whose sparsifier
     // is split over several blocks leaves the quantization of its messages to the master kernel (one launch less)
     const bool defer_ok = cfg->algo == DQ_ALGO_SPARSE && cfg->b != 32 && cfg->tau == 0 && !st->wire;
+    // CSR features, one group of workers: the master that quantizes the model in a launch of its own also leaves
+    // (decoded model) - snapshot in the workspace for the workers of the next round of this call
+    const bool csr = prob->layout == 1;
+    float *model_diff = nullptr;
+    if (csr && cfg->tau == 0 && st->ws) {
+        const int64_t off = dq::csr_model_diff_offset(prob, cfg->M);
+        if (st->ws_bytes >= off + (prob->d + 3) / 4 * 4 * 4) model_diff = reinterpret_cast<float *>(static_cast<char *>(st->ws) + off);
+    }
+    bool diff_ready = false;             // model_diff holds the difference for the model message of this round
     bool model_pending = false;          // the model of this round is still x itself (not yet a message)
     for (int64_t t = t0; t < t0 + rounds; ++t) {
         const uint32_t it = static_cast<uint32_t>(epoch * cfg->m + t);
@@ -92,6 +101,7 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
                 w.absmax_model = st->absmax_x + ((t - 1) & 1);
             }
             if (defer_ok) w.deferred = &parts;
+            if (diff_ready) w.model_diff = model_diff;
             if (worker_events && g == 0) {                       // (a null pair: this round's launch is a plain one)
                 w.ev_start = static_cast<hipEvent_t>(worker_events[2 * (t - t0)]);
                 w.ev_stop = static_cast<hipEvent_t>(worker_events[2 * (t - t0) + 1]);
@@ -110,12 +120,16 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
         uint32_t *xq_next = st->xq + ((t + 1) % slots) * st->xq_stride_words;
         float *dx_next = st->delta_x + ((t + 1) % slots);
         model_pending = fusable && t + 1 < t0 + rounds;
+        // (the difference is of use only to a next round of this call)
+        float *diff_out = (model_diff && t + 1 < t0 + rounds &&
+                           dq::master_leaves_model_diff(prob->d, cfg->b_x, parts.parts > 0)) ? model_diff : nullptr;
+        diff_ready = diff_out != nullptr;
         if (parts.parts > 0)
             rc = dq::master_step_from_parts_impl(parts, 0u, it, st->packed, st->ld_words, st->delta,
                                                  st->nnz ? st->nnz + t * cfg->M : nullptr, cfg->M, cfg->b, scale, cfg->each,
                                                  st->g_snap, st->x, eta, prob->l1, prob->d, cfg->b_x, cfg->seed, it + 1u,
                                                  xq_next, dx_next, st->absmax_x + (t & 1), st->status,
-                                                 /*absmax_zeroed=*/true, stream);
+                                                 /*absmax_zeroed=*/true, stream, st->x_snap, diff_out);
         else if (model_pending)
             rc = dq::master_update_impl(st->packed, st->ld_words, st->delta, cfg->M, cfg->b, scale, cfg->each, st->g_snap,
                                         st->x, acc ? st->y : nullptr, st->x_snap, acc ? st->xsum : nullptr, eta, theta,
@@ -124,7 +138,7 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
             rc = dq::master_step_impl(st->packed, st->ld_words, st->delta, cfg->M, cfg->b, scale, cfg->each, st->g_snap,
                                       st->x, acc ? st->y : nullptr, st->x_snap, acc ? st->xsum : nullptr, eta, theta,
                                       prob->l1, prob->d, cfg->b_x, cfg->seed, it + 1u, xq_next, dx_next,
-                                      st->absmax_x + (t & 1), st->status, /*absmax_zeroed=*/true, stream);
+                                      st->absmax_x + (t & 1), st->status, /*absmax_zeroed=*/true, stream, diff_out);
         if (rc != DQ_OK) return rc;
     }
     return DQ_OK;

@@ -379,7 +379,8 @@ def test_flag_bit_round_and_limits(dq, problems):
     # a gradient that does not fit on chip needs the worker workspace
     pw = problems["wide"]
     Pw = dq.DeviceProblem.from_host(pw)
-    assert dq.dq_workspace_bytes(dq.OP_VR_GRAD, Pw, 3, 4) == 3 * ((pw.d + 3) // 4 * 4) * 4 + 3 * 8 * 8
+    row = (pw.d + 3) // 4 * 4 * 4                      # (a row per worker, slice results, one row for dq_run_rounds)
+    assert dq.dq_workspace_bytes(dq.OP_VR_GRAD, Pw, 3, 4) == 3 * row + 3 * 8 * 8 + row
     with pytest.raises(dq.DqError) as e:
         dq.dq_worker_step(Pw, None, 3, 4, torch.zeros(pw.d, dtype=torch.int32, device="cuda"), torch.ones(1, device="cuda"),
                           8, False, torch.zeros(pw.d, device="cuda"), None, False, 8, 1, 1, 0,
