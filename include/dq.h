@@ -61,8 +61,8 @@ extern "C" {
 #define DQ_MASTER_ID     0xFFFFFFFFu   /* worker id used for the master's own stream       */
 
 /* Finite-sum problem of eq. (1) with logistic loss (Section 5.1).
- * layout 0: dense row-major features, row i at dense + i*lda, lda % 4 == 0,
- *           dense 16-byte aligned.
+ * layout 0: dense row-major features, row i at dense + i*lda, lda % 4 == 0, lda >= d,
+ *           dense 16-byte aligned and n*lda floats long (the padding of a row may be read, never used).
  * layout 1: CSR; indptr[n+1], indices sorted and unique within a row; indices and values must
  *           be non-null even when the matrix has no nonzeros (they are then never read).
  * y[n] holds +1/-1.  l2 multiplies ||x||^2/2 inside every f_i (smooth part),

@@ -422,6 +422,7 @@ struct CsrWorkerArgs {
 template <bool DIFF>
 __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorkerArgs a)
 {
+    touch_kernel_arguments<sizeof(CsrWorkerArgs)>();
     extern __shared__ __align__(16) float lds[];
     __shared__ RowMeta meta;
     __shared__ float sh_y[kCsrMaxRows];

@@ -37,25 +37,56 @@ constexpr int kMaxRowsPerBlock = 64;             // mini-batch rows a block may 
 // marked non-temporal; the contiguous sweep of the full gradient is faster without the mark (measured).
 // FULL: d equals 4 * T * NC, every column of every thread is a whole float4 inside the row and the loads
 // carry no condition at all.
-template <int NC, bool STREAM = false, bool FULL = false, int T = kRowThreads>
-__device__ __forceinline__ void load_cols(const float *__restrict__ row, int64_t d, float4 (&a)[NC])
+// The thread's columns of a vector of exactly d floats (zeros past its end).
+template <int NC, bool FULL = false, int T = kRowThreads>
+__device__ __forceinline__ void load_vec_cols(const float *__restrict__ v, int64_t d, float4 (&a)[NC])
 {
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         const int64_t col = 4ll * (threadIdx.x + T * c);
         if (FULL || col + 3 < d) {
-            if constexpr (STREAM) {
-                typedef float v4f __attribute__((ext_vector_type(4)));
-                const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(row + col));
-                a[c] = make_float4(t.x, t.y, t.z, t.w);
-            } else {
-                a[c] = *reinterpret_cast<const float4 *>(row + col);
-            }
+            a[c] = *reinterpret_cast<const float4 *>(v + col);
         } else {
-            a[c].x = col + 0 < d ? row[col + 0] : 0.0f;
-            a[c].y = col + 1 < d ? row[col + 1] : 0.0f;
-            a[c].z = col + 2 < d ? row[col + 2] : 0.0f;
+            a[c].x = col + 0 < d ? v[col + 0] : 0.0f;
+            a[c].y = col + 1 < d ? v[col + 1] : 0.0f;
+            a[c].z = col + 2 < d ? v[col + 2] : 0.0f;
             a[c].w = 0.0f;
+        }
+    }
+}
+
+// The thread's columns of a feature row (row stride lda >= d rounded up to 4, so the quad that holds the row's last
+// coordinate lies inside the row's own stride).  Without FULL the loads still carry no condition -- a test per lane
+// in front of a load, or a select behind it, is a wait for every load in flight, once per row --: a column past the
+// end reads the row's last quad instead, and mask_cols() clears what is not part of the row when the row is used.
+template <int NC, bool STREAM = false, bool FULL = false, int T = kRowThreads>
+__device__ __forceinline__ void load_cols(const float *__restrict__ row, int64_t d, float4 (&a)[NC])
+{
+    const int64_t last = (d + 3) / 4 * 4 - 4;
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        const int64_t col = FULL ? 4ll * (threadIdx.x + T * c) : min<int64_t>(4ll * (threadIdx.x + T * c), last);
+        if constexpr (STREAM) {
+            typedef float v4f __attribute__((ext_vector_type(4)));
+            const v4f t = __builtin_nontemporal_load(reinterpret_cast<const v4f *>(row + col));
+            a[c] = make_float4(t.x, t.y, t.z, t.w);
+        } else {
+            a[c] = *reinterpret_cast<const float4 *>(row + col);
+        }
+    }
+}
+
+template <int NC, bool FULL = false, int T = kRowThreads>
+__device__ __forceinline__ void mask_cols(float4 (&a)[NC], int64_t d)
+{
+    if constexpr (!FULL) {
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            const int64_t col = 4ll * (threadIdx.x + T * c);
+            a[c].x = col + 0 < d ? a[c].x : 0.0f;
+            a[c].y = col + 1 < d ? a[c].y : 0.0f;
+            a[c].z = col + 2 < d ? a[c].z : 0.0f;
+            a[c].w = col + 3 < d ? a[c].w : 0.0f;
         }
     }
 }
@@ -325,6 +356,7 @@ __device__ __forceinline__ int opaque_zero()
 template <int NC, int R, bool HAVE_Z, bool FULL, int DB, int T, int MODEL>
 __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
 {
+    touch_kernel_arguments<sizeof(VrDenseArgs)>();
     constexpr int kWaves = T / kWave;
     __shared__ float sh_red[2 * kWaves * R * 2];
     // the in-kernel tail (one block owns the worker's whole mini-batch) exists for rows of up to 4096 floats;
@@ -406,10 +438,11 @@ __global__ __launch_bounds__(T) void vr_dense_kernel(const VrDenseArgs a)
         for (int r = 0; r < R; ++r)
             load_cols<NC, true, FULL, T>(a.X + static_cast<int64_t>(row_number(rb + r)) * a.lda, d, row[r]);
     };
-    auto compute_batch = [&](int rb, const float4 (&row)[R][NC]) {
+    auto compute_batch = [&](int rb, float4 (&row)[R][NC]) {
         float dots[HAVE_Z ? R : 2 * R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
+            mask_cols<NC, FULL, T>(row[r], d);
             dots[r] = dot_cols<NC>(row[r], dx);
             if constexpr (!HAVE_Z) dots[R + r] = dot_cols<NC>(row[r], xs);
         }
@@ -502,6 +535,7 @@ constexpr int kFinishThreads = 1024;
 template <bool MODEL8, bool WANT_ALPHA>
 __global__ __launch_bounds__(kFinishThreads) void vr_dense_finish_kernel(const VrDenseArgs a)
 {
+    touch_kernel_arguments<sizeof(VrDenseArgs)>();
     extern __shared__ __align__(16) float sh_alpha_dyn[];
     __shared__ uint32_t su[kFinishThreads / kWave];
     __shared__ int si[kFinishThreads / kWave];
@@ -624,7 +658,7 @@ __global__ __launch_bounds__(T) void full_dense_partial_kernel(
     const int64_t i0 = blockIdx.x * per, i1 = min(n, i0 + per);
     float4 xv[NC], acc[NC];
     zero_cols<NC>(acc);
-    load_cols<NC, false, FULL, T>(x, d, xv);
+    load_vec_cols<NC, FULL, T>(x, d, xv);
     const float inv_n = 1.0f / static_cast<float>(n);
     double loss = 0.0;
     int buf = 0;
@@ -640,10 +674,13 @@ __global__ __launch_bounds__(T) void full_dense_partial_kernel(
         }
     };
     // rows c0 + rel .. of the current chunk (cn rows); labels in sh_y, margins to sh_z
-    auto compute_batch = [&](int rel, int cn, const float4 (&row)[R][NC]) {
+    auto compute_batch = [&](int rel, int cn, float4 (&row)[R][NC]) {
         float z[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r) z[r] = dot_cols<NC>(row[r], xv);
+        for (int r = 0; r < R; ++r) {
+            mask_cols<NC, FULL, T>(row[r], d);
+            z[r] = dot_cols<NC>(row[r], xv);
+        }
         block_sum_R<R, T>(z, sh_red, buf);
         // lane r evaluates row rel + r (slope, loss) once; wave 0 also records margin and loss
         const int lane = threadIdx.x & (kWave - 1);

@@ -132,6 +132,7 @@ __device__ __forceinline__ uint32_t quad_abs_bits(float4 v)
 template <int FIELD, bool ACC, bool EACH, int TB = kThreads>
 __global__ __launch_bounds__(TB) void master_update_kernel(const MasterArgs a, uint32_t *__restrict__ absmax_bits)
 {
+    touch_kernel_arguments<sizeof(MasterArgs) + sizeof(uint32_t *)>();
     __shared__ uint32_t scratch[TB / kWave];
     const int64_t quads = (a.d + 3) / 4;
     const int64_t stride = static_cast<int64_t>(gridDim.x) * TB;
@@ -173,6 +174,7 @@ template <int FIELD, bool EACH>
 __global__ __launch_bounds__(kPartsWorkers * kPartsQuads) void master_from_parts_kernel(const MasterArgs a, const PartsArgs p,
                                                                                        uint32_t *__restrict__ absmax_bits)
 {
+    touch_kernel_arguments<sizeof(MasterArgs) + sizeof(PartsArgs) + sizeof(uint32_t *)>();
     __shared__ float4 codes[2][kPartsWorkers][kPartsQuads];
     __shared__ float deltas[2][kPartsWorkers];
     const int ql = threadIdx.x % kPartsQuads, wl = threadIdx.x / kPartsQuads;
@@ -303,6 +305,7 @@ __global__ __launch_bounds__(kFusedThreads) void master_fused_kernel(
     const MasterArgs a, int b_x, StreamKey key, uint32_t *__restrict__ xq_out, float *__restrict__ delta_x_out,
     float *__restrict__ absmax_x_out, uint32_t *__restrict__ status)
 {
+    touch_kernel_arguments<sizeof(MasterArgs) + 64>();
     __shared__ uint32_t scratch[kFusedThreads / kWave];
     const int64_t d = a.d, quads = (d + 3) / 4;
     float4 xv[NQ];                                       // the thread's quads threadIdx.x + 1024*k of the new model
