@@ -55,21 +55,38 @@ template <int FIELD, bool ACC, bool EACH>
 __device__ __forceinline__ float4 master_quad(const MasterArgs &a, int64_t q)
 {
     const int64_t d = a.d;
-    const float4 gs4 = load_quad(a.g_snap, q, d);
-    const float gs[4] = {gs4.x, gs4.y, gs4.z, gs4.w};
     float xn[4] = {0.0f, 0.0f, 0.0f, 0.0f}, yn[4] = {0.0f, 0.0f, 0.0f, 0.0f}, xs[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     float sm[4] = {0.0f, 0.0f, 0.0f, 0.0f};
     const bool have_sum = ACC && a.xsum != nullptr;
-    if (ACC) {
-        const float4 y4 = load_quad(a.y, q, d), s4 = load_quad(a.x_snap, q, d);
-        yn[0] = y4.x; yn[1] = y4.y; yn[2] = y4.z; yn[3] = y4.w;
-        xs[0] = s4.x; xs[1] = s4.y; xs[2] = s4.z; xs[3] = s4.w;
-        if (have_sum) {
-            const float4 t = load_quad(a.xsum, q, d);
-            sm[0] = t.x; sm[1] = t.y; sm[2] = t.z; sm[3] = t.w;
+    // The state vectors of the quad.  With whole quads (d a multiple of 4, the same for every thread) the requests
+    // stand side by side in one piece of straight-line code; load_quad's per-lane tests for a ragged end make the
+    // compiler wait for each vector before it asks for the next.
+    float4 gs4, y4 = make_float4(0.0f, 0.0f, 0.0f, 0.0f), s4 = y4, t4 = y4, x4 = y4;
+    if ((d & 3) == 0) {
+        gs4 = reinterpret_cast<const float4 *>(a.g_snap)[q];
+        if (ACC) {
+            y4 = reinterpret_cast<const float4 *>(a.y)[q];
+            s4 = reinterpret_cast<const float4 *>(a.x_snap)[q];
+            if (have_sum) t4 = reinterpret_cast<const float4 *>(a.xsum)[q];
+        } else {
+            x4 = reinterpret_cast<const float4 *>(a.x)[q];
         }
     } else {
-        const float4 x4 = load_quad(a.x, q, d);
+        gs4 = load_quad(a.g_snap, q, d);
+        if (ACC) {
+            y4 = load_quad(a.y, q, d);
+            s4 = load_quad(a.x_snap, q, d);
+            if (have_sum) t4 = load_quad(a.xsum, q, d);
+        } else {
+            x4 = load_quad(a.x, q, d);
+        }
+    }
+    const float gs[4] = {gs4.x, gs4.y, gs4.z, gs4.w};
+    if (ACC) {
+        yn[0] = y4.x; yn[1] = y4.y; yn[2] = y4.z; yn[3] = y4.w;
+        xs[0] = s4.x; xs[1] = s4.y; xs[2] = s4.z; xs[3] = s4.w;
+        sm[0] = t4.x; sm[1] = t4.y; sm[2] = t4.z; sm[3] = t4.w;
+    } else {
         xn[0] = x4.x; xn[1] = x4.y; xn[2] = x4.z; xn[3] = x4.w;
     }
     float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};             // mean mode: sum_m delta_m * code_m, messages in order
