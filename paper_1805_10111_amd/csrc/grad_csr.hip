@@ -219,6 +219,92 @@ __device__ __forceinline__ int csr_row_in_chunk(const RowMeta &meta, int g1, int
     return r;
 }
 
+// Where the entry of staged position P + lane lies in the matrix, and its row number shifted above the column bits.
+// A wavefront whose 64 positions all lie past the end (P >= total) gets `inside`, the source of a position that
+// does exist, so that no load sits behind a test.
+__device__ __forceinline__ int64_t csr_stage_source(const RowMeta &meta, int g0, int g1, int base, int total, int P,
+                                                    int lane, int64_t inside, int &tag)
+{
+    const int p = min(P + lane, total - 1);
+    const int r = P >= total ? g1 - 1
+                  : g0 == 0  ? csr_row_in_chunk(meta, g1, P, p)
+                             : csr_row_of(meta, g0, g1, base, p);
+    tag = r << kColBits;
+    return P < total ? meta.start[r] + (p - (meta.pre[r] - base)) : inside;
+}
+
+// Margins and scatter for the staged group of rows [g0, g1) (`total` entries; base = pre[g0]); vmax = the largest
+// |value| among the entries this thread staged, as bits.
+template <bool SECOND, typename CoefFn>
+__device__ __forceinline__ void csr_reduce_group(RowMeta &meta, int g0, int g1, int base, int total, uint32_t vmax,
+                                                 int *acc, int c0, int c1, const CsrStage &sg, FixedAcc &fx, uint32_t *su,
+                                                 int *poison, CoefFn coef_of)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int2 *stage = sg.entry;
+    vmax = block_max_u32(vmax, su);            // (its barriers also publish the staged entries)
+    // ---- margins and coefficients: four rows per wavefront in flight; lane u evaluates row u's scalar
+    for (int r = g0 + wave; r < g1; r += kFlight * kCsrWaves) {
+        int len[kFlight], off[kFlight], maxlen = 0;
+        float sa[kFlight], sb[kFlight];
+#pragma unroll
+        for (int u = 0; u < kFlight; ++u) {
+            const int ru = r + u * kCsrWaves;
+            len[u] = ru < g1 ? meta.len[ru] : 0;
+            off[u] = ru < g1 ? meta.pre[ru] - base : 0;
+            maxlen = max(maxlen, len[u]);
+            sa[u] = sb[u] = 0.0f;
+        }
+        for (int k = lane; k < maxlen; k += kWave) {           // (maxlen > 0 implies total > 0)
+            float pa[kFlight], pb[kFlight];
+#pragma unroll
+            for (int u = 0; u < kFlight; ++u) {
+                const int at = min(off[u] + k, total - 1);
+                pa[u] = sg.prod_a[at];
+                pb[u] = SECOND ? sg.prod_b[at] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < kFlight; ++u) {
+                sa[u] += k < len[u] ? pa[u] : 0.0f;
+                if (SECOND) sb[u] += k < len[u] ? pb[u] : 0.0f;
+            }
+        }
+        float mine_a = 0.0f, mine_b = 0.0f;
+#pragma unroll
+        for (int u = 0; u < kFlight; ++u) {
+            const float ta = wave_sum_f32(sa[u]);
+            const float tb = SECOND ? wave_sum_f32(sb[u]) : 0.0f;
+            if (lane == u) {
+                mine_a = ta;
+                mine_b = tb;
+            }
+        }
+        const int rl = r + lane * kCsrWaves;
+        if (lane < kFlight && rl < g1) {
+            const float cf = coef_of(rl, mine_a, mine_b);
+            meta.coef[rl] = cf;
+        }
+    }
+    __syncthreads();
+    // ---- scatter: fixed-point terms, integer atomic adds
+    fixed_admit(fx, coef_abs_sum(meta.coef, g0, g1) * __uint_as_float(vmax), acc, c1 - c0, poison);
+    const float two_k = ldexpf(1.0f, fx.k);
+    for (int p0 = threadIdx.x; p0 < total; p0 += kStageFlight * kCsrThreads) {
+        int2 e[kStageFlight];
+        float cf[kStageFlight];
+#pragma unroll
+        for (int u = 0; u < kStageFlight; ++u) e[u] = stage[min(p0 + u * kCsrThreads, total - 1)];
+#pragma unroll
+        for (int u = 0; u < kStageFlight; ++u) cf[u] = meta.coef[(e[u].x >> kColBits) & (kCsrMaxRows - 1)];
+#pragma unroll
+        for (int u = 0; u < kStageFlight; ++u) {
+            const int c = e[u].x & kColMask;
+            if (p0 + u * kCsrThreads < total && c >= c0 && c < c1)
+                atomicAdd(&acc[c - c0], fixed_term(cf[u], __int_as_float(e[u].y), two_k));
+        }
+    }
+}
+
 // Stage, margins and scatter (the first three phases of the file header) for rows [0, nrows) described by `meta`,
 // accumulating into acc (LDS, fixed point, see FixedAcc).
 // The rows are taken in groups that fit the staging buffer:
@@ -237,7 +323,7 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
                                                  const CsrStage &sg, FixedAcc &fx, uint32_t *su, int *sh_ctl, int *poison,
                                                  VecReq vec_req, VecVal vec_val, CoefFn coef_of)
 {
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    const int lane = threadIdx.x & (kWave - 1);
     const int cap = sg.cap;
     int2 *stage = sg.entry;
     int g0 = 0;
@@ -270,16 +356,8 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
                 int tag[kStageFlight], col[kStageFlight];
                 float val[kStageFlight];
 #pragma unroll
-                for (int u = 0; u < kStageFlight; ++u) {
-                    // (a position past the end repeats the last entry and is not stored: no load sits behind a test)
-                    const int P = p0 - lane + u * kCsrThreads;         // the wavefront's 64 positions start here
-                    const int p = min(P + lane, total - 1);
-                    const int r = P >= total ? g1 - 1
-                                  : g0 == 0  ? csr_row_in_chunk(meta, g1, P, p)
-                                             : csr_row_of(meta, g0, g1, base, p);
-                    src[u] = P < total ? meta.start[r] + (p - (meta.pre[r] - base)) : src[0];    // (u = 0 is inside)
-                    tag[u] = r << kColBits;
-                }
+                for (int u = 0; u < kStageFlight; ++u)     // (a position past the end repeats an entry and is not stored)
+                    src[u] = csr_stage_source(meta, g0, g1, base, total, p0 - lane + u * kCsrThreads, lane, u ? src[0] : 0, tag[u]);
 #pragma unroll
                 for (int u = 0; u < kStageFlight; ++u) {
                     col[u] = A.indices[src[u]];
@@ -300,67 +378,7 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
                     }
                 }
             }
-            vmax = block_max_u32(vmax, su);            // (its barriers also publish the staged entries)
-            // ---- margins and coefficients: four rows per wavefront in flight; lane u evaluates row u's scalar
-            for (int r = g0 + wave; r < g1; r += kFlight * kCsrWaves) {
-                int len[kFlight], off[kFlight], maxlen = 0;
-                float sa[kFlight], sb[kFlight];
-#pragma unroll
-                for (int u = 0; u < kFlight; ++u) {
-                    const int ru = r + u * kCsrWaves;
-                    len[u] = ru < g1 ? meta.len[ru] : 0;
-                    off[u] = ru < g1 ? meta.pre[ru] - base : 0;
-                    maxlen = max(maxlen, len[u]);
-                    sa[u] = sb[u] = 0.0f;
-                }
-                for (int k = lane; k < maxlen; k += kWave) {           // (maxlen > 0 implies total > 0)
-                    float pa[kFlight], pb[kFlight];
-#pragma unroll
-                    for (int u = 0; u < kFlight; ++u) {
-                        const int at = min(off[u] + k, total - 1);
-                        pa[u] = sg.prod_a[at];
-                        pb[u] = SECOND ? sg.prod_b[at] : 0.0f;
-                    }
-#pragma unroll
-                    for (int u = 0; u < kFlight; ++u) {
-                        sa[u] += k < len[u] ? pa[u] : 0.0f;
-                        if (SECOND) sb[u] += k < len[u] ? pb[u] : 0.0f;
-                    }
-                }
-                float mine_a = 0.0f, mine_b = 0.0f;
-#pragma unroll
-                for (int u = 0; u < kFlight; ++u) {
-                    const float ta = wave_sum_f32(sa[u]);
-                    const float tb = SECOND ? wave_sum_f32(sb[u]) : 0.0f;
-                    if (lane == u) {
-                        mine_a = ta;
-                        mine_b = tb;
-                    }
-                }
-                const int rl = r + lane * kCsrWaves;
-                if (lane < kFlight && rl < g1) {
-                    const float cf = coef_of(rl, mine_a, mine_b);
-                    meta.coef[rl] = cf;
-                }
-            }
-            __syncthreads();
-            // ---- scatter: fixed-point terms, integer atomic adds
-            fixed_admit(fx, coef_abs_sum(meta.coef, g0, g1) * __uint_as_float(vmax), acc, c1 - c0, poison);
-            const float two_k = ldexpf(1.0f, fx.k);
-            for (int p0 = threadIdx.x; p0 < total; p0 += kStageFlight * kCsrThreads) {
-                int2 e[kStageFlight];
-                float cf[kStageFlight];
-#pragma unroll
-                for (int u = 0; u < kStageFlight; ++u) e[u] = stage[min(p0 + u * kCsrThreads, total - 1)];
-#pragma unroll
-                for (int u = 0; u < kStageFlight; ++u) cf[u] = meta.coef[(e[u].x >> kColBits) & (kCsrMaxRows - 1)];
-#pragma unroll
-                for (int u = 0; u < kStageFlight; ++u) {
-                    const int c = e[u].x & kColMask;
-                    if (p0 + u * kCsrThreads < total && c >= c0 && c < c1)
-                        atomicAdd(&acc[c - c0], fixed_term(cf[u], __int_as_float(e[u].y), two_k));
-                }
-            }
+            csr_reduce_group<SECOND>(meta, g0, g1, base, total, vmax, acc, c0, c1, sg, fx, su, poison, coef_of);
         } else {
             // ---- one very long row, straight from memory (every wavefront computes the same sums)
             const int64_t s = meta.start[g0];
@@ -393,6 +411,63 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
     }
 }
 
+// ---- a mini-batch prepared ahead of its round
+// What a worker step does before it first needs the model -- drawing its rows (Alg. 1, worker step 2: the sample stream),
+// reading their extents, labels and cached margins, the prefix sums, and the copy of the rows' entries into one flat run
+// -- does not depend on the model.  Between two rounds of one dq_run_rounds call an extra block per worker of the
+// worker launch does all of that for the NEXT round, on compute units the launch leaves idle, and leaves it in
+// memory as kPrepInts(cap) 32-bit words per worker:
+//   [0] 1 when the flat run is there (the batch fits the staging buffer), else 0   [1] number of entries
+//   row[kCsrMaxRows] len[kCsrMaxRows] pre[kCsrMaxRows + 4] y[kCsrMaxRows] z[kCsrMaxRows]      (RowMeta's fields)
+//   cap pairs (column | row << kColBits, value bits), the first [1] of them written
+// The next round's blocks then start from one round trip to memory instead of a chain of five.
+constexpr int kPrepRow = 4, kPrepLen = kPrepRow + kCsrMaxRows, kPrepPre = kPrepLen + kCsrMaxRows,
+              kPrepY = kPrepPre + kCsrMaxRows + 4, kPrepZ = kPrepY + kCsrMaxRows, kPrepEntries = kPrepZ + kCsrMaxRows;
+__host__ __device__ constexpr int64_t kPrepInts(int64_t cap) { return kPrepEntries + (2 * cap + 3) / 4 * 4; }
+
+// Stage, margins and scatter for a prepared mini-batch: `entry` is its flat run of `total` <= cap entries, `first`
+// what the caller has already loaded of it (positions threadIdx.x + u * kCsrThreads, clamped to the buffer), meta
+// holds the rows.  The rest as csr_process_rows.
+template <bool SECOND, typename VecReq, typename VecVal, typename CoefFn>
+__device__ __forceinline__ void csr_process_prepared(const int2 *entry, const int2 (&first)[kStageFlight], int total,
+                                                     RowMeta &meta, int nrows, int *acc, int c0, int c1, const CsrStage &sg,
+                                                     FixedAcc &fx, uint32_t *su, int *poison, VecReq vec_req,
+                                                     VecVal vec_val, CoefFn coef_of)
+{
+    uint32_t vmax = 0;
+    const auto stage_batch = [&](int p0, const int2 (&e)[kStageFlight]) {
+        int col[kStageFlight];
+        decltype(vec_req(0)) raw[kStageFlight];
+#pragma unroll
+        for (int u = 0; u < kStageFlight; ++u) {
+            // (past the end `first` holds whatever the buffer held: column 0 is gathered instead)
+            col[u] = p0 + u * kCsrThreads < total ? e[u].x & kColMask : 0;
+            raw[u] = vec_req(col[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < kStageFlight; ++u) {
+            const int p = p0 + u * kCsrThreads;
+            const float2 f = vec_val(raw[u], col[u]);
+            const float val = __int_as_float(e[u].y);
+            if (p < total) {
+                vmax = max(vmax, abs_bits(val));
+                sg.entry[p] = e[u];
+                sg.prod_a[p] = val * f.x;
+                if (SECOND) sg.prod_b[p] = val * f.y;
+            }
+        }
+    };
+    stage_batch(threadIdx.x, first);
+    for (int p0 = threadIdx.x + kStageFlight * kCsrThreads; p0 < total; p0 += kStageFlight * kCsrThreads) {
+        int2 e[kStageFlight];
+#pragma unroll
+        for (int u = 0; u < kStageFlight; ++u) e[u] = entry[min(p0 + u * kCsrThreads, total - 1)];
+        stage_batch(p0, e);
+    }
+    csr_reduce_group<SECOND>(meta, 0, nrows, 0, total, vmax, acc, c0, c1, sg, fx, su, poison, coef_of);
+    __syncthreads();
+}
+
 // ------------------------------------------------------------------ worker step
 struct CsrWorkerArgs {
     CsrView A;
@@ -416,6 +491,13 @@ struct CsrWorkerArgs {
     // row m of beta_ws and leaves the slice's largest magnitude and kept count; the quantization is a second launch
     float *beta_ws; float *part_max; int32_t *part_kept;
     const float *model_diff;       // nullable: (decoded model) - snapshot for every column, see WorkerArgs::model_diff
+    // a mini-batch prepared ahead (see kPrepInts): prep_in (nullable) holds this round's, one block of prep_stride words
+    // per worker; with prep_out the grid has one more block per worker (the last blockIdx.y), which prepares the round
+    // whose streams carry next_iter into prep_out.  Both need B <= kCsrMaxRows, drawn rows (idx == null) and win >= d.
+    const int32_t *prep_in;
+    int32_t *prep_out;
+    int64_t prep_stride;
+    uint32_t next_iter;
 };
 
 // DIFF: the model comes as a.model_diff (one float per column) instead of the message and the snapshot.
@@ -440,7 +522,8 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
 
     const int m = blockIdx.x;
     const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
-    const int slice = blockIdx.y, nslices = gridDim.y;       // identical copies of the worker; they share only the tail
+    // identical copies of the worker; they share only the tail (a last one more prepares the next round instead)
+    const int slice = blockIdx.y, nslices = static_cast<int>(gridDim.y) - (a.prep_out ? 1 : 0);
     if (a.zero_word && blockIdx.x == 0 && slice == 0 && threadIdx.x == 0) *a.zero_word = 0u;
     float *alpha_row = a.alpha_ws ? a.alpha_ws + static_cast<int64_t>(m) * a.ld_ws : nullptr;   // only with several windows
 
@@ -473,7 +556,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     };
     // the rows of one pass: which sample, where its entries start, how many, its label and cached margin
     struct RowInfo { int row; int64_t start; int len; float y, z; };
-    auto row_info = [&](int r0) {
+    auto row_info = [&](int r0, const StreamKey &round_key) {
         RowInfo ri{-1, 0, 0, 1.0f, 0.0f};
         const int nrows = min(kCsrMaxRows, a.B - r0);
         if (static_cast<int>(threadIdx.x) < nrows) {
@@ -482,7 +565,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
             if (a.idx) {
                 i = a.idx[static_cast<int64_t>(m) * a.B + r];
             } else {
-                StreamKey sk = a.key;
+                StreamKey sk = round_key;
                 sk.worker = a.worker0 + static_cast<uint32_t>(m);
                 sk.tag = DQ_TAG_SAMPLE;
                 i = __umulhi(stream_word(sk, static_cast<uint64_t>(r)), static_cast<uint32_t>(a.A.n));
@@ -497,13 +580,97 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
         }
         return ri;
     };
+    if (a.prep_out && slice == nslices) {
+        // ---- the extra block: worker m's mini-batch of the next round, left in memory (see kPrepInts)
+        StreamKey next_key = a.key;
+        next_key.iter = a.next_iter;
+        const int nrows = a.B;
+        const RowInfo ri = row_info(0, next_key);
+        if (static_cast<int>(threadIdx.x) < nrows) {
+            meta.row[threadIdx.x] = ri.row;
+            meta.start[threadIdx.x] = ri.start;
+            meta.len[threadIdx.x] = ri.len;
+        }
+        csr_prefix_lengths(meta, nrows);
+        int32_t *out = a.prep_out + static_cast<int64_t>(m) * a.prep_stride;
+        const int total = meta.pre[nrows];
+        const bool fits = total <= a.cap;
+        if (static_cast<int>(threadIdx.x) < nrows) {
+            out[kPrepRow + threadIdx.x] = ri.row;
+            out[kPrepLen + threadIdx.x] = ri.len;
+            out[kPrepPre + threadIdx.x] = meta.pre[threadIdx.x];
+            out[kPrepY + threadIdx.x] = __float_as_int(ri.y);
+            out[kPrepZ + threadIdx.x] = __float_as_int(ri.z);
+        }
+        if (threadIdx.x == 0) {
+            out[0] = fits ? 1 : 0;
+            out[1] = total;
+            out[kPrepPre + nrows] = total;
+        }
+        if (!fits) return;
+        int2 *entry = reinterpret_cast<int2 *>(out + kPrepEntries);
+        const int lane = threadIdx.x & (kWave - 1);
+        for (int p0 = threadIdx.x; p0 - lane < total; p0 += kStageFlight * kCsrThreads) {
+            int64_t src[kStageFlight];
+            int tag[kStageFlight], col[kStageFlight];
+            float val[kStageFlight];
+#pragma unroll
+            for (int u = 0; u < kStageFlight; ++u)
+                src[u] = csr_stage_source(meta, 0, nrows, 0, total, p0 - lane + u * kCsrThreads, lane, u ? src[0] : 0, tag[u]);
+#pragma unroll
+            for (int u = 0; u < kStageFlight; ++u) {
+                col[u] = a.A.indices[src[u]];
+                val[u] = a.A.values[src[u]];
+            }
+#pragma unroll
+            for (int u = 0; u < kStageFlight; ++u)
+                if (p0 + u * kCsrThreads < total) entry[p0 + u * kCsrThreads] = make_int2(col[u] | tag[u], __float_as_int(val[u]));
+        }
+        return;
+    }
     for (int64_t c0 = 0; c0 < d; c0 += win) {
         const int64_t c1 = min(d, c0 + win);
         const int64_t c1p = min((d + 3) / 4 * 4, c0 + win);     // the window, up to a whole quad past the end of the vector
         FixedAcc fx{0.0f, 0};
-        for (int r0 = 0; r0 < a.B; r0 += kCsrMaxRows) {                     // passes of at most kCsrMaxRows rows
+        bool rows_done = false;
+        if (a.prep_in) {
+            // ---- this round's mini-batch was prepared: descriptors and the first entries are requested together
+            // (a.B <= kCsrMaxRows, one window)
+            const int32_t *in = a.prep_in + static_cast<int64_t>(m) * a.prep_stride;
+            const int2 *entry = reinterpret_cast<const int2 *>(in + kPrepEntries);
+            const int nrows = a.B;
+            const int tr = min(static_cast<int>(threadIdx.x), kCsrMaxRows - 1);
+            const int ready = in[0], total = in[1];
+            const int p_row = in[kPrepRow + tr], p_len = in[kPrepLen + tr], p_pre = in[kPrepPre + tr];
+            const int p_last = in[kPrepPre + nrows];
+            const float p_y = __int_as_float(in[kPrepY + tr]), p_z = __int_as_float(in[kPrepZ + tr]);
+            int2 first[kStageFlight];
+#pragma unroll
+            for (int u = 0; u < kStageFlight; ++u) first[u] = entry[min(static_cast<int>(threadIdx.x) + u * kCsrThreads, a.cap - 1)];
+            for (int64_t j = 4ll * threadIdx.x; j < c1p - c0; j += 4ll * kCsrThreads)
+                *reinterpret_cast<int4 *>(acc + j) = make_int4(0, 0, 0, 0);
+            if (ready) {                                          // (the same for every thread)
+                if (static_cast<int>(threadIdx.x) < nrows) {
+                    meta.row[threadIdx.x] = p_row;
+                    meta.len[threadIdx.x] = p_len;
+                    meta.pre[threadIdx.x] = p_pre;
+                    sh_y[threadIdx.x] = p_y;
+                    meta.z[threadIdx.x] = p_z;
+                }
+                if (threadIdx.x == 0) meta.pre[nrows] = p_last;
+                __syncthreads();
+                if (have_z)
+                    csr_process_prepared<false>(entry, first, total, meta, nrows, acc, static_cast<int>(c0), static_cast<int>(c1),
+                                                sg, fx, su, &sh_poison, vec_req, vec_val, coef_of);
+                else
+                    csr_process_prepared<true>(entry, first, total, meta, nrows, acc, static_cast<int>(c0), static_cast<int>(c1),
+                                               sg, fx, su, &sh_poison, vec_req, vec_val, coef_of);
+                rows_done = true;
+            }
+        }
+        for (int r0 = 0; r0 < a.B && !rows_done; r0 += kCsrMaxRows) {     // passes of at most kCsrMaxRows rows
             const int nrows = min(kCsrMaxRows, a.B - r0);
-            const RowInfo ri = row_info(r0);
+            const RowInfo ri = row_info(r0, a.key);
             if (r0 == 0)                                       // (the window is cleared while the row loads are on their way)
                 for (int64_t j = 4ll * threadIdx.x; j < c1p - c0; j += 4ll * kCsrThreads)
                     *reinterpret_cast<int4 *>(acc + j) = make_int4(0, 0, 0, 0);
@@ -776,8 +943,22 @@ int64_t csr_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64
     }
     // a row per worker: the whole gradient when it does not fit in LDS, else the sparsified gradient when the
     // sparsifier is split over several blocks per worker (see csr_worker); then 8 values + 8 counts per worker; then
-    // one more row, in which dq_run_rounds keeps (decoded model) - snapshot between two rounds of a call
+    // one more row, in which dq_run_rounds keeps (decoded model) - snapshot between two rounds of a call; then two
+    // sets of prepared mini-batches (see kPrepInts), the one a round reads and the one it leaves for the next
+    return csr_prep_offset(prob, M) + 2 * M * csr_prep_stride(prob) * 4;
+}
+
+int64_t csr_prep_offset(const dq_problem *prob, int64_t M)
+{
     return csr_model_diff_offset(prob, M) + pad4(prob->d) * 4;
+}
+
+// 32-bit words per worker of a prepared mini-batch, for the larger of the two staging capacities
+int64_t csr_prep_stride(const dq_problem *prob)
+{
+    CsrPlan plan;
+    if (!csr_plan(prob->d, false, plan)) return 0;
+    return kPrepInts(plan.cap);
 }
 
 int64_t csr_model_diff_offset(const dq_problem *prob, int64_t M)
@@ -864,7 +1045,17 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
         k.part_max = k.beta_ws + a.M * k.ld_ws;
         k.part_kept = reinterpret_cast<int32_t *>(k.part_max + a.M * kMaxSlices);
     }
-    const dim3 grid(static_cast<unsigned>(a.M), slices), block(kCsrThreads);
+    // a round of dq_run_rounds that has a successor in its call prepares that round's mini-batches in one more block
+    // per worker (on compute units the launch leaves idle), and reads its own if the round before left them
+    const bool can_prepare = !a.idx && a.B <= kCsrMaxRows && plan.nwin == 1 && a.M * (slices + 1) <= 256;
+    if (can_prepare) {
+        k.prep_in = a.prep_in;
+        k.prep_out = a.prep_out;
+        k.prep_stride = csr_prep_stride(prob);
+        k.next_iter = a.iter + 1u;
+    }
+    if (a.prepared_next) *a.prepared_next = k.prep_out != nullptr;
+    const dim3 grid(static_cast<unsigned>(a.M), slices + (k.prep_out ? 1u : 0u)), block(kCsrThreads);
     const auto kernel = k.model_diff ? csr_worker_kernel<true> : csr_worker_kernel<false>;
     if (a.ev_start && a.ev_stop)      // the kernel's own start and end times go to the two events
         hipExtLaunchKernelGGL(kernel, grid, block, static_cast<uint32_t>(lds), st, a.ev_start, a.ev_stop, 0u, k);

@@ -56,6 +56,14 @@ struct WorkerArgs {
     // the master of the previous round (master_leaves_model_diff) in exactly the worker's arithmetic; the worker then
     // reads one float per column instead of decoding the message and subtracting the snapshot.
     const float *model_diff;
+    // CSR features, between the rounds of one dq_run_rounds call (all nullable): what a worker step does before it
+    // first needs the model (Alg. 1, worker step 2: drawing the rows; reading their extents and entries) is done one
+    // round ahead.  prep_out: this launch also prepares the mini-batches of round iter + 1 there (2 * M *
+    // csr_prep_stride words from csr_prep_offset in the workspace hold two such sets); *prepared_next tells whether it
+    // did.  prep_in: the set a previous launch prepared for this round, same M, B, worker0 and problem.
+    const int32_t *prep_in;
+    int32_t *prep_out;
+    bool *prepared_next;
 };
 
 // Whether the dense worker step can take the model from x_model (see WorkerArgs) for this shape.
@@ -101,6 +109,9 @@ int dense_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st);
 int64_t csr_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64_t B);
 // where in a DQ_OP_VR_GRAD workspace of a CSR problem dq_run_rounds keeps the d floats of WorkerArgs::model_diff
 int64_t csr_model_diff_offset(const dq_problem *prob, int64_t M);
+// where the two sets of prepared mini-batches lie there (WorkerArgs::prep_in / prep_out), and the words of one worker's
+int64_t csr_prep_offset(const dq_problem *prob, int64_t M);
+int64_t csr_prep_stride(const dq_problem *prob);
 int csr_full_grad(const dq_problem *prob, const float *x, float *g_out, float *z_out, double *obj_out, void *ws,
                   int64_t ws_bytes, hipStream_t st);
 int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st);

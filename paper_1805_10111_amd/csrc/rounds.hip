@@ -60,6 +60,16 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
         if (st->ws_bytes >= off + (prob->d + 3) / 4 * 4 * 4) model_diff = reinterpret_cast<float *>(static_cast<char *>(st->ws) + off);
     }
     bool diff_ready = false;             // model_diff holds the difference for the model message of this round
+    // ... and each worker launch prepares the mini-batches of the next round (two sets, alternating)
+    int32_t *prep_sets = nullptr;
+    int64_t prep_set_words = 0;
+    if (csr && cfg->tau == 0 && st->ws) {
+        const int64_t off = dq::csr_prep_offset(prob, cfg->M);
+        prep_set_words = cfg->M * dq::csr_prep_stride(prob);
+        if (prep_set_words > 0 && st->ws_bytes >= off + 2 * prep_set_words * 4)
+            prep_sets = reinterpret_cast<int32_t *>(static_cast<char *>(st->ws) + off);
+    }
+    bool prep_ready = false;             // the set of this round's parity holds this round's mini-batches
     bool model_pending = false;          // the model of this round is still x itself (not yet a message)
     for (int64_t t = t0; t < t0 + rounds; ++t) {
         const uint32_t it = static_cast<uint32_t>(epoch * cfg->m + t);
@@ -102,12 +112,19 @@ extern "C" int32_t dq_run_rounds(const dq_problem *prob, const dq_run_config *cf
             }
             if (defer_ok) w.deferred = &parts;
             if (diff_ready) w.model_diff = model_diff;
+            bool prepared_next = false;
+            if (prep_sets) {
+                if (prep_ready) w.prep_in = prep_sets + (t & 1) * prep_set_words;
+                if (t + 1 < t0 + rounds) w.prep_out = prep_sets + ((t + 1) & 1) * prep_set_words;
+                w.prepared_next = &prepared_next;
+            }
             if (worker_events && g == 0) {                       // (a null pair: this round's launch is a plain one)
                 w.ev_start = static_cast<hipEvent_t>(worker_events[2 * (t - t0)]);
                 w.ev_stop = static_cast<hipEvent_t>(worker_events[2 * (t - t0) + 1]);
             }
             rc = dq::worker_step_impl(prob, w, stream);
             if (rc != DQ_OK) return rc;
+            prep_ready = prepared_next;
         }
         // Section 4.2 on request: the sparsified messages cross to the master as (position, value) streams
         if (st->wire && cfg->algo == DQ_ALGO_SPARSE && cfg->b != 32) {

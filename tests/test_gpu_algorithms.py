@@ -198,19 +198,27 @@ def test_rounds_enqueued_together_equal_rounds_enqueued_one_by_one(dq, algo, b, 
     assert np.isfinite(host(a.x)).all() and host(a.x).any()
 
 
-@pytest.mark.parametrize("algo,b,M,B,b_x", [("asylpg", 8, 8, 32, 8), ("sparse", 4, 16, 64, 8), ("asylpg", 4, 3, 20, 4),
-                                            ("sparse", 8, 40, 16, 2), ("asylpg", 8, 8, 32, 11)])
-def test_rounds_enqueued_together_equal_rounds_enqueued_one_by_one_sparse_features(dq, algo, b, M, B, b_x):
-    """The same for CSR features (the shape of configs C2 and C3): with several rounds per call the worker kernel
-    quantizes the model itself, coordinate by coordinate where it gathers one, and must reproduce the messages,
-    scales and iterates of rounds enqueued one per call bit for bit."""
+@pytest.mark.parametrize("algo,b,M,B,b_x,cache", [
+    ("asylpg", 8, 8, 32, 8, True), ("sparse", 4, 16, 64, 8, True), ("asylpg", 4, 3, 20, 4, True),
+    ("sparse", 8, 40, 16, 2, True), ("asylpg", 8, 8, 32, 11, True),
+    ("asylpg", 8, 4, 88, 8, True),        # about 4500 entries per mini-batch: more than a thread stages in one go
+    ("asylpg", 8, 2, 128, 8, True),       # about 6500: more than the staging buffer holds, nothing is prepared ahead
+    ("asylpg", 8, 2, 300, 8, True),       # more rows than one pass takes
+    ("sparse", 4, 64, 8, 8, True),        # many workers: one block each
+    ("asylpg", 8, 8, 32, 8, False), ("sparse", 4, 16, 64, 8, False),     # margins at the snapshot recomputed
+    ("asylpg", 8, 4, 88, 8, False)])      # ... with their smaller staging buffer: not prepared ahead
+def test_rounds_enqueued_together_equal_rounds_enqueued_one_by_one_sparse_features(dq, algo, b, M, B, b_x, cache):
+    """The same for CSR features (the shape of configs C2 and C3).  With several rounds per call the master leaves
+    (decoded model) - snapshot for the next round's workers, may quantize the sparsified gradients itself, and every
+    worker launch draws, reads and lays out the next round's mini-batches in blocks of its own; rounds enqueued one
+    per call do none of that.  Messages, scales and iterates must agree bit for bit."""
     from paper_1805_10111_amd.driver import DoubleQuantTrainer
     p = synth.make_problem(synth.CONFIGS["C2"], n=3000)
     P = dq.DeviceProblem.from_host(p)
     m = 6
     runs = []
     for together in (True, False):
-        tr = DoubleQuantTrainer(P, algo, M, B, b_x, b, m, 0.5, seed=4)
+        tr = DoubleQuantTrainer(P, algo, M, B, b_x, b, m, 0.5, seed=4, cache_margins=cache)
         for _ in range(2):
             tr.epoch_prologue()
             if together:

@@ -379,8 +379,11 @@ def test_flag_bit_round_and_limits(dq, problems):
     # a gradient that does not fit on chip needs the worker workspace
     pw = problems["wide"]
     Pw = dq.DeviceProblem.from_host(pw)
-    row = (pw.d + 3) // 4 * 4 * 4                      # (a row per worker, slice results, one row for dq_run_rounds)
-    assert dq.dq_workspace_bytes(dq.OP_VR_GRAD, Pw, 3, 4) == 3 * row + 3 * 8 * 8 + row
+    # (a row per worker, slice results, one row for dq_run_rounds, and its two sets of prepared mini-batches: per
+    # worker 1288 words and a pair of words for each of at most 8192 staged entries)
+    row = (pw.d + 3) // 4 * 4 * 4
+    need = dq.dq_workspace_bytes(dq.OP_VR_GRAD, Pw, 3, 4)
+    assert 3 * row + 3 * 8 * 8 + row + 2 * 3 * 1288 * 4 < need <= 3 * row + 3 * 8 * 8 + row + 2 * 3 * (1288 + 2 * 8192) * 4
     with pytest.raises(dq.DqError) as e:
         dq.dq_worker_step(Pw, None, 3, 4, torch.zeros(pw.d, dtype=torch.int32, device="cuda"), torch.ones(1, device="cuda"),
                           8, False, torch.zeros(pw.d, device="cuda"), None, False, 8, 1, 1, 0,

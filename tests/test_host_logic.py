@@ -129,8 +129,11 @@ def test_workspace_sizes(lib):
                for g in (1, 2, 85, 86, 128, 255))
     small = dense(n=2000, d=1000)
     assert lib.dq_workspace_bytes(2, C.byref(small), 4, 16) == 4 * 1 * 1000 * 4       # small batch: one block per worker
-    # a row per worker + slice results + one row for (decoded model) - snapshot between the rounds of a call
-    assert lib.dq_workspace_bytes(2, C.byref(csr()), 8, 32) == 8 * 20960 * 4 + 8 * 8 * 8 + 20960 * 4
+    # a row per worker + slice results + one row for (decoded model) - snapshot between the rounds of a call + two sets
+    # of prepared mini-batches: per worker 1288 words of row descriptors and a pair of words for each of the
+    # (152 KB - 10 KB - 4 * 20960 bytes of LDS) / 12 = 5130 entries that can be staged at this width
+    assert lib.dq_workspace_bytes(2, C.byref(csr()), 8, 32) == \
+        8 * 20960 * 4 + 8 * 8 * 8 + 20960 * 4 + 2 * 8 * (1288 + 2 * 5130) * 4
     assert lib.dq_workspace_bytes(1, C.byref(csr()), 0, 0) > 256 * 20958 * 4
     assert lib.dq_workspace_bytes(3, C.byref(p), 1, 1) == INVALID
     assert lib.dq_workspace_bytes(2, C.byref(p), 0, 256) == INVALID
