@@ -501,7 +501,10 @@ struct CsrWorkerArgs {
 };
 
 // DIFF: the model comes as a.model_diff (one float per column) instead of the message and the snapshot.
-template <bool DIFF>
+// COMMON: the gradient fits in LDS as one window, the mini-batch in one pass of rows (B <= kCsrMaxRows), and the
+// margins at the snapshot are cached (z_snap given) -- the kernel is then straight-line code with one set of the
+// row-processing routines, which leaves the compiler far fewer values to keep alive across its phases.
+template <bool DIFF, bool COMMON>
 __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorkerArgs a)
 {
     touch_kernel_arguments<sizeof(CsrWorkerArgs)>();
@@ -518,17 +521,17 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     float *alpha = lds;                                        // the window of the gradient being built: fixed-point sums
     int *acc = reinterpret_cast<int *>(lds);                   // while the rows are added, float32 afterwards
     if (threadIdx.x == 0) sh_poison = 0;                       // (published by the barriers of the first row pass)
-    const CsrStage sg = csr_stage_in(lds + win, a.cap, a.z_snap == nullptr);
+    const CsrStage sg = csr_stage_in(lds + win, a.cap, !COMMON && a.z_snap == nullptr);
 
     const int m = blockIdx.x;
     const ModelMsg msg{a.xq, a.b_x == 32 ? 1.0f : a.delta_x[0], a.b_x};
     // identical copies of the worker; they share only the tail (a last one more prepares the next round instead)
     const int slice = blockIdx.y, nslices = static_cast<int>(gridDim.y) - (a.prep_out ? 1 : 0);
     if (a.zero_word && blockIdx.x == 0 && slice == 0 && threadIdx.x == 0) *a.zero_word = 0u;
-    float *alpha_row = a.alpha_ws ? a.alpha_ws + static_cast<int64_t>(m) * a.ld_ws : nullptr;   // only with several windows
+    float *alpha_row = (!COMMON && a.alpha_ws) ? a.alpha_ws + static_cast<int64_t>(m) * a.ld_ws : nullptr;   // only with several windows
 
     const float inv_B = 1.0f / static_cast<float>(a.B);      // the mean over the mini-batch, as one multiplication per row
-    const bool have_z = a.z_snap != nullptr;
+    const bool have_z = COMMON || a.z_snap != nullptr;
     uint32_t seen_max = 0;                                     // largest magnitude among the coordinates this thread finishes
     // the model value and the snapshot at column c: the field of column c starts at bit c*b_x of the message and
     // may continue in the next word; both words and the snapshot value are requested without any condition
@@ -688,6 +691,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
             else
                 csr_process_rows<true>(a.A, meta, nrows, acc, static_cast<int>(c0), static_cast<int>(c1), sg, fx, su, sh_ctl,
                                        &sh_poison, vec_req, vec_val, coef_of);
+            if constexpr (COMMON) break;                       // (one pass)
         }
         // the window becomes float32: the dense part  l2*(q - snapshot)  plus the accumulated sums, zero past the end
         // of the vector; four coordinates per thread and step
@@ -758,6 +762,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
             for (int64_t j = c0 + threadIdx.x; j < c1p; j += kCsrThreads) alpha_row[j] = alpha[j - c0];
             __syncthreads();
         }
+        if constexpr (COMMON) break;                           // (one window)
     }
     // the whole gradient, padded with zeros to a whole quad: in LDS when it fits in one window, else in this worker's
     // workspace row (the block's own writes, visible to all its threads after the barrier above)
@@ -1023,10 +1028,16 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     k.alpha_ws = plan.nwin > 1 ? static_cast<float *>(a.ws) : nullptr; k.ld_ws = pad4(d);
     const size_t lds = plan.lds;
     k.model_diff = a.b_x == 32 ? nullptr : a.model_diff;
-    static std::once_flag attr_once, attr_once_diff;
-    static hipError_t attr_rc = hipSuccess, attr_rc_diff = hipSuccess;
-    int rc = k.model_diff ? allow_big_lds(csr_worker_kernel<true>, attr_once_diff, attr_rc_diff)
-                          : allow_big_lds(csr_worker_kernel<false>, attr_once, attr_rc);
+    // (see csr_worker_kernel for the two switches)
+    const bool diff = k.model_diff != nullptr;
+    const bool common = plan.nwin == 1 && a.B <= kCsrMaxRows && a.z_snap != nullptr;
+    static std::once_flag attr_once[4];
+    static hipError_t attr_rc[4] = {hipSuccess, hipSuccess, hipSuccess, hipSuccess};
+    void (*const kernels[4])(const CsrWorkerArgs) = {csr_worker_kernel<false, false>, csr_worker_kernel<false, true>,
+                                                     csr_worker_kernel<true, false>, csr_worker_kernel<true, true>};
+    const int which = (diff ? 2 : 0) + (common ? 1 : 0);
+    const auto kernel = kernels[which];
+    int rc = allow_big_lds(kernel, attr_once[which], attr_rc[which]);
     if (rc != DQ_OK) return rc;
     // Few workers leave most compute units idle while each block spends a third of its time on the Philox rounds of
     // the final quantization: then several identical blocks per worker share that part (not when the nonzero count is
@@ -1056,7 +1067,6 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     }
     if (a.prepared_next) *a.prepared_next = k.prep_out != nullptr;
     const dim3 grid(static_cast<unsigned>(a.M), slices + (k.prep_out ? 1u : 0u)), block(kCsrThreads);
-    const auto kernel = k.model_diff ? csr_worker_kernel<true> : csr_worker_kernel<false>;
     if (a.ev_start && a.ev_stop)      // the kernel's own start and end times go to the two events
         hipExtLaunchKernelGGL(kernel, grid, block, static_cast<uint32_t>(lds), st, a.ev_start, a.ev_stop, 0u, k);
     else
