@@ -347,7 +347,8 @@ typedef struct dq_run_config {
  * slot t mod (tau+1).  packed: M rows of ld_words words; delta: float[M];
  * nnz: int32[m*M] nonzero codes per round and worker (written by Alg. 2 only), nullable.  ws: DQ_OP_VR_GRAD workspace
  * (scratch of the call: between the rounds of one call it also carries what one round leaves for the next, e.g. the
- * sparsified gradients that the master quantizes and, on CSR features, the decoded model minus the snapshot).
+ * sparsified gradients that the master quantizes and, on CSR features, the decoded model minus the snapshot and the
+ * next round's mini-batches -- row numbers drawn, extents, labels and entries read -- laid out by the round before).
  * wire (nullable, Alg. 2 with b in {2,4,8} only): M rows of ld_wire >= dq_sparse_stream_words(d, b) words.  When
  * given, every round really sends the sparse message of Section 4.2: the workers' packed codes are encoded into
  * `wire` (dq_sparse_encode), then the master's input is rebuilt from `wire` alone (dq_sparse_decode); wire_nnz:
