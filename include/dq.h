@@ -81,7 +81,9 @@ typedef struct dq_problem {
 
 /* Operations that need a workspace (argument of dq_workspace_bytes). */
 #define DQ_OP_FULL_GRAD    1
-#define DQ_OP_VR_GRAD      2   /* also covers dq_worker_step */
+#define DQ_OP_VR_GRAD      2   /* dq_vr_grad, dq_worker_step and dq_run_rounds (which also keeps data there between the
+                                  rounds of a call) */
+#define DQ_OP_WORKER_STEP  3   /* one dq_vr_grad or dq_worker_step call alone: never more than DQ_OP_VR_GRAD */
 
 const char *dq_version(void);
 /* Last hipError_t (as int) seen by this thread inside the library, 0 if none. */
@@ -240,7 +242,7 @@ int32_t dq_worker_step(const dq_problem *prob /*host*/, const int32_t *idx, int6
  * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments without ws / ws_bytes, same
  * results bit for bit.  The partial sums and per-worker rows that dq_worker_step passes through `ws` live in a
  * workspace of DQ_STATIC_WS_BYTES bytes built into the library, one copy per GPU, held until the process ends;
- * nothing is allocated or freed by the call.  A problem whose dq_workspace_bytes(DQ_OP_VR_GRAD, prob, M, B) exceeds
+ * nothing is allocated or freed by the call.  A problem whose dq_workspace_bytes(DQ_OP_WORKER_STEP, prob, M, B) exceeds
  * DQ_STATIC_WS_BYTES returns DQ_ERR_WORKSPACE and enqueues nothing.  All calls on one GPU share that workspace:
  * calls that may overlap on the GPU (different streams without an ordering between them) race; calls on one
  * stream, or otherwise ordered, are safe, and no call depends on what an earlier one left there. */

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libdq.so")
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_DEVICE = 0, -1, -2, -3, -4
 TAG_GRAD, TAG_MODEL, TAG_SPARSIFY, TAG_SAMPLE = 0, 1, 2, 3
 MASTER_ID = 0xFFFFFFFF
-OP_FULL_GRAD, OP_VR_GRAD = 1, 2
+OP_FULL_GRAD, OP_VR_GRAD, OP_WORKER_STEP = 1, 2, 3
 
 _ERR_NAMES = {-1: "DQ_ERR_INVALID_ARG", -2: "DQ_ERR_UNSUPPORTED", -3: "DQ_ERR_WORKSPACE", -4: "DQ_ERR_DEVICE"}
 
@@ -419,7 +419,7 @@ def dq_run_rounds(prob: DeviceProblem, cfg: RunConfig, state: RunState, epoch: i
 __all__ = [
     "DqError", "DeviceProblem", "EXPORTS", "LIB_PATH", "packed_words",
     "OK", "ERR_INVALID_ARG", "ERR_UNSUPPORTED", "ERR_WORKSPACE", "ERR_DEVICE",
-    "TAG_GRAD", "TAG_MODEL", "TAG_SPARSIFY", "TAG_SAMPLE", "MASTER_ID", "OP_FULL_GRAD", "OP_VR_GRAD",
+    "TAG_GRAD", "TAG_MODEL", "TAG_SPARSIFY", "TAG_SAMPLE", "MASTER_ID", "OP_FULL_GRAD", "OP_VR_GRAD", "OP_WORKER_STEP",
     "dq_version", "dq_last_device_error", "dq_workspace_bytes", "dq_workspace_init", "new_workspace", "dq_absmax", "dq_quantize", "dq_dequantize",
     "dq_pack", "dq_unpack", "dq_quantize_pack", "dq_unpack_dequant_sum", "dq_sample_indices", "dq_full_grad",
     "dq_vr_grad", "dq_sparsify", "dq_worker_step", "dq_worker_step_static", "STATIC_WS_BYTES", "dq_master_step", "dq_master_step_each", "dq_acc_mix", "dq_acc_snapshot",

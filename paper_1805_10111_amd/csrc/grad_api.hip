@@ -52,9 +52,11 @@ static bool gradient_bits_ok(int b) { return b == 2 || b == 4 || b == 8 || b == 
 extern "C" int64_t dq_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64_t B)
 {
     if (check_problem(prob) != DQ_OK) return DQ_ERR_INVALID_ARG;
-    if (op != DQ_OP_FULL_GRAD && op != DQ_OP_VR_GRAD) return DQ_ERR_INVALID_ARG;
-    if (op == DQ_OP_VR_GRAD && (M <= 0 || B <= 0)) return DQ_ERR_INVALID_ARG;
-    const int64_t bytes = prob->layout == 0 ? dense_workspace_bytes(op, prob, M, B) : csr_workspace_bytes(op, prob, M, B);
+    if (op != DQ_OP_FULL_GRAD && op != DQ_OP_VR_GRAD && op != DQ_OP_WORKER_STEP) return DQ_ERR_INVALID_ARG;
+    if (op != DQ_OP_FULL_GRAD && (M <= 0 || B <= 0)) return DQ_ERR_INVALID_ARG;
+    // (only CSR problems keep data between the rounds of a dq_run_rounds call)
+    const int64_t bytes = prob->layout == 0 ? dense_workspace_bytes(op == DQ_OP_FULL_GRAD ? op : DQ_OP_VR_GRAD, prob, M, B)
+                                            : csr_workspace_bytes(op, prob, M, B);
     return bytes < 0 ? bytes : (bytes + 15) / 16 * 16;
 }
 
@@ -144,7 +146,7 @@ extern "C" int32_t dq_worker_step_static(const dq_problem *prob, const int32_t *
                                          uint32_t *packed_out, int64_t ld_words, float *delta_out, int32_t *nnz_out,
                                          float *alpha_out, int64_t ld, uint32_t *status, void *stream)
 {
-    const int64_t need = dq_workspace_bytes(DQ_OP_VR_GRAD, prob, M, B);
+    const int64_t need = dq_workspace_bytes(DQ_OP_WORKER_STEP, prob, M, B);
     if (need < 0) return static_cast<int32_t>(need);
     if (need > kStaticWsBytes) return DQ_ERR_WORKSPACE;          // beyond the built-in workspace: use dq_worker_step
     void *ws = nullptr;

@@ -947,8 +947,10 @@ int64_t csr_workspace_bytes(int32_t op, const dq_problem *prob, int64_t M, int64
         return P * pad4(prob->d) * 4 + P * 8;
     }
     // a row per worker: the whole gradient when it does not fit in LDS, else the sparsified gradient when the
-    // sparsifier is split over several blocks per worker (see csr_worker); then 8 values + 8 counts per worker; then
-    // one more row, in which dq_run_rounds keeps (decoded model) - snapshot between two rounds of a call; then two
+    // sparsifier is split over several blocks per worker (see csr_worker); then 8 values + 8 counts per worker: all
+    // that a single step uses
+    if (op == DQ_OP_WORKER_STEP) return csr_model_diff_offset(prob, M);
+    // then one more row, in which dq_run_rounds keeps (decoded model) - snapshot between two rounds of a call; then two
     // sets of prepared mini-batches (see kPrepInts), the one a round reads and the one it leaves for the next
     return csr_prep_offset(prob, M) + 2 * M * csr_prep_stride(prob) * 4;
 }
@@ -1050,7 +1052,7 @@ int csr_worker(const dq_problem *prob, const WorkerArgs &a, hipStream_t st)
     // 33 us of the step at d = 20958).  With workspace for a row per worker each block sparsifies its own slice into
     // memory instead and the quantization becomes a second launch that takes the scale from the slices' maxima.
     const bool split_sparsifier = slices > 1 && a.sparsify && a.ws &&
-                                  a.ws_bytes >= csr_workspace_bytes(DQ_OP_VR_GRAD, prob, a.M, a.B);
+                                  a.ws_bytes >= csr_workspace_bytes(DQ_OP_WORKER_STEP, prob, a.M, a.B);
     if (split_sparsifier) {
         k.beta_ws = static_cast<float *>(a.ws);
         k.part_max = k.beta_ws + a.M * k.ld_ws;

@@ -135,7 +135,11 @@ def test_workspace_sizes(lib):
     assert lib.dq_workspace_bytes(2, C.byref(csr()), 8, 32) == \
         8 * 20960 * 4 + 8 * 8 * 8 + 20960 * 4 + 2 * 8 * (1288 + 2 * 5130) * 4
     assert lib.dq_workspace_bytes(1, C.byref(csr()), 0, 0) > 256 * 20958 * 4
-    assert lib.dq_workspace_bytes(3, C.byref(p), 1, 1) == INVALID
+    # a single step needs none of what dq_run_rounds keeps between the rounds of a call
+    assert lib.dq_workspace_bytes(3, C.byref(csr()), 8, 32) == 8 * 20960 * 4 + 8 * 8 * 8
+    assert lib.dq_workspace_bytes(3, C.byref(p), 32, 256) == vr
+    assert lib.dq_workspace_bytes(4, C.byref(p), 1, 1) == INVALID
+    assert lib.dq_workspace_bytes(3, C.byref(p), 0, 256) == INVALID
     assert lib.dq_workspace_bytes(2, C.byref(p), 0, 256) == INVALID
     assert lib.dq_workspace_bytes(1, None, 0, 0) == INVALID
 

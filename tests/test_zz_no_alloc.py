@@ -84,13 +84,17 @@ def test_csr_two_calls_second_smaller(dq):
     _both(dq, P, 16, 64, xq_d, dx_d, xs_d, True, 4, 9, 2)                # Alg. 2: the sparsified gradient crosses the workspace
     _both(dq, P, 4, 16, xq_d, dx_d, xs_d, True, 4, 9, 3)
     _both(dq, P, 8, 32, xq_d, dx_d, xs_d, False, 8, 9, 4)
+    # many workers: a single step still fits, although the workspace of a run (which also holds what dq_run_rounds
+    # keeps between rounds) would not
+    assert dq.dq_workspace_bytes(dq.OP_WORKER_STEP, P, 64, 8) <= dq.STATIC_WS_BYTES < dq.dq_workspace_bytes(dq.OP_VR_GRAD, P, 64, 8)
+    _both(dq, P, 64, 8, xq_d, dx_d, xs_d, True, 4, 9, 5)
 
 
 def test_too_large_for_the_builtin_workspace(dq):
     p = synth.dense_logistic(64, 16384, seed=1)
     P = dq.DeviceProblem.from_host(p)
     d, M, B = 16384, 64, 256
-    assert dq.dq_workspace_bytes(dq.OP_VR_GRAD, P, M, B) > dq.STATIC_WS_BYTES
+    assert dq.dq_workspace_bytes(dq.OP_WORKER_STEP, P, M, B) > dq.STATIC_WS_BYTES
     z = torch.zeros(d, device="cuda")
     packed = torch.zeros((M, d // 4), dtype=torch.int32, device="cuda")
     with pytest.raises(dq.DqError) as e:
