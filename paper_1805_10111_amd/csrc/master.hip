@@ -13,9 +13,8 @@ int fill_u32(uint32_t *p, int64_t n, uint32_t value, hipStream_t st);
 int launch_quantize_pack(const float *v, int64_t d, int64_t M, int64_t ld, int b, int field, const float *absmax,
                          const StreamKey &key, uint32_t worker0, uint32_t *packed, int64_t ld_words, float *delta_out,
                          uint32_t *status, hipStream_t st);
-int launch_quantize_pack_model_diff(const float *x, int64_t d, int b_x, const float *absmax, const StreamKey &key,
-                                    uint32_t *packed, float *delta_out, uint32_t *status, const float *x_snap,
-                                    float *diff_out, hipStream_t st);
+int launch_model_message(const float *x, int64_t d, int b_x, const float *absmax, const StreamKey &key, uint32_t *packed,
+                         float *delta_out, uint32_t *status, const float *x_snap, float *diff_out, hipStream_t st);
 
 constexpr int kThreads = 256;
 
@@ -537,9 +536,12 @@ static int model_message(const float *x, int64_t d, int32_t b_x, const StreamKey
                          float *delta_x_out, const float *absmax_x, uint32_t *status, hipStream_t st,
                          const float *x_snap = nullptr, float *diff_out = nullptr)
 {
-    if (diff_out && x_snap && (b_x == 2 || b_x == 4 || b_x == 8))
-        return launch_quantize_pack_model_diff(x, d, b_x, absmax_x, key, xq_packed_out, delta_x_out, status, x_snap,
-                                               diff_out, st);
+    // (below a million coordinates the launch is latency, not throughput: see model_message_kernel)
+    constexpr int64_t kSmallModel = 1 << 20;
+    const bool leave_diff = diff_out && x_snap;
+    if ((b_x == 2 || b_x == 4 || b_x == 8) && (leave_diff || d <= kSmallModel))
+        return launch_model_message(x, d, b_x, absmax_x, key, xq_packed_out, delta_x_out, status,
+                                    leave_diff ? x_snap : nullptr, leave_diff ? diff_out : nullptr, st);
     if (b_x == 32) {
         // full-precision model: "packed" output is x itself, delta is 1
         copy_f32_kernel<<<dim3(static_cast<unsigned>(ceil_div(d, kThreads))), dim3(kThreads), 0, st>>>(

@@ -287,15 +287,12 @@ __device__ __forceinline__ void store16_tile(float *__restrict__ tile, float4 *_
 // coordinates it pays for 8-bit fields only (228 -> 220 us); with narrower fields, whose packing costs more
 // arithmetic, the kernel is bound by instruction issue and the exchange costs more than the better access pattern
 // brings (4 bits 214 -> 217 us, 2 bits 197 -> 212 us).
-// DIFF (one row, the model message of Alg. 1, master (i)): the kernel also leaves what it quantized minus another
-// vector, diff_out[i] = delta * code_i - diff_from[i] -- the model a worker decodes minus the snapshot, which every
-// worker of the next round would otherwise form again, per column it touches, from the message.
-template <int FIELD, bool TILE = FIELD == 8, bool DIFF = false>
+template <int FIELD, bool TILE = FIELD == 8>
 __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(
     const float *__restrict__ v, int64_t d, int64_t ld, const float *__restrict__ absmax, int b, StreamKey key,
     uint32_t worker0, uint32_t *__restrict__ packed, int64_t ld_words, int64_t row_words,
     float *__restrict__ delta_out, uint32_t *__restrict__ status, int parts, const int32_t *__restrict__ count_parts,
-    int32_t *__restrict__ count_out, const float *__restrict__ diff_from = nullptr, float *__restrict__ diff_out = nullptr)
+    int32_t *__restrict__ count_out)
 {
     const int m = blockIdx.y;
     const float *row = v + static_cast<int64_t>(m) * ld;
@@ -326,15 +323,70 @@ __global__ __launch_bounds__(kThreads) void quantize_pack_kernel(
             if (c >= chunks) continue;
             load16(row, c * kCoordsPerThread, d, a);         // coordinates past d read as 0 -> code 0
         }
-        float other[16];
-        if constexpr (DIFF) load16(diff_from, c * kCoordsPerThread, d, other);      // (requested before the Philox rounds)
         uint32_t w[Words16<FIELD>::n];
         quantize16<FIELD>(a, s, key, c, w);
         store_words<FIELD>(out, c, row_words, w);
-        if constexpr (DIFF) {
+    }
+}
+
+// The model message of Alg. 1, master (i), for vectors of up to a million coordinates or so: such a launch is all
+// latency, so a thread takes one quad (one Philox block) and everything it reads -- the scale's input, the model, the
+// snapshot -- is requested before the Philox rounds, which depend on none of it, and waited for after them.
+// DIFF: together with diff_out[i] = delta * code_i - x_snap[i], the model a worker decodes minus the snapshot, which
+// every worker of the next round would otherwise form again, per column it touches, from the message (dq_run_rounds
+// on CSR features).  Same bits as quantize_pack_kernel on one row with the master's stream.
+template <int FIELD, bool DIFF>
+__global__ __launch_bounds__(kThreads) void model_message_kernel(
+    const float *__restrict__ x, int64_t d, const float *__restrict__ absmax, int b, StreamKey key,
+    uint32_t *__restrict__ packed, float *__restrict__ delta_out, uint32_t *__restrict__ status,
+    const float *__restrict__ x_snap, float *__restrict__ diff_out)
+{
+    touch_kernel_arguments<88>();                        // (five pointers, d, b, the key, three more pointers)
+    const int64_t quads = (d + 3) / 4;
+    const int64_t q = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    const int64_t qc = min(q, quads - 1);                // (threads past the end repeat the last quad and store nothing)
+    // (single elements at clamped positions: the same requests whether or not the vector ends inside a quad; and the
+    // scale's input through a vector load like the rest -- as a scalar load it would share its counter with the
+    // arguments that the Philox rounds need, and those would wait for it)
+    int lane_zero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(lane_zero));
+    const float amax = absmax[lane_zero];
+    float xv[4], sv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int j = 0; j < 16; ++j) other[j] = s.delta * static_cast<float>(code_of<FIELD>(w, j)) - other[j];
-            store16<false>(diff_out, c * kCoordsPerThread, d, other);
+    for (int e = 0; e < 4; ++e) {
+        xv[e] = x[min(4 * qc + e, d - 1)];
+        if constexpr (DIFF) sv[e] = x_snap[min(4 * qc + e, d - 1)];
+    }
+    key.worker = DQ_MASTER_ID;
+    const uint4 r = stream_block(key, static_cast<uint32_t>(qc));
+    asm volatile("" ::"v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));      // (the rounds stay ahead of the first wait)
+    const Scale s = make_scale(amax, b);
+    if (q == 0) {
+        delta_out[0] = s.delta;
+        if (s.bad && status) atomicOr(status, 1u);
+    }
+    constexpr int kB = CodeBias<FIELD>::value;
+    int k[4] = {kB, kB, kB, kB};
+    uint32_t bits = 0;
+    if (s.inv_delta != 0.0f) {                           // (a degenerate scale: every code is zero)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) xv[e] = 4 * qc + e < d ? xv[e] : 0.0f;      // past the end: code 0
+        k[0] = quantize_one<kB>(xv[0], s, r.x); k[1] = quantize_one<kB>(xv[1], s, r.y);
+        k[2] = quantize_one<kB>(xv[2], s, r.z); k[3] = quantize_one<kB>(xv[3], s, r.w);
+        bits = pack4<FIELD, true, FIELD != 8>(k[0], k[1], k[2], k[3]);
+    }
+    // (every lane makes the call: lanes that share a word combine their bits; lanes past the end bring none)
+    store_quad_bits<FIELD>(q < quads ? bits : 0u, q < quads ? q : quads, quads, packed);
+    if (DIFF && q < quads) {
+        float o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = s.delta * static_cast<float>(k[e] - kB) - sv[e];
+        if (4 * q + 3 < d) {
+            reinterpret_cast<float4 *>(diff_out)[q] = make_float4(o[0], o[1], o[2], o[3]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (4 * q + e < d) diff_out[4 * q + e] = o[e];
         }
     }
 }
@@ -352,19 +404,22 @@ int launch_quantize_pack(const float *v, int64_t d, int64_t M, int64_t ld, int b
                                       delta_out, status, st);
 }
 
-// The model message (one row) together with diff_out = Q(x) - x_snap (see DIFF); widths 2, 4, 8.
-int launch_quantize_pack_model_diff(const float *x, int64_t d, int b_x, const float *absmax, const StreamKey &key,
-                                    uint32_t *packed, float *delta_out, uint32_t *status, const float *x_snap,
-                                    float *diff_out, hipStream_t st)
+// The model message (one row; widths 2, 4, 8) by model_message_kernel; x_snap and diff_out both given or both null.
+int launch_model_message(const float *x, int64_t d, int b_x, const float *absmax, const StreamKey &key, uint32_t *packed,
+                         float *delta_out, uint32_t *status, const float *x_snap, float *diff_out, hipStream_t st)
 {
-    const int64_t row_words = packed_words(d, b_x);
-    const dim3 grid = grid_for(d, 1), block(kThreads);
+    if (d < 1 || (x_snap == nullptr) != (diff_out == nullptr)) return DQ_ERR_INVALID_ARG;
+    const dim3 grid(static_cast<unsigned>(ceil_div(ceil_div(d, 4), kThreads))), block(kThreads);
+#define DQ_MESSAGE(F)                                                                                                       \
+    if (diff_out) model_message_kernel<F, true><<<grid, block, 0, st>>>(x, d, absmax, b_x, key, packed, delta_out, status, x_snap, diff_out); \
+    else model_message_kernel<F, false><<<grid, block, 0, st>>>(x, d, absmax, b_x, key, packed, delta_out, status, nullptr, nullptr)
     switch (b_x) {
-    case 8: quantize_pack_kernel<8, false, true><<<grid, block, 0, st>>>(x, d, d, absmax, b_x, key, DQ_MASTER_ID, packed, row_words, row_words, delta_out, status, 1, nullptr, nullptr, x_snap, diff_out); break;
-    case 4: quantize_pack_kernel<4, false, true><<<grid, block, 0, st>>>(x, d, d, absmax, b_x, key, DQ_MASTER_ID, packed, row_words, row_words, delta_out, status, 1, nullptr, nullptr, x_snap, diff_out); break;
-    case 2: quantize_pack_kernel<2, false, true><<<grid, block, 0, st>>>(x, d, d, absmax, b_x, key, DQ_MASTER_ID, packed, row_words, row_words, delta_out, status, 1, nullptr, nullptr, x_snap, diff_out); break;
+    case 8: DQ_MESSAGE(8); break;
+    case 4: DQ_MESSAGE(4); break;
+    case 2: DQ_MESSAGE(2); break;
     default: return DQ_ERR_UNSUPPORTED;
     }
+#undef DQ_MESSAGE
     DQ_LAUNCH_CHECK();
     return DQ_OK;
 }
