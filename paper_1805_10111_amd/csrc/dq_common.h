@@ -248,15 +248,30 @@ __device__ __forceinline__ void block_max_u32_sum_i32(uint32_t &m, int &s, uint3
 // past the last one re-reads the last one): a loop that stops at `parts` would wait for every load before the next.
 constexpr int kMaxParts = 8;
 
+// (in two steps for callers that have other work to place between the requests and the first use of their result)
+struct PartsRaw {
+    float t[kMaxParts];
+};
+
+__device__ __forceinline__ PartsRaw parts_request(const float *__restrict__ v, int parts)
+{
+    PartsRaw r;
+#pragma unroll
+    for (int s = 0; s < kMaxParts; ++s) r.t[s] = v[min(s, parts - 1)];
+    return r;
+}
+
+__device__ __forceinline__ float parts_absmax_of(const PartsRaw &r)
+{
+    float amax = r.t[0];               // (magnitudes compare like their bit patterns, and so does a NaN)
+#pragma unroll
+    for (int s = 1; s < kMaxParts; ++s) amax = __float_as_uint(r.t[s]) > __float_as_uint(amax) ? r.t[s] : amax;
+    return amax;
+}
+
 __device__ __forceinline__ float parts_absmax(const float *__restrict__ v, int parts)
 {
-    float t[kMaxParts];
-#pragma unroll
-    for (int s = 0; s < kMaxParts; ++s) t[s] = v[min(s, parts - 1)];
-    float amax = t[0];                 // (magnitudes compare like their bit patterns, and so does a NaN)
-#pragma unroll
-    for (int s = 1; s < kMaxParts; ++s) amax = __float_as_uint(t[s]) > __float_as_uint(amax) ? t[s] : amax;
-    return amax;
+    return parts_absmax_of(parts_request(v, parts));
 }
 
 __device__ __forceinline__ int parts_sum(const int32_t *__restrict__ v, int parts)

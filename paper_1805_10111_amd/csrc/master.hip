@@ -237,15 +237,19 @@ __global__ __launch_bounds__(kPartsWorkers * kPartsQuads) void master_from_parts
         if (live) {
             // everything is requested before anything is waited for: slice maxima and the quad; the random bits do
             // not depend on either
-            const float amax = parts_absmax(p.in.part_max + static_cast<int64_t>(m) * p.in.parts, p.in.parts);
+            const PartsRaw maxima = parts_request(p.in.part_max + static_cast<int64_t>(m) * p.in.parts, p.in.parts);
             // (rows are padded to whole quads; what lies past d is not part of the vector)
             float4 v = reinterpret_cast<const float4 *>(p.in.beta + static_cast<int64_t>(m) * p.in.ld)[inside ? q : 0];
-            v.y = 4 * q + 1 < d ? v.y : 0.0f;
-            v.z = 4 * q + 2 < d ? v.z : 0.0f;
-            v.w = 4 * q + 3 < d ? v.w : 0.0f;
+            __builtin_amdgcn_sched_barrier(0);           // (the requests go out, then the Philox rounds, then the waits)
             StreamKey key = p.key;
             key.worker = p.worker0 + static_cast<uint32_t>(m);
             const uint4 r = stream_block(key, static_cast<uint32_t>(q));
+            asm volatile("" ::"v"(r.x), "v"(r.y), "v"(r.z), "v"(r.w));      // (... here, not where r is first used)
+            __builtin_amdgcn_sched_barrier(0);
+            const float amax = parts_absmax_of(maxima);
+            v.y = 4 * q + 1 < d ? v.y : 0.0f;
+            v.z = 4 * q + 2 < d ? v.z : 0.0f;
+            v.w = 4 * q + 3 < d ? v.w : 0.0f;
             const Scale s = make_scale(amax, p.b);
             if (ql == 0) deltas[buf][wl] = s.delta;
             if (inside && s.inv_delta != 0.0f) {         // (a degenerate scale: every code is zero)
