@@ -172,12 +172,16 @@ static int launch_master_update(bool acc, dim3 grid, hipStream_t st, const Maste
 }
 
 // ------------------------------------------------------------------ Alg. 2: quantization inside the master update
-// The workers of a round left their sparsified gradients beta_m unquantized (SparsifiedParts).  A block of 16 x 16
-// threads takes 16 quads of the model: thread (worker lane, quad lane) quantizes its worker's quad -- scale
+// The workers of a round left their sparsified gradients beta_m unquantized (SparsifiedParts).  A block of 16 x 64
+// threads takes 64 quads of the model: thread (worker lane, quad lane) quantizes its worker's quad -- scale
 // ||beta_m||_inf from the slice maxima, the worker's own Philox stream -- stores the message bits and leaves the four
-// codes in LDS; after the barrier the threads of worker lane 0 aggregate delta_m * code_m in worker order and
-// update the model exactly as master_quad does.  More than 16 workers take several passes over two LDS buffers.
-constexpr int kPartsWorkers = 16, kPartsQuads = 16;
+// codes in LDS; after the barrier the threads of worker lane 0 (one wavefront) aggregate delta_m * code_m in worker
+// order and update the model exactly as master_quad does.  More than 16 workers take several passes over two LDS
+// buffers.  (64 quads per block: a block then writes whole 128-byte lines of every message row, and 82 blocks cover
+// 20958 coordinates.  With 16 quads per block -- 328 blocks, a quarter line per row and block -- two or three blocks
+// of every launch waited 1 to 4 us for the acknowledgement of such a store before they could end: 6.9 us per launch
+// under the profiler against 4.6.)
+constexpr int kPartsWorkers = 16, kPartsQuads = 64;
 
 struct PartsArgs {
     SparsifiedParts in;
