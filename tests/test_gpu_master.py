@@ -31,7 +31,7 @@ def _messages(M, d, b, seed):
 @pytest.mark.parametrize("acc", [False, True])
 @pytest.mark.parametrize("b,bx", [(8, 8), (4, 8), (2, 4), (8, 2)])
 @pytest.mark.parametrize("M,d", [(1, 5), (4, 1000), (8, 20958), (32, 4096), (3, 4099), (2, 8192), (2, 8193), (2, 16400), (2, 40001),
-                                 (45, 4100), (70, 333), (41, 9000)])
+                                 (45, 4100), (70, 333), (41, 9000), (3, 9999), (2, 8194)])
 def test_master_step_bit_exact(dq, acc, b, bx, M, d):
     k, delta, pw = _messages(M, d, b, seed=M * 7 + d + b)
     rng = np.random.default_rng(d)
