@@ -17,6 +17,9 @@
 //      the result is reproducible whichever wavefront gets there first;
 //   4. the accumulators become float32 in place, the dense part l2*(q - snapshot) added, and the tail of the worker
 //      step (sparsify, scale, quantize, pack) runs from LDS.
+// Between the rounds of one dq_run_rounds call, everything of step 1 that does not depend on the model (which rows,
+// their extents and labels, the flat run itself) is laid out one round ahead by an extra block per worker of the
+// previous round's launch (see kPrepInts).
 // The full gradient uses the same block procedure over many blocks, each leaving a partial
 // d-vector that a second kernel adds up in a fixed order.
 #include <mutex>
