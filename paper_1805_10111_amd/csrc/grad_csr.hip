@@ -38,7 +38,8 @@ constexpr int kCsrWaves = kCsrThreads / kWave;
 constexpr int kColBits = 20;                     // staged entries carry column | row << kColBits
 constexpr int kColMask = (1 << kColBits) - 1;
 constexpr int kFlight = 4;                       // rows a wavefront reduces at the same time
-constexpr int kStageFlight = 4;                  // entries a thread stages at the same time
+constexpr int kStageFlight = 4;                  // entries a thread stages at the same time (worker step)
+constexpr int kFullFlight = 8;                   // ... in the full gradient, whose groups of rows fill the staging buffer
 constexpr int kFlushRows = 1024;                 // rows between two flushes of the fixed-point sums (full gradient)
 constexpr int kCsrMaxRows = 256;                 // rows a block handles per pass (LDS metadata)
 constexpr int kMaxStage = 8192;                  // most entries the staging buffer is given
@@ -61,7 +62,7 @@ struct RowMeta {
     int len[kCsrMaxRows];
     int pre[kCsrMaxRows + 1];    // exclusive prefix sum of len
     float coef[kCsrMaxRows];
-    float z[kCsrMaxRows];        // cached margin at the snapshot (worker step only)
+    float z[kCsrMaxRows];        // cached margin at the snapshot (worker step); the label (full gradient)
     int chunk_row[kChunkSlots];  // the row that holds entry 64 c of the rows' concatenation, for the entries below 64 * kChunkSlots
 };
 
@@ -321,9 +322,10 @@ __device__ __forceinline__ void csr_reduce_group(RowMeta &meta, int g0, int g1, 
 // A row longer than `cap` is handled alone, straight from memory.
 // Only the columns of the window [c0, c1) are accumulated: a vector too long for LDS is built one window at a
 // time (the caller repeats the call per window; margins are recomputed).
-template <bool SECOND, typename VecReq, typename VecVal, typename CoefFn>
+// FLIGHT: entries a thread stages at the same time.
+template <bool SECOND, int FLIGHT, typename VecReq, typename VecVal, typename CoefFn>
 __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta, int nrows, int *acc, int c0, int c1,
-                                                 const CsrStage &sg, FixedAcc &fx, uint32_t *su, int *sh_ctl, int *poison,
+                                                 const CsrStage &sg, FixedAcc &fx, uint32_t *su, int *poison,
                                                  VecReq vec_req, VecVal vec_val, CoefFn coef_of)
 {
     const int lane = threadIdx.x & (kWave - 1);
@@ -337,40 +339,38 @@ __device__ __forceinline__ void csr_process_rows(const CsrView &A, RowMeta &meta
         int g1 = nrows;
         bool direct = false;
         if (meta.pre[nrows] - base > cap) {            // (the same for every thread) not all remaining rows fit
-            if (threadIdx.x == 0) {
-                sh_ctl[0] = nrows;
-                sh_ctl[1] = meta.len[g0] > cap;
+            // the first row whose end lies past the buffer, by halving (every thread finds the same one)
+            int lo = g0, hi = nrows - 1;
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if (meta.pre[mid + 1] - base > cap) hi = mid;
+                else lo = mid + 1;
             }
-            __syncthreads();
-            if (static_cast<int>(threadIdx.x) >= g0 && static_cast<int>(threadIdx.x) < nrows &&
-                meta.pre[threadIdx.x + 1] - base > cap)
-                atomicMin(&sh_ctl[0], max(static_cast<int>(threadIdx.x), g0 + 1));
-            __syncthreads();
-            g1 = sh_ctl[0];
-            direct = sh_ctl[1] != 0;
+            g1 = max(lo, g0 + 1);
+            direct = meta.len[g0] > cap;
         }
         if (!direct) {
             // ---- stage: flat copy of the group's entries with their products
             const int total = meta.pre[g1] - base;
             uint32_t vmax = 0;
             // (the loop bound is the same for a whole wavefront: its lanes find their rows together)
-            for (int p0 = threadIdx.x; p0 - lane < total; p0 += kStageFlight * kCsrThreads) {
-                int64_t src[kStageFlight];
-                int tag[kStageFlight], col[kStageFlight];
-                float val[kStageFlight];
+            for (int p0 = threadIdx.x; p0 - lane < total; p0 += FLIGHT * kCsrThreads) {
+                int64_t src[FLIGHT];
+                int tag[FLIGHT], col[FLIGHT];
+                float val[FLIGHT];
 #pragma unroll
-                for (int u = 0; u < kStageFlight; ++u)     // (a position past the end repeats an entry and is not stored)
+                for (int u = 0; u < FLIGHT; ++u)     // (a position past the end repeats an entry and is not stored)
                     src[u] = csr_stage_source(meta, g0, g1, base, total, p0 - lane + u * kCsrThreads, lane, u ? src[0] : 0, tag[u]);
 #pragma unroll
-                for (int u = 0; u < kStageFlight; ++u) {
+                for (int u = 0; u < FLIGHT; ++u) {
                     col[u] = A.indices[src[u]];
                     val[u] = A.values[src[u]];
                 }
-                decltype(vec_req(0)) raw[kStageFlight];
+                decltype(vec_req(0)) raw[FLIGHT];
 #pragma unroll
-                for (int u = 0; u < kStageFlight; ++u) raw[u] = vec_req(col[u]);
+                for (int u = 0; u < FLIGHT; ++u) raw[u] = vec_req(col[u]);
 #pragma unroll
-                for (int u = 0; u < kStageFlight; ++u) {
+                for (int u = 0; u < FLIGHT; ++u) {
                     const int p = p0 + u * kCsrThreads;
                     const float2 f = vec_val(raw[u], col[u]);
                     vmax = max(vmax, abs_bits(val[u]));
@@ -517,7 +517,6 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
     __shared__ uint32_t su[kCsrWaves];
     __shared__ int si[kCsrWaves];
     __shared__ double sd[kCsrWaves];
-    __shared__ int sh_ctl[2];
     __shared__ int sh_poison;
     const int64_t d = a.A.d;
     const int win = a.win;                                     // columns per window, a multiple of 4
@@ -689,10 +688,10 @@ __global__ __launch_bounds__(kCsrThreads) void csr_worker_kernel(const CsrWorker
             }
             csr_prefix_lengths(meta, nrows);
             if (have_z)
-                csr_process_rows<false>(a.A, meta, nrows, acc, static_cast<int>(c0), static_cast<int>(c1), sg, fx, su, sh_ctl,
+                csr_process_rows<false, kStageFlight>(a.A, meta, nrows, acc, static_cast<int>(c0), static_cast<int>(c1), sg, fx, su,
                                         &sh_poison, vec_req, vec_val, coef_of);
             else
-                csr_process_rows<true>(a.A, meta, nrows, acc, static_cast<int>(c0), static_cast<int>(c1), sg, fx, su, sh_ctl,
+                csr_process_rows<true, kStageFlight>(a.A, meta, nrows, acc, static_cast<int>(c0), static_cast<int>(c1), sg, fx, su,
                                        &sh_poison, vec_req, vec_val, coef_of);
             if constexpr (COMMON) break;                       // (one pass)
         }
@@ -817,7 +816,6 @@ __global__ __launch_bounds__(kCsrThreads) void csr_full_partial_kernel(
     __shared__ RowMeta meta;
     __shared__ double sh_loss[kCsrWaves];
     __shared__ uint32_t su[kCsrWaves];
-    __shared__ int sh_ctl[2];
     __shared__ int sh_poison;
     int *acc = reinterpret_cast<int *>(lds);             // the window [c0, c1) of this block's partial sum, fixed point
     const CsrStage sg = csr_stage_in(lds + win, cap, false);
@@ -825,7 +823,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_full_partial_kernel(
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     const int64_t per = (A.n + gridDim.x - 1) / gridDim.x;
     const int64_t i0 = blockIdx.x * per, i1 = min(A.n, i0 + per);
-    const float fn = static_cast<float>(A.n);
+    const float inv_n = 1.0f / static_cast<float>(A.n);
     double loss = 0.0;                                   // the lanes that evaluate row scalars add to theirs
     float *mine = partial + static_cast<int64_t>(blockIdx.x) * ldp;
     for (int64_t c0 = 0; c0 < ldp; c0 += win) {          // one window when the vector fits in LDS
@@ -846,6 +844,7 @@ __global__ __launch_bounds__(kCsrThreads) void csr_full_partial_kernel(
                 meta.row[threadIdx.x] = static_cast<int>(i);
                 meta.start[threadIdx.x] = s;
                 meta.len[threadIdx.x] = static_cast<int>(A.indptr[i + 1] - s);
+                meta.z[threadIdx.x] = A.y[i];            // (here: the row's label, so that no lane fetches it later)
             }
             csr_prefix_lengths(meta, nrows);
             const int64_t ib_now = ib;
@@ -853,15 +852,17 @@ __global__ __launch_bounds__(kCsrThreads) void csr_full_partial_kernel(
             auto vec_val = [&](float xc, int) { return make_float2(xc, 0.0f); };
             auto coef_of = [&](int r, float z, float) {
                 const int64_t i = ib_now + r;
-                const float y = A.y[i];
+                const float y = meta.z[r];
                 if (first) {
                     if (z_out) z_out[i] = z;
-                    loss += static_cast<double>(logistic_loss(y * z));
+                    loss += static_cast<double>(logistic_loss_fast(y * z));
                 }
-                return logistic_slope(y, z) / fn;
+                // (a few lanes evaluate this while every other lane of the block waits: hardware exp, log and
+                // reciprocal, as in the dense kernel)
+                return logistic_slope_fast(y, z) * inv_n;
             };
-            csr_process_rows<false>(A, meta, nrows, acc, static_cast<int>(c0), static_cast<int>(min(A.d, c1)), sg, fx, su,
-                                    sh_ctl, &sh_poison, vec_req, vec_val, coef_of);
+            csr_process_rows<false, kFullFlight>(A, meta, nrows, acc, static_cast<int>(c0), static_cast<int>(min(A.d, c1)), sg, fx, su,
+                                    &sh_poison, vec_req, vec_val, coef_of);
             since_flush += nrows;
             if (since_flush >= kFlushRows || ib + kCsrMaxRows >= i1) {         // (ends with a barrier: all adds are in)
                 const float unit = sh_poison ? __uint_as_float(0x7FC00000u) : ldexpf(1.0f, -fx.k);
