@@ -206,7 +206,8 @@ def test_rounds_enqueued_together_equal_rounds_enqueued_one_by_one(dq, algo, b, 
     ("asylpg", 8, 2, 300, 8, True),       # more rows than one pass takes
     ("sparse", 4, 64, 8, 8, True),        # many workers: one block each
     ("asylpg", 8, 8, 32, 8, False), ("sparse", 4, 16, 64, 8, False),     # margins at the snapshot recomputed
-    ("asylpg", 8, 4, 88, 8, False)])      # ... with their smaller staging buffer: not prepared ahead
+    ("asylpg", 8, 4, 88, 8, False),       # ... with their smaller staging buffer: not prepared ahead
+    ("acc", 8, 8, 32, 8, True), ("acc", 4, 16, 64, 4, True)])            # Alg. 3 on the same features
 def test_rounds_enqueued_together_equal_rounds_enqueued_one_by_one_sparse_features(dq, algo, b, M, B, b_x, cache):
     """The same for CSR features (the shape of configs C2 and C3).  With several rounds per call the master leaves
     (decoded model) - snapshot for the next round's workers, may quantize the sparsified gradients itself, and every
@@ -231,7 +232,7 @@ def test_rounds_enqueued_together_equal_rounds_enqueued_one_by_one_sparse_featur
         torch.cuda.synchronize()
         runs.append(tr)
     a, c = runs
-    for name in ("x", "x_snap", "packed", "delta", "xq", "delta_x", "absmax_x", "nnz"):
+    for name in ("x", "x_snap", "packed", "delta", "xq", "delta_x", "absmax_x", "nnz") + (("y", "xsum") if algo == "acc" else ()):
         assert torch.equal(getattr(a, name), getattr(c, name)), name
     assert np.isfinite(host(a.x)).all() and host(a.x).any() and host(a.status)[0] == 0
 
