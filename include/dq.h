@@ -222,8 +222,8 @@ int32_t dq_sparsify(const float *alpha, int64_t d, int64_t M, int64_t ld, const 
  * writing alpha to memory (dense features with B > 32: partial sums of alpha pass through
  * `ws`; CSR with a model too wide for the on-chip buffer: alpha is assembled in `ws`; CSR with
  * sparsify != 0 and few workers: the sparsified gradient passes through `ws` between two launches).
- * ws, ws_bytes: at least dq_workspace_bytes(DQ_OP_VR_GRAD, prob, M, B) bytes.  CSR features whose
- * model fits the on-chip buffer also run without (NULL, 0), in a single launch.  packed_out: M rows of ld_words words; delta_out[M];
+ * ws, ws_bytes: at least dq_workspace_bytes(DQ_OP_WORKER_STEP, prob, M, B) bytes (a DQ_OP_VR_GRAD workspace is never
+ * smaller).  CSR features whose model fits the on-chip buffer also run without (NULL, 0), in a single launch.  packed_out: M rows of ld_words words; delta_out[M];
  * nnz_out (nullable) [M] = nonzero codes.  alpha_out (nullable): also store alpha.
  * idx == NULL: the mini-batches are sampled inside the kernel, exactly as
  * dq_sample_indices(n, M, B, seed, iter, worker0, .) would produce them.
